@@ -1,0 +1,256 @@
+"""CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Thin ctypes wrapper over ``klpm_oracle.c`` plus the pure-Python parts of the
+reference: the online-stream simulation (waiting queue bookkeeping, simulated
+clock, TTFT) and the nearest-rank percentile.  Only tests, the smoke check and
+the benchmark's CPU-baseline leg may import this package; the GPU library and
+its binding never do.
+
+Paper passages followed: Algorithm 1 (k-LPM), Def. 1 (query stream), Def. 2
+(completion-time model, used with c_attn = 0 for the simulated prefill cost),
+Sec. 2.1 (bins of B queries finish together; fixed memory pool), Sec. 1
+(radix-tree prefix cache with LRU eviction).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "klpm_oracle.c")
+_LIB = os.path.join(_HERE, "libklpm_oracle.so")
+
+K_INF = 0xFFFFFFFF
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, no intrinsics)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-shared", "-fPIC", "-pthread", "-o", _LIB, _SRC])
+    return _LIB
+
+
+class _Stats(C.Structure):
+    _fields_ = [
+        ("total_tokens", C.c_int64), ("inserted_tokens", C.c_int64), ("evicted_tokens", C.c_int64),
+        ("n_nodes", C.c_int32), ("new_nodes", C.c_int32), ("evicted_nodes", C.c_int32), ("pad", C.c_int32),
+        ("clock", C.c_uint64),
+    ]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        vp, i32, i64, u32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32
+        L.orc_tree_new.restype = vp
+        L.orc_tree_free.argtypes = [vp]
+        L.orc_total_tokens.restype = i64; L.orc_total_tokens.argtypes = [vp]
+        L.orc_n_nodes.restype = i64; L.orc_n_nodes.argtypes = [vp]
+        L.orc_clock.restype = C.c_uint64; L.orc_clock.argtypes = [vp]
+        L.orc_match.argtypes = [vp, vp, vp, vp, i32, vp]
+        L.orc_match_mt.argtypes = [vp, vp, vp, vp, i32, vp, i32]
+        L.orc_select.restype = i32
+        L.orc_select.argtypes = [vp, vp, i32, u32, i32, C.POINTER(u32), vp]
+        L.orc_commit.argtypes = [vp, vp, vp, vp, vp, i32, i64, C.POINTER(_Stats)]
+        L.orc_snapshot_bytes.restype = C.c_size_t; L.orc_snapshot_bytes.argtypes = [vp]
+        L.orc_snapshot.restype = C.c_size_t; L.orc_snapshot.argtypes = [vp, vp, C.c_size_t]
+        L.orc_def2.argtypes = [vp, vp, vp, vp, vp, i32, C.c_double, C.c_double, vp]
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+@dataclass
+class CommitStats:
+    total_tokens: int
+    inserted_tokens: int
+    evicted_tokens: int
+    n_nodes: int
+    new_nodes: int
+    evicted_nodes: int
+    clock: int
+
+
+class OracleTree:
+    """Pointer-based radix tree over token strings with per-node last-use ticks."""
+
+    def __init__(self):
+        self._L = _load()
+        self._t = self._L.orc_tree_new()
+
+    def __del__(self):
+        try:
+            if self._t:
+                self._L.orc_tree_free(self._t)
+                self._t = None
+        except Exception:
+            pass
+
+    @property
+    def total_tokens(self) -> int:
+        return int(self._L.orc_total_tokens(self._t))
+
+    @property
+    def n_nodes(self) -> int:
+        return int(self._L.orc_n_nodes(self._t))
+
+    @property
+    def clock(self) -> int:
+        return int(self._L.orc_clock(self._t))
+
+    def match(self, tokens, off, length, threads: int = 1) -> np.ndarray:
+        tokens, off, length = _c(tokens, np.int32), _c(off, np.int64), _c(length, np.int32)
+        out = np.zeros(length.shape[0], dtype=np.int32)
+        if threads <= 1:
+            self._L.orc_match(self._t, _p(tokens), _p(off), _p(length), length.shape[0], _p(out))
+        else:
+            self._L.orc_match_mt(self._t, _p(tokens), _p(off), _p(length), length.shape[0], _p(out), threads)
+        return out
+
+    def commit(self, tokens, off, length, batch_idx, budget: int) -> CommitStats:
+        tokens, off, length = _c(tokens, np.int32), _c(off, np.int64), _c(length, np.int32)
+        batch_idx = _c(batch_idx, np.int32)
+        st = _Stats()
+        self._L.orc_commit(self._t, _p(tokens), _p(off), _p(length), _p(batch_idx), batch_idx.shape[0],
+                           int(min(budget, (1 << 62))), C.byref(st))
+        return CommitStats(st.total_tokens, st.inserted_tokens, st.evicted_tokens, st.n_nodes, st.new_nodes,
+                           st.evicted_nodes, st.clock)
+
+    def build(self, prompts) -> CommitStats:
+        """Insert the initial cached prompts in order, ticks 0..P-1, no eviction."""
+        return self.commit(prompts.tokens, prompts.off, prompts.len, np.arange(prompts.n, dtype=np.int32), 1 << 62)
+
+    def snapshot(self) -> bytes:
+        n = int(self._L.orc_snapshot_bytes(self._t))
+        buf = np.zeros(n, dtype=np.uint8)
+        got = int(self._L.orc_snapshot(self._t, _p(buf), n))
+        assert got == n
+        return buf.tobytes()
+
+
+def select(arrival, match_len, k: int, batch: int, phase: int = 0) -> Tuple[np.ndarray, int]:
+    """Algorithm 1 over a static score vector, cut at ``batch`` picks. Returns (batch_idx, phase_out)."""
+    L = _load()
+    arrival, match_len = _c(arrival, np.uint64), _c(match_len, np.int32)
+    n = arrival.shape[0]
+    out = np.zeros(max(0, min(batch, n)), dtype=np.int32)
+    ph = C.c_uint32(phase)
+    got = L.orc_select(_p(arrival), _p(match_len), n, C.c_uint32(k & 0xFFFFFFFF), batch, C.byref(ph), _p(out))
+    return out[:got], int(ph.value)
+
+
+def def2_completion(prompts, order, c_attn: float = 0.0, t_start: float = 0.0) -> np.ndarray:
+    """Completion time R(.) of every query (indexed by query, not by position) under Def. 2."""
+    L = _load()
+    order = _c(order, np.int32)
+    out = np.zeros(prompts.n, dtype=np.float64)
+    L.orc_def2(_p(_c(prompts.tokens, np.int32)), _p(_c(prompts.off, np.int64)), _p(_c(prompts.len, np.int32)),
+               _p(_c(prompts.arrival, np.uint64)), _p(order), order.shape[0], float(c_attn), float(t_start), _p(out))
+    return out
+
+
+def percentile_nearest_rank(values, p: float) -> int:
+    """Nearest-rank percentile of an integer array: sorted[ceil(p*n) - 1]."""
+    v = np.sort(np.asarray(values))
+    if v.shape[0] == 0:
+        return 0
+    r = max(1, int(math.ceil(p * v.shape[0])))
+    return int(v[r - 1])
+
+
+def schedule_with_tree(prompts, k: int, budget: int, t_start: int = 0, batch: int = 1) -> np.ndarray:
+    """Run match -> select -> commit over a fixed queue until it is empty.
+
+    With ``batch = 1`` and ``budget`` = one prompt length this is the
+    last-prompt cache of Def. 2 driven through the radix-tree pipeline.  All
+    queries are taken to be waiting from the start (processing begins at
+    ``t_start`` >= every arrival).  Returns the processing order.
+    """
+    tree = OracleTree()
+    waiting = np.arange(prompts.n, dtype=np.int64)
+    phase = 0
+    order: List[int] = []
+    while waiting.shape[0]:
+        off, ln, arr = prompts.off[waiting], prompts.len[waiting], prompts.arrival[waiting]
+        m = tree.match(prompts.tokens, off, ln)
+        idx, phase = select(arr, m, k, batch, phase)
+        tree.commit(prompts.tokens, off, ln, idx, budget)
+        order.extend(int(waiting[i]) for i in idx)
+        keep = np.ones(waiting.shape[0], dtype=bool)
+        keep[idx] = False
+        waiting = waiting[keep]
+    return np.array(order, dtype=np.int32)
+
+
+@dataclass
+class StreamResult:
+    ttft: np.ndarray  # int64 per query (-1 if never admitted)
+    admitted_step: np.ndarray  # int32 per query
+    batches: List[np.ndarray]  # global query ids in pick order, per step
+    match_lens: List[np.ndarray]  # match lengths of the waiting queue, per step
+    waiting_ids: List[np.ndarray]  # global query ids of the waiting queue, per step
+    clock: int  # simulated time after the last step
+    stats: List[CommitStats]
+    snapshots: List[Optional[bytes]]
+
+
+def simulate_stream(stream, snapshot_every: int = 0, tree: Optional[OracleTree] = None) -> StreamResult:
+    """Online simulation: each step, enqueue that step's arrivals at the current simulated
+    time, score the whole waiting queue, pick a k-LPM batch (phase persists across steps),
+    commit it under the KV budget, then advance time by the batch's prefill cost.
+
+    Prefill cost of a query is its uncached token count |x| - m (Def. 2 with c_attn = 0,
+    m measured at step start); a batch finishes together (Sec. 2.1); time advances by
+    max(1, total cost); TTFT = finish time - enqueue time.
+    """
+    q = stream.queries
+    tree = tree or OracleTree()
+    n = q.n
+    ttft = np.full(n, -1, dtype=np.int64)
+    adm = np.full(n, -1, dtype=np.int32)
+    enq = np.zeros(n, dtype=np.uint64)
+    waiting = np.zeros(0, dtype=np.int64)
+    clock = 0
+    phase = 0
+    res = StreamResult(ttft, adm, [], [], [], 0, [], [])
+    for s in range(stream.steps):
+        new = np.arange(int(stream.step_start[s]), int(stream.step_start[s + 1]), dtype=np.int64)
+        enq[new] = clock
+        waiting = np.concatenate([waiting, new])
+        off, ln, arr = q.off[waiting], q.len[waiting], enq[waiting]
+        m = tree.match(q.tokens, off, ln)
+        idx, phase = select(arr, m, stream.k, stream.batch, phase)
+        st = tree.commit(q.tokens, off, ln, idx, stream.budget)
+        cost = int((ln[idx].astype(np.int64) - m[idx].astype(np.int64)).sum())
+        clock += max(1, cost)
+        gids = waiting[idx]
+        ttft[gids] = clock - enq[gids].astype(np.int64)
+        adm[gids] = s
+        res.batches.append(gids.copy())
+        res.match_lens.append(m)
+        res.waiting_ids.append(waiting.copy())
+        res.stats.append(st)
+        res.snapshots.append(tree.snapshot() if snapshot_every and (s + 1) % snapshot_every == 0 else None)
+        keep = np.ones(waiting.shape[0], dtype=bool)
+        keep[idx] = False
+        waiting = waiting[keep]
+    res.clock = clock
+    return res

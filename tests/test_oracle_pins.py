@@ -1,0 +1,320 @@
+"""CPU-only pins for the oracle: each test checks it against something other than itself
+(the paper's printed example, closed forms from the proof of Thm. 2, brute-force models in
+plain Python, textbook special cases)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import PathModel, lcp, parse_snapshot, select_literal, snapshot_paths
+
+K_INF = W.K_LPM_ENDPOINT
+
+
+# ----------------------------------------------------------------------------- match
+@pytest.mark.parametrize("seed", range(12))
+def test_match_equals_bruteforce_pairwise_overlap(seed):
+    w = W.random_small(seed, n_cache=14, n_query=30, vocab=3, max_len=9)
+    tree = oracle.OracleTree()
+    tree.build(w.cache)
+    got = tree.match(w.queries.tokens, w.queries.off, w.queries.len)
+    cached = w.cache.as_lists()
+    want = [max(lcp(x, y) for y in cached) for x in w.queries.as_lists()]
+    assert got.tolist() == want
+
+
+def test_match_special_cases():
+    w = W.config0()
+    empty = oracle.OracleTree()
+    assert not empty.match(w.queries.tokens, w.queries.off, w.queries.len).any()
+    tree = oracle.OracleTree()
+    tree.build(w.cache)
+    # a cached prompt matches in full; a full match is legal (an identical prompt costs nothing, Sec. 3.1 proof)
+    m = tree.match(w.cache.tokens, w.cache.off, w.cache.len)
+    assert (m == w.cache.len).all()
+    # idempotence: after committing the queries with no eviction each matches in full
+    tree.commit(w.queries.tokens, w.queries.off, w.queries.len, np.arange(w.queries.n), 1 << 60)
+    m2 = tree.match(w.queries.tokens, w.queries.off, w.queries.len)
+    assert (m2 == w.queries.len).all()
+
+
+def test_match_threads_agree():
+    w = W.config0()
+    tree = oracle.OracleTree()
+    tree.build(w.cache)
+    a = tree.match(w.queries.tokens, w.queries.off, w.queries.len)
+    b = tree.match(w.queries.tokens, w.queries.off, w.queries.len, threads=5)
+    assert (a == b).all()
+    # group-derived queries see at least the 128-token group prefix, fresh ones (almost) nothing
+    assert (a >= 128).mean() > 0.6 and (a <= 2).mean() > 0.15
+
+
+# ----------------------------------------------------------------------------- select
+def _rand_scores(rng, n):
+    arrival = rng.integers(0, max(2, n // 2), size=n).astype(np.uint64)  # many ties
+    m = rng.integers(0, 5, size=n).astype(np.int32)
+    return arrival, m
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_select_equals_literal_loop(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 40))
+    arrival, m = _rand_scores(rng, n)
+    for k in (1, 2, 3, 4, 7, 1000, 0, K_INF):
+        for batch in (1, 3, n, n + 5):
+            for phase in (0, 1, 5):
+                got, ph = oracle.select(arrival, m, k, batch, phase)
+                want, wph = select_literal(arrival, m, k, batch, phase)
+                assert got.tolist() == want and ph == wph
+
+
+def test_select_endpoints_are_fcfs_and_lpm():
+    rng = np.random.default_rng(99)
+    n = 200
+    arrival, m = _rand_scores(rng, n)
+    idx = np.arange(n)
+    fcfs = sorted(idx, key=lambda i: (int(arrival[i]), i))
+    lpm = sorted(idx, key=lambda i: (-int(m[i]), int(arrival[i]), i))
+    for batch in (1, 17, n):
+        got, _ = oracle.select(arrival, m, 1, batch)
+        assert got.tolist() == fcfs[:batch]  # k = 1 reduces to FCFS (Sec. 4)
+        for kinf in (0, K_INF):
+            got, ph = oracle.select(arrival, m, kinf, batch)
+            assert got.tolist() == lpm[:batch] and ph == 0  # k = infinity reduces to LPM (Sec. 4)
+        # a finite k >= batch with phase 0: the oldest query, then LPM order of the rest
+        got, _ = oracle.select(arrival, m, 1000, batch)
+        rest = [i for i in lpm if i != fcfs[0]]
+        assert got.tolist() == ([fcfs[0]] + rest)[:batch]
+        # the LPM endpoint maximises the summed match length of the batch
+        best = np.sort(m)[::-1][:batch].sum()
+        assert m[oracle.select(arrival, m, K_INF, batch)[0]].sum() == best
+
+
+def test_select_slot_property_and_no_duplicates():
+    rng = np.random.default_rng(5)
+    n = 300
+    arrival, m = _rand_scores(rng, n)
+    for k in (2, 3, 8):
+        for phase in (0, 1, k - 1):
+            got, ph = oracle.select(arrival, m, k, 64, phase)
+            assert len(set(got.tolist())) == 64
+            assert ph == (phase + 64) % k
+            left = set(range(n))
+            for j, p in enumerate(got.tolist()):
+                if (phase + j) % k == 0:
+                    assert (int(arrival[p]), p) == min((int(arrival[i]), i) for i in left)
+                else:
+                    assert (-int(m[p]), int(arrival[p]), p) == min((-int(m[i]), int(arrival[i]), i) for i in left)
+                left.remove(p)
+
+
+def test_select_degenerate():
+    got, ph = oracle.select(np.zeros(0, np.uint64), np.zeros(0, np.int32), 4, 8, 3)
+    assert got.shape[0] == 0 and ph == 3
+    got, ph = oracle.select(np.array([5], np.uint64), np.array([0], np.int32), 4, 0, 2)
+    assert got.shape[0] == 0 and ph == 2
+
+
+# ----------------------------------------------------------------------------- worked example
+def _golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "toy_example.txt")
+    out = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, vals = line.split(":")
+        out[key.strip()] = [int(v) for v in vals.split()]
+    return out
+
+
+def test_toy_example_def2_values():
+    g = _golden()
+    # spaced arrivals (s = 10): FCFS gives every query a TTFT of 10
+    p = W.toy_example(10)
+    order, _ = oracle.select(p.arrival, np.zeros(4, np.int32), 1, 4)
+    ttft = oracle.def2_completion(p, order) - p.arrival.astype(np.float64)
+    assert ttft.tolist() == g["s10_fcfs_ttft"]
+    # burst (s = 0)
+    p = W.toy_example(0)
+    order, _ = oracle.select(p.arrival, np.zeros(4, np.int32), 1, 4)
+    assert (order + 1).tolist() == g["s0_fcfs_order"]
+    ttft = oracle.def2_completion(p, order)
+    assert ttft.tolist() == g["s0_fcfs_ttft"] and ttft.max() == g["s0_fcfs_max"][0]
+    # LPM with a last-prompt cache, through the radix-tree pipeline (one prompt of budget, batch 1)
+    order = oracle.schedule_with_tree(p, K_INF, budget=10)
+    assert (order + 1).tolist() == g["s0_lpm_order"]
+    ttft = oracle.def2_completion(p, order)
+    assert ttft[order].tolist() == g["s0_lpm_ttft_in_processing_order"] and ttft.max() == g["s0_lpm_max"][0]
+    # k-LPM with k = 2 gives the same order here
+    assert (oracle.schedule_with_tree(p, 2, budget=10) + 1).tolist() == g["s0_lpm_order"]
+    # FCFS through the same pipeline
+    assert (oracle.schedule_with_tree(p, 1, budget=10) + 1).tolist() == g["s0_fcfs_order"]
+
+
+def test_def2_is_prefill_recurrence_with_attention_term():
+    # two prompts "ab" and "abc" with c_attn = 0.5: R1 = 0 + (1+0.5*2)*2 = 4, R2 = max(4, 7) + (1+0.5*3)*(3-2) = 9.5
+    p = W.generators._from_lists([[7, 8], [7, 8, 9]], [0, 7])
+    r = oracle.def2_completion(p, [0, 1], c_attn=0.5)
+    assert r.tolist() == [4.0, 9.5]
+    # reversed order: R(abc) = 7 + 2.5*3 = 14.5, R(ab) = 14.5 + 2*(2-2) = 14.5
+    r = oracle.def2_completion(p, [1, 0], c_attn=0.5)
+    assert r.tolist() == [14.5, 14.5]
+
+
+# ----------------------------------------------------------------------------- closed forms (proof of Thm. 2)
+@pytest.mark.parametrize("seed,n,u,k,d,s", [(1, 12, 6, 3, 4, 2), (2, 20, 9, 4, 3, 1), (3, 16, 5, 2, 7, 3)])
+def test_shuffled_queue_closed_forms(seed, n, u, k, d, s):
+    p, user_of = W.shuffled_queue(n, u, k, d, s, seed=seed)
+    T = s * n + 3  # processing starts once everything has arrived
+    # LPM: the j-th processed query completes at T + ceil(j/k) u + d j
+    order = oracle.schedule_with_tree(p, K_INF, budget=u + d)
+    comp = oracle.def2_completion(p, order, t_start=T)
+    for j, q in enumerate(order.tolist(), start=1):
+        assert comp[q] == T + -(-j // k) * u + d * j
+    # FCFS: the whole queue takes T + n(u+d) - u * sum_i I_i, I_i = same user as the previous arrival
+    order = oracle.schedule_with_tree(p, 1, budget=u + d)
+    assert order.tolist() == np.argsort(p.arrival, kind="stable").tolist()
+    comp = oracle.def2_completion(p, order, t_start=T)
+    same = sum(1 for a, b in zip(order[:-1], order[1:]) if user_of[a] == user_of[b])
+    assert comp[order[-1]] == T + n * (u + d) - u * same
+    # k-LPM with k = replication: every cycle consumes one whole user group, total n(u/k + d),
+    # and max TTFT <= T + n(u/k + d - s/k) for any arrival order
+    order = oracle.schedule_with_tree(p, k, budget=u + d)
+    for c in range(n // k):
+        assert len({int(user_of[q]) for q in order[c * k : (c + 1) * k]}) == 1
+    comp = oracle.def2_completion(p, order, t_start=T)
+    assert comp.max() == T + n * u // k + n * d
+    ttft = comp - p.arrival.astype(np.float64)
+    assert ttft.max() <= T + n * (u / k + d - s / k) + 1e-9
+
+
+# ----------------------------------------------------------------------------- commit / evict
+@pytest.mark.parametrize("seed", range(10))
+def test_commit_and_evict_equal_path_model(seed):
+    rng = np.random.default_rng(seed)
+    w = W.random_small(seed + 100, n_cache=10, n_query=24, vocab=3, max_len=8)
+    tree, model = oracle.OracleTree(), PathModel()
+    tree.build(w.cache)
+    model.commit(w.cache.as_lists(), 1 << 60)
+    assert tree.snapshot() == model.snapshot()
+    q = w.queries
+    qs = q.as_lists()
+    for step in range(4):
+        batch = rng.choice(q.n, size=6, replace=False).astype(np.int32)
+        budget = int(rng.integers(0, max(1, model.total())))
+        before = tree.total_tokens
+        st = tree.commit(q.tokens, q.off, q.len, batch, budget)
+        model.commit([qs[i] for i in batch], budget)
+        assert tree.snapshot() == model.snapshot()
+        assert tree.match(q.tokens, q.off, q.len).tolist() == [model.match(x) for x in qs]
+        # conservation and budget
+        assert before + st.inserted_tokens - st.evicted_tokens == st.total_tokens == model.total()
+        assert st.total_tokens <= budget
+
+
+def test_commit_invariants_on_config0():
+    w = W.config0()
+    tree = oracle.OracleTree()
+    st0 = tree.build(w.cache)
+    n_nodes, total, clock, rec, tok = parse_snapshot(tree.snapshot())
+    assert total == st0.total_tokens == int(rec["edge_len"].sum()) and clock == w.cache.n
+    # token conservation against brute-force overlaps: each prompt adds its length minus its best overlap
+    cached = w.cache.as_lists()
+    want = 0
+    for i, x in enumerate(cached):
+        want += len(x) - max((lcp(x, y) for y in cached[:i]), default=0)
+    assert total == want
+    # radix property: siblings start with distinct tokens, no empty edge; ticks never increase downwards
+    paths = snapshot_paths(tree.snapshot())
+    assert all(len(p) > 0 for p in paths)
+    by_parent = {}
+    for p in paths:
+        par = max((len(o) for o in paths if len(o) < len(p) and p[: len(o)] == o), default=0)
+        by_parent.setdefault(p[:par], []).append(p[par])
+        if par:
+            assert paths[p[:par]] >= paths[p]
+    assert all(len(v) == len(set(v)) for v in by_parent.values())
+    # leaf ticks pairwise distinct
+    leaves = [p for p in paths if not any(len(o) > len(p) and o[: len(p)] == p for o in paths)]
+    assert len({paths[p] for p in leaves}) == len(leaves)
+
+
+def test_structure_independent_of_insertion_order():
+    w = W.random_small(4242, n_cache=16, n_query=4, vocab=3, max_len=9)
+    rng = np.random.default_rng(0)
+    ref = None
+    for _ in range(5):
+        perm = rng.permutation(w.cache.n).astype(np.int32)
+        t = oracle.OracleTree()
+        t.commit(w.cache.tokens, w.cache.off, w.cache.len, perm, 1 << 60)
+        n_nodes, total, clock, rec, tok = parse_snapshot(t.snapshot())
+        shape = (rec["depth_start"].tolist(), rec["edge_len"].tolist(), rec["n_children"].tolist(), tok.tolist())
+        ref = ref or shape
+        assert shape == ref
+
+
+def test_split_at_prompt_end_either_order():
+    a = W.generators._from_lists([[1, 2], [1, 2, 3]])
+    for order in ([0, 1], [1, 0]):
+        t = oracle.OracleTree()
+        t.commit(a.tokens, a.off, a.len, np.array(order, np.int32), 1 << 60)
+        n_nodes, total, clock, rec, tok = parse_snapshot(t.snapshot())
+        assert n_nodes == 2 and total == 3 and rec["edge_len"].tolist() == [2, 1]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_lru_equals_sorted_prefix_rule(seed):
+    """Repeatedly removing the min-tick leaf == removing the shortest prefix of the nodes
+    ordered by (tick ascending, depth descending) that brings the total within budget."""
+    w = W.random_small(seed + 500, n_cache=30, n_query=2, vocab=3, max_len=10)
+    tree = oracle.OracleTree()
+    tree.build(w.cache)
+    paths = snapshot_paths(tree.snapshot())
+    total = tree.total_tokens
+    budget = total // 2
+
+    def edge_len(p):
+        return len(p) - max((len(o) for o in paths if len(o) < len(p) and p[: len(o)] == o), default=0)
+
+    order = sorted(paths, key=lambda p: (paths[p], -len(p)))
+    survivors = dict(paths)
+    remaining = total
+    for p in order:
+        if remaining <= budget:
+            break
+        remaining -= edge_len(p)
+        del survivors[p]
+    st = tree.commit(w.cache.tokens, w.cache.off, w.cache.len, np.zeros(0, np.int32), budget)
+    assert st.total_tokens == remaining <= budget
+    assert snapshot_paths(tree.snapshot()) == survivors
+
+
+# ----------------------------------------------------------------------------- stream glue
+def test_stream_simulation_bookkeeping():
+    s = W.config4_stream(steps=25, rate=12, groups=300, budget=60_000, batch=16)
+    r = oracle.simulate_stream(s, snapshot_every=5)
+    n = s.queries.n
+    seen = np.concatenate(r.batches)
+    assert len(set(seen.tolist())) == seen.shape[0]
+    assert all(st.total_tokens <= s.budget for st in r.stats)
+    assert all(len(b) <= s.batch for b in r.batches)
+    admitted = r.ttft >= 0
+    assert admitted.sum() == seen.shape[0] and (r.ttft[admitted] >= 1).all()
+    # a query is never admitted before the step it arrives in
+    step_of = np.searchsorted(s.step_start, np.arange(n), side="right") - 1
+    assert (r.admitted_step[admitted] >= step_of[admitted]).all()
+    # the simulated clock is the sum of per-step costs, each at least 1
+    assert r.clock >= s.steps
+    assert oracle.percentile_nearest_rank([5, 1, 3, 2, 4], 0.5) == 3
+    assert oracle.percentile_nearest_rank(np.arange(1, 101), 0.99) == 99
+
+
+def test_stream_fcfs_admits_in_arrival_order():
+    s = W.config4_stream(steps=20, rate=20, groups=100, budget=50_000, batch=8)
+    s.k = 1
+    r = oracle.simulate_stream(s)
+    flat = np.concatenate(r.batches)
+    assert (np.diff(flat) > 0).all()  # global ids are in arrival order, FCFS must preserve it
