@@ -1,0 +1,192 @@
+/*
+ * klpm.h - C ABI of the GPU-resident k-LPM scheduling step (MI355X / gfx950).
+ *
+ * One scheduling step of the k-LPM scheduler over a RadixAttention-style prefix cache:
+ *   match  : for every waiting query, the longest prefix of its prompt already held in the cache
+ *   select : the k-LPM batch (Algorithm 1), FCFS and LPM being its k = 1 and k = infinity endpoints
+ *   commit : insert the admitted prompts into the radix tree, then LRU-evict down to the KV budget
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE point to GPU memory owned by the caller; HOST pointers are ordinary
+ *     host memory.  The library never allocates or frees device memory: the tree lives inside an
+ *     arena the caller provides and keeps alive until kLPM_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues work on that stream and returns; outputs are valid once the stream has been
+ *     synchronised.  Only kLPM_snapshot / kLPM_snapshot_bytes / kLPM_read_stats synchronise.
+ *   - Return value: KLPM_OK or a negative KLPM_E* code.  Conditions only the device can see
+ *     (capacity exhausted, malformed offsets) set bits in the tree's sticky device_error word,
+ *     reported through kLPM_stats; the failing commit leaves the tree as it was before the call.
+ *   - Calls that use the same tree must be issued on one stream (or be externally ordered).
+ */
+#ifndef KLPM_H
+#define KLPM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KLPM_OK 0
+#define KLPM_EINVAL (-1) /* NULL pointer, negative count, inconsistent configuration */
+#define KLPM_EARENA (-2) /* arena or workspace too small / misaligned */
+#define KLPM_EHIP (-3)   /* a HIP runtime call or kernel launch failed */
+#define KLPM_ENOMEM (-4) /* host allocation failed */
+
+/* bits of kLPM_stats.device_error */
+#define KLPM_DEV_NODES_FULL 1u     /* not enough free node slots for the batch */
+#define KLPM_DEV_POOL_FULL 2u      /* edge-token pool cannot take the batch even after compaction */
+#define KLPM_DEV_BAD_INPUT 4u      /* a prompt offset/length outside the token buffer or limits */
+#define KLPM_DEV_BATCH_OVERFLOW 8u /* *n_selected larger than the capacity given to kLPM_commit */
+
+/* k value that encodes k = infinity (pure longest-prefix-match order); k = 0 means the same. */
+#define KLPM_K_INFINITY 0xFFFFFFFFu
+
+typedef void *kLPM_stream;
+typedef struct kLPM_tree kLPM_tree; /* opaque host-side handle */
+
+/* A query stream (x_i, t_i), i in [n] (Def. 1): token strings in CSR form plus arrival ticks. */
+typedef struct {
+    const int32_t *tokens;   /* DEVICE [n_tokens] token pool */
+    const int64_t *off;      /* DEVICE [n] start of prompt i in `tokens` */
+    const int32_t *len;      /* DEVICE [n] prompt length, 1 <= len <= max_prompt_len */
+    const uint64_t *arrival; /* DEVICE [n] arrival time t_i in integer ticks (may be NULL where unused) */
+    int64_t n_tokens;        /* size of `tokens`, used for bounds checks */
+    int32_t n;
+} kLPM_queries;
+
+typedef struct {
+    int64_t budget_tokens;  /* KV budget: eviction brings the cached token total down to <= this */
+    int64_t pool_tokens;    /* capacity of one half of the edge-token pool (two halves are kept);
+                               must hold the budget plus the tokens of one commit batch */
+    int32_t max_nodes;      /* node slots, root included */
+    int32_t max_batch;      /* most prompts one kLPM_commit may admit (<= 65536) */
+    int32_t max_prompt_len; /* longest prompt accepted */
+    uint32_t flags;         /* reserved, 0 */
+} kLPM_config;
+
+typedef struct {
+    int64_t total_tokens;    /* tokens held by the tree after the call */
+    int64_t inserted_tokens; /* new tokens added by this commit */
+    int64_t evicted_tokens;  /* tokens removed by this commit */
+    int32_t n_nodes;         /* non-root nodes after the call */
+    int32_t new_nodes;       /* nodes created by this commit (leaves and splits) */
+    int32_t evicted_nodes;
+    uint32_t device_error;   /* sticky KLPM_DEV_* bits */
+    uint64_t clock;          /* logical LRU clock = prompts admitted so far */
+} kLPM_stats;
+
+/* Bytes of device memory the arena needs for `cfg`. */
+int kLPM_arena_bytes(const kLPM_config *cfg, size_t *out_bytes);
+
+/*
+ * Build the prefix cache (RadixAttention radix tree, Sec. 1) inside `arena` (DEVICE, 256-byte
+ * aligned, arena_bytes >= kLPM_arena_bytes) from the prompts already processed.  Equivalent to
+ * committing initial[0..n) one by one with ticks 0..n-1 and no eviction; `initial` may be NULL or
+ * have n = 0 (empty cache, Def. 2: "the cache is empty initially").  initial->arrival is ignored.
+ * The handle is host memory owned by the library until kLPM_destroy.
+ */
+int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *arena, size_t arena_bytes,
+                    const kLPM_queries *initial, kLPM_stream stream);
+
+/*
+ * Prefix match of the whole waiting queue: match_len[i] = max over cached strings y of
+ * overlap(x_i, y), the length of the maximal common prefix (Sec. 1.2 Notation), token-granular,
+ * 0 <= match_len[i] <= len[i].  Read-only on the tree (recency is only touched by commit).
+ *   match_len  DEVICE [q->n] out
+ *   last_node  DEVICE [q->n] out or NULL: opaque id of the deepest node whose edge was entered
+ * A query whose span falls outside q->tokens gets match_len = -1 and sets KLPM_DEV_BAD_INPUT.
+ */
+int kLPM_match(kLPM_tree *tree, const kLPM_queries *q, int32_t *match_len, int32_t *last_node,
+               kLPM_stream stream);
+
+/* Workspace size for kLPM_select over n waiting queries. */
+int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
+
+/*
+ * k-LPM batch selection (Algorithm 1, with the processing order cut into bins of B, Sec. 2.1).
+ * Slot j of the batch is the oldest remaining query if (phase + j) mod k == 0, otherwise the
+ * remaining query with the longest match; ties go to the earlier arrival, then the lower index.
+ * k = 1 is FCFS; k = 0 or KLPM_K_INFINITY is pure LPM order (Sec. 4).
+ *   arrival, match_len  DEVICE [n] in
+ *   phase_inout         DEVICE [1]: position in the k-cycle, carried from step to step
+ *                       (write 0 before the call to restart the cycle every step)
+ *   batch_idx           DEVICE [min(batch, n)] out: queue indices in pick order
+ *   n_selected          DEVICE [1] out: min(batch, n)
+ *   workspace           DEVICE, >= kLPM_select_workspace_bytes(n), 256-byte aligned
+ * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
+ */
+int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
+                uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace,
+                size_t workspace_bytes, kLPM_stream stream);
+
+/*
+ * Commit a batch: for each admitted prompt, in pick order, give it the next tick of the logical
+ * clock, extend the tree to hold it (splitting an edge where the prompt diverges from it or ends
+ * inside it) and stamp the tick on every node of its path; then, while the token total exceeds the
+ * budget, remove the least-recently-used leaf (fixed-size cache with LRU eviction, Sec. 1, Sec. 2.1).
+ *   batch_idx   DEVICE [batch_cap] indices into q (as written by kLPM_select)
+ *   n_selected  DEVICE [1] number of valid entries, <= batch_cap <= cfg.max_batch
+ *   stats       DEVICE [1] out, or NULL
+ * Tokens are copied into the arena, so q's buffers may be recycled once the stream has passed.
+ */
+int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_idx, const int32_t *n_selected,
+                int32_t batch_cap, kLPM_stats *stats, kLPM_stream stream);
+
+/* Change the KV budget used by later commits (host-side, takes effect at the next kLPM_commit). */
+int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens);
+
+/*
+ * Waiting-queue bookkeeping of an online run (query stream of Def. 1 served in bins, Sec. 2.1;
+ * prefill cost of Def. 2 with c_attn = 0): given the batch just selected from a queue of n_wait
+ * entries, advance the simulated time by max(1, sum over the batch of len - match_len), record
+ * TTFT = new time - arrival for the admitted entries, remove them from the queue (order kept) and
+ * append n_new arrivals stamped with the new time.
+ *   wait_id     DEVICE [cap] in/out: global query ids of the waiting queue
+ *   wait_arr    DEVICE [cap] in/out: their arrival (enqueue) times
+ *   n_wait      DEVICE [1] in/out
+ *   match_len   DEVICE [n_wait] match lengths of the queue (as scored this step)
+ *   len_all     DEVICE [n_all] prompt length by global id
+ *   batch_idx / n_selected: as written by kLPM_select (indices into the queue)
+ *   new_id      DEVICE [n_new] global ids of the arrivals joining after this step
+ *   sim_clock   DEVICE [1] in/out simulated time
+ *   ttft        DEVICE [n_all] out (written for admitted ids only)
+ *   scratch     DEVICE, 256-byte aligned, >= 16 * max(cap,1) + 768 bytes
+ * Entries beyond `cap` set KLPM_DEV_BATCH_OVERFLOW in *dev_error (DEVICE [1]) and are dropped.
+ */
+int kLPM_queue_advance(int32_t *wait_id, uint64_t *wait_arr, int32_t *n_wait, int32_t cap,
+                       const int32_t *match_len, const int32_t *len_all, int32_t n_all,
+                       const int32_t *batch_idx, const int32_t *n_selected, int32_t batch_cap,
+                       const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
+                       void *scratch, size_t scratch_bytes, uint32_t *dev_error, kLPM_stream stream);
+
+/*
+ * Gather the CSR view of the waiting queue: off_out[i] = off_all[wait_id[i]], len_out[i] =
+ * len_all[wait_id[i]] for i < *n_wait (all DEVICE).  Lets match/select/commit run on the queue.
+ */
+int kLPM_queue_gather(const int32_t *wait_id, const int32_t *n_wait, int32_t cap, const int64_t *off_all,
+                      const int32_t *len_all, int32_t n_all, int64_t *off_out, int32_t *len_out,
+                      kLPM_stream stream);
+
+/* Synchronises the stream and copies the tree's counters to HOST memory. */
+int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_stream stream);
+
+/*
+ * Canonical tree state (synchronises).  Layout of the HOST buffer, little endian:
+ *   int64 n_nodes, int64 total_tokens, uint64 clock;
+ *   n_nodes records {int32 depth_start, int32 edge_len, uint64 tick, int32 n_children, int32 0}
+ *     in depth-first pre-order, children visited by ascending first edge token;
+ *   total_tokens int32 edge tokens in the same order.
+ * Node ids, pool offsets and hash layout are not part of the state.
+ */
+int kLPM_snapshot_bytes(kLPM_tree *tree, size_t *out_bytes, kLPM_stream stream);
+int kLPM_snapshot(kLPM_tree *tree, void *host_buf, size_t cap, size_t *out_bytes, kLPM_stream stream);
+
+int kLPM_destroy(kLPM_tree *tree);
+const char *kLPM_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KLPM_H */

@@ -1,0 +1,13 @@
+"""MI355X-native k-LPM scheduling step (match / select / commit) over a GPU-resident radix tree.
+
+The package is a binding of the C ABI declared in ``include/klpm.h``; all compute runs in the HIP
+library ``libklpm.so`` built from ``csrc/``.
+"""
+from .binding import (  # noqa: F401
+    Config, DeviceQueries, KlpmError, Stats, Tree, EXPORTS, KLPM_K_INFINITY, STATS_BYTES,
+    alloc_aligned, make_config, stats_from_tensor,
+    kLPM_arena_bytes, kLPM_build_tree, kLPM_commit, kLPM_destroy, kLPM_match, kLPM_queue_advance,
+    kLPM_queue_gather, kLPM_read_stats, kLPM_select, kLPM_select_workspace_bytes, kLPM_set_budget,
+    kLPM_snapshot,
+)
+from .pipeline import Scheduler, OnlineRun, size_config  # noqa: F401

@@ -1,0 +1,249 @@
+"""Thin Python binding of the C ABI in ``include/klpm.h`` (argument marshalling only).
+
+Every step of the scheduling path runs inside the HIP library; PyTorch is used for device memory
+and streams.  There is no CPU fallback: if the library cannot be loaded the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libklpm.so")
+
+KLPM_OK = 0
+KLPM_K_INFINITY = 0xFFFFFFFF
+DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
+
+EXPORTS = (
+    "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
+    "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_gather", "kLPM_read_stats",
+    "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
+)
+
+
+class Queries(C.Structure):
+    _fields_ = [("tokens", C.c_void_p), ("off", C.c_void_p), ("len", C.c_void_p), ("arrival", C.c_void_p),
+                ("n_tokens", C.c_int64), ("n", C.c_int32)]
+
+
+class Config(C.Structure):
+    _fields_ = [("budget_tokens", C.c_int64), ("pool_tokens", C.c_int64), ("max_nodes", C.c_int32),
+                ("max_batch", C.c_int32), ("max_prompt_len", C.c_int32), ("flags", C.c_uint32)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("total_tokens", C.c_int64), ("inserted_tokens", C.c_int64), ("evicted_tokens", C.c_int64),
+                ("n_nodes", C.c_int32), ("new_nodes", C.c_int32), ("evicted_nodes", C.c_int32),
+                ("device_error", C.c_uint32), ("clock", C.c_uint64)]
+
+
+STATS_BYTES = C.sizeof(Stats)
+
+
+def load_library() -> C.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build  # compiles with hipcc; raises if that is impossible
+        _build.build()
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_size_t
+    lib.kLPM_arena_bytes.argtypes = [C.POINTER(Config), C.POINTER(sz)]
+    lib.kLPM_build_tree.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, sz, C.POINTER(Queries), vp]
+    lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
+    lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
+    lib.kLPM_select.argtypes = [vp, vp, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
+    lib.kLPM_set_budget.argtypes = [vp, i64]
+    lib.kLPM_queue_advance.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, vp, vp, vp, sz, vp, vp]
+    lib.kLPM_queue_gather.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
+    lib.kLPM_read_stats.argtypes = [vp, C.POINTER(Stats), vp]
+    lib.kLPM_snapshot_bytes.argtypes = [vp, C.POINTER(sz), vp]
+    lib.kLPM_snapshot.argtypes = [vp, vp, sz, C.POINTER(sz), vp]
+    lib.kLPM_destroy.argtypes = [vp]
+    lib.kLPM_strerror.argtypes = [C.c_int]
+    lib.kLPM_strerror.restype = C.c_char_p
+    for name in EXPORTS:
+        if name != "kLPM_strerror":
+            getattr(lib, name).restype = C.c_int
+    return lib
+
+
+_lib = load_library()
+
+
+class KlpmError(RuntimeError):
+    pass
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != KLPM_OK:
+        raise KlpmError(f"{what}: {_lib.kLPM_strerror(rc).decode()} ({rc})")
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype, dtype)
+    return t
+
+
+@dataclass
+class DeviceQueries:
+    """Device-resident CSR prompts: tokens int32, off int64, len int32, arrival int64 (bits of uint64)."""
+
+    tokens: torch.Tensor
+    off: torch.Tensor
+    len: torch.Tensor
+    arrival: Optional[torch.Tensor]
+    n: int
+
+    @staticmethod
+    def from_host(p, device="cuda:0") -> "DeviceQueries":
+        tok = torch.from_numpy(np.ascontiguousarray(p.tokens, dtype=np.int32)).to(device)
+        if tok.numel() == 0:
+            tok = torch.zeros(1, dtype=torch.int32, device=device)
+        off = torch.from_numpy(np.ascontiguousarray(p.off, dtype=np.int64)).to(device)
+        ln = torch.from_numpy(np.ascontiguousarray(p.len, dtype=np.int32)).to(device)
+        arr = torch.from_numpy(np.ascontiguousarray(p.arrival, dtype=np.uint64).view(np.int64)).to(device)
+        return DeviceQueries(tok, off, ln, arr, int(p.len.shape[0]))
+
+    def c_struct(self) -> Queries:
+        return Queries(_dev(self.tokens, torch.int32).data_ptr(), _dev(self.off, torch.int64).data_ptr() if self.n else 0,
+                       _dev(self.len, torch.int32).data_ptr() if self.n else 0,
+                       0 if self.arrival is None else self.arrival.data_ptr(), int(self.tokens.numel()), int(self.n))
+
+
+class Tree:
+    """Owner of the arena tensor and the library handle."""
+
+    def __init__(self, handle: int, arena: torch.Tensor, cfg: Config):
+        self.handle = C.c_void_p(handle)
+        self.arena = arena
+        self.cfg = cfg
+
+    def close(self) -> None:
+        if self.handle:
+            _lib.kLPM_destroy(self.handle)
+            self.handle = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def make_config(budget_tokens: int, pool_tokens: int, max_nodes: int, max_batch: int, max_prompt_len: int) -> Config:
+    return Config(int(min(budget_tokens, (1 << 62))), int(pool_tokens), int(max_nodes), int(max_batch),
+                  int(max_prompt_len), 0)
+
+
+def kLPM_arena_bytes(cfg: Config) -> int:
+    out = C.c_size_t(0)
+    _check(_lib.kLPM_arena_bytes(C.byref(cfg), C.byref(out)), "kLPM_arena_bytes")
+    return int(out.value)
+
+
+def kLPM_build_tree(cfg: Config, initial: Optional[DeviceQueries], device="cuda:0", stream=None) -> Tree:
+    nbytes = kLPM_arena_bytes(cfg)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    base = (arena.data_ptr() + 255) // 256 * 256
+    handle = C.c_void_p(0)
+    q = initial.c_struct() if initial is not None else None
+    rc = _lib.kLPM_build_tree(C.byref(handle), C.byref(cfg), C.c_void_p(base), nbytes,
+                              C.byref(q) if q is not None else None, _stream(stream))
+    _check(rc, "kLPM_build_tree")
+    return Tree(handle.value, arena, cfg)
+
+
+def kLPM_match(tree: Tree, q: DeviceQueries, match_len: Optional[torch.Tensor] = None,
+               last_node: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if match_len is None:
+        match_len = torch.empty(max(q.n, 1), dtype=torch.int32, device=q.tokens.device)
+    qs = q.c_struct()
+    _check(_lib.kLPM_match(tree.handle, C.byref(qs), _ptr(match_len), _ptr(last_node), _stream(stream)), "kLPM_match")
+    return match_len[: q.n]
+
+
+def kLPM_select_workspace_bytes(n: int) -> int:
+    out = C.c_size_t(0)
+    _check(_lib.kLPM_select_workspace_bytes(int(n), C.byref(out)), "kLPM_select_workspace_bytes")
+    return int(out.value)
+
+
+def alloc_aligned(nbytes: int, device) -> Tuple[torch.Tensor, int]:
+    buf = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=device)
+    return buf, (buf.data_ptr() + 255) // 256 * 256
+
+
+def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, batch: int,
+                phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
+                workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None) -> None:
+    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), int(n), C.c_uint32(k & 0xFFFFFFFF), int(batch),
+                            _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
+                            int(workspace_bytes), _stream(stream)), "kLPM_select")
+
+
+def kLPM_commit(tree: Tree, q: DeviceQueries, batch_idx: Optional[torch.Tensor], n_selected: Optional[torch.Tensor],
+                batch_cap: int, stats: Optional[torch.Tensor] = None, stream=None) -> None:
+    qs = q.c_struct()
+    _check(_lib.kLPM_commit(tree.handle, C.byref(qs), _ptr(batch_idx), _ptr(n_selected), int(batch_cap), _ptr(stats),
+                            _stream(stream)), "kLPM_commit")
+
+
+def kLPM_set_budget(tree: Tree, budget_tokens: int) -> None:
+    _check(_lib.kLPM_set_budget(tree.handle, int(min(budget_tokens, 1 << 62))), "kLPM_set_budget")
+
+
+def kLPM_queue_advance(wait_id, wait_arr, n_wait, cap, match_len, len_all, n_all, batch_idx, n_selected, batch_cap,
+                       new_id, n_new, sim_clock, ttft, scratch: Tuple[torch.Tensor, int], scratch_bytes, dev_error,
+                       stream=None) -> None:
+    _check(_lib.kLPM_queue_advance(_ptr(wait_id), _ptr(wait_arr), _ptr(n_wait), int(cap), _ptr(match_len),
+                                   _ptr(len_all), int(n_all), _ptr(batch_idx), _ptr(n_selected), int(batch_cap),
+                                   _ptr(new_id), int(n_new), _ptr(sim_clock), _ptr(ttft), C.c_void_p(scratch[1]),
+                                   int(scratch_bytes), _ptr(dev_error), _stream(stream)), "kLPM_queue_advance")
+
+
+def kLPM_queue_gather(wait_id, n_wait, cap, off_all, len_all, n_all, off_out, len_out, stream=None) -> None:
+    _check(_lib.kLPM_queue_gather(_ptr(wait_id), _ptr(n_wait), int(cap), _ptr(off_all), _ptr(len_all), int(n_all),
+                                  _ptr(off_out), _ptr(len_out), _stream(stream)), "kLPM_queue_gather")
+
+
+def kLPM_read_stats(tree: Tree, stream=None) -> Stats:
+    st = Stats()
+    _check(_lib.kLPM_read_stats(tree.handle, C.byref(st), _stream(stream)), "kLPM_read_stats")
+    return st
+
+
+def stats_from_tensor(t: torch.Tensor) -> Stats:
+    """Decode a device kLPM_stats record (uint8 tensor of STATS_BYTES) after synchronising."""
+    raw = t.cpu().numpy().tobytes()
+    return Stats.from_buffer_copy(raw[:STATS_BYTES])
+
+
+def kLPM_snapshot(tree: Tree, stream=None) -> bytes:
+    need = C.c_size_t(0)
+    _check(_lib.kLPM_snapshot_bytes(tree.handle, C.byref(need), _stream(stream)), "kLPM_snapshot_bytes")
+    buf = np.zeros(int(need.value), dtype=np.uint8)
+    got = C.c_size_t(0)
+    _check(_lib.kLPM_snapshot(tree.handle, buf.ctypes.data_as(C.c_void_p), buf.shape[0], C.byref(got), _stream(stream)),
+           "kLPM_snapshot")
+    assert got.value == need.value
+    return buf.tobytes()
+
+
+def kLPM_destroy(tree: Tree) -> None:
+    tree.close()

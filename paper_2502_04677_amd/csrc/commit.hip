@@ -1,0 +1,653 @@
+// Commit: insert the admitted prompts into the flattened radix tree, then LRU-evict to the budget.
+//
+// The cache "stores the KV cache of processed queries" in a radix tree and evicts the least
+// recently used entries under a fixed memory size (Sec. 1; fixed pool, Sec. 2.1).  The serial
+// definition is: for each admitted prompt in pick order take the next tick, walk the prompt down
+// the tree, split the edge where it diverges or ends, hang the unmatched tail as a new leaf, stamp
+// the tick on the path; then repeatedly remove the smallest-tick leaf while over budget.
+//
+// The device formulation reaches the same tree state in parallel phases:
+//   1. match every admitted prompt against the pre-commit tree (the batched match kernel);
+//   2. copy every unmatched tail into one freshly reserved block of the token pool;
+//   3. structure pass: prompts that stopped at different places of the old tree touch disjoint
+//      structure (a split keeps the lower part's id, so an edge's end boundary and its children
+//      never move), so one wavefront per "stop place" inserts its prompts serially in pick order
+//      while different places proceed concurrently;
+//   4. tick pass: the final tick of a node is the largest tick of a prompt whose path contains it,
+//      an atomic max walking up from each prompt's end node;
+//   5. eviction: removing min-tick leaves one by one equals removing the shortest prefix of the
+//      nodes ordered by (tick ascending, depth descending) that frees enough tokens; the cut is
+//      found by a most-significant-digit-first search over weighted digit histograms, no sort.
+#include "klpm_internal.hpp"
+
+namespace klpm {
+
+constexpr uint64_t kNoGroup = ~0ull;
+constexpr int kPlanThreads = 1024;
+
+__device__ __forceinline__ void flag_error(DevState *st, uint32_t bit) { atomicOr(&st->device_error, bit); }
+
+// ------------------------------------------------------------------ begin / plan
+__global__ void k_commit_begin(TreeView tv, const int32_t *__restrict__ n_selected, int32_t batch_cap) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    DevState *st = tv.st;
+    int32_t nb = n_selected ? *n_selected : 0;
+    st->skip = 0;
+    st->alloc_cnt = 0;
+    st->need_compact = 0;
+    st->need_rebuild = 0;
+    st->do_evict = 0;
+    st->tail_total = 0;
+    st->inserted_tokens = 0;
+    st->evicted_tokens = 0;
+    st->new_nodes = 0;
+    st->evicted_nodes = 0;
+    if (nb < 0) nb = 0;
+    if (nb > batch_cap || nb > tv.max_batch) {
+        st->device_error |= 8u;  // KLPM_DEV_BATCH_OVERFLOW
+        st->skip = 1;
+        nb = 0;
+    }
+    int64_t free_nodes = (int64_t)(tv.max_nodes - st->n_slots) + (int64_t)st->free_cnt;
+    if (2ll * nb > free_nodes) {
+        st->device_error |= 1u;  // KLPM_DEV_NODES_FULL
+        st->skip = 1;
+        nb = 0;
+    }
+    st->nb = nb;
+    st->free_cnt0 = st->free_cnt;
+    st->n_slots0 = st->n_slots;
+    st->clock0 = st->clock;
+}
+
+// tail lengths -> offsets inside the pool block of this commit; group keys; capacity decision
+__global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView q,
+                                                              const int32_t *__restrict__ batch_idx, CommitWs ws) {
+    __shared__ int64_t buf[kPlanThreads];
+    __shared__ int64_t carry;
+    __shared__ int bad;
+    DevState *st = tv.st;
+    if (st->skip) return;
+    const int tid = threadIdx.x;
+    const int32_t nb = st->nb;
+    if (tid == 0) { carry = 0; bad = 0; }
+    __syncthreads();
+    for (int32_t base = 0; base < nb; base += kPlanThreads) {
+        int32_t j = base + tid;
+        int64_t tl = 0;
+        if (j < nb) {
+            int32_t m = ws.bm_len[j];
+            if (m < 0) {
+                atomicOr(&bad, 1);
+                ws.gkey[j] = kNoGroup;
+                ws.end_node[j] = kRoot;
+            } else {
+                int32_t qi = batch_idx[j];
+                int32_t L = q.len[qi];
+                int32_t e = ws.bm_node[j];
+                tl = (int64_t)(L - m);
+                bool inside = m < tv.depth_end[e];
+                uint64_t g;
+                if (!inside && m == L) {
+                    g = kNoGroup;  // already present and ending on a node boundary: ticks only
+                } else if (inside) {
+                    g = (uint64_t)(uint32_t)e << 33;
+                } else {
+                    int32_t nxt = q.tokens[q.off[qi] + m];
+                    g = ((uint64_t)(uint32_t)e << 33) | (1ull << 32) | (uint64_t)(uint32_t)nxt;
+                }
+                ws.gkey[j] = g;
+                ws.end_node[j] = e;
+            }
+        }
+        buf[tid] = tl;
+        __syncthreads();
+        for (int d = 1; d < kPlanThreads; d <<= 1) {
+            int64_t v = (tid >= d) ? buf[tid - d] : 0;
+            __syncthreads();
+            buf[tid] += v;
+            __syncthreads();
+        }
+        if (j < nb) ws.tail_off[j] = carry + buf[tid] - tl;
+        __syncthreads();
+        if (tid == kPlanThreads - 1) carry += buf[tid];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        st->tail_total = carry;
+        if (bad) {
+            st->skip = 1;
+        } else {
+            int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
+            if (st->pool_top + carry > half_end) st->need_compact = 1;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ pool compaction (rare)
+__global__ void k_compact_begin(TreeView tv) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    DevState *st = tv.st;
+    if (!st->need_compact) return;
+    st->compact_cursor = (int64_t)(1 - st->active_half) * tv.pool_half;
+}
+
+__global__ __launch_bounds__(256) void k_compact_copy(TreeView tv) {
+    DevState *st = tv.st;
+    if (!st->need_compact) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+    const int32_t n_slots = st->n_slots;
+    const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
+    for (int64_t id = 1 + wave; id < n_slots; id += n_waves) {
+        int32_t len = uni(tv.edge_len[id]);
+        if (len <= 0) continue;
+        int64_t src = uni64(tv.edge_off[id]);
+        int64_t dst = 0;
+        if (lane == 0) dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)len);
+        dst = uni64(dst);
+        if (dst + len > dst_end) {  // cannot happen while total_tokens <= pool_half
+            if (lane == 0) flag_error(st, 2u);
+            continue;
+        }
+        for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
+        if (lane == 0) tv.edge_off[id] = dst;
+    }
+}
+
+__global__ void k_compact_end(TreeView tv) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    DevState *st = tv.st;
+    if (!st->need_compact) return;
+    st->active_half = 1 - st->active_half;
+    st->pool_top = st->compact_cursor;
+    st->need_rebuild = 1;
+    int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
+    if (st->pool_top + st->tail_total > half_end) {
+        st->device_error |= 2u;  // KLPM_DEV_POOL_FULL
+        st->skip = 1;
+    }
+}
+
+// ------------------------------------------------------------------ child table rebuild
+__global__ __launch_bounds__(256) void k_hash_clear(TreeView tv) {
+    if (!tv.st->need_rebuild) return;
+    const int64_t n = (int64_t)tv.slot_mask + 1;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        tv.slots[i].key = kEmptyKey;
+}
+
+__global__ __launch_bounds__(256) void k_hash_fill(TreeView tv) {
+    DevState *st = tv.st;
+    if (!st->need_rebuild) return;
+    const int32_t n_slots = st->n_slots;
+    for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < n_slots;
+         id += (int64_t)gridDim.x * blockDim.x) {
+        int32_t len = tv.edge_len[id];
+        if (len <= 0) continue;
+        int64_t off = tv.edge_off[id];
+        uint64_t key = make_key(tv.parent[id], tv.pool[off]);
+        uint32_t h = hash_key(key) & tv.slot_mask;
+        for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+            unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key, (unsigned long long)kEmptyKey,
+                                                (unsigned long long)key);
+            if (prev == (unsigned long long)kEmptyKey) {
+                tv.slots[h].child = (int32_t)id;
+                tv.slots[h].edge_len = len;
+                tv.slots[h].edge_off = off;
+                break;
+            }
+            h = (h + 1) & tv.slot_mask;
+        }
+    }
+}
+
+__global__ void k_rebuild_done(TreeView tv) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) tv.st->need_rebuild = 0;
+}
+
+// ------------------------------------------------------------------ tails
+__global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                    CommitWs ws) {
+    DevState *st = tv.st;
+    if (st->skip) return;
+    const int32_t j = blockIdx.x;
+    if (j >= st->nb) return;
+    const int32_t qi = batch_idx[j];
+    const int32_t m = ws.bm_len[j];
+    const int32_t L = q.len[qi];
+    const int32_t *__restrict__ src = q.tokens + q.off[qi] + m;
+    int32_t *__restrict__ dst = tv.pool + st->pool_top + ws.tail_off[j];
+    for (int32_t i = threadIdx.x; i < L - m; i += blockDim.x) dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------ structure pass
+// Loads that must observe other compute units' table inserts bypass the per-CU cache.
+__device__ __forceinline__ uint64_t ld_u64(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t ld_i32(const int32_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int64_t ld_i64(const int64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ int32_t slot_find_live(const TreeView &tv, uint64_t key, int32_t &child, int32_t &edge_len,
+                                                  int64_t &edge_off) {
+    uint32_t h = hash_key(key) & tv.slot_mask;
+    for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+        uint64_t k = ld_u64(&tv.slots[h].key);
+        if (k == key) {
+            child = ld_i32(&tv.slots[h].child);
+            edge_len = ld_i32(&tv.slots[h].edge_len);
+            edge_off = ld_i64(&tv.slots[h].edge_off);
+            return (int32_t)h;
+        }
+        if (k == kEmptyKey) return -1;
+        h = (h + 1) & tv.slot_mask;
+    }
+    return -1;
+}
+
+// lane 0 only
+__device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key, int32_t child, int32_t edge_len,
+                                               int64_t edge_off) {
+    uint32_t h = hash_key(key) & tv.slot_mask;
+    for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+        unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key, (unsigned long long)kEmptyKey,
+                                            (unsigned long long)key);
+        if (prev == (unsigned long long)kEmptyKey) {
+            tv.slots[h].child = child;
+            tv.slots[h].edge_len = edge_len;
+            tv.slots[h].edge_off = edge_off;
+            return (int32_t)h;
+        }
+        h = (h + 1) & tv.slot_mask;
+    }
+    return -1;
+}
+
+// lane 0 only
+__device__ __forceinline__ int32_t alloc_node(const TreeView &tv) {
+    DevState *st = tv.st;
+    int32_t a = atomicAdd(&st->alloc_cnt, 1);
+    int32_t id = (a < st->free_cnt0) ? tv.free_stack[st->free_cnt0 - 1 - a] : st->n_slots0 + (a - st->free_cnt0);
+    if (id <= 0 || id >= tv.max_nodes) {
+        flag_error(st, 1u);
+        return -1;
+    }
+    return id;
+}
+
+// Split node c (reached through table slot s) after its first `at` edge tokens. The new node takes
+// the upper part; c keeps the lower part, its id, its end boundary, its children and its tick.
+// Returns the new upper node (wave-uniform) or -1.
+__device__ __forceinline__ int32_t split_node(const TreeView &tv, int32_t c, int32_t s, int32_t at, uint64_t tick,
+                                              int lane) {
+    int32_t up = -1;
+    if (lane == 0) {
+        up = alloc_node(tv);
+        if (up > 0) {
+            int64_t eo = ld_i64(&tv.edge_off[c]);
+            int32_t el = ld_i32(&tv.edge_len[c]);
+            int32_t de = ld_i32(&tv.depth_end[c]);
+            tv.parent[up] = ld_i32(&tv.parent[c]);
+            tv.edge_off[up] = eo;
+            tv.edge_len[up] = at;
+            tv.depth_end[up] = de - el + at;
+            tv.tick[up] = tick;
+            tv.slots[s].child = up;
+            tv.slots[s].edge_len = at;
+            tv.edge_off[c] = eo + at;
+            tv.edge_len[c] = el - at;
+            tv.parent[c] = up;
+            slot_insert(tv, make_key(up, tv.pool[eo + at]), c, el - at, eo + at);
+            atomicAdd(&tv.st->new_nodes, 1);
+        }
+    }
+    up = uni(__shfl(up, 0));
+    __syncthreads();
+    return up;
+}
+
+__device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t *__restrict__ batch_idx,
+                              const CommitWs &ws, int32_t j, int lane) {
+    DevState *st = tv.st;
+    const int32_t qi = uni(batch_idx[j]);
+    const int64_t qoff = uni64(q.off[qi]);
+    const int32_t L = uni(q.len[qi]);
+    const int32_t m = uni(ws.bm_len[j]);
+    const int32_t e = uni(ws.bm_node[j]);
+    const uint64_t tick = st->clock0 + (uint64_t)j;
+    const int64_t tail_base = st->pool_top + ws.tail_off[j];  // pool index holding x[m]
+    const int32_t *__restrict__ x = q.tokens + qoff;
+
+    int32_t cur = e;
+    int32_t d = m;
+    if (e != kRoot && m < uni(ld_i32(&tv.depth_end[e]))) {
+        // The match stopped inside the edge that node e had before this commit. Earlier prompts of
+        // this group may have cut that edge into a chain of pieces ending in e; find the piece
+        // whose span (start, end] contains depth m.
+        for (int guard = 0; guard <= tv.max_batch + 1; ++guard) {
+            int32_t ds = uni(ld_i32(&tv.depth_end[cur])) - uni(ld_i32(&tv.edge_len[cur]));
+            if (ds < m) break;
+            cur = uni(ld_i32(&tv.parent[cur]));
+        }
+        int32_t de = uni(ld_i32(&tv.depth_end[cur]));
+        if (m < de) {
+            int32_t el = uni(ld_i32(&tv.edge_len[cur]));
+            int32_t ds = de - el;
+            int32_t c2, el2;
+            int64_t eo2;
+            int64_t eo = uni64(ld_i64(&tv.edge_off[cur]));
+            int32_t s = slot_find_live(tv, make_key(uni(ld_i32(&tv.parent[cur])), uni(tv.pool[eo])), c2, el2, eo2);
+            if (s < 0 || uni(c2) != cur || m - ds <= 0) {
+                if (lane == 0) flag_error(st, 4u);
+                return;
+            }
+            int32_t up = split_node(tv, cur, uni(s), m - ds, tick, lane);
+            if (up < 0) return;
+            cur = up;
+        }
+    }
+    // From here on every child met is a node created by this commit; compare for real.
+    while (d < L) {
+        int32_t tok = uni(x[d]);
+        int32_t c, el;
+        int64_t eo;
+        int32_t s = uni(slot_find_live(tv, make_key(cur, tok), c, el, eo));
+        if (s < 0) {
+            int32_t leaf = -1;
+            if (lane == 0) {
+                leaf = alloc_node(tv);
+                if (leaf > 0) {
+                    int64_t off = tail_base + (int64_t)(d - m);
+                    tv.parent[leaf] = cur;
+                    tv.edge_off[leaf] = off;
+                    tv.edge_len[leaf] = L - d;
+                    tv.depth_end[leaf] = L;
+                    tv.tick[leaf] = tick;
+                    slot_insert(tv, make_key(cur, tok), leaf, L - d, off);
+                    atomicAdd((unsigned long long *)&st->inserted_tokens, (unsigned long long)(L - d));
+                    atomicAdd(&st->new_nodes, 1);
+                }
+            }
+            leaf = uni(__shfl(leaf, 0));
+            __syncthreads();
+            if (leaf < 0) return;
+            cur = leaf;
+            d = L;
+            break;
+        }
+        c = uni(c);
+        el = uni(el);
+        eo = uni64(eo);
+        int32_t lim = el < L - d ? el : L - d;
+        int32_t jj = wave_common_prefix(x + d, tv.pool + eo, lim, lane);
+        if (jj <= 0) {  // the first token matched by construction; anything else is corruption
+            if (lane == 0) flag_error(st, 4u);
+            return;
+        }
+        if (jj == el) {
+            cur = c;
+            d += el;
+            continue;
+        }
+        int32_t up = split_node(tv, c, s, jj, tick, lane);
+        if (up < 0) return;
+        cur = up;
+        d += jj;
+    }
+    if (lane == 0) ws.end_node[j] = cur;
+}
+
+__global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                     CommitWs ws) {
+    DevState *st = tv.st;
+    if (st->skip) return;
+    const int lane = threadIdx.x;
+    const int32_t g = blockIdx.x;
+    const int32_t nb = st->nb;
+    if (g >= nb) return;
+    const uint64_t key = ws.gkey[g];
+    if (key == kNoGroup) return;
+    // the first prompt of a group (in pick order) owns the group
+    for (int32_t base = 0; base < g; base += kWave) {
+        int32_t i = base + lane;
+        bool eq = (i < g) && (ws.gkey[i] == key);
+        if (__ballot(eq)) return;
+    }
+    insert_prompt(tv, q, batch_idx, ws, g, lane);
+    for (int32_t base = g + 1; base < nb; base += kWave) {
+        int32_t i = base + lane;
+        bool eq = (i < nb) && (ws.gkey[i] == key);
+        uint64_t mask = __ballot(eq);
+        while (mask) {
+            int32_t b = (int32_t)__builtin_ctzll(mask);
+            mask &= mask - 1ull;
+            insert_prompt(tv, q, batch_idx, ws, base + b, lane);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ ticks
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws) {
+    DevState *st = tv.st;
+    if (st->skip) return;
+    const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= st->nb) return;
+    const uint64_t t = st->clock0 + (uint64_t)j;
+    int32_t v = ws.end_node[j];
+    for (int32_t guard = 0; guard <= tv.max_prompt_len && v > kRoot && v < tv.max_nodes; ++guard) {
+        unsigned long long old = atomicMax((unsigned long long *)&tv.tick[v], (unsigned long long)t);
+        // a strictly later prompt already stamped this node and stamps its ancestors too; an equal
+        // value is this prompt's own stamp on a node it created, so keep climbing
+        if (old > (unsigned long long)t) break;
+        v = tv.parent[v];
+    }
+}
+
+// ------------------------------------------------------------------ mid: publish the inserts, decide eviction
+__global__ void k_commit_mid(TreeView tv, CommitWs ws, int64_t budget) {
+    DevState *st = tv.st;
+    const int tid = threadIdx.x;
+    if (blockIdx.x != 0) return;
+    __shared__ int evict;
+    if (tid == 0) {
+        evict = 0;
+        if (!st->skip) {
+            st->clock = st->clock0 + (uint64_t)st->nb;
+            int32_t a = st->alloc_cnt;
+            if (a <= st->free_cnt0) {
+                st->free_cnt = st->free_cnt0 - a;
+            } else {
+                st->free_cnt = 0;
+                st->n_slots = st->n_slots0 + (a - st->free_cnt0);
+            }
+            st->pool_top += st->tail_total;
+            st->total_tokens += st->inserted_tokens;
+            st->n_nodes += st->new_nodes;
+            int64_t need = st->total_tokens - budget;
+            if (need > 0) {
+                st->do_evict = 1;
+                st->need_evict = need;
+                evict = 1;
+            }
+        }
+    }
+    __syncthreads();
+    if (evict)
+        for (int i = tid; i < 8 * 256; i += blockDim.x) ws.evict_hist[i] = 0;
+}
+
+// ------------------------------------------------------------------ eviction
+// Order of removal: tick ascending, then depth descending (the deepest node of the oldest path is
+// the one leaf carrying the smallest tick).  key = tick * 2^depth_bits + (depth_mask - depth_end).
+__device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, int depth_bits) {
+    uint64_t dm = (1ull << depth_bits) - 1ull;
+    return (tv.tick[id] << depth_bits) | (dm - (uint64_t)(uint32_t)tv.depth_end[id]);
+}
+
+// after `upto` finished passes: the key digits fixed so far and the tokens still to free inside them
+__device__ void evict_descend(const int64_t *__restrict__ hist, int upto, int64_t need, uint64_t *prefix_out,
+                              int64_t *rem_out) {
+    // block of 256 threads; every thread returns the same values
+    __shared__ int64_t sc[256];
+    __shared__ int pick;
+    const int tid = threadIdx.x;
+    uint64_t prefix = 0;
+    int64_t rem = need;
+    for (int p = 0; p < upto; ++p) {
+        int64_t h = hist[p * 256 + tid];
+        sc[tid] = h;
+        if (tid == 0) pick = 255;
+        __syncthreads();
+        for (int d = 1; d < 256; d <<= 1) {
+            int64_t v = (tid >= d) ? sc[tid - d] : 0;
+            __syncthreads();
+            sc[tid] += v;
+            __syncthreads();
+        }
+        // smallest digit whose inclusive weight reaches what is still needed
+        if (sc[tid] >= rem) atomicMin(&pick, tid);
+        __syncthreads();
+        int dg = pick;
+        int64_t below = (dg > 0) ? sc[dg - 1] : 0;
+        __syncthreads();
+        rem -= below;
+        prefix = (prefix << 8) | (uint64_t)dg;
+    }
+    *prefix_out = prefix;
+    *rem_out = rem;
+}
+
+__global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, int pass, int n_pass, int depth_bits) {
+    DevState *st = tv.st;
+    if (!st->do_evict) return;
+    __shared__ unsigned long long h[256];
+    const int tid = threadIdx.x;
+    uint64_t prefix;
+    int64_t rem;
+    evict_descend(ws.evict_hist, pass, st->need_evict, &prefix, &rem);
+    h[tid] = 0;
+    __syncthreads();
+    const int shift = 8 * (n_pass - 1 - pass);
+    const int32_t n_slots = st->n_slots;
+    for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
+        int32_t len = tv.edge_len[id];
+        if (len <= 0) continue;
+        uint64_t key = evict_key(tv, id, depth_bits);
+        bool in_prefix = (pass == 0) || ((key >> (shift + 8)) == prefix);
+        if (in_prefix) atomicAdd(&h[(key >> shift) & 255ull], (unsigned long long)len);
+    }
+    __syncthreads();
+    if (h[tid]) atomicAdd((unsigned long long *)&ws.evict_hist[pass * 256 + tid], h[tid]);
+}
+
+__global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int n_pass, int depth_bits) {
+    DevState *st = tv.st;
+    if (!st->do_evict) return;
+    __shared__ unsigned long long s_tok;
+    __shared__ int s_cnt;
+    const int tid = threadIdx.x;
+    uint64_t cut;
+    int64_t rem;
+    evict_descend(ws.evict_hist, n_pass, st->need_evict, &cut, &rem);
+    if (tid == 0) { s_tok = 0; s_cnt = 0; }
+    __syncthreads();
+    const int32_t n_slots = st->n_slots;
+    for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
+        int32_t len = tv.edge_len[id];
+        if (len <= 0) continue;
+        if (evict_key(tv, id, depth_bits) <= cut) {
+            tv.edge_len[id] = 0;
+            int32_t pos = atomicAdd(&st->free_cnt, 1);
+            if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
+            atomicAdd(&s_tok, (unsigned long long)len);
+            atomicAdd(&s_cnt, 1);
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && s_cnt) {
+        atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
+        atomicAdd(&st->evicted_nodes, s_cnt);
+    }
+}
+
+__global__ void k_evict_end(TreeView tv) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    DevState *st = tv.st;
+    if (!st->do_evict) return;
+    st->total_tokens -= st->evicted_tokens;
+    st->n_nodes -= st->evicted_nodes;
+    if (st->evicted_nodes > 0) st->need_rebuild = 1;
+}
+
+__global__ void k_commit_end(TreeView tv, kLPM_stats *__restrict__ out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    DevState *st = tv.st;
+    st->need_rebuild = 0;
+    if (!out) return;
+    out->total_tokens = st->total_tokens;
+    out->inserted_tokens = st->skip ? 0 : st->inserted_tokens;
+    out->evicted_tokens = st->evicted_tokens;
+    out->n_nodes = st->n_nodes;
+    out->new_nodes = st->skip ? 0 : st->new_nodes;
+    out->evicted_nodes = st->evicted_nodes;
+    out->device_error = st->device_error;
+    out->clock = st->clock;
+}
+
+static void launch_rebuild(const TreeView &tv, hipStream_t stream) {
+    int64_t n = (int64_t)tv.slot_mask + 1;
+    unsigned gc = (unsigned)((n + 255) / 256);
+    if (gc > 4096u) gc = 4096u;
+    unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
+    if (gf > 4096u) gf = 4096u;
+    hipLaunchKernelGGL(k_hash_clear, dim3(gc), dim3(256), 0, stream, tv);
+    hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv);
+}
+
+int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
+                    int32_t batch_cap, int64_t budget, kLPM_stats *stats_out, hipStream_t stream) {
+    const TreeView &tv = t->tv;
+    const CommitWs &ws = t->ws;
+    if (batch_cap > t->cfg.max_batch) batch_cap = t->cfg.max_batch;
+    hipLaunchKernelGGL(k_commit_begin, dim3(1), dim3(1), 0, stream, tv, n_selected, batch_cap);
+    if (batch_cap > 0) {
+        int rc = launch_match(tv, q, batch_idx, &tv.st->nb, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, ws);
+        unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
+        if (gn > 2048u) gn = 2048u;
+        hipLaunchKernelGGL(k_compact_begin, dim3(1), dim3(1), 0, stream, tv);
+        hipLaunchKernelGGL(k_compact_copy, dim3(gn), dim3(256), 0, stream, tv);
+        hipLaunchKernelGGL(k_compact_end, dim3(1), dim3(1), 0, stream, tv);
+        launch_rebuild(tv, stream);
+        hipLaunchKernelGGL(k_rebuild_done, dim3(1), dim3(1), 0, stream, tv);
+        hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws);
+        hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
+        hipLaunchKernelGGL(k_ticks, dim3((batch_cap + 255) / 256), dim3(256), 0, stream, tv, ws);
+    }
+    hipLaunchKernelGGL(k_commit_mid, dim3(1), dim3(256), 0, stream, tv, ws, budget);
+    // eviction key = (tick, inverted depth); its width follows from host-known upper bounds
+    t->clock_ub += (uint64_t)(batch_cap > 0 ? batch_cap : 0);
+    int tick_bits = 1;
+    while (tick_bits < 64 && (t->clock_ub >> tick_bits)) ++tick_bits;
+    int key_bits = tick_bits + t->depth_bits;
+    if (key_bits > 64) return KLPM_EINVAL;
+    int n_pass = (key_bits + 7) / 8;
+    unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
+    if (ge > 1024u) ge = 1024u;
+    for (int p = 0; p < n_pass; ++p)
+        hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, n_pass, t->depth_bits);
+    hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, t->depth_bits);
+    hipLaunchKernelGGL(k_evict_end, dim3(1), dim3(1), 0, stream, tv);
+    launch_rebuild(tv, stream);
+    hipLaunchKernelGGL(k_commit_end, dim3(1), dim3(1), 0, stream, tv, stats_out);
+    return check_launch();
+}
+
+}  // namespace klpm

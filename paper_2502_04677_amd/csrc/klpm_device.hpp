@@ -1,0 +1,163 @@
+// Device-side layout of the flattened radix tree and helpers shared by the HIP kernels.
+//
+// The prefix cache of RadixAttention (Sec. 1 of the paper) is kept entirely in HBM as
+//   - structure-of-arrays node records (one node = one edge from its parent),
+//   - an edge-token pool holding every edge label as a contiguous span,
+//   - an open-addressing child table keyed by (parent id, first edge token) whose slots also carry
+//     the child's edge span, so that one 32-byte slot read is enough to start comparing tokens.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace klpm {
+
+constexpr int kWave = 64;
+constexpr int32_t kRoot = 0;
+constexpr uint64_t kEmptyKey = ~0ull;
+
+// Child-table slot. key = (parent id << 32) | first edge token.
+struct __attribute__((aligned(32))) Slot {
+    uint64_t key;
+    int32_t child;
+    int32_t edge_len;
+    int64_t edge_off;
+    int64_t pad;
+};
+static_assert(sizeof(Slot) == 32, "slot must be 32 bytes");
+
+// Counters and per-call scalars, at the start of the arena.
+struct DevState {
+    int64_t total_tokens;  // tokens held by live nodes
+    uint64_t clock;        // logical LRU clock: prompts admitted so far
+    int64_t pool_top;      // absolute pool index of the next free token in the active half
+    int32_t n_nodes;       // live non-root nodes
+    int32_t n_slots;       // node ids in [0, n_slots) have been handed out at some time
+    int32_t free_cnt;      // entries on the free-id stack
+    int32_t active_half;   // which half of the pool holds the live spans
+    uint32_t device_error; // sticky KLPM_DEV_* bits
+    // ---- scalars of the commit in flight ----
+    int32_t nb;            // admitted prompts in this commit
+    int32_t skip;          // 1 = this commit is abandoned (error), later kernels do nothing
+    int32_t alloc_cnt;     // node ids handed out during the structure pass
+    int32_t free_cnt0;     // free_cnt / n_slots / pool_top / clock at the start of the structure pass
+    int32_t n_slots0;
+    int32_t need_compact;
+    int32_t need_rebuild;
+    int32_t do_evict;
+    int32_t pad0;
+    int64_t pool_top0;
+    uint64_t clock0;
+    int64_t tail_total;    // tokens of all unmatched tails of the batch
+    int64_t compact_cursor;
+    int64_t need_evict;    // tokens that must go
+    int64_t inserted_tokens;
+    int64_t evicted_tokens;
+    int32_t new_nodes;
+    int32_t evicted_nodes;
+};
+
+// Everything a kernel needs to walk or edit the tree; passed by value.
+struct TreeView {
+    DevState *st;
+    int32_t *parent;
+    int64_t *edge_off;   // absolute index into pool
+    int32_t *edge_len;   // 0 = dead slot (root is id 0 with length 0)
+    int32_t *depth_end;  // tokens from the root to the end of this node's edge
+    uint64_t *tick;      // last-use tick
+    int32_t *free_stack;
+    Slot *slots;
+    uint32_t slot_mask;  // number of slots - 1 (power of two)
+    int32_t max_nodes;
+    int32_t *pool;       // 2 * pool_half tokens
+    int64_t pool_half;
+    int32_t max_prompt_len;
+    int32_t max_batch;
+};
+
+// Per-commit device workspace (inside the arena).
+struct CommitWs {
+    int32_t *bm_len;    // [max_batch] match length of admitted prompt j against the pre-commit tree
+    int32_t *bm_node;   // [max_batch] node where that match stopped
+    int64_t *tail_off;  // [max_batch] offset of prompt j's unmatched tail inside this commit's pool block
+    uint64_t *gkey;     // [max_batch] key of the group of prompts that may touch the same new structure
+    int32_t *end_node;  // [max_batch] node at which prompt j ends after insertion
+    int64_t *evict_hist; // [8][256] weighted digit histograms of the eviction threshold search
+    int32_t *iota_idx;  // [max_batch] scratch batch indices for build_tree
+    int32_t *iota_n;    // [1]
+};
+
+struct QView {
+    const int32_t *tokens;
+    const int64_t *off;
+    const int32_t *len;
+    int64_t n_tokens;
+    int32_t n;
+};
+
+__device__ __forceinline__ uint64_t make_key(int32_t parent, int32_t tok) {
+    return ((uint64_t)(uint32_t)parent << 32) | (uint64_t)(uint32_t)tok;
+}
+
+__device__ __forceinline__ uint32_t hash_key(uint64_t k) {
+    // 64-bit finaliser of the public-domain MurmurHash3
+    k ^= k >> 33;
+    k *= 0xff51afd7ed558ccdULL;
+    k ^= k >> 33;
+    k *= 0xc4ceb9fe1a85ec53ULL;
+    k ^= k >> 33;
+    return (uint32_t)k;
+}
+
+// Wave-uniform value: tells the compiler the value is the same in every lane (keeps it in an SGPR).
+__device__ __forceinline__ int32_t uni(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uni64(int64_t v) {
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)(uint64_t)v);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Read-only probe (tree not being modified by this kernel). Returns the slot index or -1 and, when
+// found, the child's id and edge span. All arguments are wave-uniform.
+__device__ __forceinline__ int32_t slot_find(const Slot *__restrict__ slots, uint32_t mask, uint64_t key,
+                                             int32_t &child, int32_t &edge_len, int64_t &edge_off) {
+    uint32_t h = hash_key(key) & mask;
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        const Slot s = slots[h];
+        if (s.key == key) {
+            child = s.child;
+            edge_len = s.edge_len;
+            edge_off = s.edge_off;
+            return (int32_t)h;
+        }
+        if (s.key == kEmptyKey) return -1;
+        h = (h + 1) & mask;
+    }
+    return -1;
+}
+
+// Number of leading positions (< lim) where a[] and b[] agree; the whole wavefront cooperates.
+// Each lane reads single dwords so neither span needs any alignment; four 64-token rows are
+// issued before the first compare to keep 2 KB per wave in flight.
+__device__ __forceinline__ int32_t wave_common_prefix(const int32_t *__restrict__ a, const int32_t *__restrict__ b,
+                                                      int32_t lim, int lane) {
+    for (int32_t base = 0; base < lim; base += 4 * kWave) {
+        int32_t i0 = base + lane, i1 = i0 + kWave, i2 = i1 + kWave, i3 = i2 + kWave;
+        int32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0, b0 = 0, b1 = 0, b2 = 0, b3 = 0;
+        if (i0 < lim) { a0 = a[i0]; b0 = b[i0]; }
+        if (i1 < lim) { a1 = a[i1]; b1 = b[i1]; }
+        if (i2 < lim) { a2 = a[i2]; b2 = b[i2]; }
+        if (i3 < lim) { a3 = a[i3]; b3 = b[i3]; }
+        uint64_t m0 = __ballot(i0 < lim && a0 != b0);
+        if (m0) return base + (int32_t)__builtin_ctzll(m0);
+        uint64_t m1 = __ballot(i1 < lim && a1 != b1);
+        if (m1) return base + kWave + (int32_t)__builtin_ctzll(m1);
+        uint64_t m2 = __ballot(i2 < lim && a2 != b2);
+        if (m2) return base + 2 * kWave + (int32_t)__builtin_ctzll(m2);
+        uint64_t m3 = __ballot(i3 < lim && a3 != b3);
+        if (m3) return base + 3 * kWave + (int32_t)__builtin_ctzll(m3);
+    }
+    return lim;
+}
+
+}  // namespace klpm

@@ -1,0 +1,472 @@
+// Arena layout, tree construction, the match/commit entry points, the canonical snapshot and the
+// waiting-queue bookkeeping of an online run.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "klpm_internal.hpp"
+
+namespace klpm {
+
+struct Layout {
+    size_t state, parent, edge_off, edge_len, depth_end, tick, free_stack, slots, pool;
+    size_t bm_len, bm_node, tail_off, gkey, end_node, evict_hist, iota_idx, iota_n;
+    size_t total;
+    uint32_t n_slots_table;
+};
+
+static bool config_ok(const kLPM_config *c) {
+    return c && c->budget_tokens >= 0 && c->pool_tokens > 0 && c->max_nodes >= 2 && c->max_nodes <= (1 << 30) &&
+           c->max_batch >= 1 && c->max_batch <= 65536 && c->max_prompt_len >= 1 && c->max_prompt_len <= (1 << 28) &&
+           c->pool_tokens <= (int64_t)1 << 40;
+}
+
+static Layout make_layout(const kLPM_config &c) {
+    Layout L;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
+    uint32_t ns = 64;
+    while (ns < 2u * (uint32_t)c.max_nodes) ns <<= 1;
+    L.n_slots_table = ns;
+    size_t mn = (size_t)c.max_nodes, mb = (size_t)c.max_batch;
+    L.state = take(sizeof(DevState));
+    L.parent = take(mn * 4);
+    L.edge_off = take(mn * 8);
+    L.edge_len = take(mn * 4);
+    L.depth_end = take(mn * 4);
+    L.tick = take(mn * 8);
+    L.free_stack = take(mn * 4);
+    L.slots = take((size_t)ns * sizeof(Slot));
+    L.pool = take((size_t)c.pool_tokens * 2 * 4);
+    L.bm_len = take(mb * 4);
+    L.bm_node = take(mb * 4);
+    L.tail_off = take(mb * 8);
+    L.gkey = take(mb * 8);
+    L.end_node = take(mb * 4);
+    L.evict_hist = take(8 * 256 * 8);
+    L.iota_idx = take(mb * 4);
+    L.iota_n = take(256);
+    L.total = o;
+    return L;
+}
+
+__global__ __launch_bounds__(256) void k_tree_init(TreeView tv) {
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t ns = (int64_t)tv.slot_mask + 1;
+    for (int64_t i = gid; i < ns; i += stride) {
+        tv.slots[i].key = kEmptyKey;
+        tv.slots[i].child = -1;
+        tv.slots[i].edge_len = 0;
+        tv.slots[i].edge_off = 0;
+        tv.slots[i].pad = 0;
+    }
+    for (int64_t i = gid; i < tv.max_nodes; i += stride) {
+        tv.parent[i] = -1;
+        tv.edge_off[i] = 0;
+        tv.edge_len[i] = 0;
+        tv.depth_end[i] = 0;
+        tv.tick[i] = 0;
+        tv.free_stack[i] = 0;
+    }
+    if (gid == 0) {
+        DevState *st = tv.st;
+        char *p = (char *)st;
+        for (size_t b = 0; b < sizeof(DevState); ++b) p[b] = 0;
+        st->n_slots = 1;  // id 0 is the root
+    }
+}
+
+__global__ __launch_bounds__(256) void k_iota(int32_t *__restrict__ idx, int32_t *__restrict__ n_out, int32_t base,
+                                              int32_t count) {
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) idx[i] = base + i;
+    if (i == 0) *n_out = count;
+}
+
+// ---- waiting-queue bookkeeping (single block; the queue is a few thousand entries) ----
+constexpr int kQueueThreads = 1024;
+
+__global__ __launch_bounds__(kQueueThreads) void k_queue_advance(
+    int32_t *__restrict__ wait_id, uint64_t *__restrict__ wait_arr, int32_t *__restrict__ n_wait, int32_t cap,
+    const int32_t *__restrict__ match_len, const int32_t *__restrict__ len_all, int32_t n_all,
+    const int32_t *__restrict__ batch_idx, const int32_t *__restrict__ n_selected, int32_t batch_cap,
+    const int32_t *__restrict__ new_id, int32_t n_new, uint64_t *__restrict__ sim_clock, int64_t *__restrict__ ttft,
+    int32_t *__restrict__ flags, int32_t *__restrict__ id_tmp, uint64_t *__restrict__ arr_tmp,
+    uint32_t *__restrict__ dev_error) {
+    __shared__ unsigned long long s_cost;
+    __shared__ uint64_t s_clock;
+    __shared__ int32_t buf[kQueueThreads];
+    __shared__ int32_t carry;
+    const int tid = threadIdx.x;
+    int32_t nw = *n_wait;
+    if (nw < 0) nw = 0;
+    if (nw > cap) nw = cap;
+    int32_t nb = *n_selected;
+    if (nb < 0) nb = 0;
+    if (nb > batch_cap) nb = batch_cap;
+    if (tid == 0) { s_cost = 0; carry = 0; }
+    for (int32_t i = tid; i < nw; i += kQueueThreads) flags[i] = 0;
+    __syncthreads();
+    // mark the admitted entries and sum their uncached tokens (prefill cost with c_attn = 0)
+    unsigned long long my_cost = 0;
+    for (int32_t j = tid; j < nb; j += kQueueThreads) {
+        int32_t w = batch_idx[j];
+        if (w >= 0 && w < nw) {
+            flags[w] = 1;
+            int32_t id = wait_id[w];
+            int32_t len = (id >= 0 && id < n_all) ? len_all[id] : 0;
+            int32_t m = match_len[w];
+            if (m < 0) m = 0;
+            if (len > m) my_cost += (unsigned long long)(len - m);
+        }
+    }
+    if (my_cost) atomicAdd(&s_cost, my_cost);
+    __syncthreads();
+    if (tid == 0) s_clock = *sim_clock + (s_cost > 0 ? (uint64_t)s_cost : 1ull);
+    __syncthreads();
+    const uint64_t now = s_clock;
+    // the whole batch finishes together: TTFT = finish time - arrival
+    for (int32_t j = tid; j < nb; j += kQueueThreads) {
+        int32_t w = batch_idx[j];
+        if (w >= 0 && w < nw) {
+            int32_t id = wait_id[w];
+            if (id >= 0 && id < n_all) ttft[id] = (int64_t)(now - wait_arr[w]);
+        }
+    }
+    // stable removal of the admitted entries
+    for (int32_t base = 0; base < nw; base += kQueueThreads) {
+        int32_t i = base + tid;
+        int32_t keep = (i < nw && flags[i] == 0) ? 1 : 0;
+        buf[tid] = keep;
+        __syncthreads();
+        for (int d = 1; d < kQueueThreads; d <<= 1) {
+            int32_t v = (tid >= d) ? buf[tid - d] : 0;
+            __syncthreads();
+            buf[tid] += v;
+            __syncthreads();
+        }
+        if (keep) {
+            int32_t dst = carry + buf[tid] - 1;
+            id_tmp[dst] = wait_id[i];
+            arr_tmp[dst] = wait_arr[i];
+        }
+        __syncthreads();
+        if (tid == kQueueThreads - 1) carry += buf[tid];
+        __syncthreads();
+    }
+    const int32_t kept = carry;
+    for (int32_t i = tid; i < kept; i += kQueueThreads) {
+        wait_id[i] = id_tmp[i];
+        wait_arr[i] = arr_tmp[i];
+    }
+    int32_t room = cap - kept;
+    int32_t add = n_new < room ? n_new : room;
+    for (int32_t r = tid; r < add; r += kQueueThreads) {
+        wait_id[kept + r] = new_id[r];
+        wait_arr[kept + r] = now;
+    }
+    if (tid == 0) {
+        if (add < n_new && dev_error) atomicOr(dev_error, 8u);
+        *n_wait = kept + add;
+        *sim_clock = now;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_queue_gather(const int32_t *__restrict__ wait_id,
+                                                      const int32_t *__restrict__ n_wait, int32_t cap,
+                                                      const int64_t *__restrict__ off_all,
+                                                      const int32_t *__restrict__ len_all, int32_t n_all,
+                                                      int64_t *__restrict__ off_out, int32_t *__restrict__ len_out) {
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    int32_t nw = *n_wait;
+    if (nw > cap) nw = cap;
+    if (i >= nw) return;
+    int32_t id = wait_id[i];
+    bool ok = id >= 0 && id < n_all;
+    off_out[i] = ok ? off_all[id] : -1;  // an invalid id fails the bounds check of the match kernel
+    len_out[i] = ok ? len_all[id] : 0;
+}
+
+static QView make_qview(const kLPM_queries *q) {
+    QView v;
+    v.tokens = q->tokens;
+    v.off = q->off;
+    v.len = q->len;
+    v.n_tokens = q->n_tokens;
+    v.n = q->n;
+    return v;
+}
+
+static bool queries_ok(const kLPM_queries *q) {
+    if (!q || q->n < 0 || q->n_tokens < 0) return false;
+    if (q->n > 0 && (!q->tokens || !q->off || !q->len)) return false;
+    return true;
+}
+
+}  // namespace klpm
+
+using namespace klpm;
+
+extern "C" int kLPM_arena_bytes(const kLPM_config *cfg, size_t *out_bytes) {
+    if (!config_ok(cfg) || !out_bytes) return KLPM_EINVAL;
+    *out_bytes = make_layout(*cfg).total;
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *arena, size_t arena_bytes,
+                               const kLPM_queries *initial, kLPM_stream stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!out || !config_ok(cfg) || !arena) return KLPM_EINVAL;
+    if (initial && !queries_ok(initial)) return KLPM_EINVAL;
+    Layout L = make_layout(*cfg);
+    if (arena_bytes < L.total || ((uintptr_t)arena & 255u)) return KLPM_EARENA;
+    kLPM_tree *t = new (std::nothrow) kLPM_tree();
+    if (!t) return KLPM_ENOMEM;
+    char *base = (char *)arena;
+    t->cfg = *cfg;
+    t->arena = arena;
+    t->arena_bytes = arena_bytes;
+    t->budget = cfg->budget_tokens;
+    t->clock_ub = 0;
+    t->depth_bits = 1;
+    while ((cfg->max_prompt_len >> t->depth_bits) != 0) ++t->depth_bits;
+    TreeView &tv = t->tv;
+    tv.st = (DevState *)(base + L.state);
+    tv.parent = (int32_t *)(base + L.parent);
+    tv.edge_off = (int64_t *)(base + L.edge_off);
+    tv.edge_len = (int32_t *)(base + L.edge_len);
+    tv.depth_end = (int32_t *)(base + L.depth_end);
+    tv.tick = (uint64_t *)(base + L.tick);
+    tv.free_stack = (int32_t *)(base + L.free_stack);
+    tv.slots = (Slot *)(base + L.slots);
+    tv.slot_mask = L.n_slots_table - 1;
+    tv.max_nodes = cfg->max_nodes;
+    tv.pool = (int32_t *)(base + L.pool);
+    tv.pool_half = cfg->pool_tokens;
+    tv.max_prompt_len = cfg->max_prompt_len;
+    tv.max_batch = cfg->max_batch;
+    CommitWs &ws = t->ws;
+    ws.bm_len = (int32_t *)(base + L.bm_len);
+    ws.bm_node = (int32_t *)(base + L.bm_node);
+    ws.tail_off = (int64_t *)(base + L.tail_off);
+    ws.gkey = (uint64_t *)(base + L.gkey);
+    ws.end_node = (int32_t *)(base + L.end_node);
+    ws.evict_hist = (int64_t *)(base + L.evict_hist);
+    ws.iota_idx = (int32_t *)(base + L.iota_idx);
+    ws.iota_n = (int32_t *)(base + L.iota_n);
+
+    hipLaunchKernelGGL(k_tree_init, dim3(2048), dim3(256), 0, stream, tv);
+    int rc = check_launch();
+    if (rc == KLPM_OK && initial && initial->n > 0) {
+        QView q = make_qview(initial);
+        for (int32_t base_i = 0; base_i < initial->n && rc == KLPM_OK; base_i += cfg->max_batch) {
+            int32_t cnt = std::min(cfg->max_batch, initial->n - base_i);
+            hipLaunchKernelGGL(k_iota, dim3((cnt + 255) / 256), dim3(256), 0, stream, ws.iota_idx, ws.iota_n, base_i,
+                               cnt);
+            rc = commit_pipeline(t, q, ws.iota_idx, ws.iota_n, cnt, INT64_MAX, nullptr, stream);
+        }
+    }
+    if (rc != KLPM_OK) {
+        delete t;
+        return rc;
+    }
+    *out = t;
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_match(kLPM_tree *tree, const kLPM_queries *q, int32_t *match_len, int32_t *last_node,
+                          kLPM_stream stream_) {
+    if (!tree || !queries_ok(q)) return KLPM_EINVAL;
+    if (q->n == 0) return KLPM_OK;
+    if (!match_len) return KLPM_EINVAL;
+    return launch_match(tree->tv, make_qview(q), nullptr, nullptr, q->n, 0, match_len, last_node,
+                        (hipStream_t)stream_);
+}
+
+extern "C" int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_idx,
+                           const int32_t *n_selected, int32_t batch_cap, kLPM_stats *stats, kLPM_stream stream_) {
+    if (!tree || !queries_ok(q) || batch_cap < 0) return KLPM_EINVAL;
+    if (batch_cap > 0 && (!batch_idx || !n_selected)) return KLPM_EINVAL;
+    if (batch_cap > tree->cfg.max_batch) return KLPM_EINVAL;
+    return commit_pipeline(tree, make_qview(q), batch_idx, n_selected, batch_cap, tree->budget, stats,
+                           (hipStream_t)stream_);
+}
+
+extern "C" int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens) {
+    if (!tree || budget_tokens < 0) return KLPM_EINVAL;
+    tree->budget = budget_tokens;
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_queue_advance(int32_t *wait_id, uint64_t *wait_arr, int32_t *n_wait, int32_t cap,
+                                  const int32_t *match_len, const int32_t *len_all, int32_t n_all,
+                                  const int32_t *batch_idx, const int32_t *n_selected, int32_t batch_cap,
+                                  const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
+                                  void *scratch, size_t scratch_bytes, uint32_t *dev_error, kLPM_stream stream_) {
+    if (!wait_id || !wait_arr || !n_wait || cap < 0 || n_all < 0 || batch_cap < 0 || n_new < 0 || !sim_clock ||
+        !ttft || !scratch || !n_selected)
+        return KLPM_EINVAL;
+    if ((batch_cap > 0 && (!batch_idx || !match_len || !len_all)) || (n_new > 0 && !new_id)) return KLPM_EINVAL;
+    size_t c = (size_t)(cap > 0 ? cap : 1);
+    size_t o_flags = 0, o_id = align_up(c * 4, 256), o_arr = o_id + align_up(c * 4, 256);
+    size_t need = o_arr + align_up(c * 8, 256);
+    if (scratch_bytes < need || ((uintptr_t)scratch & 255u)) return KLPM_EARENA;
+    char *s = (char *)scratch;
+    hipLaunchKernelGGL(k_queue_advance, dim3(1), dim3(kQueueThreads), 0, (hipStream_t)stream_, wait_id, wait_arr,
+                       n_wait, cap, match_len, len_all, n_all, batch_idx, n_selected, batch_cap, new_id, n_new,
+                       sim_clock, ttft, (int32_t *)(s + o_flags), (int32_t *)(s + o_id), (uint64_t *)(s + o_arr),
+                       dev_error);
+    return check_launch();
+}
+
+extern "C" int kLPM_queue_gather(const int32_t *wait_id, const int32_t *n_wait, int32_t cap, const int64_t *off_all,
+                                 const int32_t *len_all, int32_t n_all, int64_t *off_out, int32_t *len_out,
+                                 kLPM_stream stream_) {
+    if (!wait_id || !n_wait || cap < 0 || !off_all || !len_all || n_all < 0 || !off_out || !len_out)
+        return KLPM_EINVAL;
+    if (cap == 0) return KLPM_OK;
+    hipLaunchKernelGGL(k_queue_gather, dim3((cap + 255) / 256), dim3(256), 0, (hipStream_t)stream_, wait_id, n_wait,
+                       cap, off_all, len_all, n_all, off_out, len_out);
+    return check_launch();
+}
+
+extern "C" int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_stream stream_) {
+    if (!tree || !host_out) return KLPM_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream_) != hipSuccess) return KLPM_EHIP;
+    DevState st;
+    if (hipMemcpy(&st, tree->tv.st, sizeof(st), hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    std::memset(host_out, 0, sizeof(*host_out));
+    host_out->total_tokens = st.total_tokens;
+    host_out->n_nodes = st.n_nodes;
+    host_out->device_error = st.device_error;
+    host_out->clock = st.clock;
+    return KLPM_OK;
+}
+
+// ---- canonical snapshot (host side; plumbing, not part of the scheduling step) ----
+namespace {
+struct SnapRec {
+    int32_t depth_start, edge_len;
+    uint64_t tick;
+    int32_t n_children, pad;
+};
+
+struct HostTree {
+    DevState st;
+    std::vector<int32_t> parent, edge_len, depth_end;
+    std::vector<int64_t> edge_off;
+    std::vector<uint64_t> tick;
+};
+
+int download(kLPM_tree *t, HostTree &h, hipStream_t stream) {
+    if (hipStreamSynchronize(stream) != hipSuccess) return KLPM_EHIP;
+    if (hipMemcpy(&h.st, t->tv.st, sizeof(DevState), hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    size_t n = (size_t)h.st.n_slots;
+    if (n > (size_t)t->cfg.max_nodes) return KLPM_EHIP;
+    h.parent.resize(n); h.edge_len.resize(n); h.depth_end.resize(n); h.edge_off.resize(n); h.tick.resize(n);
+    if (hipMemcpy(h.parent.data(), t->tv.parent, n * 4, hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    if (hipMemcpy(h.edge_len.data(), t->tv.edge_len, n * 4, hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    if (hipMemcpy(h.depth_end.data(), t->tv.depth_end, n * 4, hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    if (hipMemcpy(h.edge_off.data(), t->tv.edge_off, n * 8, hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    if (hipMemcpy(h.tick.data(), t->tv.tick, n * 8, hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    return KLPM_OK;
+}
+}  // namespace
+
+extern "C" int kLPM_snapshot_bytes(kLPM_tree *tree, size_t *out_bytes, kLPM_stream stream_) {
+    if (!tree || !out_bytes) return KLPM_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream_) != hipSuccess) return KLPM_EHIP;
+    DevState st;
+    if (hipMemcpy(&st, tree->tv.st, sizeof(st), hipMemcpyDeviceToHost) != hipSuccess) return KLPM_EHIP;
+    *out_bytes = 24 + (size_t)st.n_nodes * sizeof(SnapRec) + (size_t)st.total_tokens * 4;
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_snapshot(kLPM_tree *tree, void *host_buf, size_t cap, size_t *out_bytes, kLPM_stream stream_) {
+    if (!tree || !host_buf || !out_bytes) return KLPM_EINVAL;
+    HostTree h;
+    int rc = download(tree, h, (hipStream_t)stream_);
+    if (rc) return rc;
+    const size_t n_ids = h.parent.size();
+    // live nodes and the span of the pool they use
+    int64_t lo = INT64_MAX, hi = 0;
+    size_t n_live = 0;
+    int64_t tokens = 0;
+    for (size_t id = 1; id < n_ids; ++id) {
+        if (h.edge_len[id] <= 0) continue;
+        ++n_live;
+        tokens += h.edge_len[id];
+        lo = std::min(lo, h.edge_off[id]);
+        hi = std::max(hi, h.edge_off[id] + h.edge_len[id]);
+    }
+    size_t need = 24 + n_live * sizeof(SnapRec) + (size_t)tokens * 4;
+    *out_bytes = need;
+    if (cap < need) return KLPM_EARENA;
+    std::vector<int32_t> pool;
+    if (n_live) {
+        if (lo < 0 || hi > 2 * tree->tv.pool_half) return KLPM_EHIP;
+        pool.resize((size_t)(hi - lo));
+        if (hipMemcpy(pool.data(), tree->tv.pool + lo, (size_t)(hi - lo) * 4, hipMemcpyDeviceToHost) != hipSuccess)
+            return KLPM_EHIP;
+    }
+    // children lists (CSR by parent), each sorted by first edge token
+    std::vector<int32_t> deg(n_ids + 1, 0);
+    for (size_t id = 1; id < n_ids; ++id)
+        if (h.edge_len[id] > 0 && h.parent[id] >= 0 && (size_t)h.parent[id] < n_ids) deg[h.parent[id] + 1]++;
+    for (size_t i = 0; i < n_ids; ++i) deg[i + 1] += deg[i];
+    std::vector<int32_t> kids((size_t)deg[n_ids]);
+    {
+        std::vector<int32_t> fill(deg.begin(), deg.end() - 1);
+        for (size_t id = 1; id < n_ids; ++id)
+            if (h.edge_len[id] > 0 && h.parent[id] >= 0 && (size_t)h.parent[id] < n_ids)
+                kids[(size_t)fill[h.parent[id]]++] = (int32_t)id;
+    }
+    auto first_tok = [&](int32_t id) { return pool[(size_t)(h.edge_off[id] - lo)]; };
+    for (size_t p = 0; p < n_ids; ++p)
+        std::sort(kids.begin() + deg[p], kids.begin() + deg[p + 1],
+                  [&](int32_t a, int32_t b) { return first_tok(a) < first_tok(b); });
+    char *out = (char *)host_buf;
+    int64_t head[3] = {(int64_t)n_live, tokens, (int64_t)h.st.clock};
+    std::memcpy(out, head, 24);
+    SnapRec *rec = (SnapRec *)(out + 24);
+    int32_t *tok = (int32_t *)(out + 24 + n_live * sizeof(SnapRec));
+    // iterative pre-order
+    std::vector<int32_t> stack;
+    for (int32_t i = deg[1] - 1; i >= deg[0]; --i) stack.push_back(kids[(size_t)i]);
+    size_t written = 0;
+    while (!stack.empty()) {
+        int32_t id = stack.back();
+        stack.pop_back();
+        if (written >= n_live) return KLPM_EHIP;  // a cycle or a node reachable twice
+        SnapRec r;
+        r.depth_start = h.depth_end[id] - h.edge_len[id];
+        r.edge_len = h.edge_len[id];
+        r.tick = h.tick[id];
+        r.n_children = deg[(size_t)id + 1] - deg[(size_t)id];
+        r.pad = 0;
+        rec[written++] = r;
+        std::memcpy(tok, pool.data() + (h.edge_off[id] - lo), (size_t)h.edge_len[id] * 4);
+        tok += h.edge_len[id];
+        for (int32_t i = deg[(size_t)id + 1] - 1; i >= deg[(size_t)id]; --i) stack.push_back(kids[(size_t)i]);
+    }
+    if (written != n_live) return KLPM_EHIP;  // live nodes not reachable from the root
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_destroy(kLPM_tree *tree) {
+    delete tree;
+    return KLPM_OK;
+}
+
+extern "C" const char *kLPM_strerror(int code) {
+    switch (code) {
+        case KLPM_OK: return "ok";
+        case KLPM_EINVAL: return "invalid argument";
+        case KLPM_EARENA: return "arena or workspace too small or misaligned";
+        case KLPM_EHIP: return "HIP runtime error";
+        case KLPM_ENOMEM: return "host allocation failed";
+        default: return "unknown error";
+    }
+}
