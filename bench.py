@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the k-LPM scheduling step on one MI355X.
+
+A step is one pass of the whole path over the waiting queue: prefix-match every waiting query
+against the GPU-resident radix tree, pick the k-LPM batch, commit it (insert + LRU-evict to the KV
+budget), retire the batch from the queue and enqueue the next arrivals.  The workload is the large
+configuration (about 100M cached tokens, 65,536 waiting queries of up to 8,192 tokens, k = 8,
+batch 1,024); inputs are synthetic, seeded and already resident in HBM when timing starts.
+
+Prints one JSON line: prefix-match tokens/s over the timed steps, plus the roofline figures of the
+match kernel (algorithmic bytes / measured kernel time, against the 8 TB/s HBM peak) and the CPU
+oracle timed on the host cores over a bounded sample of the same steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(sum_match: int, n_queries: int) -> int:
+    """Bytes the match kernel has to move for one launch: for every compared position (the matched
+    tokens and the first mismatch) 4 B of query token and 4 B of edge token, plus per query its
+    offset (8 B), length (4 B) and the 4 B result.  Child-table slots are left out (lower bound)."""
+    return 8 * (sum_match + n_queries) + 16 * n_queries
+
+
+def build_workload(scale: float, steps_total: int):
+    import workloads as W
+
+    t0 = time.time()
+    base = W.config2(scale=scale, extra_queries=0)
+    batch = base.batch
+    w = W.config2(scale=scale, extra_queries=steps_total * batch)
+    log(f"generated {w.name} scale={scale}: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, "
+        f"queue {w.queries.n}, later arrivals {w.extra.n} in {time.time() - t0:.1f}s")
+    allq = W.Prompts(w.queries.tokens, np.concatenate([w.queries.off, w.extra.off]),
+                     np.concatenate([w.queries.len, w.extra.len]),
+                     np.concatenate([w.queries.arrival, w.extra.arrival]))
+    return w, allq
+
+
+def cpu_baseline(w, allq, steps: int, threads: int):
+    """The oracle run over the first `steps` steps of the same workload (match on `threads` host
+    threads, select and commit serial), timed without the tree build."""
+    import oracle
+
+    tree = oracle.OracleTree()
+    tree.build(w.cache)
+    n0, batch = w.queries.n, w.batch
+    waiting = np.arange(n0, dtype=np.int64)
+    enq = np.zeros(allq.n, dtype=np.uint64)
+    enq[:n0] = w.queries.arrival
+    clock, phase, matched = 0, 0, 0
+    first_sum = None
+    t_match = 0.0
+    t0 = time.perf_counter()
+    for s in range(steps):
+        off, ln, arr = allq.off[waiting], allq.len[waiting], enq[waiting]
+        ta = time.perf_counter()
+        m = tree.match(allq.tokens, off, ln, threads=threads)
+        t_match += time.perf_counter() - ta
+        idx, phase = oracle.select(arr, m, w.k, batch, phase)
+        tree.commit(allq.tokens, off, ln, idx, w.budget)
+        clock += max(1, int((ln[idx].astype(np.int64) - m[idx]).sum()))
+        keep = np.ones(waiting.shape[0], dtype=bool)
+        keep[idx] = False
+        new = np.arange(n0 + s * batch, n0 + (s + 1) * batch, dtype=np.int64)
+        enq[new] = clock
+        waiting = np.concatenate([waiting[keep], new])
+        matched += int(m.sum())
+        if first_sum is None:
+            first_sum = int(m.sum())
+    dt = time.perf_counter() - t0
+    return matched / dt, dt, t_match, first_sum
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
+    ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps timed for the CPU baseline (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU; --gpus must be 1 (there is no multi-GPU path to time)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2502_04677_amd as K
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    steps_total = args.steps + args.warmup
+    w, allq = build_workload(args.scale, steps_total)
+    batch, k, n0 = w.batch, w.k, w.queries.n
+    max_len = int(max(w.cache.len.max(), allq.len.max()))
+
+    t0 = time.time()
+    cache_d = K.DeviceQueries.from_host(w.cache, dev)
+    all_d = K.DeviceQueries.from_host(allq, dev)
+    cfg = K.size_config(int(w.cache.tokens.shape[0]), w.cache.n, w.budget, batch, max_len,
+                        extra_prompts=steps_total * batch)
+    sched = K.Scheduler(cfg, cache_d, n0, dev)
+    torch.cuda.synchronize()
+    st = K.kLPM_read_stats(sched.tree)
+    log(f"tree built on the GPU in {time.time() - t0:.1f}s: {st.total_tokens} tokens, {st.n_nodes} nodes, "
+        f"device_error={st.device_error}")
+    del cache_d
+    run = K.OnlineRun(sched, all_d, n0, np.arange(n0))
+    run.wait_arr[:n0] = all_d.arrival[:n0]
+    new_ids = [torch.arange(n0 + s * batch, n0 + (s + 1) * batch, dtype=torch.int32, device=dev)
+               for s in range(steps_total)]
+    sums = torch.zeros(steps_total, dtype=torch.int64, device=dev)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps_total)]
+
+    def one_step(s: int) -> None:
+        n = run.n_host
+        K.kLPM_queue_gather(run.wait_id, run.n_wait, n, all_d.off, all_d.len, all_d.n, run.off_w, run.len_w)
+        q = K.DeviceQueries(all_d.tokens, run.off_w, run.len_w, run.wait_arr, n)
+        ev[s][0].record()
+        sched.match(q)
+        ev[s][1].record()
+        sums[s] = sched.match_len[:n].sum(dtype=torch.int64)
+        sched.select(q, k, batch)
+        ev[s][2].record()
+        sched.commit(q, batch)
+        ev[s][3].record()
+        K.kLPM_queue_advance(run.wait_id, run.wait_arr, run.n_wait, run.cap, sched.match_len, all_d.len, all_d.n,
+                             sched.batch_idx, sched.n_selected, batch, new_ids[s], batch, run.sim_clock, run.ttft,
+                             run.scratch, run.scratch_bytes, run.dev_error)
+        ev[s][4].record()
+        run.n_host = min(run.cap, n - min(batch, n) + batch)
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(args.warmup, steps_total):
+        one_step(s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    st = sched.read_stats()
+    assert st.device_error == 0 and int(run.dev_error.item()) == 0, f"device error {st.device_error}"
+    sums_h = sums.cpu().numpy()
+    timed = range(args.warmup, steps_total)
+    match_ms = np.array([ev[s][0].elapsed_time(ev[s][1]) for s in timed])
+    select_ms = np.array([ev[s][1].elapsed_time(ev[s][2]) for s in timed])
+    commit_ms = np.array([ev[s][2].elapsed_time(ev[s][3]) for s in timed])
+    adv_ms = np.array([ev[s][3].elapsed_time(ev[s][4]) for s in timed])
+    sum_timed = int(sums_h[args.warmup:].sum())
+    value = sum_timed / elapsed
+    alg_bytes = float(np.mean([algorithmic_bytes(int(sums_h[s]), n0) for s in timed]))
+    match_s = float(match_ms.mean()) * 1e-3
+    achieved = alg_bytes / match_s / 1e9
+
+    out = {
+        "metric": "prefix-match tokens/sec (whole scheduling step: match + select + commit + queue update)",
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": w.name if args.scale == 1.0 else f"{w.name}-scale{args.scale}",
+                   "cache_tokens": int(st.total_tokens), "tree_nodes": int(st.n_nodes), "waiting_queries": n0,
+                   "batch": batch, "k": k, "kv_budget_tokens": int(w.budget), "max_prompt_len": max_len},
+        "schedule_latency_us": elapsed / args.steps * 1e6,
+        "phase_ms": {"match": float(match_ms.mean()), "select": float(select_ms.mean()),
+                     "commit": float(commit_ms.mean()), "queue_advance": float(adv_ms.mean())},
+        "match_tokens_per_s_kernel": float(np.mean(sums_h[args.warmup:])) / match_s,
+        "matched_tokens_per_step": float(np.mean(sums_h[args.warmup:])),
+        "roofline": {"kernel": "k_match", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": float(match_ms.mean())},
+    }
+
+    if args.cpu_steps > 0:
+        cores = len(os.sched_getaffinity(0))
+        threads = max(1, min(cores, 16))
+        cpu_steps = min(args.cpu_steps, steps_total)
+        v, dt, t_match, first_sum = cpu_baseline(w, allq, cpu_steps, threads)
+        assert first_sum == int(sums_h[0]), f"GPU and oracle disagree on step 0: {int(sums_h[0])} vs {first_sum}"
+        out["cpu_baseline"] = {"value": v, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                               "sample": f"first {cpu_steps} steps of the same workload (match on {threads} threads, "
+                                         f"select/commit serial), {dt:.1f}s; match alone {t_match:.2f}s"}
+        log(f"cpu baseline: {v:.3e} tokens/s on {threads} threads ({dt:.1f}s for {cpu_steps} steps)")
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
