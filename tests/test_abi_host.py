@@ -1,0 +1,95 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, and its
+host-side argument validation and sizing logic behave (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "klpm.h")
+
+
+@pytest.fixture(scope="module")
+def K():
+    import paper_2502_04677_amd as K
+
+    return K
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kLPM_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(K):
+    from paper_2502_04677_amd import binding
+
+    lib = C.CDLL(os.path.join(ROOT, "paper_2502_04677_amd", "libklpm.so"))
+    names = declared_functions()
+    assert {"kLPM_build_tree", "kLPM_match", "kLPM_select", "kLPM_commit"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:  # the binding carries the same names
+        assert hasattr(K, n) or n in ("kLPM_snapshot_bytes", "kLPM_strerror"), n
+
+
+def test_struct_layouts_match_header(K):
+    from paper_2502_04677_amd import binding
+
+    assert C.sizeof(binding.Queries) == 48
+    assert C.sizeof(binding.Config) == 32
+    assert C.sizeof(binding.Stats) == 48 and binding.STATS_BYTES == 48
+
+
+def test_arena_sizing_and_config_validation(K):
+    from paper_2502_04677_amd import binding
+
+    small = K.kLPM_arena_bytes(K.make_config(1000, 10_000, 100, 16, 64))
+    big = K.kLPM_arena_bytes(K.make_config(1000, 20_000, 100, 16, 64))
+    assert big - small >= 2 * 10_000 * 4 - 256  # two pool halves of int32 tokens (sub-ranges are 256-byte aligned)
+    assert small % 256 == 0
+    for bad in (K.make_config(-1, 10, 10, 1, 8), K.make_config(10, 0, 10, 1, 8), K.make_config(10, 10, 1, 1, 8),
+                K.make_config(10, 10, 10, 0, 8), K.make_config(10, 10, 10, 1, 0), K.make_config(10, 10, 10, 70000, 8)):
+        with pytest.raises(K.KlpmError):
+            K.kLPM_arena_bytes(bad)
+    lib = binding._lib
+    assert lib.kLPM_arena_bytes(None, None) == -1
+    assert lib.kLPM_strerror(0) == b"ok" and b"invalid" in lib.kLPM_strerror(-1)
+    assert b"arena" in lib.kLPM_strerror(-2) and b"unknown" in lib.kLPM_strerror(-77)
+
+
+def test_select_workspace_grows_with_n(K):
+    a, b = K.kLPM_select_workspace_bytes(0), K.kLPM_select_workspace_bytes(100_000)
+    assert 0 < a < b and b >= 100_000 * (8 + 8 + 4 * 5)
+    with pytest.raises(K.KlpmError):
+        K.kLPM_select_workspace_bytes(-1)
+
+
+def test_null_and_negative_arguments_are_rejected_before_any_launch(K):
+    from paper_2502_04677_amd import binding
+
+    lib = binding._lib
+    cfg = K.make_config(100, 1000, 16, 4, 32)
+    out = C.c_void_p(0)
+    assert lib.kLPM_build_tree(C.byref(out), C.byref(cfg), None, 0, None, None) == -1  # no arena
+    assert lib.kLPM_build_tree(None, C.byref(cfg), C.c_void_p(256), 1 << 30, None, None) == -1
+    # misaligned / too small arena
+    assert lib.kLPM_build_tree(C.byref(out), C.byref(cfg), C.c_void_p(264), 1 << 30, None, None) == -2
+    assert lib.kLPM_build_tree(C.byref(out), C.byref(cfg), C.c_void_p(256), 16, None, None) == -2
+    q = binding.Queries(0, 0, 0, 0, 0, -1)
+    assert lib.kLPM_match(None, C.byref(q), None, None, None) == -1
+    assert lib.kLPM_commit(None, C.byref(q), None, None, 0, None, None) == -1
+    assert lib.kLPM_set_budget(None, 5) == -1
+    assert lib.kLPM_read_stats(None, None, None) == -1
+    assert lib.kLPM_snapshot(None, None, 0, None, None) == -1
+    assert lib.kLPM_destroy(None) == 0
+
+
+def test_size_config_leaves_room_for_a_batch(K):
+    cfg = K.size_config(cache_tokens=1_000_000, cache_prompts=500, budget=600_000, max_batch=64, max_prompt_len=4096)
+    assert cfg.pool_tokens >= 600_000 + 64 * 4096 and cfg.max_nodes >= 2 * 500 + 2 * 64
+    assert cfg.budget_tokens == 600_000
