@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libklpm.so")
+# KLPM_LIBRARY may point at another build of the same library (same ABI)
+_LIB_PATH = os.environ.get("KLPM_LIBRARY") or os.path.join(_PKG, "libklpm.so")
 
 KLPM_OK = 0
 KLPM_K_INFINITY = 0xFFFFFFFF

@@ -118,44 +118,78 @@ __device__ __forceinline__ int64_t uni64(int64_t v) {
 }
 
 // Read-only probe (tree not being modified by this kernel). Returns the slot index or -1 and, when
-// found, the child's id and edge span. All arguments are wave-uniform.
+// found, the child's id and edge span. All arguments are wave-uniform; so are the results.
 __device__ __forceinline__ int32_t slot_find(const Slot *__restrict__ slots, uint32_t mask, uint64_t key,
                                              int32_t &child, int32_t &edge_len, int64_t &edge_off) {
     uint32_t h = hash_key(key) & mask;
     for (uint32_t probe = 0; probe <= mask; ++probe) {
-        const Slot s = slots[h];
-        if (s.key == key) {
-            child = s.child;
-            edge_len = s.edge_len;
-            edge_off = s.edge_off;
+        const uint4 *p = reinterpret_cast<const uint4 *>(slots + h);
+        uint4 lo = p[0];
+        uint4 hi = p[1];
+        uint32_t k0 = (uint32_t)uni((int32_t)lo.x), k1 = (uint32_t)uni((int32_t)lo.y);
+        uint32_t c = (uint32_t)uni((int32_t)lo.z), l = (uint32_t)uni((int32_t)lo.w);
+        uint32_t o0 = (uint32_t)uni((int32_t)hi.x), o1 = (uint32_t)uni((int32_t)hi.y);
+        // Both halves of the slot are made live here so that they are fetched in one round trip
+        // (otherwise the payload read is deferred until after the key compare).
+        asm volatile("" : "+s"(k0), "+s"(k1), "+s"(c), "+s"(l), "+s"(o0), "+s"(o1));
+        uint64_t k = ((uint64_t)k1 << 32) | (uint64_t)k0;
+        if (k == key) {
+            child = (int32_t)c;
+            edge_len = (int32_t)l;
+            edge_off = (int64_t)(((uint64_t)o1 << 32) | (uint64_t)o0);
             return (int32_t)h;
         }
-        if (s.key == kEmptyKey) return -1;
+        if (k == kEmptyKey) return -1;
         h = (h + 1) & mask;
     }
     return -1;
 }
 
-// Number of leading positions (< lim) where a[] and b[] agree; the whole wavefront cooperates.
-// Each lane reads single dwords so neither span needs any alignment; four 64-token rows are
-// issued before the first compare to keep 2 KB per wave in flight.
+// First position in [base, base + ROWS*64) at which a[] and b[] differ, or -1. Each lane reads
+// single dwords, so neither span needs any alignment. Lanes past `lim` re-read the last valid
+// element (no branch around the loads), and no result is looked at before every load of the window
+// has been issued: the whole window costs one memory round trip.
+template <int ROWS>
+__device__ __forceinline__ int32_t window_mismatch(const int32_t *__restrict__ a, const int32_t *__restrict__ b,
+                                                   int32_t base, int32_t lim, int lane) {
+    int32_t av[ROWS], bv[ROWS];
+    const int32_t last = lim - 1;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        int32_t i = base + r * kWave + lane;
+        int32_t ic = i < last ? i : last;
+        av[r] = a[ic];
+        bv[r] = b[ic];
+    }
+    int32_t res = -1;
+#pragma unroll
+    for (int r = ROWS - 1; r >= 0; --r) {
+        uint64_t m = __ballot(av[r] != bv[r]);
+        if (m) res = base + r * kWave + (int32_t)__builtin_ctzll(m);
+    }
+    // A clamped lane can only report a difference that the lane owning the last element reports
+    // too, from a lower position, so res < lim whenever res >= 0.
+    return res;
+}
+
+// Number of leading positions (< lim, lim >= 1) where a[] and b[] agree; the whole wavefront
+// cooperates. Windows grow from 128 tokens (a mismatch right after a node boundary is the common
+// case) to 1024 tokens (16 rows of query and edge tokens = 8 KB per wave in flight) on long edges.
 __device__ __forceinline__ int32_t wave_common_prefix(const int32_t *__restrict__ a, const int32_t *__restrict__ b,
                                                       int32_t lim, int lane) {
-    for (int32_t base = 0; base < lim; base += 4 * kWave) {
-        int32_t i0 = base + lane, i1 = i0 + kWave, i2 = i1 + kWave, i3 = i2 + kWave;
-        int32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0, b0 = 0, b1 = 0, b2 = 0, b3 = 0;
-        if (i0 < lim) { a0 = a[i0]; b0 = b[i0]; }
-        if (i1 < lim) { a1 = a[i1]; b1 = b[i1]; }
-        if (i2 < lim) { a2 = a[i2]; b2 = b[i2]; }
-        if (i3 < lim) { a3 = a[i3]; b3 = b[i3]; }
-        uint64_t m0 = __ballot(i0 < lim && a0 != b0);
-        if (m0) return base + (int32_t)__builtin_ctzll(m0);
-        uint64_t m1 = __ballot(i1 < lim && a1 != b1);
-        if (m1) return base + kWave + (int32_t)__builtin_ctzll(m1);
-        uint64_t m2 = __ballot(i2 < lim && a2 != b2);
-        if (m2) return base + 2 * kWave + (int32_t)__builtin_ctzll(m2);
-        uint64_t m3 = __ballot(i3 < lim && a3 != b3);
-        if (m3) return base + 3 * kWave + (int32_t)__builtin_ctzll(m3);
+    int32_t r = window_mismatch<2>(a, b, 0, lim, lane);
+    if (r >= 0) return r;
+    int32_t base = 2 * kWave;
+    while (base < lim) {
+        if (lim - base > 4 * kWave) {
+            r = window_mismatch<16>(a, b, base, lim, lane);
+            if (r >= 0) return r;
+            base += 16 * kWave;
+        } else {
+            r = window_mismatch<4>(a, b, base, lim, lane);
+            if (r >= 0) return r;
+            base += 4 * kWave;
+        }
     }
     return lim;
 }

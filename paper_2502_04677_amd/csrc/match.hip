@@ -9,19 +9,23 @@
 
 namespace klpm {
 
-__global__ __launch_bounds__(256) void k_match(TreeView tv, QView q, const int32_t *__restrict__ sel,
-                                               const int32_t *__restrict__ n_dev, int32_t n_cap, int honor_skip,
-                                               int32_t *__restrict__ out_len, int32_t *__restrict__ out_node) {
+// ADMITTED = false: the queue-wide match (wave w handles query w).
+// ADMITTED = true : the match of the admitted prompts inside commit (wave w handles query sel[w],
+//                   the count comes from device memory, an abandoned commit does nothing).
+template <bool ADMITTED>
+__device__ __forceinline__ void match_body(const TreeView &tv, const QView &q, const int32_t *__restrict__ sel,
+                                           const int32_t *__restrict__ n_dev, int32_t n_cap,
+                                           int32_t *__restrict__ out_len, int32_t *__restrict__ out_node) {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t w = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
     int32_t n = n_cap;
-    if (n_dev) {
+    if (ADMITTED) {
+        if (tv.st->skip) return;
         int32_t nd = *n_dev;
         n = nd < n_cap ? nd : n_cap;
     }
-    if (honor_skip && tv.st->skip) return;
     if (w >= n) return;
-    int32_t qi = sel ? uni(sel[w]) : (int32_t)w;
+    int32_t qi = ADMITTED ? uni(sel[w]) : (int32_t)w;
     bool bad = (qi < 0 || qi >= q.n);
     int64_t off = 0;
     int32_t L = 0;
@@ -46,9 +50,6 @@ __global__ __launch_bounds__(256) void k_match(TreeView tv, QView q, const int32
         int32_t c, el;
         int64_t eo;
         if (slot_find(tv.slots, tv.slot_mask, make_key(cur, tok), c, el, eo) < 0) break;
-        c = uni(c);
-        el = uni(el);
-        eo = uni64(eo);
         int32_t lim = el < L - d ? el : L - d;
         int32_t j = wave_common_prefix(x + d, pool + eo, lim, lane);
         d += j;
@@ -62,13 +63,30 @@ __global__ __launch_bounds__(256) void k_match(TreeView tv, QView q, const int32
     }
 }
 
+__global__ __launch_bounds__(256) void k_match(TreeView tv, QView q, int32_t n, int32_t *__restrict__ out_len,
+                                               int32_t *__restrict__ out_node) {
+    match_body<false>(tv, q, nullptr, nullptr, n, out_len, out_node);
+}
+
+__global__ __launch_bounds__(256) void k_match_admitted(TreeView tv, QView q, const int32_t *__restrict__ sel,
+                                                        const int32_t *__restrict__ n_dev, int32_t n_cap,
+                                                        int32_t *__restrict__ out_len,
+                                                        int32_t *__restrict__ out_node) {
+    match_body<true>(tv, q, sel, n_dev, n_cap, out_len, out_node);
+}
+
 int launch_match(const TreeView &tv, const QView &q, const int32_t *sel, const int32_t *n_dev, int32_t n_cap,
                  int honor_skip, int32_t *out_len, int32_t *out_node, hipStream_t stream) {
     if (n_cap <= 0) return 0;
     const int waves_per_block = 4;
     unsigned blocks = (unsigned)((n_cap + waves_per_block - 1) / waves_per_block);
-    hipLaunchKernelGGL(k_match, dim3(blocks), dim3(waves_per_block * kWave), 0, stream, tv, q, sel, n_dev, n_cap,
-                       honor_skip, out_len, out_node);
+    if (sel && n_dev && honor_skip) {
+        hipLaunchKernelGGL(k_match_admitted, dim3(blocks), dim3(waves_per_block * kWave), 0, stream, tv, q, sel, n_dev,
+                           n_cap, out_len, out_node);
+    } else {
+        hipLaunchKernelGGL(k_match, dim3(blocks), dim3(waves_per_block * kWave), 0, stream, tv, q, n_cap, out_len,
+                           out_node);
+    }
     return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
