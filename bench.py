@@ -124,30 +124,23 @@ def main() -> int:
     log(f"tree built on the GPU in {time.time() - t0:.1f}s: {st.total_tokens} tokens, {st.n_nodes} nodes, "
         f"device_error={st.device_error}")
     del cache_d
-    run = K.OnlineRun(sched, all_d, n0, np.arange(n0))
-    run.wait_arr[:n0] = all_d.arrival[:n0]
+    run = K.OnlineRun(sched, all_d, n0, np.arange(n0), first_arrival=w.queries.arrival)
     new_ids = [torch.arange(n0 + s * batch, n0 + (s + 1) * batch, dtype=torch.int32, device=dev)
                for s in range(steps_total)]
     sums = torch.zeros(steps_total, dtype=torch.int64, device=dev)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps_total)]
 
     def one_step(s: int) -> None:
-        n = run.n_host
-        K.kLPM_queue_gather(run.wait_id, run.n_wait, n, all_d.off, all_d.len, all_d.n, run.off_w, run.len_w)
-        q = K.DeviceQueries(all_d.tokens, run.off_w, run.len_w, run.wait_arr, n)
+        q = run.view()
         ev[s][0].record()
         sched.match(q)
         ev[s][1].record()
-        sums[s] = sched.match_len[:n].sum(dtype=torch.int64)
-        sched.select(q, k, batch)
+        sched.select(q, k, batch, fifo=True)  # the queue is kept in arrival order
         ev[s][2].record()
         sched.commit(q, batch)
         ev[s][3].record()
-        K.kLPM_queue_advance(run.wait_id, run.wait_arr, run.n_wait, run.cap, sched.match_len, all_d.len, all_d.n,
-                             sched.batch_idx, sched.n_selected, batch, new_ids[s], batch, run.sim_clock, run.ttft,
-                             run.scratch, run.scratch_bytes, run.dev_error)
+        run.advance(batch, new_ids[s], matched=sums[s:s + 1])
         ev[s][4].record()
-        run.n_host = min(run.cap, n - min(batch, n) + batch)
 
     for s in range(args.warmup):
         one_step(s)

@@ -101,6 +101,11 @@ int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *arena, size_t
 int kLPM_match(kLPM_tree *tree, const kLPM_queries *q, int32_t *match_len, int32_t *last_node,
                kLPM_stream stream);
 
+/* kLPM_select flag: the caller asserts that arrival[] is non-decreasing in the queue index (a queue
+ * kept in arrival order).  Selection then runs as a single kernel.  The assertion is checked on the
+ * device; if it does not hold, *n_selected is set to -1, nothing is selected and the phase is kept. */
+#define KLPM_SELECT_FIFO 1u
+
 /* Workspace size for kLPM_select over n waiting queries. */
 int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
 
@@ -109,7 +114,8 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * Slot j of the batch is the oldest remaining query if (phase + j) mod k == 0, otherwise the
  * remaining query with the longest match; ties go to the earlier arrival, then the lower index.
  * k = 1 is FCFS; k = 0 or KLPM_K_INFINITY is pure LPM order (Sec. 4).
- *   arrival, match_len  DEVICE [n] in
+ *   arrival, match_len  DEVICE [n] in (a negative match_len counts as 0)
+ *   flags               0 or KLPM_SELECT_FIFO
  *   phase_inout         DEVICE [1]: position in the k-cycle, carried from step to step
  *                       (write 0 before the call to restart the cycle every step)
  *   batch_idx           DEVICE [min(batch, n)] out: queue indices in pick order
@@ -118,7 +124,7 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
  */
 int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace,
+                uint32_t flags, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace,
                 size_t workspace_bytes, kLPM_stream stream);
 
 /*
@@ -138,36 +144,46 @@ int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_idx
 int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens);
 
 /*
- * Waiting-queue bookkeeping of an online run (query stream of Def. 1 served in bins, Sec. 2.1;
- * prefill cost of Def. 2 with c_attn = 0): given the batch just selected from a queue of n_wait
- * entries, advance the simulated time by max(1, sum over the batch of len - match_len), record
- * TTFT = new time - arrival for the admitted entries, remove them from the queue (order kept) and
- * append n_new arrivals stamped with the new time.
- *   wait_id     DEVICE [cap] in/out: global query ids of the waiting queue
- *   wait_arr    DEVICE [cap] in/out: their arrival (enqueue) times
- *   n_wait      DEVICE [1] in/out
- *   match_len   DEVICE [n_wait] match lengths of the queue (as scored this step)
- *   len_all     DEVICE [n_all] prompt length by global id
- *   batch_idx / n_selected: as written by kLPM_select (indices into the queue)
- *   new_id      DEVICE [n_new] global ids of the arrivals joining after this step
- *   sim_clock   DEVICE [1] in/out simulated time
- *   ttft        DEVICE [n_all] out (written for admitted ids only)
- *   scratch     DEVICE, 256-byte aligned, >= 16 * max(cap,1) + 768 bytes
- * Entries beyond `cap` set KLPM_DEV_BATCH_OVERFLOW in *dev_error (DEVICE [1]) and are dropped.
+ * A device-resident waiting queue kept in arrival order, with the CSR view (off, len) of its
+ * prompts inside the token pool of the whole stream.  All pointers DEVICE.
  */
-int kLPM_queue_advance(int32_t *wait_id, uint64_t *wait_arr, int32_t *n_wait, int32_t cap,
-                       const int32_t *match_len, const int32_t *len_all, int32_t n_all,
-                       const int32_t *batch_idx, const int32_t *n_selected, int32_t batch_cap,
-                       const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
-                       void *scratch, size_t scratch_bytes, uint32_t *dev_error, kLPM_stream stream);
+typedef struct {
+    int32_t *id;       /* [cap] global query ids */
+    uint64_t *arrival; /* [cap] enqueue times */
+    int64_t *off;      /* [cap] start of each waiting prompt in the stream's token pool */
+    int32_t *len;      /* [cap] prompt lengths */
+    int32_t *n;        /* [1]  entries in use */
+    int32_t cap;
+} kLPM_queue;
+
+/* Fill q->off / q->len from q->id (off = -1, len = 0 for an id outside `all`). */
+int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream stream);
+
+/* Scratch size for kLPM_queue_advance with batches of up to batch_cap (<= 4096) entries. */
+int kLPM_queue_scratch_bytes(int32_t batch_cap, size_t *out_bytes);
 
 /*
- * Gather the CSR view of the waiting queue: off_out[i] = off_all[wait_id[i]], len_out[i] =
- * len_all[wait_id[i]] for i < *n_wait (all DEVICE).  Lets match/select/commit run on the queue.
+ * Waiting-queue bookkeeping of an online run (query stream of Def. 1 served in bins, Sec. 2.1;
+ * prefill cost of Def. 2 with c_attn = 0).  Given the batch just selected from `cur`: advance the
+ * simulated time by max(1, sum over the batch of len - match_len), record TTFT = new time -
+ * arrival for the admitted entries, and write into `next` (a distinct buffer set) the surviving
+ * entries in their old order followed by the n_new arrivals stamped with the new time, together
+ * with the CSR view of the new queue.
+ *   all         the whole stream's prompts (tokens unused; off/len indexed by global id)
+ *   match_len   DEVICE [*cur->n] match lengths of the queue as scored this step
+ *   batch_idx / n_selected  as written by kLPM_select (positions in `cur`), batch_cap <= 4096
+ *   new_id      DEVICE [n_new] global ids of the arrivals joining after this step
+ *   sim_clock   DEVICE [1] in/out simulated time
+ *   ttft        DEVICE [all->n] out (written for admitted ids only)
+ *   matched_accum DEVICE [1] or NULL: += sum of match_len over the queue (throughput accounting)
+ *   scratch     DEVICE, 256-byte aligned, >= kLPM_queue_scratch_bytes(batch_cap)
+ * Arrivals that do not fit next->cap are dropped and set KLPM_DEV_BATCH_OVERFLOW in *dev_error.
  */
-int kLPM_queue_gather(const int32_t *wait_id, const int32_t *n_wait, int32_t cap, const int64_t *off_all,
-                      const int32_t *len_all, int32_t n_all, int64_t *off_out, int32_t *len_out,
-                      kLPM_stream stream);
+int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
+                       const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
+                       int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
+                       int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
+                       kLPM_stream stream);
 
 /* Synchronises the stream and copies the tree's counters to HOST memory. */
 int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_stream stream);

@@ -19,11 +19,13 @@ _LIB_PATH = os.environ.get("KLPM_LIBRARY") or os.path.join(_PKG, "libklpm.so")
 
 KLPM_OK = 0
 KLPM_K_INFINITY = 0xFFFFFFFF
+KLPM_SELECT_FIFO = 1
 DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
-    "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_gather", "kLPM_read_stats",
+    "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
+    "kLPM_read_stats",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
 
@@ -31,6 +33,11 @@ EXPORTS = (
 class Queries(C.Structure):
     _fields_ = [("tokens", C.c_void_p), ("off", C.c_void_p), ("len", C.c_void_p), ("arrival", C.c_void_p),
                 ("n_tokens", C.c_int64), ("n", C.c_int32)]
+
+
+class Queue(C.Structure):
+    _fields_ = [("id", C.c_void_p), ("arrival", C.c_void_p), ("off", C.c_void_p), ("len", C.c_void_p),
+                ("n", C.c_void_p), ("cap", C.c_int32)]
 
 
 class Config(C.Structure):
@@ -57,11 +64,13 @@ def load_library() -> C.CDLL:
     lib.kLPM_build_tree.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, sz, C.POINTER(Queries), vp]
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select.argtypes = [vp, vp, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select.argtypes = [vp, vp, i32, u32, i32, u32, vp, vp, vp, vp, sz, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
     lib.kLPM_set_budget.argtypes = [vp, i64]
-    lib.kLPM_queue_advance.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, vp, vp, vp, sz, vp, vp]
-    lib.kLPM_queue_gather.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
+    lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
+                                       vp, vp, vp, vp, sz, vp, vp]
+    lib.kLPM_queue_gather.argtypes = [C.POINTER(Queue), C.POINTER(Queries), vp]
+    lib.kLPM_queue_scratch_bytes.argtypes = [i32, C.POINTER(sz)]
     lib.kLPM_read_stats.argtypes = [vp, C.POINTER(Stats), vp]
     lib.kLPM_snapshot_bytes.argtypes = [vp, C.POINTER(sz), vp]
     lib.kLPM_snapshot.argtypes = [vp, vp, sz, C.POINTER(sz), vp]
@@ -192,9 +201,9 @@ def alloc_aligned(nbytes: int, device) -> Tuple[torch.Tensor, int]:
 
 def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, batch: int,
                 phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
-                workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None) -> None:
+                workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None, flags: int = 0) -> None:
     _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), int(n), C.c_uint32(k & 0xFFFFFFFF), int(batch),
-                            _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
+                            C.c_uint32(flags), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
 
 
@@ -209,18 +218,48 @@ def kLPM_set_budget(tree: Tree, budget_tokens: int) -> None:
     _check(_lib.kLPM_set_budget(tree.handle, int(min(budget_tokens, 1 << 62))), "kLPM_set_budget")
 
 
-def kLPM_queue_advance(wait_id, wait_arr, n_wait, cap, match_len, len_all, n_all, batch_idx, n_selected, batch_cap,
-                       new_id, n_new, sim_clock, ttft, scratch: Tuple[torch.Tensor, int], scratch_bytes, dev_error,
-                       stream=None) -> None:
-    _check(_lib.kLPM_queue_advance(_ptr(wait_id), _ptr(wait_arr), _ptr(n_wait), int(cap), _ptr(match_len),
-                                   _ptr(len_all), int(n_all), _ptr(batch_idx), _ptr(n_selected), int(batch_cap),
-                                   _ptr(new_id), int(n_new), _ptr(sim_clock), _ptr(ttft), C.c_void_p(scratch[1]),
-                                   int(scratch_bytes), _ptr(dev_error), _stream(stream)), "kLPM_queue_advance")
+@dataclass
+class DeviceQueue:
+    """Device buffers of one waiting queue (ids, enqueue times, CSR view, count)."""
+
+    id: torch.Tensor  # int32 [cap]
+    arrival: torch.Tensor  # int64 [cap] (bits of uint64)
+    off: torch.Tensor  # int64 [cap]
+    len: torch.Tensor  # int32 [cap]
+    n: torch.Tensor  # int32 [1]
+    cap: int
+
+    @staticmethod
+    def empty(cap: int, device) -> "DeviceQueue":
+        c = max(int(cap), 1)
+        return DeviceQueue(torch.zeros(c, dtype=torch.int32, device=device), torch.zeros(c, dtype=torch.int64, device=device),
+                           torch.zeros(c, dtype=torch.int64, device=device), torch.zeros(c, dtype=torch.int32, device=device),
+                           torch.zeros(1, dtype=torch.int32, device=device), int(cap))
+
+    def c_struct(self) -> Queue:
+        return Queue(self.id.data_ptr(), self.arrival.data_ptr(), self.off.data_ptr(), self.len.data_ptr(),
+                     self.n.data_ptr(), self.cap)
 
 
-def kLPM_queue_gather(wait_id, n_wait, cap, off_all, len_all, n_all, off_out, len_out, stream=None) -> None:
-    _check(_lib.kLPM_queue_gather(_ptr(wait_id), _ptr(n_wait), int(cap), _ptr(off_all), _ptr(len_all), int(n_all),
-                                  _ptr(off_out), _ptr(len_out), _stream(stream)), "kLPM_queue_gather")
+def kLPM_queue_scratch_bytes(batch_cap: int) -> int:
+    out = C.c_size_t(0)
+    _check(_lib.kLPM_queue_scratch_bytes(int(batch_cap), C.byref(out)), "kLPM_queue_scratch_bytes")
+    return int(out.value)
+
+
+def kLPM_queue_advance(cur: DeviceQueue, nxt: DeviceQueue, all_q: DeviceQueries, match_len, batch_idx, n_selected,
+                       batch_cap: int, new_id, n_new: int, sim_clock, ttft, matched_accum,
+                       scratch: Tuple[torch.Tensor, int], scratch_bytes: int, dev_error, stream=None) -> None:
+    c, n, a = cur.c_struct(), nxt.c_struct(), all_q.c_struct()
+    _check(_lib.kLPM_queue_advance(C.byref(c), C.byref(n), C.byref(a), _ptr(match_len), _ptr(batch_idx),
+                                   _ptr(n_selected), int(batch_cap), _ptr(new_id), int(n_new), _ptr(sim_clock),
+                                   _ptr(ttft), _ptr(matched_accum), C.c_void_p(scratch[1]), int(scratch_bytes),
+                                   _ptr(dev_error), _stream(stream)), "kLPM_queue_advance")
+
+
+def kLPM_queue_gather(q: DeviceQueue, all_q: DeviceQueries, stream=None) -> None:
+    c, a = q.c_struct(), all_q.c_struct()
+    _check(_lib.kLPM_queue_gather(C.byref(c), C.byref(a), _stream(stream)), "kLPM_queue_gather")
 
 
 def kLPM_read_stats(tree: Tree, stream=None) -> Stats:

@@ -27,55 +27,64 @@ constexpr int kPlanThreads = 1024;
 
 __device__ __forceinline__ void flag_error(DevState *st, uint32_t bit) { atomicOr(&st->device_error, bit); }
 
-// ------------------------------------------------------------------ begin / plan
-__global__ void k_commit_begin(TreeView tv, const int32_t *__restrict__ n_selected, int32_t batch_cap) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    DevState *st = tv.st;
-    int32_t nb = n_selected ? *n_selected : 0;
-    st->skip = 0;
-    st->alloc_cnt = 0;
-    st->need_compact = 0;
-    st->need_rebuild = 0;
-    st->do_evict = 0;
-    st->tail_total = 0;
-    st->inserted_tokens = 0;
-    st->evicted_tokens = 0;
-    st->new_nodes = 0;
-    st->evicted_nodes = 0;
-    if (nb < 0) nb = 0;
-    if (nb > batch_cap || nb > tv.max_batch) {
-        st->device_error |= 8u;  // KLPM_DEV_BATCH_OVERFLOW
-        st->skip = 1;
-        nb = 0;
+// ------------------------------------------------------------------ plan
+// True for exactly one workgroup of the grid: the one that finishes last. `slot` picks one of the
+// per-commit counters (reset by the plan kernel). Every thread of every workgroup must call it.
+__device__ __forceinline__ bool last_block_done(DevState *st, int slot) {
+    __shared__ int s_last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        s_last = (atomicAdd(&st->done[slot], 1) == (int)gridDim.x - 1) ? 1 : 0;
     }
-    int64_t free_nodes = (int64_t)(tv.max_nodes - st->n_slots) + (int64_t)st->free_cnt;
-    if (2ll * nb > free_nodes) {
-        st->device_error |= 1u;  // KLPM_DEV_NODES_FULL
-        st->skip = 1;
-        nb = 0;
-    }
-    st->nb = nb;
-    st->free_cnt0 = st->free_cnt;
-    st->n_slots0 = st->n_slots;
-    st->clock0 = st->clock;
+    __syncthreads();
+    if (s_last) __threadfence();
+    return s_last != 0;
 }
 
-// tail lengths -> offsets inside the pool block of this commit; group keys; capacity decision
+// Resets the per-commit scalars, admits the batch (or abandons the commit), then: tail lengths ->
+// offsets inside the pool block of this commit; group keys; capacity decision.
 __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView q,
-                                                              const int32_t *__restrict__ batch_idx, CommitWs ws) {
+                                                              const int32_t *__restrict__ batch_idx,
+                                                              const int32_t *__restrict__ n_selected,
+                                                              int32_t batch_cap, CommitWs ws) {
     __shared__ int64_t buf[kPlanThreads];
     __shared__ int64_t carry;
     __shared__ int bad;
+    __shared__ int32_t s_nb;
     DevState *st = tv.st;
-    if (st->skip) return;
     const int tid = threadIdx.x;
-    const int32_t nb = st->nb;
-    if (tid == 0) { carry = 0; bad = 0; }
+    if (tid == 0) {
+        uint32_t err = 0;
+        int32_t nb = commit_gate(tv, n_selected, batch_cap, &err);
+        if (err) st->device_error |= err;
+        st->skip = err ? 1 : 0;
+        st->nb = nb;
+        st->alloc_cnt = 0;
+        st->need_compact = 0;
+        st->need_rebuild = 0;
+        st->do_evict = 0;
+        st->tail_total = 0;
+        st->inserted_tokens = 0;
+        st->evicted_tokens = 0;
+        st->new_nodes = 0;
+        st->evicted_nodes = 0;
+        st->free_cnt0 = st->free_cnt;
+        st->n_slots0 = st->n_slots;
+        st->clock0 = st->clock;
+        for (int i = 0; i < 12; ++i) st->done[i] = 0;
+        s_nb = nb;
+        carry = 0;
+        bad = 0;
+    }
     __syncthreads();
+    const int32_t nb = s_nb;
     for (int32_t base = 0; base < nb; base += kPlanThreads) {
         int32_t j = base + tid;
         int64_t tl = 0;
         if (j < nb) {
+            ws.used[j] = 0;
+            ws.leaf_tok[j] = 0;
             int32_t m = ws.bm_len[j];
             if (m < 0) {
                 atomicOr(&bad, 1);
@@ -113,25 +122,23 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
         if (tid == kPlanThreads - 1) carry += buf[tid];
         __syncthreads();
     }
-    if (tid == 0) {
+    if (tid == 0 && nb > 0) {
         st->tail_total = carry;
         if (bad) {
             st->skip = 1;
         } else {
             int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
-            if (st->pool_top + carry > half_end) st->need_compact = 1;
+            if (st->pool_top + carry > half_end) {
+                st->need_compact = 1;
+                st->compact_cursor = (int64_t)(1 - st->active_half) * tv.pool_half;
+            }
         }
     }
 }
 
 // ------------------------------------------------------------------ pool compaction (rare)
-__global__ void k_compact_begin(TreeView tv) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    DevState *st = tv.st;
-    if (!st->need_compact) return;
-    st->compact_cursor = (int64_t)(1 - st->active_half) * tv.pool_half;
-}
-
+// Moves every live edge span into the other half of the pool, patches the span kept in the child
+// table, and the last workgroup to finish switches halves.
 __global__ __launch_bounds__(256) void k_compact_copy(TreeView tv) {
     DevState *st = tv.st;
     if (!st->need_compact) return;
@@ -151,22 +158,24 @@ __global__ __launch_bounds__(256) void k_compact_copy(TreeView tv) {
             if (lane == 0) flag_error(st, 2u);
             continue;
         }
+        int32_t first = uni(tv.pool[src]);
         for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
-        if (lane == 0) tv.edge_off[id] = dst;
+        if (lane == 0) {
+            tv.edge_off[id] = dst;
+            int32_t c, el;
+            int64_t eo;
+            int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
+            if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, 4u);
+        }
     }
-}
-
-__global__ void k_compact_end(TreeView tv) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    DevState *st = tv.st;
-    if (!st->need_compact) return;
-    st->active_half = 1 - st->active_half;
-    st->pool_top = st->compact_cursor;
-    st->need_rebuild = 1;
-    int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
-    if (st->pool_top + st->tail_total > half_end) {
-        st->device_error |= 2u;  // KLPM_DEV_POOL_FULL
-        st->skip = 1;
+    if (last_block_done(st, 0) && threadIdx.x == 0) {
+        st->active_half = 1 - st->active_half;
+        st->pool_top = st->compact_cursor;
+        int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
+        if (st->pool_top + st->tail_total > half_end) {
+            st->device_error |= 2u;  // KLPM_DEV_POOL_FULL
+            st->skip = 1;
+        }
     }
 }
 
@@ -178,33 +187,46 @@ __global__ __launch_bounds__(256) void k_hash_clear(TreeView tv) {
         tv.slots[i].key = kEmptyKey;
 }
 
-__global__ __launch_bounds__(256) void k_hash_fill(TreeView tv) {
-    DevState *st = tv.st;
-    if (!st->need_rebuild) return;
-    const int32_t n_slots = st->n_slots;
-    for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < n_slots;
-         id += (int64_t)gridDim.x * blockDim.x) {
-        int32_t len = tv.edge_len[id];
-        if (len <= 0) continue;
-        int64_t off = tv.edge_off[id];
-        uint64_t key = make_key(tv.parent[id], tv.pool[off]);
-        uint32_t h = hash_key(key) & tv.slot_mask;
-        for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
-            unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key, (unsigned long long)kEmptyKey,
-                                                (unsigned long long)key);
-            if (prev == (unsigned long long)kEmptyKey) {
-                tv.slots[h].child = (int32_t)id;
-                tv.slots[h].edge_len = len;
-                tv.slots[h].edge_off = off;
-                break;
-            }
-            h = (h + 1) & tv.slot_mask;
-        }
-    }
+__device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict__ out) {
+    st->need_rebuild = 0;
+    if (!out) return;
+    out->total_tokens = st->total_tokens;
+    out->inserted_tokens = st->skip ? 0 : st->inserted_tokens;
+    out->evicted_tokens = st->evicted_tokens;
+    out->n_nodes = st->n_nodes;
+    out->new_nodes = st->skip ? 0 : st->new_nodes;
+    out->evicted_nodes = st->evicted_nodes;
+    out->device_error = st->device_error;
+    out->clock = st->clock;
 }
 
-__global__ void k_rebuild_done(TreeView tv) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) tv.st->need_rebuild = 0;
+// Re-inserts every live node into the (cleared) child table; the last workgroup to finish writes
+// the commit's counters for the caller.
+__global__ __launch_bounds__(256) void k_hash_fill(TreeView tv, kLPM_stats *__restrict__ stats_out) {
+    DevState *st = tv.st;
+    if (st->need_rebuild) {
+        const int32_t n_slots = st->n_slots;
+        for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < n_slots;
+             id += (int64_t)gridDim.x * blockDim.x) {
+            int32_t len = tv.edge_len[id];
+            if (len <= 0) continue;
+            int64_t off = tv.edge_off[id];
+            uint64_t key = make_key(tv.parent[id], tv.pool[off]);
+            uint32_t h = hash_key(key) & tv.slot_mask;
+            for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+                unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key,
+                                                    (unsigned long long)kEmptyKey, (unsigned long long)key);
+                if (prev == (unsigned long long)kEmptyKey) {
+                    tv.slots[h].child = (int32_t)id;
+                    tv.slots[h].edge_len = len;
+                    tv.slots[h].edge_off = off;
+                    break;
+                }
+                h = (h + 1) & tv.slot_mask;
+            }
+        }
+    }
+    if (last_block_done(st, 3) && threadIdx.x == 0) write_stats(st, stats_out);
 }
 
 // ------------------------------------------------------------------ tails
@@ -234,15 +256,43 @@ __device__ __forceinline__ int64_t ld_i64(const int64_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// A node record read with loads that see other compute units' writes; the four loads are issued
+// together (one round trip).
+struct NodeRec {
+    int32_t parent, edge_len, depth_end;
+    int64_t edge_off;
+};
+__device__ __forceinline__ NodeRec load_node(const TreeView &tv, int32_t id) {
+    int32_t pa = ld_i32(&tv.parent[id]);
+    int32_t el = ld_i32(&tv.edge_len[id]);
+    int32_t de = ld_i32(&tv.depth_end[id]);
+    int64_t eo = ld_i64(&tv.edge_off[id]);
+    NodeRec r;
+    r.parent = uni(pa);
+    r.edge_len = uni(el);
+    r.depth_end = uni(de);
+    r.edge_off = uni64(eo);
+    return r;
+}
+
 __device__ __forceinline__ int32_t slot_find_live(const TreeView &tv, uint64_t key, int32_t &child, int32_t &edge_len,
                                                   int64_t &edge_off) {
     uint32_t h = hash_key(key) & tv.slot_mask;
     for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+        // all four fields in one round trip; the payload is only meaningful when the key matches,
+        // and a key is only ever looked up by the wavefront that inserted it
         uint64_t k = ld_u64(&tv.slots[h].key);
+        int32_t c = ld_i32(&tv.slots[h].child);
+        int32_t l = ld_i32(&tv.slots[h].edge_len);
+        int64_t o = ld_i64(&tv.slots[h].edge_off);
+        k = (uint64_t)uni64((int64_t)k);
+        c = uni(c);
+        l = uni(l);
+        o = uni64(o);
         if (k == key) {
-            child = ld_i32(&tv.slots[h].child);
-            edge_len = ld_i32(&tv.slots[h].edge_len);
-            edge_off = ld_i64(&tv.slots[h].edge_off);
+            child = c;
+            edge_len = l;
+            edge_off = o;
             return (int32_t)h;
         }
         if (k == kEmptyKey) return -1;
@@ -269,31 +319,32 @@ __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key,
     return -1;
 }
 
-// lane 0 only
-__device__ __forceinline__ int32_t alloc_node(const TreeView &tv) {
-    DevState *st = tv.st;
-    int32_t a = atomicAdd(&st->alloc_cnt, 1);
-    int32_t id = (a < st->free_cnt0) ? tv.free_stack[st->free_cnt0 - 1 - a] : st->n_slots0 + (a - st->free_cnt0);
-    if (id <= 0 || id >= tv.max_nodes) {
-        flag_error(st, 1u);
-        return -1;
-    }
-    return id;
+// Node ids are reserved up front, two per admitted prompt (an insertion makes at most one split
+// and at most one leaf), so the structure pass needs no shared allocation counter: reservation a
+// comes off the top of the free-id stack while it lasts, then from never-used ids.  Reservations
+// that end up unused are pushed back when the inserts are published.
+__device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
+    const DevState *st = tv.st;
+    int32_t f0 = st->free_cnt0;
+    int32_t id = (a < f0) ? tv.free_stack[f0 - 1 - a] : st->n_slots0 + (a - f0);
+    return (id > 0 && id < tv.max_nodes) ? id : -1;
 }
 
 // Split node c (reached through table slot s) after its first `at` edge tokens. The new node takes
 // the upper part; c keeps the lower part, its id, its end boundary, its children and its tick.
 // Returns the new upper node (wave-uniform) or -1.
-__device__ __forceinline__ int32_t split_node(const TreeView &tv, int32_t c, int32_t s, int32_t at, uint64_t tick,
-                                              int lane) {
+__device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs &ws, int32_t j, int32_t c,
+                                              const NodeRec &rec, int32_t s, int32_t at, uint64_t tick, int lane) {
     int32_t up = -1;
     if (lane == 0) {
-        up = alloc_node(tv);
+        int32_t low_first = tv.pool[rec.edge_off + at];  // first token of the lower part (tokens never move)
+        up = reserved_id(tv, 2 * j);
+        if (up < 0) flag_error(tv.st, 1u);
         if (up > 0) {
-            int64_t eo = ld_i64(&tv.edge_off[c]);
-            int32_t el = ld_i32(&tv.edge_len[c]);
-            int32_t de = ld_i32(&tv.depth_end[c]);
-            tv.parent[up] = ld_i32(&tv.parent[c]);
+            int64_t eo = rec.edge_off;
+            int32_t el = rec.edge_len;
+            int32_t de = rec.depth_end;
+            tv.parent[up] = rec.parent;
             tv.edge_off[up] = eo;
             tv.edge_len[up] = at;
             tv.depth_end[up] = de - el + at;
@@ -303,8 +354,8 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, int32_t c, int
             tv.edge_off[c] = eo + at;
             tv.edge_len[c] = el - at;
             tv.parent[c] = up;
-            slot_insert(tv, make_key(up, tv.pool[eo + at]), c, el - at, eo + at);
-            atomicAdd(&tv.st->new_nodes, 1);
+            slot_insert(tv, make_key(up, low_first), c, el - at, eo + at);
+            ws.used[j] |= 1;
         }
     }
     up = uni(__shfl(up, 0));
@@ -315,39 +366,49 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, int32_t c, int
 __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t *__restrict__ batch_idx,
                               const CommitWs &ws, int32_t j, int lane) {
     DevState *st = tv.st;
-    const int32_t qi = uni(batch_idx[j]);
-    const int64_t qoff = uni64(q.off[qi]);
-    const int32_t L = uni(q.len[qi]);
-    const int32_t m = uni(ws.bm_len[j]);
-    const int32_t e = uni(ws.bm_node[j]);
-    const uint64_t tick = st->clock0 + (uint64_t)j;
-    const int64_t tail_base = st->pool_top + ws.tail_off[j];  // pool index holding x[m]
+    // independent reads first, then the ones that depend on them
+    const int32_t qi_v = batch_idx[j];
+    const int32_t m_v = ws.bm_len[j];
+    const int32_t e_v = ws.bm_node[j];
+    const int64_t to_v = ws.tail_off[j];
+    const uint64_t clock0 = st->clock0;
+    const int64_t pool_top = st->pool_top;
+    const int32_t qi = uni(qi_v);
+    const int32_t m = uni(m_v);
+    const int32_t e = uni(e_v);
+    const int64_t qoff_v = q.off[qi];
+    const int32_t L_v = q.len[qi];
+    const int32_t de_e_v = ld_i32(&tv.depth_end[e]);
+    const int64_t qoff = uni64(qoff_v);
+    const int32_t L = uni(L_v);
+    const int32_t de_e = uni(de_e_v);
+    const uint64_t tick = clock0 + (uint64_t)j;
+    const int64_t tail_base = uni64(pool_top + to_v);  // pool index holding x[m]
     const int32_t *__restrict__ x = q.tokens + qoff;
 
     int32_t cur = e;
     int32_t d = m;
-    if (e != kRoot && m < uni(ld_i32(&tv.depth_end[e]))) {
+    if (e != kRoot && m < de_e) {
         // The match stopped inside the edge that node e had before this commit. Earlier prompts of
         // this group may have cut that edge into a chain of pieces ending in e; find the piece
         // whose span (start, end] contains depth m.
+        NodeRec rec = load_node(tv, cur);
         for (int guard = 0; guard <= tv.max_batch + 1; ++guard) {
-            int32_t ds = uni(ld_i32(&tv.depth_end[cur])) - uni(ld_i32(&tv.edge_len[cur]));
-            if (ds < m) break;
-            cur = uni(ld_i32(&tv.parent[cur]));
+            if (rec.depth_end - rec.edge_len < m) break;
+            cur = rec.parent;
+            rec = load_node(tv, cur);
         }
-        int32_t de = uni(ld_i32(&tv.depth_end[cur]));
-        if (m < de) {
-            int32_t el = uni(ld_i32(&tv.edge_len[cur]));
-            int32_t ds = de - el;
+        if (m < rec.depth_end) {
+            int32_t ds = rec.depth_end - rec.edge_len;
             int32_t c2, el2;
             int64_t eo2;
-            int64_t eo = uni64(ld_i64(&tv.edge_off[cur]));
-            int32_t s = slot_find_live(tv, make_key(uni(ld_i32(&tv.parent[cur])), uni(tv.pool[eo])), c2, el2, eo2);
-            if (s < 0 || uni(c2) != cur || m - ds <= 0) {
+            int32_t first = uni(tv.pool[rec.edge_off]);
+            int32_t s = slot_find_live(tv, make_key(rec.parent, first), c2, el2, eo2);
+            if (s < 0 || c2 != cur || m - ds <= 0) {
                 if (lane == 0) flag_error(st, 4u);
                 return;
             }
-            int32_t up = split_node(tv, cur, uni(s), m - ds, tick, lane);
+            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, lane);
             if (up < 0) return;
             cur = up;
         }
@@ -357,11 +418,12 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
         int32_t tok = uni(x[d]);
         int32_t c, el;
         int64_t eo;
-        int32_t s = uni(slot_find_live(tv, make_key(cur, tok), c, el, eo));
+        int32_t s = slot_find_live(tv, make_key(cur, tok), c, el, eo);
         if (s < 0) {
             int32_t leaf = -1;
             if (lane == 0) {
-                leaf = alloc_node(tv);
+                leaf = reserved_id(tv, 2 * j + 1);
+                if (leaf < 0) flag_error(st, 1u);
                 if (leaf > 0) {
                     int64_t off = tail_base + (int64_t)(d - m);
                     tv.parent[leaf] = cur;
@@ -370,8 +432,8 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
                     tv.depth_end[leaf] = L;
                     tv.tick[leaf] = tick;
                     slot_insert(tv, make_key(cur, tok), leaf, L - d, off);
-                    atomicAdd((unsigned long long *)&st->inserted_tokens, (unsigned long long)(L - d));
-                    atomicAdd(&st->new_nodes, 1);
+                    ws.used[j] |= 2;
+                    ws.leaf_tok[j] = L - d;
                 }
             }
             leaf = uni(__shfl(leaf, 0));
@@ -381,9 +443,6 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
             d = L;
             break;
         }
-        c = uni(c);
-        el = uni(el);
-        eo = uni64(eo);
         int32_t lim = el < L - d ? el : L - d;
         int32_t jj = wave_common_prefix(x + d, tv.pool + eo, lim, lane);
         if (jj <= 0) {  // the first token matched by construction; anything else is corruption
@@ -395,7 +454,8 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
             d += el;
             continue;
         }
-        int32_t up = split_node(tv, c, s, jj, tick, lane);
+        NodeRec rec = load_node(tv, c);
+        int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, lane);
         if (up < 0) return;
         cur = up;
         d += jj;
@@ -413,59 +473,109 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
     if (g >= nb) return;
     const uint64_t key = ws.gkey[g];
     if (key == kNoGroup) return;
-    // the first prompt of a group (in pick order) owns the group
+    // the first prompt of a group (in pick order) owns the group; the compares are independent
+    // loads, so no early exit inside the loop
+    bool dup = false;
     for (int32_t base = 0; base < g; base += kWave) {
         int32_t i = base + lane;
-        bool eq = (i < g) && (ws.gkey[i] == key);
-        if (__ballot(eq)) return;
+        dup |= (i < g) && (ws.gkey[i] == key);
     }
+    if (__ballot(dup)) return;
     insert_prompt(tv, q, batch_idx, ws, g, lane);
-    for (int32_t base = g + 1; base < nb; base += kWave) {
-        int32_t i = base + lane;
-        bool eq = (i < nb) && (ws.gkey[i] == key);
-        uint64_t mask = __ballot(eq);
-        while (mask) {
-            int32_t b = (int32_t)__builtin_ctzll(mask);
-            mask &= mask - 1ull;
-            insert_prompt(tv, q, batch_idx, ws, base + b, lane);
+    // later members of the group, 4096 candidates at a time: bit t of `mine` = candidate base+64t+lane
+    for (int32_t base = g + 1; base < nb; base += 64 * kWave) {
+        uint64_t mine = 0;
+        const int32_t rows = (nb - base + kWave - 1) / kWave < 64 ? (nb - base + kWave - 1) / kWave : 64;
+#pragma unroll 8
+        for (int32_t t = 0; t < rows; ++t) {
+            int32_t i = base + t * kWave + lane;
+            uint64_t kk = ws.gkey[i < nb ? i : nb - 1];
+            if (i < nb && kk == key) mine |= (1ull << t);
+        }
+        if (!__ballot(mine != 0)) continue;
+        for (int32_t t = 0; t < 64 && base + t * kWave < nb; ++t) {
+            uint64_t mask = __ballot((mine >> t) & 1ull);
+            while (mask) {
+                int32_t b = (int32_t)__builtin_ctzll(mask);
+                mask &= mask - 1ull;
+                insert_prompt(tv, q, batch_idx, ws, base + t * kWave + b, lane);
+            }
         }
     }
 }
 
-// ------------------------------------------------------------------ ticks
-__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws) {
+// ------------------------------------------------------------------ ticks, then publish the inserts
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget) {
     DevState *st = tv.st;
-    if (st->skip) return;
     const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= st->nb) return;
-    const uint64_t t = st->clock0 + (uint64_t)j;
-    int32_t v = ws.end_node[j];
-    for (int32_t guard = 0; guard <= tv.max_prompt_len && v > kRoot && v < tv.max_nodes; ++guard) {
-        unsigned long long old = atomicMax((unsigned long long *)&tv.tick[v], (unsigned long long)t);
-        // a strictly later prompt already stamped this node and stamps its ancestors too; an equal
-        // value is this prompt's own stamp on a node it created, so keep climbing
-        if (old > (unsigned long long)t) break;
-        v = tv.parent[v];
+    if (!st->skip && j < st->nb) {
+        const uint64_t t = st->clock0 + (uint64_t)j;
+        int32_t v = ws.end_node[j];
+        for (int32_t guard = 0; guard <= tv.max_prompt_len && v > kRoot && v < tv.max_nodes; ++guard) {
+            unsigned long long old = atomicMax((unsigned long long *)&tv.tick[v], (unsigned long long)t);
+            // a strictly later prompt already stamped this node and stamps its ancestors too; an equal
+            // value is this prompt's own stamp on a node it created, so keep climbing
+            if (old > (unsigned long long)t) break;
+            v = tv.parent[v];
+        }
     }
-}
-
-// ------------------------------------------------------------------ mid: publish the inserts, decide eviction
-__global__ void k_commit_mid(TreeView tv, CommitWs ws, int64_t budget) {
-    DevState *st = tv.st;
-    const int tid = threadIdx.x;
-    if (blockIdx.x != 0) return;
+    // the last workgroup publishes the inserts and decides whether anything must be evicted
     __shared__ int evict;
-    if (tid == 0) {
-        evict = 0;
-        if (!st->skip) {
-            st->clock = st->clock0 + (uint64_t)st->nb;
-            int32_t a = st->alloc_cnt;
-            if (a <= st->free_cnt0) {
-                st->free_cnt = st->free_cnt0 - a;
-            } else {
-                st->free_cnt = 0;
-                st->n_slots = st->n_slots0 + (a - st->free_cnt0);
+    __shared__ int32_t sbuf[256];
+    __shared__ int32_t s_carry;
+    __shared__ unsigned long long s_tok;
+    __shared__ int32_t s_new;
+    if (!last_block_done(st, 1)) return;
+    const int tid = threadIdx.x;
+    if (tid == 0) { s_carry = 0; s_tok = 0; s_new = 0; evict = 0; }
+    __syncthreads();
+    if (!st->skip) {
+        // give back the reserved node ids that were not used, count what was added
+        const int32_t nb = st->nb;
+        const int32_t A = 2 * nb;
+        const int32_t f0 = st->free_cnt0;
+        const int32_t from_free = A < f0 ? A : f0;
+        const int32_t base = f0 - from_free;
+        for (int32_t a = tid; a < A; a += 256) ws.resv_id[a] = reserved_id(tv, a);
+        unsigned long long my_tok = 0;
+        int32_t my_new = 0;
+        for (int32_t j2 = tid; j2 < nb; j2 += 256) {
+            int32_t u = ws.used[j2];
+            my_new += (u & 1) + ((u >> 1) & 1);
+            my_tok += (unsigned long long)ws.leaf_tok[j2];
+        }
+        if (my_tok) atomicAdd(&s_tok, my_tok);
+        if (my_new) atomicAdd(&s_new, my_new);
+        __syncthreads();
+        for (int32_t a0 = 0; a0 < A; a0 += 256) {
+            int32_t a = a0 + tid;
+            int32_t unused = 0;
+            if (a < A) unused = ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
+            sbuf[tid] = unused;
+            __syncthreads();
+            for (int d = 1; d < 256; d <<= 1) {
+                int32_t v = (tid >= d) ? sbuf[tid - d] : 0;
+                __syncthreads();
+                sbuf[tid] += v;
+                __syncthreads();
             }
+            if (unused) {
+                int32_t dst = base + s_carry + sbuf[tid] - 1;
+                if (dst >= 0 && dst < tv.max_nodes) tv.free_stack[dst] = ws.resv_id[a];
+            }
+            __syncthreads();
+            if (tid == 255) s_carry += sbuf[255];
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        if (!st->skip) {
+            const int32_t A = 2 * st->nb;
+            st->clock = st->clock0 + (uint64_t)st->nb;
+            st->free_cnt = st->free_cnt0 - (A < st->free_cnt0 ? A : st->free_cnt0) + s_carry;
+            if (A > st->free_cnt0) st->n_slots = st->n_slots0 + (A - st->free_cnt0);
+            st->inserted_tokens = (int64_t)s_tok;
+            st->new_nodes = s_new;
             st->pool_top += st->tail_total;
             st->total_tokens += st->inserted_tokens;
             st->n_nodes += st->new_nodes;
@@ -473,6 +583,8 @@ __global__ void k_commit_mid(TreeView tv, CommitWs ws, int64_t budget) {
             if (need > 0) {
                 st->do_evict = 1;
                 st->need_evict = need;
+                st->evict_rem = need;
+                st->evict_prefix = 0;
                 evict = 1;
             }
         }
@@ -490,37 +602,31 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
     return (tv.tick[id] << depth_bits) | (dm - (uint64_t)(uint32_t)tv.depth_end[id]);
 }
 
-// after `upto` finished passes: the key digits fixed so far and the tokens still to free inside them
-__device__ void evict_descend(const int64_t *__restrict__ hist, int upto, int64_t need, uint64_t *prefix_out,
-                              int64_t *rem_out) {
-    // block of 256 threads; every thread returns the same values
+// One step of the search for the cut key, run by one workgroup of 256 threads once the weighted
+// histogram of the current digit is complete: pick the smallest digit whose inclusive weight
+// reaches what is still to be freed, append it to the prefix and reduce the remainder.
+__device__ void evict_descend_step(DevState *st, const int64_t *__restrict__ hist) {
     __shared__ int64_t sc[256];
     __shared__ int pick;
     const int tid = threadIdx.x;
-    uint64_t prefix = 0;
-    int64_t rem = need;
-    for (int p = 0; p < upto; ++p) {
-        int64_t h = hist[p * 256 + tid];
-        sc[tid] = h;
-        if (tid == 0) pick = 255;
+    const int64_t rem = st->evict_rem;
+    sc[tid] = hist[tid];
+    if (tid == 0) pick = 255;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {
+        int64_t v = (tid >= d) ? sc[tid - d] : 0;
         __syncthreads();
-        for (int d = 1; d < 256; d <<= 1) {
-            int64_t v = (tid >= d) ? sc[tid - d] : 0;
-            __syncthreads();
-            sc[tid] += v;
-            __syncthreads();
-        }
-        // smallest digit whose inclusive weight reaches what is still needed
-        if (sc[tid] >= rem) atomicMin(&pick, tid);
+        sc[tid] += v;
         __syncthreads();
+    }
+    if (sc[tid] >= rem) atomicMin(&pick, tid);
+    __syncthreads();
+    if (tid == 0) {
         int dg = pick;
         int64_t below = (dg > 0) ? sc[dg - 1] : 0;
-        __syncthreads();
-        rem -= below;
-        prefix = (prefix << 8) | (uint64_t)dg;
+        st->evict_rem = rem - below;
+        st->evict_prefix = (st->evict_prefix << 8) | (uint64_t)dg;
     }
-    *prefix_out = prefix;
-    *rem_out = rem;
 }
 
 __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, int pass, int n_pass, int depth_bits) {
@@ -528,9 +634,7 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     if (!st->do_evict) return;
     __shared__ unsigned long long h[256];
     const int tid = threadIdx.x;
-    uint64_t prefix;
-    int64_t rem;
-    evict_descend(ws.evict_hist, pass, st->need_evict, &prefix, &rem);
+    const uint64_t prefix = st->evict_prefix;  // digits fixed by the earlier passes
     h[tid] = 0;
     __syncthreads();
     const int shift = 8 * (n_pass - 1 - pass);
@@ -544,6 +648,7 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     }
     __syncthreads();
     if (h[tid]) atomicAdd((unsigned long long *)&ws.evict_hist[pass * 256 + tid], h[tid]);
+    if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * 256);
 }
 
 __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int n_pass, int depth_bits) {
@@ -552,9 +657,7 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
     __shared__ unsigned long long s_tok;
     __shared__ int s_cnt;
     const int tid = threadIdx.x;
-    uint64_t cut;
-    int64_t rem;
-    evict_descend(ws.evict_hist, n_pass, st->need_evict, &cut, &rem);
+    const uint64_t cut = st->evict_prefix;  // every live node with key <= cut goes
     if (tid == 0) { s_tok = 0; s_cnt = 0; }
     __syncthreads();
     const int32_t n_slots = st->n_slots;
@@ -574,40 +677,14 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
         atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
         atomicAdd(&st->evicted_nodes, s_cnt);
     }
-}
-
-__global__ void k_evict_end(TreeView tv) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    DevState *st = tv.st;
-    if (!st->do_evict) return;
-    st->total_tokens -= st->evicted_tokens;
-    st->n_nodes -= st->evicted_nodes;
-    if (st->evicted_nodes > 0) st->need_rebuild = 1;
-}
-
-__global__ void k_commit_end(TreeView tv, kLPM_stats *__restrict__ out) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    DevState *st = tv.st;
-    st->need_rebuild = 0;
-    if (!out) return;
-    out->total_tokens = st->total_tokens;
-    out->inserted_tokens = st->skip ? 0 : st->inserted_tokens;
-    out->evicted_tokens = st->evicted_tokens;
-    out->n_nodes = st->n_nodes;
-    out->new_nodes = st->skip ? 0 : st->new_nodes;
-    out->evicted_nodes = st->evicted_nodes;
-    out->device_error = st->device_error;
-    out->clock = st->clock;
-}
-
-static void launch_rebuild(const TreeView &tv, hipStream_t stream) {
-    int64_t n = (int64_t)tv.slot_mask + 1;
-    unsigned gc = (unsigned)((n + 255) / 256);
-    if (gc > 4096u) gc = 4096u;
-    unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
-    if (gf > 4096u) gf = 4096u;
-    hipLaunchKernelGGL(k_hash_clear, dim3(gc), dim3(256), 0, stream, tv);
-    hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv);
+    if (last_block_done(st, 2) && tid == 0) {
+        int64_t ev_tok = (int64_t)__hip_atomic_load((unsigned long long *)&st->evicted_tokens, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        st->total_tokens -= ev_tok;
+        st->n_nodes -= ev_cnt;
+        if (ev_cnt > 0) st->need_rebuild = 1;
+    }
 }
 
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
@@ -615,23 +692,21 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     const TreeView &tv = t->tv;
     const CommitWs &ws = t->ws;
     if (batch_cap > t->cfg.max_batch) batch_cap = t->cfg.max_batch;
-    hipLaunchKernelGGL(k_commit_begin, dim3(1), dim3(1), 0, stream, tv, n_selected, batch_cap);
     if (batch_cap > 0) {
-        int rc = launch_match(tv, q, batch_idx, &tv.st->nb, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
+        int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, ws);
+    }
+    hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
+                       ws);
+    if (batch_cap > 0) {
         unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
         if (gn > 2048u) gn = 2048u;
-        hipLaunchKernelGGL(k_compact_begin, dim3(1), dim3(1), 0, stream, tv);
         hipLaunchKernelGGL(k_compact_copy, dim3(gn), dim3(256), 0, stream, tv);
-        hipLaunchKernelGGL(k_compact_end, dim3(1), dim3(1), 0, stream, tv);
-        launch_rebuild(tv, stream);
-        hipLaunchKernelGGL(k_rebuild_done, dim3(1), dim3(1), 0, stream, tv);
         hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws);
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
-        hipLaunchKernelGGL(k_ticks, dim3((batch_cap + 255) / 256), dim3(256), 0, stream, tv, ws);
     }
-    hipLaunchKernelGGL(k_commit_mid, dim3(1), dim3(256), 0, stream, tv, ws, budget);
+    hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,
+                       budget);
     // eviction key = (tick, inverted depth); its width follows from host-known upper bounds
     t->clock_ub += (uint64_t)(batch_cap > 0 ? batch_cap : 0);
     int tick_bits = 1;
@@ -639,14 +714,19 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     int key_bits = tick_bits + t->depth_bits;
     if (key_bits > 64) return KLPM_EINVAL;
     int n_pass = (key_bits + 7) / 8;
-    unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
-    if (ge > 1024u) ge = 1024u;
+    // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
+    unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
+    if (ge > 256u) ge = 256u;
     for (int p = 0; p < n_pass; ++p)
         hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, n_pass, t->depth_bits);
     hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, t->depth_bits);
-    hipLaunchKernelGGL(k_evict_end, dim3(1), dim3(1), 0, stream, tv);
-    launch_rebuild(tv, stream);
-    hipLaunchKernelGGL(k_commit_end, dim3(1), dim3(1), 0, stream, tv, stats_out);
+    int64_t n = (int64_t)tv.slot_mask + 1;
+    unsigned gc = (unsigned)((n + 255) / 256);
+    if (gc > 4096u) gc = 4096u;
+    unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
+    if (gf > 4096u) gf = 4096u;
+    hipLaunchKernelGGL(k_hash_clear, dim3(gc), dim3(256), 0, stream, tv);
+    hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv, stats_out);
     return check_launch();
 }
 

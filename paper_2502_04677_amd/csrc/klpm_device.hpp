@@ -39,7 +39,7 @@ struct DevState {
     // ---- scalars of the commit in flight ----
     int32_t nb;            // admitted prompts in this commit
     int32_t skip;          // 1 = this commit is abandoned (error), later kernels do nothing
-    int32_t alloc_cnt;     // node ids handed out during the structure pass
+    int32_t alloc_cnt;     // unused
     int32_t free_cnt0;     // free_cnt / n_slots / pool_top / clock at the start of the structure pass
     int32_t n_slots0;
     int32_t need_compact;
@@ -55,6 +55,9 @@ struct DevState {
     int64_t evicted_tokens;
     int32_t new_nodes;
     int32_t evicted_nodes;
+    int32_t done[12];      // workgroups finished, per fused kernel of the commit (4.. = eviction passes)
+    uint64_t evict_prefix; // digits of the eviction cut key fixed so far
+    int64_t evict_rem;     // tokens still to free among the keys that share that prefix
 };
 
 // Everything a kernel needs to walk or edit the tree; passed by value.
@@ -82,6 +85,9 @@ struct CommitWs {
     int64_t *tail_off;  // [max_batch] offset of prompt j's unmatched tail inside this commit's pool block
     uint64_t *gkey;     // [max_batch] key of the group of prompts that may touch the same new structure
     int32_t *end_node;  // [max_batch] node at which prompt j ends after insertion
+    int32_t *used;      // [max_batch] bit 0: prompt j used its reserved split id, bit 1: its reserved leaf id
+    int32_t *leaf_tok;  // [max_batch] tokens of the leaf prompt j added (0 if none)
+    int32_t *resv_id;   // [2*max_batch] scratch: the node ids reserved for this commit
     int64_t *evict_hist; // [8][256] weighted digit histograms of the eviction threshold search
     int32_t *iota_idx;  // [max_batch] scratch batch indices for build_tree
     int32_t *iota_n;    // [1]
@@ -192,6 +198,19 @@ __device__ __forceinline__ int32_t wave_common_prefix(const int32_t *__restrict_
         }
     }
     return lim;
+}
+
+// How many prompts a commit admits (0 if it must be abandoned, with the reason in *err).
+__device__ __forceinline__ int32_t commit_gate(const TreeView &tv, const int32_t *n_selected, int32_t batch_cap,
+                                               uint32_t *err) {
+    int32_t nb = n_selected ? *n_selected : 0;
+    if (nb < 0) nb = 0;
+    uint32_t e = 0;
+    if (nb > batch_cap || nb > tv.max_batch) e |= 8u;  // KLPM_DEV_BATCH_OVERFLOW
+    int64_t free_nodes = (int64_t)(tv.max_nodes - tv.st->n_slots) + (int64_t)tv.st->free_cnt;
+    if (!e && 2ll * nb > free_nodes) e |= 1u;          // KLPM_DEV_NODES_FULL: a prompt adds at most two nodes
+    *err = e;
+    return e ? 0 : nb;
 }
 
 }  // namespace klpm

@@ -11,7 +11,7 @@ namespace klpm {
 
 // ADMITTED = false: the queue-wide match (wave w handles query w).
 // ADMITTED = true : the match of the admitted prompts inside commit (wave w handles query sel[w],
-//                   the count comes from device memory, an abandoned commit does nothing).
+//                   the count comes from device memory, a commit that must be abandoned matches nothing).
 template <bool ADMITTED>
 __device__ __forceinline__ void match_body(const TreeView &tv, const QView &q, const int32_t *__restrict__ sel,
                                            const int32_t *__restrict__ n_dev, int32_t n_cap,
@@ -20,9 +20,8 @@ __device__ __forceinline__ void match_body(const TreeView &tv, const QView &q, c
     const int64_t w = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
     int32_t n = n_cap;
     if (ADMITTED) {
-        if (tv.st->skip) return;
-        int32_t nd = *n_dev;
-        n = nd < n_cap ? nd : n_cap;
+        uint32_t err;
+        n = commit_gate(tv, n_dev, n_cap, &err);  // the plan kernel records the reason of a refusal
     }
     if (w >= n) return;
     int32_t qi = ADMITTED ? uni(sel[w]) : (int32_t)w;

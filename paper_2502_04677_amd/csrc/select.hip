@@ -199,75 +199,362 @@ static int radix_sort(uint64_t *k0, uint32_t *v0, uint64_t *k1, uint32_t *v1, in
 }
 
 // ---- the two-cursor walk over the oldest-first and longest-match orders ----
+// Acc gives, for a position r < n_valid of either order: the queue index stored there
+// (a_elem / l_elem) and the position of that same query in the other order (a_in_l / l_in_a; any
+// value >= nb stands for "not among the first nb of the other order").  One wavefront runs it.
+template <class Acc>
+__device__ __forceinline__ void two_cursor_walk(const Acc &acc, int32_t n_valid, int32_t nb, uint32_t k, uint32_t phase,
+                                                int32_t *__restrict__ batch_idx, int lane) {
+    int32_t ia = 0, il = 0, j = 0;
+    uint32_t pos = phase;  // (phase + j) mod k, kept incrementally; phase < k on entry
+    const uint32_t km1 = k - 1u;
+    while (j < nb) {
+        // ---- several whole cycles at once, when the two orders do not interfere inside the window
+        if (pos == 0u && (uint32_t)(nb - j) >= k && km1 <= (uint32_t)kWave) {
+            const int32_t ra = ia + lane, rl = il + lane;
+            uint32_t a_other = 0, l_other = 0, a_el = 0, l_el = 0;
+            bool cand_a = false, cand_l = false;
+            if (ra < n_valid) { a_other = acc.a_in_l(ra); a_el = acc.a_elem(ra); cand_a = a_other >= (uint32_t)il; }
+            if (rl < n_valid) { l_other = acc.l_in_a(rl); l_el = acc.l_elem(rl); cand_l = l_other >= (uint32_t)ia; }
+            const uint64_t mask_a = __ballot(cand_a), mask_l = __ballot(cand_l);
+            const int32_t n_a = (int32_t)__popcll(mask_a), n_l = (int32_t)__popcll(mask_l);
+            int32_t c = n_a;
+            if ((int32_t)((uint32_t)n_l / km1) < c) c = (int32_t)((uint32_t)n_l / km1);
+            if ((int32_t)((uint32_t)(nb - j) / k) < c) c = (int32_t)((uint32_t)(nb - j) / k);
+            if (c > 0) {
+                const int32_t my_a = (int32_t)__popcll(mask_a & ((1ull << lane) - 1ull));
+                const int32_t my_l = (int32_t)__popcll(mask_l & ((1ull << lane) - 1ull));
+                const int32_t take_l = c * (int32_t)km1;
+                const bool ch_a = cand_a && my_a < c;
+                const bool ch_l = cand_l && my_l < take_l;
+                const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
+                const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
+                // an oldest pick that also lies in the consumed stretch of the longest-match order (or
+                // the other way round) makes the two streams interact: then go one run at a time
+                const uint64_t clash = __ballot((ch_a && a_other < (uint32_t)il_end) || (ch_l && l_other < (uint32_t)ia_end));
+                if (clash == 0ull) {
+                    if (ch_a) batch_idx[j + my_a * (int32_t)k] = (int32_t)a_el;
+                    if (ch_l) {
+                        uint32_t cyc = (uint32_t)my_l / km1;
+                        uint32_t within = (uint32_t)my_l - cyc * km1;
+                        batch_idx[j + (int32_t)(cyc * k + 1u + within)] = (int32_t)l_el;
+                    }
+                    ia = ia_end;
+                    il = il_end;
+                    j += c * (int32_t)k;
+                    continue;
+                }
+            }
+        }
+        // ---- one run: a single oldest pick, or the longest-match picks up to the next oldest pick
+        const bool oldest = (pos == 0u);
+        const uint32_t run = oldest ? 1u : (k - pos);
+        int32_t want = (int32_t)(run < (uint32_t)(nb - j) ? run : (uint32_t)(nb - j));
+        pos = oldest ? (k > 1u ? 1u : 0u) : 0u;  // position in the cycle after this run
+        while (want > 0) {
+            const int32_t cur = oldest ? ia : il;
+            const int32_t r = cur + lane;
+            bool cand = false;
+            uint32_t elem = 0;
+            if (r < n_valid) {
+                // after consuming A[0,ia) and L[0,il) the picked set is {pos_A < ia} U {pos_L < il}
+                uint32_t other = oldest ? acc.a_in_l(r) : acc.l_in_a(r);
+                cand = oldest ? (other >= (uint32_t)il) : (other >= (uint32_t)ia);
+                elem = oldest ? acc.a_elem(r) : acc.l_elem(r);
+            }
+            const uint64_t mask = __ballot(cand);
+            const int32_t avail = (int32_t)__popcll(mask);
+            const int32_t take = avail < want ? avail : want;
+            const int32_t my = (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            if (cand && my < take) batch_idx[j + my] = (int32_t)elem;
+            int32_t adv = kWave;  // window exhausted: keep looking further along the order
+            if (take == want) {
+                // advance just past the last candidate taken
+                const uint64_t lastm = __ballot(cand && my == take - 1);
+                adv = (int32_t)__builtin_ctzll(lastm) + 1;
+            }
+            if (oldest) ia += adv; else il += adv;
+            j += take;
+            want -= take;
+            if ((oldest ? ia : il) >= n_valid && want > 0) { want = 0; j = nb; }  // unreachable while nb <= n
+        }
+    }
+}
+
 constexpr int kStage = 4096;  // entries of each order staged in LDS
 
-__global__ __launch_bounds__(kWave) void k_sel_walk(const uint32_t *__restrict__ order_a,
-                                                    const uint32_t *__restrict__ order_l,
-                                                    const uint32_t *__restrict__ rank_a,
-                                                    const uint32_t *__restrict__ rank_l, int32_t n, uint32_t k,
-                                                    int32_t batch, uint32_t *__restrict__ phase_inout,
-                                                    int32_t *__restrict__ batch_idx,
-                                                    int32_t *__restrict__ n_selected) {
-    // a_in_l[r] = rank in L of the r-th oldest query, l_in_a[r] = rank in A of the r-th longest match
-    __shared__ uint32_t s_a_in_l[kStage];
-    __shared__ uint32_t s_l_in_a[kStage];
-    const int lane = threadIdx.x;
+struct StagedAcc {
+    const uint32_t *order_a, *order_l, *rank_a, *rank_l;  // global
+    const uint32_t *s_a_elem, *s_l_elem, *s_a_in_l, *s_l_in_a;  // LDS copies of the first `staged` entries
+    int32_t staged;
+    __device__ __forceinline__ uint32_t a_elem(int32_t r) const { return r < staged ? s_a_elem[r] : order_a[r]; }
+    __device__ __forceinline__ uint32_t l_elem(int32_t r) const { return r < staged ? s_l_elem[r] : order_l[r]; }
+    __device__ __forceinline__ uint32_t a_in_l(int32_t r) const { return r < staged ? s_a_in_l[r] : rank_l[order_a[r]]; }
+    __device__ __forceinline__ uint32_t l_in_a(int32_t r) const { return r < staged ? s_l_in_a[r] : rank_a[order_l[r]]; }
+};
+
+__global__ __launch_bounds__(256) void k_sel_walk(const uint32_t *__restrict__ order_a,
+                                                  const uint32_t *__restrict__ order_l,
+                                                  const uint32_t *__restrict__ rank_a,
+                                                  const uint32_t *__restrict__ rank_l, int32_t n, uint32_t k,
+                                                  int32_t batch, uint32_t *__restrict__ phase_inout,
+                                                  int32_t *__restrict__ batch_idx,
+                                                  int32_t *__restrict__ n_selected) {
+    __shared__ uint32_t s_a_elem[kStage], s_l_elem[kStage], s_a_in_l[kStage], s_l_in_a[kStage];
+    const int tid = threadIdx.x;
     const int32_t nb = batch < n ? batch : n;
     const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
     const uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
-    if (lane == 0) {
+    __syncthreads();  // every thread has read the phase before it is rewritten
+    if (tid == 0) {
         *n_selected = nb;
         *phase_inout = lpm_only ? 0u : (uint32_t)(((uint64_t)phase + (uint64_t)nb) % k);
     }
     if (nb <= 0) return;
     if (lpm_only || k == 1u) {  // a single order: the batch is its first nb entries
         const uint32_t *ord = lpm_only ? order_l : order_a;
-        for (int32_t j = lane; j < nb; j += kWave) batch_idx[j] = (int32_t)ord[j];
+        for (int32_t j = tid; j < nb; j += blockDim.x) batch_idx[j] = (int32_t)ord[j];
         return;
     }
-    const int32_t staged = nb < kStage ? nb : kStage;  // cursors never pass nb
-    for (int32_t r = lane; r < staged; r += kWave) {
-        s_a_in_l[r] = rank_l[order_a[r]];
-        s_l_in_a[r] = rank_a[order_l[r]];
+    const int32_t staged = nb < kStage ? nb : kStage;  // the cursors never pass nb
+    for (int32_t r = tid; r < staged; r += blockDim.x) {
+        uint32_t ea = order_a[r], el = order_l[r];
+        s_a_elem[r] = ea;
+        s_l_elem[r] = el;
+        s_a_in_l[r] = rank_l[ea];
+        s_l_in_a[r] = rank_a[el];
     }
     __syncthreads();
-    int32_t ia = 0, il = 0, j = 0;
-    while (j < nb) {
-        // number of consecutive slots of the same kind starting at slot j
-        uint32_t pos = (uint32_t)(((uint64_t)phase + (uint64_t)j) % k);
-        bool oldest = (pos == 0u);
-        int32_t want = oldest ? 1 : (int32_t)((k - pos) < (uint32_t)(nb - j) ? (k - pos) : (uint32_t)(nb - j));
-        if (want > nb - j) want = nb - j;
-        // take `want` unpicked entries from the chosen order, 64 candidates per round
-        while (want > 0) {
-            int32_t cur = oldest ? ia : il;
-            int32_t r = cur + lane;
-            bool cand = false;
-            if (r < n) {
-                uint32_t other = oldest ? (r < staged ? s_a_in_l[r] : rank_l[order_a[r]])
-                                        : (r < staged ? s_l_in_a[r] : rank_a[order_l[r]]);
-                cand = oldest ? (other >= (uint32_t)il) : (other >= (uint32_t)ia);
+    if (tid >= kWave) return;
+    StagedAcc acc{order_a, order_l, rank_a, rank_l, s_a_elem, s_l_elem, s_a_in_l, s_l_in_a, staged};
+    two_cursor_walk(acc, n, nb, k, phase, batch_idx, tid);
+}
+
+// ---- single-kernel selection for a queue kept in arrival order ----
+// When arrival[] is non-decreasing in the queue index, the oldest-first order is the index order
+// and the longest-match order is (-match_len, index).  One workgroup then finds the nb-th largest
+// match length by a few histogram sweeps over match_len, gathers the nb winners of the
+// longest-match order, sorts them in LDS and runs the two-cursor walk, all in one launch.
+constexpr int kFifoThreads = 1024;
+constexpr int kFifoMaxBatch = 4096;
+constexpr int kFifoBins = 2048;
+constexpr int kSweepRows = 16;  // independent loads per thread and trip in the queue sweeps
+
+struct FifoAcc {
+    const uint32_t *l_elem_, *a_in_l_;
+    __device__ __forceinline__ uint32_t a_elem(int32_t r) const { return (uint32_t)r; }
+    __device__ __forceinline__ uint32_t l_elem(int32_t r) const { return l_elem_[r]; }
+    __device__ __forceinline__ uint32_t a_in_l(int32_t r) const { return a_in_l_[r]; }
+    __device__ __forceinline__ uint32_t l_in_a(int32_t r) const { return l_elem_[r]; }
+};
+
+// block-wide inclusive scan of one int per thread (kFifoThreads threads)
+__device__ __forceinline__ int32_t block_scan_incl(int32_t v, int32_t *buf, int tid) {
+    buf[tid] = v;
+    __syncthreads();
+    for (int d = 1; d < kFifoThreads; d <<= 1) {
+        int32_t t = (tid >= d) ? buf[tid - d] : 0;
+        __syncthreads();
+        buf[tid] += t;
+        __syncthreads();
+    }
+    int32_t r = buf[tid];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__restrict__ arrival,
+                                                               const int32_t *__restrict__ match_len, int32_t n,
+                                                               uint32_t k, int32_t batch,
+                                                               uint32_t *__restrict__ phase_inout,
+                                                               int32_t *__restrict__ batch_idx,
+                                                               int32_t *__restrict__ n_selected) {
+    __shared__ uint32_t hist[kFifoBins];
+    __shared__ uint64_t cand[kFifoMaxBatch];
+    __shared__ uint32_t l_elem[kFifoMaxBatch];
+    __shared__ uint32_t a_in_l[kFifoMaxBatch];
+    __shared__ int32_t sbuf[kFifoThreads];
+    __shared__ int32_t s_flag, s_max, s_bin, s_above, s_count;
+    const int tid = threadIdx.x;
+    const int32_t nb = batch < n ? batch : n;
+    const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
+    const uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
+    if (tid == 0) { s_flag = 0; s_max = 0; s_count = 0; }
+    __syncthreads();
+    if (nb <= 0) {
+        if (tid == 0) { *n_selected = 0; *phase_inout = phase; }
+        return;
+    }
+    // sweep 0 (coalesced): arrival order check and the largest match length
+    {
+        int32_t mx = 0;
+        bool viol = false;
+        // eight independent rows per trip keep the single workgroup's loads in flight together
+        for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
+            int32_t mv[kSweepRows];
+            uint64_t t0[kSweepRows], t1[kSweepRows];
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kFifoThreads + tid;
+                int32_t ic = i < n ? i : n - 1;
+                int32_t in = ic + 1 < n ? ic + 1 : n - 1;
+                mv[r] = match_len[ic];
+                t0[r] = arrival[ic];
+                t1[r] = arrival[in];
             }
-            uint64_t mask = __ballot(cand);
-            int32_t avail = (int32_t)__popcll(mask);
-            int32_t take = avail < want ? avail : want;
-            int32_t my = (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (cand && my < take) batch_idx[j + my] = (int32_t)(oldest ? order_a[r] : order_l[r]);
-            int32_t adv;
-            if (take == avail && take < want) {
-                adv = kWave;  // window exhausted, keep looking further along the order
-            } else {
-                // advance just past the last entry taken: position of the take-th set bit
-                uint64_t m2 = mask;
-                for (int32_t t = 1; t < take; ++t) m2 &= m2 - 1ull;
-                adv = (int32_t)__builtin_ctzll(m2) + 1;
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                mx = mv[r] > mx ? mv[r] : mx;
+                viol |= t0[r] > t1[r];
             }
-            if (oldest) ia += adv; else il += adv;
-            j += take;
-            want -= take;
-            if ((oldest ? ia : il) >= n && want > 0) { want = 0; j = nb; }  // cannot happen: nb <= n
+        }
+        if (viol) atomicOr(&s_flag, 1);
+        atomicMax(&s_max, mx);
+    }
+    __syncthreads();
+    if (s_flag) {  // the caller's promise does not hold: select nothing, say so
+        if (tid == 0) *n_selected = -1;
+        return;
+    }
+    if (tid == 0) {
+        *n_selected = nb;
+        *phase_inout = lpm_only ? 0u : (uint32_t)(((uint64_t)phase + (uint64_t)nb) % k);
+    }
+    if (k == 1u) {  // FCFS on an arrival-ordered queue: its first nb entries
+        for (int32_t j = tid; j < nb; j += kFifoThreads) batch_idx[j] = j;
+        return;
+    }
+    // the nb-th largest match length m*, found digit by digit (11 bits per sweep)
+    int mbits = 0;
+    while (mbits < 31 && (s_max >> mbits) != 0) ++mbits;
+    int32_t fixed_hi = 0;      // value of the bits above `shift` already decided
+    int32_t need = nb;         // winners still to be found among elements matching fixed_hi
+    int shift = mbits;         // bits [shift, mbits) are decided
+    while (shift > 0) {
+        const int width = shift < 11 ? shift : 11;
+        const int nshift = shift - width;
+        for (int i = tid; i < kFifoBins; i += kFifoThreads) hist[i] = 0;
+        __syncthreads();
+        for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
+            int32_t mv[kSweepRows];
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kFifoThreads + tid;
+                mv[r] = match_len[i < n ? i : n - 1];
+            }
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kFifoThreads + tid;
+                int32_t m = mv[r] < 0 ? 0 : mv[r];
+                if (i < n && (m >> shift) == fixed_hi) atomicAdd(&hist[(m >> nshift) & ((1 << width) - 1)], 1u);
+            }
+        }
+        __syncthreads();
+        // suffix counts over the bins, top down: thread t owns bins 2t and 2t+1 counted from the top
+        const int nbins = 1 << width;
+        int b0 = nbins - 1 - 2 * tid, b1 = nbins - 2 - 2 * tid;
+        int32_t c0 = (b0 >= 0) ? (int32_t)hist[b0] : 0;
+        int32_t c1 = (b1 >= 0) ? (int32_t)hist[b1] : 0;
+        int32_t incl = block_scan_incl(c0 + c1, sbuf, tid);
+        int32_t before = incl - c0 - c1;  // elements in bins above b0
+        if (b0 >= 0 && before < need && before + c0 >= need) { s_bin = b0; s_above = before; }
+        if (b1 >= 0 && before + c0 < need && before + c0 + c1 >= need) { s_bin = b1; s_above = before + c0; }
+        __syncthreads();
+        fixed_hi = (fixed_hi << width) | s_bin;
+        need -= s_above;
+        shift = nshift;
+        __syncthreads();
+    }
+    const int32_t m_star = fixed_hi;  // count(m > m*) = nb - need < nb <= count(m >= m*)
+    // gather: every query above m*, and the first `need` queries (by index) equal to m*.  Each
+    // wavefront owns a contiguous segment of the queue and reads it 64 entries at a time, so the
+    // index order of the equal-to-m* queries is a ballot prefix plus the counts of earlier segments.
+    {
+        const int lane = tid & (kWave - 1);
+        const int wv = tid / kWave;
+        const int n_wv = kFifoThreads / kWave;
+        const int32_t seg = ((n + n_wv - 1) / n_wv + kWave - 1) / kWave * kWave;
+        const int32_t lo = (int64_t)wv * seg < n ? wv * seg : n;
+        const int32_t hi = lo + seg < n ? lo + seg : n;
+        int32_t eq = 0;
+        for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
+            int32_t mv[kSweepRows];
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kWave + lane;
+                mv[r] = match_len[i < hi ? i : hi - 1];
+            }
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kWave + lane;
+                int32_t m = mv[r] < 0 ? 0 : mv[r];
+                eq += (int32_t)__popcll(__ballot(i < hi && m == m_star));
+            }
+        }
+        if (lane == 0) sbuf[wv] = eq;
+        __syncthreads();
+        int32_t rank = 0;  // equal-to-m* queries in earlier segments
+        for (int w2 = 0; w2 < wv; ++w2) rank += sbuf[w2];
+        for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
+            int32_t mv[kSweepRows];
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kWave + lane;
+                mv[r] = match_len[i < hi ? i : hi - 1];
+            }
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kWave + lane;
+                bool in = i < hi;
+                int32_t m = mv[r] < 0 ? 0 : mv[r];
+                bool is_eq = in && m == m_star;
+                uint64_t eqmask = __ballot(is_eq);
+                int32_t my_rank = rank + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
+                bool win = in && (m > m_star || (is_eq && my_rank < need));
+                if (win) {
+                    int32_t at = atomicAdd(&s_count, 1);
+                    if (at < kFifoMaxBatch)
+                        cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+                }
+                rank += (int32_t)__popcll(eqmask);
+            }
         }
     }
+    __syncthreads();
+    // sort the nb winners by (-match_len, index): bitonic network over the next power of two
+    int32_t np2 = 1;
+    while (np2 < nb) np2 <<= 1;
+    for (int32_t i = nb + tid; i < np2; i += kFifoThreads) cand[i] = ~0ull;
+    __syncthreads();
+    for (int32_t size = 2; size <= np2; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = tid; t < (np2 >> 1); t += kFifoThreads) {
+                int32_t a = 2 * t - (t & (stride - 1));
+                int32_t b = a + stride;
+                bool up = ((a & size) == 0);
+                uint64_t ka = cand[a], kb = cand[b];
+                if ((ka > kb) == up) { cand[a] = kb; cand[b] = ka; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int32_t p = tid; p < nb; p += kFifoThreads) {
+        l_elem[p] = (uint32_t)cand[p];
+        a_in_l[p] = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    if (lpm_only) {
+        for (int32_t j = tid; j < nb; j += kFifoThreads) batch_idx[j] = (int32_t)l_elem[j];
+        return;
+    }
+    for (int32_t p = tid; p < nb; p += kFifoThreads) {
+        uint32_t e = l_elem[p];
+        if (e < (uint32_t)nb) a_in_l[e] = (uint32_t)p;  // the e-th oldest query sits at position p of L
+    }
+    __syncthreads();
+    if (tid >= kWave) return;
+    FifoAcc acc{l_elem, a_in_l};
+    two_cursor_walk(acc, nb, nb, k, phase, batch_idx, tid);
 }
 
 static void carve(SelectWs &ws, char *base, int32_t n, size_t *used) {
@@ -300,12 +587,17 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
 }
 
 extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                           uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace,
-                           size_t workspace_bytes, kLPM_stream stream_) {
+                           uint32_t flags, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+                           void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (n < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
+    if ((flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch) {
+        hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, n, k, batch,
+                           phase_inout, batch_idx, n_selected);
+        return check_launch();
+    }
     SelectWs ws;
     size_t need = 0;
     carve(ws, (char *)workspace, n, &need);
@@ -329,7 +621,7 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, in
             hipLaunchKernelGGL(k_sel_ranks, dim3(g), dim3(256), 0, stream, order_a, order_l, n, ws.rank_a, ws.rank_l);
         }
     }
-    hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(kWave), 0, stream, order_a, order_l, ws.rank_a, ws.rank_l, n, k,
+    hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, order_a, order_l, ws.rank_a, ws.rank_l, n, k,
                        batch, phase_inout, batch_idx, n_selected);
     return check_launch();
 }

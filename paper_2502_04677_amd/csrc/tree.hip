@@ -11,7 +11,7 @@ namespace klpm {
 
 struct Layout {
     size_t state, parent, edge_off, edge_len, depth_end, tick, free_stack, slots, pool;
-    size_t bm_len, bm_node, tail_off, gkey, end_node, evict_hist, iota_idx, iota_n;
+    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, resv_id, evict_hist, iota_idx, iota_n;
     size_t total;
     uint32_t n_slots_table;
 };
@@ -44,6 +44,9 @@ static Layout make_layout(const kLPM_config &c) {
     L.tail_off = take(mb * 8);
     L.gkey = take(mb * 8);
     L.end_node = take(mb * 4);
+    L.used = take(mb * 4);
+    L.leaf_tok = take(mb * 4);
+    L.resv_id = take(mb * 8);
     L.evict_hist = take(8 * 256 * 8);
     L.iota_idx = take(mb * 4);
     L.iota_n = take(256);
@@ -85,108 +88,166 @@ __global__ __launch_bounds__(256) void k_iota(int32_t *__restrict__ idx, int32_t
     if (i == 0) *n_out = count;
 }
 
-// ---- waiting-queue bookkeeping (single block; the queue is a few thousand entries) ----
+// ---- waiting-queue bookkeeping of an online run ----
+// Retire: one workgroup sums the batch's uncached tokens, advances the simulated clock, stamps the
+// TTFT of the admitted queries and sorts their queue positions.  Compact: every surviving entry
+// moves down by the number of retired positions before it (binary search in the sorted list), the
+// arrivals are appended, and the CSR view of the new queue is written on the way.
 constexpr int kQueueThreads = 1024;
+constexpr int kRetireMax = 4096;  // admitted entries the sorted-positions path handles
 
-__global__ __launch_bounds__(kQueueThreads) void k_queue_advance(
-    int32_t *__restrict__ wait_id, uint64_t *__restrict__ wait_arr, int32_t *__restrict__ n_wait, int32_t cap,
-    const int32_t *__restrict__ match_len, const int32_t *__restrict__ len_all, int32_t n_all,
-    const int32_t *__restrict__ batch_idx, const int32_t *__restrict__ n_selected, int32_t batch_cap,
-    const int32_t *__restrict__ new_id, int32_t n_new, uint64_t *__restrict__ sim_clock, int64_t *__restrict__ ttft,
-    int32_t *__restrict__ flags, int32_t *__restrict__ id_tmp, uint64_t *__restrict__ arr_tmp,
-    uint32_t *__restrict__ dev_error) {
+struct QueueHdr {  // at the start of the scratch buffer
+    int32_t nw, n_removed, kept, add;
+    uint64_t now;
+};
+
+struct QueueView {
+    int32_t *id;
+    uint64_t *arrival;
+    int64_t *off;
+    int32_t *len;
+    int32_t *n;
+    int32_t cap;
+};
+
+__global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, QueueView next, QView all,
+                                                                const int32_t *__restrict__ match_len,
+                                                                const int32_t *__restrict__ batch_idx,
+                                                                const int32_t *__restrict__ n_selected,
+                                                                int32_t batch_cap, int32_t n_new,
+                                                                uint64_t *__restrict__ sim_clock,
+                                                                int64_t *__restrict__ ttft, QueueHdr *hdr,
+                                                                int32_t *__restrict__ removed_sorted,
+                                                                uint32_t *__restrict__ dev_error) {
+    __shared__ uint32_t pos[kRetireMax];
     __shared__ unsigned long long s_cost;
     __shared__ uint64_t s_clock;
-    __shared__ int32_t buf[kQueueThreads];
-    __shared__ int32_t carry;
+    __shared__ int32_t s_valid;
     const int tid = threadIdx.x;
-    int32_t nw = *n_wait;
-    if (nw < 0) nw = 0;
-    if (nw > cap) nw = cap;
+    int32_t nw = *cur.n;
+    nw = nw < 0 ? 0 : (nw > cur.cap ? cur.cap : nw);
     int32_t nb = *n_selected;
-    if (nb < 0) nb = 0;
-    if (nb > batch_cap) nb = batch_cap;
-    if (tid == 0) { s_cost = 0; carry = 0; }
-    for (int32_t i = tid; i < nw; i += kQueueThreads) flags[i] = 0;
+    nb = nb < 0 ? 0 : (nb > batch_cap ? batch_cap : nb);
+    if (nb > kRetireMax) nb = kRetireMax;
+    if (tid == 0) { s_cost = 0; s_valid = 0; }
     __syncthreads();
-    // mark the admitted entries and sum their uncached tokens (prefill cost with c_attn = 0)
     unsigned long long my_cost = 0;
     for (int32_t j = tid; j < nb; j += kQueueThreads) {
         int32_t w = batch_idx[j];
+        uint32_t p = 0xFFFFFFFFu;  // invalid positions sort to the end
         if (w >= 0 && w < nw) {
-            flags[w] = 1;
-            int32_t id = wait_id[w];
-            int32_t len = (id >= 0 && id < n_all) ? len_all[id] : 0;
+            p = (uint32_t)w;
+            atomicAdd(&s_valid, 1);
+            int32_t id = cur.id[w];
+            int32_t len = (id >= 0 && id < all.n) ? all.len[id] : 0;
             int32_t m = match_len[w];
-            if (m < 0) m = 0;
-            if (len > m) my_cost += (unsigned long long)(len - m);
+            m = m < 0 ? 0 : m;
+            if (len > m) my_cost += (unsigned long long)(len - m);  // uncached tokens (Def. 2, c_attn = 0)
         }
+        pos[j] = p;
     }
     if (my_cost) atomicAdd(&s_cost, my_cost);
+    int32_t np2 = 1;
+    while (np2 < nb) np2 <<= 1;
+    for (int32_t j = nb + tid; j < np2; j += kQueueThreads) pos[j] = 0xFFFFFFFFu;
     __syncthreads();
     if (tid == 0) s_clock = *sim_clock + (s_cost > 0 ? (uint64_t)s_cost : 1ull);
+    for (int32_t size = 2; size <= np2; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = tid; t < (np2 >> 1); t += kQueueThreads) {
+                int32_t a = 2 * t - (t & (stride - 1));
+                int32_t b = a + stride;
+                bool up = ((a & size) == 0);
+                uint32_t ka = pos[a], kb = pos[b];
+                if ((ka > kb) == up) { pos[a] = kb; pos[b] = ka; }
+            }
+            __syncthreads();
+        }
+    }
     __syncthreads();
     const uint64_t now = s_clock;
-    // the whole batch finishes together: TTFT = finish time - arrival
-    for (int32_t j = tid; j < nb; j += kQueueThreads) {
-        int32_t w = batch_idx[j];
-        if (w >= 0 && w < nw) {
-            int32_t id = wait_id[w];
-            if (id >= 0 && id < n_all) ttft[id] = (int64_t)(now - wait_arr[w]);
-        }
-    }
-    // stable removal of the admitted entries
-    for (int32_t base = 0; base < nw; base += kQueueThreads) {
-        int32_t i = base + tid;
-        int32_t keep = (i < nw && flags[i] == 0) ? 1 : 0;
-        buf[tid] = keep;
-        __syncthreads();
-        for (int d = 1; d < kQueueThreads; d <<= 1) {
-            int32_t v = (tid >= d) ? buf[tid - d] : 0;
-            __syncthreads();
-            buf[tid] += v;
-            __syncthreads();
-        }
-        if (keep) {
-            int32_t dst = carry + buf[tid] - 1;
-            id_tmp[dst] = wait_id[i];
-            arr_tmp[dst] = wait_arr[i];
-        }
-        __syncthreads();
-        if (tid == kQueueThreads - 1) carry += buf[tid];
-        __syncthreads();
-    }
-    const int32_t kept = carry;
-    for (int32_t i = tid; i < kept; i += kQueueThreads) {
-        wait_id[i] = id_tmp[i];
-        wait_arr[i] = arr_tmp[i];
-    }
-    int32_t room = cap - kept;
-    int32_t add = n_new < room ? n_new : room;
-    for (int32_t r = tid; r < add; r += kQueueThreads) {
-        wait_id[kept + r] = new_id[r];
-        wait_arr[kept + r] = now;
+    const int32_t nv = s_valid;
+    // the whole batch finishes together (Sec. 2.1): TTFT = finish time - arrival
+    for (int32_t j = tid; j < nv; j += kQueueThreads) {
+        int32_t w = (int32_t)pos[j];
+        removed_sorted[j] = w;
+        int32_t id = cur.id[w];
+        if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[w]);
     }
     if (tid == 0) {
-        if (add < n_new && dev_error) atomicOr(dev_error, 8u);
-        *n_wait = kept + add;
+        int32_t kept = nw - nv;
+        int32_t room = next.cap - kept;
+        room = room < 0 ? 0 : room;
+        int32_t add = n_new < room ? n_new : room;
+        if ((add < n_new || kept > next.cap) && dev_error) atomicOr(dev_error, 8u);
+        hdr->nw = nw;
+        hdr->n_removed = nv;
+        hdr->kept = kept < next.cap ? kept : next.cap;
+        hdr->add = add;
+        hdr->now = now;
+        *next.n = hdr->kept + add;
         *sim_clock = now;
     }
 }
 
-__global__ __launch_bounds__(256) void k_queue_gather(const int32_t *__restrict__ wait_id,
-                                                      const int32_t *__restrict__ n_wait, int32_t cap,
-                                                      const int64_t *__restrict__ off_all,
-                                                      const int32_t *__restrict__ len_all, int32_t n_all,
-                                                      int64_t *__restrict__ off_out, int32_t *__restrict__ len_out) {
+__global__ __launch_bounds__(256) void k_queue_compact(QueueView cur, QueueView next, QView all,
+                                                       const int32_t *__restrict__ match_len,
+                                                       const int32_t *__restrict__ new_id, const QueueHdr *hdr,
+                                                       const int32_t *__restrict__ removed_sorted,
+                                                       int64_t *__restrict__ matched_accum) {
+    __shared__ unsigned long long s_sum;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_sum = 0;
+    __syncthreads();
+    const int32_t nw = hdr->nw, nr = hdr->n_removed, kept = hdr->kept, add = hdr->add;
+    const uint64_t now = hdr->now;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + tid;
+    unsigned long long my = 0;
+    if (i < nw) {
+        int32_t m = match_len[i];
+        if (m > 0) my = (unsigned long long)m;
+        // retired positions strictly below i, and whether i itself is retired
+        int32_t lo = 0, hi = nr;
+        while (lo < hi) {
+            int32_t mid = (lo + hi) >> 1;
+            if (removed_sorted[mid] < (int32_t)i) lo = mid + 1; else hi = mid;
+        }
+        bool gone = (lo < nr && removed_sorted[lo] == (int32_t)i);
+        int64_t dst = i - lo;
+        if (!gone && dst < kept) {
+            int32_t id = cur.id[i];
+            next.id[dst] = id;
+            next.arrival[dst] = cur.arrival[i];
+            bool ok = id >= 0 && id < all.n;
+            next.off[dst] = ok ? all.off[id] : -1;
+            next.len[dst] = ok ? all.len[id] : 0;
+        }
+    } else if (i < (int64_t)nw + add) {
+        int32_t r = (int32_t)(i - nw);
+        int32_t id = new_id[r];
+        int64_t dst = (int64_t)kept + r;
+        next.id[dst] = id;
+        next.arrival[dst] = now;  // enqueued at the time the previous batch finished
+        bool ok = id >= 0 && id < all.n;
+        next.off[dst] = ok ? all.off[id] : -1;
+        next.len[dst] = ok ? all.len[id] : 0;
+    }
+    if (matched_accum) {
+        if (my) atomicAdd(&s_sum, my);
+        __syncthreads();
+        if (tid == 0 && s_sum) atomicAdd((unsigned long long *)matched_accum, s_sum);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_queue_gather(QueueView q, QView all) {
     int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    int32_t nw = *n_wait;
-    if (nw > cap) nw = cap;
+    int32_t nw = *q.n;
+    if (nw > q.cap) nw = q.cap;
     if (i >= nw) return;
-    int32_t id = wait_id[i];
-    bool ok = id >= 0 && id < n_all;
-    off_out[i] = ok ? off_all[id] : -1;  // an invalid id fails the bounds check of the match kernel
-    len_out[i] = ok ? len_all[id] : 0;
+    int32_t id = q.id[i];
+    bool ok = id >= 0 && id < all.n;
+    q.off[i] = ok ? all.off[id] : -1;  // an invalid id fails the bounds check of the match kernel
+    q.len[i] = ok ? all.len[id] : 0;
 }
 
 static QView make_qview(const kLPM_queries *q) {
@@ -253,6 +314,9 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     ws.tail_off = (int64_t *)(base + L.tail_off);
     ws.gkey = (uint64_t *)(base + L.gkey);
     ws.end_node = (int32_t *)(base + L.end_node);
+    ws.used = (int32_t *)(base + L.used);
+    ws.leaf_tok = (int32_t *)(base + L.leaf_tok);
+    ws.resv_id = (int32_t *)(base + L.resv_id);
     ws.evict_hist = (int64_t *)(base + L.evict_hist);
     ws.iota_idx = (int32_t *)(base + L.iota_idx);
     ws.iota_n = (int32_t *)(base + L.iota_n);
@@ -300,35 +364,55 @@ extern "C" int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens) {
     return KLPM_OK;
 }
 
-extern "C" int kLPM_queue_advance(int32_t *wait_id, uint64_t *wait_arr, int32_t *n_wait, int32_t cap,
-                                  const int32_t *match_len, const int32_t *len_all, int32_t n_all,
-                                  const int32_t *batch_idx, const int32_t *n_selected, int32_t batch_cap,
-                                  const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
-                                  void *scratch, size_t scratch_bytes, uint32_t *dev_error, kLPM_stream stream_) {
-    if (!wait_id || !wait_arr || !n_wait || cap < 0 || n_all < 0 || batch_cap < 0 || n_new < 0 || !sim_clock ||
-        !ttft || !scratch || !n_selected)
+static bool queue_ok(const kLPM_queue *q) {
+    return q && q->cap >= 0 && q->n && (q->cap == 0 || (q->id && q->arrival && q->off && q->len));
+}
+
+static QueueView make_queue_view(const kLPM_queue *q) {
+    QueueView v;
+    v.id = q->id; v.arrival = q->arrival; v.off = q->off; v.len = q->len; v.n = q->n; v.cap = q->cap;
+    return v;
+}
+
+extern "C" int kLPM_queue_scratch_bytes(int32_t batch_cap, size_t *out_bytes) {
+    if (batch_cap < 0 || !out_bytes) return KLPM_EINVAL;
+    *out_bytes = 256 + align_up((size_t)(batch_cap > 0 ? batch_cap : 1) * 4, 256);
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
+                                  const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
+                                  int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock,
+                                  int64_t *ttft, int64_t *matched_accum, void *scratch, size_t scratch_bytes,
+                                  uint32_t *dev_error, kLPM_stream stream_) {
+    if (!queue_ok(cur) || !queue_ok(next) || !queries_ok(all) || batch_cap < 0 || n_new < 0 || !sim_clock || !ttft ||
+        !scratch || !n_selected)
         return KLPM_EINVAL;
-    if ((batch_cap > 0 && (!batch_idx || !match_len || !len_all)) || (n_new > 0 && !new_id)) return KLPM_EINVAL;
-    size_t c = (size_t)(cap > 0 ? cap : 1);
-    size_t o_flags = 0, o_id = align_up(c * 4, 256), o_arr = o_id + align_up(c * 4, 256);
-    size_t need = o_arr + align_up(c * 8, 256);
+    if (cur->id == next->id || cur->arrival == next->arrival || cur->n == next->n) return KLPM_EINVAL;
+    if ((batch_cap > 0 && (!batch_idx || !match_len)) || (n_new > 0 && !new_id)) return KLPM_EINVAL;
+    if (batch_cap > kRetireMax) return KLPM_EINVAL;
+    size_t need = 0;
+    kLPM_queue_scratch_bytes(batch_cap, &need);
     if (scratch_bytes < need || ((uintptr_t)scratch & 255u)) return KLPM_EARENA;
-    char *s = (char *)scratch;
-    hipLaunchKernelGGL(k_queue_advance, dim3(1), dim3(kQueueThreads), 0, (hipStream_t)stream_, wait_id, wait_arr,
-                       n_wait, cap, match_len, len_all, n_all, batch_idx, n_selected, batch_cap, new_id, n_new,
-                       sim_clock, ttft, (int32_t *)(s + o_flags), (int32_t *)(s + o_id), (uint64_t *)(s + o_arr),
-                       dev_error);
+    hipStream_t stream = (hipStream_t)stream_;
+    QueueHdr *hdr = (QueueHdr *)scratch;
+    int32_t *removed = (int32_t *)((char *)scratch + 256);
+    QueueView c = make_queue_view(cur), n = make_queue_view(next);
+    QView a = make_qview(all);
+    hipLaunchKernelGGL(k_queue_retire, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
+                       n_selected, batch_cap, n_new, sim_clock, ttft, hdr, removed, dev_error);
+    int64_t work = (int64_t)cur->cap + n_new;
+    if (work > 0)
+        hipLaunchKernelGGL(k_queue_compact, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, c, n, a,
+                           match_len, new_id, hdr, removed, matched_accum);
     return check_launch();
 }
 
-extern "C" int kLPM_queue_gather(const int32_t *wait_id, const int32_t *n_wait, int32_t cap, const int64_t *off_all,
-                                 const int32_t *len_all, int32_t n_all, int64_t *off_out, int32_t *len_out,
-                                 kLPM_stream stream_) {
-    if (!wait_id || !n_wait || cap < 0 || !off_all || !len_all || n_all < 0 || !off_out || !len_out)
-        return KLPM_EINVAL;
-    if (cap == 0) return KLPM_OK;
-    hipLaunchKernelGGL(k_queue_gather, dim3((cap + 255) / 256), dim3(256), 0, (hipStream_t)stream_, wait_id, n_wait,
-                       cap, off_all, len_all, n_all, off_out, len_out);
+extern "C" int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream stream_) {
+    if (!queue_ok(q) || !queries_ok(all)) return KLPM_EINVAL;
+    if (q->cap == 0) return KLPM_OK;
+    hipLaunchKernelGGL(k_queue_gather, dim3((q->cap + 255) / 256), dim3(256), 0, (hipStream_t)stream_,
+                       make_queue_view(q), make_qview(all));
     return check_launch();
 }
 

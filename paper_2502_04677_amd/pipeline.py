@@ -40,10 +40,11 @@ class Scheduler:
         assert q.n <= self.n_max
         return B.kLPM_match(self.tree, q, self.match_len, self.last_node if want_nodes else None)
 
-    def select(self, q: B.DeviceQueries, k: int, batch: int, n: Optional[int] = None) -> None:
+    def select(self, q: B.DeviceQueries, k: int, batch: int, n: Optional[int] = None, fifo: bool = False) -> None:
+        """``fifo`` promises that the queue is in arrival order (checked on the device)."""
         assert batch <= self.cfg.max_batch
         B.kLPM_select(q.arrival, self.match_len, q.n if n is None else n, k, batch, self.phase, self.batch_idx,
-                      self.n_selected, self.ws, self.ws_bytes)
+                      self.n_selected, self.ws, self.ws_bytes, flags=B.KLPM_SELECT_FIFO if fifo else 0)
 
     def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None) -> None:
         B.kLPM_commit(self.tree, q, self.batch_idx, self.n_selected,
@@ -74,43 +75,63 @@ class Scheduler:
 
 
 class OnlineRun:
-    """Device-resident waiting queue for an online stream (arrivals per scheduling step)."""
+    """Device-resident waiting queue for an online stream (arrivals per scheduling step).
 
-    def __init__(self, sched: Scheduler, all_q: B.DeviceQueries, cap: int, first_ids: np.ndarray):
+    Two buffer sets are used in turn: each step reads the current queue and writes the next one.
+    The queue length evolves deterministically (admitted = min(batch, waiting)), so the host tracks
+    it without reading anything back.
+    """
+
+    def __init__(self, sched: Scheduler, all_q: B.DeviceQueries, cap: int, first_ids: np.ndarray,
+                 first_arrival: Optional[np.ndarray] = None):
         dev = sched.device
         self.s = sched
         self.all_q = all_q
         self.cap = int(cap)
-        self.wait_id = torch.zeros(self.cap, dtype=torch.int32, device=dev)
-        self.wait_arr = torch.zeros(self.cap, dtype=torch.int64, device=dev)
-        self.n_wait = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.off_w = torch.zeros(self.cap, dtype=torch.int64, device=dev)
-        self.len_w = torch.zeros(self.cap, dtype=torch.int32, device=dev)
+        self.queues = [B.DeviceQueue.empty(cap, dev), B.DeviceQueue.empty(cap, dev)]
+        self.cur = 0
         self.sim_clock = torch.zeros(1, dtype=torch.int64, device=dev)
         self.ttft = torch.full((max(all_q.n, 1),), -1, dtype=torch.int64, device=dev)
+        self.matched = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dev_error = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.scratch_bytes = 16 * max(self.cap, 1) + 768
+        self.scratch_bytes = B.kLPM_queue_scratch_bytes(sched.cfg.max_batch)
         self.scratch = B.alloc_aligned(self.scratch_bytes, dev)
         n0 = int(first_ids.shape[0])
         assert n0 <= self.cap
-        self.wait_id[:n0] = torch.from_numpy(first_ids.astype(np.int32)).to(dev)
-        self.n_wait.fill_(n0)
+        q0 = self.queues[0]
+        q0.id[:n0] = torch.from_numpy(first_ids.astype(np.int32)).to(dev)
+        if first_arrival is not None:
+            q0.arrival[:n0] = torch.from_numpy(np.ascontiguousarray(first_arrival, dtype=np.uint64).view(np.int64)).to(dev)
+        q0.n.fill_(n0)
         self.n_host = n0
+        B.kLPM_queue_gather(q0, all_q)
+
+    @property
+    def queue(self) -> B.DeviceQueue:
+        return self.queues[self.cur]
+
+    def view(self) -> B.DeviceQueries:
+        """The current queue as a query set sharing the stream's token pool."""
+        q = self.queue
+        return B.DeviceQueries(self.all_q.tokens, q.off, q.len, q.arrival, self.n_host)
+
+    def advance(self, batch: int, new_ids: Optional[torch.Tensor], matched: Optional[torch.Tensor] = None) -> None:
+        """Retire the batch and enqueue ``new_ids``; the queue's summed match length is added to
+        ``matched`` (a one-element int64 device tensor; default: this run's own accumulator)."""
+        s = self.s
+        n_new = 0 if new_ids is None else int(new_ids.shape[0])
+        B.kLPM_queue_advance(self.queues[self.cur], self.queues[1 - self.cur], self.all_q, s.match_len, s.batch_idx,
+                             s.n_selected, batch, new_ids, n_new, self.sim_clock, self.ttft,
+                             self.matched if matched is None else matched,
+                             self.scratch, self.scratch_bytes, self.dev_error)
+        self.cur = 1 - self.cur
+        self.n_host = min(self.cap, self.n_host - min(batch, self.n_host) + n_new)
 
     def step(self, k: int, batch: int, new_ids: Optional[torch.Tensor]) -> None:
-        """One scheduling step: gather the queue view, match, select, commit, then retire the
-        batch and enqueue ``new_ids``.  The queue length evolves deterministically (admitted =
-        min(batch, waiting)), so the host tracks it without reading anything back."""
+        """One scheduling step: match, select, commit, then retire the batch and enqueue ``new_ids``."""
         s = self.s
-        n = self.n_host
-        B.kLPM_queue_gather(self.wait_id, self.n_wait, n, self.all_q.off, self.all_q.len, self.all_q.n,
-                            self.off_w, self.len_w)
-        q = B.DeviceQueries(self.all_q.tokens, self.off_w, self.len_w, self.wait_arr, n)
+        q = self.view()
         s.match(q)
-        s.select(q, k, batch)
+        s.select(q, k, batch, fifo=True)  # this queue is append-only with stable removal
         s.commit(q, batch)
-        n_new = 0 if new_ids is None else int(new_ids.shape[0])
-        B.kLPM_queue_advance(self.wait_id, self.wait_arr, self.n_wait, self.cap, s.match_len, self.all_q.len,
-                             self.all_q.n, s.batch_idx, s.n_selected, batch, new_ids, n_new, self.sim_clock,
-                             self.ttft, self.scratch, self.scratch_bytes, self.dev_error)
-        self.n_host = min(self.cap, n - min(batch, n) + n_new)
+        self.advance(batch, new_ids)

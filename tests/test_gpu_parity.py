@@ -47,13 +47,13 @@ def _same_tree(s, ref, big=False):
         assert a == b
 
 
-def _check_step(s, ref, q, hq, k, batch, phase, budget, big=False):
+def _check_step(s, ref, q, hq, k, batch, phase, budget, big=False, fifo=False):
     """One match -> select -> commit step on both sides, compared at every stage."""
     s.set_phase(phase)
     m = s.match(q).cpu().numpy()
     m_ref = ref.match(hq.tokens, hq.off, hq.len)
     assert (m == m_ref).all()
-    s.select(q, k, batch)
+    s.select(q, k, batch, fifo=fifo)
     idx_ref, ph_ref = oracle.select(hq.arrival, m_ref, k, batch, phase)
     assert s.batch().tolist() == idx_ref.tolist()
     assert s.phase_value() == ph_ref
@@ -107,11 +107,12 @@ def test_select_sweep_on_config0():
     for k in (1, 2, 3, 4, 8, 31, 32, 33, 1000, 0, K_INF):
         for batch in (1, 2, 31, 32, 64):
             for phase in (0, 1, 7):
-                s.set_phase(phase)
-                s.select(q, k, batch)
                 idx_ref, ph_ref = oracle.select(w.queries.arrival, m_ref, k, batch, phase)
-                assert s.batch().tolist() == idx_ref.tolist(), (k, batch, phase)
-                assert s.phase_value() == ph_ref
+                for fifo in (False, True):  # config 0's queue is in arrival order
+                    s.set_phase(phase)
+                    s.select(q, k, batch, fifo=fifo)
+                    assert s.batch().tolist() == idx_ref.tolist(), (k, batch, phase, fifo)
+                    assert s.phase_value() == ph_ref
 
 
 def test_select_ties_and_unsorted_arrivals():
@@ -136,6 +137,40 @@ def test_select_ties_and_unsorted_arrivals():
                 assert int(nsel.item()) == idx_ref.shape[0]
                 assert out.cpu().numpy().tolist() == idx_ref.tolist(), (n, k, batch)
                 assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
+
+
+def test_select_arrival_ordered_queue_single_kernel():
+    """The single-kernel path for a queue kept in arrival order, against the oracle; a queue that
+    breaks the promise is refused (-1) instead of being mis-scheduled."""
+    rng = np.random.default_rng(11)
+    for n, mmax in ((1, 3), (64, 1), (1000, 6), (3000, 5000), (70000, 9000), (5000, 2**30)):
+        arrival = np.sort(rng.integers(0, max(2, n // 2), size=n)).astype(np.uint64)  # sorted, many ties
+        m = rng.integers(0, mmax + 1, size=n).astype(np.int32)
+        if n >= 1000:
+            m[rng.integers(0, n, size=n // 2)] = 0  # a big tie class at the bottom
+            m[rng.integers(0, n, size=n // 4)] = mmax  # and one at the top
+        d_arr = torch.from_numpy(arrival.view(np.int64)).cuda()
+        d_m = torch.from_numpy(m).cuda()
+        ws_bytes = K.kLPM_select_workspace_bytes(n)
+        ws = K.alloc_aligned(ws_bytes, "cuda:0")
+        phase = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        nsel = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        for k in (1, 2, 3, 8, 1000, 0):
+            for batch in (1, 5, min(n, 1024), min(n, 4096)):
+                out = torch.full((min(batch, n),), -1, dtype=torch.int32, device="cuda:0")
+                phase.fill_(2)
+                K.kLPM_select(d_arr, d_m, n, k, batch, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO)
+                idx_ref, ph_ref = oracle.select(arrival, m, k, batch, 2)
+                assert int(nsel.item()) == idx_ref.shape[0], (n, k, batch)
+                assert out.cpu().numpy().tolist() == idx_ref.tolist(), (n, mmax, k, batch)
+                assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
+        if n >= 64:
+            bad = arrival.copy()
+            bad[n // 2] = bad[n // 2 + 1] + 5
+            phase.fill_(1)
+            K.kLPM_select(torch.from_numpy(bad.view(np.int64)).cuda(), d_m, n, 4, 8, phase, out, nsel, ws, ws_bytes,
+                          flags=K.KLPM_SELECT_FIFO)
+            assert int(nsel.item()) == -1 and int(phase.item()) == 1
 
 
 def test_degenerate_inputs():
@@ -167,7 +202,7 @@ def test_config1_step():
     _say(f"config1: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, {w.queries.n} queries")
     s, ref, q = _setup(w, extra_prompts=w.batch)
     _same_tree(s, ref, big=True)
-    _check_step(s, ref, q, w.queries, w.k, w.batch, 0, w.budget, big=True)
+    _check_step(s, ref, q, w.queries, w.k, w.batch, 0, w.budget, big=True, fifo=True)
 
 
 def test_config2_scaled_steps():
@@ -177,7 +212,7 @@ def test_config2_scaled_steps():
     _same_tree(s, ref, big=True)
     phase = 0
     for step in range(3):  # budget = initial size: every step evicts what it inserts
-        phase = _check_step(s, ref, q, w.queries, w.k, w.batch, phase, w.budget, big=True)
+        phase = _check_step(s, ref, q, w.queries, w.k, w.batch, phase, w.budget, big=True, fifo=(step % 2 == 1))
 
 
 def test_config3_scaled_k_sweep():
