@@ -159,8 +159,8 @@ typedef struct {
 /* Fill q->off / q->len from q->id (off = -1, len = 0 for an id outside `all`). */
 int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream stream);
 
-/* Scratch size for kLPM_queue_advance with batches of up to batch_cap (<= 4096) entries. */
-int kLPM_queue_scratch_bytes(int32_t batch_cap, size_t *out_bytes);
+/* Scratch size for kLPM_queue_advance on queues of up to queue_cap entries. */
+int kLPM_queue_scratch_bytes(int32_t queue_cap, size_t *out_bytes);
 
 /*
  * Waiting-queue bookkeeping of an online run (query stream of Def. 1 served in bins, Sec. 2.1;
@@ -171,12 +171,12 @@ int kLPM_queue_scratch_bytes(int32_t batch_cap, size_t *out_bytes);
  * with the CSR view of the new queue.
  *   all         the whole stream's prompts (tokens unused; off/len indexed by global id)
  *   match_len   DEVICE [*cur->n] match lengths of the queue as scored this step
- *   batch_idx / n_selected  as written by kLPM_select (positions in `cur`), batch_cap <= 4096
+ *   batch_idx / n_selected  as written by kLPM_select (positions in `cur`)
  *   new_id      DEVICE [n_new] global ids of the arrivals joining after this step
  *   sim_clock   DEVICE [1] in/out simulated time
  *   ttft        DEVICE [all->n] out (written for admitted ids only)
  *   matched_accum DEVICE [1] or NULL: += sum of match_len over the queue (throughput accounting)
- *   scratch     DEVICE, 256-byte aligned, >= kLPM_queue_scratch_bytes(batch_cap)
+ *   scratch     DEVICE, 256-byte aligned, >= kLPM_queue_scratch_bytes(cur->cap)
  * Arrivals that do not fit next->cap are dropped and set KLPM_DEV_BATCH_OVERFLOW in *dev_error.
  */
 int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,

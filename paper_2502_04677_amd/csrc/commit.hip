@@ -546,27 +546,29 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
         }
         if (my_tok) atomicAdd(&s_tok, my_tok);
         if (my_new) atomicAdd(&s_new, my_new);
-        __syncthreads();
-        for (int32_t a0 = 0; a0 < A; a0 += 256) {
-            int32_t a = a0 + tid;
-            int32_t unused = 0;
-            if (a < A) unused = ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
-            sbuf[tid] = unused;
+        // each thread owns a contiguous run of reservations; one scan places the unused ones
+        const int32_t per = (A + 255) / 256;
+        const int32_t lo = tid * per < A ? tid * per : A;
+        const int32_t hi = lo + per < A ? lo + per : A;
+        int32_t cnt = 0;
+        for (int32_t a = lo; a < hi; ++a) cnt += ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
+        sbuf[tid] = cnt;
+        __syncthreads();  // also orders the resv_id writes before the reads below
+        for (int d = 1; d < 256; d <<= 1) {
+            int32_t v = (tid >= d) ? sbuf[tid - d] : 0;
             __syncthreads();
-            for (int d = 1; d < 256; d <<= 1) {
-                int32_t v = (tid >= d) ? sbuf[tid - d] : 0;
-                __syncthreads();
-                sbuf[tid] += v;
-                __syncthreads();
-            }
-            if (unused) {
-                int32_t dst = base + s_carry + sbuf[tid] - 1;
-                if (dst >= 0 && dst < tv.max_nodes) tv.free_stack[dst] = ws.resv_id[a];
-            }
-            __syncthreads();
-            if (tid == 255) s_carry += sbuf[255];
+            sbuf[tid] += v;
             __syncthreads();
         }
+        int32_t dst = base + sbuf[tid] - cnt;
+        for (int32_t a = lo; a < hi; ++a) {
+            if (((ws.used[a >> 1] >> (a & 1)) & 1) == 0) {
+                if (dst >= 0 && dst < tv.max_nodes) tv.free_stack[dst] = ws.resv_id[a];
+                ++dst;
+            }
+        }
+        if (tid == 255) s_carry = sbuf[255];
+        __syncthreads();
     }
     if (tid == 0) {
         if (!st->skip) {

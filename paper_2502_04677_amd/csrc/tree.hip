@@ -94,7 +94,6 @@ __global__ __launch_bounds__(256) void k_iota(int32_t *__restrict__ idx, int32_t
 // moves down by the number of retired positions before it (binary search in the sorted list), the
 // arrivals are appended, and the CSR view of the new queue is written on the way.
 constexpr int kQueueThreads = 1024;
-constexpr int kRetireMax = 4096;  // admitted entries the sorted-positions path handles
 
 struct QueueHdr {  // at the start of the scratch buffer
     int32_t nw, n_removed, kept, add;
@@ -110,6 +109,9 @@ struct QueueView {
     int32_t cap;
 };
 
+// Retire: one workgroup marks the admitted queue positions in a bitmap, sums the batch's uncached
+// tokens, advances the simulated clock, stamps the TTFT of the admitted queries and leaves, for every
+// 32-position word of the queue, the number of retired positions before it.
 __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, QueueView next, QView all,
                                                                 const int32_t *__restrict__ match_len,
                                                                 const int32_t *__restrict__ batch_idx,
@@ -117,62 +119,67 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
                                                                 int32_t batch_cap, int32_t n_new,
                                                                 uint64_t *__restrict__ sim_clock,
                                                                 int64_t *__restrict__ ttft, QueueHdr *hdr,
-                                                                int32_t *__restrict__ removed_sorted,
+                                                                uint32_t *__restrict__ bitmap,
+                                                                uint32_t *__restrict__ before,
                                                                 uint32_t *__restrict__ dev_error) {
-    __shared__ uint32_t pos[kRetireMax];
     __shared__ unsigned long long s_cost;
     __shared__ uint64_t s_clock;
-    __shared__ int32_t s_valid;
+    __shared__ int32_t sbuf[kQueueThreads];
     const int tid = threadIdx.x;
     int32_t nw = *cur.n;
     nw = nw < 0 ? 0 : (nw > cur.cap ? cur.cap : nw);
     int32_t nb = *n_selected;
     nb = nb < 0 ? 0 : (nb > batch_cap ? batch_cap : nb);
-    if (nb > kRetireMax) nb = kRetireMax;
-    if (tid == 0) { s_cost = 0; s_valid = 0; }
+    const int32_t n_words = (nw + 31) / 32;
+    if (tid == 0) s_cost = 0;
+    for (int32_t w = tid; w < n_words; w += kQueueThreads) bitmap[w] = 0u;
     __syncthreads();
     unsigned long long my_cost = 0;
     for (int32_t j = tid; j < nb; j += kQueueThreads) {
         int32_t w = batch_idx[j];
-        uint32_t p = 0xFFFFFFFFu;  // invalid positions sort to the end
         if (w >= 0 && w < nw) {
-            p = (uint32_t)w;
-            atomicAdd(&s_valid, 1);
-            int32_t id = cur.id[w];
-            int32_t len = (id >= 0 && id < all.n) ? all.len[id] : 0;
-            int32_t m = match_len[w];
-            m = m < 0 ? 0 : m;
-            if (len > m) my_cost += (unsigned long long)(len - m);  // uncached tokens (Def. 2, c_attn = 0)
+            uint32_t bit = 1u << (w & 31);
+            uint32_t old = atomicOr(&bitmap[w >> 5], bit);
+            if (!(old & bit)) {  // a position listed twice counts once
+                int32_t id = cur.id[w];
+                int32_t len = (id >= 0 && id < all.n) ? all.len[id] : 0;
+                int32_t m = match_len[w];
+                m = m < 0 ? 0 : m;
+                if (len > m) my_cost += (unsigned long long)(len - m);  // uncached tokens (Def. 2, c_attn = 0)
+            }
         }
-        pos[j] = p;
     }
     if (my_cost) atomicAdd(&s_cost, my_cost);
-    int32_t np2 = 1;
-    while (np2 < nb) np2 <<= 1;
-    for (int32_t j = nb + tid; j < np2; j += kQueueThreads) pos[j] = 0xFFFFFFFFu;
     __syncthreads();
     if (tid == 0) s_clock = *sim_clock + (s_cost > 0 ? (uint64_t)s_cost : 1ull);
-    for (int32_t size = 2; size <= np2; size <<= 1) {
-        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int32_t t = tid; t < (np2 >> 1); t += kQueueThreads) {
-                int32_t a = 2 * t - (t & (stride - 1));
-                int32_t b = a + stride;
-                bool up = ((a & size) == 0);
-                uint32_t ka = pos[a], kb = pos[b];
-                if ((ka > kb) == up) { pos[a] = kb; pos[b] = ka; }
-            }
-            __syncthreads();
-        }
-    }
+    // retired positions before each word: contiguous runs of words per thread, one scan
+    const int32_t per = (n_words + kQueueThreads - 1) / kQueueThreads;
+    const int32_t lo = tid * per < n_words ? tid * per : n_words;
+    const int32_t hi = lo + per < n_words ? lo + per : n_words;
+    int32_t cnt = 0;
+    for (int32_t w = lo; w < hi; ++w) cnt += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    sbuf[tid] = cnt;
     __syncthreads();
+    for (int d = 1; d < kQueueThreads; d <<= 1) {
+        int32_t v = (tid >= d) ? sbuf[tid - d] : 0;
+        __syncthreads();
+        sbuf[tid] += v;
+        __syncthreads();
+    }
+    int32_t run = sbuf[tid] - cnt;
+    for (int32_t w = lo; w < hi; ++w) {
+        before[w] = (uint32_t)run;
+        run += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    }
+    const int32_t nv = sbuf[kQueueThreads - 1];
     const uint64_t now = s_clock;
-    const int32_t nv = s_valid;
     // the whole batch finishes together (Sec. 2.1): TTFT = finish time - arrival
-    for (int32_t j = tid; j < nv; j += kQueueThreads) {
-        int32_t w = (int32_t)pos[j];
-        removed_sorted[j] = w;
-        int32_t id = cur.id[w];
-        if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[w]);
+    for (int32_t j = tid; j < nb; j += kQueueThreads) {
+        int32_t w = batch_idx[j];
+        if (w >= 0 && w < nw) {
+            int32_t id = cur.id[w];
+            if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[w]);
+        }
     }
     if (tid == 0) {
         int32_t kept = nw - nv;
@@ -190,31 +197,29 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
     }
 }
 
+// Compact: every surviving entry moves down by the number of retired positions before it, the
+// arrivals are appended, and the CSR view of the new queue is written on the way.
 __global__ __launch_bounds__(256) void k_queue_compact(QueueView cur, QueueView next, QView all,
                                                        const int32_t *__restrict__ match_len,
                                                        const int32_t *__restrict__ new_id, const QueueHdr *hdr,
-                                                       const int32_t *__restrict__ removed_sorted,
+                                                       const uint32_t *__restrict__ bitmap,
+                                                       const uint32_t *__restrict__ before,
                                                        int64_t *__restrict__ matched_accum) {
     __shared__ unsigned long long s_sum;
     const int tid = threadIdx.x;
     if (tid == 0) s_sum = 0;
     __syncthreads();
-    const int32_t nw = hdr->nw, nr = hdr->n_removed, kept = hdr->kept, add = hdr->add;
+    const int32_t nw = hdr->nw, kept = hdr->kept, add = hdr->add;
     const uint64_t now = hdr->now;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + tid;
     unsigned long long my = 0;
     if (i < nw) {
         int32_t m = match_len[i];
         if (m > 0) my = (unsigned long long)m;
-        // retired positions strictly below i, and whether i itself is retired
-        int32_t lo = 0, hi = nr;
-        while (lo < hi) {
-            int32_t mid = (lo + hi) >> 1;
-            if (removed_sorted[mid] < (int32_t)i) lo = mid + 1; else hi = mid;
-        }
-        bool gone = (lo < nr && removed_sorted[lo] == (int32_t)i);
-        int64_t dst = i - lo;
-        if (!gone && dst < kept) {
+        uint32_t word = bitmap[i >> 5];
+        uint32_t bit = 1u << (i & 31);
+        int64_t dst = i - (int64_t)(before[i >> 5] + (uint32_t)__popc(word & (bit - 1u)));
+        if (!(word & bit) && dst < kept) {
             int32_t id = cur.id[i];
             next.id[dst] = id;
             next.arrival[dst] = cur.arrival[i];
@@ -374,9 +379,10 @@ static QueueView make_queue_view(const kLPM_queue *q) {
     return v;
 }
 
-extern "C" int kLPM_queue_scratch_bytes(int32_t batch_cap, size_t *out_bytes) {
-    if (batch_cap < 0 || !out_bytes) return KLPM_EINVAL;
-    *out_bytes = 256 + align_up((size_t)(batch_cap > 0 ? batch_cap : 1) * 4, 256);
+extern "C" int kLPM_queue_scratch_bytes(int32_t queue_cap, size_t *out_bytes) {
+    if (queue_cap < 0 || !out_bytes) return KLPM_EINVAL;
+    size_t words = ((size_t)queue_cap + 31) / 32 + 1;
+    *out_bytes = 256 + 2 * align_up(words * 4, 256);
     return KLPM_OK;
 }
 
@@ -390,21 +396,22 @@ extern "C" int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next,
         return KLPM_EINVAL;
     if (cur->id == next->id || cur->arrival == next->arrival || cur->n == next->n) return KLPM_EINVAL;
     if ((batch_cap > 0 && (!batch_idx || !match_len)) || (n_new > 0 && !new_id)) return KLPM_EINVAL;
-    if (batch_cap > kRetireMax) return KLPM_EINVAL;
     size_t need = 0;
-    kLPM_queue_scratch_bytes(batch_cap, &need);
+    kLPM_queue_scratch_bytes(cur->cap, &need);
     if (scratch_bytes < need || ((uintptr_t)scratch & 255u)) return KLPM_EARENA;
     hipStream_t stream = (hipStream_t)stream_;
     QueueHdr *hdr = (QueueHdr *)scratch;
-    int32_t *removed = (int32_t *)((char *)scratch + 256);
+    size_t words = ((size_t)cur->cap + 31) / 32 + 1;
+    uint32_t *bitmap = (uint32_t *)((char *)scratch + 256);
+    uint32_t *before = (uint32_t *)((char *)scratch + 256 + align_up(words * 4, 256));
     QueueView c = make_queue_view(cur), n = make_queue_view(next);
     QView a = make_qview(all);
     hipLaunchKernelGGL(k_queue_retire, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
-                       n_selected, batch_cap, n_new, sim_clock, ttft, hdr, removed, dev_error);
+                       n_selected, batch_cap, n_new, sim_clock, ttft, hdr, bitmap, before, dev_error);
     int64_t work = (int64_t)cur->cap + n_new;
     if (work > 0)
         hipLaunchKernelGGL(k_queue_compact, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, c, n, a,
-                           match_len, new_id, hdr, removed, matched_accum);
+                           match_len, new_id, hdr, bitmap, before, matched_accum);
     return check_launch();
 }
 

@@ -94,7 +94,7 @@ class OnlineRun:
         self.ttft = torch.full((max(all_q.n, 1),), -1, dtype=torch.int64, device=dev)
         self.matched = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dev_error = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.scratch_bytes = B.kLPM_queue_scratch_bytes(sched.cfg.max_batch)
+        self.scratch_bytes = B.kLPM_queue_scratch_bytes(self.cap)
         self.scratch = B.alloc_aligned(self.scratch_bytes, dev)
         n0 = int(first_ids.shape[0])
         assert n0 <= self.cap
