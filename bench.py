@@ -96,6 +96,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps timed for the CPU baseline (0 = skip)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain copy kernel over this many MiB (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU; --gpus must be 1 (there is no multi-GPU path to time)",
@@ -142,6 +144,15 @@ def main() -> int:
         run.advance(batch, new_ids[s], matched=sums[s:s + 1])
         ev[s][4].record()
 
+    if args.calib_copy_mib > 0:
+        # a plain elementwise copy of known size: reads and writes calib_copy_mib MiB each
+        n_el = args.calib_copy_mib * (1 << 20) // 4
+        src = torch.ones(n_el, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for s in range(args.warmup):
         one_step(s)
     torch.cuda.synchronize()

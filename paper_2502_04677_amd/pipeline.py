@@ -13,9 +13,15 @@ from . import binding as B
 
 
 def size_config(cache_tokens: int, cache_prompts: int, budget: int, max_batch: int, max_prompt_len: int,
-                extra_prompts: int = 0) -> B.Config:
-    """A configuration with room for the given cache plus commits of ``max_batch`` prompts."""
-    live = min(int(cache_tokens), int(budget)) if budget < (1 << 60) else int(cache_tokens)
+                extra_prompts: int = 0, extra_tokens: int = 0) -> B.Config:
+    """A configuration with room for the initial cache plus commits of ``max_batch`` prompts.
+
+    The tree is built without eviction, so one pool half must hold the whole initial cache; under a
+    finite budget it later holds at most the budget plus one batch, otherwise the initial cache plus
+    ``extra_tokens`` of later insertions.
+    """
+    finite = budget < (1 << 36)  # anything larger cannot be reached and means "never evict"
+    live = max(int(cache_tokens), int(budget)) if finite else int(cache_tokens) + int(extra_tokens)
     pool = int(live * 1.05) + 2 * max_batch * max_prompt_len + 4096
     nodes = 2 * (cache_prompts + extra_prompts) + 4 * max_batch + 64
     return B.make_config(budget, pool, nodes, max_batch, max_prompt_len)

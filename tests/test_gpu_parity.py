@@ -30,7 +30,8 @@ def _setup(w, budget=None, max_batch=None, extra_prompts=0, max_len=None):
     budget = w.budget if budget is None else budget
     max_batch = max_batch or max(w.batch, 1)
     max_len = max_len or int(max(w.cache.len.max(initial=1), w.queries.len.max(initial=1)))
-    cfg = K.size_config(int(w.cache.tokens.shape[0]), w.cache.n, budget, max_batch, max_len, extra_prompts)
+    cfg = K.size_config(int(w.cache.tokens.shape[0]), w.cache.n, budget, max_batch, max_len, extra_prompts,
+                        extra_tokens=int(w.queries.tokens.shape[0]))
     cache = K.DeviceQueries.from_host(w.cache)
     q = K.DeviceQueries.from_host(w.queries)
     s = K.Scheduler(cfg, cache, max(q.n, 1))
@@ -183,7 +184,7 @@ def test_degenerate_inputs():
     s.select(q, 4, 8, n=0)
     assert s.batch().tolist() == [] and s.phase_value() == 3
     # empty tree: every match is 0; committing into it equals the oracle
-    cfg = K.size_config(0, 0, 1 << 50, 32, 1024, extra_prompts=64)
+    cfg = K.size_config(0, 0, 1 << 50, 32, 1024, extra_prompts=64, extra_tokens=int(w.queries.tokens.shape[0]))
     s2 = K.Scheduler(cfg, None, q.n)
     assert not s2.match(q).cpu().numpy().any()
     ref2 = oracle.OracleTree()
@@ -234,15 +235,46 @@ def test_config3_scaled_k_sweep():
     _check_step(s, ref, q, w.queries, 4, w.batch, 0, w.budget, big=True)
 
 
-def test_config4_scaled_online_stream():
-    stream = W.config4_stream(steps=60, rate=24, groups=2000, budget=150_000, batch=32)
-    r = oracle.simulate_stream(stream, snapshot_every=10)
+def test_config2_full_size_steps():
+    """The large configuration at full size, in the launch shapes the benchmark times."""
+    w = W.config2()
+    _say(f"config2 full: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, {w.queries.n} queries")
+    s, ref, q = _setup(w, extra_prompts=4 * w.batch, max_len=8192)
+    _say("  built both trees")
+    _same_tree(s, ref, big=True)
+    phase = 0
+    for step in range(2):
+        _say(f"  step {step}")
+        phase = _check_step(s, ref, q, w.queries, w.k, w.batch, phase, w.budget, big=True, fifo=(step == 0))
+
+
+def test_config3_full_size_k_sweep():
+    """The hierarchical configuration at full size: match once, select for every k of the sweep."""
+    w = W.config3()
+    _say(f"config3 full: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, {w.queries.n} queries")
+    s, ref, q = _setup(w)
+    _say("  built both trees")
+    _same_tree(s, ref, big=True)
+    m = s.match(q).cpu().numpy()
+    m_ref = ref.match(w.queries.tokens, w.queries.off, w.queries.len)
+    assert (m == m_ref).all()
+    for k in w.ks:
+        for fifo in (False, True):
+            s.set_phase(0)
+            s.select(q, k, w.batch, fifo=fifo)
+            idx_ref, ph_ref = oracle.select(w.queries.arrival, m_ref, k, w.batch, 0)
+            assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref, (k, fifo)
+    _check_step(s, ref, q, w.queries, 4, w.batch, 0, w.budget, big=True)
+
+
+def _run_stream(stream, cap, snapshot_every, check_every_step=True):
+    r = oracle.simulate_stream(stream, snapshot_every=snapshot_every)
     hq = stream.queries
     q = K.DeviceQueries.from_host(hq)
     cfg = K.size_config(0, 0, stream.budget, stream.batch, int(hq.len.max()), extra_prompts=hq.n)
-    s = K.Scheduler(cfg, None, 4096)
+    s = K.Scheduler(cfg, None, cap)
     first = np.arange(int(stream.step_start[0]), int(stream.step_start[1]))
-    run = K.OnlineRun(s, q, 4096, first)
+    run = K.OnlineRun(s, q, cap, first)
     for step in range(stream.steps):
         nxt = None
         if step + 1 < stream.steps:
@@ -250,17 +282,44 @@ def test_config4_scaled_online_stream():
             nxt = torch.from_numpy(ids).cuda()
         n_before = run.n_host
         run.step(stream.k, stream.batch, nxt)
-        torch.cuda.synchronize()
-        assert s.match_len[:n_before].cpu().numpy().tolist() == r.match_lens[step].tolist(), step
-        got_batch = s.batch()
-        assert r.waiting_ids[step][got_batch].tolist() == r.batches[step].tolist(), step
-        st = s.read_stats()
-        want = r.stats[step]
-        assert st.device_error == 0
-        assert (st.total_tokens, st.evicted_tokens, st.n_nodes, st.clock) == (
-            want.total_tokens, want.evicted_tokens, want.n_nodes, want.clock), step
+        if check_every_step or r.snapshots[step] is not None:
+            torch.cuda.synchronize()
+            assert s.match_len[:n_before].cpu().numpy().tolist() == r.match_lens[step].tolist(), step
+            got_batch = s.batch()
+            assert r.waiting_ids[step][got_batch].tolist() == r.batches[step].tolist(), step
+            st = s.read_stats()
+            want = r.stats[step]
+            assert st.device_error == 0
+            assert (st.total_tokens, st.evicted_tokens, st.n_nodes, st.clock) == (
+                want.total_tokens, want.evicted_tokens, want.n_nodes, want.clock), step
         if r.snapshots[step] is not None:
+            _say(f"  stream step {step}: snapshot compare")
             assert s.snapshot() == r.snapshots[step], step
     assert int(run.sim_clock.item()) == r.clock
-    assert run.ttft.cpu().numpy().tolist() == r.ttft.tolist()
+    ttft = run.ttft.cpu().numpy()
+    assert ttft.tolist() == r.ttft.tolist()
     assert int(run.dev_error.item()) == 0
+    done = ttft[ttft >= 0]
+    assert oracle.percentile_nearest_rank(done, 0.5) == oracle.percentile_nearest_rank(r.ttft[r.ttft >= 0], 0.5)
+    assert oracle.percentile_nearest_rank(done, 0.99) == oracle.percentile_nearest_rank(r.ttft[r.ttft >= 0], 0.99)
+    return r
+
+
+def test_config4_scaled_online_stream():
+    stream = W.config4_stream(steps=60, rate=24, groups=2000, budget=150_000, batch=32)
+    _run_stream(stream, 4096, snapshot_every=10)
+
+
+def test_config4_overloaded_stream_keeps_a_backlog():
+    """More arrivals than the batch admits: the queue backs up, k matters, phases carry over."""
+    stream = W.config4_stream(steps=40, rate=40, groups=300, budget=120_000, batch=24)
+    stream.k = 3
+    r = _run_stream(stream, 4096, snapshot_every=8)
+    assert max(len(w) for w in r.waiting_ids) > 10 * stream.batch
+
+
+def test_config4_full_size_online_stream():
+    """1,000 steps, Poisson(128) arrivals per step, 4M-token budget; every step compared."""
+    stream = W.config4_stream()
+    _say(f"config4 full: {stream.queries.n} queries / {stream.queries.tokens.shape[0]} tokens over {stream.steps} steps")
+    _run_stream(stream, 8192, snapshot_every=100)
