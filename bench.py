@@ -39,6 +39,24 @@ def algorithmic_bytes(sum_match: int, n_queries: int) -> int:
     return 8 * (sum_match + n_queries) + 16 * n_queries
 
 
+def recorded_traffic():
+    """HBM bytes per match launch from the committed rocprofv3 counter summary, or None when the
+    kernel sources have changed since those counters were taken (or the summary is missing)."""
+    import hashlib
+
+    path = os.path.join(ROOT, "profiles", "k_match_cfg2-large_hbm_counters.txt")
+    try:
+        fields = dict(line.strip().split("=", 1) for line in open(path) if "=" in line and not line.startswith(" "))
+        h = hashlib.sha256()
+        for rel in ("paper_2502_04677_amd/csrc/match.hip", "paper_2502_04677_amd/csrc/klpm_device.hpp"):
+            h.update(open(os.path.join(ROOT, rel), "rb").read())
+        if fields.get("kernel_source_sha256") != h.hexdigest():
+            return None
+        return float(fields["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def build_workload(scale: float, steps_total: int):
     import workloads as W
 
@@ -198,7 +216,8 @@ def main() -> int:
         "match_tokens_per_s_kernel": float(np.mean(sums_h[args.warmup:])) / match_s,
         "matched_tokens_per_step": float(np.mean(sums_h[args.warmup:])),
         "roofline": {"kernel": "k_match", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": recorded_traffic() if args.scale == 1.0 and args.steps == 20 and args.warmup == 3 else None,
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": float(match_ms.mean())},
     }
 
