@@ -197,6 +197,97 @@ def test_degenerate_inputs():
     assert m[5] == -1 and (K.kLPM_read_stats(s.tree).device_error & 4)
 
 
+def test_pool_compaction_keeps_the_tree_intact():
+    """A pool barely larger than budget + one batch: the bump allocator fills a half every few
+    commits, so live spans are compacted into the other half again and again."""
+    w = W.config0()
+    hq = w.queries
+    budget = 9000
+    max_len = int(max(w.cache.len.max(), hq.len.max()))
+    batch = 16
+    cache_tokens = int(w.cache.tokens.shape[0])
+    cfg = K.make_config(budget, cache_tokens + batch * max_len + 64, 2 * (w.cache.n + hq.n) + 4 * batch + 64, batch, max_len)
+    s = K.Scheduler(cfg, K.DeviceQueries.from_host(w.cache), hq.n)
+    ref = oracle.OracleTree()
+    ref.build(w.cache)
+    q = K.DeviceQueries.from_host(hq)
+    _same_tree(s, ref)
+    rng = np.random.default_rng(3)
+    phase = 0
+    for step in range(40):
+        k = int(rng.choice([1, 2, 4, K_INF]))
+        phase = _check_step(s, ref, q, hq, k, batch, phase, budget)
+
+
+def test_commit_refusals_leave_the_tree_as_it_was():
+    w = W.config0()
+    hq = w.queries
+    max_len = int(max(w.cache.len.max(), hq.len.max()))
+    q = K.DeviceQueries.from_host(hq)
+    cache = K.DeviceQueries.from_host(w.cache)
+    ref = oracle.OracleTree()
+    ref.build(w.cache)
+    m_ref = ref.match(hq.tokens, hq.off, hq.len)
+
+    def fresh(cfg):
+        s = K.Scheduler(cfg, cache, hq.n)
+        _same_tree(s, ref)
+        s.match(q)
+        s.select(q, 2, 32)
+        return s
+
+    big_pool = int(w.cache.tokens.shape[0]) + 64 * max_len
+    # not enough free node ids for two per admitted prompt
+    s = fresh(K.make_config(1 << 40, big_pool, ref.n_nodes + 1 + 40, 32, max_len))
+    s.commit(q, 32)
+    st = s.read_stats()
+    assert st.device_error & 1 and st.inserted_tokens == 0 and st.clock == w.cache.n
+    _same_tree(s, ref)
+    # the pool runs out: commits of fresh slices of the queue succeed until one batch's tails no
+    # longer fit even after compaction; that commit is refused and changes nothing
+    s = fresh(K.make_config(1 << 40, ref.total_tokens + 13000, 4096, 32, max_len))
+    ref_p = oracle.OracleTree()
+    ref_p.build(w.cache)
+    refused = False
+    for i in range(hq.n // 32):
+        idx = np.arange(32 * i, 32 * i + 32, dtype=np.int32)
+        s.batch_idx[:32] = torch.from_numpy(idx).cuda()
+        s.n_selected.fill_(32)
+        before = ref_p.snapshot()
+        s.commit(q, 32)
+        st = s.read_stats()
+        if st.device_error & 2:
+            assert s.snapshot() == before and st.inserted_tokens == 0
+            refused = True
+            break
+        ref_p.commit(hq.tokens, hq.off, hq.len, idx, 1 << 60)
+        assert s.snapshot() == ref_p.snapshot()
+    assert refused
+    assert (s.match(q).cpu().numpy() == ref_p.match(hq.tokens, hq.off, hq.len)).all()
+    # more selected entries than the capacity passed to commit
+    s = fresh(K.make_config(1 << 40, big_pool, 4096, 32, max_len))
+    s.commit(q, 8)
+    st = s.read_stats()
+    assert st.device_error & 8 and st.inserted_tokens == 0
+    _same_tree(s, ref)
+    # an admitted prompt whose span lies outside the token buffer
+    s = fresh(K.make_config(1 << 40, big_pool, 4096, 32, max_len))
+    first = int(s.batch()[0])
+    bad = K.DeviceQueries(q.tokens, q.off.clone(), q.len.clone(), q.arrival, q.n)
+    bad.off[first] = q.tokens.numel() - 2
+    s.commit(bad, 32)
+    st = s.read_stats()
+    assert st.device_error & 4 and st.inserted_tokens == 0
+    _same_tree(s, ref)
+    # after a refusal the same tree still commits normally
+    s.commit(q, 32)
+    idx_ref, _ = oracle.select(hq.arrival, m_ref, 2, 32, 0)
+    ref2 = oracle.OracleTree()
+    ref2.build(w.cache)
+    ref2.commit(hq.tokens, hq.off, hq.len, idx_ref, 1 << 60)
+    assert s.snapshot() == ref2.snapshot()
+
+
 # ----------------------------------------------------------------------------- the configurations
 def test_config1_step():
     w = W.config1()
