@@ -57,13 +57,14 @@ def recorded_traffic():
         return None
 
 
-def build_workload(scale: float, steps_total: int):
+def build_workload(scale: float, steps_total: int, deep: bool = False):
     import workloads as W
 
     t0 = time.time()
-    base = W.config2(scale=scale, extra_queries=0)
-    batch = base.batch
-    w = W.config2(scale=scale, extra_queries=steps_total * batch)
+    gen = W.config2_deep if deep else W.config2
+    batch = max(4, int(round(1024 * scale)))
+    w = gen(scale=scale, extra_queries=steps_total * batch)
+    assert w.batch == batch
     log(f"generated {w.name} scale={scale}: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, "
         f"queue {w.queries.n}, later arrivals {w.extra.n} in {time.time() - t0:.1f}s")
     allq = W.Prompts(w.queries.tokens, np.concatenate([w.queries.off, w.extra.off]),
@@ -114,6 +115,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps timed for the CPU baseline (0 = skip)")
+    ap.add_argument("--deep", action="store_true",
+                    help="deep-tree variant of the workload (about 50-90 tokens per tree node)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel over this many MiB (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -129,7 +132,7 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     steps_total = args.steps + args.warmup
-    w, allq = build_workload(args.scale, steps_total)
+    w, allq = build_workload(args.scale, steps_total, args.deep)
     batch, k, n0 = w.batch, w.k, w.queries.n
     max_len = int(max(w.cache.len.max(), allq.len.max()))
 
@@ -217,7 +220,8 @@ def main() -> int:
         "matched_tokens_per_step": float(np.mean(sums_h[args.warmup:])),
         "roofline": {"kernel": "k_match", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": recorded_traffic() if args.scale == 1.0 and args.steps == 20 and args.warmup == 3 else None,
+                     "traffic": (recorded_traffic()
+                                 if args.scale == 1.0 and args.steps == 20 and args.warmup == 3 and not args.deep else None),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": float(match_ms.mean())},
     }
 

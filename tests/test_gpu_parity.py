@@ -307,6 +307,19 @@ def test_config2_scaled_steps():
         phase = _check_step(s, ref, q, w.queries, w.k, w.batch, phase, w.budget, big=True, fifo=(step % 2 == 1))
 
 
+def test_config2_deep_tree_variant():
+    """Same token recipe as the large step but about one node per 50-90 tokens: long chains of
+    child-table probes, many short edges, many prompts that add no token at all."""
+    w = W.config2_deep(scale=1 / 16)
+    _say(f"config2-deep/16: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, {w.queries.n} queries")
+    s, ref, q = _setup(w, extra_prompts=4 * w.batch)
+    _say(f"  oracle tree: {ref.total_tokens} tokens, {ref.n_nodes} nodes")
+    _same_tree(s, ref, big=True)
+    phase = 0
+    for step in range(3):
+        phase = _check_step(s, ref, q, w.queries, w.k, w.batch, phase, w.budget, big=True, fifo=(step % 2 == 0))
+
+
 def test_config3_scaled_k_sweep():
     w = W.config3(scale=1 / 16)
     _say(f"config3/16: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, {w.queries.n} queries")

@@ -331,7 +331,7 @@ def config2(seed: int = SEED_BASE + 2, scale: float = 1.0, extra_queries: int = 
     return Workload("cfg2-large", cache, queries, k=8, batch=batch, budget=target, extra=extra)
 
 
-def config2_deep(seed: int = SEED_BASE + 12, scale: float = 1.0) -> Workload:
+def config2_deep(seed: int = SEED_BASE + 12, scale: float = 1.0, extra_queries: int = 0) -> Workload:
     """Deep-tree variant of the large step: same token target, about 50 tokens per node.
 
     Suffixes are short walks over a per-group pool of 32-64-token segments, so
@@ -391,11 +391,14 @@ def config2_deep(seed: int = SEED_BASE + 12, scale: float = 1.0) -> Workload:
 
     cache = assemble(plist)
     rq = _rng(seed, 2)
-    qg = _zipf_draw(rq, cdf, n)
-    qdepth = rq.integers(1, 7, size=n)
-    qpicks = rq.integers(0, pool_segments, size=(n, 6))
-    queries = assemble([(int(qg[i]), tuple(int(v) for v in qpicks[i, : int(qdepth[i])])) for i in range(n)])
-    return Workload("cfg2-deep", cache, queries, k=8, batch=batch, budget=target)
+    nq = n + int(extra_queries)
+    qg = _zipf_draw(rq, cdf, nq)
+    qdepth = rq.integers(1, 7, size=nq)
+    qpicks = rq.integers(0, pool_segments, size=(nq, 6))
+    allq = assemble([(int(qg[i]), tuple(int(v) for v in qpicks[i, : int(qdepth[i])])) for i in range(nq)])
+    queries = take_prompts(allq, np.arange(n))
+    extra = take_prompts(allq, np.arange(n, nq)) if extra_queries else None
+    return Workload("cfg2-deep", cache, queries, k=8, batch=batch, budget=target, extra=extra)
 
 
 def config3(seed: int = SEED_BASE + 3, scale: float = 1.0) -> Workload:
