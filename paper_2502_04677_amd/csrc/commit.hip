@@ -188,6 +188,7 @@ __global__ __launch_bounds__(256) void k_hash_clear(TreeView tv) {
 }
 
 __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict__ out) {
+    if (st->need_rebuild) st->tombstones = 0;  // the table has just been rebuilt
     st->need_rebuild = 0;
     if (!out) return;
     out->total_tokens = st->total_tokens;
@@ -301,14 +302,21 @@ __device__ __forceinline__ int32_t slot_find_live(const TreeView &tv, uint64_t k
     return -1;
 }
 
-// lane 0 only
+// lane 0 only. Takes the first free slot of the probe sequence, empty or left by an evicted node.
+// The caller has just looked the key up and not found it.
 __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key, int32_t child, int32_t edge_len,
                                                int64_t edge_off) {
     uint32_t h = hash_key(key) & tv.slot_mask;
     for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
-        unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key, (unsigned long long)kEmptyKey,
-                                            (unsigned long long)key);
-        if (prev == (unsigned long long)kEmptyKey) {
+        unsigned long long *kp = (unsigned long long *)&tv.slots[h].key;
+        unsigned long long prev = atomicCAS(kp, (unsigned long long)kEmptyKey, (unsigned long long)key);
+        bool mine = (prev == (unsigned long long)kEmptyKey);
+        if (!mine && prev == (unsigned long long)kTombKey) {
+            // (the tombstone counter is not decremented: it counts evictions since the last rebuild,
+            // an upper bound that needs no shared atomic here)
+            mine = (atomicCAS(kp, (unsigned long long)kTombKey, (unsigned long long)key) == (unsigned long long)kTombKey);
+        }
+        if (mine) {
             tv.slots[h].child = child;
             tv.slots[h].edge_len = edge_len;
             tv.slots[h].edge_off = edge_off;
@@ -668,6 +676,18 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
         if (len <= 0) continue;
         if (evict_key(tv, id, depth_bits) <= cut) {
             tv.edge_len[id] = 0;
+            // leave a tombstone where the parent pointed at this node
+            const uint64_t key = make_key(tv.parent[id], tv.pool[tv.edge_off[id]]);
+            uint32_t h = hash_key(key) & tv.slot_mask;
+            for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+                uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (kk == key) {
+                    __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                if (kk == kEmptyKey) { flag_error(st, 4u); break; }
+                h = (h + 1) & tv.slot_mask;
+            }
             int32_t pos = atomicAdd(&st->free_cnt, 1);
             if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
             atomicAdd(&s_tok, (unsigned long long)len);
@@ -685,7 +705,9 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
         int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         st->total_tokens -= ev_tok;
         st->n_nodes -= ev_cnt;
-        if (ev_cnt > 0) st->need_rebuild = 1;
+        st->tombstones += ev_cnt;
+        // rebuild the child table only when tombstones start to lengthen the probe sequences
+        if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1) st->need_rebuild = 1;
     }
 }
 

@@ -15,6 +15,9 @@ namespace klpm {
 constexpr int kWave = 64;
 constexpr int32_t kRoot = 0;
 constexpr uint64_t kEmptyKey = ~0ull;
+// A slot whose node was evicted: probes walk past it, inserts may take it over. (No real key has
+// parent id -1.)
+constexpr uint64_t kTombKey = ~0ull - 1ull;
 
 // Child-table slot. key = (parent id << 32) | first edge token.
 struct __attribute__((aligned(32))) Slot {
@@ -56,6 +59,8 @@ struct DevState {
     int32_t new_nodes;
     int32_t evicted_nodes;
     int32_t done[12];      // workgroups finished, per fused kernel of the commit (4.. = eviction passes)
+    int32_t tombstones;    // nodes evicted since the last child-table rebuild (upper bound of the tombstones)
+    int32_t pad1;
     uint64_t evict_prefix; // digits of the eviction cut key fixed so far
     int64_t evict_rem;     // tokens still to free among the keys that share that prefix
 };
