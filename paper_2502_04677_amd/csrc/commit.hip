@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
                                                               const int32_t *__restrict__ batch_idx,
                                                               const int32_t *__restrict__ n_selected,
                                                               int32_t batch_cap, CommitWs ws) {
-    __shared__ int64_t buf[kPlanThreads];
+    __shared__ int64_t buf[kPlanThreads / kWave];
     __shared__ int64_t carry;
     __shared__ int bad;
     __shared__ int32_t s_nb;
@@ -109,17 +109,11 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
                 ws.end_node[j] = e;
             }
         }
-        buf[tid] = tl;
+        int64_t chunk_total;
+        int64_t incl = block_inclusive_scan<int64_t, kPlanThreads>(tl, buf, tid, chunk_total);
+        if (j < nb) ws.tail_off[j] = carry + incl - tl;
         __syncthreads();
-        for (int d = 1; d < kPlanThreads; d <<= 1) {
-            int64_t v = (tid >= d) ? buf[tid - d] : 0;
-            __syncthreads();
-            buf[tid] += v;
-            __syncthreads();
-        }
-        if (j < nb) ws.tail_off[j] = carry + buf[tid] - tl;
-        __syncthreads();
-        if (tid == kPlanThreads - 1) carry += buf[tid];
+        if (tid == 0) carry += chunk_total;
         __syncthreads();
     }
     if (tid == 0 && nb > 0) {
@@ -529,7 +523,7 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
     }
     // the last workgroup publishes the inserts and decides whether anything must be evicted
     __shared__ int evict;
-    __shared__ int32_t sbuf[256];
+    __shared__ int32_t sbuf[256 / kWave];
     __shared__ int32_t s_carry;
     __shared__ unsigned long long s_tok;
     __shared__ int32_t s_new;
@@ -560,22 +554,17 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
         const int32_t hi = lo + per < A ? lo + per : A;
         int32_t cnt = 0;
         for (int32_t a = lo; a < hi; ++a) cnt += ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
-        sbuf[tid] = cnt;
-        __syncthreads();  // also orders the resv_id writes before the reads below
-        for (int d = 1; d < 256; d <<= 1) {
-            int32_t v = (tid >= d) ? sbuf[tid - d] : 0;
-            __syncthreads();
-            sbuf[tid] += v;
-            __syncthreads();
-        }
-        int32_t dst = base + sbuf[tid] - cnt;
+        __syncthreads();  // orders the resv_id writes before the reads below
+        int32_t unused_total;
+        int32_t incl = block_inclusive_scan<int32_t, 256>(cnt, sbuf, tid, unused_total);
+        int32_t dst = base + incl - cnt;
         for (int32_t a = lo; a < hi; ++a) {
             if (((ws.used[a >> 1] >> (a & 1)) & 1) == 0) {
                 if (dst >= 0 && dst < tv.max_nodes) tv.free_stack[dst] = ws.resv_id[a];
                 ++dst;
             }
         }
-        if (tid == 255) s_carry = sbuf[255];
+        if (tid == 255) s_carry = unused_total;
         __syncthreads();
     }
     if (tid == 0) {
@@ -616,20 +605,16 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
 // histogram of the current digit is complete: pick the smallest digit whose inclusive weight
 // reaches what is still to be freed, append it to the prefix and reduce the remainder.
 __device__ void evict_descend_step(DevState *st, const int64_t *__restrict__ hist) {
+    __shared__ int64_t part[256 / kWave];
     __shared__ int64_t sc[256];
     __shared__ int pick;
     const int tid = threadIdx.x;
     const int64_t rem = st->evict_rem;
-    sc[tid] = hist[tid];
     if (tid == 0) pick = 255;
-    __syncthreads();
-    for (int d = 1; d < 256; d <<= 1) {
-        int64_t v = (tid >= d) ? sc[tid - d] : 0;
-        __syncthreads();
-        sc[tid] += v;
-        __syncthreads();
-    }
-    if (sc[tid] >= rem) atomicMin(&pick, tid);
+    int64_t all;
+    int64_t incl = block_inclusive_scan<int64_t, 256>(hist[tid], part, tid, all);
+    sc[tid] = incl;
+    if (incl >= rem) atomicMin(&pick, tid);
     __syncthreads();
     if (tid == 0) {
         int dg = pick;

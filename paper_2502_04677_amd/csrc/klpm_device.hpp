@@ -205,6 +205,38 @@ __device__ __forceinline__ int32_t wave_common_prefix(const int32_t *__restrict_
     return lim;
 }
 
+// Inclusive scan across the 64 lanes of a wavefront (no barrier, no LDS).
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        T t = __shfl_up(v, d);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// Inclusive scan across a workgroup of THREADS threads with two barriers: lanes scan inside their
+// wavefront, the wavefront totals go through `part` (THREADS/64 elements of shared memory).
+// `total` receives the sum over the whole workgroup. Every thread must call it.
+template <typename T, int THREADS>
+__device__ __forceinline__ T block_inclusive_scan(T v, T *part, int tid, T &total) {
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+    T incl = wave_inclusive_scan(v, lane);
+    __syncthreads();  // `part` may still be read from an earlier call
+    if (lane == kWave - 1) part[wv] = incl;
+    __syncthreads();
+    T before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < THREADS / kWave; ++w) {
+        T p = part[w];
+        all += p;
+        if (w < wv) before += p;
+    }
+    total = all;
+    return incl + before;
+}
+
 // How many prompts a commit admits (0 if it must be abandoned, with the reason in *err).
 __device__ __forceinline__ int32_t commit_gate(const TreeView &tv, const int32_t *n_selected, int32_t batch_cap,
                                                uint32_t *err) {

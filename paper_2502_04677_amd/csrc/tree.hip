@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
                                                                 uint32_t *__restrict__ dev_error) {
     __shared__ unsigned long long s_cost;
     __shared__ uint64_t s_clock;
-    __shared__ int32_t sbuf[kQueueThreads];
+    __shared__ int32_t sbuf[kQueueThreads / kWave];
     const int tid = threadIdx.x;
     int32_t nw = *cur.n;
     nw = nw < 0 ? 0 : (nw > cur.cap ? cur.cap : nw);
@@ -158,20 +158,12 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
     const int32_t hi = lo + per < n_words ? lo + per : n_words;
     int32_t cnt = 0;
     for (int32_t w = lo; w < hi; ++w) cnt += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    sbuf[tid] = cnt;
-    __syncthreads();
-    for (int d = 1; d < kQueueThreads; d <<= 1) {
-        int32_t v = (tid >= d) ? sbuf[tid - d] : 0;
-        __syncthreads();
-        sbuf[tid] += v;
-        __syncthreads();
-    }
-    int32_t run = sbuf[tid] - cnt;
+    int32_t nv;
+    int32_t run = block_inclusive_scan<int32_t, kQueueThreads>(cnt, sbuf, tid, nv) - cnt;
     for (int32_t w = lo; w < hi; ++w) {
         before[w] = (uint32_t)run;
         run += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     }
-    const int32_t nv = sbuf[kQueueThreads - 1];
     const uint64_t now = s_clock;
     // the whole batch finishes together (Sec. 2.1): TTFT = finish time - arrival
     for (int32_t j = tid; j < nb; j += kQueueThreads) {
