@@ -116,6 +116,9 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * k = 1 is FCFS; k = 0 or KLPM_K_INFINITY is pure LPM order (Sec. 4).
  *   arrival, match_len  DEVICE [n] in (a negative match_len counts as 0)
  *   flags               0 or KLPM_SELECT_FIFO
+ *   max_match           with KLPM_SELECT_FIFO: an upper bound of the match_len values (the longest
+ *                       prompt accepted will do); 0 = unknown.  A smaller bound means fewer passes; a
+ *                       match_len above it is reported like a broken arrival order (*n_selected = -1)
  *   phase_inout         DEVICE [1]: position in the k-cycle, carried from step to step
  *                       (write 0 before the call to restart the cycle every step)
  *   batch_idx           DEVICE [min(batch, n)] out: queue indices in pick order
@@ -124,8 +127,8 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
  */
 int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                uint32_t flags, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace,
-                size_t workspace_bytes, kLPM_stream stream);
+                uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+                void *workspace, size_t workspace_bytes, kLPM_stream stream);
 
 /*
  * Commit a batch: for each admitted prompt, in pick order, give it the next tick of the logical

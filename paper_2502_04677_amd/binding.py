@@ -64,7 +64,7 @@ def load_library() -> C.CDLL:
     lib.kLPM_build_tree.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, sz, C.POINTER(Queries), vp]
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select.argtypes = [vp, vp, i32, u32, i32, u32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select.argtypes = [vp, vp, i32, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
     lib.kLPM_set_budget.argtypes = [vp, i64]
     lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
@@ -201,9 +201,10 @@ def alloc_aligned(nbytes: int, device) -> Tuple[torch.Tensor, int]:
 
 def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, batch: int,
                 phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
-                workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None, flags: int = 0) -> None:
+                workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None, flags: int = 0,
+                max_match: int = 0) -> None:
     _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), int(n), C.c_uint32(k & 0xFFFFFFFF), int(batch),
-                            C.c_uint32(flags), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
+                            C.c_uint32(flags), int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
 
 

@@ -557,6 +557,327 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
     two_cursor_walk(acc, nb, nb, k, phase, batch_idx, tid);
 }
 
+// ---- the same selection for long arrival-ordered queues: short multi-workgroup kernels ----
+// One compute unit sweeping a 65,536-entry queue is bound by its own LDS-atomic and load rates, so
+// long queues are histogrammed, counted and gathered by many workgroups (1,024 entries each) and only
+// the final sort + walk over the nb winners runs in one workgroup.
+constexpr int kFqThreads = 256;
+constexpr int kFqTile = 1024;       // queue entries per workgroup
+constexpr int kFqLevelBits = 13;    // bits of match length resolved per histogram kernel
+constexpr int kFqBins = 1 << kFqLevelBits;
+constexpr int kFqMaxLevels = 3;     // 31 bits at most
+constexpr int kFqSingleBlockN = 8192;  // shorter queues are cheaper in the single-workgroup kernel
+
+struct FqMeta {        // zeroed before every call
+    int32_t violated;  // arrival order broken, or a match length above the caller's bound
+    int32_t fixed_hi;  // decided high bits of the nb-th largest match length
+    int32_t need;      // winners still to be found among the entries that share fixed_hi
+    int32_t done[kFqMaxLevels + 1];  // finished workgroups per kernel
+    int32_t pad;
+};
+
+struct FqWs {
+    FqMeta *meta;
+    uint32_t *hist;      // [kFqMaxLevels][kFqBins]
+    int32_t *blockcnt;   // [n_blocks][2]: entries above m*, entries equal to m*
+    uint64_t *cand;      // [kFifoMaxBatch] winners as (inverted match length, index)
+};
+
+__device__ __forceinline__ bool fq_last_block(int32_t *counter) {
+    __shared__ int s_last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        s_last = (atomicAdd(counter, 1) == (int)gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (s_last) __threadfence();
+    return s_last != 0;
+}
+
+// Histogram of one 13-bit digit of the match lengths that share the digits fixed so far; level 0 also
+// checks the arrival order.  The last workgroup to finish fixes the digit of the nb-th largest length.
+__global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restrict__ arrival,
+                                                       const int32_t *__restrict__ match_len, int32_t n, int32_t nb,
+                                                       int32_t max_match, int level, int shift, int width,
+                                                       FqWs ws) {
+    __shared__ uint32_t h[kFqBins];
+    __shared__ int32_t part[kFqThreads / kWave];
+    __shared__ int32_t s_viol, s_pick, s_above;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    for (int i = tid; i < (1 << width); i += kFqThreads) h[i] = 0;
+    if (tid == 0) s_viol = 0;
+    __syncthreads();
+    const int32_t fixed_hi = (level == 0) ? 0 : ws.meta->fixed_hi;
+    const int32_t base = blockIdx.x * kFqTile;
+    bool viol = false;
+#pragma unroll
+    for (int r = 0; r < kFqTile / kFqThreads; ++r) {
+        int32_t i = base + r * kFqThreads + tid;
+        bool in = i < n;
+        int32_t m = in ? match_len[i] : 0;
+        m = m < 0 ? 0 : m;
+        if (level == 0 && in) {
+            viol |= m > max_match;
+            viol |= (i + 1 < n) && (arrival[i] > arrival[i + 1]);
+        }
+        in = in && ((m >> (shift + width)) == fixed_hi || level == 0);
+        int32_t bin = (m >> shift) & ((1 << width) - 1);
+        // lanes that share the first active lane's bin are added once (match lengths cluster and
+        // same-address LDS atomics serialise)
+        uint64_t act = __ballot(in);
+        if (act) {
+            int32_t lead = __shfl(bin, (int)__builtin_ctzll(act));
+            uint64_t same = __ballot(in && bin == lead);
+            if (in && bin == lead) {
+                if (lane == (int)__builtin_ctzll(same)) atomicAdd(&h[bin], (uint32_t)__popcll(same));
+            } else if (in) {
+                atomicAdd(&h[bin], 1u);
+            }
+        }
+    }
+    if (viol) atomicOr(&s_viol, 1);
+    __syncthreads();
+    if (tid == 0 && s_viol) atomicOr(&ws.meta->violated, 1);
+    uint32_t *gh = ws.hist + (size_t)level * kFqBins;
+    for (int i = tid; i < (1 << width); i += kFqThreads) {
+        uint32_t c = h[i];
+        if (c) atomicAdd(&gh[i], c);
+    }
+    if (!fq_last_block(&ws.meta->done[level])) return;
+    // suffix counts over the bins, top down: thread t owns a contiguous run of bins counted from the top
+    const int nbins = 1 << width;
+    const int per = (nbins + kFqThreads - 1) / kFqThreads;
+    const int32_t need = (level == 0) ? nb : ws.meta->need;
+    int32_t mine = 0;
+    for (int q = 0; q < per; ++q) {
+        int b = nbins - 1 - (tid * per + q);
+        if (b >= 0) mine += (int32_t)__hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    int32_t all;
+    int32_t before = block_inclusive_scan<int32_t, kFqThreads>(mine, part, tid, all) - mine;  // entries in higher bins
+    int32_t run = before;
+    for (int q = 0; q < per; ++q) {
+        int b = nbins - 1 - (tid * per + q);
+        if (b < 0) break;
+        int32_t c = (int32_t)__hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (run < need && run + c >= need) { s_pick = b; s_above = run; }
+        run += c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ws.meta->fixed_hi = (fixed_hi << width) | s_pick;
+        ws.meta->need = need - s_above;
+    }
+}
+
+// Per workgroup: how many of its entries lie above m* and how many equal it.
+__global__ __launch_bounds__(kFqThreads) void k_fq_count(const int32_t *__restrict__ match_len, int32_t n, FqWs ws) {
+    __shared__ int32_t s_gt, s_eq;
+    const int tid = threadIdx.x;
+    if (tid == 0) { s_gt = 0; s_eq = 0; }
+    __syncthreads();
+    const int32_t m_star = ws.meta->fixed_hi;
+    const int32_t base = blockIdx.x * kFqTile;
+    int32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int r = 0; r < kFqTile / kFqThreads; ++r) {
+        int32_t i = base + r * kFqThreads + tid;
+        int32_t m = (i < n) ? match_len[i] : -1;
+        m = (m < 0 && i < n) ? 0 : m;
+        gt += (int32_t)__popcll(__ballot(m > m_star));
+        eq += (int32_t)__popcll(__ballot(i < n && m == m_star));
+    }
+    if ((tid & (kWave - 1)) == 0) { atomicAdd(&s_gt, gt); atomicAdd(&s_eq, eq); }
+    __syncthreads();
+    if (tid == 0) { ws.blockcnt[2 * blockIdx.x] = s_gt; ws.blockcnt[2 * blockIdx.x + 1] = s_eq; }
+}
+
+// Winners = every entry above m* and the first `need` entries (by index) equal to m*; written in
+// index order at positions given by prefix counts (no atomics).
+__global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restrict__ match_len, int32_t n, FqWs ws) {
+    __shared__ int32_t part[kFqThreads / kWave];
+    __shared__ int32_t s_rank, s_out;
+    __shared__ int32_t w_eq[kFqThreads / kWave], w_win[kFqThreads / kWave];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+    const int32_t m_star = ws.meta->fixed_hi;
+    const int32_t need = ws.meta->need;
+    // entries equal to m* and winners in the workgroups before this one
+    {
+        int32_t eq_b = 0, gt_b = 0;
+        for (int32_t b = tid; b < (int32_t)blockIdx.x; b += kFqThreads) {
+            gt_b += ws.blockcnt[2 * b];
+            eq_b += ws.blockcnt[2 * b + 1];
+        }
+        int32_t eq_all, gt_all;
+        block_inclusive_scan<int32_t, kFqThreads>(eq_b, part, tid, eq_all);
+        block_inclusive_scan<int32_t, kFqThreads>(gt_b, part, tid, gt_all);
+        if (tid == 0) {
+            s_rank = eq_all;
+            s_out = gt_all + (eq_all < need ? eq_all : need);
+        }
+        __syncthreads();
+    }
+    int32_t rank = s_rank, out = s_out;
+    const int32_t base = blockIdx.x * kFqTile;
+    for (int r = 0; r < kFqTile / kFqThreads; ++r) {
+        int32_t i = base + r * kFqThreads + tid;
+        bool in = i < n;
+        int32_t m = in ? match_len[i] : 0;
+        m = m < 0 ? 0 : m;
+        bool is_eq = in && m == m_star;
+        uint64_t eqmask = __ballot(is_eq);
+        // this row: counts of the wavefronts before mine
+        __syncthreads();
+        if (lane == 0) w_eq[wv] = (int32_t)__popcll(eqmask);
+        __syncthreads();
+        int32_t eq_before = 0, eq_row = 0;
+        for (int w = 0; w < kFqThreads / kWave; ++w) {
+            if (w < wv) eq_before += w_eq[w];
+            eq_row += w_eq[w];
+        }
+        int32_t my_rank = rank + eq_before + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
+        bool win = in && (m > m_star || (is_eq && my_rank < need));
+        uint64_t wmask = __ballot(win);
+        __syncthreads();
+        if (lane == 0) w_win[wv] = (int32_t)__popcll(wmask);
+        __syncthreads();
+        int32_t win_before = 0, win_row = 0;
+        for (int w = 0; w < kFqThreads / kWave; ++w) {
+            if (w < wv) win_before += w_win[w];
+            win_row += w_win[w];
+        }
+        if (win) {
+            int32_t at = out + win_before + (int32_t)__popcll(wmask & ((1ull << lane) - 1ull));
+            if (at >= 0 && at < kFifoMaxBatch)
+                ws.cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+        }
+        rank += eq_row;
+        out += win_row;
+    }
+}
+
+// Sort the nb winners by (-match_len, index) in LDS and run the two-cursor walk.
+__global__ __launch_bounds__(kFifoThreads) void k_fq_finish(int32_t n, uint32_t k, int32_t batch, FqWs ws,
+                                                            uint32_t *__restrict__ phase_inout,
+                                                            int32_t *__restrict__ batch_idx,
+                                                            int32_t *__restrict__ n_selected) {
+    __shared__ uint64_t cand[kFifoMaxBatch];
+    __shared__ uint32_t l_elem[kFifoMaxBatch];
+    __shared__ uint32_t a_in_l[kFifoMaxBatch];
+    const int tid = threadIdx.x;
+    const int32_t nb = batch < n ? batch : n;
+    const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
+    const uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
+    __syncthreads();
+    if (ws.meta->violated) {  // the caller's promise does not hold: select nothing, say so
+        if (tid == 0) *n_selected = -1;
+        return;
+    }
+    if (tid == 0) {
+        *n_selected = nb;
+        *phase_inout = lpm_only ? 0u : (uint32_t)(((uint64_t)phase + (uint64_t)nb) % k);
+    }
+    int32_t np2 = 1;
+    while (np2 < nb) np2 <<= 1;
+    for (int32_t i = tid; i < np2; i += kFifoThreads) cand[i] = (i < nb) ? ws.cand[i] : ~0ull;
+    __syncthreads();
+    for (int32_t size = 2; size <= np2; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = tid; t < (np2 >> 1); t += kFifoThreads) {
+                int32_t a = 2 * t - (t & (stride - 1));
+                int32_t b = a + stride;
+                bool up = ((a & size) == 0);
+                uint64_t ka = cand[a], kb = cand[b];
+                if ((ka > kb) == up) { cand[a] = kb; cand[b] = ka; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int32_t p = tid; p < nb; p += kFifoThreads) {
+        l_elem[p] = (uint32_t)cand[p];
+        a_in_l[p] = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    if (lpm_only) {
+        for (int32_t j = tid; j < nb; j += kFifoThreads) batch_idx[j] = (int32_t)l_elem[j];
+        return;
+    }
+    for (int32_t p = tid; p < nb; p += kFifoThreads) {
+        uint32_t e = l_elem[p];
+        if (e < (uint32_t)nb) a_in_l[e] = (uint32_t)p;  // the e-th oldest query sits at position p of L
+    }
+    __syncthreads();
+    if (tid >= kWave) return;
+    FifoAcc acc{l_elem, a_in_l};
+    two_cursor_walk(acc, nb, nb, k, phase, batch_idx, tid);
+}
+
+// FCFS on an arrival-ordered queue: its first nb entries (after the order check of the histogram kernel).
+__global__ __launch_bounds__(256) void k_fq_fcfs(int32_t n, int32_t batch, FqWs ws, uint32_t *__restrict__ phase_inout,
+                                                 int32_t *__restrict__ batch_idx, int32_t *__restrict__ n_selected) {
+    const int32_t nb = batch < n ? batch : n;
+    if (ws.meta->violated) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) *n_selected = -1;
+        return;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *n_selected = nb;
+        *phase_inout = 0u;  // k = 1: every slot is the start of a cycle
+    }
+    int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < nb) batch_idx[j] = j;
+}
+
+static void carve_fq(FqWs &f, char *base, int32_t n, size_t *used) {
+    size_t o = 0;
+    auto take = [&](size_t bytes) { void *p = base ? base + o : nullptr; o += align_up(bytes, 256); return p; };
+    int32_t nblk = (n + kFqTile - 1) / kFqTile;
+    if (nblk < 1) nblk = 1;
+    f.meta = (FqMeta *)take(sizeof(FqMeta));
+    f.hist = (uint32_t *)take((size_t)kFqMaxLevels * kFqBins * 4);
+    f.blockcnt = (int32_t *)take((size_t)nblk * 8);
+    f.cand = (uint64_t *)take((size_t)kFifoMaxBatch * 8);
+    *used = o;
+}
+
+static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
+                            int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+                            char *workspace, hipStream_t stream) {
+    FqWs f;
+    size_t used = 0;
+    carve_fq(f, workspace, n, &used);
+    const int32_t nb = batch < n ? batch : n;
+    const int32_t nblk = (n + kFqTile - 1) / kFqTile;
+    // meta and histograms are contiguous at the start of the workspace
+    if (hipMemsetAsync(f.meta, 0, (size_t)((char *)f.blockcnt - (char *)f.meta), stream) != hipSuccess) return KLPM_EHIP;
+    int mbits = 0;
+    while (mbits < 31 && (max_match >> mbits) != 0) ++mbits;
+    if (mbits == 0) mbits = 1;
+    const bool fcfs = (k == 1u);
+    int shift = mbits, level = 0;
+    while (shift > 0 && level < kFqMaxLevels) {
+        int width = shift < kFqLevelBits ? shift : kFqLevelBits;
+        shift -= width;
+        hipLaunchKernelGGL(k_fq_hist, dim3(nblk), dim3(kFqThreads), 0, stream, arrival, match_len, n, nb, max_match,
+                           level, shift, width, f);
+        ++level;
+        if (fcfs) break;  // only the order check of level 0 is needed
+    }
+    if (fcfs) {
+        hipLaunchKernelGGL(k_fq_fcfs, dim3((nb + 255) / 256), dim3(256), 0, stream, n, batch, f, phase_inout, batch_idx,
+                           n_selected);
+        return check_launch();
+    }
+    hipLaunchKernelGGL(k_fq_count, dim3(nblk), dim3(kFqThreads), 0, stream, match_len, n, f);
+    hipLaunchKernelGGL(k_fq_gather, dim3(nblk), dim3(kFqThreads), 0, stream, match_len, n, f);
+    hipLaunchKernelGGL(k_fq_finish, dim3(1), dim3(kFifoThreads), 0, stream, n, k, batch, f, phase_inout, batch_idx,
+                       n_selected);
+    return check_launch();
+}
+
 static void carve(SelectWs &ws, char *base, int32_t n, size_t *used) {
     size_t o = 0;
     auto take = [&](size_t bytes) { void *p = base ? base + o : nullptr; o += align_up(bytes, 256); return p; };
@@ -583,20 +904,32 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
     if (n < 0 || !out_bytes) return KLPM_EINVAL;
     SelectWs ws;
     carve(ws, nullptr, n, out_bytes);
+    FqWs f;
+    size_t fq = 0;
+    carve_fq(f, nullptr, n, &fq);
+    if (fq > *out_bytes) *out_bytes = fq;
     return KLPM_OK;
 }
 
 extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                           uint32_t flags, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+                           uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                            void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (n < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
-    if ((flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch) {
-        hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, n, k, batch,
-                           phase_inout, batch_idx, n_selected);
-        return check_launch();
+    if ((flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0) {
+        if (n <= kFqSingleBlockN) {
+            hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, n, k, batch,
+                               phase_inout, batch_idx, n_selected);
+            return check_launch();
+        }
+        size_t fq_need = 0;
+        FqWs probe;
+        carve_fq(probe, nullptr, n, &fq_need);
+        if (!workspace || workspace_bytes < fq_need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
+        return select_fifo_long(arrival, match_len, n, k, batch, max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout,
+                                batch_idx, n_selected, (char *)workspace, stream);
     }
     SelectWs ws;
     size_t need = 0;

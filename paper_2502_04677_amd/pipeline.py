@@ -50,7 +50,8 @@ class Scheduler:
         """``fifo`` promises that the queue is in arrival order (checked on the device)."""
         assert batch <= self.cfg.max_batch
         B.kLPM_select(q.arrival, self.match_len, q.n if n is None else n, k, batch, self.phase, self.batch_idx,
-                      self.n_selected, self.ws, self.ws_bytes, flags=B.KLPM_SELECT_FIFO if fifo else 0)
+                      self.n_selected, self.ws, self.ws_bytes, flags=B.KLPM_SELECT_FIFO if fifo else 0,
+                      max_match=self.cfg.max_prompt_len)
 
     def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None) -> None:
         B.kLPM_commit(self.tree, q, self.batch_idx, self.n_selected,

@@ -144,7 +144,7 @@ def test_select_arrival_ordered_queue_single_kernel():
     """The single-kernel path for a queue kept in arrival order, against the oracle; a queue that
     breaks the promise is refused (-1) instead of being mis-scheduled."""
     rng = np.random.default_rng(11)
-    for n, mmax in ((1, 3), (64, 1), (1000, 6), (3000, 5000), (70000, 9000), (5000, 2**30)):
+    for n, mmax in ((1, 3), (64, 1), (1000, 6), (3000, 5000), (70000, 9000), (5000, 2**30), (20000, 2**30), (9000, 0)):
         arrival = np.sort(rng.integers(0, max(2, n // 2), size=n)).astype(np.uint64)  # sorted, many ties
         m = rng.integers(0, mmax + 1, size=n).astype(np.int32)
         if n >= 1000:
@@ -166,6 +166,14 @@ def test_select_arrival_ordered_queue_single_kernel():
                 assert out.cpu().numpy().tolist() == idx_ref.tolist(), (n, mmax, k, batch)
                 assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
         if n >= 64:
+            # a match length above the promised bound is refused like a broken arrival order
+            K.kLPM_select(d_arr, d_m, n, 4, 8, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO,
+                          max_match=max(1, int(m.max()) - 1))
+            if n > 8192 and int(m.max()) >= 2:  # (the short-queue kernel needs no bound and ignores it)
+                assert int(nsel.item()) == -1
+            K.kLPM_select(d_arr, d_m, n, 4, 8, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO,
+                          max_match=int(m.max()))
+            assert int(nsel.item()) == min(8, n)
             bad = arrival.copy()
             bad[n // 2] = bad[n // 2 + 1] + 5
             phase.fill_(1)
