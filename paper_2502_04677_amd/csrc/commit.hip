@@ -23,6 +23,9 @@
 namespace klpm {
 
 constexpr uint64_t kNoGroup = ~0ull;
+constexpr int kEvictDigitBits = 11;  // eviction cut search: bits of the key resolved per pass
+constexpr int kEvictBins = 1 << kEvictDigitBits;
+constexpr int kEvictMaxPass = 6;     // 64-bit keys
 constexpr int kPlanThreads = 1024;
 
 __device__ __forceinline__ void flag_error(DevState *st, uint32_t bit) { atomicOr(&st->device_error, bit); }
@@ -236,7 +239,21 @@ __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const 
     const int32_t L = q.len[qi];
     const int32_t *__restrict__ src = q.tokens + q.off[qi] + m;
     int32_t *__restrict__ dst = tv.pool + st->pool_top + ws.tail_off[j];
-    for (int32_t i = threadIdx.x; i < L - m; i += blockDim.x) dst[i] = src[i];
+    const int32_t len = L - m;
+    // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
+    for (int32_t base = 0; base < len; base += 8 * (int32_t)blockDim.x) {
+        int32_t v[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            int32_t i = base + r * (int32_t)blockDim.x + (int32_t)threadIdx.x;
+            v[r] = src[i < len ? i : len - 1];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            int32_t i = base + r * (int32_t)blockDim.x + (int32_t)threadIdx.x;
+            if (i < len) dst[i] = v[r];
+        }
+    }
 }
 
 // ------------------------------------------------------------------ structure pass
@@ -590,7 +607,7 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
     }
     __syncthreads();
     if (evict)
-        for (int i = tid; i < 8 * 256; i += blockDim.x) ws.evict_hist[i] = 0;
+        for (int i = tid; i < kEvictMaxPass * kEvictBins; i += blockDim.x) ws.evict_hist[i] = 0;
 }
 
 // ------------------------------------------------------------------ eviction
@@ -606,44 +623,54 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
 // reaches what is still to be freed, append it to the prefix and reduce the remainder.
 __device__ void evict_descend_step(DevState *st, const int64_t *__restrict__ hist) {
     __shared__ int64_t part[256 / kWave];
-    __shared__ int64_t sc[256];
     __shared__ int pick;
+    __shared__ int64_t s_below;
     const int tid = threadIdx.x;
+    constexpr int per = kEvictBins / 256;  // contiguous bins per thread
     const int64_t rem = st->evict_rem;
-    if (tid == 0) pick = 255;
+    if (tid == 0) { pick = kEvictBins - 1; s_below = 0; }
+    int64_t w[per];
+    int64_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < per; ++q) {
+        w[q] = hist[tid * per + q];
+        mine += w[q];
+    }
     int64_t all;
-    int64_t incl = block_inclusive_scan<int64_t, 256>(hist[tid], part, tid, all);
-    sc[tid] = incl;
-    if (incl >= rem) atomicMin(&pick, tid);
+    int64_t run = block_inclusive_scan<int64_t, 256>(mine, part, tid, all) - mine;  // weight of the lower bins
+#pragma unroll
+    for (int q = 0; q < per; ++q) {
+        if (run < rem && run + w[q] >= rem) { pick = tid * per + q; s_below = run; }
+        run += w[q];
+    }
     __syncthreads();
     if (tid == 0) {
-        int dg = pick;
-        int64_t below = (dg > 0) ? sc[dg - 1] : 0;
-        st->evict_rem = rem - below;
-        st->evict_prefix = (st->evict_prefix << 8) | (uint64_t)dg;
+        st->evict_rem = rem - s_below;
+        st->evict_prefix = (st->evict_prefix << kEvictDigitBits) | (uint64_t)pick;
     }
 }
 
 __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, int pass, int n_pass, int depth_bits) {
     DevState *st = tv.st;
     if (!st->do_evict) return;
-    __shared__ unsigned long long h[256];
+    __shared__ unsigned long long h[kEvictBins];
     const int tid = threadIdx.x;
     const uint64_t prefix = st->evict_prefix;  // digits fixed by the earlier passes
-    h[tid] = 0;
+    for (int i = tid; i < kEvictBins; i += 256) h[i] = 0;
     __syncthreads();
-    const int shift = 8 * (n_pass - 1 - pass);
+    const int shift = kEvictDigitBits * (n_pass - 1 - pass);
     const int32_t n_slots = st->n_slots;
     for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
         int32_t len = tv.edge_len[id];
         if (len <= 0) continue;
         uint64_t key = evict_key(tv, id, depth_bits);
-        bool in_prefix = (pass == 0) || ((key >> (shift + 8)) == prefix);
-        if (in_prefix) atomicAdd(&h[(key >> shift) & 255ull], (unsigned long long)len);
+        bool in_prefix = (pass == 0) || ((key >> (shift + kEvictDigitBits)) == prefix);
+        if (in_prefix) atomicAdd(&h[(key >> shift) & (uint64_t)(kEvictBins - 1)], (unsigned long long)len);
     }
     __syncthreads();
-    if (h[tid]) atomicAdd((unsigned long long *)&ws.evict_hist[pass * 256 + tid], h[tid]);
-    if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * 256);
+    for (int i = tid; i < kEvictBins; i += 256)
+        if (h[i]) atomicAdd((unsigned long long *)&ws.evict_hist[pass * kEvictBins + i], h[i]);
+    if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * kEvictBins);
 }
 
 __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int n_pass, int depth_bits) {
@@ -722,7 +749,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     while (tick_bits < 64 && (t->clock_ub >> tick_bits)) ++tick_bits;
     int key_bits = tick_bits + t->depth_bits;
     if (key_bits > 64) return KLPM_EINVAL;
-    int n_pass = (key_bits + 7) / 8;
+    int n_pass = (key_bits + kEvictDigitBits - 1) / kEvictDigitBits;
     // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
     unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
     if (ge > 256u) ge = 256u;
@@ -730,10 +757,12 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, n_pass, t->depth_bits);
     hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, t->depth_bits);
     int64_t n = (int64_t)tv.slot_mask + 1;
+    // few workgroups with grid-stride loops: these two usually have nothing to do, and every
+    // workgroup of the second one ends on a shared counter
     unsigned gc = (unsigned)((n + 255) / 256);
-    if (gc > 4096u) gc = 4096u;
+    if (gc > 256u) gc = 256u;
     unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
-    if (gf > 4096u) gf = 4096u;
+    if (gf > 128u) gf = 128u;
     hipLaunchKernelGGL(k_hash_clear, dim3(gc), dim3(256), 0, stream, tv);
     hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv, stats_out);
     return check_launch();

@@ -650,20 +650,25 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
     const int nbins = 1 << width;
     const int per = (nbins + kFqThreads - 1) / kFqThreads;
     const int32_t need = (level == 0) ? nb : ws.meta->need;
+    // (after the fence of fq_last_block plain loads see the other workgroups' atomics)
+    constexpr int kMaxPer = kFqBins / kFqThreads;
+    int32_t c[kMaxPer];
     int32_t mine = 0;
-    for (int q = 0; q < per; ++q) {
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
         int b = nbins - 1 - (tid * per + q);
-        if (b >= 0) mine += (int32_t)__hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        c[q] = (q < per && b >= 0) ? (int32_t)gh[b] : 0;
+        mine += c[q];
     }
     int32_t all;
-    int32_t before = block_inclusive_scan<int32_t, kFqThreads>(mine, part, tid, all) - mine;  // entries in higher bins
-    int32_t run = before;
-    for (int q = 0; q < per; ++q) {
+    int32_t run = block_inclusive_scan<int32_t, kFqThreads>(mine, part, tid, all) - mine;  // entries in higher bins
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) {
         int b = nbins - 1 - (tid * per + q);
-        if (b < 0) break;
-        int32_t c = (int32_t)__hip_atomic_load(&gh[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (run < need && run + c >= need) { s_pick = b; s_above = run; }
-        run += c;
+        if (q < per && b >= 0) {
+            if (run < need && run + c[q] >= need) { s_pick = b; s_above = run; }
+            run += c[q];
+        }
     }
     __syncthreads();
     if (tid == 0) {

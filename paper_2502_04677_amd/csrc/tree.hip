@@ -47,7 +47,7 @@ static Layout make_layout(const kLPM_config &c) {
     L.used = take(mb * 4);
     L.leaf_tok = take(mb * 4);
     L.resv_id = take(mb * 8);
-    L.evict_hist = take(8 * 256 * 8);
+    L.evict_hist = take(6 * 2048 * 8);  // eviction cut search: 6 passes of 2048 weighted bins
     L.iota_idx = take(mb * 4);
     L.iota_n = take(256);
     L.total = o;
