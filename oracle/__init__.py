@@ -9,7 +9,9 @@ its binding never do.
 Paper passages followed: Algorithm 1 (k-LPM), Def. 1 (query stream), Def. 2
 (completion-time model, used with c_attn = 0 for the simulated prefill cost),
 Sec. 2.1 (bins of B queries finish together; fixed memory pool), Sec. 1
-(radix-tree prefix cache with LRU eviction).
+(radix-tree prefix cache with LRU eviction); ``simulate_timed`` follows Def. 2's
+timeline with the attention term (c_attn >= 0) on queries that arrive at their
+own times (Def. 1, Def. 3).
 """
 from __future__ import annotations
 
@@ -252,5 +254,73 @@ def simulate_stream(stream, snapshot_every: int = 0, tree: Optional[OracleTree] 
         keep = np.ones(waiting.shape[0], dtype=bool)
         keep[idx] = False
         waiting = waiting[keep]
+    res.clock = clock
+    return res
+
+
+@dataclass
+class TimedResult:
+    ttft: np.ndarray  # int64 per query, in clock units (-1 if never admitted)
+    order: np.ndarray  # query ids in processing order
+    batches: List[np.ndarray]  # query ids in pick order, per step
+    match_lens: List[np.ndarray]  # match lengths of the waiting queue, per step
+    waiting_ids: List[np.ndarray]  # query ids of the waiting queue, per step
+    clock: int  # time at which the last batch finished
+    steps: int
+
+
+def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_den: int = 1, t_start: int = 0,
+                   queue_cap: Optional[int] = None, tree: Optional[OracleTree] = None) -> TimedResult:
+    """Def. 2's timeline driven through match -> select -> commit, with queries that become
+    visible to the scheduler only once they have arrived (Def. 1: arrival time t_i).
+
+    Time is an integer count of units of 1/c_den of one token's linear prefill time; arrival times
+    are given in that unit.  A query costs (|x| - m)(c_den + c_num |x|) units, i.e.
+    (1 + c_attn |x|)(|x| - m) token times with c_attn = c_num / c_den (Def. 2); m is its match
+    length at the start of the step; the batch finishes together (Sec. 2.1), and nothing starts
+    before it has arrived: when nobody is waiting the clock jumps to the next arrival
+    (the max(R, t) of Def. 2).  With batch = 1 and budget = one prompt this is Def. 2 itself.
+    ``queue_cap`` bounds the waiting queue; arrivals that find it full stay outside, in arrival
+    order, keeping their arrival time.
+    """
+    n = prompts.n
+    arr = np.asarray(prompts.arrival, dtype=np.uint64)
+    pending = np.lexsort((np.arange(n), arr))  # by (arrival, id)
+    cap = n if queue_cap is None else int(queue_cap)
+    tree = tree or OracleTree()
+    ttft = np.full(n, -1, dtype=np.int64)
+    res = TimedResult(ttft, np.zeros(0, np.int32), [], [], [], int(t_start), 0)
+    waiting: List[int] = []
+    cursor, clock, phase = 0, int(t_start), 0
+    order: List[int] = []
+    while True:
+        while cursor < n and len(waiting) < cap and int(arr[pending[cursor]]) <= clock:
+            waiting.append(int(pending[cursor]))
+            cursor += 1
+        if not waiting:
+            if cursor == n:
+                break
+            clock = int(arr[pending[cursor]])  # idle until the next arrival
+            continue
+        w = np.array(waiting, dtype=np.int64)
+        off, ln = prompts.off[w], prompts.len[w]
+        m = tree.match(prompts.tokens, off, ln)
+        idx, phase = select(arr[w], m, k, batch, phase)
+        tree.commit(prompts.tokens, off, ln, idx, budget)
+        cost = 0
+        for i in idx.tolist():
+            x = int(ln[i])
+            cost += (x - int(m[i])) * (c_den + c_num * x)
+        clock += cost
+        gids = w[idx]
+        ttft[gids] = clock - arr[gids].astype(np.int64)
+        order.extend(int(g) for g in gids)
+        res.batches.append(gids.astype(np.int32))
+        res.match_lens.append(m)
+        res.waiting_ids.append(w.astype(np.int32))
+        res.steps += 1
+        gone = set(idx.tolist())
+        waiting = [q for i, q in enumerate(waiting) if i not in gone]
+    res.order = np.array(order, dtype=np.int32)
     res.clock = clock
     return res

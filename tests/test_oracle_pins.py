@@ -318,3 +318,82 @@ def test_stream_fcfs_admits_in_arrival_order():
     r = oracle.simulate_stream(s)
     flat = np.concatenate(r.batches)
     assert (np.diff(flat) > 0).all()  # global ids are in arrival order, FCFS must preserve it
+
+
+# ----------------------------------------------------------------------------- timed arrivals (Def. 2 timeline)
+def test_timed_toy_example_values():
+    g = _golden()
+    # arrivals every 10 (s = 10): each query is done before the next one arrives, whatever k is
+    for k in (1, 2, K_INF):
+        r = oracle.simulate_timed(W.toy_example(10), k, batch=1, budget=10)
+        assert r.ttft.tolist() == g["s10_fcfs_ttft"]
+    # burst (s = 0), processing starts at 0
+    r = oracle.simulate_timed(W.toy_example(0), 1, batch=1, budget=10)
+    assert (r.order + 1).tolist() == g["s0_fcfs_order"] and r.ttft.tolist() == g["s0_fcfs_ttft"]
+    for k in (2, K_INF):
+        r = oracle.simulate_timed(W.toy_example(0), k, batch=1, budget=10)
+        assert (r.order + 1).tolist() == g["s0_lpm_order"]
+        assert r.ttft[r.order].tolist() == g["s0_lpm_ttft_in_processing_order"]
+        assert r.clock == g["s0_lpm_max"][0]
+
+
+@pytest.mark.parametrize("seed,n,u,rep,d", [(1, 24, 6, 3, 4), (2, 40, 9, 4, 3), (3, 32, 5, 2, 7)])
+@pytest.mark.parametrize("c_num,c_den", [(0, 1), (3, 64)])
+def test_timed_run_equals_def2_recurrence(seed, n, u, rep, d, c_num, c_den):
+    """Batch 1 with one prompt of cache: arrival + TTFT must be Def. 2's R(.) of the order taken,
+    evaluated by the stand-alone recurrence (pairwise overlap with the previous prompt)."""
+    for s in (0, 1, (u + d) // 2, 3 * (u + d)):
+        p, _ = W.shuffled_queue(n, u, rep, d, s, seed=seed)
+        p.arrival[:] = p.arrival * np.uint64(c_den)
+        for k in (1, rep, K_INF):
+            r = oracle.simulate_timed(p, k, batch=1, budget=u + d, c_num=c_num, c_den=c_den)
+            assert sorted(r.order.tolist()) == list(range(n))
+            # the recurrence works in token times: rescale arrivals, then scale its result back
+            q = W.Prompts(p.tokens, p.off, p.len, p.arrival // np.uint64(c_den))
+            comp = oracle.def2_completion(q, r.order, c_attn=c_num / c_den) * c_den
+            assert (r.ttft + p.arrival.astype(np.int64)).tolist() == comp.tolist()
+            # nothing is processed before it arrives, nor scheduled while it was not there
+            start = r.ttft + p.arrival.astype(np.int64)
+            assert (r.ttft >= 0).all() and r.clock == start.max()
+
+
+def test_timed_slow_arrivals_are_served_on_arrival():
+    n, u, rep, d, c_num, c_den = 20, 7, 4, 5, 1, 16
+    x = u + d
+    s = x * (c_den + c_num * x) // c_den + 1  # longer than any processing time
+    p, user_of = W.shuffled_queue(n, u, rep, d, s, seed=5)
+    p.arrival[:] = p.arrival * np.uint64(c_den)
+    by_arrival = np.argsort(p.arrival, kind="stable")
+    for k in (1, 2, K_INF):
+        r = oracle.simulate_timed(p, k, batch=1, budget=x, c_num=c_num, c_den=c_den)
+        assert r.order.tolist() == by_arrival.tolist() and r.steps == n
+        prev_same = np.zeros(n, dtype=bool)
+        prev_same[by_arrival[1:]] = user_of[by_arrival[1:]] == user_of[by_arrival[:-1]]
+        want = (x - u * prev_same) * (c_den + c_num * x)
+        assert r.ttft.tolist() == want.tolist()
+
+
+@pytest.mark.parametrize("seed,n,u,rep,d,s", [(1, 12, 6, 3, 4, 2), (2, 20, 9, 4, 3, 1)])
+def test_timed_run_after_all_arrived_meets_closed_forms(seed, n, u, rep, d, s):
+    p, user_of = W.shuffled_queue(n, u, rep, d, s, seed=seed)
+    T = s * n + 3
+    r = oracle.simulate_timed(p, K_INF, batch=1, budget=u + d, t_start=T)
+    done = r.ttft + p.arrival.astype(np.int64)
+    for j, q in enumerate(r.order.tolist(), start=1):
+        assert done[q] == T + -(-j // rep) * u + d * j  # j-th completion under LPM (proof of Thm. 2)
+    r = oracle.simulate_timed(p, rep, batch=1, budget=u + d, t_start=T)
+    assert r.clock == T + n * u // rep + n * d
+    assert r.ttft.max() <= T + n * (u / rep + d - s / rep) + 1e-9
+
+
+def test_timed_bounded_queue_keeps_everyone_and_fcfs_order():
+    p, _ = W.shuffled_queue(24, 6, 3, 4, 1, seed=9)
+    full = oracle.simulate_timed(p, 1, batch=2, budget=40)
+    small = oracle.simulate_timed(p, 1, batch=2, budget=40, queue_cap=3)
+    assert full.order.tolist() == small.order.tolist() == np.argsort(p.arrival, kind="stable").tolist()
+    r = oracle.simulate_timed(p, K_INF, batch=2, budget=40, queue_cap=3)
+    assert sorted(r.order.tolist()) == list(range(24)) and all(len(w) <= 3 for w in r.waiting_ids)
+    # a batch of B finishes together: both members of a step get the same completion time
+    done = r.ttft + p.arrival.astype(np.int64)
+    for b in r.batches:
+        assert len(set(done[b].tolist())) == 1
