@@ -53,7 +53,11 @@ typedef struct {
     const int32_t *len;      /* DEVICE [n] prompt length, 1 <= len <= max_prompt_len */
     const uint64_t *arrival; /* DEVICE [n] arrival time t_i in integer ticks (may be NULL where unused) */
     int64_t n_tokens;        /* size of `tokens`, used for bounds checks */
-    int32_t n;
+    int32_t n;               /* number of queries (HOST value; launches are sized for it) */
+    const int32_t *n_live;   /* DEVICE [1] or NULL.  When given, only the first
+                                min(n, max(0, *n_live)) queries exist: a queue whose length is decided
+                                on the device is passed with n = its capacity, and no step of the
+                                scheduling loop needs the host to read the length back */
 } kLPM_queries;
 
 typedef struct {
@@ -94,7 +98,7 @@ int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *arena, size_t
  * Prefix match of the whole waiting queue: match_len[i] = max over cached strings y of
  * overlap(x_i, y), the length of the maximal common prefix (Sec. 1.2 Notation), token-granular,
  * 0 <= match_len[i] <= len[i].  Read-only on the tree (recency is only touched by commit).
- *   match_len  DEVICE [q->n] out
+ *   match_len  DEVICE [q->n] out (entries at or beyond *q->n_live are left untouched)
  *   last_node  DEVICE [q->n] out or NULL: opaque id of the deepest node whose edge was entered
  * A query whose span falls outside q->tokens gets match_len = -1 and sets KLPM_DEV_BAD_INPUT.
  */
@@ -115,6 +119,8 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * remaining query with the longest match; ties go to the earlier arrival, then the lower index.
  * k = 1 is FCFS; k = 0 or KLPM_K_INFINITY is pure LPM order (Sec. 4).
  *   arrival, match_len  DEVICE [n] in (a negative match_len counts as 0)
+ *   n_live              DEVICE [1] or NULL: as in kLPM_queries, the queue holds min(n, max(0, *n_live))
+ *                       entries; n then only sizes the launches and the workspace
  *   flags               0 or KLPM_SELECT_FIFO
  *   max_match           with KLPM_SELECT_FIFO: an upper bound of the match_len values (the longest
  *                       prompt accepted will do); 0 = unknown.  A smaller bound means fewer passes; a
@@ -122,12 +128,12 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  *   phase_inout         DEVICE [1]: position in the k-cycle, carried from step to step
  *                       (write 0 before the call to restart the cycle every step)
  *   batch_idx           DEVICE [min(batch, n)] out: queue indices in pick order
- *   n_selected          DEVICE [1] out: min(batch, n)
+ *   n_selected          DEVICE [1] out: min(batch, number of entries)
  *   workspace           DEVICE, >= kLPM_select_workspace_bytes(n), 256-byte aligned
  * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
  */
-int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, const int32_t *n_live, uint32_t k,
+                int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                 void *workspace, size_t workspace_bytes, kLPM_stream stream);
 
 /*
@@ -187,6 +193,37 @@ int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM
                        int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
                        int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
                        kLPM_stream stream);
+
+/*
+ * Arrivals that reach the scheduler at their own times (query stream of Def. 1; the Regular
+ * Arrival Shuffled Queue of Def. 3 is one).  All pointers DEVICE.  Times and the simulated clock
+ * count units of 1/c_den of one token's linear prefill time.
+ */
+typedef struct {
+    const int32_t *id;    /* [n] global query ids ordered by (arrival time, id) */
+    const uint64_t *time; /* [n] their arrival times t_i, non-decreasing */
+    int32_t *cursor;      /* [1] in/out: how many of them have joined the queue so far */
+    int32_t n;
+    uint32_t c_num;       /* attention coefficient of Def. 2: c_attn = c_num / c_den */
+    uint32_t c_den;       /* >= 1 */
+} kLPM_arrivals;
+
+/*
+ * The same bookkeeping as kLPM_queue_advance under Def. 2's timeline: the batch costs the sum over
+ * its queries of (len - match_len) * (c_den + c_num * len) clock units, i.e.
+ * (1 + c_attn |x|)(|x| - overlap) token times each; the clock moves by exactly that; TTFT = new time
+ * - arrival time.  Then every pending arrival with time <= clock joins `next` behind the survivors,
+ * keeping its own arrival time, as far as next->cap allows (the rest stay pending, in order).  If
+ * that leaves the queue empty while arrivals are still pending, the clock jumps to the next
+ * arrival time (a query cannot start before it arrives, Def. 2) and the queries arriving then join.
+ * The queue length is left in *next->n for the next step's n_live.  Calling it on an empty queue
+ * with *n_selected = 0 performs the initial fill.
+ */
+int kLPM_queue_advance_timed(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
+                             const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
+                             int32_t batch_cap, const kLPM_arrivals *pending, uint64_t *sim_clock, int64_t *ttft,
+                             int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
+                             kLPM_stream stream);
 
 /* Synchronises the stream and copies the tree's counters to HOST memory. */
 int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_stream stream);

@@ -4,10 +4,10 @@ The package is a binding of the C ABI declared in ``include/klpm.h``; all comput
 library ``libklpm.so`` built from ``csrc/``.
 """
 from .binding import (  # noqa: F401
-    Config, DeviceQueries, DeviceQueue, KlpmError, Stats, Tree, EXPORTS, KLPM_K_INFINITY, KLPM_SELECT_FIFO, STATS_BYTES,
+    Config, DeviceArrivals, DeviceQueries, DeviceQueue, KlpmError, Stats, Tree, EXPORTS, KLPM_K_INFINITY, KLPM_SELECT_FIFO, STATS_BYTES,
     alloc_aligned, make_config, stats_from_tensor,
-    kLPM_arena_bytes, kLPM_build_tree, kLPM_commit, kLPM_destroy, kLPM_match, kLPM_queue_advance,
+    kLPM_arena_bytes, kLPM_build_tree, kLPM_commit, kLPM_destroy, kLPM_match, kLPM_queue_advance, kLPM_queue_advance_timed,
     kLPM_queue_gather, kLPM_queue_scratch_bytes, kLPM_read_stats, kLPM_select, kLPM_select_workspace_bytes, kLPM_set_budget,
     kLPM_snapshot,
 )
-from .pipeline import Scheduler, OnlineRun, size_config  # noqa: F401
+from .pipeline import Scheduler, OnlineRun, TimedRun, size_config  # noqa: F401

@@ -24,7 +24,7 @@ DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
-    "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
+    "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
     "kLPM_read_stats",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
@@ -32,7 +32,12 @@ EXPORTS = (
 
 class Queries(C.Structure):
     _fields_ = [("tokens", C.c_void_p), ("off", C.c_void_p), ("len", C.c_void_p), ("arrival", C.c_void_p),
-                ("n_tokens", C.c_int64), ("n", C.c_int32)]
+                ("n_tokens", C.c_int64), ("n", C.c_int32), ("n_live", C.c_void_p)]
+
+
+class Arrivals(C.Structure):
+    _fields_ = [("id", C.c_void_p), ("time", C.c_void_p), ("cursor", C.c_void_p), ("n", C.c_int32),
+                ("c_num", C.c_uint32), ("c_den", C.c_uint32)]
 
 
 class Queue(C.Structure):
@@ -64,11 +69,13 @@ def load_library() -> C.CDLL:
     lib.kLPM_build_tree.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, sz, C.POINTER(Queries), vp]
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select.argtypes = [vp, vp, i32, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select.argtypes = [vp, vp, i32, vp, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
     lib.kLPM_set_budget.argtypes = [vp, i64]
     lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
                                        vp, vp, vp, vp, sz, vp, vp]
+    lib.kLPM_queue_advance_timed.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32,
+                                             C.POINTER(Arrivals), vp, vp, vp, vp, sz, vp, vp]
     lib.kLPM_queue_gather.argtypes = [C.POINTER(Queue), C.POINTER(Queries), vp]
     lib.kLPM_queue_scratch_bytes.argtypes = [i32, C.POINTER(sz)]
     lib.kLPM_read_stats.argtypes = [vp, C.POINTER(Stats), vp]
@@ -119,6 +126,7 @@ class DeviceQueries:
     len: torch.Tensor
     arrival: Optional[torch.Tensor]
     n: int
+    n_live: Optional[torch.Tensor] = None  # int32 [1] on the device: how many of the n entries exist
 
     @staticmethod
     def from_host(p, device="cuda:0") -> "DeviceQueries":
@@ -133,7 +141,8 @@ class DeviceQueries:
     def c_struct(self) -> Queries:
         return Queries(_dev(self.tokens, torch.int32).data_ptr(), _dev(self.off, torch.int64).data_ptr() if self.n else 0,
                        _dev(self.len, torch.int32).data_ptr() if self.n else 0,
-                       0 if self.arrival is None else self.arrival.data_ptr(), int(self.tokens.numel()), int(self.n))
+                       0 if self.arrival is None else self.arrival.data_ptr(), int(self.tokens.numel()), int(self.n),
+                       0 if self.n_live is None else _dev(self.n_live, torch.int32).data_ptr())
 
 
 class Tree:
@@ -202,8 +211,8 @@ def alloc_aligned(nbytes: int, device) -> Tuple[torch.Tensor, int]:
 def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, batch: int,
                 phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
                 workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None, flags: int = 0,
-                max_match: int = 0) -> None:
-    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), int(n), C.c_uint32(k & 0xFFFFFFFF), int(batch),
+                max_match: int = 0, n_live: Optional[torch.Tensor] = None) -> None:
+    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), int(n), _ptr(n_live), C.c_uint32(k & 0xFFFFFFFF), int(batch),
                             C.c_uint32(flags), int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
 
@@ -256,6 +265,44 @@ def kLPM_queue_advance(cur: DeviceQueue, nxt: DeviceQueue, all_q: DeviceQueries,
                                    _ptr(n_selected), int(batch_cap), _ptr(new_id), int(n_new), _ptr(sim_clock),
                                    _ptr(ttft), _ptr(matched_accum), C.c_void_p(scratch[1]), int(scratch_bytes),
                                    _ptr(dev_error), _stream(stream)), "kLPM_queue_advance")
+
+
+@dataclass
+class DeviceArrivals:
+    """Arrivals in time order, resident on the device, with the cursor of those already enqueued."""
+
+    id: torch.Tensor  # int32 [n], ordered by (time, id)
+    time: torch.Tensor  # int64 [n] (bits of uint64), non-decreasing
+    cursor: torch.Tensor  # int32 [1]
+    n: int
+    c_num: int = 0
+    c_den: int = 1
+
+    @staticmethod
+    def from_host(arrival: np.ndarray, c_num: int, c_den: int, device) -> "DeviceArrivals":
+        arrival = np.ascontiguousarray(arrival, dtype=np.uint64)
+        order = np.lexsort((np.arange(arrival.shape[0]), arrival)).astype(np.int32)
+        t = arrival[order].view(np.int64)
+        n = int(order.shape[0])
+        pad = max(n, 1)
+        ids = torch.zeros(pad, dtype=torch.int32, device=device)
+        tim = torch.zeros(pad, dtype=torch.int64, device=device)
+        ids[:n] = torch.from_numpy(order).to(device)
+        tim[:n] = torch.from_numpy(np.ascontiguousarray(t)).to(device)
+        return DeviceArrivals(ids, tim, torch.zeros(1, dtype=torch.int32, device=device), n, int(c_num), int(c_den))
+
+    def c_struct(self) -> Arrivals:
+        return Arrivals(self.id.data_ptr(), self.time.data_ptr(), self.cursor.data_ptr(), self.n, self.c_num, self.c_den)
+
+
+def kLPM_queue_advance_timed(cur: DeviceQueue, nxt: DeviceQueue, all_q: DeviceQueries, match_len, batch_idx, n_selected,
+                             batch_cap: int, pending: DeviceArrivals, sim_clock, ttft, matched_accum,
+                             scratch: Tuple[torch.Tensor, int], scratch_bytes: int, dev_error, stream=None) -> None:
+    c, n, a, p = cur.c_struct(), nxt.c_struct(), all_q.c_struct(), pending.c_struct()
+    _check(_lib.kLPM_queue_advance_timed(C.byref(c), C.byref(n), C.byref(a), _ptr(match_len), _ptr(batch_idx),
+                                         _ptr(n_selected), int(batch_cap), C.byref(p), _ptr(sim_clock), _ptr(ttft),
+                                         _ptr(matched_accum), C.c_void_p(scratch[1]), int(scratch_bytes),
+                                         _ptr(dev_error), _stream(stream)), "kLPM_queue_advance_timed")
 
 
 def kLPM_queue_gather(q: DeviceQueue, all_q: DeviceQueries, stream=None) -> None:

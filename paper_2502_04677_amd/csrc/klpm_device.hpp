@@ -104,6 +104,7 @@ struct QView {
     const int32_t *len;
     int64_t n_tokens;
     int32_t n;
+    const int32_t *n_live;  // device-side count (may be null): only the first min(n, *n_live) queries exist
 };
 
 __device__ __forceinline__ uint64_t make_key(int32_t parent, int32_t tok) {
@@ -126,6 +127,14 @@ __device__ __forceinline__ int64_t uni64(int64_t v) {
     uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)(uint64_t)v);
     uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)((uint64_t)v >> 32));
     return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// Number of entries that exist: the host-side count, cut down by the device-side count if one is given.
+__device__ __forceinline__ int32_t live_count(int32_t n, const int32_t *__restrict__ n_live) {
+    if (!n_live) return n;
+    int32_t v = *n_live;
+    v = v < 0 ? 0 : v;
+    return v < n ? v : n;
 }
 
 // Read-only probe (tree not being modified by this kernel). Returns the slot index or -1 and, when

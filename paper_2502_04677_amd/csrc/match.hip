@@ -22,10 +22,12 @@ __device__ __forceinline__ void match_body(const TreeView &tv, const QView &q, c
     if (ADMITTED) {
         uint32_t err;
         n = commit_gate(tv, n_dev, n_cap, &err);  // the plan kernel records the reason of a refusal
+    } else {
+        n = uni(live_count(n, q.n_live));
     }
     if (w >= n) return;
     int32_t qi = ADMITTED ? uni(sel[w]) : (int32_t)w;
-    bool bad = (qi < 0 || qi >= q.n);
+    bool bad = (qi < 0 || qi >= (ADMITTED ? uni(live_count(q.n, q.n_live)) : q.n));
     int64_t off = 0;
     int32_t L = 0;
     if (!bad) {

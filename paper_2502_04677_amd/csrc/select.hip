@@ -19,6 +19,14 @@ constexpr int kSortTile = kSortThreads * kSortItems;          // 2048 keys per b
 constexpr int kSortWaveTile = kWave * kSortItems;             // 512 contiguous keys per wave
 constexpr int kScanThreads = 1024;
 
+// The queue length as the kernels get it: the host-side count (which sizes the launches) and the
+// optional device-side count that cuts it down.
+struct LiveN {
+    int32_t n;
+    const int32_t *live;
+    __device__ __forceinline__ int32_t get() const { return live_count(n, live); }
+};
+
 struct SelectWs {
     uint64_t *key_a, *key_b;
     uint32_t *val_a, *val_b, *val_c;
@@ -27,8 +35,9 @@ struct SelectWs {
     int32_t *skip;
 };
 
-__global__ __launch_bounds__(256) void k_sel_init(const uint64_t *__restrict__ arrival, int32_t n,
+__global__ __launch_bounds__(256) void k_sel_init(const uint64_t *__restrict__ arrival, LiveN nn,
                                                   uint64_t *__restrict__ key, uint32_t *__restrict__ val) {
+    const int32_t n = nn.get();
     int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) {
         key[i] = arrival[i];
@@ -39,8 +48,9 @@ __global__ __launch_bounds__(256) void k_sel_init(const uint64_t *__restrict__ a
 // keys for the longest-match order, laid out in oldest-first order so that a stable sort on the
 // match length alone yields (-match_len, arrival, index)
 __global__ __launch_bounds__(256) void k_sel_lkeys(const uint32_t *__restrict__ order_a,
-                                                   const int32_t *__restrict__ match_len, int32_t n,
+                                                   const int32_t *__restrict__ match_len, LiveN nn,
                                                    uint64_t *__restrict__ key, uint32_t *__restrict__ val) {
+    const int32_t n = nn.get();
     int32_t r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r < n) {
         uint32_t i = order_a[r];
@@ -52,8 +62,9 @@ __global__ __launch_bounds__(256) void k_sel_lkeys(const uint32_t *__restrict__ 
 }
 
 __global__ __launch_bounds__(256) void k_sel_ranks(const uint32_t *__restrict__ order_a,
-                                                   const uint32_t *__restrict__ order_l, int32_t n,
+                                                   const uint32_t *__restrict__ order_l, LiveN nn,
                                                    uint32_t *__restrict__ rank_a, uint32_t *__restrict__ rank_l) {
+    const int32_t n = nn.get();
     int32_t r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r < n) {
         rank_a[order_a[r]] = (uint32_t)r;
@@ -62,8 +73,9 @@ __global__ __launch_bounds__(256) void k_sel_ranks(const uint32_t *__restrict__ 
 }
 
 // ---- stable LSD radix sort, 8-bit digits: histogram / scan / scatter per pass ----
-__global__ __launch_bounds__(kSortThreads) void k_rs_hist(const uint64_t *__restrict__ key, int32_t n, int shift,
+__global__ __launch_bounds__(kSortThreads) void k_rs_hist(const uint64_t *__restrict__ key, LiveN nn, int shift,
                                                           uint32_t *__restrict__ hist, int32_t nblk) {
+    const int32_t n = nn.get();
     __shared__ uint32_t h[256];
     h[threadIdx.x] = 0;
     __syncthreads();
@@ -78,8 +90,9 @@ __global__ __launch_bounds__(kSortThreads) void k_rs_hist(const uint64_t *__rest
 
 // exclusive scan of the digit-major table hist[256][nblk]; also flags a pass in which every key
 // has the same digit (the scatter then degenerates to a copy)
-__global__ __launch_bounds__(kScanThreads) void k_rs_scan(uint32_t *__restrict__ hist, int32_t nblk, int32_t n,
+__global__ __launch_bounds__(kScanThreads) void k_rs_scan(uint32_t *__restrict__ hist, int32_t nblk, LiveN nn,
                                                           int32_t *__restrict__ skip) {
+    const int32_t n = nn.get();
     __shared__ uint32_t part[kScanThreads];
     const int tid = threadIdx.x;
     const int64_t total = 256ll * nblk;
@@ -115,9 +128,10 @@ __global__ __launch_bounds__(kScanThreads) void k_rs_scan(uint32_t *__restrict__
 __global__ __launch_bounds__(kSortThreads) void k_rs_scatter(const uint64_t *__restrict__ key_in,
                                                              const uint32_t *__restrict__ val_in,
                                                              uint64_t *__restrict__ key_out,
-                                                             uint32_t *__restrict__ val_out, int32_t n, int shift,
+                                                             uint32_t *__restrict__ val_out, LiveN nn, int shift,
                                                              const uint32_t *__restrict__ hist, int32_t nblk,
                                                              const int32_t *__restrict__ skip) {
+    const int32_t n = nn.get();
     __shared__ uint32_t wcount[kSortThreads / kWave][256];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -181,9 +195,10 @@ __global__ __launch_bounds__(kSortThreads) void k_rs_scatter(const uint64_t *__r
 
 // sorts (key, val) by bits [0, 8*passes) of key; result ends in (key_in, val_in) when `passes` is
 // even, else in (key_out, val_out). Returns which one through `result_in_first`.
-static int radix_sort(uint64_t *k0, uint32_t *v0, uint64_t *k1, uint32_t *v1, int32_t n, int passes, SelectWs &ws,
+static int radix_sort(uint64_t *k0, uint32_t *v0, uint64_t *k1, uint32_t *v1, LiveN nn, int passes, SelectWs &ws,
                       hipStream_t stream, bool *result_in_first) {
-    int32_t nblk = (n + kSortTile - 1) / kSortTile;
+    const LiveN n = nn;
+    int32_t nblk = (nn.n + kSortTile - 1) / kSortTile;
     uint64_t *ki = k0, *ko = k1;
     uint32_t *vi = v0, *vo = v1;
     for (int p = 0; p < passes; ++p) {
@@ -296,10 +311,11 @@ struct StagedAcc {
 __global__ __launch_bounds__(256) void k_sel_walk(const uint32_t *__restrict__ order_a,
                                                   const uint32_t *__restrict__ order_l,
                                                   const uint32_t *__restrict__ rank_a,
-                                                  const uint32_t *__restrict__ rank_l, int32_t n, uint32_t k,
+                                                  const uint32_t *__restrict__ rank_l, LiveN nn, uint32_t k,
                                                   int32_t batch, uint32_t *__restrict__ phase_inout,
                                                   int32_t *__restrict__ batch_idx,
                                                   int32_t *__restrict__ n_selected) {
+    const int32_t n = nn.get();
     __shared__ uint32_t s_a_elem[kStage], s_l_elem[kStage], s_a_in_l[kStage], s_l_in_a[kStage];
     const int tid = threadIdx.x;
     const int32_t nb = batch < n ? batch : n;
@@ -364,11 +380,12 @@ __device__ __forceinline__ int32_t block_scan_incl(int32_t v, int32_t *buf, int 
 }
 
 __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__restrict__ arrival,
-                                                               const int32_t *__restrict__ match_len, int32_t n,
+                                                               const int32_t *__restrict__ match_len, LiveN nn,
                                                                uint32_t k, int32_t batch,
                                                                uint32_t *__restrict__ phase_inout,
                                                                int32_t *__restrict__ batch_idx,
                                                                int32_t *__restrict__ n_selected) {
+    const int32_t n = nn.get();
     __shared__ uint32_t hist[kFifoBins];
     __shared__ uint64_t cand[kFifoMaxBatch];
     __shared__ uint32_t l_elem[kFifoMaxBatch];
@@ -598,16 +615,17 @@ __device__ __forceinline__ bool fq_last_block(int32_t *counter) {
 // Histogram of one 13-bit digit of the match lengths that share the digits fixed so far; level 0 also
 // checks the arrival order.  The last workgroup to finish fixes the digit of the nb-th largest length.
 __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restrict__ arrival,
-                                                       const int32_t *__restrict__ match_len, int32_t n, int32_t nb,
+                                                       const int32_t *__restrict__ match_len, LiveN nn, int32_t batch,
                                                        int32_t max_match, int level, int shift, int width,
                                                        FqWs ws) {
+    const int32_t n = nn.get();
     __shared__ uint32_t h[kFqBins];
     __shared__ int32_t part[kFqThreads / kWave];
     __shared__ int32_t s_viol, s_pick, s_above;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     for (int i = tid; i < (1 << width); i += kFqThreads) h[i] = 0;
-    if (tid == 0) s_viol = 0;
+    if (tid == 0) { s_viol = 0; s_pick = 0; s_above = 0; }
     __syncthreads();
     const int32_t fixed_hi = (level == 0) ? 0 : ws.meta->fixed_hi;
     const int32_t base = blockIdx.x * kFqTile;
@@ -649,6 +667,7 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
     // suffix counts over the bins, top down: thread t owns a contiguous run of bins counted from the top
     const int nbins = 1 << width;
     const int per = (nbins + kFqThreads - 1) / kFqThreads;
+    const int32_t nb = batch < n ? batch : n;
     const int32_t need = (level == 0) ? nb : ws.meta->need;
     // (after the fence of fq_last_block plain loads see the other workgroups' atomics)
     constexpr int kMaxPer = kFqBins / kFqThreads;
@@ -678,7 +697,8 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
 }
 
 // Per workgroup: how many of its entries lie above m* and how many equal it.
-__global__ __launch_bounds__(kFqThreads) void k_fq_count(const int32_t *__restrict__ match_len, int32_t n, FqWs ws) {
+__global__ __launch_bounds__(kFqThreads) void k_fq_count(const int32_t *__restrict__ match_len, LiveN nn, FqWs ws) {
+    const int32_t n = nn.get();
     __shared__ int32_t s_gt, s_eq;
     const int tid = threadIdx.x;
     if (tid == 0) { s_gt = 0; s_eq = 0; }
@@ -701,7 +721,8 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_count(const int32_t *__restri
 
 // Winners = every entry above m* and the first `need` entries (by index) equal to m*; written in
 // index order at positions given by prefix counts (no atomics).
-__global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restrict__ match_len, int32_t n, FqWs ws) {
+__global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restrict__ match_len, LiveN nn, FqWs ws) {
+    const int32_t n = nn.get();
     __shared__ int32_t part[kFqThreads / kWave];
     __shared__ int32_t s_rank, s_out;
     __shared__ int32_t w_eq[kFqThreads / kWave], w_win[kFqThreads / kWave];
@@ -765,10 +786,11 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restr
 }
 
 // Sort the nb winners by (-match_len, index) in LDS and run the two-cursor walk.
-__global__ __launch_bounds__(kFifoThreads) void k_fq_finish(int32_t n, uint32_t k, int32_t batch, FqWs ws,
+__global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, uint32_t k, int32_t batch, FqWs ws,
                                                             uint32_t *__restrict__ phase_inout,
                                                             int32_t *__restrict__ batch_idx,
                                                             int32_t *__restrict__ n_selected) {
+    const int32_t n = nn.get();
     __shared__ uint64_t cand[kFifoMaxBatch];
     __shared__ uint32_t l_elem[kFifoMaxBatch];
     __shared__ uint32_t a_in_l[kFifoMaxBatch];
@@ -821,8 +843,9 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(int32_t n, uint32_t 
 }
 
 // FCFS on an arrival-ordered queue: its first nb entries (after the order check of the histogram kernel).
-__global__ __launch_bounds__(256) void k_fq_fcfs(int32_t n, int32_t batch, FqWs ws, uint32_t *__restrict__ phase_inout,
+__global__ __launch_bounds__(256) void k_fq_fcfs(LiveN nn, int32_t batch, FqWs ws, uint32_t *__restrict__ phase_inout,
                                                  int32_t *__restrict__ batch_idx, int32_t *__restrict__ n_selected) {
+    const int32_t n = nn.get();
     const int32_t nb = batch < n ? batch : n;
     if (ws.meta->violated) {
         if (blockIdx.x == 0 && threadIdx.x == 0) *n_selected = -1;
@@ -848,14 +871,15 @@ static void carve_fq(FqWs &f, char *base, int32_t n, size_t *used) {
     *used = o;
 }
 
-static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
+static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, LiveN nn, uint32_t k, int32_t batch,
                             int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                             char *workspace, hipStream_t stream) {
     FqWs f;
     size_t used = 0;
-    carve_fq(f, workspace, n, &used);
-    const int32_t nb = batch < n ? batch : n;
-    const int32_t nblk = (n + kFqTile - 1) / kFqTile;
+    carve_fq(f, workspace, nn.n, &used);
+    const LiveN n = nn;
+    const int32_t nb = batch < nn.n ? batch : nn.n;  // upper bound of the picks, sizes the FCFS launch
+    const int32_t nblk = (nn.n + kFqTile - 1) / kFqTile;
     // meta and histograms are contiguous at the start of the workspace
     if (hipMemsetAsync(f.meta, 0, (size_t)((char *)f.blockcnt - (char *)f.meta), stream) != hipSuccess) return KLPM_EHIP;
     int mbits = 0;
@@ -866,7 +890,7 @@ static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, i
     while (shift > 0 && level < kFqMaxLevels) {
         int width = shift < kFqLevelBits ? shift : kFqLevelBits;
         shift -= width;
-        hipLaunchKernelGGL(k_fq_hist, dim3(nblk), dim3(kFqThreads), 0, stream, arrival, match_len, n, nb, max_match,
+        hipLaunchKernelGGL(k_fq_hist, dim3(nblk), dim3(kFqThreads), 0, stream, arrival, match_len, n, batch, max_match,
                            level, shift, width, f);
         ++level;
         if (fcfs) break;  // only the order check of level 0 is needed
@@ -916,16 +940,17 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
     return KLPM_OK;
 }
 
-extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                           uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, const int32_t *n_live,
+                           uint32_t k, int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                            void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (n < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
+    const LiveN nn{n, n_live};
     if ((flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0) {
         if (n <= kFqSingleBlockN) {
-            hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, n, k, batch,
+            hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, nn, k, batch,
                                phase_inout, batch_idx, n_selected);
             return check_launch();
         }
@@ -933,7 +958,7 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, in
         FqWs probe;
         carve_fq(probe, nullptr, n, &fq_need);
         if (!workspace || workspace_bytes < fq_need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
-        return select_fifo_long(arrival, match_len, n, k, batch, max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout,
+        return select_fifo_long(arrival, match_len, nn, k, batch, max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout,
                                 batch_idx, n_selected, (char *)workspace, stream);
     }
     SelectWs ws;
@@ -943,23 +968,23 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, in
     const uint32_t *order_a = ws.val_a, *order_l = ws.val_a;
     if (n > 0 && batch > 0) {
         unsigned g = (unsigned)((n + 255) / 256);
-        hipLaunchKernelGGL(k_sel_init, dim3(g), dim3(256), 0, stream, arrival, n, ws.key_a, ws.val_a);
+        hipLaunchKernelGGL(k_sel_init, dim3(g), dim3(256), 0, stream, arrival, nn, ws.key_a, ws.val_a);
         bool first = true;
-        int rc = radix_sort(ws.key_a, ws.val_a, ws.key_b, ws.val_b, n, 8, ws, stream, &first);
+        int rc = radix_sort(ws.key_a, ws.val_a, ws.key_b, ws.val_b, nn, 8, ws, stream, &first);
         if (rc) return rc;
         order_a = first ? ws.val_a : ws.val_b;  // 8 passes: back in the first buffer
         if (k != 1u) {
             // stable sort of the oldest-first order by descending match length
             uint32_t *spare = first ? ws.val_b : ws.val_a;
-            hipLaunchKernelGGL(k_sel_lkeys, dim3(g), dim3(256), 0, stream, order_a, match_len, n, ws.key_a, ws.val_c);
+            hipLaunchKernelGGL(k_sel_lkeys, dim3(g), dim3(256), 0, stream, order_a, match_len, nn, ws.key_a, ws.val_c);
             bool lfirst = true;
-            rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, spare, n, 4, ws, stream, &lfirst);
+            rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, spare, nn, 4, ws, stream, &lfirst);
             if (rc) return rc;
             order_l = lfirst ? ws.val_c : spare;
-            hipLaunchKernelGGL(k_sel_ranks, dim3(g), dim3(256), 0, stream, order_a, order_l, n, ws.rank_a, ws.rank_l);
+            hipLaunchKernelGGL(k_sel_ranks, dim3(g), dim3(256), 0, stream, order_a, order_l, nn, ws.rank_a, ws.rank_l);
         }
     }
-    hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, order_a, order_l, ws.rank_a, ws.rank_l, n, k,
+    hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, order_a, order_l, ws.rank_a, ws.rank_l, nn, k,
                        batch, phase_inout, batch_idx, n_selected);
     return check_launch();
 }

@@ -98,6 +98,15 @@ constexpr int kQueueThreads = 1024;
 struct QueueHdr {  // at the start of the scratch buffer
     int32_t nw, n_removed, kept, add;
     uint64_t now;
+    int32_t new_base, pad;  // first entry of the arrival list that joins in this step
+};
+
+struct ArrivalsView {  // arrivals in time order; `time`/`cursor` are null for the per-step lists of kLPM_queue_advance
+    const int32_t *id;
+    const uint64_t *time;
+    int32_t *cursor;
+    int32_t n;
+    uint32_t c_num, c_den;
 };
 
 struct QueueView {
@@ -112,11 +121,15 @@ struct QueueView {
 // Retire: one workgroup marks the admitted queue positions in a bitmap, sums the batch's uncached
 // tokens, advances the simulated clock, stamps the TTFT of the admitted queries and leaves, for every
 // 32-position word of the queue, the number of retired positions before it.
+// TIMED: Def. 2's timeline (cost with the attention term, arrivals join when their time has come,
+// an idle scheduler waits for the next arrival); otherwise the n_new arrivals of this step join at
+// the new time and the clock moves by at least 1.
+template <bool TIMED>
 __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, QueueView next, QView all,
                                                                 const int32_t *__restrict__ match_len,
                                                                 const int32_t *__restrict__ batch_idx,
                                                                 const int32_t *__restrict__ n_selected,
-                                                                int32_t batch_cap, int32_t n_new,
+                                                                int32_t batch_cap, ArrivalsView pend,
                                                                 uint64_t *__restrict__ sim_clock,
                                                                 int64_t *__restrict__ ttft, QueueHdr *hdr,
                                                                 uint32_t *__restrict__ bitmap,
@@ -145,13 +158,17 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
                 int32_t len = (id >= 0 && id < all.n) ? all.len[id] : 0;
                 int32_t m = match_len[w];
                 m = m < 0 ? 0 : m;
-                if (len > m) my_cost += (unsigned long long)(len - m);  // uncached tokens (Def. 2, c_attn = 0)
+                // (1 + c_attn |x|)(|x| - overlap) token times, in units of 1/c_den (Def. 2)
+                if (len > m)
+                    my_cost += (unsigned long long)(len - m) *
+                               (TIMED ? (unsigned long long)pend.c_den + (unsigned long long)pend.c_num * (unsigned long long)len
+                                      : 1ull);
             }
         }
     }
     if (my_cost) atomicAdd(&s_cost, my_cost);
     __syncthreads();
-    if (tid == 0) s_clock = *sim_clock + (s_cost > 0 ? (uint64_t)s_cost : 1ull);
+    if (tid == 0) s_clock = *sim_clock + ((TIMED || s_cost > 0) ? (uint64_t)s_cost : 1ull);
     // retired positions before each word: contiguous runs of words per thread, one scan
     const int32_t per = (n_words + kQueueThreads - 1) / kQueueThreads;
     const int32_t lo = tid * per < n_words ? tid * per : n_words;
@@ -173,19 +190,43 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
             if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[w]);
         }
     }
+    const int32_t kept = nw - nv;
+    int32_t room = next.cap - kept;
+    room = room < 0 ? 0 : room;
+    uint64_t now_out = now;
+    int32_t base = 0, add = pend.n;
+    if (TIMED) {
+        // pending arrivals whose time has come: times are sorted, so their number is a prefix length
+        base = *pend.cursor;
+        base = base < 0 ? 0 : (base > pend.n ? pend.n : base);
+        add = 0;
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int32_t b = base; b < pend.n; b += kQueueThreads) {
+                int32_t i = b + tid;
+                int c = __syncthreads_count(i < pend.n && pend.time[i] <= now_out);
+                add += c;
+                if (c < kQueueThreads) break;
+            }
+            if (pass == 1 || kept > 0 || add > 0 || base >= pend.n) break;
+            now_out = pend.time[base];  // nobody waiting: idle until the next arrival (Def. 2: max(R, t))
+        }
+    }
     if (tid == 0) {
-        int32_t kept = nw - nv;
-        int32_t room = next.cap - kept;
-        room = room < 0 ? 0 : room;
-        int32_t add = n_new < room ? n_new : room;
-        if ((add < n_new || kept > next.cap) && dev_error) atomicOr(dev_error, 8u);
+        if (TIMED) {
+            add = add < room ? add : room;  // the rest stay pending, in order
+            *pend.cursor = base + add;
+        } else {
+            if ((add > room || kept > next.cap) && dev_error) atomicOr(dev_error, 8u);
+            add = add < room ? add : room;
+        }
         hdr->nw = nw;
         hdr->n_removed = nv;
         hdr->kept = kept < next.cap ? kept : next.cap;
         hdr->add = add;
-        hdr->now = now;
+        hdr->now = now_out;
+        hdr->new_base = base;
         *next.n = hdr->kept + add;
-        *sim_clock = now;
+        *sim_clock = now_out;
     }
 }
 
@@ -193,7 +234,8 @@ __global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, Q
 // arrivals are appended, and the CSR view of the new queue is written on the way.
 __global__ __launch_bounds__(256) void k_queue_compact(QueueView cur, QueueView next, QView all,
                                                        const int32_t *__restrict__ match_len,
-                                                       const int32_t *__restrict__ new_id, const QueueHdr *hdr,
+                                                       const int32_t *__restrict__ new_id,
+                                                       const uint64_t *__restrict__ new_time, const QueueHdr *hdr,
                                                        const uint32_t *__restrict__ bitmap,
                                                        const uint32_t *__restrict__ before,
                                                        int64_t *__restrict__ matched_accum) {
@@ -221,10 +263,11 @@ __global__ __launch_bounds__(256) void k_queue_compact(QueueView cur, QueueView 
         }
     } else if (i < (int64_t)nw + add) {
         int32_t r = (int32_t)(i - nw);
-        int32_t id = new_id[r];
+        int32_t id = new_id[hdr->new_base + r];
         int64_t dst = (int64_t)kept + r;
         next.id[dst] = id;
-        next.arrival[dst] = now;  // enqueued at the time the previous batch finished
+        // a timed arrival keeps its own time; otherwise it is enqueued when the previous batch finished
+        next.arrival[dst] = new_time ? new_time[hdr->new_base + r] : now;
         bool ok = id >= 0 && id < all.n;
         next.off[dst] = ok ? all.off[id] : -1;
         next.len[dst] = ok ? all.len[id] : 0;
@@ -254,6 +297,7 @@ static QView make_qview(const kLPM_queries *q) {
     v.len = q->len;
     v.n_tokens = q->n_tokens;
     v.n = q->n;
+    v.n_live = q->n_live;
     return v;
 }
 
@@ -378,33 +422,60 @@ extern "C" int kLPM_queue_scratch_bytes(int32_t queue_cap, size_t *out_bytes) {
     return KLPM_OK;
 }
 
-extern "C" int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
-                                  const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
-                                  int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock,
-                                  int64_t *ttft, int64_t *matched_accum, void *scratch, size_t scratch_bytes,
-                                  uint32_t *dev_error, kLPM_stream stream_) {
-    if (!queue_ok(cur) || !queue_ok(next) || !queries_ok(all) || batch_cap < 0 || n_new < 0 || !sim_clock || !ttft ||
+static int queue_advance_impl(bool timed, const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
+                              const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
+                              int32_t batch_cap, const ArrivalsView &pend, uint64_t *sim_clock, int64_t *ttft,
+                              int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
+                              hipStream_t stream) {
+    if (!queue_ok(cur) || !queue_ok(next) || !queries_ok(all) || batch_cap < 0 || pend.n < 0 || !sim_clock || !ttft ||
         !scratch || !n_selected)
         return KLPM_EINVAL;
     if (cur->id == next->id || cur->arrival == next->arrival || cur->n == next->n) return KLPM_EINVAL;
-    if ((batch_cap > 0 && (!batch_idx || !match_len)) || (n_new > 0 && !new_id)) return KLPM_EINVAL;
+    if ((batch_cap > 0 && (!batch_idx || !match_len)) || (pend.n > 0 && !pend.id)) return KLPM_EINVAL;
     size_t need = 0;
     kLPM_queue_scratch_bytes(cur->cap, &need);
     if (scratch_bytes < need || ((uintptr_t)scratch & 255u)) return KLPM_EARENA;
-    hipStream_t stream = (hipStream_t)stream_;
     QueueHdr *hdr = (QueueHdr *)scratch;
     size_t words = ((size_t)cur->cap + 31) / 32 + 1;
     uint32_t *bitmap = (uint32_t *)((char *)scratch + 256);
     uint32_t *before = (uint32_t *)((char *)scratch + 256 + align_up(words * 4, 256));
     QueueView c = make_queue_view(cur), n = make_queue_view(next);
     QView a = make_qview(all);
-    hipLaunchKernelGGL(k_queue_retire, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
-                       n_selected, batch_cap, n_new, sim_clock, ttft, hdr, bitmap, before, dev_error);
-    int64_t work = (int64_t)cur->cap + n_new;
+    if (timed)
+        hipLaunchKernelGGL(k_queue_retire<true>, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
+                           n_selected, batch_cap, pend, sim_clock, ttft, hdr, bitmap, before, dev_error);
+    else
+        hipLaunchKernelGGL(k_queue_retire<false>, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
+                           n_selected, batch_cap, pend, sim_clock, ttft, hdr, bitmap, before, dev_error);
+    // survivors come from at most cur->cap positions; how many arrivals join is decided on the device
+    // in the timed case (at most next->cap of them)
+    int64_t work = (int64_t)cur->cap + (timed ? (int64_t)(pend.n < next->cap ? pend.n : next->cap) : (int64_t)pend.n);
     if (work > 0)
         hipLaunchKernelGGL(k_queue_compact, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, c, n, a,
-                           match_len, new_id, hdr, bitmap, before, matched_accum);
+                           match_len, pend.id, pend.time, hdr, bitmap, before, matched_accum);
     return check_launch();
+}
+
+extern "C" int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
+                                  const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
+                                  int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock,
+                                  int64_t *ttft, int64_t *matched_accum, void *scratch, size_t scratch_bytes,
+                                  uint32_t *dev_error, kLPM_stream stream_) {
+    ArrivalsView pend{new_id, nullptr, nullptr, n_new, 0u, 1u};
+    return queue_advance_impl(false, cur, next, all, match_len, batch_idx, n_selected, batch_cap, pend, sim_clock, ttft,
+                              matched_accum, scratch, scratch_bytes, dev_error, (hipStream_t)stream_);
+}
+
+extern "C" int kLPM_queue_advance_timed(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
+                                        const int32_t *match_len, const int32_t *batch_idx,
+                                        const int32_t *n_selected, int32_t batch_cap, const kLPM_arrivals *pending,
+                                        uint64_t *sim_clock, int64_t *ttft, int64_t *matched_accum, void *scratch,
+                                        size_t scratch_bytes, uint32_t *dev_error, kLPM_stream stream_) {
+    if (!pending || pending->n < 0 || !pending->cursor || pending->c_den < 1u) return KLPM_EINVAL;
+    if (pending->n > 0 && (!pending->id || !pending->time)) return KLPM_EINVAL;
+    ArrivalsView pend{pending->id, pending->time, pending->cursor, pending->n, pending->c_num, pending->c_den};
+    return queue_advance_impl(true, cur, next, all, match_len, batch_idx, n_selected, batch_cap, pend, sim_clock, ttft,
+                              matched_accum, scratch, scratch_bytes, dev_error, (hipStream_t)stream_);
 }
 
 extern "C" int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream stream_) {

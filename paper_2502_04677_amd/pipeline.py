@@ -51,7 +51,7 @@ class Scheduler:
         assert batch <= self.cfg.max_batch
         B.kLPM_select(q.arrival, self.match_len, q.n if n is None else n, k, batch, self.phase, self.batch_idx,
                       self.n_selected, self.ws, self.ws_bytes, flags=B.KLPM_SELECT_FIFO if fifo else 0,
-                      max_match=self.cfg.max_prompt_len)
+                      max_match=self.cfg.max_prompt_len, n_live=q.n_live)
 
     def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None) -> None:
         B.kLPM_commit(self.tree, q, self.batch_idx, self.n_selected,
@@ -142,3 +142,54 @@ class OnlineRun:
         s.select(q, k, batch, fifo=True)  # this queue is append-only with stable removal
         s.commit(q, batch)
         self.advance(batch, new_ids)
+
+
+class TimedRun:
+    """Def. 2's timeline on the device: queries join the waiting queue when their arrival time has
+    come, a batch costs (1 + c_attn |x|)(|x| - match) token times per query, an idle scheduler waits
+    for the next arrival.  The queue length lives on the device (``n_live``), so a step never reads
+    anything back; a step on an empty queue with nothing pending is a no-op.
+
+    Times (arrivals, clock, TTFT) count units of 1/c_den of one token's linear prefill time.
+    """
+
+    def __init__(self, sched: Scheduler, all_q: B.DeviceQueries, cap: int, arrival: np.ndarray, c_num: int = 0,
+                 c_den: int = 1, t_start: int = 0):
+        dev = sched.device
+        self.s = sched
+        self.all_q = all_q
+        self.cap = int(cap)
+        self.queues = [B.DeviceQueue.empty(cap, dev), B.DeviceQueue.empty(cap, dev)]
+        self.cur = 0
+        self.pending = B.DeviceArrivals.from_host(arrival, c_num, c_den, dev)
+        self.sim_clock = torch.full((1,), int(t_start), dtype=torch.int64, device=dev)
+        self.ttft = torch.full((max(all_q.n, 1),), -1, dtype=torch.int64, device=dev)
+        self.matched = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.dev_error = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.scratch_bytes = B.kLPM_queue_scratch_bytes(self.cap)
+        self.scratch = B.alloc_aligned(self.scratch_bytes, dev)
+        sched.n_selected.zero_()
+        self._advance(0)  # initial fill: everything that has arrived by t_start, or the first arrival
+
+    @property
+    def queue(self) -> B.DeviceQueue:
+        return self.queues[self.cur]
+
+    def view(self) -> B.DeviceQueries:
+        q = self.queue
+        return B.DeviceQueries(self.all_q.tokens, q.off, q.len, q.arrival, self.cap, n_live=q.n)
+
+    def _advance(self, batch: int) -> None:
+        s = self.s
+        B.kLPM_queue_advance_timed(self.queues[self.cur], self.queues[1 - self.cur], self.all_q, s.match_len,
+                                   s.batch_idx, s.n_selected, batch, self.pending, self.sim_clock, self.ttft,
+                                   self.matched, self.scratch, self.scratch_bytes, self.dev_error)
+        self.cur = 1 - self.cur
+
+    def step(self, k: int, batch: int) -> None:
+        s = self.s
+        q = self.view()
+        s.match(q)
+        s.select(q, k, batch, fifo=True)  # arrivals join in time order, removal is stable
+        s.commit(q, batch)
+        self._advance(batch)

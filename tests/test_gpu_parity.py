@@ -435,3 +435,126 @@ def test_config4_full_size_online_stream():
     stream = W.config4_stream()
     _say(f"config4 full: {stream.queries.n} queries / {stream.queries.tokens.shape[0]} tokens over {stream.steps} steps")
     _run_stream(stream, 8192, snapshot_every=100)
+
+
+# ----------------------------------------------------------------------------- device-side queue length
+def test_select_with_device_side_queue_length():
+    """Buffers sized for a capacity, of which only the first *n_live entries exist: every selection
+    path must ignore what lies beyond (filled here with entries that would win every pick)."""
+    rng = np.random.default_rng(23)
+    dev = "cuda:0"
+    for cap in (300, 6000, 20000):
+        ws_bytes = K.kLPM_select_workspace_bytes(cap)
+        ws = K.alloc_aligned(ws_bytes, dev)
+        phase = torch.zeros(1, dtype=torch.int32, device=dev)
+        nsel = torch.zeros(1, dtype=torch.int32, device=dev)
+        live_d = torch.zeros(1, dtype=torch.int32, device=dev)
+        for live in (0, 1, 2, cap // 3, cap - 1, cap, cap + 50):
+            n = min(live, cap)
+            m = rng.integers(0, 400, size=cap).astype(np.int32)
+            for fifo in (True, False):
+                arrival = rng.integers(0, max(2, cap // 4), size=cap).astype(np.uint64)
+                if fifo:
+                    arrival[:n] = np.sort(arrival[:n])
+                arrival[n:] = 0  # beyond the live part: older and longer than everything
+                m[n:] = 400
+                d_arr = torch.from_numpy(arrival.view(np.int64)).to(dev)
+                d_m = torch.from_numpy(m).to(dev)
+                live_d.fill_(live)
+                for k in (1, 3, 0):
+                    for batch in (1, 7, 256):
+                        out = torch.full((batch,), -7, dtype=torch.int32, device=dev)
+                        phase.fill_(1)
+                        K.kLPM_select(d_arr, d_m, cap, k, batch, phase, out, nsel, ws, ws_bytes,
+                                      flags=K.KLPM_SELECT_FIFO if fifo else 0, max_match=400, n_live=live_d)
+                        idx_ref, ph_ref = oracle.select(arrival[:n], m[:n], k, batch, 1)
+                        got_n = int(nsel.item())
+                        assert got_n == idx_ref.shape[0], (cap, live, fifo, k, batch)
+                        assert out[:got_n].cpu().numpy().tolist() == idx_ref.tolist(), (cap, live, fifo, k, batch)
+                        assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref, (cap, live, fifo, k, batch)
+
+
+def test_match_with_device_side_queue_length():
+    w = W.config0()
+    s, ref, q = _setup(w)
+    want = ref.match(w.queries.tokens, w.queries.off, w.queries.len)
+    live_d = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for live in (0, 1, 100, q.n, q.n + 9):
+        live_d.fill_(live)
+        s.match_len.fill_(-5)
+        ql = K.DeviceQueries(q.tokens, q.off, q.len, q.arrival, q.n, n_live=live_d)
+        got = s.match(ql).cpu().numpy()
+        n = min(live, q.n)
+        assert got[:n].tolist() == want[:n].tolist() and (got[n:q.n] == -5).all()  # the rest is untouched
+
+
+# ----------------------------------------------------------------------------- Def. 2 timeline with timed arrivals
+def _run_timed(p, k, batch, budget, c_num=0, c_den=1, t_start=0, cap=None, check_every=1):
+    """The device-resident timed run against the oracle's event loop: queue contents, match lengths
+    and batch at the checked steps; TTFT of every query, final clock and step count at the end."""
+    cap_o = p.n if cap is None else cap
+    r = oracle.simulate_timed(p, k, batch, budget, c_num=c_num, c_den=c_den, t_start=t_start, queue_cap=cap_o)
+    q = K.DeviceQueries.from_host(p)
+    cfg = K.size_config(0, 0, budget, batch, int(p.len.max()), extra_prompts=2 * batch)
+    s = K.Scheduler(cfg, None, cap_o)
+    run = K.TimedRun(s, q, cap_o, p.arrival, c_num=c_num, c_den=c_den, t_start=t_start)
+    for step in range(r.steps):
+        check = check_every and (step % check_every == 0 or step == r.steps - 1)
+        if check:
+            n_live = int(run.queue.n.item())
+            ids = run.queue.id[:n_live].cpu().numpy()
+            assert ids.tolist() == r.waiting_ids[step].tolist(), step
+        run.step(k, batch)
+        if check:
+            assert s.match_len[:n_live].cpu().numpy().tolist() == r.match_lens[step].tolist(), step
+            assert ids[s.batch()].tolist() == r.batches[step].tolist(), step
+    run.step(k, batch)  # one step past the end: nobody is waiting, nothing is pending, nothing changes
+    torch.cuda.synchronize()
+    assert int(run.queue.n.item()) == 0 and int(run.pending.cursor.item()) == p.n
+    assert int(run.sim_clock.item()) == r.clock
+    assert run.ttft[:p.n].cpu().numpy().tolist() == r.ttft.tolist()
+    assert int(run.dev_error.item()) == 0 and s.read_stats().device_error == 0
+    return r
+
+
+@pytest.mark.parametrize("seed,n,u,rep,d", [(1, 24, 6, 3, 4), (2, 40, 9, 4, 3), (3, 64, 70, 2, 90)])
+def test_timed_shuffled_queue_small(seed, n, u, rep, d):
+    """Regular Arrival Shuffled Queue (Def. 3) served one query at a time with one prompt of cache
+    (the last-prompt cache of Def. 2), from bursts (s = 0) to arrivals slower than the service."""
+    for s_gap in (0, 1, (u + d) // 2, u // rep + d, 3 * (u + d)):
+        for c_num, c_den in ((0, 1), (3, 64)):
+            p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=seed)
+            p.arrival[:] = p.arrival * np.uint64(c_den)
+            for k in (1, rep, K_INF):
+                _say(f"timed small: n={n} u={u} d={d} s={s_gap} c={c_num}/{c_den} k={k}")
+                _run_timed(p, k, 1, u + d, c_num=c_num, c_den=c_den)
+
+
+def test_timed_batches_bounded_queue_and_late_start():
+    """Batches of several queries, a waiting queue smaller than the backlog (arrivals stay outside, in
+    order), a cache of a few prompts, and a start time after part of the stream has arrived."""
+    p, _ = W.shuffled_queue(96, 40, 4, 25, 30, seed=7)
+    for k, batch, cap, t_start in ((2, 4, 16, 0), (K_INF, 3, 8, 500), (4, 8, 96, 1200), (1, 5, 7, 0)):
+        _say(f"timed batched: k={k} B={batch} cap={cap} T={t_start}")
+        _run_timed(p, k, batch, 4 * 65, c_num=1, c_den=128, t_start=t_start, cap=cap)
+
+
+@pytest.mark.parametrize("u,d", [(1000, 5000), (3000, 3000), (5000, 1000)])
+def test_timed_shuffled_queue_paper_shape(u, d):
+    """n = 2000 queries, 4 per shared prefix, prompt length 6000 split as in the paper's table on
+    varying the prefix-length ratio; arrival gap between the per-query cost with and without reuse,
+    so that how much a policy reuses decides whether its backlog grows."""
+    n, rep, c_num, c_den = 2000, 4, 1, 1 << 16
+    gap = ((u // rep + d) + (u + d)) // 2
+    p, _ = W.shuffled_queue(n, u, rep, d, gap, seed=11)
+    p.arrival[:] = p.arrival * np.uint64(c_den)
+    for t_start in (0, gap * n * c_den):  # served while arriving / after everything has arrived (setting of Thm. 2)
+        res = {}
+        for k in (1, rep, K_INF):
+            _say(f"timed paper shape: u={u} d={d} k={k} T={t_start // c_den}")
+            r = _run_timed(p, k, 1, u + d, c_num=c_num, c_den=c_den, t_start=t_start, cap=2048, check_every=500)
+            res[k] = [oracle.percentile_nearest_rank(r.ttft, q) / c_den for q in (0.5, 0.9, 0.95, 0.99)]
+            _say(f"   TTFT P50/P90/P95/P99 (token times): {res[k]}")
+        # more reuse, lower median: LPM <= k-LPM <= FCFS at P50 (Sec. 4.2 and the discussion of the
+        # table on varying the prefix-length ratio)
+        assert res[K_INF][0] <= res[rep][0] <= res[1][0]
