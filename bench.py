@@ -108,6 +108,74 @@ def cpu_baseline(w, allq, steps: int, threads: int):
     return matched / dt, dt, t_match, first_sum
 
 
+def bench_def3(args) -> int:
+    """Second workload: a Regular Arrival Shuffled Queue (Def. 3) at the shape of the paper's table on
+    varying the prefix-length ratio (n = 2000, 4 queries per shared prefix, prompt length 6000), served
+    one query per step with one prompt of cache under Def. 2's timeline with an attention term.  A
+    step is match -> select -> commit -> timed queue advance on a device-resident queue; the queue
+    length never leaves the device."""
+    import torch
+
+    import paper_2502_04677_amd as K
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    n, rep, c_num, c_den = 2000, 4, 1, 1 << 16
+    u, d = args.def3_u, 6000 - args.def3_u
+    gap = ((u // rep + d) + (u + d)) // 2
+    p, _ = W.shuffled_queue(n, u, rep, d, gap, seed=W.generators.SEED_BASE + 100)
+    p.arrival[:] = p.arrival * np.uint64(c_den)
+    k, cap, budget = rep, 2048, u + d
+    q = K.DeviceQueries.from_host(p, dev)
+    cfg = K.size_config(0, 0, budget, 1, u + d, extra_prompts=2)
+
+    def one_run():
+        sched = K.Scheduler(cfg, None, cap, dev)
+        run = K.TimedRun(sched, q, cap, p.arrival, c_num=c_num, c_den=c_den)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):  # one query per step: exactly n steps serve everybody
+            run.step(k, 1)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        assert int(run.queue.n.item()) == 0 and int(run.pending.cursor.item()) == n
+        assert int(run.dev_error.item()) == 0 and sched.read_stats().device_error == 0
+        return dt, run
+
+    for _ in range(args.warmup):
+        one_run()
+    times = []
+    for _ in range(max(1, args.steps // 4)):
+        dt, run = one_run()
+        times.append(dt)
+    dt = float(np.mean(times))
+    ttft = run.ttft[:n].cpu().numpy()
+    matched = int(run.matched.item())
+    out = {
+        "metric": "scheduling steps/sec (match + select + commit + timed queue advance, one query per step)",
+        "value": n / dt, "unit": "steps/s", "n_gpus": 1, "steps": n * len(times), "warmup": n * args.warmup,
+        "ms_per_step": dt / n * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"def3-n{n}-rep{rep}-u{u}-d{d}", "k": k, "batch": 1, "kv_budget_tokens": budget,
+                   "arrival_gap_tokens": gap, "c_attn": c_num / c_den, "queue_cap": cap},
+        "matched_tokens_per_run": matched,
+        "ttft_token_times": {f"p{int(x * 100)}": float(np.sort(ttft)[int(np.ceil(x * n)) - 1]) / c_den
+                             for x in (0.5, 0.9, 0.95, 0.99)},
+        "roofline": None,  # launch-latency bound at this size (a few KB per step); see the large configuration
+    }
+    if args.cpu_steps > 0:
+        import oracle
+
+        t0 = time.perf_counter()
+        r = oracle.simulate_timed(p, k, 1, budget, c_num=c_num, c_den=c_den, queue_cap=cap)
+        cdt = time.perf_counter() - t0
+        assert r.ttft.tolist() == ttft.tolist(), "GPU and oracle disagree on the TTFT of the timed run"
+        out["cpu_baseline"] = {"value": r.steps / cdt, "unit": "steps/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the whole run ({r.steps} steps), {cdt:.2f}s"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +187,9 @@ def main() -> int:
                     help="deep-tree variant of the workload (about 50-90 tokens per tree node)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel over this many MiB (reference point for HBM byte counters)")
+    ap.add_argument("--workload", choices=("cfg2-large", "def3"), default="cfg2-large",
+                    help="def3: the timed Regular Arrival Shuffled Queue run (second workload)")
+    ap.add_argument("--def3-u", type=int, default=3000, help="shared-prefix length of the def3 workload (prompt = 6000)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU; --gpus must be 1 (there is no multi-GPU path to time)",
@@ -130,6 +201,8 @@ def main() -> int:
     import paper_2502_04677_amd as K
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "def3":
+        return bench_def3(args)
     dev = torch.device("cuda:0")
     steps_total = args.steps + args.warmup
     w, allq = build_workload(args.scale, steps_total, args.deep)
