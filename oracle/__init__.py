@@ -11,7 +11,9 @@ Paper passages followed: Algorithm 1 (k-LPM), Def. 1 (query stream), Def. 2
 Sec. 2.1 (bins of B queries finish together; fixed memory pool), Sec. 1
 (radix-tree prefix cache with LRU eviction); ``simulate_timed`` follows Def. 2's
 timeline with the attention term (c_attn >= 0) on queries that arrive at their
-own times (Def. 1, Def. 3).
+own times (Def. 1, Def. 3); ``score_hit_rate`` and ``tie_keys`` are the hit-rate
+score of Algorithm 1's wording and the uniformly random tie-break assumed by the
+theory (footnote of Sec. 4.2), the latter drawn from Philox-4x32-10 (SC'11).
 """
 from __future__ import annotations
 
@@ -63,7 +65,7 @@ def _load():
         L.orc_match.argtypes = [vp, vp, vp, vp, i32, vp]
         L.orc_match_mt.argtypes = [vp, vp, vp, vp, i32, vp, i32]
         L.orc_select.restype = i32
-        L.orc_select.argtypes = [vp, vp, i32, u32, i32, C.POINTER(u32), vp]
+        L.orc_select.argtypes = [vp, vp, vp, i32, u32, i32, C.POINTER(u32), vp]
         L.orc_commit.argtypes = [vp, vp, vp, vp, vp, i32, i64, C.POINTER(_Stats)]
         L.orc_snapshot_bytes.restype = C.c_size_t; L.orc_snapshot_bytes.argtypes = [vp]
         L.orc_snapshot.restype = C.c_size_t; L.orc_snapshot.argtypes = [vp, vp, C.c_size_t]
@@ -148,15 +150,61 @@ class OracleTree:
         return buf.tobytes()
 
 
-def select(arrival, match_len, k: int, batch: int, phase: int = 0) -> Tuple[np.ndarray, int]:
-    """Algorithm 1 over a static score vector, cut at ``batch`` picks. Returns (batch_idx, phase_out)."""
+def select(arrival, match_len, k: int, batch: int, phase: int = 0, tie_key=None) -> Tuple[np.ndarray, int]:
+    """Algorithm 1 over a static score vector, cut at ``batch`` picks. Returns (batch_idx, phase_out).
+
+    ``match_len`` is the score (any int32 vector: match lengths, or ``score_hit_rate``); ``tie_key``
+    (uint32 per query, optional) decides between equal scores before the arrival time does.
+    """
     L = _load()
     arrival, match_len = _c(arrival, np.uint64), _c(match_len, np.int32)
     n = arrival.shape[0]
+    tie = None if tie_key is None else _c(tie_key, np.uint32)
+    assert tie is None or tie.shape[0] == n
     out = np.zeros(max(0, min(batch, n)), dtype=np.int32)
     ph = C.c_uint32(phase)
-    got = L.orc_select(_p(arrival), _p(match_len), n, C.c_uint32(k & 0xFFFFFFFF), batch, C.byref(ph), _p(out))
+    got = L.orc_select(_p(arrival), _p(match_len), None if tie is None else _p(tie), n, C.c_uint32(k & 0xFFFFFFFF),
+                       batch, C.byref(ph), _p(out))
     return out[:got], int(ph.value)
+
+
+def score_hit_rate(match_len, length, scale_bits: int = 30) -> np.ndarray:
+    """Prefix-cache hit *rate* of each query (the wording of Algorithm 1) as an integer score:
+    floor(m * 2^scale_bits / |x|).  Exact as an order of the rationals m/|x| whenever
+    |x| <= 2^(scale_bits/2); beyond that nearly equal rates may share a score."""
+    m = np.maximum(np.asarray(match_len, dtype=np.int64), 0)
+    ln = np.asarray(length, dtype=np.int64)
+    assert 1 <= scale_bits <= 30 and (ln >= 1).all() and (m <= ln).all()
+    return ((m << scale_bits) // ln).astype(np.int32)
+
+
+_PHILOX_M0, _PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key) -> Tuple[int, int, int, int]:
+    """Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as
+    1, 2, 3", SC'11): a keyed bijection of a 128-bit counter; each round multiplies two counter
+    words by fixed odd constants, swaps the halves around and mixes in the key, which moves on by a
+    Weyl constant per round."""
+    c0, c1, c2, c3 = (int(v) & 0xFFFFFFFF for v in counter)
+    k0, k1 = (int(v) & 0xFFFFFFFF for v in key)
+    for r in range(10):
+        if r:
+            k0, k1 = (k0 + _PHILOX_W0) & 0xFFFFFFFF, (k1 + _PHILOX_W1) & 0xFFFFFFFF
+        p0, p1 = _PHILOX_M0 * c0, _PHILOX_M1 * c2
+        c0, c1, c2, c3 = (p1 >> 32) ^ c1 ^ k0, p1 & 0xFFFFFFFF, (p0 >> 32) ^ c3 ^ k1, p0 & 0xFFFFFFFF
+    return c0, c1, c2, c3
+
+
+def tie_keys(seed: int, step: int, ids) -> np.ndarray:
+    """One uniform 32-bit tie key per query and scheduling step: word 0 of Philox-4x32-10 at counter
+    (id, 0, step low, step high) under the key (seed low, seed high).  Redrawn every step, so a
+    query's luck does not persist; independent of where the query sits in the queue."""
+    ids = np.asarray(ids, dtype=np.int64)
+    key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    return np.array([philox4x32_10((int(i), 0, step & 0xFFFFFFFF, (step >> 32) & 0xFFFFFFFF), key)[0] for i in ids],
+                    dtype=np.uint32)
 
 
 def def2_completion(prompts, order, c_attn: float = 0.0, t_start: float = 0.0) -> np.ndarray:

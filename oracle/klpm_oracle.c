@@ -27,6 +27,10 @@
  * all nodes of its path; eviction removes whole leaves, smallest tick first,
  * until the token total is within budget; only commit touches ticks.
  *
+ * Variants: the score handed to orc_select may be the hit rate floor(m 2^b / |x|)
+ * instead of m (the wording of Algorithm 1), and a per-query tie key (uniform
+ * random numbers: the footnote of Sec. 4.2) may decide between equal scores.
+ *
  * Parity pins (tests, CPU-only): brute-force pairwise common prefixes, a
  * literal list-based Algorithm 1, a dictionary-of-paths LRU model, the worked
  * four-query example of Sec. 4.2, and the closed forms in the proof of Thm. 2.
@@ -202,8 +206,11 @@ void orc_match_mt(const OTree *t, const int32_t *tokens, const int64_t *off, con
 
 /* ---- select: Algorithm 1 over a static score vector, cut after B picks ---- */
 /* k == 0 or k == UINT32_MAX encodes k = infinity (pure LPM order, no oldest pick). */
-int32_t orc_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, uint32_t k, int32_t batch,
-                   uint32_t *phase_inout, int32_t *batch_idx) {
+/* tie (may be NULL): a per-query key that decides between equal scores before the arrival time does;
+ * filled with independent uniform numbers it gives the uniformly random tie-break that the
+ * theory of Sec. 4.2 assumes (footnote there). */
+int32_t orc_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie, int32_t n, uint32_t k,
+                   int32_t batch, uint32_t *phase_inout, int32_t *batch_idx) {
     int lpm_only = (k == 0u || k == 0xFFFFFFFFu);
     uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
     char *taken = (char *)calloc((size_t)(n > 0 ? n : 1), 1);
@@ -219,10 +226,14 @@ int32_t orc_select(const uint64_t *arrival, const int32_t *match_len, int32_t n,
                 /* oldest waiting query; equal times -> lower index (i ascending keeps the first) */
                 if (arrival[i] < arrival[best]) best = i;
             } else {
-                /* largest prefix-cache hit; ties -> earlier arrival, then lower index */
-                if (match_len[i] > match_len[best] ||
-                    (match_len[i] == match_len[best] && arrival[i] < arrival[best]))
+                /* largest prefix-cache hit; ties -> smaller tie key (if any), earlier arrival, lower index */
+                if (match_len[i] != match_len[best]) {
+                    if (match_len[i] > match_len[best]) best = i;
+                } else if (tie && tie[i] != tie[best]) {
+                    if (tie[i] < tie[best]) best = i;
+                } else if (arrival[i] < arrival[best]) {
                     best = i;
+                }
             }
         }
         taken[best] = 1;

@@ -118,8 +118,9 @@ class PathModel:
         return head + rec.tobytes() + np.asarray(toks, dtype="<i4").tobytes()
 
 
-def select_literal(arrival, match_len, k, batch, phase):
+def select_literal(arrival, match_len, k, batch, phase, tie_key=None):
     """Algorithm 1 as a loop over a Python list of waiting queries."""
+    tie = [0] * len(arrival) if tie_key is None else [int(v) for v in tie_key]
     inf = k in (0, 0xFFFFFFFF)
     remaining = list(range(len(arrival)))
     out = []
@@ -128,7 +129,7 @@ def select_literal(arrival, match_len, k, batch, phase):
         if not inf and (ph + j) % k == 0:
             p = min(remaining, key=lambda i: (int(arrival[i]), i))
         else:
-            p = min(remaining, key=lambda i: (-int(match_len[i]), int(arrival[i]), i))
+            p = min(remaining, key=lambda i: (-int(match_len[i]), tie[i], int(arrival[i]), i))
         out.append(p)
         remaining.remove(p)
     return out, (0 if inf else (ph + len(out)) % k)

@@ -397,3 +397,86 @@ def test_timed_bounded_queue_keeps_everyone_and_fcfs_order():
     done = r.ttft + p.arrival.astype(np.int64)
     for b in r.batches:
         assert len(set(done[b].tolist())) == 1
+
+
+# ----------------------------------------------------------------------------- score and tie variants
+def test_philox_known_answers():
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [[int(v, 16) for v in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        assert list(oracle.philox4x32_10(r[0:4], r[4:6])) == r[6:10]
+    # a tie key is word 0 at counter (id, 0, step lo, step hi) under key (seed lo, seed hi)
+    assert oracle.tie_keys(0, 0, [0])[0] == rows[0][6]
+    seed, step = (0x299F31D0 << 32) | 0xA4093822, (0x03707344 << 32) | 0x13198A2E
+    assert oracle.philox4x32_10((0x243F6A88, 0, step & 0xFFFFFFFF, step >> 32), (seed & 0xFFFFFFFF, seed >> 32))[0] == \
+        oracle.tie_keys(seed, step, [0x243F6A88])[0]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_select_with_tie_keys_equals_literal_loop(seed):
+    rng = np.random.default_rng(500 + seed)
+    n = int(rng.integers(1, 60))
+    arrival, m = _rand_scores(rng, n)
+    tie = rng.integers(0, 4, size=n).astype(np.uint32) if seed % 2 else oracle.tie_keys(seed, 3, np.arange(n))
+    for k in (1, 2, 3, 5, K_INF):
+        for batch in (1, n // 2 + 1, n + 3):
+            got, ph = oracle.select(arrival, m, k, batch, phase=seed % 3, tie_key=tie)
+            want, ph_want = select_literal(arrival, m, k, batch, seed % 3, tie_key=tie)
+            assert got.tolist() == want and ph == ph_want
+    # a constant tie key changes nothing; oldest picks never look at it
+    base, _ = oracle.select(arrival, m, 3, n, 0)
+    same, _ = oracle.select(arrival, m, 3, n, 0, tie_key=np.full(n, 77, np.uint32))
+    assert base.tolist() == same.tolist()
+    fcfs, _ = oracle.select(arrival, m, 1, n, 0, tie_key=tie)
+    assert fcfs.tolist() == np.lexsort((np.arange(n), arrival)).tolist()
+
+
+def test_random_tie_break_is_uniform_over_the_tied_queries():
+    """Footnote of Sec. 4.2: ties are broken uniformly at random.  Eight queries share the top
+    score; over 4,000 scheduling steps each must be picked first about 500 times, and the order of
+    the first two picks must cover all 56 ordered pairs about evenly."""
+    n, steps = 12, 4000
+    m = np.array([9] * 8 + [1, 2, 3, 4], np.int32)
+    arrival = np.arange(n, dtype=np.uint64)
+    first = np.zeros(8, np.int64)
+    pairs = np.zeros((8, 8), np.int64)
+    for step in range(steps):
+        got, _ = oracle.select(arrival, m, K_INF, 2, 0, tie_key=oracle.tie_keys(20250204677, step, np.arange(n)))
+        assert got[0] < 8 and got[1] < 8
+        first[got[0]] += 1
+        pairs[got[0], got[1]] += 1
+    chi2 = float(((first - steps / 8) ** 2 / (steps / 8)).sum())
+    assert chi2 < 24.3  # 7 degrees of freedom, p = 0.001
+    off = pairs[~np.eye(8, dtype=bool)]
+    chi2 = float(((off - steps / 56) ** 2 / (steps / 56)).sum())
+    assert chi2 < 93.2  # 55 degrees of freedom, p = 0.001
+    # without tie keys the earliest of the tied queries always wins
+    got, _ = oracle.select(arrival, m, K_INF, 2, 0)
+    assert got.tolist() == [0, 1]
+
+
+def test_hit_rate_score_orders_like_the_exact_ratio():
+    from fractions import Fraction
+
+    rng = np.random.default_rng(77)
+    ln = rng.integers(1, 1 << 15, size=400)
+    m = (rng.random(400) * (ln + 1)).astype(np.int64).clip(0, ln)
+    m[:20], m[20:40] = 0, ln[20:40]
+    sc = oracle.score_hit_rate(m, ln, 30)
+    assert (sc[:20] == 0).all() and (sc[20:40] == 1 << 30).all()
+    fr = [Fraction(int(a), int(b)) for a, b in zip(m, ln)]
+    for i in range(400):
+        for j in range(i + 1, 400, 7):
+            assert (sc[i] < sc[j]) == (fr[i] < fr[j]) and (sc[i] == sc[j]) == (fr[i] == fr[j])
+    # equal prompt lengths (the setting of the paper's theory): the rate orders like the match length
+    ln_eq = np.full(50, 1000)
+    m_eq = rng.integers(0, 1001, size=50)
+    arrival = rng.integers(0, 5, size=50).astype(np.uint64)
+    a, _ = oracle.select(arrival, m_eq.astype(np.int32), 3, 50, 0)
+    b, _ = oracle.select(arrival, oracle.score_hit_rate(m_eq, ln_eq, 20), 3, 50, 0)
+    assert a.tolist() == b.tolist()
+    # and where lengths differ the two keys disagree: a short prompt cached in full beats a long half-cached one
+    a, _ = oracle.select(np.zeros(2, np.uint64), np.array([500, 40], np.int32), K_INF, 1, 0)
+    b, _ = oracle.select(np.zeros(2, np.uint64), oracle.score_hit_rate([500, 40], [1000, 40]), K_INF, 1, 0)
+    assert a.tolist() == [0] and b.tolist() == [1]
