@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TIE_SEED = 2502046770
 
 
 def log(msg: str) -> None:
@@ -73,7 +74,7 @@ def build_workload(scale: float, steps_total: int, deep: bool = False):
     return w, allq
 
 
-def cpu_baseline(w, allq, steps: int, threads: int):
+def cpu_baseline(w, allq, steps: int, threads: int, rate_bits: int = 0, random_ties: bool = False):
     """The oracle run over the first `steps` steps of the same workload (match on `threads` host
     threads, select and commit serial), timed without the tree build."""
     import oracle
@@ -85,7 +86,7 @@ def cpu_baseline(w, allq, steps: int, threads: int):
     enq = np.zeros(allq.n, dtype=np.uint64)
     enq[:n0] = w.queries.arrival
     clock, phase, matched = 0, 0, 0
-    first_sum = None
+    step_sums = []
     t_match = 0.0
     t0 = time.perf_counter()
     for s in range(steps):
@@ -93,7 +94,9 @@ def cpu_baseline(w, allq, steps: int, threads: int):
         ta = time.perf_counter()
         m = tree.match(allq.tokens, off, ln, threads=threads)
         t_match += time.perf_counter() - ta
-        idx, phase = oracle.select(arr, m, w.k, batch, phase)
+        sc = oracle.score_hit_rate(m, ln, rate_bits) if rate_bits else m
+        tk = oracle.tie_keys(TIE_SEED, s, waiting) if random_ties else None
+        idx, phase = oracle.select(arr, sc, w.k, batch, phase, tie_key=tk)
         tree.commit(allq.tokens, off, ln, idx, w.budget)
         clock += max(1, int((ln[idx].astype(np.int64) - m[idx]).sum()))
         keep = np.ones(waiting.shape[0], dtype=bool)
@@ -102,10 +105,9 @@ def cpu_baseline(w, allq, steps: int, threads: int):
         enq[new] = clock
         waiting = np.concatenate([waiting[keep], new])
         matched += int(m.sum())
-        if first_sum is None:
-            first_sum = int(m.sum())
+        step_sums.append(int(m.sum()))
     dt = time.perf_counter() - t0
-    return matched / dt, dt, t_match, first_sum
+    return matched / dt, dt, t_match, step_sums
 
 
 def bench_def3(args) -> int:
@@ -187,6 +189,9 @@ def main() -> int:
                     help="deep-tree variant of the workload (about 50-90 tokens per tree node)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel over this many MiB (reference point for HBM byte counters)")
+    ap.add_argument("--score", choices=("length", "rate"), default="length",
+                    help="what longest-match picks maximise: match length (default) or hit rate m/|x|")
+    ap.add_argument("--random-ties", action="store_true", help="break score ties uniformly at random (Philox keys)")
     ap.add_argument("--workload", choices=("cfg2-large", "def3"), default="cfg2-large",
                     help="def3: the timed Regular Arrival Shuffled Queue run (second workload)")
     ap.add_argument("--def3-u", type=int, default=3000, help="shared-prefix length of the def3 workload (prompt = 6000)")
@@ -226,12 +231,21 @@ def main() -> int:
     sums = torch.zeros(steps_total, dtype=torch.int64, device=dev)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps_total)]
 
+    rate_bits = 26  # two 13-bit histogram levels; exact as a ratio order for prompts up to 8,192 tokens
+    score = torch.zeros(n0, dtype=torch.int32, device=dev) if args.score == "rate" else None
+    tie = torch.zeros(n0, dtype=torch.int32, device=dev) if args.random_ties else None
+
     def one_step(s: int) -> None:
         q = run.view()
         ev[s][0].record()
         sched.match(q)
         ev[s][1].record()
-        sched.select(q, k, batch, fifo=True)  # the queue is kept in arrival order
+        if score is not None:  # hit rate instead of match length (the wording of Algorithm 1)
+            K.kLPM_score_hit_rate(sched.match_len, q.len, n0, rate_bits, score)
+        if tie is not None:  # uniformly random tie-break, redrawn every step, keyed by query id
+            K.kLPM_tie_keys(TIE_SEED, s, run.queue.id, n0, tie)
+        # the queue is kept in arrival order
+        sched.select(q, k, batch, fifo=True, score=score, score_max=1 << rate_bits, tie_key=tie)
         ev[s][2].record()
         sched.commit(q, batch)
         ev[s][3].record()
@@ -285,7 +299,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name if args.scale == 1.0 else f"{w.name}-scale{args.scale}",
                    "cache_tokens": int(st.total_tokens), "tree_nodes": int(st.n_nodes), "waiting_queries": n0,
-                   "batch": batch, "k": k, "kv_budget_tokens": int(w.budget), "max_prompt_len": max_len},
+                   "batch": batch, "k": k, "kv_budget_tokens": int(w.budget), "max_prompt_len": max_len,
+                   "score": args.score, "ties": "random" if args.random_ties else "arrival"},
         "schedule_latency_us": elapsed / args.steps * 1e6,
         "phase_ms": {"match": float(match_ms.mean()), "select": float(select_ms.mean()),
                      "commit": float(commit_ms.mean()), "queue_advance": float(adv_ms.mean())},
@@ -302,8 +317,10 @@ def main() -> int:
         cores = len(os.sched_getaffinity(0))
         threads = max(1, min(cores, 16))
         cpu_steps = min(args.cpu_steps, steps_total)
-        v, dt, t_match, first_sum = cpu_baseline(w, allq, cpu_steps, threads)
-        assert first_sum == int(sums_h[0]), f"GPU and oracle disagree on step 0: {int(sums_h[0])} vs {first_sum}"
+        v, dt, t_match, step_sums = cpu_baseline(w, allq, cpu_steps, threads, rate_bits if score is not None else 0,
+                                                 args.random_ties)
+        # matched tokens of every sampled step: they depend on all earlier selections and commits
+        assert step_sums == [int(v) for v in sums_h[:cpu_steps]], f"GPU and oracle disagree: {sums_h[:cpu_steps]} vs {step_sums}"
         out["cpu_baseline"] = {"value": v, "unit": "tokens/s", "cores": threads, "kind": "oracle",
                                "sample": f"first {cpu_steps} steps of the same workload (match on {threads} threads, "
                                          f"select/commit serial), {dt:.1f}s; match alone {t_match:.2f}s"}

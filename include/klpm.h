@@ -118,7 +118,14 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * Slot j of the batch is the oldest remaining query if (phase + j) mod k == 0, otherwise the
  * remaining query with the longest match; ties go to the earlier arrival, then the lower index.
  * k = 1 is FCFS; k = 0 or KLPM_K_INFINITY is pure LPM order (Sec. 4).
- *   arrival, match_len  DEVICE [n] in (a negative match_len counts as 0)
+ *   arrival, match_len  DEVICE [n] in (a negative match_len counts as 0).  match_len is the score of
+ *                       the longest-match picks: the match lengths, or any other int32 score such as
+ *                       the hit rate written by kLPM_score_hit_rate
+ *   tie_key             DEVICE [n] or NULL: decides between equal scores before the arrival time
+ *                       does (smaller key first); kLPM_tie_keys fills it with uniform random numbers
+ *                       for the random tie-break that the theory assumes (footnote of Sec. 4.2).
+ *                       Oldest picks never look at it.  With tie keys the selection always takes
+ *                       the sorting path, whatever `flags` says
  *   n_live              DEVICE [1] or NULL: as in kLPM_queries, the queue holds min(n, max(0, *n_live))
  *                       entries; n then only sizes the launches and the workspace
  *   flags               0 or KLPM_SELECT_FIFO
@@ -132,9 +139,28 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  *   workspace           DEVICE, >= kLPM_select_workspace_bytes(n), 256-byte aligned
  * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
  */
-int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, const int32_t *n_live, uint32_t k,
+int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
+                const int32_t *n_live, uint32_t k,
                 int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                 void *workspace, size_t workspace_bytes, kLPM_stream stream);
+
+/*
+ * Prefix-cache hit *rate* (the wording of Algorithm 1) as a score for kLPM_select:
+ * score[i] = floor(match_len[i] * 2^scale_bits / len[i]), 1 <= scale_bits <= 30.  It orders the
+ * queries exactly like the ratios m/|x| whenever every |x| <= 2^(scale_bits/2); beyond that
+ * nearly equal rates may share a score (and then count as tied).  All arrays DEVICE [n].
+ */
+int kLPM_score_hit_rate(const int32_t *match_len, const int32_t *len, int32_t n, const int32_t *n_live,
+                        int32_t scale_bits, int32_t *score, kLPM_stream stream);
+
+/*
+ * Uniform 32-bit tie keys, one per query, redrawn for every scheduling step:
+ * tie_key[i] = word 0 of Philox-4x32-10 (Salmon et al., SC'11) at counter
+ * (id[i], 0, step low, step high) under the key (seed low, seed high); id = NULL uses i itself.
+ *   id       DEVICE [n] or NULL     tie_key  DEVICE [n] out
+ */
+int kLPM_tie_keys(uint64_t seed, uint64_t step, const int32_t *id, int32_t n, const int32_t *n_live,
+                  uint32_t *tie_key, kLPM_stream stream);
 
 /*
  * Commit a batch: for each admitted prompt, in pick order, give it the next tick of the logical

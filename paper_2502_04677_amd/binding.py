@@ -24,6 +24,7 @@ DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
+    "kLPM_score_hit_rate", "kLPM_tie_keys",
     "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
     "kLPM_read_stats",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
@@ -64,12 +65,18 @@ def load_library() -> C.CDLL:
         from . import build as _build  # compiles with hipcc; raises if that is impossible
         _build.build()
     lib = C.CDLL(_LIB_PATH)
+    missing = [name for name in EXPORTS if not hasattr(lib, name)]
+    if missing:
+        raise ImportError(f"{_LIB_PATH} is older than its sources (no {', '.join(missing)}): rebuild it with "
+                          "`python paper_2502_04677_amd/build.py` or __graft_entry__.build()")
     vp, i32, i64, u32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_size_t
     lib.kLPM_arena_bytes.argtypes = [C.POINTER(Config), C.POINTER(sz)]
     lib.kLPM_build_tree.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, sz, C.POINTER(Queries), vp]
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select.argtypes = [vp, vp, i32, vp, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select.argtypes = [vp, vp, vp, i32, vp, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_score_hit_rate.argtypes = [vp, vp, i32, vp, i32, vp, vp]
+    lib.kLPM_tie_keys.argtypes = [C.c_uint64, C.c_uint64, vp, i32, vp, vp, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
     lib.kLPM_set_budget.argtypes = [vp, i64]
     lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
@@ -211,10 +218,23 @@ def alloc_aligned(nbytes: int, device) -> Tuple[torch.Tensor, int]:
 def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, batch: int,
                 phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
                 workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None, flags: int = 0,
-                max_match: int = 0, n_live: Optional[torch.Tensor] = None) -> None:
-    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), int(n), _ptr(n_live), C.c_uint32(k & 0xFFFFFFFF), int(batch),
+                max_match: int = 0, n_live: Optional[torch.Tensor] = None,
+                tie_key: Optional[torch.Tensor] = None) -> None:
+    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), _ptr(tie_key), int(n), _ptr(n_live), C.c_uint32(k & 0xFFFFFFFF), int(batch),
                             C.c_uint32(flags), int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
+
+
+def kLPM_score_hit_rate(match_len: torch.Tensor, length: torch.Tensor, n: int, scale_bits: int, score: torch.Tensor,
+                        n_live: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(_lib.kLPM_score_hit_rate(_ptr(match_len), _ptr(length), int(n), _ptr(n_live), int(scale_bits), _ptr(score),
+                                    _stream(stream)), "kLPM_score_hit_rate")
+
+
+def kLPM_tie_keys(seed: int, step: int, ids: Optional[torch.Tensor], n: int, tie_key: torch.Tensor,
+                  n_live: Optional[torch.Tensor] = None, stream=None) -> None:
+    _check(_lib.kLPM_tie_keys(C.c_uint64(seed & (2**64 - 1)), C.c_uint64(step & (2**64 - 1)), _ptr(ids), int(n),
+                              _ptr(n_live), _ptr(tie_key), _stream(stream)), "kLPM_tie_keys")
 
 
 def kLPM_commit(tree: Tree, q: DeviceQueries, batch_idx: Optional[torch.Tensor], n_selected: Optional[torch.Tensor],

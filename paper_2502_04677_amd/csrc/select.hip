@@ -47,8 +47,10 @@ __global__ __launch_bounds__(256) void k_sel_init(const uint64_t *__restrict__ a
 
 // keys for the longest-match order, laid out in oldest-first order so that a stable sort on the
 // match length alone yields (-match_len, arrival, index)
+// (with tie keys: (-match_len, tie key, arrival, index); the tie key goes below the inverted length)
 __global__ __launch_bounds__(256) void k_sel_lkeys(const uint32_t *__restrict__ order_a,
-                                                   const int32_t *__restrict__ match_len, LiveN nn,
+                                                   const int32_t *__restrict__ match_len,
+                                                   const uint32_t *__restrict__ tie_key, LiveN nn,
                                                    uint64_t *__restrict__ key, uint32_t *__restrict__ val) {
     const int32_t n = nn.get();
     int32_t r = blockIdx.x * blockDim.x + threadIdx.x;
@@ -56,7 +58,8 @@ __global__ __launch_bounds__(256) void k_sel_lkeys(const uint32_t *__restrict__ 
         uint32_t i = order_a[r];
         int32_t m = match_len[i];
         if (m < 0) m = 0;
-        key[r] = (uint64_t)(0x7FFFFFFFu - (uint32_t)m);
+        uint64_t inv = (uint64_t)(0x7FFFFFFFu - (uint32_t)m);
+        key[r] = tie_key ? ((inv << 32) | (uint64_t)tie_key[i]) : inv;
         val[r] = i;
     }
 }
@@ -925,9 +928,71 @@ static void carve(SelectWs &ws, char *base, int32_t n, size_t *used) {
     *used = o;
 }
 
+// ---- score and tie-key variants of Algorithm 1 ----
+// Hit rate of Algorithm 1's wording as an integer score: floor(m * 2^bits / |x|).
+__global__ __launch_bounds__(256) void k_score_hit_rate(const int32_t *__restrict__ match_len,
+                                                        const int32_t *__restrict__ len, LiveN nn, int bits,
+                                                        int32_t *__restrict__ score) {
+    const int32_t n = nn.get();
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    int64_t m = match_len[i], l = len[i];
+    m = m < 0 ? 0 : m;
+    l = l < 1 ? 1 : l;
+    m = m > l ? l : m;
+    score[i] = (int32_t)((uint64_t)(m << bits) / (uint64_t)l);
+}
+
+// Philox-4x32 with 10 rounds (Salmon et al., SC'11): each round multiplies counter words 0 and 2 by
+// two fixed odd constants, crosses the halves over and mixes in the key; the key advances by a Weyl
+// constant between rounds.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                        uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+    }
+    return c0;
+}
+
+__global__ __launch_bounds__(256) void k_tie_keys(uint64_t seed, uint64_t step, const int32_t *__restrict__ id, LiveN nn,
+                                                  uint32_t *__restrict__ tie_key) {
+    const int32_t n = nn.get();
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint32_t c0 = id ? (uint32_t)id[i] : (uint32_t)i;
+    tie_key[i] = philox4x32_10_word0(c0, 0u, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
 }  // namespace klpm
 
 using namespace klpm;
+
+extern "C" int kLPM_score_hit_rate(const int32_t *match_len, const int32_t *len, int32_t n, const int32_t *n_live,
+                                   int32_t scale_bits, int32_t *score, kLPM_stream stream) {
+    if (n < 0 || scale_bits < 1 || scale_bits > 30) return KLPM_EINVAL;
+    if (n == 0) return KLPM_OK;
+    if (!match_len || !len || !score) return KLPM_EINVAL;
+    hipLaunchKernelGGL(k_score_hit_rate, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, match_len,
+                       len, LiveN{n, n_live}, (int)scale_bits, score);
+    return check_launch();
+}
+
+extern "C" int kLPM_tie_keys(uint64_t seed, uint64_t step, const int32_t *id, int32_t n, const int32_t *n_live,
+                             uint32_t *tie_key, kLPM_stream stream) {
+    if (n < 0) return KLPM_EINVAL;
+    if (n == 0) return KLPM_OK;
+    if (!tie_key) return KLPM_EINVAL;
+    hipLaunchKernelGGL(k_tie_keys, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, seed, step, id,
+                       LiveN{n, n_live}, tie_key);
+    return check_launch();
+}
 
 extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
     if (n < 0 || !out_bytes) return KLPM_EINVAL;
@@ -940,7 +1005,8 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
     return KLPM_OK;
 }
 
-extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, int32_t n, const int32_t *n_live,
+extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
+                           const int32_t *n_live,
                            uint32_t k, int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                            void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
@@ -948,7 +1014,8 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, in
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
     const LiveN nn{n, n_live};
-    if ((flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0) {
+    // (tie keys reorder the longest-match order within equal scores: that needs the full sort)
+    if ((flags & KLPM_SELECT_FIFO) && !tie_key && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0) {
         if (n <= kFqSingleBlockN) {
             hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, nn, k, batch,
                                phase_inout, batch_idx, n_selected);
@@ -976,9 +1043,10 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, in
         if (k != 1u) {
             // stable sort of the oldest-first order by descending match length
             uint32_t *spare = first ? ws.val_b : ws.val_a;
-            hipLaunchKernelGGL(k_sel_lkeys, dim3(g), dim3(256), 0, stream, order_a, match_len, nn, ws.key_a, ws.val_c);
+            hipLaunchKernelGGL(k_sel_lkeys, dim3(g), dim3(256), 0, stream, order_a, match_len, tie_key, nn, ws.key_a,
+                               ws.val_c);
             bool lfirst = true;
-            rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, spare, nn, 4, ws, stream, &lfirst);
+            rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, spare, nn, tie_key ? 8 : 4, ws, stream, &lfirst);
             if (rc) return rc;
             order_l = lfirst ? ws.val_c : spare;
             hipLaunchKernelGGL(k_sel_ranks, dim3(g), dim3(256), 0, stream, order_a, order_l, nn, ws.rank_a, ws.rank_l);

@@ -46,12 +46,17 @@ class Scheduler:
         assert q.n <= self.n_max
         return B.kLPM_match(self.tree, q, self.match_len, self.last_node if want_nodes else None)
 
-    def select(self, q: B.DeviceQueries, k: int, batch: int, n: Optional[int] = None, fifo: bool = False) -> None:
-        """``fifo`` promises that the queue is in arrival order (checked on the device)."""
+    def select(self, q: B.DeviceQueries, k: int, batch: int, n: Optional[int] = None, fifo: bool = False,
+               score: Optional[torch.Tensor] = None, score_max: int = 0, tie_key: Optional[torch.Tensor] = None) -> None:
+        """``fifo`` promises that the queue is in arrival order (checked on the device).  ``score``
+        (default: the match lengths of the last ``match``) is what longest-match picks maximise,
+        ``score_max`` its upper bound; ``tie_key`` decides between equal scores."""
         assert batch <= self.cfg.max_batch
-        B.kLPM_select(q.arrival, self.match_len, q.n if n is None else n, k, batch, self.phase, self.batch_idx,
-                      self.n_selected, self.ws, self.ws_bytes, flags=B.KLPM_SELECT_FIFO if fifo else 0,
-                      max_match=self.cfg.max_prompt_len, n_live=q.n_live)
+        B.kLPM_select(q.arrival, self.match_len if score is None else score, q.n if n is None else n, k, batch,
+                      self.phase, self.batch_idx, self.n_selected, self.ws, self.ws_bytes,
+                      flags=B.KLPM_SELECT_FIFO if fifo else 0,
+                      max_match=self.cfg.max_prompt_len if score is None else score_max, n_live=q.n_live,
+                      tie_key=tie_key)
 
     def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None) -> None:
         B.kLPM_commit(self.tree, q, self.batch_idx, self.n_selected,

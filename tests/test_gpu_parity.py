@@ -558,3 +558,96 @@ def test_timed_shuffled_queue_paper_shape(u, d):
         # more reuse, lower median: LPM <= k-LPM <= FCFS at P50 (Sec. 4.2 and the discussion of the
         # table on varying the prefix-length ratio)
         assert res[K_INF][0] <= res[rep][0] <= res[1][0]
+
+
+# ----------------------------------------------------------------------------- score and tie variants of Algorithm 1
+def test_hit_rate_score_and_tie_keys_match_the_oracle():
+    rng = np.random.default_rng(31)
+    dev = "cuda:0"
+    for n in (1, 257, 5000):
+        ln = rng.integers(1, 70000, size=n).astype(np.int32)
+        m = (rng.random(n) * (ln + 1)).astype(np.int64).clip(0, ln).astype(np.int32)
+        m[: n // 8], m[n // 8: n // 4] = 0, ln[n // 8: n // 4]
+        d_m, d_ln = torch.from_numpy(m).to(dev), torch.from_numpy(ln).to(dev)
+        score = torch.zeros(n, dtype=torch.int32, device=dev)
+        for bits in (30, 20, 1):
+            K.kLPM_score_hit_rate(d_m, d_ln, n, bits, score)
+            assert score.cpu().numpy().tolist() == oracle.score_hit_rate(m, ln, bits).tolist(), (n, bits)
+        tie = torch.zeros(n, dtype=torch.int32, device=dev)
+        ids = rng.integers(0, 2**31 - 1, size=n).astype(np.int32)
+        for seed, step in ((0, 0), (2502046770, 17), ((0xDEADBEEF << 32) | 0x12345678, (5 << 32) | 9)):
+            K.kLPM_tie_keys(seed, step, None, n, tie)
+            assert tie.cpu().numpy().view(np.uint32).tolist() == oracle.tie_keys(seed, step, np.arange(n)).tolist()
+            K.kLPM_tie_keys(seed, step, torch.from_numpy(ids).to(dev), n, tie)
+            assert tie.cpu().numpy().view(np.uint32).tolist() == oracle.tie_keys(seed, step, ids).tolist()
+
+
+def test_select_with_random_ties_and_hit_rate_score():
+    rng = np.random.default_rng(37)
+    dev = "cuda:0"
+    for n in (1, 40, 3000, 20000):
+        ws_bytes = K.kLPM_select_workspace_bytes(n)
+        ws = K.alloc_aligned(ws_bytes, dev)
+        phase = torch.zeros(1, dtype=torch.int32, device=dev)
+        nsel = torch.zeros(1, dtype=torch.int32, device=dev)
+        live_d = torch.zeros(1, dtype=torch.int32, device=dev)
+        ln = rng.integers(1, 3000, size=n).astype(np.int32)
+        m = np.minimum(rng.integers(0, 6, size=n) * 500, ln).astype(np.int32)  # few distinct values: big tie classes
+        arrival = np.sort(rng.integers(0, max(2, n // 3), size=n)).astype(np.uint64)
+        d_arr = torch.from_numpy(arrival.view(np.int64)).to(dev)
+        d_m, d_ln = torch.from_numpy(m).to(dev), torch.from_numpy(ln).to(dev)
+        score = torch.zeros(n, dtype=torch.int32, device=dev)
+        K.kLPM_score_hit_rate(d_m, d_ln, n, 30, score)
+        sc_ref = oracle.score_hit_rate(m, ln, 30)
+        tie = torch.zeros(n, dtype=torch.int32, device=dev)
+        for step, live in ((0, n), (1, max(1, n // 2))):
+            K.kLPM_tie_keys(99, step, None, n, tie)
+            tie_ref = oracle.tie_keys(99, step, np.arange(n))
+            assert tie.cpu().numpy().view(np.uint32).tolist() == tie_ref.tolist()
+            live_d.fill_(live)
+            for which, d_s, s_ref in (("length", d_m, m), ("rate", score, sc_ref)):
+                for k in (1, 2, 7, 0):
+                    for batch in (1, 33, 1024):
+                        for flags in (0, K.KLPM_SELECT_FIFO):
+                            out = torch.full((batch,), -3, dtype=torch.int32, device=dev)
+                            phase.fill_(1)
+                            K.kLPM_select(d_arr, d_s, n, k, batch, phase, out, nsel, ws, ws_bytes, flags=flags,
+                                          max_match=1 << 30, n_live=live_d, tie_key=tie)
+                            idx_ref, ph_ref = oracle.select(arrival[:live], s_ref[:live], k, batch, 1, tie_key=tie_ref[:live])
+                            got_n = int(nsel.item())
+                            assert got_n == idx_ref.shape[0]
+                            assert out[:got_n].cpu().numpy().tolist() == idx_ref.tolist(), (n, which, k, batch, flags)
+                            assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
+        # the hit-rate score without tie keys also runs on the arrival-ordered paths
+        for k in (3, 0):
+            out = torch.full((64,), -3, dtype=torch.int32, device=dev)
+            phase.fill_(0)
+            K.kLPM_select(d_arr, score, n, k, 64, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO,
+                          max_match=1 << 30)
+            idx_ref, _ = oracle.select(arrival, sc_ref, k, 64, 0)
+            assert out[: int(nsel.item())].cpu().numpy().tolist() == idx_ref.tolist(), (n, k)
+
+
+def test_steps_with_hit_rate_score_and_random_ties_keep_the_tree_in_step():
+    """Whole steps (match -> score -> tie keys -> select -> commit) under the variant rules."""
+    w = W.config0()
+    s, ref, q = _setup(w, budget=9000)
+    hq = w.queries
+    score = torch.zeros(q.n, dtype=torch.int32, device="cuda:0")
+    tie = torch.zeros(q.n, dtype=torch.int32, device="cuda:0")
+    phase = 0
+    for step in range(4):
+        m = s.match(q).cpu().numpy()
+        m_ref = ref.match(hq.tokens, hq.off, hq.len)
+        assert (m == m_ref).all()
+        K.kLPM_score_hit_rate(s.match_len, q.len, q.n, 24, score)
+        K.kLPM_tie_keys(7, step, None, q.n, tie)
+        s.set_phase(phase)
+        K.kLPM_select(q.arrival, score, q.n, 3, 32, s.phase, s.batch_idx, s.n_selected, s.ws, s.ws_bytes, tie_key=tie)
+        idx_ref, phase = oracle.select(hq.arrival, oracle.score_hit_rate(m_ref, hq.len, 24), 3, 32, phase,
+                                       tie_key=oracle.tie_keys(7, step, np.arange(q.n)))
+        assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == phase
+        s.commit(q, 32)
+        ref.commit(hq.tokens, hq.off, hq.len, idx_ref, 9000)
+        assert s.read_stats().device_error == 0
+        _same_tree(s, ref)

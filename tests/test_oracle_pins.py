@@ -406,6 +406,13 @@ def test_philox_known_answers():
     assert len(rows) == 3
     for r in rows:
         assert list(oracle.philox4x32_10(r[0:4], r[4:6])) == r[6:10]
+    # the array form used for tie keys runs the same rounds
+    rng = np.random.default_rng(3)
+    ids = rng.integers(0, 2**31, size=50)
+    for seed, step in ((0, 0), (rows[2][4] | (rows[2][5] << 32), 12345678901234)):
+        want = [oracle.philox4x32_10((int(i), 0, step & 0xFFFFFFFF, step >> 32), (seed & 0xFFFFFFFF, seed >> 32))[0]
+                for i in ids]
+        assert oracle.tie_keys(seed, step, ids).tolist() == want
     # a tie key is word 0 at counter (id, 0, step lo, step hi) under key (seed lo, seed hi)
     assert oracle.tie_keys(0, 0, [0])[0] == rows[0][6]
     seed, step = (0x299F31D0 << 32) | 0xA4093822, (0x03707344 << 32) | 0x13198A2E
