@@ -69,6 +69,8 @@ def _load():
         L.orc_commit.argtypes = [vp, vp, vp, vp, vp, i32, i64, C.POINTER(_Stats)]
         L.orc_snapshot_bytes.restype = C.c_size_t; L.orc_snapshot_bytes.argtypes = [vp]
         L.orc_snapshot.restype = C.c_size_t; L.orc_snapshot.argtypes = [vp, vp, C.c_size_t]
+        L.orc_select_dynamic.restype = i32
+        L.orc_select_dynamic.argtypes = [vp, vp, vp, vp, vp, i32, u32, i32, C.POINTER(u32), vp]
         L.orc_def2.argtypes = [vp, vp, vp, vp, vp, i32, C.c_double, C.c_double, vp]
         _lib = L
     return _lib
@@ -166,6 +168,25 @@ def select(arrival, match_len, k: int, batch: int, phase: int = 0, tie_key=None)
     got = L.orc_select(_p(arrival), _p(match_len), None if tie is None else _p(tie), n, C.c_uint32(k & 0xFFFFFFFF),
                        batch, C.byref(ph), _p(out))
     return out[:got], int(ph.value)
+
+
+def select_dynamic(prompts_tokens, off, length, arrival, match_len, k: int, batch: int,
+                   phase: int = 0) -> Tuple[np.ndarray, int, np.ndarray]:
+    """Algorithm 1 with in-batch rescoring: after every pick p the score of each remaining query i
+    becomes max(score_i, overlap(x_i, x_p)) - the cache holds what it has processed (Sec. 1), and
+    Def. 2 credits a query with what the prompts before it left there.  Returns (batch_idx,
+    phase_out, scores): a picked query's entry of ``scores`` is its score when it was picked."""
+    L = _load()
+    tok, off, ln = _c(prompts_tokens, np.int32), _c(off, np.int64), _c(length, np.int32)
+    arrival = _c(arrival, np.uint64)
+    score = np.array(match_len, dtype=np.int32, copy=True)
+    n = arrival.shape[0]
+    assert off.shape[0] == n and ln.shape[0] == n and score.shape[0] == n
+    out = np.zeros(max(0, min(batch, n)), dtype=np.int32)
+    ph = C.c_uint32(phase)
+    got = L.orc_select_dynamic(_p(tok), _p(off), _p(ln), _p(arrival), _p(score), n, C.c_uint32(k & 0xFFFFFFFF), batch,
+                               C.byref(ph), _p(out))
+    return out[:got], int(ph.value), score
 
 
 def score_hit_rate(match_len, length, scale_bits: int = 30) -> np.ndarray:

@@ -244,6 +244,53 @@ int32_t orc_select(const uint64_t *arrival, const int32_t *match_len, const uint
     return n_out;
 }
 
+static int32_t overlap(const int32_t *a, int32_t la, const int32_t *b, int32_t lb) {
+    int32_t lim = la < lb ? la : lb, j = 0;
+    while (j < lim && a[j] == b[j]) j++;
+    return j;
+}
+
+/* ---- select with in-batch rescoring (the dynamic rule of Def. 2 inside one bin) ----
+ * Def. 2 credits a query with its overlap with the prompt processed just before it; with a cache
+ * that keeps what it has processed, a query picked later in the same bin overlaps with the cached
+ * strings *and* with every prompt picked before it in the bin.  So after each pick p the score of
+ * every remaining query i becomes max(score_i, overlap(x_i, x_p)); Algorithm 1's rule is applied to
+ * the current scores.  score[] holds the match lengths against the cache on entry and, on return,
+ * for a picked query its score when it was picked, for the others their final score. */
+int32_t orc_select_dynamic(const int32_t *tokens, const int64_t *off, const int32_t *len, const uint64_t *arrival,
+                           int32_t *score, int32_t n, uint32_t k, int32_t batch, uint32_t *phase_inout,
+                           int32_t *batch_idx) {
+    int lpm_only = (k == 0u || k == 0xFFFFFFFFu);
+    uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
+    char *taken = (char *)calloc((size_t)(n > 0 ? n : 1), 1);
+    int32_t n_out = batch < n ? batch : n;
+    if (n_out < 0) n_out = 0;
+    for (int32_t j = 0; j < n_out; j++) {
+        int oldest_slot = !lpm_only && ((phase + (uint32_t)j) % k == 0u);
+        int32_t best = -1;
+        for (int32_t i = 0; i < n; i++) {
+            if (taken[i]) continue;
+            if (best < 0) { best = i; continue; }
+            if (oldest_slot) {
+                if (arrival[i] < arrival[best]) best = i;
+            } else if (score[i] > score[best] || (score[i] == score[best] && arrival[i] < arrival[best])) {
+                best = i;
+            }
+        }
+        if (best < 0) break; /* cannot happen: n_out <= n */
+        taken[best] = 1;
+        batch_idx[j] = best;
+        for (int32_t i = 0; i < n; i++) {
+            if (taken[i]) continue;
+            int32_t ov = overlap(tokens + off[i], len[i], tokens + off[best], len[best]);
+            if (ov > score[i]) score[i] = ov;
+        }
+    }
+    free(taken);
+    *phase_inout = lpm_only ? 0u : (uint32_t)(((uint64_t)phase + (uint64_t)n_out) % k);
+    return n_out;
+}
+
 /* ---- commit: insert admitted prompts in pick order, then LRU-evict to the budget ---- */
 static void split_edge(OTree *t, ONode *v, int32_t j) {
     /* v keeps tok[0..j); a new lower node takes tok[j..len), v's children and v's old tick */
@@ -344,11 +391,6 @@ size_t orc_snapshot(const OTree *t, void *buf, size_t cap) {
 }
 
 /* ---- Def. 2: completion times for a given processing order (last-prompt cache model) ---- */
-static int32_t overlap(const int32_t *a, int32_t la, const int32_t *b, int32_t lb) {
-    int32_t lim = la < lb ? la : lb, j = 0;
-    while (j < lim && a[j] == b[j]) j++;
-    return j;
-}
 
 void orc_def2(const int32_t *tokens, const int64_t *off, const int32_t *len, const uint64_t *arrival,
               const int32_t *order, int32_t n, double c_attn, double t_start, double *completion) {

@@ -487,3 +487,77 @@ def test_hit_rate_score_orders_like_the_exact_ratio():
     a, _ = oracle.select(np.zeros(2, np.uint64), np.array([500, 40], np.int32), K_INF, 1, 0)
     b, _ = oracle.select(np.zeros(2, np.uint64), oracle.score_hit_rate([500, 40], [1000, 40]), K_INF, 1, 0)
     assert a.tolist() == [0] and b.tolist() == [1]
+
+
+# ----------------------------------------------------------------------------- in-batch rescoring
+def _dynamic_literal(p, arrival, m, k, batch, phase):
+    """Literal form on Python lists: pick by the current scores, then raise the others' scores to
+    their common prefix with the picked prompt."""
+    inf = k in (0, K_INF)
+    toks = [p.tokens[int(o): int(o) + int(l)].tolist() for o, l in zip(p.off, p.len)]
+    score = [int(v) for v in m]
+    remaining = list(range(p.n))
+    out = []
+    ph = 0 if inf else phase % k
+    for j in range(min(batch, p.n)):
+        if not inf and (ph + j) % k == 0:
+            pick = min(remaining, key=lambda i: (int(arrival[i]), i))
+        else:
+            pick = min(remaining, key=lambda i: (-score[i], int(arrival[i]), i))
+        out.append(pick)
+        remaining.remove(pick)
+        for i in remaining:
+            score[i] = max(score[i], lcp(toks[i], toks[pick]))
+    return out, (0 if inf else (ph + len(out)) % k), score
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_dynamic_select_equals_literal_and_sequential_steps(seed):
+    w = W.random_small(seed + 300, n_cache=8, n_query=30, vocab=3, max_len=9)
+    q = w.queries
+    tree = oracle.OracleTree()
+    tree.build(w.cache)
+    m = tree.match(q.tokens, q.off, q.len)
+    for k in (1, 2, 3, K_INF):
+        for batch in (1, 7, q.n):
+            got, ph, sc = oracle.select_dynamic(q.tokens, q.off, q.len, q.arrival, m, k, batch, phase=1)
+            want, ph_want, sc_want = _dynamic_literal(q, q.arrival, m, k, batch, 1)
+            assert got.tolist() == want and ph == ph_want and sc.tolist() == sc_want
+            if batch == 1:  # one pick: nothing to rescore
+                st, _ = oracle.select(q.arrival, m, k, 1, 1)
+                assert got.tolist() == st.tolist()
+    # one bin with rescoring == the same number of single-query steps through the tree without
+    # eviction (each step matches against cache + everything processed so far)
+    for k in (2, 3, K_INF):
+        got, _, sc = oracle.select_dynamic(q.tokens, q.off, q.len, q.arrival, m, k, q.n, phase=0)
+        t2 = oracle.OracleTree()
+        t2.build(w.cache)
+        waiting, phase, order, at_pick = np.arange(q.n), 0, [], []
+        while waiting.shape[0]:
+            mm = t2.match(q.tokens, q.off[waiting], q.len[waiting])
+            idx, phase = oracle.select(q.arrival[waiting], mm, k, 1, phase)
+            t2.commit(q.tokens, q.off[waiting], q.len[waiting], idx, 1 << 60)
+            order.append(int(waiting[idx[0]]))
+            at_pick.append(int(mm[idx[0]]))
+            waiting = np.delete(waiting, idx[0])
+        assert got.tolist() == order and sc[got].tolist() == at_pick
+
+
+def test_dynamic_select_reproduces_the_worked_example_in_one_bin():
+    """Sec. 4.2's example with an empty cache and all four queries in one bin: static scores are all
+    zero (arrival order), rescoring gives the LPM order x1, x3, x2, x4 and the overlaps 0, 5, 0, 5
+    that make up the printed TTFTs 10, 15, 25, 30."""
+    g = _golden()
+    p = W.toy_example(0)
+    zero = np.zeros(4, np.int32)
+    static, _ = oracle.select(p.arrival, zero, K_INF, 4)
+    assert (static + 1).tolist() == g["s0_fcfs_order"]
+    for k in (2, K_INF):
+        got, _, sc = oracle.select_dynamic(p.tokens, p.off, p.len, p.arrival, zero, k, 4)
+        assert (got + 1).tolist() == g["s0_lpm_order"]
+        cost = p.len[got] - sc[got]
+        assert np.cumsum(cost).tolist() == g["s0_lpm_ttft_in_processing_order"]
+    got, _, sc = oracle.select_dynamic(p.tokens, p.off, p.len, p.arrival, zero, 1, 4)
+    # FCFS order; a cache that keeps all of the bin's prompts (not only the last one, as Def. 2's
+    # model does when it prints 30 and 40) still holds x1 when x3 comes, and x2 when x4 comes
+    assert (got + 1).tolist() == g["s0_fcfs_order"] and np.cumsum(p.len[got] - sc[got]).tolist() == [10, 20, 25, 30]
