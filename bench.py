@@ -74,7 +74,8 @@ def build_workload(scale: float, steps_total: int, deep: bool = False):
     return w, allq
 
 
-def cpu_baseline(w, allq, steps: int, threads: int, rate_bits: int = 0, random_ties: bool = False):
+def cpu_baseline(w, allq, steps: int, threads: int, rate_bits: int = 0, random_ties: bool = False,
+                 dynamic: bool = False):
     """The oracle run over the first `steps` steps of the same workload (match on `threads` host
     threads, select and commit serial), timed without the tree build."""
     import oracle
@@ -96,7 +97,10 @@ def cpu_baseline(w, allq, steps: int, threads: int, rate_bits: int = 0, random_t
         t_match += time.perf_counter() - ta
         sc = oracle.score_hit_rate(m, ln, rate_bits) if rate_bits else m
         tk = oracle.tie_keys(TIE_SEED, s, waiting) if random_ties else None
-        idx, phase = oracle.select(arr, sc, w.k, batch, phase, tie_key=tk)
+        if dynamic:
+            idx, phase, _ = oracle.select_dynamic(allq.tokens, off, ln, arr, m, w.k, batch, phase)
+        else:
+            idx, phase = oracle.select(arr, sc, w.k, batch, phase, tie_key=tk)
         tree.commit(allq.tokens, off, ln, idx, w.budget)
         clock += max(1, int((ln[idx].astype(np.int64) - m[idx]).sum()))
         keep = np.ones(waiting.shape[0], dtype=bool)
@@ -192,6 +196,8 @@ def main() -> int:
     ap.add_argument("--score", choices=("length", "rate"), default="length",
                     help="what longest-match picks maximise: match length (default) or hit rate m/|x|")
     ap.add_argument("--random-ties", action="store_true", help="break score ties uniformly at random (Philox keys)")
+    ap.add_argument("--dynamic", action="store_true",
+                    help="in-batch rescoring: scores follow the prompts picked earlier in the same batch")
     ap.add_argument("--workload", choices=("cfg2-large", "def3"), default="cfg2-large",
                     help="def3: the timed Regular Arrival Shuffled Queue run (second workload)")
     ap.add_argument("--def3-u", type=int, default=3000, help="shared-prefix length of the def3 workload (prompt = 6000)")
@@ -235,11 +241,25 @@ def main() -> int:
     score = torch.zeros(n0, dtype=torch.int32, device=dev) if args.score == "rate" else None
     tie = torch.zeros(n0, dtype=torch.int32, device=dev) if args.random_ties else None
 
+    if args.dynamic:
+        dyn_bytes = K.kLPM_select_dynamic_workspace_bytes(n0)
+        dyn_ws = K.alloc_aligned(dyn_bytes, dev)
+        dyn = torch.zeros(n0, dtype=torch.int32, device=dev)
+
     def one_step(s: int) -> None:
         q = run.view()
         ev[s][0].record()
-        sched.match(q)
+        sched.match(q, want_nodes=args.dynamic)
         ev[s][1].record()
+        if args.dynamic:  # Algorithm 1 on scores that follow the picks made so far in the bin
+            K.kLPM_select_dynamic(q, sched.match_len, sched.last_node, k, batch, sched.phase, dyn, sched.batch_idx,
+                                  sched.n_selected, dyn_ws, dyn_bytes)
+            ev[s][2].record()
+            sched.commit(q, batch)
+            ev[s][3].record()
+            run.advance(batch, new_ids[s], matched=sums[s:s + 1])
+            ev[s][4].record()
+            return
         if score is not None:  # hit rate instead of match length (the wording of Algorithm 1)
             K.kLPM_score_hit_rate(sched.match_len, q.len, n0, rate_bits, score)
         if tie is not None:  # uniformly random tie-break, redrawn every step, keyed by query id
@@ -300,7 +320,8 @@ def main() -> int:
         "config": {"workload": w.name if args.scale == 1.0 else f"{w.name}-scale{args.scale}",
                    "cache_tokens": int(st.total_tokens), "tree_nodes": int(st.n_nodes), "waiting_queries": n0,
                    "batch": batch, "k": k, "kv_budget_tokens": int(w.budget), "max_prompt_len": max_len,
-                   "score": args.score, "ties": "random" if args.random_ties else "arrival"},
+                   "score": args.score, "ties": "random" if args.random_ties else "arrival",
+                   "rescoring": "in-batch" if args.dynamic else "per step"},
         "schedule_latency_us": elapsed / args.steps * 1e6,
         "phase_ms": {"match": float(match_ms.mean()), "select": float(select_ms.mean()),
                      "commit": float(commit_ms.mean()), "queue_advance": float(adv_ms.mean())},
@@ -318,7 +339,7 @@ def main() -> int:
         threads = max(1, min(cores, 16))
         cpu_steps = min(args.cpu_steps, steps_total)
         v, dt, t_match, step_sums = cpu_baseline(w, allq, cpu_steps, threads, rate_bits if score is not None else 0,
-                                                 args.random_ties)
+                                                 args.random_ties, args.dynamic)
         # matched tokens of every sampled step: they depend on all earlier selections and commits
         assert step_sums == [int(v) for v in sums_h[:cpu_steps]], f"GPU and oracle disagree: {sums_h[:cpu_steps]} vs {step_sums}"
         out["cpu_baseline"] = {"value": v, "unit": "tokens/s", "cores": threads, "kind": "oracle",

@@ -145,6 +145,27 @@ int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_
                 void *workspace, size_t workspace_bytes, kLPM_stream stream);
 
 /*
+ * k-LPM selection with in-batch rescoring: Algorithm 1 applied to scores that follow the cache
+ * inside the bin.  Def. 2 credits a query with its overlap with what was processed before it; with
+ * a cache that keeps every processed prompt (Sec. 1) a query picked later in the same bin of B
+ * (Sec. 2.1) overlaps with the cached strings and with every prompt picked before it.  After each
+ * pick p the score of every remaining query i becomes max(score_i, overlap(x_i, x_p)); each slot
+ * is filled by Algorithm 1's rule on the current scores (ties: earlier arrival, lower index).
+ * Equivalent to `batch` single-query steps of match -> select -> commit without eviction.
+ *   q           the waiting queue, q->arrival required, q->n <= 262144
+ *   match_len   DEVICE [q->n] in: match lengths against the cache (kLPM_match)
+ *   last_node   DEVICE [q->n] in: the last_node output of the same kLPM_match call
+ *   dyn_match   DEVICE [q->n] out: for a picked query its score when it was picked (its overlap
+ *               credit: it costs len - dyn_match), for the others their final score
+ *   phase_inout, batch_idx, n_selected   as in kLPM_select
+ *   workspace   DEVICE, 256-byte aligned, >= kLPM_select_dynamic_workspace_bytes(q->n)
+ */
+int kLPM_select_dynamic_workspace_bytes(int32_t n, size_t *out_bytes);
+int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node, uint32_t k,
+                        int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
+                        int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream);
+
+/*
  * Prefix-cache hit *rate* (the wording of Algorithm 1) as a score for kLPM_select:
  * score[i] = floor(match_len[i] * 2^scale_bits / len[i]), 1 <= scale_bits <= 30.  It orders the
  * queries exactly like the ratios m/|x| whenever every |x| <= 2^(scale_bits/2); beyond that

@@ -24,7 +24,7 @@ DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
-    "kLPM_score_hit_rate", "kLPM_tie_keys",
+    "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
     "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
     "kLPM_read_stats",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
@@ -75,6 +75,8 @@ def load_library() -> C.CDLL:
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
     lib.kLPM_select.argtypes = [vp, vp, vp, i32, vp, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select_dynamic_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
+    lib.kLPM_select_dynamic.argtypes = [C.POINTER(Queries), vp, vp, u32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.kLPM_score_hit_rate.argtypes = [vp, vp, i32, vp, i32, vp, vp]
     lib.kLPM_tie_keys.argtypes = [C.c_uint64, C.c_uint64, vp, i32, vp, vp, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
@@ -223,6 +225,23 @@ def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, 
     _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), _ptr(tie_key), int(n), _ptr(n_live), C.c_uint32(k & 0xFFFFFFFF), int(batch),
                             C.c_uint32(flags), int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
+
+
+def kLPM_select_dynamic_workspace_bytes(n: int) -> int:
+    out = C.c_size_t(0)
+    _check(_lib.kLPM_select_dynamic_workspace_bytes(int(n), C.byref(out)), "kLPM_select_dynamic_workspace_bytes")
+    return int(out.value)
+
+
+def kLPM_select_dynamic(q: DeviceQueries, match_len: torch.Tensor, last_node: torch.Tensor, k: int, batch: int,
+                        phase_inout: torch.Tensor, dyn_match: torch.Tensor, batch_idx: torch.Tensor,
+                        n_selected: torch.Tensor, workspace: Tuple[torch.Tensor, int], workspace_bytes: int,
+                        stream=None) -> None:
+    qs = q.c_struct()
+    _check(_lib.kLPM_select_dynamic(C.byref(qs), _ptr(match_len), _ptr(last_node), C.c_uint32(k & 0xFFFFFFFF), int(batch),
+                                    _ptr(phase_inout), _ptr(dyn_match), _ptr(batch_idx), _ptr(n_selected),
+                                    C.c_void_p(workspace[1]), int(workspace_bytes), _stream(stream)),
+           "kLPM_select_dynamic")
 
 
 def kLPM_score_hit_rate(match_len: torch.Tensor, length: torch.Tensor, n: int, scale_bits: int, score: torch.Tensor,

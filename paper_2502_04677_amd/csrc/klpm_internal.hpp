@@ -26,6 +26,17 @@ int launch_match(const TreeView &tv, const QView &q, const int32_t *sel, const i
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
                     int32_t batch_cap, int64_t budget, kLPM_stats *stats_out, hipStream_t stream);
 
+// The two total orders behind Algorithm 1's picks, as built by the sorting path of the selection:
+// queue indices in oldest-first order (arrival, index) and in longest-match order (-score, [tie key,]
+// arrival, index), and every query's position in each.  The arrays live in the caller's workspace.
+struct SelectOrders {
+    const uint32_t *order_a, *order_l, *rank_a, *rank_l;
+};
+size_t select_sort_workspace_bytes(int32_t n);
+int build_select_orders(const uint64_t *arrival, const int32_t *score, const uint32_t *tie_key, int32_t n,
+                        const int32_t *n_live, bool want_l, void *workspace, size_t workspace_bytes,
+                        hipStream_t stream, SelectOrders *out);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? KLPM_OK : KLPM_EHIP; }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

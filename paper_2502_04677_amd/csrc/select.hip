@@ -928,6 +928,50 @@ static void carve(SelectWs &ws, char *base, int32_t n, size_t *used) {
     *used = o;
 }
 
+size_t select_sort_workspace_bytes(int32_t n) {
+    SelectWs ws;
+    size_t need = 0;
+    carve(ws, nullptr, n, &need);
+    return need;
+}
+
+// Both total orders of the queue and each query's position in them (see the head of this file).
+// Without `want_l` only the oldest-first order is built (the other pointers then alias it).
+int build_select_orders(const uint64_t *arrival, const int32_t *score, const uint32_t *tie_key, int32_t n,
+                        const int32_t *n_live, bool want_l, void *workspace, size_t workspace_bytes,
+                        hipStream_t stream, SelectOrders *out) {
+    SelectWs ws;
+    size_t need = 0;
+    carve(ws, (char *)workspace, n, &need);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
+    const LiveN nn{n, n_live};
+    const uint32_t *order_a = ws.val_a, *order_l = ws.val_a;
+    if (n > 0) {
+        unsigned g = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(k_sel_init, dim3(g), dim3(256), 0, stream, arrival, nn, ws.key_a, ws.val_a);
+        bool first = true;
+        int rc = radix_sort(ws.key_a, ws.val_a, ws.key_b, ws.val_b, nn, 8, ws, stream, &first);
+        if (rc) return rc;
+        order_a = first ? ws.val_a : ws.val_b;  // 8 passes: back in the first buffer
+        if (want_l) {
+            // stable sort of the oldest-first order by descending score (then ascending tie key)
+            uint32_t *spare = first ? ws.val_b : ws.val_a;
+            hipLaunchKernelGGL(k_sel_lkeys, dim3(g), dim3(256), 0, stream, order_a, score, tie_key, nn, ws.key_a,
+                               ws.val_c);
+            bool lfirst = true;
+            rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, spare, nn, tie_key ? 8 : 4, ws, stream, &lfirst);
+            if (rc) return rc;
+            order_l = lfirst ? ws.val_c : spare;
+            hipLaunchKernelGGL(k_sel_ranks, dim3(g), dim3(256), 0, stream, order_a, order_l, nn, ws.rank_a, ws.rank_l);
+        }
+    }
+    out->order_a = order_a;
+    out->order_l = order_l;
+    out->rank_a = ws.rank_a;
+    out->rank_l = ws.rank_l;
+    return check_launch();
+}
+
 // ---- score and tie-key variants of Algorithm 1 ----
 // Hit rate of Algorithm 1's wording as an integer score: floor(m * 2^bits / |x|).
 __global__ __launch_bounds__(256) void k_score_hit_rate(const int32_t *__restrict__ match_len,
@@ -1006,9 +1050,8 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
 }
 
 extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
-                           const int32_t *n_live,
-                           uint32_t k, int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
-                           void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
+                           const int32_t *n_live, uint32_t k, int32_t batch, uint32_t flags, int32_t max_match,
+                           uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (n < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
@@ -1028,31 +1071,11 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, co
         return select_fifo_long(arrival, match_len, nn, k, batch, max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout,
                                 batch_idx, n_selected, (char *)workspace, stream);
     }
-    SelectWs ws;
-    size_t need = 0;
-    carve(ws, (char *)workspace, n, &need);
-    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
-    const uint32_t *order_a = ws.val_a, *order_l = ws.val_a;
-    if (n > 0 && batch > 0) {
-        unsigned g = (unsigned)((n + 255) / 256);
-        hipLaunchKernelGGL(k_sel_init, dim3(g), dim3(256), 0, stream, arrival, nn, ws.key_a, ws.val_a);
-        bool first = true;
-        int rc = radix_sort(ws.key_a, ws.val_a, ws.key_b, ws.val_b, nn, 8, ws, stream, &first);
-        if (rc) return rc;
-        order_a = first ? ws.val_a : ws.val_b;  // 8 passes: back in the first buffer
-        if (k != 1u) {
-            // stable sort of the oldest-first order by descending match length
-            uint32_t *spare = first ? ws.val_b : ws.val_a;
-            hipLaunchKernelGGL(k_sel_lkeys, dim3(g), dim3(256), 0, stream, order_a, match_len, tie_key, nn, ws.key_a,
-                               ws.val_c);
-            bool lfirst = true;
-            rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, spare, nn, tie_key ? 8 : 4, ws, stream, &lfirst);
-            if (rc) return rc;
-            order_l = lfirst ? ws.val_c : spare;
-            hipLaunchKernelGGL(k_sel_ranks, dim3(g), dim3(256), 0, stream, order_a, order_l, nn, ws.rank_a, ws.rank_l);
-        }
-    }
-    hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, order_a, order_l, ws.rank_a, ws.rank_l, nn, k,
+    SelectOrders ord;
+    int rc = build_select_orders(arrival, match_len, tie_key, n, n_live, k != 1u && batch > 0, workspace, workspace_bytes,
+                                 stream, &ord);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, ord.order_a, ord.order_l, ord.rank_a, ord.rank_l, nn, k,
                        batch, phase_inout, batch_idx, n_selected);
     return check_launch();
 }

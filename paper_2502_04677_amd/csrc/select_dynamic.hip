@@ -1,0 +1,418 @@
+// k-LPM batch selection with in-batch rescoring (Algorithm 1 applied inside one bin of B queries,
+// Sec. 2.1, with the overlap credit of Def. 2 taken against everything processed so far).
+//
+// After a pick p the score of every remaining query i becomes max(score_i, overlap(x_i, x_p)).  Only
+// few queries can gain: overlap(x_i, x_p) exceeds i's match against the cache only if x_p leaves the
+// cached tree at the very place x_i does and goes on with the same token, i.e. if both have the same
+// (stop node, match length, next token).  Queries are grouped by that key up front (a hash table
+// with one chain per key); a pick then rescans its own group only, and a query whose group has no
+// other member can neither gain nor give.  The picks themselves are made by one wavefront walking
+// the oldest-first and longest-match orders: whole k-cycles at a time while no picked query has a
+// group, one pick at a time (static head of the longest-match order against the best boosted
+// query) otherwise.
+#include "klpm_internal.hpp"
+
+namespace klpm {
+
+constexpr int32_t kDynMaxN = 262144;  // two state bits per query are kept in LDS (64 KB)
+
+struct DynWs {
+    uint64_t *gk;       // [n] (stop node << 32) | next token
+    int32_t *slot_of;   // [n] table slot of the query's group, -1: no group (prompt cached in full, bad input)
+    int32_t *next;      // [n] next member of the same group
+    uint8_t *multi;     // [n] 1: the group has at least two members
+    int32_t *rep;       // [table] first query that claimed the slot, -1: free
+    int32_t *head;      // [table] chain head
+    int32_t *cnt;       // [table] members
+    uint64_t *bkey;     // [n] boosted set: (inverted score, position in the oldest-first order)
+    int32_t *bidx;      // [n] boosted set: query index
+    int32_t *bpos;      // [n] where a boosted query sits in the set
+    uint32_t table_mask;
+};
+
+struct LiveQ {
+    int32_t n;
+    const int32_t *live;
+    __device__ __forceinline__ int32_t get() const { return live_count(n, live); }
+};
+
+__device__ __forceinline__ uint32_t group_hash(uint64_t gk, int32_t m) {
+    return hash_key(gk ^ ((uint64_t)(uint32_t)m * 0x9E3779B97F4A7C15ull));
+}
+
+__global__ __launch_bounds__(256) void k_dyn_init(QView q, const int32_t *__restrict__ match_len,
+                                                  const int32_t *__restrict__ last_node, DynWs ws,
+                                                  int32_t *__restrict__ dyn) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= (int64_t)ws.table_mask) {
+        ws.rep[i] = -1;
+        ws.head[i] = -1;
+        ws.cnt[i] = 0;
+    }
+    const int32_t n = live_count(q.n, q.n_live);
+    if (i >= n) return;
+    int32_t m = match_len[i];
+    const int64_t off = q.off[i];
+    const int32_t len = q.len[i];
+    const bool ok = m >= 0 && off >= 0 && len >= 1 && off + (int64_t)len <= q.n_tokens && m <= len;
+    dyn[i] = ok ? m : 0;
+    ws.next[i] = -1;
+    ws.multi[i] = 0;
+    // a prompt that is cached in full adds nothing to the cache and cannot gain either
+    const bool grouped = ok && m < len;
+    ws.slot_of[i] = grouped ? 0 : -1;
+    ws.gk[i] = grouped ? (((uint64_t)(uint32_t)last_node[i] << 32) | (uint64_t)(uint32_t)q.tokens[off + m]) : 0ull;
+}
+
+__global__ __launch_bounds__(256) void k_dyn_insert(LiveQ nn, const int32_t *__restrict__ match_len, DynWs ws) {
+    const int32_t n = nn.get();
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n || ws.slot_of[i] < 0) return;
+    const uint64_t gk = ws.gk[i];
+    const int32_t m = match_len[i];
+    uint32_t h = group_hash(gk, m) & ws.table_mask;
+    for (uint32_t probe = 0; probe <= ws.table_mask; ++probe) {
+        int32_t r = atomicCAS(&ws.rep[h], -1, i);
+        if (r == -1 || (ws.gk[r] == gk && match_len[r] == m)) break;  // claimed, or the group's slot
+        h = (h + 1u) & ws.table_mask;
+    }
+    ws.slot_of[i] = (int32_t)h;
+    ws.next[i] = atomicExch(&ws.head[h], i);
+    atomicAdd(&ws.cnt[h], 1);
+}
+
+__global__ __launch_bounds__(256) void k_dyn_multi(LiveQ nn, DynWs ws) {
+    const int32_t n = nn.get();
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t s = ws.slot_of[i];
+    ws.multi[i] = (s >= 0 && ws.cnt[s] > 1) ? 1 : 0;
+}
+
+// loads and stores of the arrays the walking wavefront both writes (lane 0) and reads (any lane)
+template <typename T>
+__device__ __forceinline__ T coh_load(const T *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void coh_store(T *p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ uint64_t pack_key(int32_t score, uint32_t rank_a) {
+    return ((uint64_t)(0x7FFFFFFFu - (uint32_t)score) << 32) | (uint64_t)rank_a;
+}
+
+__global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__restrict__ match_len, SelectOrders ord,
+                                                    DynWs ws, int32_t *__restrict__ dyn, uint32_t k, int32_t batch,
+                                                    uint32_t *__restrict__ phase_inout,
+                                                    int32_t *__restrict__ batch_idx,
+                                                    int32_t *__restrict__ n_selected) {
+    __shared__ uint32_t st[kDynMaxN / 16];  // per query: bit 0 = picked, bit 1 = in the boosted set
+    const int lane = threadIdx.x;
+    const int32_t n = live_count(q.n, q.n_live);
+    const int32_t nb = batch < n ? batch : n;
+    const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
+    const uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
+    for (int32_t w = lane; w < (n + 15) / 16; w += kWave) st[w] = 0u;
+    __syncthreads();
+    if (lane == 0) {
+        *n_selected = nb;
+        *phase_inout = lpm_only ? 0u : (uint32_t)(((uint64_t)phase + (uint64_t)nb) % k);
+    }
+    auto state = [&](uint32_t e) -> uint32_t { return (st[e >> 4] >> ((e & 15u) * 2u)) & 3u; };
+    auto set_bits = [&](uint32_t e, uint32_t bits) { atomicOr(&st[e >> 4], bits << ((e & 15u) * 2u)); };
+    const uint32_t km1 = k - 1u;
+    int32_t ia = 0, il = 0, j = 0, n_boost = 0;
+    uint32_t pos = phase;  // (phase + j) mod k
+    // best entry of the boosted set (smallest key), kept up to date lazily
+    uint64_t kb = ~0ull;
+    int32_t pb = -1;
+    bool kb_valid = true;
+    while (j < nb) {
+        const bool oldest = !lpm_only && pos == 0u;
+        if (!kb_valid) {
+            kb = ~0ull;
+            pb = -1;
+            for (int32_t b = lane; b < n_boost; b += kWave) {
+                const uint64_t v = coh_load(&ws.bkey[b]);
+                if (v < kb) { kb = v; pb = b; }
+            }
+#pragma unroll
+            for (int d = kWave / 2; d > 0; d >>= 1) {
+                const uint64_t ok = __shfl_xor(kb, d);
+                const int32_t op = __shfl_xor(pb, d);
+                if (ok < kb) { kb = ok; pb = op; }
+            }
+            kb_valid = true;
+        }
+        // A pick made in bulk must be one that needs no bookkeeping: it has no group (nobody gains
+        // from it), it is not in the boosted set, and for a longest-match pick no boosted query
+        // ranks before it.
+        // ---- whole k-cycles at once
+        if (oldest && k > 1u && (uint32_t)(nb - j) >= k && km1 <= (uint32_t)kWave) {
+            const int32_t ra = ia + lane, rl = il + lane;
+            uint32_t a_el = 0, l_el = 0, a_other = 0, l_other = 0;
+            bool cand_a = false, cand_l = false, hard_a = false, hard_l = false;
+            if (ra < n) {
+                a_el = ord.order_a[ra];
+                const uint32_t sa = state(a_el);
+                cand_a = (sa & 1u) == 0u;
+                a_other = ord.rank_l[a_el];
+                hard_a = ws.multi[a_el] != 0 || (sa & 2u) != 0u;
+            }
+            if (rl < n) {
+                l_el = ord.order_l[rl];
+                cand_l = state(l_el) == 0u;
+                l_other = ord.rank_a[l_el];
+                int32_t ml = match_len[l_el];
+                hard_l = ws.multi[l_el] != 0 || pack_key(ml < 0 ? 0 : ml, l_other) > kb;
+            }
+            const uint64_t mask_a = __ballot(cand_a), mask_l = __ballot(cand_l);
+            int32_t c = (int32_t)__popcll(mask_a);
+            const int32_t by_l = (int32_t)((uint32_t)__popcll(mask_l) / km1), by_b = (int32_t)((uint32_t)(nb - j) / k);
+            c = by_l < c ? by_l : c;
+            c = by_b < c ? by_b : c;
+            if (c > 0) {
+                const int32_t my_a = (int32_t)__popcll(mask_a & ((1ull << lane) - 1ull));
+                const int32_t my_l = (int32_t)__popcll(mask_l & ((1ull << lane) - 1ull));
+                // cycles before the first pick that needs bookkeeping
+                const uint64_t ha = __ballot(cand_a && hard_a), hl = __ballot(cand_l && hard_l);
+                if (ha) { const int32_t lim = (int32_t)__popcll(mask_a & ((1ull << __builtin_ctzll(ha)) - 1ull)); c = lim < c ? lim : c; }
+                if (hl) {
+                    const int32_t lim = (int32_t)((uint32_t)__popcll(mask_l & ((1ull << __builtin_ctzll(hl)) - 1ull)) / km1);
+                    c = lim < c ? lim : c;
+                }
+                if (c > 0) {
+                    const int32_t take_l = c * (int32_t)km1;
+                    const bool ch_a = cand_a && my_a < c, ch_l = cand_l && my_l < take_l;
+                    const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
+                    const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
+                    // the two streams must not meet inside the consumed stretches
+                    const uint64_t clash = __ballot((ch_a && a_other < (uint32_t)il_end) || (ch_l && l_other < (uint32_t)ia_end));
+                    if (clash == 0ull) {
+                        if (ch_a) { batch_idx[j + my_a * (int32_t)k] = (int32_t)a_el; set_bits(a_el, 1u); }
+                        if (ch_l) {
+                            const uint32_t cyc = (uint32_t)my_l / km1, within = (uint32_t)my_l - cyc * km1;
+                            batch_idx[j + (int32_t)(cyc * k + 1u + within)] = (int32_t)l_el;
+                            set_bits(l_el, 1u);
+                        }
+                        __syncthreads();
+                        ia = ia_end;
+                        il = il_end;
+                        j += c * (int32_t)k;
+                        continue;
+                    }
+                }
+            }
+        }
+        // ---- a run of picks of one kind, up to the first pick that needs bookkeeping
+        bool single_from_set = false;
+        {
+            const uint32_t run = oldest ? (k == 1u ? (uint32_t)(nb - j) : 1u) : (lpm_only ? (uint32_t)(nb - j) : k - pos);
+            const int32_t want = (int32_t)(run < (uint32_t)(nb - j) ? run : (uint32_t)(nb - j));
+            const int32_t r = (oldest ? ia : il) + lane;
+            uint32_t el = 0;
+            bool cand = false, hard = false;
+            if (r < n) {
+                el = oldest ? ord.order_a[r] : ord.order_l[r];
+                const uint32_t sv = state(el);
+                cand = oldest ? ((sv & 1u) == 0u) : (sv == 0u);
+                hard = ws.multi[el] != 0;
+                if (oldest) {
+                    hard = hard || (sv & 2u) != 0u;
+                } else if (cand && n_boost > 0) {
+                    int32_t ml = match_len[el];
+                    hard = hard || pack_key(ml < 0 ? 0 : ml, ord.rank_a[el]) > kb;
+                }
+            }
+            const uint64_t mask = __ballot(cand), hmask = __ballot(cand && hard);
+            const int32_t my = (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            int32_t take = (int32_t)__popcll(mask);
+            take = take < want ? take : want;
+            if (hmask) {
+                const int32_t clean = (int32_t)__popcll(mask & ((1ull << __builtin_ctzll(hmask)) - 1ull));
+                take = clean < take ? clean : take;
+            }
+            if (take > 0) {
+                if (cand && my < take) { batch_idx[j + my] = (int32_t)el; set_bits(el, 1u); }
+                __syncthreads();
+                const int32_t adv = (int32_t)__builtin_ctzll(__ballot(cand && my == take - 1)) + 1;
+                if (oldest) ia += adv; else il += adv;
+                j += take;
+                pos = lpm_only ? 0u : (uint32_t)(((uint64_t)pos + (uint64_t)take) % k);
+                continue;
+            }
+            if (mask == 0ull) {  // nothing pickable in this window
+                if ((oldest ? ia : il) + kWave < n) {  // look further along the order
+                    if (oldest) ia += kWave; else il += kWave;
+                    continue;
+                }
+                if (oldest) break;          // unreachable while nb <= n
+                if (n_boost == 0) break;    // unreachable while nb <= n
+                il = n;
+                single_from_set = true;     // only boosted queries are left
+            }
+            // otherwise the next pick needs bookkeeping: it is made on its own below
+        }
+        // ---- one pick; then the rescoring of the pick's group
+        int32_t p = -1;
+        if (oldest) {
+            const int32_t r = ia + lane;
+            uint32_t el = 0;
+            bool cand = false;
+            if (r < n) { el = ord.order_a[r]; cand = (state(el) & 1u) == 0u; }
+            const uint64_t mask = __ballot(cand);  // not empty: see the run block above
+            const int f = (int)__builtin_ctzll(mask);
+            p = __shfl((int32_t)el, f);
+            ia += f + 1;
+        } else {
+            // head of the static longest-match order among the queries never boosted, against the
+            // best boosted query
+            int32_t c1 = -1;
+            uint64_t key1 = ~0ull;
+            if (!single_from_set) {
+                const int32_t r = il + lane;
+                uint32_t el = 0;
+                bool cand = false;
+                if (r < n) { el = ord.order_l[r]; cand = state(el) == 0u; }
+                const uint64_t mask = __ballot(cand);  // not empty: see the run block above
+                const int f = (int)__builtin_ctzll(mask);
+                c1 = __shfl((int32_t)el, f);
+                il += f;  // stays on it until it is picked
+                int32_t m1 = match_len[c1];
+                key1 = pack_key(m1 < 0 ? 0 : m1, ord.rank_a[c1]);
+            }
+            if (kb < key1) {
+                p = coh_load(&ws.bidx[pb]);
+            } else {
+                p = c1;
+                il += 1;
+            }
+        }
+        if (p < 0) break;  // unreachable while nb <= n
+        p = uni(p);
+        const uint32_t sp = state((uint32_t)p);
+        if (lane == 0) {
+            batch_idx[j] = p;
+            set_bits((uint32_t)p, 1u);
+        }
+        if (sp & 2u) {  // leaves the boosted set: the last entry takes its place
+            const int32_t at = uni(coh_load(&ws.bpos[p]));
+            const int32_t last = n_boost - 1;
+            if (lane == 0 && at != last) {
+                const int32_t moved = coh_load(&ws.bidx[last]);
+                coh_store(&ws.bkey[at], coh_load(&ws.bkey[last]));
+                coh_store(&ws.bidx[at], moved);
+                coh_store(&ws.bpos[moved], at);
+            }
+            n_boost = last;
+            kb_valid = false;
+        }
+        j += 1;
+        pos = lpm_only ? 0u : (pos + 1u == k ? 0u : pos + 1u);
+        if (ws.multi[p]) {
+            // everything processed stays cached for the rest of the bin: raise the scores of the
+            // pick's group to their common prefix with it
+            const int64_t off_p = uni64(q.off[p]);
+            const int32_t len_p = uni(q.len[p]);
+            const int32_t s0 = uni(match_len[p]) + 1;  // the group shares the cached part and the next token
+            int32_t i = uni(ws.head[ws.slot_of[p]]);
+            while (i >= 0) {
+                const int32_t nxt = uni(ws.next[i]);
+                const uint32_t si = state((uint32_t)i);
+                if (i != p && (si & 1u) == 0u) {
+                    const int64_t off_i = uni64(q.off[i]);
+                    const int32_t len_i = uni(q.len[i]);
+                    const int32_t lim = len_i < len_p ? len_i : len_p;
+                    int32_t ov = s0;
+                    if (lim > s0) ov = s0 + wave_common_prefix(q.tokens + off_i + s0, q.tokens + off_p + s0, lim - s0, lane);
+                    if (ov > uni(coh_load(&dyn[i]))) {
+                        const uint64_t key = pack_key(ov, ord.rank_a[i]);
+                        const bool in_set = (si & 2u) != 0u;
+                        const int32_t at = in_set ? uni(coh_load(&ws.bpos[i])) : n_boost;
+                        if (lane == 0) {
+                            coh_store(&dyn[i], ov);
+                            coh_store(&ws.bkey[at], key);
+                            if (!in_set) {
+                                coh_store(&ws.bidx[at], i);
+                                coh_store(&ws.bpos[i], at);
+                                set_bits((uint32_t)i, 2u);
+                            }
+                        }
+                        if (!in_set) n_boost += 1;
+                        if (kb_valid && key < kb) { kb = key; pb = at; }  // keys only ever get smaller
+                    }
+                }
+                i = nxt;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");  // lane 0's stores before the next reads of any lane
+        __syncthreads();
+    }
+}
+
+static size_t carve_dyn(DynWs &d, char *base, int32_t n, size_t start) {
+    size_t o = start;
+    auto take = [&](size_t bytes) { void *p = base ? base + o : nullptr; o += align_up(bytes, 256); return p; };
+    size_t nn = (size_t)(n > 0 ? n : 1);
+    uint32_t table = 64;
+    while (table < 2 * nn) table <<= 1;
+    d.table_mask = table - 1u;
+    d.gk = (uint64_t *)take(nn * 8);
+    d.slot_of = (int32_t *)take(nn * 4);
+    d.next = (int32_t *)take(nn * 4);
+    d.multi = (uint8_t *)take(nn);
+    d.rep = (int32_t *)take((size_t)table * 4);
+    d.head = (int32_t *)take((size_t)table * 4);
+    d.cnt = (int32_t *)take((size_t)table * 4);
+    d.bkey = (uint64_t *)take(nn * 8);
+    d.bidx = (int32_t *)take(nn * 4);
+    d.bpos = (int32_t *)take(nn * 4);
+    return o;
+}
+
+}  // namespace klpm
+
+using namespace klpm;
+
+extern "C" int kLPM_select_dynamic_workspace_bytes(int32_t n, size_t *out_bytes) {
+    if (n < 0 || !out_bytes) return KLPM_EINVAL;
+    DynWs d;
+    *out_bytes = carve_dyn(d, nullptr, n, align_up(select_sort_workspace_bytes(n), 256));
+    return KLPM_OK;
+}
+
+extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node, uint32_t k,
+                                   int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
+                                   int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!q || q->n < 0 || q->n > kDynMaxN || q->n_tokens < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
+    const int32_t n = q->n;
+    if (n > 0 && (!q->tokens || !q->off || !q->len || !q->arrival || !match_len || !last_node || !dyn_match))
+        return KLPM_EINVAL;
+    if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
+    size_t need = 0;
+    kLPM_select_dynamic_workspace_bytes(n, &need);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
+    const size_t sort_bytes = align_up(select_sort_workspace_bytes(n), 256);
+    DynWs d;
+    carve_dyn(d, (char *)workspace, n, sort_bytes);
+    QView qv;
+    qv.tokens = q->tokens; qv.off = q->off; qv.len = q->len; qv.n_tokens = q->n_tokens; qv.n = n; qv.n_live = q->n_live;
+    SelectOrders ord;
+    // the static orders are taken over the match lengths against the cache
+    int rc = build_select_orders(q->arrival, match_len, nullptr, n, q->n_live, true, workspace, sort_bytes, stream, &ord);
+    if (rc) return rc;
+    if (n > 0) {
+        const int64_t work = (int64_t)d.table_mask + 1 > n ? (int64_t)d.table_mask + 1 : n;
+        const unsigned g = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(k_dyn_init, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, qv, match_len, last_node, d,
+                           dyn_match);
+        hipLaunchKernelGGL(k_dyn_insert, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, match_len, d);
+        hipLaunchKernelGGL(k_dyn_multi, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, d);
+    }
+    hipLaunchKernelGGL(k_dyn_walk, dim3(1), dim3(kWave), 0, stream, qv, match_len, ord, d, dyn_match, k, batch, phase_inout,
+                       batch_idx, n_selected);
+    return check_launch();
+}

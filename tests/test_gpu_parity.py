@@ -651,3 +651,91 @@ def test_steps_with_hit_rate_score_and_random_ties_keep_the_tree_in_step():
         ref.commit(hq.tokens, hq.off, hq.len, idx_ref, 9000)
         assert s.read_stats().device_error == 0
         _same_tree(s, ref)
+
+
+# ----------------------------------------------------------------------------- in-batch rescoring
+def _check_dynamic(s, ref, q, hq, ks, batches, live=None):
+    dev = "cuda:0"
+    n = q.n if live is None else min(live, q.n)
+    live_d = None if live is None else torch.full((1,), live, dtype=torch.int32, device=dev)
+    ql = K.DeviceQueries(q.tokens, q.off, q.len, q.arrival, q.n, n_live=live_d)
+    m = s.match(ql, want_nodes=True).cpu().numpy()[:n]
+    m_ref = ref.match(hq.tokens, hq.off[:n], hq.len[:n])
+    assert (m == m_ref).all()
+    ws_bytes = K.kLPM_select_dynamic_workspace_bytes(q.n)
+    ws = K.alloc_aligned(ws_bytes, dev)
+    dyn = torch.zeros(max(q.n, 1), dtype=torch.int32, device=dev)
+    for k in ks:
+        for batch in batches:
+            out = torch.full((max(batch, 1),), -9, dtype=torch.int32, device=dev)
+            s.set_phase(1)
+            dyn.fill_(-1)
+            K.kLPM_select_dynamic(ql, s.match_len, s.last_node, k, batch, s.phase, dyn, out, s.n_selected, ws, ws_bytes)
+            idx_ref, ph_ref, sc_ref = oracle.select_dynamic(hq.tokens, hq.off[:n], hq.len[:n], hq.arrival[:n], m_ref, k,
+                                                            batch, 1)
+            got_n = int(s.n_selected.item())
+            assert got_n == idx_ref.shape[0], (k, batch)
+            assert out[:got_n].cpu().numpy().tolist() == idx_ref.tolist(), (k, batch)
+            assert s.phase_value() == ph_ref
+            assert dyn[:n].cpu().numpy().tolist() == sc_ref.tolist(), (k, batch)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_dynamic_select_small_dense(seed):
+    w = W.random_small(seed + 300, n_cache=8, n_query=90, vocab=3, max_len=9)
+    s, ref, q = _setup(w, max_batch=128)
+    _check_dynamic(s, ref, q, w.queries, (1, 2, 3, 70, K_INF), (0, 1, 7, 64, 90, 128))
+    _check_dynamic(s, ref, q, w.queries, (2, K_INF), (5, 90), live=37)
+    _check_dynamic(s, ref, q, w.queries, (3,), (5,), live=0)
+
+
+def test_dynamic_select_shuffled_queue_and_duplicates():
+    # Def. 3 queue on an empty cache: every query's group is its user's four queries
+    p, _ = W.shuffled_queue(400, 50, 4, 30, 1, seed=3)
+    w = W.Workload("def3", W.take_prompts(p, np.zeros(0, np.int64)), p, 4, 400, 1 << 40)
+    s, ref, q = _setup(w, max_batch=400)
+    _check_dynamic(s, ref, q, p, (1, 4, 9, K_INF), (1, 100, 400))
+    # config 0 with a block of identical prompts and prompts that are prefixes of one another
+    w0 = W.config0()
+    hq = w0.queries
+    big = int(np.argmax(hq.len))
+    extra = [hq.tokens[int(hq.off[big]): int(hq.off[big]) + int(hq.len[big])]] * 12
+    extra += [extra[0][: int(hq.len[big]) - 7 * i] for i in range(1, 6)]
+    dup = W.generators._from_lists([e.tolist() for e in extra], [3] * len(extra))
+    hq2 = W.concat_prompts(hq, dup)
+    hq2.arrival[:] = np.sort(hq2.arrival)
+    w2 = W.Workload("cfg0+dups", w0.cache, hq2, w0.k, w0.batch, w0.budget)
+    s, ref, q = _setup(w2, max_batch=hq2.n)
+    _check_dynamic(s, ref, q, hq2, (2, 5, K_INF), (32, hq2.n))
+
+
+def test_dynamic_select_medium_queue_then_commit():
+    """Config-1-like queue (scaled) plus injected near-duplicates; the batch chosen with rescoring
+    is committed on both sides and the trees must agree."""
+    w = W.config1(scale=0.125)
+    hq = w.queries
+    rng = np.random.default_rng(5)
+    src = rng.integers(0, hq.n, size=300)
+    extra = []
+    for i in src:
+        t = hq.tokens[int(hq.off[i]): int(hq.off[i]) + int(hq.len[i])].copy()
+        cut = int(rng.integers(1, t.shape[0] + 1))
+        extra.append(np.concatenate([t[:cut], rng.integers(0, 32000, size=int(rng.integers(0, 40))).astype(np.int32)]).tolist())
+    hq2 = W.concat_prompts(hq, W.generators._from_lists(extra, rng.integers(0, 1000, size=300).tolist()))
+    w2 = W.Workload("cfg1+near-dups", w.cache, hq2, w.k, 256, w.budget)
+    s, ref, q = _setup(w2, max_batch=256, extra_prompts=256)
+    _say(f"dynamic medium: {hq2.n} waiting, cache {w.cache.n} prompts")
+    _check_dynamic(s, ref, q, hq2, (1, 4, K_INF), (256,))
+    # the last call's batch (k = infinity, 256 picks) goes into the tree
+    idx_ref, _, _ = oracle.select_dynamic(hq2.tokens, hq2.off, hq2.len, hq2.arrival,
+                                          ref.match(hq2.tokens, hq2.off, hq2.len), K_INF, 256, 1)
+    ws_bytes = K.kLPM_select_dynamic_workspace_bytes(q.n)
+    ws = K.alloc_aligned(ws_bytes, "cuda:0")
+    dyn = torch.zeros(q.n, dtype=torch.int32, device="cuda:0")
+    s.set_phase(1)
+    K.kLPM_select_dynamic(q, s.match_len, s.last_node, K_INF, 256, s.phase, dyn, s.batch_idx, s.n_selected, ws, ws_bytes)
+    assert s.batch().tolist() == idx_ref.tolist()
+    s.commit(q, 256)
+    ref.commit(hq2.tokens, hq2.off, hq2.len, idx_ref, w.budget)
+    assert s.read_stats().device_error == 0
+    _same_tree(s, ref, big=True)
