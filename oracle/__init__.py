@@ -66,7 +66,7 @@ def _load():
         L.orc_match_mt.argtypes = [vp, vp, vp, vp, i32, vp, i32]
         L.orc_select.restype = i32
         L.orc_select.argtypes = [vp, vp, vp, i32, u32, i32, C.POINTER(u32), vp]
-        L.orc_commit.argtypes = [vp, vp, vp, vp, vp, i32, i64, C.POINTER(_Stats)]
+        L.orc_commit.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, C.POINTER(_Stats)]
         L.orc_snapshot_bytes.restype = C.c_size_t; L.orc_snapshot_bytes.argtypes = [vp]
         L.orc_snapshot.restype = C.c_size_t; L.orc_snapshot.argtypes = [vp, vp, C.c_size_t]
         L.orc_select_dynamic.restype = i32
@@ -131,12 +131,14 @@ class OracleTree:
             self._L.orc_match_mt(self._t, _p(tokens), _p(off), _p(length), length.shape[0], _p(out), threads)
         return out
 
-    def commit(self, tokens, off, length, batch_idx, budget: int) -> CommitStats:
+    def commit(self, tokens, off, length, batch_idx, budget: int, protect: int = 0) -> CommitStats:
+        """``protect``: the paths of that many most recently admitted prompts (this batch included)
+        are in flight and are never evicted, even if the total then stays above the budget."""
         tokens, off, length = _c(tokens, np.int32), _c(off, np.int64), _c(length, np.int32)
         batch_idx = _c(batch_idx, np.int32)
         st = _Stats()
         self._L.orc_commit(self._t, _p(tokens), _p(off), _p(length), _p(batch_idx), batch_idx.shape[0],
-                           int(min(budget, (1 << 62))), C.byref(st))
+                           int(min(budget, (1 << 62))), int(protect), C.byref(st))
         return CommitStats(st.total_tokens, st.inserted_tokens, st.evicted_tokens, st.n_nodes, st.new_nodes,
                            st.evicted_nodes, st.clock)
 
@@ -187,6 +189,26 @@ def select_dynamic(prompts_tokens, off, length, arrival, match_len, k: int, batc
     got = L.orc_select_dynamic(_p(tok), _p(off), _p(ln), _p(arrival), _p(score), n, C.c_uint32(k & 0xFFFFFFFF), batch,
                                C.byref(ph), _p(out))
     return out[:got], int(ph.value), score
+
+
+def token_budget_cut(batch_idx, length, match_len, token_budget: int) -> int:
+    """Dynamic batch size (Sec. 2.1): of the picks in order, keep the longest prefix whose uncached
+    tokens sum(|x| - m) fit the prefill token budget; the first pick always stays (a prompt longer
+    than the budget must still run some time).  Returns how many picks are kept."""
+    total, keep = 0, 0
+    for j, i in enumerate(np.asarray(batch_idx).tolist()):
+        total += max(0, int(length[i]) - max(0, int(match_len[i])))
+        if j > 0 and total > token_budget:
+            break
+        keep = j + 1
+    return keep
+
+
+def phase_after_cut(phase_after: int, n_selected: int, n_kept: int, k: int) -> int:
+    """Position in the k-cycle once the picks beyond ``n_kept`` have been handed back."""
+    if k in (0, K_INF):
+        return 0
+    return (phase_after - (n_selected - n_kept)) % k
 
 
 def score_hit_rate(match_len, length, scale_bits: int = 30) -> np.ndarray:

@@ -327,7 +327,11 @@ static void insert_one(OTree *t, const int32_t *x, int32_t len, uint64_t tick, O
     }
 }
 
-static void evict_to_budget(OTree *t, int64_t budget, OStats *st) {
+/* protect: the paths of the `protect` most recently admitted prompts (ticks >= clock - protect) are in
+ * flight and must stay; eviction stops when the least recently used leaf is one of them, even if
+ * the total is still above the budget. */
+static void evict_to_budget(OTree *t, int64_t budget, int64_t protect, OStats *st) {
+    uint64_t keep_from = (protect <= 0) ? UINT64_MAX : ((uint64_t)protect >= t->clock ? 0 : t->clock - (uint64_t)protect);
     while (t->total_tokens > budget && t->n_all > 0) {
         ONode *victim = NULL;
         for (int64_t i = 0; i < t->n_all; i++) {
@@ -335,6 +339,7 @@ static void evict_to_budget(OTree *t, int64_t budget, OStats *st) {
             if (v->n_child != 0) continue;
             if (!victim || v->tick < victim->tick) victim = v;
         }
+        if (victim->tick >= keep_from) break;
         child_remove(victim->parent, victim);
         tree_unregister(t, victim);
         t->total_tokens -= victim->len;
@@ -347,14 +352,14 @@ static void evict_to_budget(OTree *t, int64_t budget, OStats *st) {
 }
 
 void orc_commit(OTree *t, const int32_t *tokens, const int64_t *off, const int32_t *len, const int32_t *batch_idx,
-                int32_t n_batch, int64_t budget, OStats *st) {
+                int32_t n_batch, int64_t budget, int64_t protect, OStats *st) {
     memset(st, 0, sizeof(*st));
     for (int32_t j = 0; j < n_batch; j++) {
         int32_t q = batch_idx[j];
         insert_one(t, tokens + off[q], len[q], t->clock, st);
         t->clock++;
     }
-    evict_to_budget(t, budget, st);
+    evict_to_budget(t, budget, protect, st);
     st->total_tokens = t->total_tokens;
     st->n_nodes = (int32_t)t->n_all;
     st->clock = t->clock;

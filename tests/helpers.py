@@ -92,18 +92,20 @@ class PathModel:
         ks = list(self.nodes)
         return [k for k in ks if not any(len(o) > len(k) and o[: len(k)] == k for o in ks)]
 
-    def evict(self, budget: int) -> int:
+    def evict(self, budget: int, protect: int = 0) -> int:
         n = 0
         while self.nodes and self.total() > budget:
             victim = min(self.leaves(), key=lambda k: self.nodes[k])
+            if protect > 0 and self.nodes[victim] >= self.clock - protect:
+                break  # the least recently used leaf belongs to a prompt still in flight
             del self.nodes[victim]
             n += 1
         return n
 
-    def commit(self, prompts: Sequence[Sequence[int]], budget: int) -> None:
+    def commit(self, prompts: Sequence[Sequence[int]], budget: int, protect: int = 0) -> None:
         for x in prompts:
             self.insert(x)
-        self.evict(budget)
+        self.evict(budget, protect)
 
     def snapshot(self) -> bytes:
         keys = sorted(self.nodes)

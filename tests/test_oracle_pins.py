@@ -561,3 +561,69 @@ def test_dynamic_select_reproduces_the_worked_example_in_one_bin():
     # FCFS order; a cache that keeps all of the bin's prompts (not only the last one, as Def. 2's
     # model does when it prints 30 and 40) still holds x1 when x3 comes, and x2 when x4 comes
     assert (got + 1).tolist() == g["s0_fcfs_order"] and np.cumsum(p.len[got] - sc[got]).tolist() == [10, 20, 25, 30]
+
+
+# ----------------------------------------------------------------------------- serving-side variants
+@pytest.mark.parametrize("seed", range(8))
+def test_eviction_protects_prompts_in_flight(seed):
+    rng = np.random.default_rng(900 + seed)
+    w = W.random_small(seed + 700, n_cache=10, n_query=30, vocab=3, max_len=8)
+    tree, model = oracle.OracleTree(), PathModel()
+    tree.build(w.cache)
+    model.commit([w.cache.tokens[int(o): int(o) + int(l)] for o, l in zip(w.cache.off, w.cache.len)], 1 << 60)
+    q = w.queries
+    history = []
+    for step in range(5):
+        idx = rng.choice(q.n, size=4, replace=False).astype(np.int32)
+        budget, protect = int(rng.integers(0, 25)), int(rng.integers(0, 7))
+        st = tree.commit(q.tokens, q.off, q.len, idx, budget, protect=protect)
+        xs = [q.tokens[int(q.off[i]): int(q.off[i]) + int(q.len[i])].tolist() for i in idx]
+        model.commit(xs, budget, protect)
+        assert tree.snapshot() == model.snapshot()
+        history.extend(xs)
+        # whatever the budget, the last `protect` admitted prompts are still cached in full
+        for x in history[len(history) - protect:] if protect else []:
+            arr = np.array(x, np.int32)
+            assert tree.match(arr, np.zeros(1, np.int64), np.array([len(x)], np.int32))[0] == len(x)
+        # and eviction went as far as it could: either within budget, or nothing unprotected is left
+        if st.total_tokens > budget:
+            rec = parse_snapshot(tree.snapshot())[3]
+            assert protect > 0 and all(int(t) >= st.clock - protect for t in rec["tick"])
+    # protect = 0 is the plain rule
+    a, b = oracle.OracleTree(), oracle.OracleTree()
+    a.build(w.cache), b.build(w.cache)
+    idx = np.arange(6, dtype=np.int32)
+    a.commit(q.tokens, q.off, q.len, idx, 12)
+    b.commit(q.tokens, q.off, q.len, idx, 12, protect=0)
+    assert a.snapshot() == b.snapshot()
+
+
+def test_token_budget_cut_and_phase():
+    ln = np.array([10, 4, 7, 3, 9], np.int32)
+    m = np.array([2, 4, 0, 1, 9], np.int32)   # costs 8, 0, 7, 2, 0
+    order = np.array([0, 1, 2, 3, 4])
+    assert [oracle.token_budget_cut(order, ln, m, b) for b in (0, 7, 8, 14, 15, 16, 17, 100)] == [1, 1, 2, 2, 3, 3, 5, 5]
+    assert oracle.token_budget_cut(order[::-1], ln, m, 0) == 1  # pick 4 is free, pick 3 already overflows
+    assert oracle.token_budget_cut(np.array([4, 1, 3]), ln, m, 0) == 2  # free picks ride along until something costs
+    assert oracle.token_budget_cut(np.zeros(0, np.int64), ln, m, 5) == 0
+    # brute force: the kept count is the largest prefix (of at least one pick) within the budget
+    rng = np.random.default_rng(4)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        ln = rng.integers(1, 30, size=n)
+        m = (rng.random(n) * (ln + 1)).astype(np.int64).clip(0, ln)
+        order = rng.permutation(n)
+        b = int(rng.integers(0, 80))
+        cost = np.cumsum((ln - m)[order])
+        want = max(1, int((cost <= b).sum()) if (np.diff((cost <= b).astype(int)) <= 0).all() else 0)
+        assert oracle.token_budget_cut(order, ln, m, b) == want
+    # handing picks back rewinds the k-cycle: selecting n_kept in the first place gives the same phase
+    arrival = np.arange(20, dtype=np.uint64)
+    mm = rng.integers(0, 9, size=20).astype(np.int32)
+    for k in (1, 2, 3, 7, K_INF):
+        for phase in (0, 1, 5):
+            full, ph_full = oracle.select(arrival, mm, k, 12, phase)
+            for kept in (1, 5, 12):
+                part, ph_part = oracle.select(arrival, mm, k, kept, phase)
+                assert part.tolist() == full[:kept].tolist()
+                assert oracle.phase_after_cut(ph_full, 12, kept, k) == ph_part
