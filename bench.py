@@ -198,6 +198,8 @@ def main() -> int:
     ap.add_argument("--random-ties", action="store_true", help="break score ties uniformly at random (Philox keys)")
     ap.add_argument("--dynamic", action="store_true",
                     help="in-batch rescoring: scores follow the prompts picked earlier in the same batch")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the prefill-token cut and the cache-slot output on the last batch")
     ap.add_argument("--workload", choices=("cfg2-large", "def3"), default="cfg2-large",
                     help="def3: the timed Regular Arrival Shuffled Queue run (second workload)")
     ap.add_argument("--def3-u", type=int, default=3000, help="shared-prefix length of the def3 workload (prompt = 6000)")
@@ -333,6 +335,33 @@ def main() -> int:
                                  if args.scale == 1.0 and args.steps == 20 and args.warmup == 3 and not args.deep else None),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": float(match_ms.mean())},
     }
+
+    if args.extras:
+        # serving-side steps on the last step's state (outside the timed loop): the prefill-token cut
+        # of the batch and the cache slots of its matched prefixes
+        q = run.view()
+        sched.match(q)
+        sched.select(q, k, batch, fifo=True)
+        n_m = torch.zeros(batch, dtype=torch.int32, device=dev)
+        slots = torch.empty(batch * max_len, dtype=torch.int64, device=dev)
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        reps = 20
+        for _ in range(3):
+            K.kLPM_kv_slots(sched.tree, q, sched.batch_idx, sched.n_selected, batch, max_len, n_m, slots)
+        e0.record()
+        for _ in range(reps):
+            K.kLPM_batch_token_budget(q, sched.match_len, sched.batch_idx, sched.n_selected, batch, 1 << 50, k, sched.phase)
+        e1.record()
+        for _ in range(reps):
+            K.kLPM_kv_slots(sched.tree, q, sched.batch_idx, sched.n_selected, batch, max_len, n_m, slots)
+        e2.record()
+        torch.cuda.synchronize()
+        m_batch = int(n_m.sum().item())
+        kv_ms = e1.elapsed_time(e2) / reps
+        out["extras"] = {"token_budget_ms": e0.elapsed_time(e1) / reps, "kv_slots_ms": kv_ms,
+                         "kv_slots_matched_tokens": m_batch,
+                         # per matched token: 4 B query + 4 B edge token read, 8 B slot written
+                         "kv_slots_GBps": 16.0 * m_batch / (kv_ms * 1e-3) / 1e9}
 
     if args.cpu_steps > 0:
         cores = len(os.sched_getaffinity(0))

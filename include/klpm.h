@@ -196,6 +196,44 @@ int kLPM_tie_keys(uint64_t seed, uint64_t step, const int32_t *id, int32_t n, co
 int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_idx, const int32_t *n_selected,
                 int32_t batch_cap, kLPM_stats *stats, kLPM_stream stream);
 
+/*
+ * Eviction protection for prompts in flight: the paths of the `recent_prompts` most recently
+ * admitted prompts (the batch of the commit itself included) are never evicted by later commits;
+ * eviction then stops early and the token total may stay above the budget (kLPM_stats.total_tokens
+ * tells).  0 (the default) protects nothing: plain LRU under the fixed cache size (Sec. 1).
+ * Host-side, takes effect at the next kLPM_commit.
+ */
+int kLPM_set_protect(kLPM_tree *tree, int64_t recent_prompts);
+
+/*
+ * Dynamic batch size under a prefill token budget (Sec. 2.1: dynamic batch size with a fixed
+ * memory pool): of the picks batch_idx[0 .. *n_selected) keep the longest prefix whose uncached
+ * tokens, sum of len - match_len, fit `token_budget`; the first pick always stays.  *n_selected is
+ * lowered accordingly and *phase_inout is rewound by the picks handed back, so that the k-cycle
+ * continues as if only the kept picks had been made.  Call between kLPM_select and kLPM_commit with
+ * the k that the selection used.  All pointers DEVICE.
+ */
+int kLPM_batch_token_budget(const kLPM_queries *q, const int32_t *match_len, const int32_t *batch_idx,
+                            int32_t *n_selected, int32_t batch_cap, int64_t token_budget, uint32_t k,
+                            uint32_t *phase_inout, kLPM_stream stream);
+
+/*
+ * Cache slots of a batch's matched prefixes (what the prefix cache returns for attention to read:
+ * RadixAttention, Sec. 1).  For pick j (prompt batch_idx[j] of q) and t < n_matched[j],
+ * slots[j * stride + t] identifies the cache entry of token t of that prompt: equal prefixes get
+ * equal slots, different cached prefixes different ones.  A slot is the position of the token in
+ * the tree's token pool; slots stay valid until a commit evicts the entry or compacts the pool, so
+ * they are taken after kLPM_match / kLPM_select and used before the next kLPM_commit.
+ *   stride     row length, >= the longest match wanted (longer matches are cut at stride)
+ *   n_matched  DEVICE [batch_cap] out: matched tokens of pick j (0 beyond *n_selected, -1 bad input)
+ *   slots      DEVICE [batch_cap * stride] out
+ */
+int kLPM_kv_slots(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_idx, const int32_t *n_selected,
+                  int32_t batch_cap, int32_t stride, int32_t *n_matched, int64_t *slots, kLPM_stream stream);
+
+/* tokens_out[i] = the token held in cache slot slots[i] (-1 for a value that is no slot).  DEVICE arrays [n]. */
+int kLPM_gather_slots(kLPM_tree *tree, const int64_t *slots, int64_t n, int32_t *tokens_out, kLPM_stream stream);
+
 /* Change the KV budget used by later commits (host-side, takes effect at the next kLPM_commit). */
 int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens);
 

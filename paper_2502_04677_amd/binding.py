@@ -25,7 +25,7 @@ DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
     "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
-    "kLPM_commit", "kLPM_set_budget", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
+    "kLPM_commit", "kLPM_set_budget", "kLPM_set_protect", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
     "kLPM_read_stats",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
@@ -81,6 +81,10 @@ def load_library() -> C.CDLL:
     lib.kLPM_tie_keys.argtypes = [C.c_uint64, C.c_uint64, vp, i32, vp, vp, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
     lib.kLPM_set_budget.argtypes = [vp, i64]
+    lib.kLPM_set_protect.argtypes = [vp, i64]
+    lib.kLPM_batch_token_budget.argtypes = [C.POINTER(Queries), vp, vp, vp, i32, i64, u32, vp, vp]
+    lib.kLPM_kv_slots.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, i32, vp, vp, vp]
+    lib.kLPM_gather_slots.argtypes = [vp, vp, i64, vp, vp]
     lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
                                        vp, vp, vp, vp, sz, vp, vp]
     lib.kLPM_queue_advance_timed.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32,
@@ -261,6 +265,32 @@ def kLPM_commit(tree: Tree, q: DeviceQueries, batch_idx: Optional[torch.Tensor],
     qs = q.c_struct()
     _check(_lib.kLPM_commit(tree.handle, C.byref(qs), _ptr(batch_idx), _ptr(n_selected), int(batch_cap), _ptr(stats),
                             _stream(stream)), "kLPM_commit")
+
+
+def kLPM_set_protect(tree: Tree, recent_prompts: int) -> None:
+    _check(_lib.kLPM_set_protect(tree.handle, int(recent_prompts)), "kLPM_set_protect")
+
+
+def kLPM_batch_token_budget(q: DeviceQueries, match_len: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
+                            batch_cap: int, token_budget: int, k: int, phase_inout: torch.Tensor, stream=None) -> None:
+    qs = q.c_struct()
+    _check(_lib.kLPM_batch_token_budget(C.byref(qs), _ptr(match_len), _ptr(batch_idx), _ptr(n_selected), int(batch_cap),
+                                        int(token_budget), C.c_uint32(k & 0xFFFFFFFF), _ptr(phase_inout), _stream(stream)),
+           "kLPM_batch_token_budget")
+
+
+def kLPM_kv_slots(tree: Tree, q: DeviceQueries, batch_idx: torch.Tensor, n_selected: torch.Tensor, batch_cap: int,
+                  stride: int, n_matched: torch.Tensor, slots: torch.Tensor, stream=None) -> None:
+    qs = q.c_struct()
+    assert slots.dtype == torch.int64 and slots.numel() >= batch_cap * stride and n_matched.numel() >= batch_cap
+    _check(_lib.kLPM_kv_slots(tree.handle, C.byref(qs), _ptr(batch_idx), _ptr(n_selected), int(batch_cap), int(stride),
+                              _ptr(n_matched), _ptr(slots), _stream(stream)), "kLPM_kv_slots")
+
+
+def kLPM_gather_slots(tree: Tree, slots: torch.Tensor, tokens_out: torch.Tensor, stream=None) -> None:
+    assert slots.dtype == torch.int64 and tokens_out.dtype == torch.int32 and tokens_out.numel() >= slots.numel()
+    _check(_lib.kLPM_gather_slots(tree.handle, _ptr(slots), int(slots.numel()), _ptr(tokens_out), _stream(stream)),
+           "kLPM_gather_slots")
 
 
 def kLPM_set_budget(tree: Tree, budget_tokens: int) -> None:

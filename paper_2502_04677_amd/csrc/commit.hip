@@ -524,7 +524,7 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 }
 
 // ------------------------------------------------------------------ ticks, then publish the inserts
-__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget) {
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect) {
     DevState *st = tv.st;
     const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
     if (!st->skip && j < st->nb) {
@@ -595,6 +595,8 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
             st->pool_top += st->tail_total;
             st->total_tokens += st->inserted_tokens;
             st->n_nodes += st->new_nodes;
+            // the paths of the `protect` most recently admitted prompts (this batch included) stay
+            st->keep_from = protect <= 0 ? ~0ull : ((uint64_t)protect >= st->clock ? 0ull : st->clock - (uint64_t)protect);
             int64_t need = st->total_tokens - budget;
             if (need > 0) {
                 st->do_evict = 1;
@@ -620,7 +622,9 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
 
 // One step of the search for the cut key, run by one workgroup of 256 threads once the weighted
 // histogram of the current digit is complete: pick the smallest digit whose inclusive weight
-// reaches what is still to be freed, append it to the prefix and reduce the remainder.
+// reaches what is still to be freed, append it to the prefix and reduce the remainder.  When the
+// nodes that may go (protected ones are left out of the histograms) do not free enough, the largest
+// digit is taken at every step and the cut ends above every key: all of them go.
 __device__ void evict_descend_step(DevState *st, const int64_t *__restrict__ hist) {
     __shared__ int64_t part[256 / kWave];
     __shared__ int pick;
@@ -660,9 +664,10 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     __syncthreads();
     const int shift = kEvictDigitBits * (n_pass - 1 - pass);
     const int32_t n_slots = st->n_slots;
+    const uint64_t keep_from = st->keep_from;
     for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
         int32_t len = tv.edge_len[id];
-        if (len <= 0) continue;
+        if (len <= 0 || tv.tick[id] >= keep_from) continue;
         uint64_t key = evict_key(tv, id, depth_bits);
         bool in_prefix = (pass == 0) || ((key >> (shift + kEvictDigitBits)) == prefix);
         if (in_prefix) atomicAdd(&h[(key >> shift) & (uint64_t)(kEvictBins - 1)], (unsigned long long)len);
@@ -679,13 +684,14 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
     __shared__ unsigned long long s_tok;
     __shared__ int s_cnt;
     const int tid = threadIdx.x;
-    const uint64_t cut = st->evict_prefix;  // every live node with key <= cut goes
+    const uint64_t cut = st->evict_prefix;  // every live, unprotected node with key <= cut goes
+    const uint64_t keep_from = st->keep_from;
     if (tid == 0) { s_tok = 0; s_cnt = 0; }
     __syncthreads();
     const int32_t n_slots = st->n_slots;
     for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
         int32_t len = tv.edge_len[id];
-        if (len <= 0) continue;
+        if (len <= 0 || tv.tick[id] >= keep_from) continue;
         if (evict_key(tv, id, depth_bits) <= cut) {
             tv.edge_len[id] = 0;
             // leave a tombstone where the parent pointed at this node
@@ -724,7 +730,7 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
 }
 
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
-                    int32_t batch_cap, int64_t budget, kLPM_stats *stats_out, hipStream_t stream) {
+                    int32_t batch_cap, int64_t budget, int64_t protect, kLPM_stats *stats_out, hipStream_t stream) {
     const TreeView &tv = t->tv;
     const CommitWs &ws = t->ws;
     if (batch_cap > t->cfg.max_batch) batch_cap = t->cfg.max_batch;
@@ -742,7 +748,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
     hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,
-                       budget);
+                       budget, protect);
     // eviction key = (tick, inverted depth); its width follows from host-known upper bounds
     t->clock_ub += (uint64_t)(batch_cap > 0 ? batch_cap : 0);
     int tick_bits = 1;

@@ -63,6 +63,7 @@ struct DevState {
     int32_t pad1;
     uint64_t evict_prefix; // digits of the eviction cut key fixed so far
     int64_t evict_rem;     // tokens still to free among the keys that share that prefix
+    uint64_t keep_from;    // nodes with tick >= this belong to prompts in flight and are not evicted
 };
 
 // Everything a kernel needs to walk or edit the tree; passed by value.

@@ -11,6 +11,7 @@ struct kLPM_tree {
     void *arena;
     size_t arena_bytes;
     int64_t budget;
+    int64_t protect;    // most recently admitted prompts whose paths eviction must leave alone
     uint64_t clock_ub;  // host-side upper bound of the logical clock (sizes the eviction key)
     int depth_bits;     // bits needed for a depth value (<= max_prompt_len)
 };
@@ -24,7 +25,7 @@ int launch_match(const TreeView &tv, const QView &q, const int32_t *sel, const i
 
 // Enqueue one whole commit (insert + evict) on the stream.
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
-                    int32_t batch_cap, int64_t budget, kLPM_stats *stats_out, hipStream_t stream);
+                    int32_t batch_cap, int64_t budget, int64_t protect, kLPM_stats *stats_out, hipStream_t stream);
 
 // The two total orders behind Algorithm 1's picks, as built by the sorting path of the selection:
 // queue indices in oldest-first order (arrival, index) and in longest-match order (-score, [tie key,]

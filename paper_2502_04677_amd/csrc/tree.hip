@@ -331,6 +331,7 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     t->arena = arena;
     t->arena_bytes = arena_bytes;
     t->budget = cfg->budget_tokens;
+    t->protect = 0;
     t->clock_ub = 0;
     t->depth_bits = 1;
     while ((cfg->max_prompt_len >> t->depth_bits) != 0) ++t->depth_bits;
@@ -370,7 +371,7 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
             int32_t cnt = std::min(cfg->max_batch, initial->n - base_i);
             hipLaunchKernelGGL(k_iota, dim3((cnt + 255) / 256), dim3(256), 0, stream, ws.iota_idx, ws.iota_n, base_i,
                                cnt);
-            rc = commit_pipeline(t, q, ws.iota_idx, ws.iota_n, cnt, INT64_MAX, nullptr, stream);
+            rc = commit_pipeline(t, q, ws.iota_idx, ws.iota_n, cnt, INT64_MAX, 0, nullptr, stream);
         }
     }
     if (rc != KLPM_OK) {
@@ -395,8 +396,14 @@ extern "C" int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t
     if (!tree || !queries_ok(q) || batch_cap < 0) return KLPM_EINVAL;
     if (batch_cap > 0 && (!batch_idx || !n_selected)) return KLPM_EINVAL;
     if (batch_cap > tree->cfg.max_batch) return KLPM_EINVAL;
-    return commit_pipeline(tree, make_qview(q), batch_idx, n_selected, batch_cap, tree->budget, stats,
+    return commit_pipeline(tree, make_qview(q), batch_idx, n_selected, batch_cap, tree->budget, tree->protect, stats,
                            (hipStream_t)stream_);
+}
+
+extern "C" int kLPM_set_protect(kLPM_tree *tree, int64_t recent_prompts) {
+    if (!tree || recent_prompts < 0) return KLPM_EINVAL;
+    tree->protect = recent_prompts;
+    return KLPM_OK;
 }
 
 extern "C" int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens) {

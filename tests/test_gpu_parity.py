@@ -739,3 +739,130 @@ def test_dynamic_select_medium_queue_then_commit():
     ref.commit(hq2.tokens, hq2.off, hq2.len, idx_ref, w.budget)
     assert s.read_stats().device_error == 0
     _same_tree(s, ref, big=True)
+
+
+# ----------------------------------------------------------------------------- serving-side variants
+@pytest.mark.parametrize("seed", range(4))
+def test_eviction_protection_small(seed):
+    rng = np.random.default_rng(40 + seed)
+    w = W.random_small(seed + 700, n_cache=10, n_query=40, vocab=3, max_len=8)
+    s, ref, q = _setup(w, max_batch=8)
+    hq = w.queries
+    for step in range(8):
+        idx = rng.choice(hq.n, size=int(rng.integers(1, 8)), replace=False).astype(np.int32)
+        budget, protect = int(rng.integers(0, 30)), int(rng.integers(0, 10))
+        s.batch_idx[: idx.shape[0]] = torch.from_numpy(idx).cuda()
+        s.n_selected.fill_(idx.shape[0])
+        K.kLPM_set_budget(s.tree, budget)
+        K.kLPM_set_protect(s.tree, protect)
+        s.commit(q, 8)
+        st_ref = ref.commit(hq.tokens, hq.off, hq.len, idx, budget, protect=protect)
+        st = s.read_stats()
+        assert st.device_error == 0
+        assert (st.total_tokens, st.evicted_tokens, st.n_nodes, st.evicted_nodes, st.clock) == (
+            st_ref.total_tokens, st_ref.evicted_tokens, st_ref.n_nodes, st_ref.evicted_nodes, st_ref.clock), (step, budget, protect)
+        _same_tree(s, ref)
+
+
+def test_eviction_protection_stream():
+    """Config-4-like stream with a budget far below what the prompts in flight need: the last two
+    batches stay cached whatever the budget says."""
+    stream = W.config4_stream(steps=30, rate=24, groups=400, budget=40_000, batch=16)
+    hq = stream.queries
+    q = K.DeviceQueries.from_host(hq)
+    cfg = K.size_config(0, 0, 400_000, stream.batch, int(hq.len.max()), extra_prompts=hq.n)
+    s = K.Scheduler(cfg, None, hq.n)
+    K.kLPM_set_budget(s.tree, stream.budget)
+    K.kLPM_set_protect(s.tree, 2 * stream.batch)
+    ref = oracle.OracleTree()
+    phase = 0
+    for step in range(stream.steps):
+        lo, hi = int(stream.step_start[step]), int(stream.step_start[step + 1])
+        sub = W.take_prompts(hq, np.arange(lo, hi))
+        dq = K.DeviceQueries.from_host(sub)
+        m = s.match(dq).cpu().numpy()[: sub.n]
+        m_ref = ref.match(sub.tokens, sub.off, sub.len)
+        assert (m == m_ref).all()
+        s.set_phase(phase)
+        s.select(dq, stream.k, stream.batch)
+        idx_ref, phase = oracle.select(sub.arrival, m_ref, stream.k, stream.batch, phase)
+        assert s.batch().tolist() == idx_ref.tolist()
+        s.commit(dq, stream.batch)
+        st_ref = ref.commit(sub.tokens, sub.off, sub.len, idx_ref, stream.budget, protect=2 * stream.batch)
+        st = s.read_stats()
+        assert st.device_error == 0 and (st.total_tokens, st.n_nodes, st.evicted_tokens) == (
+            st_ref.total_tokens, st_ref.n_nodes, st_ref.evicted_tokens), step
+        if step % 6 == 5:
+            _same_tree(s, ref)
+    _same_tree(s, ref)
+
+
+def test_batch_token_budget_cut():
+    w = W.config1(scale=0.125)
+    s, ref, q = _setup(w, max_batch=256)
+    hq = w.queries
+    m_ref = ref.match(hq.tokens, hq.off, hq.len)
+    live_d = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for live in (hq.n, 100):
+        live_d.fill_(live)
+        ql = K.DeviceQueries(q.tokens, q.off, q.len, q.arrival, q.n, n_live=live_d)
+        s.match(ql)
+        for k in (1, 3, 4, K_INF):
+            for batch in (1, 17, 256):
+                full_ref, ph_full = oracle.select(hq.arrival[:live], m_ref[:live], k, batch, 2)
+                cost = (hq.len[full_ref] - m_ref[full_ref]).astype(np.int64)
+                for budget in (0, int(cost[0]), int(cost.sum() // 3), int(cost.sum()) - 1, int(cost.sum()), 1 << 40):
+                    s.set_phase(2)
+                    s.select(ql, k, batch)
+                    K.kLPM_batch_token_budget(ql, s.match_len, s.batch_idx, s.n_selected, batch, budget, k, s.phase)
+                    keep = oracle.token_budget_cut(full_ref, hq.len, m_ref, budget)
+                    assert int(s.n_selected.item()) == keep, (live, k, batch, budget)
+                    assert s.batch().tolist() == full_ref[:keep].tolist()
+                    assert s.phase_value() == oracle.phase_after_cut(ph_full, full_ref.shape[0], keep, k)
+    # a cut batch commits like any other batch
+    s.commit(q, 256)
+    ref.commit(hq.tokens, hq.off, hq.len, full_ref[:keep], w.budget)
+    _same_tree(s, ref, big=True)
+
+
+def test_kv_slots_identify_cached_tokens():
+    """A slot is a function of the cached prefix string: it holds that prefix's last token, equal
+    prefixes share it, different prefixes never do; a query has exactly match_len of them."""
+    w = W.config0()
+    s, ref, q = _setup(w)
+    hq = w.queries
+    K.kLPM_set_budget(s.tree, 9000)
+    for step in range(3):
+        m_ref = ref.match(hq.tokens, hq.off, hq.len)
+        s.match(q)
+        s.set_phase(0)
+        s.select(q, 2, 32)
+        idx_ref, _ = oracle.select(hq.arrival, m_ref, 2, 32, 0)
+        idx = s.batch()
+        assert idx.tolist() == idx_ref.tolist()
+        stride = int(hq.len.max())
+        n_matched = torch.full((32,), -7, dtype=torch.int32, device="cuda:0")
+        slots = torch.full((32 * stride,), -1, dtype=torch.int64, device="cuda:0")
+        K.kLPM_kv_slots(s.tree, q, s.batch_idx, s.n_selected, 32, stride, n_matched, slots)
+        got_n = n_matched.cpu().numpy()
+        assert got_n.tolist() == m_ref[idx].tolist()
+        toks = torch.zeros(32 * stride, dtype=torch.int32, device="cuda:0")
+        K.kLPM_gather_slots(s.tree, slots, toks)
+        sl, tk = slots.cpu().numpy().reshape(32, stride), toks.cpu().numpy().reshape(32, stride)
+        by_prefix, by_slot = {}, {}
+        for j, qi in enumerate(idx.tolist()):
+            x = hq.tokens[int(hq.off[qi]): int(hq.off[qi]) + int(hq.len[qi])]
+            assert tk[j, : got_n[j]].tolist() == x[: got_n[j]].tolist()       # the slot holds the token
+            assert (sl[j, got_n[j]:] == -1).all() and (tk[j, got_n[j]:] == -1).all()  # nothing written past the match
+            for t in range(int(got_n[j])):
+                key = x[: t + 1].tobytes()
+                assert by_prefix.setdefault(key, int(sl[j, t])) == int(sl[j, t])  # same prefix, same slot
+                assert by_slot.setdefault(int(sl[j, t]), key) == key              # same slot, same prefix
+        s.commit(q, 32)
+        ref.commit(hq.tokens, hq.off, hq.len, idx_ref, 9000)
+    # fewer picks than the capacity: the rest of n_matched is 0; a short stride cuts the rows
+    s.n_selected.fill_(3)
+    K.kLPM_kv_slots(s.tree, q, s.batch_idx, s.n_selected, 32, 16, n_matched, slots)
+    got = n_matched.cpu().numpy()
+    want = np.minimum(ref.match(hq.tokens, hq.off, hq.len)[s.batch_idx[:3].cpu().numpy()], 16)
+    assert got[:3].tolist() == want.tolist() and (got[3:] == 0).all()
