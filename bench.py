@@ -138,10 +138,22 @@ def bench_def3(args) -> int:
     def one_run():
         sched = K.Scheduler(cfg, None, cap, dev)
         run = K.TimedRun(sched, q, cap, p.arrival, c_num=c_num, c_den=c_den)
+        graphs = {}
+        if args.graph:  # one captured step per queue buffer set, replayed in turn
+            K.kLPM_reserve_clock(sched.tree, n + 8)
+            for _ in range(2):
+                parity = run.cur
+                graphs[parity] = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graphs[parity]):
+                    run.step(k, 1)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(n):  # one query per step: exactly n steps serve everybody
-            run.step(k, 1)
+            if graphs:
+                graphs[run.cur].replay()
+                run.cur = 1 - run.cur
+            else:
+                run.step(k, 1)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         assert int(run.queue.n.item()) == 0 and int(run.pending.cursor.item()) == n
@@ -163,7 +175,8 @@ def bench_def3(args) -> int:
         "ms_per_step": dt / n * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"def3-n{n}-rep{rep}-u{u}-d{d}", "k": k, "batch": 1, "kv_budget_tokens": budget,
-                   "arrival_gap_tokens": gap, "c_attn": c_num / c_den, "queue_cap": cap},
+                   "arrival_gap_tokens": gap, "c_attn": c_num / c_den, "queue_cap": cap,
+                   "launch": "hip graph replay" if args.graph else "stream"},
         "matched_tokens_per_run": matched,
         "ttft_token_times": {f"p{int(x * 100)}": float(np.sort(ttft)[int(np.ceil(x * n)) - 1]) / c_den
                              for x in (0.5, 0.9, 0.95, 0.99)},
@@ -198,6 +211,8 @@ def main() -> int:
     ap.add_argument("--random-ties", action="store_true", help="break score ties uniformly at random (Philox keys)")
     ap.add_argument("--dynamic", action="store_true",
                     help="in-batch rescoring: scores follow the prompts picked earlier in the same batch")
+    ap.add_argument("--graph", action="store_true",
+                    help="after the timed steps, replay K more steps from one captured HIP graph and report them too")
     ap.add_argument("--extras", action="store_true",
                     help="also time the prefill-token cut and the cache-slot output on the last batch")
     ap.add_argument("--workload", choices=("cfg2-large", "def3"), default="cfg2-large",
@@ -217,7 +232,7 @@ def main() -> int:
     if args.workload == "def3":
         return bench_def3(args)
     dev = torch.device("cuda:0")
-    steps_total = args.steps + args.warmup
+    steps_total = args.steps + args.warmup + (2 * args.steps if args.graph else 0)
     w, allq = build_workload(args.scale, steps_total, args.deep)
     batch, k, n0 = w.batch, w.k, w.queries.n
     max_len = int(max(w.cache.len.max(), allq.len.max()))
@@ -248,19 +263,25 @@ def main() -> int:
         dyn_ws = K.alloc_aligned(dyn_bytes, dev)
         dyn = torch.zeros(n0, dtype=torch.int32, device=dev)
 
+    timing = {"on": True}  # no event records while a graph is being captured
+
+    def mark(s: int, i: int) -> None:
+        if timing["on"]:
+            ev[s][i].record()
+
     def one_step(s: int) -> None:
         q = run.view()
-        ev[s][0].record()
+        mark(s, 0)
         sched.match(q, want_nodes=args.dynamic)
-        ev[s][1].record()
+        mark(s, 1)
         if args.dynamic:  # Algorithm 1 on scores that follow the picks made so far in the bin
             K.kLPM_select_dynamic(q, sched.match_len, sched.last_node, k, batch, sched.phase, dyn, sched.batch_idx,
                                   sched.n_selected, dyn_ws, dyn_bytes)
-            ev[s][2].record()
+            mark(s, 2)
             sched.commit(q, batch)
-            ev[s][3].record()
+            mark(s, 3)
             run.advance(batch, new_ids[s], matched=sums[s:s + 1])
-            ev[s][4].record()
+            mark(s, 4)
             return
         if score is not None:  # hit rate instead of match length (the wording of Algorithm 1)
             K.kLPM_score_hit_rate(sched.match_len, q.len, n0, rate_bits, score)
@@ -268,11 +289,11 @@ def main() -> int:
             K.kLPM_tie_keys(TIE_SEED, s, run.queue.id, n0, tie)
         # the queue is kept in arrival order
         sched.select(q, k, batch, fifo=True, score=score, score_max=1 << rate_bits, tie_key=tie)
-        ev[s][2].record()
+        mark(s, 2)
         sched.commit(q, batch)
-        ev[s][3].record()
+        mark(s, 3)
         run.advance(batch, new_ids[s], matched=sums[s:s + 1])
-        ev[s][4].record()
+        mark(s, 4)
 
     if args.calib_copy_mib > 0:
         # a plain elementwise copy of known size: reads and writes calib_copy_mib MiB each
@@ -287,20 +308,42 @@ def main() -> int:
         one_step(s)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for s in range(args.warmup, steps_total):
+    for s in range(args.warmup, args.warmup + args.steps):
         one_step(s)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
 
+    graph_elapsed = None
+    if args.graph:
+        # the next K steps once more, captured into one HIP graph (every library call only enqueues
+        # kernels) and replayed in one go: the same launches without the per-launch host cost
+        # (two graphs of K steps each: the first replay is a warm-up of the graph machinery)
+        K.kLPM_reserve_clock(sched.tree, (2 * args.steps + 1) * batch)
+        g_warm, g = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+        timing["on"] = False
+        with torch.cuda.graph(g_warm):
+            for s in range(args.warmup + args.steps, args.warmup + 2 * args.steps):
+                one_step(s)
+        with torch.cuda.graph(g):
+            for s in range(args.warmup + 2 * args.steps, steps_total):
+                one_step(s)
+        timing["on"] = True
+        g_warm.replay()
+        torch.cuda.synchronize()
+        t_g = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        graph_elapsed = time.perf_counter() - t_g
+
     st = sched.read_stats()
     assert st.device_error == 0 and int(run.dev_error.item()) == 0, f"device error {st.device_error}"
     sums_h = sums.cpu().numpy()
-    timed = range(args.warmup, steps_total)
+    timed = range(args.warmup, args.warmup + args.steps)
     match_ms = np.array([ev[s][0].elapsed_time(ev[s][1]) for s in timed])
     select_ms = np.array([ev[s][1].elapsed_time(ev[s][2]) for s in timed])
     commit_ms = np.array([ev[s][2].elapsed_time(ev[s][3]) for s in timed])
     adv_ms = np.array([ev[s][3].elapsed_time(ev[s][4]) for s in timed])
-    sum_timed = int(sums_h[args.warmup:].sum())
+    sum_timed = int(sums_h[args.warmup:args.warmup + args.steps].sum())
     value = sum_timed / elapsed
     alg_bytes = float(np.mean([algorithmic_bytes(int(sums_h[s]), n0) for s in timed]))
     match_s = float(match_ms.mean()) * 1e-3
@@ -327,14 +370,20 @@ def main() -> int:
         "schedule_latency_us": elapsed / args.steps * 1e6,
         "phase_ms": {"match": float(match_ms.mean()), "select": float(select_ms.mean()),
                      "commit": float(commit_ms.mean()), "queue_advance": float(adv_ms.mean())},
-        "match_tokens_per_s_kernel": float(np.mean(sums_h[args.warmup:])) / match_s,
-        "matched_tokens_per_step": float(np.mean(sums_h[args.warmup:])),
+        "match_tokens_per_s_kernel": float(np.mean(sums_h[args.warmup:args.warmup + args.steps])) / match_s,
+        "matched_tokens_per_step": float(np.mean(sums_h[args.warmup:args.warmup + args.steps])),
         "roofline": {"kernel": "k_match", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (recorded_traffic()
                                  if args.scale == 1.0 and args.steps == 20 and args.warmup == 3 and not args.deep else None),
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": float(match_ms.mean())},
     }
+
+    if graph_elapsed is not None:
+        g_sum = int(sums_h[args.warmup + 2 * args.steps:].sum())
+        out["graph_replay"] = {"steps": args.steps, "ms_per_step": graph_elapsed / args.steps * 1e3,
+                               "value": g_sum / graph_elapsed, "unit": "tokens/s",
+                               "note": "K later steps captured into one HIP graph and replayed once (after a warm-up replay of K steps)"}
 
     if args.extras:
         # serving-side steps on the last step's state (outside the timed loop): the prefill-token cut

@@ -39,6 +39,8 @@ extern "C" {
 #define KLPM_DEV_POOL_FULL 2u      /* edge-token pool cannot take the batch even after compaction */
 #define KLPM_DEV_BAD_INPUT 4u      /* a prompt offset/length outside the token buffer or limits */
 #define KLPM_DEV_BATCH_OVERFLOW 8u /* *n_selected larger than the capacity given to kLPM_commit */
+#define KLPM_DEV_CLOCK_RANGE 16u   /* more prompts admitted than the launch sequence was sized for
+                                      (see kLPM_reserve_clock); that commit evicted nothing */
 
 /* k value that encodes k = infinity (pure longest-prefix-match order); k = 0 means the same. */
 #define KLPM_K_INFINITY 0xFFFFFFFFu
@@ -233,6 +235,16 @@ int kLPM_kv_slots(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_i
 
 /* tokens_out[i] = the token held in cache slot slots[i] (-1 for a value that is no slot).  DEVICE arrays [n]. */
 int kLPM_gather_slots(kLPM_tree *tree, const int64_t *slots, int64_t n, int32_t *tokens_out, kLPM_stream stream);
+
+/*
+ * Every call only enqueues kernels (no memset or copy nodes, no synchronisation), so a scheduling
+ * step can be captured into a HIP graph and replayed.  The number of eviction passes a commit
+ * enqueues follows from a host-side bound of the LRU clock, which replays do not advance: before
+ * capturing, reserve as many admissions as will be replayed (or committed without the host seeing
+ * them).  A commit that finds the clock beyond the bound evicts nothing and sets
+ * KLPM_DEV_CLOCK_RANGE.  kLPM_read_stats re-reads the clock and renews the bound.
+ */
+int kLPM_reserve_clock(kLPM_tree *tree, uint64_t extra_prompts);
 
 /* Change the KV budget used by later commits (host-side, takes effect at the next kLPM_commit). */
 int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens);

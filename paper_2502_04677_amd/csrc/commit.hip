@@ -524,7 +524,7 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 }
 
 // ------------------------------------------------------------------ ticks, then publish the inserts
-__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect) {
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits) {
     DevState *st = tv.st;
     const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
     if (!st->skip && j < st->nb) {
@@ -598,6 +598,11 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
             // the paths of the `protect` most recently admitted prompts (this batch included) stay
             st->keep_from = protect <= 0 ? ~0ull : ((uint64_t)protect >= st->clock ? 0ull : st->clock - (uint64_t)protect);
             int64_t need = st->total_tokens - budget;
+            if (tick_bits < 64 && (st->clock >> tick_bits) != 0) {
+                // the eviction passes enqueued behind this kernel were sized for a smaller clock
+                flag_error(st, 16u /* KLPM_DEV_CLOCK_RANGE */);
+                need = 0;
+            }
             if (need > 0) {
                 st->do_evict = 1;
                 st->need_evict = need;
@@ -734,6 +739,15 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     const TreeView &tv = t->tv;
     const CommitWs &ws = t->ws;
     if (batch_cap > t->cfg.max_batch) batch_cap = t->cfg.max_batch;
+    // eviction key = (tick, inverted depth); its width follows from host-known upper bounds
+    const uint64_t clock_ub = t->clock_ub + (uint64_t)(batch_cap > 0 ? batch_cap : 0);
+    const uint64_t clock_bound = clock_ub + t->clock_reserve;
+    int tick_bits = 1;
+    while (tick_bits < 64 && (clock_bound >> tick_bits)) ++tick_bits;
+    const int key_bits = tick_bits + t->depth_bits;
+    if (key_bits > 64) return KLPM_EINVAL;
+    const int n_pass = (key_bits + kEvictDigitBits - 1) / kEvictDigitBits;
+    t->clock_ub = clock_ub;
     if (batch_cap > 0) {
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
         if (rc) return rc;
@@ -748,14 +762,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
     hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,
-                       budget, protect);
-    // eviction key = (tick, inverted depth); its width follows from host-known upper bounds
-    t->clock_ub += (uint64_t)(batch_cap > 0 ? batch_cap : 0);
-    int tick_bits = 1;
-    while (tick_bits < 64 && (t->clock_ub >> tick_bits)) ++tick_bits;
-    int key_bits = tick_bits + t->depth_bits;
-    if (key_bits > 64) return KLPM_EINVAL;
-    int n_pass = (key_bits + kEvictDigitBits - 1) / kEvictDigitBits;
+                       budget, protect, tick_bits);
     // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
     unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
     if (ge > 256u) ge = 256u;

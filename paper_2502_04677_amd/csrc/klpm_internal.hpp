@@ -13,6 +13,7 @@ struct kLPM_tree {
     int64_t budget;
     int64_t protect;    // most recently admitted prompts whose paths eviction must leave alone
     uint64_t clock_ub;  // host-side upper bound of the logical clock (sizes the eviction key)
+    uint64_t clock_reserve;  // admissions the caller may enqueue without this host code seeing them
     int depth_bits;     // bits needed for a depth value (<= max_prompt_len)
 };
 

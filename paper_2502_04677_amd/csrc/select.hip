@@ -862,6 +862,12 @@ __global__ __launch_bounds__(256) void k_fq_fcfs(LiveN nn, int32_t batch, FqWs w
     if (j < nb) batch_idx[j] = j;
 }
 
+// Zeroes the meta block and the histograms (a kernel rather than a memset node, so that the whole
+// selection can be captured into a HIP graph and replayed).
+__global__ __launch_bounds__(256) void k_fq_zero(uint32_t *__restrict__ p, int32_t n_words) {
+    for (int32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) p[i] = 0u;
+}
+
 static void carve_fq(FqWs &f, char *base, int32_t n, size_t *used) {
     size_t o = 0;
     auto take = [&](size_t bytes) { void *p = base ? base + o : nullptr; o += align_up(bytes, 256); return p; };
@@ -884,7 +890,8 @@ static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, L
     const int32_t nb = batch < nn.n ? batch : nn.n;  // upper bound of the picks, sizes the FCFS launch
     const int32_t nblk = (nn.n + kFqTile - 1) / kFqTile;
     // meta and histograms are contiguous at the start of the workspace
-    if (hipMemsetAsync(f.meta, 0, (size_t)((char *)f.blockcnt - (char *)f.meta), stream) != hipSuccess) return KLPM_EHIP;
+    const int32_t zero_words = (int32_t)(((char *)f.blockcnt - (char *)f.meta) / 4);
+    hipLaunchKernelGGL(k_fq_zero, dim3(32), dim3(256), 0, stream, (uint32_t *)f.meta, zero_words);
     int mbits = 0;
     while (mbits < 31 && (max_match >> mbits) != 0) ++mbits;
     if (mbits == 0) mbits = 1;

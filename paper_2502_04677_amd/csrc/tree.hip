@@ -333,6 +333,7 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     t->budget = cfg->budget_tokens;
     t->protect = 0;
     t->clock_ub = 0;
+    t->clock_reserve = 0;
     t->depth_bits = 1;
     while ((cfg->max_prompt_len >> t->depth_bits) != 0) ++t->depth_bits;
     TreeView &tv = t->tv;
@@ -398,6 +399,12 @@ extern "C" int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t
     if (batch_cap > tree->cfg.max_batch) return KLPM_EINVAL;
     return commit_pipeline(tree, make_qview(q), batch_idx, n_selected, batch_cap, tree->budget, tree->protect, stats,
                            (hipStream_t)stream_);
+}
+
+extern "C" int kLPM_reserve_clock(kLPM_tree *tree, uint64_t extra_prompts) {
+    if (!tree) return KLPM_EINVAL;
+    tree->clock_reserve = extra_prompts;
+    return KLPM_OK;
 }
 
 extern "C" int kLPM_set_protect(kLPM_tree *tree, int64_t recent_prompts) {
@@ -503,6 +510,7 @@ extern "C" int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_strea
     host_out->n_nodes = st.n_nodes;
     host_out->device_error = st.device_error;
     host_out->clock = st.clock;
+    if (st.clock > tree->clock_ub) tree->clock_ub = st.clock;  // admissions enqueued by graph replays
     return KLPM_OK;
 }
 

@@ -866,3 +866,47 @@ def test_kv_slots_identify_cached_tokens():
     got = n_matched.cpu().numpy()
     want = np.minimum(ref.match(hq.tokens, hq.off, hq.len)[s.batch_idx[:3].cpu().numpy()], 16)
     assert got[:3].tolist() == want.tolist() and (got[3:] == 0).all()
+
+
+# ----------------------------------------------------------------------------- replay from a captured HIP graph
+def test_graph_replay_of_scheduling_steps():
+    """A scheduling step with a device-side queue length has fixed launch shapes, so it can be
+    captured once per queue buffer set and replayed; every replay must leave what the eager step
+    leaves (checked against the oracle's run step by step, with host reads between replays)."""
+    n, u, rep, d, gap = 96, 40, 4, 25, 30
+    p, _ = W.shuffled_queue(n, u, rep, d, gap, seed=21)
+    k, batch, budget, cap = 3, 2, 4 * (u + d), 32
+    r = oracle.simulate_timed(p, k, batch, budget, c_num=1, c_den=128, queue_cap=cap)
+    q = K.DeviceQueries.from_host(p)
+    cfg = K.size_config(0, 0, budget, batch, int(p.len.max()), extra_prompts=2 * batch)
+    s = K.Scheduler(cfg, None, cap)
+    run = K.TimedRun(s, q, cap, p.arrival, c_num=1, c_den=128)
+    K.kLPM_reserve_clock(s.tree, n + 8)
+    # two eager steps first (they also bring every kernel's code onto the device)
+    done = 0
+    for _ in range(2):
+        run.step(k, batch)
+        done += 1
+    torch.cuda.synchronize()
+    graphs = {}
+    for _ in range(2):  # one graph per buffer set; capturing enqueues nothing
+        parity = run.cur
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run.step(k, batch)
+        graphs[parity] = g
+    assert set(graphs) == {0, 1} and run.cur in (0, 1)
+    while done < r.steps:
+        n_live = int(run.queue.n.item())
+        ids = run.queue.id[:n_live].cpu().numpy()
+        assert ids.tolist() == r.waiting_ids[done].tolist(), done
+        graphs[run.cur].replay()
+        run.cur = 1 - run.cur
+        torch.cuda.synchronize()
+        assert s.match_len[:n_live].cpu().numpy().tolist() == r.match_lens[done].tolist(), done
+        assert ids[s.batch()].tolist() == r.batches[done].tolist(), done
+        st = s.read_stats()  # host work between replays
+        assert st.device_error == 0
+        done += 1
+    assert int(run.queue.n.item()) == 0 and int(run.sim_clock.item()) == r.clock
+    assert run.ttft[:n].cpu().numpy().tolist() == r.ttft.tolist()
