@@ -156,7 +156,7 @@ def bench_def3(args) -> int:
                 run.step(k, 1)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        assert int(run.queue.n.item()) == 0 and int(run.pending.cursor.item()) == n
+        assert int(run.queue.n.item()) == 0 and int(run.queue.n_joined.item()) == n
         assert int(run.dev_error.item()) == 0 and sched.read_stats().device_error == 0
         return dt, run
 

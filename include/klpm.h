@@ -259,37 +259,35 @@ typedef struct {
     int64_t *off;      /* [cap] start of each waiting prompt in the stream's token pool */
     int32_t *len;      /* [cap] prompt lengths */
     int32_t *n;        /* [1]  entries in use */
+    uint64_t *clock;   /* [1]  simulated time at which this queue state holds */
+    int32_t *n_joined; /* [1]  timed runs: entries of the kLPM_arrivals list that have joined so far
+                               (NULL where kLPM_queue_advance_timed is not used) */
     int32_t cap;
 } kLPM_queue;
 
 /* Fill q->off / q->len from q->id (off = -1, len = 0 for an id outside `all`). */
 int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream stream);
 
-/* Scratch size for kLPM_queue_advance on queues of up to queue_cap entries. */
-int kLPM_queue_scratch_bytes(int32_t queue_cap, size_t *out_bytes);
-
 /*
  * Waiting-queue bookkeeping of an online run (query stream of Def. 1 served in bins, Sec. 2.1;
- * prefill cost of Def. 2 with c_attn = 0).  Given the batch just selected from `cur`: advance the
- * simulated time by max(1, sum over the batch of len - match_len), record TTFT = new time -
- * arrival for the admitted entries, and write into `next` (a distinct buffer set) the surviving
- * entries in their old order followed by the n_new arrivals stamped with the new time, together
- * with the CSR view of the new queue.
+ * prefill cost of Def. 2 with c_attn = 0).  Given the batch just selected from `cur`: the simulated
+ * time moves from *cur->clock by max(1, sum over the batch of len - match_len); TTFT = new time -
+ * arrival is recorded for the admitted entries; `next` (a distinct buffer set: entries, count and
+ * clock) receives the surviving entries in their old order followed by the n_new arrivals stamped
+ * with the new time, the CSR view of the new queue, its length and the new time.  One launch;
+ * nothing of `cur` is written, so the two buffer sets are used in turn.
  *   all         the whole stream's prompts (tokens unused; off/len indexed by global id)
  *   match_len   DEVICE [*cur->n] match lengths of the queue as scored this step
- *   batch_idx / n_selected  as written by kLPM_select (positions in `cur`)
+ *   batch_idx / n_selected  as written by kLPM_select (distinct positions in `cur`)
  *   new_id      DEVICE [n_new] global ids of the arrivals joining after this step
- *   sim_clock   DEVICE [1] in/out simulated time
  *   ttft        DEVICE [all->n] out (written for admitted ids only)
  *   matched_accum DEVICE [1] or NULL: += sum of match_len over the queue (throughput accounting)
- *   scratch     DEVICE, 256-byte aligned, >= kLPM_queue_scratch_bytes(cur->cap)
  * Arrivals that do not fit next->cap are dropped and set KLPM_DEV_BATCH_OVERFLOW in *dev_error.
  */
 int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
                        const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
-                       int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock, int64_t *ttft,
-                       int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
-                       kLPM_stream stream);
+                       int32_t batch_cap, const int32_t *new_id, int32_t n_new, int64_t *ttft, int64_t *matched_accum,
+                       uint32_t *dev_error, kLPM_stream stream);
 
 /*
  * Arrivals that reach the scheduler at their own times (query stream of Def. 1; the Regular
@@ -299,7 +297,6 @@ int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM
 typedef struct {
     const int32_t *id;    /* [n] global query ids ordered by (arrival time, id) */
     const uint64_t *time; /* [n] their arrival times t_i, non-decreasing */
-    int32_t *cursor;      /* [1] in/out: how many of them have joined the queue so far */
     int32_t n;
     uint32_t c_num;       /* attention coefficient of Def. 2: c_attn = c_num / c_den */
     uint32_t c_den;       /* >= 1 */
@@ -313,14 +310,14 @@ typedef struct {
  * keeping its own arrival time, as far as next->cap allows (the rest stay pending, in order).  If
  * that leaves the queue empty while arrivals are still pending, the clock jumps to the next
  * arrival time (a query cannot start before it arrives, Def. 2) and the queries arriving then join.
- * The queue length is left in *next->n for the next step's n_live.  Calling it on an empty queue
- * with *n_selected = 0 performs the initial fill.
+ * How many arrivals have joined is read from *cur->n_joined and left in *next->n_joined; the queue
+ * length is left in *next->n for the next step's n_live.  Calling it on an empty queue with
+ * *n_selected = 0 performs the initial fill.
  */
 int kLPM_queue_advance_timed(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
                              const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
-                             int32_t batch_cap, const kLPM_arrivals *pending, uint64_t *sim_clock, int64_t *ttft,
-                             int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
-                             kLPM_stream stream);
+                             int32_t batch_cap, const kLPM_arrivals *pending, int64_t *ttft, int64_t *matched_accum,
+                             uint32_t *dev_error, kLPM_stream stream);
 
 /* Synchronises the stream and copies the tree's counters to HOST memory. */
 int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_stream stream);

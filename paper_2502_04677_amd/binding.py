@@ -25,7 +25,7 @@ DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
     "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
-    "kLPM_commit", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather", "kLPM_queue_scratch_bytes",
+    "kLPM_commit", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather",
     "kLPM_read_stats",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
@@ -37,13 +37,12 @@ class Queries(C.Structure):
 
 
 class Arrivals(C.Structure):
-    _fields_ = [("id", C.c_void_p), ("time", C.c_void_p), ("cursor", C.c_void_p), ("n", C.c_int32),
-                ("c_num", C.c_uint32), ("c_den", C.c_uint32)]
+    _fields_ = [("id", C.c_void_p), ("time", C.c_void_p), ("n", C.c_int32), ("c_num", C.c_uint32), ("c_den", C.c_uint32)]
 
 
 class Queue(C.Structure):
     _fields_ = [("id", C.c_void_p), ("arrival", C.c_void_p), ("off", C.c_void_p), ("len", C.c_void_p),
-                ("n", C.c_void_p), ("cap", C.c_int32)]
+                ("n", C.c_void_p), ("clock", C.c_void_p), ("n_joined", C.c_void_p), ("cap", C.c_int32)]
 
 
 class Config(C.Structure):
@@ -87,11 +86,10 @@ def load_library() -> C.CDLL:
     lib.kLPM_kv_slots.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, i32, vp, vp, vp]
     lib.kLPM_gather_slots.argtypes = [vp, vp, i64, vp, vp]
     lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
-                                       vp, vp, vp, vp, sz, vp, vp]
+                                       vp, vp, vp, vp]
     lib.kLPM_queue_advance_timed.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32,
-                                             C.POINTER(Arrivals), vp, vp, vp, vp, sz, vp, vp]
+                                             C.POINTER(Arrivals), vp, vp, vp, vp]
     lib.kLPM_queue_gather.argtypes = [C.POINTER(Queue), C.POINTER(Queries), vp]
-    lib.kLPM_queue_scratch_bytes.argtypes = [i32, C.POINTER(sz)]
     lib.kLPM_read_stats.argtypes = [vp, C.POINTER(Stats), vp]
     lib.kLPM_snapshot_bytes.argtypes = [vp, C.POINTER(sz), vp]
     lib.kLPM_snapshot.argtypes = [vp, vp, sz, C.POINTER(sz), vp]
@@ -311,43 +309,38 @@ class DeviceQueue:
     off: torch.Tensor  # int64 [cap]
     len: torch.Tensor  # int32 [cap]
     n: torch.Tensor  # int32 [1]
+    clock: torch.Tensor  # int64 [1] (bits of uint64): simulated time of this queue state
+    n_joined: torch.Tensor  # int32 [1]: timed runs, arrivals that have joined so far
     cap: int
 
     @staticmethod
-    def empty(cap: int, device) -> "DeviceQueue":
+    def empty(cap: int, device, clock: int = 0) -> "DeviceQueue":
         c = max(int(cap), 1)
         return DeviceQueue(torch.zeros(c, dtype=torch.int32, device=device), torch.zeros(c, dtype=torch.int64, device=device),
                            torch.zeros(c, dtype=torch.int64, device=device), torch.zeros(c, dtype=torch.int32, device=device),
+                           torch.zeros(1, dtype=torch.int32, device=device),
+                           torch.full((1,), int(clock), dtype=torch.int64, device=device),
                            torch.zeros(1, dtype=torch.int32, device=device), int(cap))
 
     def c_struct(self) -> Queue:
         return Queue(self.id.data_ptr(), self.arrival.data_ptr(), self.off.data_ptr(), self.len.data_ptr(),
-                     self.n.data_ptr(), self.cap)
-
-
-def kLPM_queue_scratch_bytes(batch_cap: int) -> int:
-    out = C.c_size_t(0)
-    _check(_lib.kLPM_queue_scratch_bytes(int(batch_cap), C.byref(out)), "kLPM_queue_scratch_bytes")
-    return int(out.value)
+                     self.n.data_ptr(), self.clock.data_ptr(), self.n_joined.data_ptr(), self.cap)
 
 
 def kLPM_queue_advance(cur: DeviceQueue, nxt: DeviceQueue, all_q: DeviceQueries, match_len, batch_idx, n_selected,
-                       batch_cap: int, new_id, n_new: int, sim_clock, ttft, matched_accum,
-                       scratch: Tuple[torch.Tensor, int], scratch_bytes: int, dev_error, stream=None) -> None:
+                       batch_cap: int, new_id, n_new: int, ttft, matched_accum, dev_error, stream=None) -> None:
     c, n, a = cur.c_struct(), nxt.c_struct(), all_q.c_struct()
     _check(_lib.kLPM_queue_advance(C.byref(c), C.byref(n), C.byref(a), _ptr(match_len), _ptr(batch_idx),
-                                   _ptr(n_selected), int(batch_cap), _ptr(new_id), int(n_new), _ptr(sim_clock),
-                                   _ptr(ttft), _ptr(matched_accum), C.c_void_p(scratch[1]), int(scratch_bytes),
-                                   _ptr(dev_error), _stream(stream)), "kLPM_queue_advance")
+                                   _ptr(n_selected), int(batch_cap), _ptr(new_id), int(n_new), _ptr(ttft),
+                                   _ptr(matched_accum), _ptr(dev_error), _stream(stream)), "kLPM_queue_advance")
 
 
 @dataclass
 class DeviceArrivals:
-    """Arrivals in time order, resident on the device, with the cursor of those already enqueued."""
+    """Arrivals in time order, resident on the device."""
 
     id: torch.Tensor  # int32 [n], ordered by (time, id)
     time: torch.Tensor  # int64 [n] (bits of uint64), non-decreasing
-    cursor: torch.Tensor  # int32 [1]
     n: int
     c_num: int = 0
     c_den: int = 1
@@ -363,19 +356,17 @@ class DeviceArrivals:
         tim = torch.zeros(pad, dtype=torch.int64, device=device)
         ids[:n] = torch.from_numpy(order).to(device)
         tim[:n] = torch.from_numpy(np.ascontiguousarray(t)).to(device)
-        return DeviceArrivals(ids, tim, torch.zeros(1, dtype=torch.int32, device=device), n, int(c_num), int(c_den))
+        return DeviceArrivals(ids, tim, n, int(c_num), int(c_den))
 
     def c_struct(self) -> Arrivals:
-        return Arrivals(self.id.data_ptr(), self.time.data_ptr(), self.cursor.data_ptr(), self.n, self.c_num, self.c_den)
+        return Arrivals(self.id.data_ptr(), self.time.data_ptr(), self.n, self.c_num, self.c_den)
 
 
 def kLPM_queue_advance_timed(cur: DeviceQueue, nxt: DeviceQueue, all_q: DeviceQueries, match_len, batch_idx, n_selected,
-                             batch_cap: int, pending: DeviceArrivals, sim_clock, ttft, matched_accum,
-                             scratch: Tuple[torch.Tensor, int], scratch_bytes: int, dev_error, stream=None) -> None:
+                             batch_cap: int, pending: DeviceArrivals, ttft, matched_accum, dev_error, stream=None) -> None:
     c, n, a, p = cur.c_struct(), nxt.c_struct(), all_q.c_struct(), pending.c_struct()
     _check(_lib.kLPM_queue_advance_timed(C.byref(c), C.byref(n), C.byref(a), _ptr(match_len), _ptr(batch_idx),
-                                         _ptr(n_selected), int(batch_cap), C.byref(p), _ptr(sim_clock), _ptr(ttft),
-                                         _ptr(matched_accum), C.c_void_p(scratch[1]), int(scratch_bytes),
+                                         _ptr(n_selected), int(batch_cap), C.byref(p), _ptr(ttft), _ptr(matched_accum),
                                          _ptr(dev_error), _stream(stream)), "kLPM_queue_advance_timed")
 
 

@@ -89,25 +89,13 @@ __global__ __launch_bounds__(256) void k_iota(int32_t *__restrict__ idx, int32_t
 }
 
 // ---- waiting-queue bookkeeping of an online run ----
-// Retire: one workgroup sums the batch's uncached tokens, advances the simulated clock, stamps the
-// TTFT of the admitted queries and sorts their queue positions.  Compact: every surviving entry
-// moves down by the number of retired positions before it (binary search in the sorted list), the
-// arrivals are appended, and the CSR view of the new queue is written on the way.
-constexpr int kQueueThreads = 1024;
-
-struct QueueHdr {  // at the start of the scratch buffer
-    int32_t nw, n_removed, kept, add;
-    uint64_t now;
-    int32_t new_base, pad;  // first entry of the arrival list that joins in this step
-};
-
-struct ArrivalsView {  // arrivals in time order; `time`/`cursor` are null for the per-step lists of kLPM_queue_advance
-    const int32_t *id;
-    const uint64_t *time;
-    int32_t *cursor;
-    int32_t n;
-    uint32_t c_num, c_den;
-};
+// One launch: every workgroup owns a stretch of queue positions.  It reads the whole batch (a few KB)
+// to learn which of its own positions retire, how many retire before its stretch, and what the batch
+// costs; with that each surviving entry knows where it moves (down by the retired positions before
+// it), retired entries get their TTFT, and the arrivals are appended behind the survivors together
+// with the CSR view of the new queue.  Everything is read from the current buffer set (entries,
+// count, clock, arrival cursor) and written to the other one, so workgroups never wait for each other.
+constexpr int kQaThreads = 512;
 
 struct QueueView {
     int32_t *id;
@@ -115,162 +103,128 @@ struct QueueView {
     int64_t *off;
     int32_t *len;
     int32_t *n;
+    uint64_t *clock;
+    int32_t *n_joined;
     int32_t cap;
 };
 
-// Retire: one workgroup marks the admitted queue positions in a bitmap, sums the batch's uncached
-// tokens, advances the simulated clock, stamps the TTFT of the admitted queries and leaves, for every
-// 32-position word of the queue, the number of retired positions before it.
+struct ArrivalsView {  // arrivals in time order; `time` is null for the per-step lists of kLPM_queue_advance
+    const int32_t *id;
+    const uint64_t *time;
+    int32_t n;
+    uint32_t c_num, c_den;
+};
+
 // TIMED: Def. 2's timeline (cost with the attention term, arrivals join when their time has come,
 // an idle scheduler waits for the next arrival); otherwise the n_new arrivals of this step join at
 // the new time and the clock moves by at least 1.
 template <bool TIMED>
-__global__ __launch_bounds__(kQueueThreads) void k_queue_retire(QueueView cur, QueueView next, QView all,
-                                                                const int32_t *__restrict__ match_len,
-                                                                const int32_t *__restrict__ batch_idx,
-                                                                const int32_t *__restrict__ n_selected,
-                                                                int32_t batch_cap, ArrivalsView pend,
-                                                                uint64_t *__restrict__ sim_clock,
-                                                                int64_t *__restrict__ ttft, QueueHdr *hdr,
-                                                                uint32_t *__restrict__ bitmap,
-                                                                uint32_t *__restrict__ before,
-                                                                uint32_t *__restrict__ dev_error) {
-    __shared__ unsigned long long s_cost;
-    __shared__ uint64_t s_clock;
-    __shared__ int32_t sbuf[kQueueThreads / kWave];
+__global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, QueueView next, QView all,
+                                                              const int32_t *__restrict__ match_len,
+                                                              const int32_t *__restrict__ batch_idx,
+                                                              const int32_t *__restrict__ n_selected,
+                                                              int32_t batch_cap, ArrivalsView pend,
+                                                              int64_t *__restrict__ ttft,
+                                                              int64_t *__restrict__ matched_accum,
+                                                              uint32_t *__restrict__ dev_error) {
+    __shared__ uint32_t bm[kQaThreads / 32];  // retired positions of this workgroup's stretch
+    __shared__ unsigned long long s_cost, s_sum;
+    __shared__ int32_t s_below, s_valid;
     const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kQaThreads;
     int32_t nw = *cur.n;
     nw = nw < 0 ? 0 : (nw > cur.cap ? cur.cap : nw);
     int32_t nb = *n_selected;
     nb = nb < 0 ? 0 : (nb > batch_cap ? batch_cap : nb);
-    const int32_t n_words = (nw + 31) / 32;
-    if (tid == 0) s_cost = 0;
-    for (int32_t w = tid; w < n_words; w += kQueueThreads) bitmap[w] = 0u;
+    const uint64_t clock = *cur.clock;
+    if (tid < kQaThreads / 32) bm[tid] = 0u;
+    if (tid == 0) { s_cost = 0; s_sum = 0; s_below = 0; s_valid = 0; }
     __syncthreads();
-    unsigned long long my_cost = 0;
-    for (int32_t j = tid; j < nb; j += kQueueThreads) {
-        int32_t w = batch_idx[j];
-        if (w >= 0 && w < nw) {
-            uint32_t bit = 1u << (w & 31);
-            uint32_t old = atomicOr(&bitmap[w >> 5], bit);
-            if (!(old & bit)) {  // a position listed twice counts once
-                int32_t id = cur.id[w];
-                int32_t len = (id >= 0 && id < all.n) ? all.len[id] : 0;
-                int32_t m = match_len[w];
-                m = m < 0 ? 0 : m;
-                // (1 + c_attn |x|)(|x| - overlap) token times, in units of 1/c_den (Def. 2)
-                if (len > m)
-                    my_cost += (unsigned long long)(len - m) *
-                               (TIMED ? (unsigned long long)pend.c_den + (unsigned long long)pend.c_num * (unsigned long long)len
-                                      : 1ull);
-            }
+    {
+        unsigned long long my_cost = 0;
+        int32_t below = 0, valid = 0;
+        for (int32_t j = tid; j < nb; j += kQaThreads) {
+            const int32_t w = batch_idx[j];
+            if (w < 0 || w >= nw) continue;
+            ++valid;
+            if (w < base) ++below;
+            else if (w < base + kQaThreads) atomicOr(&bm[(w - base) >> 5], 1u << ((w - base) & 31));
+            const int32_t len = cur.len[w];  // (the queue carries the CSR view of its prompts)
+            int32_t m = match_len[w];
+            m = m < 0 ? 0 : m;
+            // (1 + c_attn |x|)(|x| - overlap) token times, in units of 1/c_den (Def. 2); c_attn = 0 otherwise
+            if (len > m)
+                my_cost += (unsigned long long)(len - m) *
+                           (TIMED ? (unsigned long long)pend.c_den + (unsigned long long)pend.c_num * (unsigned long long)len
+                                  : 1ull);
         }
+        if (my_cost) atomicAdd(&s_cost, my_cost);
+        if (below) atomicAdd(&s_below, below);
+        if (valid) atomicAdd(&s_valid, valid);
     }
-    if (my_cost) atomicAdd(&s_cost, my_cost);
     __syncthreads();
-    if (tid == 0) s_clock = *sim_clock + ((TIMED || s_cost > 0) ? (uint64_t)s_cost : 1ull);
-    // retired positions before each word: contiguous runs of words per thread, one scan
-    const int32_t per = (n_words + kQueueThreads - 1) / kQueueThreads;
-    const int32_t lo = tid * per < n_words ? tid * per : n_words;
-    const int32_t hi = lo + per < n_words ? lo + per : n_words;
-    int32_t cnt = 0;
-    for (int32_t w = lo; w < hi; ++w) cnt += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    int32_t nv;
-    int32_t run = block_inclusive_scan<int32_t, kQueueThreads>(cnt, sbuf, tid, nv) - cnt;
-    for (int32_t w = lo; w < hi; ++w) {
-        before[w] = (uint32_t)run;
-        run += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    }
-    const uint64_t now = s_clock;
-    // the whole batch finishes together (Sec. 2.1): TTFT = finish time - arrival
-    for (int32_t j = tid; j < nb; j += kQueueThreads) {
-        int32_t w = batch_idx[j];
-        if (w >= 0 && w < nw) {
-            int32_t id = cur.id[w];
-            if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[w]);
-        }
-    }
-    const int32_t kept = nw - nv;
+    // the whole batch finishes together (Sec. 2.1)
+    const uint64_t now = clock + ((TIMED || s_cost > 0) ? (uint64_t)s_cost : 1ull);
+    const int32_t kept_all = nw - s_valid;
+    const int32_t kept = kept_all < next.cap ? kept_all : next.cap;
     int32_t room = next.cap - kept;
     room = room < 0 ? 0 : room;
     uint64_t now_out = now;
-    int32_t base = 0, add = pend.n;
+    int32_t first = 0, add = pend.n;
     if (TIMED) {
         // pending arrivals whose time has come: times are sorted, so their number is a prefix length
-        base = *pend.cursor;
-        base = base < 0 ? 0 : (base > pend.n ? pend.n : base);
+        first = *cur.n_joined;
+        first = first < 0 ? 0 : (first > pend.n ? pend.n : first);
         add = 0;
         for (int pass = 0; pass < 2; ++pass) {
-            for (int32_t b = base; b < pend.n; b += kQueueThreads) {
-                int32_t i = b + tid;
-                int c = __syncthreads_count(i < pend.n && pend.time[i] <= now_out);
+            for (int32_t b = first; b < pend.n; b += kQaThreads) {
+                const int32_t i = b + tid;
+                const int c = __syncthreads_count(i < pend.n && pend.time[i] <= now_out);
                 add += c;
-                if (c < kQueueThreads) break;
+                if (c < kQaThreads) break;
             }
-            if (pass == 1 || kept > 0 || add > 0 || base >= pend.n) break;
-            now_out = pend.time[base];  // nobody waiting: idle until the next arrival (Def. 2: max(R, t))
+            if (pass == 1 || kept_all > 0 || add > 0 || first >= pend.n) break;
+            now_out = pend.time[first];  // nobody waiting: idle until the next arrival (Def. 2: max(R, t))
         }
     }
-    if (tid == 0) {
-        if (TIMED) {
-            add = add < room ? add : room;  // the rest stay pending, in order
-            *pend.cursor = base + add;
-        } else {
-            if ((add > room || kept > next.cap) && dev_error) atomicOr(dev_error, 8u);
-            add = add < room ? add : room;
-        }
-        hdr->nw = nw;
-        hdr->n_removed = nv;
-        hdr->kept = kept < next.cap ? kept : next.cap;
-        hdr->add = add;
-        hdr->now = now_out;
-        hdr->new_base = base;
-        *next.n = hdr->kept + add;
-        *sim_clock = now_out;
-    }
-}
-
-// Compact: every surviving entry moves down by the number of retired positions before it, the
-// arrivals are appended, and the CSR view of the new queue is written on the way.
-__global__ __launch_bounds__(256) void k_queue_compact(QueueView cur, QueueView next, QView all,
-                                                       const int32_t *__restrict__ match_len,
-                                                       const int32_t *__restrict__ new_id,
-                                                       const uint64_t *__restrict__ new_time, const QueueHdr *hdr,
-                                                       const uint32_t *__restrict__ bitmap,
-                                                       const uint32_t *__restrict__ before,
-                                                       int64_t *__restrict__ matched_accum) {
-    __shared__ unsigned long long s_sum;
-    const int tid = threadIdx.x;
-    if (tid == 0) s_sum = 0;
-    __syncthreads();
-    const int32_t nw = hdr->nw, kept = hdr->kept, add = hdr->add;
-    const uint64_t now = hdr->now;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + tid;
+    const bool overflow = !TIMED && (add > room || kept_all > next.cap);
+    add = add < room ? add : room;  // (timed: the rest stay pending, in order)
+    const int64_t i = base + tid;
     unsigned long long my = 0;
     if (i < nw) {
-        int32_t m = match_len[i];
+        const int32_t m = match_len[i];
         if (m > 0) my = (unsigned long long)m;
-        uint32_t word = bitmap[i >> 5];
-        uint32_t bit = 1u << (i & 31);
-        int64_t dst = i - (int64_t)(before[i >> 5] + (uint32_t)__popc(word & (bit - 1u)));
-        if (!(word & bit) && dst < kept) {
-            int32_t id = cur.id[i];
-            next.id[dst] = id;
-            next.arrival[dst] = cur.arrival[i];
-            bool ok = id >= 0 && id < all.n;
-            next.off[dst] = ok ? all.off[id] : -1;
-            next.len[dst] = ok ? all.len[id] : 0;
+        const uint32_t word = bm[tid >> 5], bit = 1u << (tid & 31);
+        int32_t before = s_below + (int32_t)__popc(word & (bit - 1u));
+        for (int wd = 0; wd < (tid >> 5); ++wd) before += (int32_t)__popc(bm[wd]);
+        const int32_t id = cur.id[i];
+        if (word & bit) {
+            if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[i]);  // TTFT = finish time - arrival
+        } else {
+            const int64_t dst = i - before;
+            if (dst >= 0 && dst < kept) {
+                next.id[dst] = id;
+                next.arrival[dst] = cur.arrival[i];
+                next.off[dst] = cur.off[i];
+                next.len[dst] = cur.len[i];
+            }
         }
     } else if (i < (int64_t)nw + add) {
-        int32_t r = (int32_t)(i - nw);
-        int32_t id = new_id[hdr->new_base + r];
-        int64_t dst = (int64_t)kept + r;
+        const int32_t r = (int32_t)(i - nw);
+        const int32_t id = pend.id[first + r];
+        const int64_t dst = (int64_t)kept + r;
         next.id[dst] = id;
         // a timed arrival keeps its own time; otherwise it is enqueued when the previous batch finished
-        next.arrival[dst] = new_time ? new_time[hdr->new_base + r] : now;
-        bool ok = id >= 0 && id < all.n;
+        next.arrival[dst] = TIMED ? pend.time[first + r] : now;
+        const bool ok = id >= 0 && id < all.n;
         next.off[dst] = ok ? all.off[id] : -1;
         next.len[dst] = ok ? all.len[id] : 0;
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        if (overflow && dev_error) atomicOr(dev_error, 8u);
+        *next.n = kept + add;
+        *next.clock = now_out;
+        if (next.n_joined) *next.n_joined = first + add;
     }
     if (matched_accum) {
         if (my) atomicAdd(&s_sum, my);
@@ -420,76 +374,60 @@ extern "C" int kLPM_set_budget(kLPM_tree *tree, int64_t budget_tokens) {
 }
 
 static bool queue_ok(const kLPM_queue *q) {
-    return q && q->cap >= 0 && q->n && (q->cap == 0 || (q->id && q->arrival && q->off && q->len));
+    return q && q->cap >= 0 && q->n && q->clock && (q->cap == 0 || (q->id && q->arrival && q->off && q->len));
 }
 
 static QueueView make_queue_view(const kLPM_queue *q) {
     QueueView v;
-    v.id = q->id; v.arrival = q->arrival; v.off = q->off; v.len = q->len; v.n = q->n; v.cap = q->cap;
+    v.id = q->id; v.arrival = q->arrival; v.off = q->off; v.len = q->len; v.n = q->n; v.clock = q->clock;
+    v.n_joined = q->n_joined; v.cap = q->cap;
     return v;
-}
-
-extern "C" int kLPM_queue_scratch_bytes(int32_t queue_cap, size_t *out_bytes) {
-    if (queue_cap < 0 || !out_bytes) return KLPM_EINVAL;
-    size_t words = ((size_t)queue_cap + 31) / 32 + 1;
-    *out_bytes = 256 + 2 * align_up(words * 4, 256);
-    return KLPM_OK;
 }
 
 static int queue_advance_impl(bool timed, const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
                               const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
-                              int32_t batch_cap, const ArrivalsView &pend, uint64_t *sim_clock, int64_t *ttft,
-                              int64_t *matched_accum, void *scratch, size_t scratch_bytes, uint32_t *dev_error,
-                              hipStream_t stream) {
-    if (!queue_ok(cur) || !queue_ok(next) || !queries_ok(all) || batch_cap < 0 || pend.n < 0 || !sim_clock || !ttft ||
-        !scratch || !n_selected)
+                              int32_t batch_cap, const ArrivalsView &pend, int64_t *ttft, int64_t *matched_accum,
+                              uint32_t *dev_error, hipStream_t stream) {
+    if (!queue_ok(cur) || !queue_ok(next) || !queries_ok(all) || batch_cap < 0 || pend.n < 0 || !ttft || !n_selected)
         return KLPM_EINVAL;
-    if (cur->id == next->id || cur->arrival == next->arrival || cur->n == next->n) return KLPM_EINVAL;
+    if (cur->id == next->id || cur->arrival == next->arrival || cur->n == next->n || cur->clock == next->clock)
+        return KLPM_EINVAL;
+    if (timed && (!cur->n_joined || !next->n_joined || cur->n_joined == next->n_joined)) return KLPM_EINVAL;
     if ((batch_cap > 0 && (!batch_idx || !match_len)) || (pend.n > 0 && !pend.id)) return KLPM_EINVAL;
-    size_t need = 0;
-    kLPM_queue_scratch_bytes(cur->cap, &need);
-    if (scratch_bytes < need || ((uintptr_t)scratch & 255u)) return KLPM_EARENA;
-    QueueHdr *hdr = (QueueHdr *)scratch;
-    size_t words = ((size_t)cur->cap + 31) / 32 + 1;
-    uint32_t *bitmap = (uint32_t *)((char *)scratch + 256);
-    uint32_t *before = (uint32_t *)((char *)scratch + 256 + align_up(words * 4, 256));
     QueueView c = make_queue_view(cur), n = make_queue_view(next);
     QView a = make_qview(all);
-    if (timed)
-        hipLaunchKernelGGL(k_queue_retire<true>, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
-                           n_selected, batch_cap, pend, sim_clock, ttft, hdr, bitmap, before, dev_error);
-    else
-        hipLaunchKernelGGL(k_queue_retire<false>, dim3(1), dim3(kQueueThreads), 0, stream, c, n, a, match_len, batch_idx,
-                           n_selected, batch_cap, pend, sim_clock, ttft, hdr, bitmap, before, dev_error);
     // survivors come from at most cur->cap positions; how many arrivals join is decided on the device
     // in the timed case (at most next->cap of them)
-    int64_t work = (int64_t)cur->cap + (timed ? (int64_t)(pend.n < next->cap ? pend.n : next->cap) : (int64_t)pend.n);
-    if (work > 0)
-        hipLaunchKernelGGL(k_queue_compact, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, c, n, a,
-                           match_len, pend.id, pend.time, hdr, bitmap, before, matched_accum);
+    const int64_t work = (int64_t)cur->cap + (timed ? (int64_t)(pend.n < next->cap ? pend.n : next->cap) : (int64_t)pend.n);
+    const unsigned blocks = (unsigned)((work + kQaThreads - 1) / kQaThreads);
+    if (timed)
+        hipLaunchKernelGGL(k_queue_advance<true>, dim3(blocks ? blocks : 1), dim3(kQaThreads), 0, stream, c, n, a, match_len,
+                           batch_idx, n_selected, batch_cap, pend, ttft, matched_accum, dev_error);
+    else
+        hipLaunchKernelGGL(k_queue_advance<false>, dim3(blocks ? blocks : 1), dim3(kQaThreads), 0, stream, c, n, a, match_len,
+                           batch_idx, n_selected, batch_cap, pend, ttft, matched_accum, dev_error);
     return check_launch();
 }
 
 extern "C" int kLPM_queue_advance(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
                                   const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
-                                  int32_t batch_cap, const int32_t *new_id, int32_t n_new, uint64_t *sim_clock,
-                                  int64_t *ttft, int64_t *matched_accum, void *scratch, size_t scratch_bytes,
-                                  uint32_t *dev_error, kLPM_stream stream_) {
-    ArrivalsView pend{new_id, nullptr, nullptr, n_new, 0u, 1u};
-    return queue_advance_impl(false, cur, next, all, match_len, batch_idx, n_selected, batch_cap, pend, sim_clock, ttft,
-                              matched_accum, scratch, scratch_bytes, dev_error, (hipStream_t)stream_);
+                                  int32_t batch_cap, const int32_t *new_id, int32_t n_new, int64_t *ttft,
+                                  int64_t *matched_accum, uint32_t *dev_error, kLPM_stream stream_) {
+    ArrivalsView pend{new_id, nullptr, n_new, 0u, 1u};
+    return queue_advance_impl(false, cur, next, all, match_len, batch_idx, n_selected, batch_cap, pend, ttft, matched_accum,
+                              dev_error, (hipStream_t)stream_);
 }
 
 extern "C" int kLPM_queue_advance_timed(const kLPM_queue *cur, const kLPM_queue *next, const kLPM_queries *all,
                                         const int32_t *match_len, const int32_t *batch_idx,
                                         const int32_t *n_selected, int32_t batch_cap, const kLPM_arrivals *pending,
-                                        uint64_t *sim_clock, int64_t *ttft, int64_t *matched_accum, void *scratch,
-                                        size_t scratch_bytes, uint32_t *dev_error, kLPM_stream stream_) {
-    if (!pending || pending->n < 0 || !pending->cursor || pending->c_den < 1u) return KLPM_EINVAL;
+                                        int64_t *ttft, int64_t *matched_accum, uint32_t *dev_error,
+                                        kLPM_stream stream_) {
+    if (!pending || pending->n < 0 || pending->c_den < 1u) return KLPM_EINVAL;
     if (pending->n > 0 && (!pending->id || !pending->time)) return KLPM_EINVAL;
-    ArrivalsView pend{pending->id, pending->time, pending->cursor, pending->n, pending->c_num, pending->c_den};
-    return queue_advance_impl(true, cur, next, all, match_len, batch_idx, n_selected, batch_cap, pend, sim_clock, ttft,
-                              matched_accum, scratch, scratch_bytes, dev_error, (hipStream_t)stream_);
+    ArrivalsView pend{pending->id, pending->time, pending->n, pending->c_num, pending->c_den};
+    return queue_advance_impl(true, cur, next, all, match_len, batch_idx, n_selected, batch_cap, pend, ttft, matched_accum,
+                              dev_error, (hipStream_t)stream_);
 }
 
 extern "C" int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream stream_) {

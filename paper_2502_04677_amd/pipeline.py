@@ -102,12 +102,9 @@ class OnlineRun:
         self.cap = int(cap)
         self.queues = [B.DeviceQueue.empty(cap, dev), B.DeviceQueue.empty(cap, dev)]
         self.cur = 0
-        self.sim_clock = torch.zeros(1, dtype=torch.int64, device=dev)
         self.ttft = torch.full((max(all_q.n, 1),), -1, dtype=torch.int64, device=dev)
         self.matched = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dev_error = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.scratch_bytes = B.kLPM_queue_scratch_bytes(self.cap)
-        self.scratch = B.alloc_aligned(self.scratch_bytes, dev)
         n0 = int(first_ids.shape[0])
         assert n0 <= self.cap
         q0 = self.queues[0]
@@ -122,6 +119,11 @@ class OnlineRun:
     def queue(self) -> B.DeviceQueue:
         return self.queues[self.cur]
 
+    @property
+    def sim_clock(self) -> torch.Tensor:
+        """Simulated time of the current queue state (one-element int64 device tensor)."""
+        return self.queue.clock
+
     def view(self) -> B.DeviceQueries:
         """The current queue as a query set sharing the stream's token pool."""
         q = self.queue
@@ -133,9 +135,8 @@ class OnlineRun:
         s = self.s
         n_new = 0 if new_ids is None else int(new_ids.shape[0])
         B.kLPM_queue_advance(self.queues[self.cur], self.queues[1 - self.cur], self.all_q, s.match_len, s.batch_idx,
-                             s.n_selected, batch, new_ids, n_new, self.sim_clock, self.ttft,
-                             self.matched if matched is None else matched,
-                             self.scratch, self.scratch_bytes, self.dev_error)
+                             s.n_selected, batch, new_ids, n_new, self.ttft,
+                             self.matched if matched is None else matched, self.dev_error)
         self.cur = 1 - self.cur
         self.n_host = min(self.cap, self.n_host - min(batch, self.n_host) + n_new)
 
@@ -164,21 +165,22 @@ class TimedRun:
         self.s = sched
         self.all_q = all_q
         self.cap = int(cap)
-        self.queues = [B.DeviceQueue.empty(cap, dev), B.DeviceQueue.empty(cap, dev)]
+        self.queues = [B.DeviceQueue.empty(cap, dev, clock=t_start), B.DeviceQueue.empty(cap, dev, clock=t_start)]
         self.cur = 0
         self.pending = B.DeviceArrivals.from_host(arrival, c_num, c_den, dev)
-        self.sim_clock = torch.full((1,), int(t_start), dtype=torch.int64, device=dev)
         self.ttft = torch.full((max(all_q.n, 1),), -1, dtype=torch.int64, device=dev)
         self.matched = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dev_error = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.scratch_bytes = B.kLPM_queue_scratch_bytes(self.cap)
-        self.scratch = B.alloc_aligned(self.scratch_bytes, dev)
         sched.n_selected.zero_()
         self._advance(0)  # initial fill: everything that has arrived by t_start, or the first arrival
 
     @property
     def queue(self) -> B.DeviceQueue:
         return self.queues[self.cur]
+
+    @property
+    def sim_clock(self) -> torch.Tensor:
+        return self.queue.clock
 
     def view(self) -> B.DeviceQueries:
         q = self.queue
@@ -187,8 +189,8 @@ class TimedRun:
     def _advance(self, batch: int) -> None:
         s = self.s
         B.kLPM_queue_advance_timed(self.queues[self.cur], self.queues[1 - self.cur], self.all_q, s.match_len,
-                                   s.batch_idx, s.n_selected, batch, self.pending, self.sim_clock, self.ttft,
-                                   self.matched, self.scratch, self.scratch_bytes, self.dev_error)
+                                   s.batch_idx, s.n_selected, batch, self.pending, self.ttft, self.matched,
+                                   self.dev_error)
         self.cur = 1 - self.cur
 
     def step(self, k: int, batch: int) -> None:

@@ -41,7 +41,7 @@ def test_struct_layouts_match_header(K):
     from paper_2502_04677_amd import binding
 
     assert C.sizeof(binding.Queries) == 56
-    assert C.sizeof(binding.Arrivals) == 40 and C.sizeof(binding.Queue) == 48
+    assert C.sizeof(binding.Arrivals) == 32 and C.sizeof(binding.Queue) == 64
     assert C.sizeof(binding.Config) == 32
     assert C.sizeof(binding.Stats) == 48 and binding.STATS_BYTES == 48
 
@@ -86,13 +86,18 @@ def test_null_and_negative_arguments_are_rejected_before_any_launch(K):
     assert lib.kLPM_commit(None, C.byref(q), None, None, 0, None, None) == -1
     assert lib.kLPM_set_budget(None, 5) == -1
     # timed queue advance: no arrival list, zero denominator of the attention coefficient
-    qu = binding.Queue(8, 8, 8, 8, 8, 0)
+    qa, qb = binding.Queue(8, 8, 8, 8, 8, 8, 8, 0), binding.Queue(16, 16, 16, 16, 16, 16, 16, 0)
     q0 = binding.Queries(0, 0, 0, 0, 0, 0, 0)
-    args = (C.byref(qu), C.byref(qu), C.byref(q0), None, None, C.c_void_p(8), 0)
-    tail = (C.c_void_p(8), C.c_void_p(8), None, C.c_void_p(256), 1 << 20, None, None)
+    args = (C.byref(qa), C.byref(qb), C.byref(q0), None, None, C.c_void_p(8), 0)
+    tail = (C.c_void_p(8), None, None, None)
     assert lib.kLPM_queue_advance_timed(*args, None, *tail) == -1
-    bad = binding.Arrivals(0, 0, 8, 0, 1, 0)
+    bad = binding.Arrivals(0, 0, 0, 1, 0)
     assert lib.kLPM_queue_advance_timed(*args, C.byref(bad), *tail) == -1
+    ok = binding.Arrivals(0, 0, 0, 0, 1)
+    # the two buffer sets must be distinct, and a timed run needs the joined counters
+    assert lib.kLPM_queue_advance_timed(C.byref(qa), C.byref(qa), C.byref(q0), None, None, C.c_void_p(8), 0, C.byref(ok), *tail) == -1
+    no_join = binding.Queue(16, 16, 16, 16, 16, 16, 0, 0)
+    assert lib.kLPM_queue_advance_timed(C.byref(qa), C.byref(no_join), C.byref(q0), None, None, C.c_void_p(8), 0, C.byref(ok), *tail) == -1
     assert lib.kLPM_read_stats(None, None, None) == -1
     assert lib.kLPM_snapshot(None, None, 0, None, None) == -1
     assert lib.kLPM_destroy(None) == 0

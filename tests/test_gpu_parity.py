@@ -510,7 +510,7 @@ def _run_timed(p, k, batch, budget, c_num=0, c_den=1, t_start=0, cap=None, check
             assert ids[s.batch()].tolist() == r.batches[step].tolist(), step
     run.step(k, batch)  # one step past the end: nobody is waiting, nothing is pending, nothing changes
     torch.cuda.synchronize()
-    assert int(run.queue.n.item()) == 0 and int(run.pending.cursor.item()) == p.n
+    assert int(run.queue.n.item()) == 0 and int(run.queue.n_joined.item()) == p.n
     assert int(run.sim_clock.item()) == r.clock
     assert run.ttft[:p.n].cpu().numpy().tolist() == r.ttft.tolist()
     assert int(run.dev_error.item()) == 0 and s.read_stats().device_error == 0
