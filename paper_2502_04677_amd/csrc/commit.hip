@@ -63,7 +63,6 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
         if (err) st->device_error |= err;
         st->skip = err ? 1 : 0;
         st->nb = nb;
-        st->alloc_cnt = 0;
         st->need_compact = 0;
         st->need_rebuild = 0;
         st->do_evict = 0;

@@ -42,7 +42,7 @@ struct DevState {
     // ---- scalars of the commit in flight ----
     int32_t nb;            // admitted prompts in this commit
     int32_t skip;          // 1 = this commit is abandoned (error), later kernels do nothing
-    int32_t alloc_cnt;     // unused
+    int32_t pad2;
     int32_t free_cnt0;     // free_cnt / n_slots / pool_top / clock at the start of the structure pass
     int32_t n_slots0;
     int32_t need_compact;

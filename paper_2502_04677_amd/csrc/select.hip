@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kSortThreads) void k_rs_hist(const uint64_t *__rest
 __global__ __launch_bounds__(kScanThreads) void k_rs_scan(uint32_t *__restrict__ hist, int32_t nblk, LiveN nn,
                                                           int32_t *__restrict__ skip) {
     const int32_t n = nn.get();
-    __shared__ uint32_t part[kScanThreads];
+    __shared__ uint32_t part[kScanThreads / kWave];
     const int tid = threadIdx.x;
     const int64_t total = 256ll * nblk;
     const int64_t chunk = (total + kScanThreads - 1) / kScanThreads;
@@ -104,17 +104,10 @@ __global__ __launch_bounds__(kScanThreads) void k_rs_scan(uint32_t *__restrict__
     const int64_t hi = (lo + chunk < total) ? lo + chunk : total;
     uint32_t s = 0;
     for (int64_t i = lo; i < hi; ++i) s += hist[i];
-    part[tid] = s;
     if (tid == 0) *skip = 0;
-    __syncthreads();
-    // Hillis-Steele inclusive scan over the 1024 partial sums
-    for (int d = 1; d < kScanThreads; d <<= 1) {
-        uint32_t v = (tid >= d) ? part[tid - d] : 0u;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    uint32_t run = part[tid] - s;  // exclusive prefix of this thread's chunk
+    uint32_t all;
+    const uint32_t incl = block_inclusive_scan<uint32_t, kScanThreads>(s, part, tid, all);
+    uint32_t run = incl - s;  // exclusive prefix of this thread's chunk
     for (int64_t i = lo; i < hi; ++i) {
         uint32_t c = hist[i];
         hist[i] = run;
@@ -367,21 +360,6 @@ struct FifoAcc {
     __device__ __forceinline__ uint32_t l_in_a(int32_t r) const { return l_elem_[r]; }
 };
 
-// block-wide inclusive scan of one int per thread (kFifoThreads threads)
-__device__ __forceinline__ int32_t block_scan_incl(int32_t v, int32_t *buf, int tid) {
-    buf[tid] = v;
-    __syncthreads();
-    for (int d = 1; d < kFifoThreads; d <<= 1) {
-        int32_t t = (tid >= d) ? buf[tid - d] : 0;
-        __syncthreads();
-        buf[tid] += t;
-        __syncthreads();
-    }
-    int32_t r = buf[tid];
-    __syncthreads();
-    return r;
-}
-
 __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__restrict__ arrival,
                                                                const int32_t *__restrict__ match_len, LiveN nn,
                                                                uint32_t k, int32_t batch,
@@ -475,7 +453,8 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         int b0 = nbins - 1 - 2 * tid, b1 = nbins - 2 - 2 * tid;
         int32_t c0 = (b0 >= 0) ? (int32_t)hist[b0] : 0;
         int32_t c1 = (b1 >= 0) ? (int32_t)hist[b1] : 0;
-        int32_t incl = block_scan_incl(c0 + c1, sbuf, tid);
+        int32_t all_bins;
+        int32_t incl = block_inclusive_scan<int32_t, kFifoThreads>(c0 + c1, sbuf, tid, all_bins);
         int32_t before = incl - c0 - c1;  // elements in bins above b0
         if (b0 >= 0 && before < need && before + c0 >= need) { s_bin = b0; s_above = before; }
         if (b1 >= 0 && before + c0 < need && before + c0 + c1 >= need) { s_bin = b1; s_above = before + c0; }

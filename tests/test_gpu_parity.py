@@ -910,3 +910,88 @@ def test_graph_replay_of_scheduling_steps():
         done += 1
     assert int(run.queue.n.item()) == 0 and int(run.sim_clock.item()) == r.clock
     assert run.ttft[:n].cpu().numpy().tolist() == r.ttft.tolist()
+
+
+# ----------------------------------------------------------------------------- sizes at the far end
+def _short_prompts(rng, n, vocab, lo, hi, arrival=None):
+    ln = rng.integers(lo, hi + 1, size=n).astype(np.int32)
+    off = np.zeros(n, np.int64)
+    off[1:] = np.cumsum(ln[:-1])
+    tok = rng.integers(0, vocab, size=int(ln.sum())).astype(np.int32)
+    arr = np.arange(n, dtype=np.uint64) if arrival is None else arrival
+    return W.Prompts(tok, off, ln, arr)
+
+
+def test_million_query_queue():
+    """A queue of a million short prompts (heavy prefix sharing over a small alphabet): match of all
+    of them, selection on the arrival-ordered paths and on the sorting path."""
+    rng = np.random.default_rng(61)
+    cache = _short_prompts(rng, 3000, 6, 3, 14)
+    n = 1_000_000
+    hq = _short_prompts(rng, n, 6, 2, 12)
+    w = W.Workload("million", cache, hq, 8, 1024, 1 << 40)
+    s, ref, q = _setup(w, max_batch=4096)
+    m = s.match(q).cpu().numpy()
+    m_ref = ref.match(hq.tokens, hq.off, hq.len, threads=8)
+    assert (m == m_ref).all()
+    for k, batch, fifo in ((8, 1024, True), (K_INF, 4096, True), (3, 300, False)):
+        _say(f"million queue: select k={k} B={batch} fifo={fifo}")
+        s.set_phase(2)
+        s.select(q, k, batch, fifo=fifo)
+        idx_ref, ph_ref = oracle.select(hq.arrival, m_ref, k, batch, 2)
+        assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref
+    # unsorted arrival times with many ties: only the sorting path applies
+    arr2 = rng.integers(0, 1000, size=n).astype(np.uint64)
+    d_arr2 = torch.from_numpy(arr2.view(np.int64)).cuda()
+    q2 = K.DeviceQueries(q.tokens, q.off, q.len, d_arr2, q.n)
+    s.set_phase(0)
+    s.select(q2, 5, 512)
+    idx_ref, ph_ref = oracle.select(arr2, m_ref, 5, 512, 0)
+    assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref
+
+
+def test_largest_batch_and_very_long_prompts():
+    """A commit of 65,536 prompts at once (the largest batch a configuration may name), and prompts
+    of several hundred thousand tokens (edges far longer than any window of the match kernel)."""
+    rng = np.random.default_rng(67)
+    # 65,536 tiny prompts over 3,000 first tokens: about 20 prompts per root child, deep sharing
+    hq = _short_prompts(rng, 65536, 3000, 1, 4)
+    empty = W.take_prompts(hq, np.zeros(0, np.int64))
+    w = W.Workload("max-batch", empty, hq, 4, 65536, 1 << 40)
+    s, ref, q = _setup(w, max_batch=65536)
+    m = s.match(q).cpu().numpy()
+    assert (m == 0).all()
+    s.set_phase(0)
+    s.select(q, 4, 65536)  # more than the arrival-ordered kernels take: the sorting path
+    idx_ref, ph_ref = oracle.select(hq.arrival, m, 4, 65536, 0)
+    assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref
+    s.commit(q, 65536)
+    st_ref = ref.commit(hq.tokens, hq.off, hq.len, idx_ref, 1 << 40)
+    st = s.read_stats()
+    assert st.device_error == 0 and (st.total_tokens, st.n_nodes, st.clock) == (st_ref.total_tokens, st_ref.n_nodes, st_ref.clock)
+    _same_tree(s, ref, big=True)
+    # then evict most of it in one go
+    K.kLPM_set_budget(s.tree, 5000)
+    s.n_selected.fill_(0)
+    s.commit(q, 0)
+    ref.commit(hq.tokens, hq.off, hq.len, np.zeros(0, np.int32), 5000)
+    assert s.read_stats().total_tokens <= 5000
+    _same_tree(s, ref, big=True)
+
+    # very long prompts: a 400,000-token prompt, a copy that differs in its last token, a copy cut in
+    # the middle of the edge, one diverging at token 300,001, and an unrelated one
+    base = rng.integers(0, 32000, size=400_000).astype(np.int32)
+    a = base.copy()
+    b = base.copy(); b[-1] ^= 1
+    c = base[:123_457].copy()
+    d = np.concatenate([base[:300_001], rng.integers(0, 32000, size=50_000).astype(np.int32)]); d[300_001] = (base[300_001] + 1) % 32000
+    e = rng.integers(0, 32000, size=200_000).astype(np.int32); e[0] = (base[0] + 1) % 32000
+    hq = W.generators._from_lists([a, b, c, d, e], [0, 1, 2, 3, 4])
+    empty = W.take_prompts(hq, np.zeros(0, np.int64))
+    w = W.Workload("long", empty, hq, 1, 5, 1 << 40)
+    s, ref, q = _setup(w, max_batch=5, max_len=400_000)
+    _check_step(s, ref, q, hq, 1, 5, 0, 1 << 40, big=True)   # all five in one batch, in arrival order
+    m = s.match(q).cpu().numpy()
+    assert m.tolist() == hq.len.tolist() == ref.match(hq.tokens, hq.off, hq.len).tolist()
+    # and a budget that keeps only the most recent path
+    _check_step(s, ref, q, hq, K_INF, 1, 0, 250_000, big=True)
