@@ -25,7 +25,6 @@ namespace klpm {
 constexpr uint64_t kNoGroup = ~0ull;
 constexpr int kEvictDigitBits = 11;  // eviction cut search: bits of the key resolved per pass
 constexpr int kEvictBins = 1 << kEvictDigitBits;
-constexpr int kEvictMaxPass = 6;     // 64-bit keys
 constexpr int kPlanThreads = 1024;
 
 __device__ __forceinline__ void flag_error(DevState *st, uint32_t bit) { atomicOr(&st->device_error, bit); }
@@ -523,18 +522,19 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 }
 
 // ------------------------------------------------------------------ ticks, then publish the inserts
-__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits) {
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass) {
     DevState *st = tv.st;
     const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
     if (!st->skip && j < st->nb) {
         const uint64_t t = st->clock0 + (uint64_t)j;
         int32_t v = ws.end_node[j];
         for (int32_t guard = 0; guard <= tv.max_prompt_len && v > kRoot && v < tv.max_nodes; ++guard) {
+            const int32_t up = tv.parent[v];  // requested together with the atomic: one round trip per level
             unsigned long long old = atomicMax((unsigned long long *)&tv.tick[v], (unsigned long long)t);
             // a strictly later prompt already stamped this node and stamps its ancestors too; an equal
             // value is this prompt's own stamp on a node it created, so keep climbing
             if (old > (unsigned long long)t) break;
-            v = tv.parent[v];
+            v = up;
         }
     }
     // the last workgroup publishes the inserts and decides whether anything must be evicted
@@ -613,7 +613,7 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
     }
     __syncthreads();
     if (evict)
-        for (int i = tid; i < kEvictMaxPass * kEvictBins; i += blockDim.x) ws.evict_hist[i] = 0;
+        for (int i = tid; i < n_pass * kEvictBins; i += blockDim.x) ws.evict_hist[i] = 0;
 }
 
 // ------------------------------------------------------------------ eviction
@@ -745,7 +745,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     while (tick_bits < 64 && (clock_bound >> tick_bits)) ++tick_bits;
     const int key_bits = tick_bits + t->depth_bits;
     if (key_bits > 64) return KLPM_EINVAL;
-    const int n_pass = (key_bits + kEvictDigitBits - 1) / kEvictDigitBits;
+    const int n_pass = (key_bits + kEvictDigitBits - 1) / kEvictDigitBits;  // <= 6: the arena holds six histograms
     t->clock_ub = clock_ub;
     if (batch_cap > 0) {
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
@@ -761,7 +761,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
     hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,
-                       budget, protect, tick_bits);
+                       budget, protect, tick_bits, n_pass);
     // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
     unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
     if (ge > 256u) ge = 256u;
