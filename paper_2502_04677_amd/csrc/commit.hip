@@ -44,6 +44,17 @@ __device__ __forceinline__ bool last_block_done(DevState *st, int slot) {
     return s_last != 0;
 }
 
+// Node ids are reserved up front, two per admitted prompt (an insertion makes at most one split
+// and at most one leaf), so the structure pass needs no shared allocation counter: reservation a
+// comes off the top of the free-id stack while it lasts, then from never-used ids.  Reservations
+// that end up unused are pushed back when the inserts are published.
+__device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
+    const DevState *st = tv.st;
+    int32_t f0 = st->free_cnt0;
+    int32_t id = (a < f0) ? tv.free_stack[f0 - 1 - a] : st->n_slots0 + (a - f0);
+    return (id > 0 && id < tv.max_nodes) ? id : -1;
+}
+
 // Resets the per-commit scalars, admits the batch (or abandons the commit), then: tail lengths ->
 // offsets inside the pool block of this commit; group keys; capacity decision.
 __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView q,
@@ -86,28 +97,33 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
         if (j < nb) {
             ws.used[j] = 0;
             ws.leaf_tok[j] = 0;
+            // the two node ids this prompt may use (at most one split and one leaf)
+            ws.resv_id[2 * j] = reserved_id(tv, 2 * j);
+            ws.resv_id[2 * j + 1] = reserved_id(tv, 2 * j + 1);
             int32_t m = ws.bm_len[j];
             if (m < 0) {
                 atomicOr(&bad, 1);
                 ws.gkey[j] = kNoGroup;
                 ws.end_node[j] = kRoot;
+                ws.next_tok[j] = -1;
             } else {
                 int32_t qi = batch_idx[j];
                 int32_t L = q.len[qi];
                 int32_t e = ws.bm_node[j];
                 tl = (int64_t)(L - m);
                 bool inside = m < tv.depth_end[e];
+                const int32_t nxt = (m < L) ? q.tokens[q.off[qi] + m] : -1;
                 uint64_t g;
                 if (!inside && m == L) {
                     g = kNoGroup;  // already present and ending on a node boundary: ticks only
                 } else if (inside) {
                     g = (uint64_t)(uint32_t)e << 33;
                 } else {
-                    int32_t nxt = q.tokens[q.off[qi] + m];
                     g = ((uint64_t)(uint32_t)e << 33) | (1ull << 32) | (uint64_t)(uint32_t)nxt;
                 }
                 ws.gkey[j] = g;
                 ws.end_node[j] = e;
+                ws.next_tok[j] = nxt;
             }
         }
         int64_t chunk_total;
@@ -336,26 +352,16 @@ __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key,
     return -1;
 }
 
-// Node ids are reserved up front, two per admitted prompt (an insertion makes at most one split
-// and at most one leaf), so the structure pass needs no shared allocation counter: reservation a
-// comes off the top of the free-id stack while it lasts, then from never-used ids.  Reservations
-// that end up unused are pushed back when the inserts are published.
-__device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
-    const DevState *st = tv.st;
-    int32_t f0 = st->free_cnt0;
-    int32_t id = (a < f0) ? tv.free_stack[f0 - 1 - a] : st->n_slots0 + (a - f0);
-    return (id > 0 && id < tv.max_nodes) ? id : -1;
-}
-
 // Split node c (reached through table slot s) after its first `at` edge tokens. The new node takes
 // the upper part; c keeps the lower part, its id, its end boundary, its children and its tick.
 // Returns the new upper node (wave-uniform) or -1.
 __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs &ws, int32_t j, int32_t c,
-                                              const NodeRec &rec, int32_t s, int32_t at, uint64_t tick, int lane) {
+                                              const NodeRec &rec, int32_t s, int32_t at, uint64_t tick, int32_t new_id,
+                                              int lane) {
     int32_t up = -1;
     if (lane == 0) {
         int32_t low_first = tv.pool[rec.edge_off + at];  // first token of the lower part (tokens never move)
-        up = reserved_id(tv, 2 * j);
+        up = new_id;
         if (up < 0) flag_error(tv.st, 1u);
         if (up > 0) {
             int64_t eo = rec.edge_off;
@@ -388,11 +394,13 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
     const int32_t m_v = ws.bm_len[j];
     const int32_t e_v = ws.bm_node[j];
     const int64_t to_v = ws.tail_off[j];
+    const int32_t split_id_v = ws.resv_id[2 * j], leaf_id_v = ws.resv_id[2 * j + 1], tok_m_v = ws.next_tok[j];
     const uint64_t clock0 = st->clock0;
     const int64_t pool_top = st->pool_top;
     const int32_t qi = uni(qi_v);
     const int32_t m = uni(m_v);
     const int32_t e = uni(e_v);
+    const int32_t split_id = uni(split_id_v), leaf_id = uni(leaf_id_v), tok_m = uni(tok_m_v);
     const int64_t qoff_v = q.off[qi];
     const int32_t L_v = q.len[qi];
     const int32_t de_e_v = ld_i32(&tv.depth_end[e]);
@@ -425,21 +433,21 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
                 if (lane == 0) flag_error(st, 4u);
                 return;
             }
-            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, lane);
+            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane);
             if (up < 0) return;
             cur = up;
         }
     }
     // From here on every child met is a node created by this commit; compare for real.
     while (d < L) {
-        int32_t tok = uni(x[d]);
+        int32_t tok = (d == m) ? tok_m : uni(x[d]);  // (the first unmatched token came with the plan)
         int32_t c, el;
         int64_t eo;
         int32_t s = slot_find_live(tv, make_key(cur, tok), c, el, eo);
         if (s < 0) {
             int32_t leaf = -1;
             if (lane == 0) {
-                leaf = reserved_id(tv, 2 * j + 1);
+                leaf = leaf_id;
                 if (leaf < 0) flag_error(st, 1u);
                 if (leaf > 0) {
                     int64_t off = tail_base + (int64_t)(d - m);
@@ -472,7 +480,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
             continue;
         }
         NodeRec rec = load_node(tv, c);
-        int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, lane);
+        int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane);
         if (up < 0) return;
         cur = up;
         d += jj;
@@ -493,9 +501,15 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
     // the first prompt of a group (in pick order) owns the group; the compares are independent
     // loads, so no early exit inside the loop
     bool dup = false;
-    for (int32_t base = 0; base < g; base += kWave) {
-        int32_t i = base + lane;
-        dup |= (i < g) && (ws.gkey[i] == key);
+    for (int32_t base = 0; base < g; base += 16 * kWave) {
+        uint64_t kk[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {  // sixteen rows requested together
+            const int32_t i = base + t * kWave + lane;
+            kk[t] = ws.gkey[i < g ? i : g];
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) dup |= (base + t * kWave + lane < g) && (kk[t] == key);
     }
     if (__ballot(dup)) return;
     insert_prompt(tv, q, batch_idx, ws, g, lane);
@@ -554,7 +568,6 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
         const int32_t f0 = st->free_cnt0;
         const int32_t from_free = A < f0 ? A : f0;
         const int32_t base = f0 - from_free;
-        for (int32_t a = tid; a < A; a += 256) ws.resv_id[a] = reserved_id(tv, a);
         unsigned long long my_tok = 0;
         int32_t my_new = 0;
         for (int32_t j2 = tid; j2 < nb; j2 += 256) {
@@ -570,7 +583,6 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
         const int32_t hi = lo + per < A ? lo + per : A;
         int32_t cnt = 0;
         for (int32_t a = lo; a < hi; ++a) cnt += ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
-        __syncthreads();  // orders the resv_id writes before the reads below
         int32_t unused_total;
         int32_t incl = block_inclusive_scan<int32_t, 256>(cnt, sbuf, tid, unused_total);
         int32_t dst = base + incl - cnt;

@@ -93,6 +93,7 @@ struct CommitWs {
     int32_t *end_node;  // [max_batch] node at which prompt j ends after insertion
     int32_t *used;      // [max_batch] bit 0: prompt j used its reserved split id, bit 1: its reserved leaf id
     int32_t *leaf_tok;  // [max_batch] tokens of the leaf prompt j added (0 if none)
+    int32_t *next_tok;  // [max_batch] first unmatched token of prompt j (-1: matched in full)
     int32_t *resv_id;   // [2*max_batch] scratch: the node ids reserved for this commit
     int64_t *evict_hist; // [6][2048] weighted digit histograms of the eviction cut search
     int32_t *iota_idx;  // [max_batch] scratch batch indices for build_tree

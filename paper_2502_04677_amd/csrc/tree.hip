@@ -11,7 +11,7 @@ namespace klpm {
 
 struct Layout {
     size_t state, parent, edge_off, edge_len, depth_end, tick, free_stack, slots, pool;
-    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, resv_id, evict_hist, iota_idx, iota_n;
+    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, resv_id, evict_hist, iota_idx, iota_n;
     size_t total;
     uint32_t n_slots_table;
 };
@@ -46,6 +46,7 @@ static Layout make_layout(const kLPM_config &c) {
     L.end_node = take(mb * 4);
     L.used = take(mb * 4);
     L.leaf_tok = take(mb * 4);
+    L.next_tok = take(mb * 4);
     L.resv_id = take(mb * 8);
     L.evict_hist = take(6 * 2048 * 8);  // eviction cut search: 6 passes of 2048 weighted bins
     L.iota_idx = take(mb * 4);
@@ -313,6 +314,7 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     ws.end_node = (int32_t *)(base + L.end_node);
     ws.used = (int32_t *)(base + L.used);
     ws.leaf_tok = (int32_t *)(base + L.leaf_tok);
+    ws.next_tok = (int32_t *)(base + L.next_tok);
     ws.resv_id = (int32_t *)(base + L.resv_id);
     ws.evict_hist = (int64_t *)(base + L.evict_hist);
     ws.iota_idx = (int32_t *)(base + L.iota_idx);
