@@ -41,6 +41,8 @@ extern "C" {
 #define KLPM_DEV_BATCH_OVERFLOW 8u /* *n_selected larger than the capacity given to kLPM_commit */
 #define KLPM_DEV_CLOCK_RANGE 16u   /* more prompts admitted than the launch sequence was sized for
                                       (see kLPM_reserve_clock); that commit evicted nothing */
+#define KLPM_DEV_INTERNAL 32u      /* the tree and its child table disagree (memory overwritten from outside,
+                                      or a defect of the library): the tree is no longer usable */
 
 /* k value that encodes k = infinity (pure longest-prefix-match order); k = 0 means the same. */
 #define KLPM_K_INFINITY 0xFFFFFFFFu

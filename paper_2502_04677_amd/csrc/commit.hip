@@ -23,6 +23,7 @@
 namespace klpm {
 
 constexpr uint64_t kNoGroup = ~0ull;
+constexpr uint32_t kDevInternal = 32u;  // KLPM_DEV_INTERNAL: the tree and its child table disagree
 constexpr int kEvictDigitBits = 11;  // eviction cut search: bits of the key resolved per pass
 constexpr int kEvictBins = 1 << kEvictDigitBits;
 constexpr int kPlanThreads = 1024;
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(256) void k_compact_copy(TreeView tv) {
             int32_t c, el;
             int64_t eo;
             int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
-            if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, 4u);
+            if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, kDevInternal);
         }
     }
     if (last_block_done(st, 0) && threadIdx.x == 0) {
@@ -430,7 +431,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
             int32_t first = uni(tv.pool[rec.edge_off]);
             int32_t s = slot_find_live(tv, make_key(rec.parent, first), c2, el2, eo2);
             if (s < 0 || c2 != cur || m - ds <= 0) {
-                if (lane == 0) flag_error(st, 4u);
+                if (lane == 0) flag_error(st, kDevInternal);
                 return;
             }
             int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane);
@@ -471,7 +472,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
         int32_t lim = el < L - d ? el : L - d;
         int32_t jj = wave_common_prefix(x + d, tv.pool + eo, lim, lane);
         if (jj <= 0) {  // the first token matched by construction; anything else is corruption
-            if (lane == 0) flag_error(st, 4u);
+            if (lane == 0) flag_error(st, kDevInternal);
             return;
         }
         if (jj == el) {
@@ -719,7 +720,7 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
                     __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
                 }
-                if (kk == kEmptyKey) { flag_error(st, 4u); break; }
+                if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
                 h = (h + 1) & tv.slot_mask;
             }
             int32_t pos = atomicAdd(&st->free_cnt, 1);
