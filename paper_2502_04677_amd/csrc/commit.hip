@@ -620,6 +620,8 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
                 st->need_evict = need;
                 st->evict_rem = need;
                 st->evict_prefix = 0;
+                st->evict_all = 0;
+                st->cand_cnt = 0;
                 evict = 1;
             }
         }
@@ -632,24 +634,30 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
 // ------------------------------------------------------------------ eviction
 // Order of removal: tick ascending, then depth descending (the deepest node of the oldest path is
 // the one leaf carrying the smallest tick).  key = tick * 2^depth_bits + (depth_mask - depth_end).
+// The cut key is found from the top: weighted digit histograms over all nodes narrow the key down to
+// a window of 64 ticks; the few nodes inside that window are then collected and sorted, and a prefix
+// sum of their lengths gives the exact cut.
+constexpr int kEvictTailTicks = 6;  // log2 of the tick window that the sorting pass takes over
+
 __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, int depth_bits) {
     uint64_t dm = (1ull << depth_bits) - 1ull;
     return (tv.tick[id] << depth_bits) | (dm - (uint64_t)(uint32_t)tv.depth_end[id]);
 }
 
 // One step of the search for the cut key, run by one workgroup of 256 threads once the weighted
-// histogram of the current digit is complete: pick the smallest digit whose inclusive weight
-// reaches what is still to be freed, append it to the prefix and reduce the remainder.  When the
-// nodes that may go (protected ones are left out of the histograms) do not free enough, the largest
-// digit is taken at every step and the cut ends above every key: all of them go.
-__device__ void evict_descend_step(DevState *st, const int64_t *__restrict__ hist) {
+// histogram of the current digit (`width` bits) is complete: pick the smallest digit whose inclusive
+// weight reaches what is still to be freed, append it to the prefix and reduce the remainder.  When
+// the nodes that may go (protected ones are left out of the histograms) do not free enough, all of
+// them go.
+__device__ void evict_descend_step(DevState *st, const int64_t *hist, int width, bool first) {
     __shared__ int64_t part[256 / kWave];
     __shared__ int pick;
     __shared__ int64_t s_below;
     const int tid = threadIdx.x;
     constexpr int per = kEvictBins / 256;  // contiguous bins per thread
     const int64_t rem = st->evict_rem;
-    if (tid == 0) { pick = kEvictBins - 1; s_below = 0; }
+    __syncthreads();
+    if (tid == 0) { pick = (1 << width) - 1; s_below = 0; }
     int64_t w[per];
     int64_t mine = 0;
 #pragma unroll
@@ -666,12 +674,17 @@ __device__ void evict_descend_step(DevState *st, const int64_t *__restrict__ his
     }
     __syncthreads();
     if (tid == 0) {
+        if (first && all < rem) st->evict_all = 1;
         st->evict_rem = rem - s_below;
-        st->evict_prefix = (st->evict_prefix << kEvictDigitBits) | (uint64_t)pick;
+        st->evict_prefix = (st->evict_prefix << width) | (uint64_t)pick;
     }
+    __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, int pass, int n_pass, int depth_bits) {
+// Histogram pass over every node: digit = bits [shift, shift + width) of the key, among the nodes
+// whose higher key bits equal the prefix found so far.
+__global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, int pass, int shift, int width,
+                                                    int depth_bits) {
     DevState *st = tv.st;
     if (!st->do_evict) return;
     __shared__ unsigned long long h[kEvictBins];
@@ -679,23 +692,122 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     const uint64_t prefix = st->evict_prefix;  // digits fixed by the earlier passes
     for (int i = tid; i < kEvictBins; i += 256) h[i] = 0;
     __syncthreads();
-    const int shift = kEvictDigitBits * (n_pass - 1 - pass);
     const int32_t n_slots = st->n_slots;
     const uint64_t keep_from = st->keep_from;
+    const int upper = shift + width;
     for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
         int32_t len = tv.edge_len[id];
         if (len <= 0 || tv.tick[id] >= keep_from) continue;
         uint64_t key = evict_key(tv, id, depth_bits);
-        bool in_prefix = (pass == 0) || ((key >> (shift + kEvictDigitBits)) == prefix);
-        if (in_prefix) atomicAdd(&h[(key >> shift) & (uint64_t)(kEvictBins - 1)], (unsigned long long)len);
+        bool in_prefix = (pass == 0) || (upper >= 64 ? prefix == 0 : (key >> upper) == prefix);
+        if (in_prefix) atomicAdd(&h[(key >> shift) & (uint64_t)((1 << width) - 1)], (unsigned long long)len);
     }
     __syncthreads();
-    for (int i = tid; i < kEvictBins; i += 256)
+    for (int i = tid; i < (1 << width); i += 256)
         if (h[i]) atomicAdd((unsigned long long *)&ws.evict_hist[pass * kEvictBins + i], h[i]);
-    if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * kEvictBins);
+    if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * kEvictBins, width, pass == 0);
 }
 
-__global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int n_pass, int depth_bits) {
+// Last stretch of the search: collect the nodes whose key agrees with the prefix above bit `shift`;
+// the last workgroup sorts them by key and cuts where their lengths add up to what is left to free.
+// More nodes than fit (very deep paths stamped by few prompts) are handled by the same workgroup
+// with digit passes of its own over all nodes.
+__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
+    DevState *st = tv.st;
+    if (!st->do_evict) return;
+    __shared__ uint64_t s_key[kEvictCand];
+    __shared__ int32_t s_len[kEvictCand];
+    __shared__ int64_t part[256 / kWave];
+    __shared__ unsigned long long s_cut;
+    const int tid = threadIdx.x;
+    const uint64_t prefix = st->evict_prefix;
+    const int32_t n_slots = st->n_slots;
+    const uint64_t keep_from = st->keep_from;
+    const bool evict_all = st->evict_all != 0;
+    if (!evict_all) {
+        for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
+            int32_t len = tv.edge_len[id];
+            if (len <= 0 || tv.tick[id] >= keep_from) continue;
+            uint64_t key = evict_key(tv, id, depth_bits);
+            if (n_hist_pass == 0 || shift >= 64 || (key >> shift) == prefix) {
+                int32_t at = atomicAdd(&st->cand_cnt, 1);
+                if (at < kEvictCand) {
+                    ws.cand_key[at] = key;
+                    ws.cand_len[at] = len;
+                }
+            }
+        }
+    }
+    if (!last_block_done(st, 10)) return;
+    if (evict_all) {
+        if (tid == 0) st->evict_prefix = ~0ull;
+        return;
+    }
+    const int32_t n = __hip_atomic_load(&st->cand_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (n > kEvictCand) {
+        // digit passes over all nodes by this workgroup alone (rare): the remaining `shift` bits of the key
+        unsigned long long *h = reinterpret_cast<unsigned long long *>(s_key);  // kEvictBins words fit
+        int low = shift;
+        while (low > 0) {
+            const int width = low % kEvictDigitBits ? low % kEvictDigitBits : kEvictDigitBits;
+            low -= width;
+            const uint64_t pre = st->evict_prefix;
+            for (int i = tid; i < kEvictBins; i += 256) h[i] = 0;
+            __syncthreads();
+            for (int64_t id = 1 + tid; id < n_slots; id += 256) {
+                int32_t len = tv.edge_len[id];
+                if (len <= 0 || tv.tick[id] >= keep_from) continue;
+                uint64_t key = evict_key(tv, id, depth_bits);
+                const int upper = low + width;
+                bool in_prefix = (n_hist_pass == 0 && upper == shift) || upper >= 64 || (key >> upper) == pre;
+                if (in_prefix) atomicAdd(&h[(key >> low) & (uint64_t)((1 << width) - 1)], (unsigned long long)len);
+            }
+            __syncthreads();
+            evict_descend_step(st, reinterpret_cast<const int64_t *>(h), width, false);
+        }
+        return;
+    }
+    // sort the collected nodes by key (bitonic network in LDS), then the cut
+    int32_t np2 = 1;
+    while (np2 < n) np2 <<= 1;
+    for (int32_t i = tid; i < np2; i += 256) {
+        s_key[i] = i < n ? __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
+        s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    }
+    __syncthreads();
+    for (int32_t size = 2; size <= np2; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = tid; t < (np2 >> 1); t += 256) {
+                const int32_t a = 2 * t - (t & (stride - 1)), b = a + stride;
+                const bool up = (a & size) == 0;
+                const uint64_t ka = s_key[a], kb = s_key[b];
+                if ((ka > kb) == up) {
+                    s_key[a] = kb; s_key[b] = ka;
+                    const int32_t la = s_len[a]; s_len[a] = s_len[b]; s_len[b] = la;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
+    // reaches the remainder is the last one to go
+    const int64_t rem = st->evict_rem;
+    const int32_t per = (n + 255) / 256;
+    const int32_t lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
+    int64_t mine = 0;
+    for (int32_t i = lo; i < hi; ++i) mine += s_len[i];
+    if (tid == 0) s_cut = ~0ull;  // (all of them, should the weights fall short)
+    int64_t all;
+    int64_t run = block_inclusive_scan<int64_t, 256>(mine, part, tid, all) - mine;
+    for (int32_t i = lo; i < hi; ++i) {
+        if (run < rem && run + s_len[i] >= rem) s_cut = s_key[i];
+        run += s_len[i];
+    }
+    __syncthreads();
+    if (tid == 0) st->evict_prefix = s_cut;
+}
+
+__global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int depth_bits) {
     DevState *st = tv.st;
     if (!st->do_evict) return;
     __shared__ unsigned long long s_tok;
@@ -758,7 +870,11 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     while (tick_bits < 64 && (clock_bound >> tick_bits)) ++tick_bits;
     const int key_bits = tick_bits + t->depth_bits;
     if (key_bits > 64) return KLPM_EINVAL;
-    const int n_pass = (key_bits + kEvictDigitBits - 1) / kEvictDigitBits;  // <= 6: the arena holds six histograms
+    // digit passes narrow the tick down to a window of 2^tail ticks, the sorting pass does the rest
+    const int tail = tick_bits < kEvictTailTicks ? tick_bits : kEvictTailTicks;
+    const int hist_bits = tick_bits - tail;
+    const int n_pass = (hist_bits + kEvictDigitBits - 1) / kEvictDigitBits;  // <= 6: the arena holds six histograms
+    const int final_shift = t->depth_bits + tail;  // key bits left to the sorting pass
     t->clock_ub = clock_ub;
     if (batch_cap > 0) {
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
@@ -778,9 +894,14 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
     unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
     if (ge > 256u) ge = 256u;
-    for (int p = 0; p < n_pass; ++p)
-        hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, n_pass, t->depth_bits);
-    hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, t->depth_bits);
+    for (int p = 0; p < n_pass; ++p) {
+        // the first digit takes what the others leave over, so that the last one ends at final_shift
+        const int shift = final_shift + kEvictDigitBits * (n_pass - 1 - p);
+        const int width = p == 0 ? hist_bits - kEvictDigitBits * (n_pass - 1) : kEvictDigitBits;
+        hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, shift, width, t->depth_bits);
+    }
+    hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits);
+    hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
     int64_t n = (int64_t)tv.slot_mask + 1;
     // few workgroups with grid-stride loops: these two usually have nothing to do, and every
     // workgroup of the second one ends on a shared counter

@@ -14,6 +14,7 @@ namespace klpm {
 
 constexpr int kWave = 64;
 constexpr int32_t kRoot = 0;
+constexpr int kEvictCand = 8192;  // nodes the last stretch of the eviction cut search sorts in LDS
 constexpr uint64_t kEmptyKey = ~0ull;
 // A slot whose node was evicted: probes walk past it, inserts may take it over. (No real key has
 // parent id -1.)
@@ -64,6 +65,8 @@ struct DevState {
     uint64_t evict_prefix; // digits of the eviction cut key fixed so far
     int64_t evict_rem;     // tokens still to free among the keys that share that prefix
     uint64_t keep_from;    // nodes with tick >= this belong to prompts in flight and are not evicted
+    int32_t evict_all;     // the nodes that may go do not free enough: all of them go
+    int32_t cand_cnt;      // nodes collected for the last stretch of the cut search
 };
 
 // Everything a kernel needs to walk or edit the tree; passed by value.
@@ -96,6 +99,8 @@ struct CommitWs {
     int32_t *next_tok;  // [max_batch] first unmatched token of prompt j (-1: matched in full)
     int32_t *resv_id;   // [2*max_batch] scratch: the node ids reserved for this commit
     int64_t *evict_hist; // [6][2048] weighted digit histograms of the eviction cut search
+    uint64_t *cand_key;  // [kEvictCand] eviction keys of the nodes collected for the last stretch of the search
+    int32_t *cand_len;   // [kEvictCand] their edge lengths
     int32_t *iota_idx;  // [max_batch] scratch batch indices for build_tree
     int32_t *iota_n;    // [1]
 };

@@ -995,3 +995,37 @@ def test_largest_batch_and_very_long_prompts():
     assert m.tolist() == hq.len.tolist() == ref.match(hq.tokens, hq.off, hq.len).tolist()
     # and a budget that keeps only the most recent path
     _check_step(s, ref, q, hq, K_INF, 1, 0, 250_000, big=True)
+
+
+def test_eviction_cut_inside_a_tick_with_thousands_of_nodes():
+    """A chain of 9,000 one-token nodes, all stamped by one prompt (the full string inserted last):
+    the eviction cut then falls among more nodes of a single tick than the sorting pass holds, and
+    the search has to finish with digit passes over the depth."""
+    rng = np.random.default_rng(71)
+    n = 9000
+    base = rng.integers(0, 32000, size=n).astype(np.int32)
+    # prompts = prefixes of one string, shortest first: every insertion appends a one-token node
+    ln = np.arange(1, n + 1, dtype=np.int32)
+    off = np.zeros(n, np.int64)
+    tok = np.tile(base, 1)
+    cache = W.Prompts(tok, off, ln, np.arange(n, dtype=np.uint64))  # all prompts share the one token buffer
+    other = _short_prompts(rng, 64, 32000, 40, 80)
+    full = W.generators._from_lists([base.tolist()], [0])
+    hq = W.concat_prompts(full, other)
+    w = W.Workload("chain", cache, hq, 1, 8, 1 << 40)
+    s, ref, q = _setup(w, max_batch=64, max_len=n)
+    assert K.kLPM_read_stats(s.tree).n_nodes == n
+    # the full string stamps all 9,000 nodes with one tick; then a few unrelated prompts
+    for batch_ids, budget in (([0], 1 << 40), (list(range(1, 9)), n - 100), (list(range(9, 17)), 5000),
+                              (list(range(17, 25)), 4321), (list(range(25, 33)), 700), (list(range(33, 41)), 0)):
+        idx = np.array(batch_ids, dtype=np.int32)
+        s.batch_idx[: idx.shape[0]] = torch.from_numpy(idx).cuda()
+        s.n_selected.fill_(idx.shape[0])
+        K.kLPM_set_budget(s.tree, budget)
+        s.commit(q, 64)
+        st_ref = ref.commit(hq.tokens, hq.off, hq.len, idx, budget)
+        st = s.read_stats()
+        assert st.device_error == 0
+        assert (st.total_tokens, st.evicted_tokens, st.n_nodes, st.evicted_nodes) == (
+            st_ref.total_tokens, st_ref.evicted_tokens, st_ref.n_nodes, st_ref.evicted_nodes), budget
+        _same_tree(s, ref, big=True)
