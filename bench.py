@@ -407,7 +407,27 @@ def main() -> int:
         torch.cuda.synchronize()
         m_batch = int(n_m.sum().item())
         kv_ms = e1.elapsed_time(e2) / reps
-        out["extras"] = {"token_budget_ms": e0.elapsed_time(e1) / reps, "kv_slots_ms": kv_ms,
+        # what plain streaming reaches on this GPU (context for the match kernel's figure): a 1 GiB
+        # device-to-device copy (read + write) and a 1 GiB read-only sweep
+        big = torch.empty(1 << 28, dtype=torch.int32, device=dev).fill_(1)
+        dst = torch.empty_like(big)
+        sink = torch.zeros(1, dtype=torch.int64, device=dev)
+        c0, c1, c2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        dst.copy_(big)
+        K.kLPM_probe_read(big, sink)
+        c0.record()
+        for _ in range(5):
+            dst.copy_(big)
+        c1.record()
+        for _ in range(5):
+            K.kLPM_probe_read(big, sink)
+        c2.record()
+        torch.cuda.synchronize()
+        copy_gbs = 2.0 * big.numel() * 4 / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
+        read_gbs = 1.0 * big.numel() * 4 / (c1.elapsed_time(c2) / 5 * 1e-3) / 1e9
+        del big, dst
+        out["extras"] = {"stream_copy_GBps": copy_gbs, "stream_read_GBps": read_gbs,
+                         "token_budget_ms": e0.elapsed_time(e1) / reps, "kv_slots_ms": kv_ms,
                          "kv_slots_matched_tokens": m_batch,
                          # per matched token: 4 B query + 4 B edge token read, 8 B slot written
                          "kv_slots_GBps": 16.0 * m_batch / (kv_ms * 1e-3) / 1e9}

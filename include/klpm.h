@@ -321,6 +321,13 @@ int kLPM_queue_advance_timed(const kLPM_queue *cur, const kLPM_queue *next, cons
                              int32_t batch_cap, const kLPM_arrivals *pending, int64_t *ttft, int64_t *matched_accum,
                              uint32_t *dev_error, kLPM_stream stream);
 
+/*
+ * Measurement helper: one plain streaming read over `bytes` of DEVICE memory at `src` (16-byte
+ * aligned).  Nothing is computed; *sink (DEVICE) only keeps the loads alive.  Timing it gives the
+ * read bandwidth a kernel can reach on this GPU, the yardstick beside kLPM_match's figures.
+ */
+int kLPM_probe_read(const void *src, size_t bytes, uint64_t *sink, kLPM_stream stream);
+
 /* Synchronises the stream and copies the tree's counters to HOST memory. */
 int kLPM_read_stats(kLPM_tree *tree, kLPM_stats *host_out, kLPM_stream stream);
 

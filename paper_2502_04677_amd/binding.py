@@ -26,7 +26,7 @@ EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
     "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
     "kLPM_commit", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather",
-    "kLPM_read_stats",
+    "kLPM_read_stats", "kLPM_probe_read",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
 
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
     lib.kLPM_queue_advance_timed.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32,
                                              C.POINTER(Arrivals), vp, vp, vp, vp]
     lib.kLPM_queue_gather.argtypes = [C.POINTER(Queue), C.POINTER(Queries), vp]
+    lib.kLPM_probe_read.argtypes = [vp, sz, vp, vp]
     lib.kLPM_read_stats.argtypes = [vp, C.POINTER(Stats), vp]
     lib.kLPM_snapshot_bytes.argtypes = [vp, C.POINTER(sz), vp]
     lib.kLPM_snapshot.argtypes = [vp, vp, sz, C.POINTER(sz), vp]
@@ -373,6 +374,12 @@ def kLPM_queue_advance_timed(cur: DeviceQueue, nxt: DeviceQueue, all_q: DeviceQu
 def kLPM_queue_gather(q: DeviceQueue, all_q: DeviceQueries, stream=None) -> None:
     c, a = q.c_struct(), all_q.c_struct()
     _check(_lib.kLPM_queue_gather(C.byref(c), C.byref(a), _stream(stream)), "kLPM_queue_gather")
+
+
+def kLPM_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    assert sink.dtype == torch.int64 and src.is_contiguous()
+    _check(_lib.kLPM_probe_read(_ptr(src), int(src.numel() * src.element_size()), _ptr(sink), _stream(stream)),
+           "kLPM_probe_read")
 
 
 def kLPM_read_stats(tree: Tree, stream=None) -> Stats:
