@@ -235,15 +235,32 @@ __device__ __forceinline__ void two_cursor_walk(const Acc &acc, int32_t n_valid,
             if (c > 0) {
                 const int32_t my_a = (int32_t)__popcll(mask_a & ((1ull << lane) - 1ull));
                 const int32_t my_l = (int32_t)__popcll(mask_l & ((1ull << lane) - 1ull));
-                const int32_t take_l = c * (int32_t)km1;
-                const bool ch_a = cand_a && my_a < c;
-                const bool ch_l = cand_l && my_l < take_l;
-                const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
-                const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
-                // an oldest pick that also lies in the consumed stretch of the longest-match order (or
-                // the other way round) makes the two streams interact: then go one run at a time
-                const uint64_t clash = __ballot((ch_a && a_other < (uint32_t)il_end) || (ch_l && l_other < (uint32_t)ia_end));
-                if (clash == 0ull) {
+                {
+                    // an oldest pick that also lies in the consumed stretch of the longest-match order (or
+                    // the other way round) makes the two streams interact: only the cycles before the
+                    // first such pick are taken at once (a shorter stretch cannot create new clashes)
+                    const int32_t take_l = c * (int32_t)km1;
+                    const bool ch_a = cand_a && my_a < c;
+                    const bool ch_l = cand_l && my_l < take_l;
+                    const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
+                    const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
+                    const uint64_t clash_a = __ballot(ch_a && a_other < (uint32_t)il_end);
+                    const uint64_t clash_l = __ballot(ch_l && l_other < (uint32_t)ia_end);
+                    if (clash_a) {
+                        const int32_t before = (int32_t)__popcll(mask_a & ((1ull << __builtin_ctzll(clash_a)) - 1ull));
+                        c = before < c ? before : c;
+                    }
+                    if (clash_l) {
+                        const int32_t before = (int32_t)((uint32_t)__popcll(mask_l & ((1ull << __builtin_ctzll(clash_l)) - 1ull)) / km1);
+                        c = before < c ? before : c;
+                    }
+                }
+                if (c > 0) {
+                    const int32_t take_l = c * (int32_t)km1;
+                    const bool ch_a = cand_a && my_a < c;
+                    const bool ch_l = cand_l && my_l < take_l;
+                    const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
+                    const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
                     if (ch_a) batch_idx[j + my_a * (int32_t)k] = (int32_t)a_el;
                     if (ch_l) {
                         uint32_t cyc = (uint32_t)my_l / km1;
@@ -422,108 +439,120 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         for (int32_t j = tid; j < nb; j += kFifoThreads) batch_idx[j] = j;
         return;
     }
-    // the nb-th largest match length m*, found digit by digit (11 bits per sweep)
-    int mbits = 0;
-    while (mbits < 31 && (s_max >> mbits) != 0) ++mbits;
-    int32_t fixed_hi = 0;      // value of the bits above `shift` already decided
-    int32_t need = nb;         // winners still to be found among elements matching fixed_hi
-    int shift = mbits;         // bits [shift, mbits) are decided
-    while (shift > 0) {
-        const int width = shift < 11 ? shift : 11;
-        const int nshift = shift - width;
-        for (int i = tid; i < kFifoBins; i += kFifoThreads) hist[i] = 0;
-        __syncthreads();
-        for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
-            int32_t mv[kSweepRows];
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kFifoThreads + tid;
-                mv[r] = match_len[i < n ? i : n - 1];
-            }
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kFifoThreads + tid;
-                int32_t m = mv[r] < 0 ? 0 : mv[r];
-                if (i < n && (m >> shift) == fixed_hi) atomicAdd(&hist[(m >> nshift) & ((1 << width) - 1)], 1u);
-            }
+    // the entries that can be picked: all of a short queue, else the nb best by match length
+    int32_t n_cand = nb;
+    if (n <= kFifoMaxBatch) {
+        n_cand = n;
+        for (int32_t i = tid; i < n; i += kFifoThreads) {
+            int32_t m = match_len[i];
+            m = m < 0 ? 0 : m;
+            cand[i] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
         }
-        __syncthreads();
-        // suffix counts over the bins, top down: thread t owns bins 2t and 2t+1 counted from the top
-        const int nbins = 1 << width;
-        int b0 = nbins - 1 - 2 * tid, b1 = nbins - 2 - 2 * tid;
-        int32_t c0 = (b0 >= 0) ? (int32_t)hist[b0] : 0;
-        int32_t c1 = (b1 >= 0) ? (int32_t)hist[b1] : 0;
-        int32_t all_bins;
-        int32_t incl = block_inclusive_scan<int32_t, kFifoThreads>(c0 + c1, sbuf, tid, all_bins);
-        int32_t before = incl - c0 - c1;  // elements in bins above b0
-        if (b0 >= 0 && before < need && before + c0 >= need) { s_bin = b0; s_above = before; }
-        if (b1 >= 0 && before + c0 < need && before + c0 + c1 >= need) { s_bin = b1; s_above = before + c0; }
-        __syncthreads();
-        fixed_hi = (fixed_hi << width) | s_bin;
-        need -= s_above;
-        shift = nshift;
-        __syncthreads();
-    }
-    const int32_t m_star = fixed_hi;  // count(m > m*) = nb - need < nb <= count(m >= m*)
-    // gather: every query above m*, and the first `need` queries (by index) equal to m*.  Each
-    // wavefront owns a contiguous segment of the queue and reads it 64 entries at a time, so the
-    // index order of the equal-to-m* queries is a ballot prefix plus the counts of earlier segments.
-    {
-        const int lane = tid & (kWave - 1);
-        const int wv = tid / kWave;
-        const int n_wv = kFifoThreads / kWave;
-        const int32_t seg = ((n + n_wv - 1) / n_wv + kWave - 1) / kWave * kWave;
-        const int32_t lo = (int64_t)wv * seg < n ? wv * seg : n;
-        const int32_t hi = lo + seg < n ? lo + seg : n;
-        int32_t eq = 0;
-        for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
-            int32_t mv[kSweepRows];
+    } else {
+        // the nb-th largest match length m*, found digit by digit (11 bits per sweep)
+        int mbits = 0;
+        while (mbits < 31 && (s_max >> mbits) != 0) ++mbits;
+        int32_t fixed_hi = 0;      // value of the bits above `shift` already decided
+        int32_t need = nb;         // winners still to be found among elements matching fixed_hi
+        int shift = mbits;         // bits [shift, mbits) are decided
+        while (shift > 0) {
+            const int width = shift < 11 ? shift : 11;
+            const int nshift = shift - width;
+            for (int i = tid; i < kFifoBins; i += kFifoThreads) hist[i] = 0;
+            __syncthreads();
+            for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
+                int32_t mv[kSweepRows];
 #pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kWave + lane;
-                mv[r] = match_len[i < hi ? i : hi - 1];
-            }
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kWave + lane;
-                int32_t m = mv[r] < 0 ? 0 : mv[r];
-                eq += (int32_t)__popcll(__ballot(i < hi && m == m_star));
-            }
-        }
-        if (lane == 0) sbuf[wv] = eq;
-        __syncthreads();
-        int32_t rank = 0;  // equal-to-m* queries in earlier segments
-        for (int w2 = 0; w2 < wv; ++w2) rank += sbuf[w2];
-        for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
-            int32_t mv[kSweepRows];
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kWave + lane;
-                mv[r] = match_len[i < hi ? i : hi - 1];
-            }
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kWave + lane;
-                bool in = i < hi;
-                int32_t m = mv[r] < 0 ? 0 : mv[r];
-                bool is_eq = in && m == m_star;
-                uint64_t eqmask = __ballot(is_eq);
-                int32_t my_rank = rank + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
-                bool win = in && (m > m_star || (is_eq && my_rank < need));
-                if (win) {
-                    int32_t at = atomicAdd(&s_count, 1);
-                    if (at < kFifoMaxBatch)
-                        cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+                for (int r = 0; r < kSweepRows; ++r) {
+                    int32_t i = base + r * kFifoThreads + tid;
+                    mv[r] = match_len[i < n ? i : n - 1];
                 }
-                rank += (int32_t)__popcll(eqmask);
+#pragma unroll
+                for (int r = 0; r < kSweepRows; ++r) {
+                    int32_t i = base + r * kFifoThreads + tid;
+                    int32_t m = mv[r] < 0 ? 0 : mv[r];
+                    if (i < n && (m >> shift) == fixed_hi) atomicAdd(&hist[(m >> nshift) & ((1 << width) - 1)], 1u);
+                }
+            }
+            __syncthreads();
+            // suffix counts over the bins, top down: thread t owns bins 2t and 2t+1 counted from the top
+            const int nbins = 1 << width;
+            int b0 = nbins - 1 - 2 * tid, b1 = nbins - 2 - 2 * tid;
+            int32_t c0 = (b0 >= 0) ? (int32_t)hist[b0] : 0;
+            int32_t c1 = (b1 >= 0) ? (int32_t)hist[b1] : 0;
+            int32_t all_bins;
+            int32_t incl = block_inclusive_scan<int32_t, kFifoThreads>(c0 + c1, sbuf, tid, all_bins);
+            int32_t before = incl - c0 - c1;  // elements in bins above b0
+            if (b0 >= 0 && before < need && before + c0 >= need) { s_bin = b0; s_above = before; }
+            if (b1 >= 0 && before + c0 < need && before + c0 + c1 >= need) { s_bin = b1; s_above = before + c0; }
+            __syncthreads();
+            fixed_hi = (fixed_hi << width) | s_bin;
+            need -= s_above;
+            shift = nshift;
+            __syncthreads();
+        }
+        const int32_t m_star = fixed_hi;  // count(m > m*) = nb - need < nb <= count(m >= m*)
+        // gather: every query above m*, and the first `need` queries (by index) equal to m*.  Each
+        // wavefront owns a contiguous segment of the queue and reads it 64 entries at a time, so the
+        // index order of the equal-to-m* queries is a ballot prefix plus the counts of earlier segments.
+        {
+            const int lane = tid & (kWave - 1);
+            const int wv = tid / kWave;
+            const int n_wv = kFifoThreads / kWave;
+            const int32_t seg = ((n + n_wv - 1) / n_wv + kWave - 1) / kWave * kWave;
+            const int32_t lo = (int64_t)wv * seg < n ? wv * seg : n;
+            const int32_t hi = lo + seg < n ? lo + seg : n;
+            int32_t eq = 0;
+            for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
+                int32_t mv[kSweepRows];
+#pragma unroll
+                for (int r = 0; r < kSweepRows; ++r) {
+                    int32_t i = base + r * kWave + lane;
+                    mv[r] = match_len[i < hi ? i : hi - 1];
+                }
+#pragma unroll
+                for (int r = 0; r < kSweepRows; ++r) {
+                    int32_t i = base + r * kWave + lane;
+                    int32_t m = mv[r] < 0 ? 0 : mv[r];
+                    eq += (int32_t)__popcll(__ballot(i < hi && m == m_star));
+                }
+            }
+            if (lane == 0) sbuf[wv] = eq;
+            __syncthreads();
+            int32_t rank = 0;  // equal-to-m* queries in earlier segments
+            for (int w2 = 0; w2 < wv; ++w2) rank += sbuf[w2];
+            for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
+                int32_t mv[kSweepRows];
+#pragma unroll
+                for (int r = 0; r < kSweepRows; ++r) {
+                    int32_t i = base + r * kWave + lane;
+                    mv[r] = match_len[i < hi ? i : hi - 1];
+                }
+#pragma unroll
+                for (int r = 0; r < kSweepRows; ++r) {
+                    int32_t i = base + r * kWave + lane;
+                    bool in = i < hi;
+                    int32_t m = mv[r] < 0 ? 0 : mv[r];
+                    bool is_eq = in && m == m_star;
+                    uint64_t eqmask = __ballot(is_eq);
+                    int32_t my_rank = rank + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
+                    bool win = in && (m > m_star || (is_eq && my_rank < need));
+                    if (win) {
+                        int32_t at = atomicAdd(&s_count, 1);
+                        if (at < kFifoMaxBatch)
+                            cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+                    }
+                    rank += (int32_t)__popcll(eqmask);
+                }
             }
         }
+        __syncthreads();
     }
     __syncthreads();
-    // sort the nb winners by (-match_len, index): bitonic network over the next power of two
+    // sort them by (-match_len, index): bitonic network over the next power of two
     int32_t np2 = 1;
-    while (np2 < nb) np2 <<= 1;
-    for (int32_t i = nb + tid; i < np2; i += kFifoThreads) cand[i] = ~0ull;
+    while (np2 < n_cand) np2 <<= 1;
+    for (int32_t i = n_cand + tid; i < np2; i += kFifoThreads) cand[i] = ~0ull;
     __syncthreads();
     for (int32_t size = 2; size <= np2; size <<= 1) {
         for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {

@@ -22,7 +22,8 @@ def size_config(cache_tokens: int, cache_prompts: int, budget: int, max_batch: i
     """
     finite = budget < (1 << 36)  # anything larger cannot be reached and means "never evict"
     live = max(int(cache_tokens), int(budget)) if finite else int(cache_tokens) + int(extra_tokens)
-    pool = int(live * 1.05) + 2 * max_batch * max_prompt_len + 4096
+    # (room for several worst-case batches between two pool compactions: the pool is cheap next to the HBM size)
+    pool = int(live * 1.05) + 8 * max_batch * max_prompt_len + 4096
     nodes = 2 * (cache_prompts + extra_prompts) + 4 * max_batch + 64
     return B.make_config(budget, pool, nodes, max_batch, max_prompt_len)
 
