@@ -14,7 +14,7 @@ namespace klpm {
 
 constexpr int kWave = 64;
 constexpr int32_t kRoot = 0;
-constexpr int kEvictCand = 8192;  // nodes the last stretch of the eviction cut search sorts in LDS
+constexpr int kEvictCand = 2048;  // nodes the last stretch of the eviction cut search sorts in LDS
 constexpr uint64_t kEmptyKey = ~0ull;
 // A slot whose node was evicted: probes walk past it, inserts may take it over. (No real key has
 // parent id -1.)
