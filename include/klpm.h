@@ -67,7 +67,9 @@ typedef struct {
 typedef struct {
     int64_t budget_tokens;  /* KV budget: eviction brings the cached token total down to <= this */
     int64_t pool_tokens;    /* capacity of one half of the edge-token pool (two halves are kept);
-                               must hold the budget plus the tokens of one commit batch */
+                               must hold what stays cached (the budget, or the initial cache if
+                               larger) plus one worst-case batch of max_batch * max_prompt_len tokens:
+                               the end of a commit compacts the pool when less than that is left */
     int32_t max_nodes;      /* node slots, root included */
     int32_t max_batch;      /* most prompts one kLPM_commit may admit (<= 65536) */
     int32_t max_prompt_len; /* longest prompt accepted */

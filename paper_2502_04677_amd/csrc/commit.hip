@@ -139,64 +139,63 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
         if (bad) {
             st->skip = 1;
         } else {
+            // the end of every commit leaves room for a worst-case batch if compaction can make it;
+            // tails that still do not fit mean the pool is too small for what must stay cached
             int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
             if (st->pool_top + carry > half_end) {
-                st->need_compact = 1;
-                st->compact_cursor = (int64_t)(1 - st->active_half) * tv.pool_half;
+                st->device_error |= 2u;  // KLPM_DEV_POOL_FULL
+                st->skip = 1;
             }
         }
     }
 }
 
-// ------------------------------------------------------------------ pool compaction (rare)
-// Moves every live edge span into the other half of the pool, patches the span kept in the child
-// table, and the last workgroup to finish switches halves.
-__global__ __launch_bounds__(256) void k_compact_copy(TreeView tv) {
+// ------------------------------------------------------------------ end-of-commit maintenance (rare work)
+// One launch that usually finds nothing to do.  Either pool compaction - when the active half no
+// longer has room for a worst-case batch and holds garbage, every live edge span moves into the other
+// half, the span kept in the child table is patched, and the last workgroup to finish switches
+// halves - or, when evictions have left many tombstones, the child table is emptied for the rebuild
+// that the next kernel does.  (Both at once: compaction now, the rebuild at the next commit.)
+__global__ __launch_bounds__(256) void k_maintain(TreeView tv) {
     DevState *st = tv.st;
-    if (!st->need_compact) return;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
-    const int32_t n_slots = st->n_slots;
-    const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
-    for (int64_t id = 1 + wave; id < n_slots; id += n_waves) {
-        int32_t len = uni(tv.edge_len[id]);
-        if (len <= 0) continue;
-        int64_t src = uni64(tv.edge_off[id]);
-        int64_t dst = 0;
-        if (lane == 0) dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)len);
-        dst = uni64(dst);
-        if (dst + len > dst_end) {  // cannot happen while total_tokens <= pool_half
-            if (lane == 0) flag_error(st, 2u);
-            continue;
+    if (st->need_compact) {
+        const int lane = threadIdx.x & (kWave - 1);
+        const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+        const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
+        const int32_t n_slots = st->n_slots;
+        const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
+        for (int64_t id = 1 + wave; id < n_slots; id += n_waves) {
+            int32_t len = uni(tv.edge_len[id]);
+            if (len <= 0) continue;
+            int64_t src = uni64(tv.edge_off[id]);
+            int64_t dst = 0;
+            if (lane == 0) dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)len);
+            dst = uni64(dst);
+            if (dst + len > dst_end) {  // cannot happen while total_tokens <= pool_half
+                if (lane == 0) flag_error(st, 2u);
+                continue;
+            }
+            int32_t first = uni(tv.pool[src]);
+            for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
+            if (lane == 0) {
+                tv.edge_off[id] = dst;
+                int32_t c, el;
+                int64_t eo;
+                int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
+                if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, kDevInternal);
+            }
         }
-        int32_t first = uni(tv.pool[src]);
-        for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
-        if (lane == 0) {
-            tv.edge_off[id] = dst;
-            int32_t c, el;
-            int64_t eo;
-            int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
-            if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, kDevInternal);
+        if (last_block_done(st, 0) && threadIdx.x == 0) {
+            st->active_half = 1 - st->active_half;
+            st->pool_top = st->compact_cursor;
         }
+        return;
     }
-    if (last_block_done(st, 0) && threadIdx.x == 0) {
-        st->active_half = 1 - st->active_half;
-        st->pool_top = st->compact_cursor;
-        int64_t half_end = ((int64_t)st->active_half + 1) * tv.pool_half;
-        if (st->pool_top + st->tail_total > half_end) {
-            st->device_error |= 2u;  // KLPM_DEV_POOL_FULL
-            st->skip = 1;
-        }
+    if (st->need_rebuild) {
+        const int64_t n = (int64_t)tv.slot_mask + 1;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+            tv.slots[i].key = kEmptyKey;
     }
-}
-
-// ------------------------------------------------------------------ child table rebuild
-__global__ __launch_bounds__(256) void k_hash_clear(TreeView tv) {
-    if (!tv.st->need_rebuild) return;
-    const int64_t n = (int64_t)tv.slot_mask + 1;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-        tv.slots[i].key = kEmptyKey;
 }
 
 __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict__ out) {
@@ -607,6 +606,19 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
             st->pool_top += st->tail_total;
             st->total_tokens += st->inserted_tokens;
             st->n_nodes += st->new_nodes;
+            // pool compaction at the end of this commit: wanted when the active half could not take a
+            // worst-case batch any more, useful when part of what it holds is garbage (spans of
+            // evicted nodes; an eviction further down only adds to it)
+            {
+                const int64_t half_base = (int64_t)st->active_half * tv.pool_half;
+                const int64_t room = half_base + tv.pool_half - st->pool_top;
+                const int64_t used = st->pool_top - half_base;
+                const int64_t worst = (int64_t)tv.max_batch * (int64_t)tv.max_prompt_len;
+                if (room < worst && (used > st->total_tokens || st->total_tokens > budget)) {
+                    st->need_compact = 1;
+                    st->compact_cursor = (int64_t)(1 - st->active_half) * tv.pool_half;
+                }
+            }
             // the paths of the `protect` most recently admitted prompts (this batch included) stay
             st->keep_from = protect <= 0 ? ~0ull : ((uint64_t)protect >= st->clock ? 0ull : st->clock - (uint64_t)protect);
             int64_t need = st->total_tokens - budget;
@@ -854,7 +866,7 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
         st->n_nodes -= ev_cnt;
         st->tombstones += ev_cnt;
         // rebuild the child table only when tombstones start to lengthen the probe sequences
-        if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1) st->need_rebuild = 1;
+        if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact) st->need_rebuild = 1;
     }
 }
 
@@ -883,9 +895,6 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
                        ws);
     if (batch_cap > 0) {
-        unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
-        if (gn > 2048u) gn = 2048u;
-        hipLaunchKernelGGL(k_compact_copy, dim3(gn), dim3(256), 0, stream, tv);
         hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws);
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
@@ -902,14 +911,13 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     }
     hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits);
     hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
-    int64_t n = (int64_t)tv.slot_mask + 1;
-    // few workgroups with grid-stride loops: these two usually have nothing to do, and every
-    // workgroup of the second one ends on a shared counter
-    unsigned gc = (unsigned)((n + 255) / 256);
-    if (gc > 256u) gc = 256u;
+    // maintenance and table refill usually have nothing to do: few workgroups with grid-stride loops
+    // (compaction works one wavefront per node)
+    unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
+    if (gn > 1024u) gn = 1024u;
     unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
     if (gf > 128u) gf = 128u;
-    hipLaunchKernelGGL(k_hash_clear, dim3(gc), dim3(256), 0, stream, tv);
+    hipLaunchKernelGGL(k_maintain, dim3(gn), dim3(256), 0, stream, tv);
     hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv, stats_out);
     return check_launch();
 }
