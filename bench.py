@@ -276,6 +276,8 @@ def main() -> int:
     ap.add_argument("--random-ties", action="store_true", help="break score ties uniformly at random (Philox keys)")
     ap.add_argument("--dynamic", action="store_true",
                     help="in-batch rescoring: scores follow the prompts picked earlier in the same batch")
+    ap.add_argument("--rematch", action="store_true",
+                    help="let the commit match the admitted prompts again instead of taking the step's match results")
     ap.add_argument("--graph", action="store_true",
                     help="after the timed steps, replay K more steps from one captured HIP graph and report them too")
     ap.add_argument("--extras", action="store_true",
@@ -339,13 +341,13 @@ def main() -> int:
     def one_step(s: int) -> None:
         q = run.view()
         mark(s, 0)
-        sched.match(q, want_nodes=args.dynamic)
+        sched.match(q)  # lengths and end nodes: the commit takes the admitted prompts' matches from here
         mark(s, 1)
         if args.dynamic:  # Algorithm 1 on scores that follow the picks made so far in the bin
             K.kLPM_select_dynamic(q, sched.match_len, sched.last_node, k, batch, sched.phase, dyn, sched.batch_idx,
                                   sched.n_selected, dyn_ws, dyn_bytes)
             mark(s, 2)
-            sched.commit(q, batch)
+            sched.commit(q, batch, reuse_match=not args.rematch)
             mark(s, 3)
             run.advance(batch, new_ids[s], matched=sums[s:s + 1])
             mark(s, 4)
@@ -357,7 +359,7 @@ def main() -> int:
         # the queue is kept in arrival order
         sched.select(q, k, batch, fifo=True, score=score, score_max=1 << rate_bits, tie_key=tie)
         mark(s, 2)
-        sched.commit(q, batch)
+        sched.commit(q, batch, reuse_match=not args.rematch)
         mark(s, 3)
         run.advance(batch, new_ids[s], matched=sums[s:s + 1])
         mark(s, 4)

@@ -203,6 +203,22 @@ int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t *batch_idx
                 int32_t batch_cap, kLPM_stats *stats, kLPM_stream stream);
 
 /*
+ * kLPM_commit for a caller that has just matched the whole queue: the admitted prompts' prefix
+ * matches are taken from that call's results instead of being computed again (within one scheduling
+ * step the tree does not change between the match and the commit, Algorithm 1).
+ *   match_len, last_node  DEVICE [q->n] as written by kLPM_match for this q on the tree as it is
+ *                         now (no commit or budget change with eviction in between)
+ * Each entry used is checked against the tree where that is cheap (node alive, match ends inside
+ * that node's edge on an equal token, nothing continues it); an entry that fails sets
+ * KLPM_DEV_BAD_INPUT and the commit is abandoned.  A stale entry that passes these checks leaves a
+ * tree with duplicated paths (never an out-of-bounds access): when in doubt call kLPM_commit.
+ * Everything else is as for kLPM_commit.
+ */
+int kLPM_commit_matched(kLPM_tree *tree, const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node,
+                        const int32_t *batch_idx, const int32_t *n_selected, int32_t batch_cap, kLPM_stats *stats,
+                        kLPM_stream stream);
+
+/*
  * Eviction protection for prompts in flight: the paths of the `recent_prompts` most recently
  * admitted prompts (the batch of the commit itself included) are never evicted by later commits;
  * eviction then stops early and the token total may stay above the budget (kLPM_stats.total_tokens

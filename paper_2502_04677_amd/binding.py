@@ -25,7 +25,7 @@ DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 EXPORTS = (
     "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
     "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
-    "kLPM_commit", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather",
+    "kLPM_commit", "kLPM_commit_matched", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather",
     "kLPM_read_stats", "kLPM_probe_read",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
@@ -79,6 +79,7 @@ def load_library() -> C.CDLL:
     lib.kLPM_score_hit_rate.argtypes = [vp, vp, i32, vp, i32, vp, vp]
     lib.kLPM_tie_keys.argtypes = [C.c_uint64, C.c_uint64, vp, i32, vp, vp, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
+    lib.kLPM_commit_matched.argtypes = [vp, C.POINTER(Queries), vp, vp, vp, vp, i32, vp, vp]
     lib.kLPM_set_budget.argtypes = [vp, i64]
     lib.kLPM_set_protect.argtypes = [vp, i64]
     lib.kLPM_reserve_clock.argtypes = [vp, C.c_uint64]
@@ -265,6 +266,16 @@ def kLPM_commit(tree: Tree, q: DeviceQueries, batch_idx: Optional[torch.Tensor],
     qs = q.c_struct()
     _check(_lib.kLPM_commit(tree.handle, C.byref(qs), _ptr(batch_idx), _ptr(n_selected), int(batch_cap), _ptr(stats),
                             _stream(stream)), "kLPM_commit")
+
+
+def kLPM_commit_matched(tree: Tree, q: DeviceQueries, match_len: torch.Tensor, last_node: torch.Tensor,
+                        batch_idx: Optional[torch.Tensor], n_selected: Optional[torch.Tensor], batch_cap: int,
+                        stats: Optional[torch.Tensor] = None, stream=None) -> None:
+    assert match_len.shape[0] >= q.n and last_node.shape[0] >= q.n
+    qs = q.c_struct()
+    _check(_lib.kLPM_commit_matched(tree.handle, C.byref(qs), _ptr(match_len), _ptr(last_node), _ptr(batch_idx),
+                                    _ptr(n_selected), int(batch_cap), _ptr(stats), _stream(stream)),
+           "kLPM_commit_matched")
 
 
 def kLPM_reserve_clock(tree: Tree, extra_prompts: int) -> None:

@@ -56,12 +56,53 @@ __device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
     return (id > 0 && id < tv.max_nodes) ? id : -1;
 }
 
+// A commit may take the admitted prompts' matches from queue-wide match results the caller vouches
+// for.  The plan kernel checks the ranges that later addressing depends on (index, the prompt's span,
+// 0 <= m <= |x|, node id); -1 = refused.
+__device__ __forceinline__ int32_t hinted_match(const TreeView &tv, const QView &q, int32_t qi,
+                                                const int32_t *__restrict__ hint_len,
+                                                const int32_t *__restrict__ hint_node, int32_t &node) {
+    node = kRoot;
+    if (qi < 0 || qi >= live_count(q.n, q.n_live)) return -1;
+    const int64_t off = q.off[qi];
+    const int32_t L = q.len[qi];
+    const int32_t m = hint_len[qi], e = hint_node[qi];
+    if (off < 0 || L < 1 || L > tv.max_prompt_len || off + (int64_t)L > q.n_tokens) return -1;
+    if (m < 0 || m > L || e < 0 || e >= tv.max_nodes) return -1;
+    node = e;
+    return m;
+}
+
+// What else can be checked locally about such a match, done by one lane per admitted prompt beside
+// the tail copy: the node is alive, the match ends inside that node's edge (or is empty at the
+// root), the last matched token is the edge's token there, and neither the edge nor a child
+// continues the prompt.
+__device__ __forceinline__ bool hinted_match_ok(const TreeView &tv, const int32_t *__restrict__ x, int32_t L, int32_t m,
+                                                int32_t e) {
+    if (m == 0) return e == kRoot ? true : false;
+    if (e == kRoot) return false;
+    const int32_t el = tv.edge_len[e], de = tv.depth_end[e];
+    const int64_t eo = tv.edge_off[e];
+    if (el <= 0 || m > de || m <= de - el) return false;
+    const int64_t at = eo + (int64_t)(m - 1 - (de - el));
+    if (tv.pool[at] != x[m - 1]) return false;
+    if (m == L) return true;
+    if (m < de) return tv.pool[at + 1] != x[m];
+    int32_t c, cl;
+    int64_t co;
+    return slot_find(tv.slots, tv.slot_mask, make_key(e, x[m]), c, cl, co) < 0;
+}
+
 // Resets the per-commit scalars, admits the batch (or abandons the commit), then: tail lengths ->
-// offsets inside the pool block of this commit; group keys; capacity decision.
+// offsets inside the pool block of this commit; group keys; capacity decision.  With hint_len the
+// admitted prompts' matches come from there instead of from a match launch before this kernel
+// (range-checked here, verified against the tree by the tail copy).
 __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView q,
                                                               const int32_t *__restrict__ batch_idx,
                                                               const int32_t *__restrict__ n_selected,
-                                                              int32_t batch_cap, CommitWs ws) {
+                                                              int32_t batch_cap, CommitWs ws,
+                                                              const int32_t *__restrict__ hint_len,
+                                                              const int32_t *__restrict__ hint_node) {
     __shared__ int64_t buf[kPlanThreads / kWave];
     __shared__ int64_t carry;
     __shared__ int bad;
@@ -101,7 +142,16 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
             // the two node ids this prompt may use (at most one split and one leaf)
             ws.resv_id[2 * j] = reserved_id(tv, 2 * j);
             ws.resv_id[2 * j + 1] = reserved_id(tv, 2 * j + 1);
-            int32_t m = ws.bm_len[j];
+            int32_t m;
+            if (hint_len) {
+                int32_t e_h;
+                m = hinted_match(tv, q, batch_idx[j], hint_len, hint_node, e_h);
+                if (m < 0) atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
+                ws.bm_len[j] = m;
+                ws.bm_node[j] = e_h;
+            } else {
+                m = ws.bm_len[j];
+            }
             if (m < 0) {
                 atomicOr(&bad, 1);
                 ws.gkey[j] = kNoGroup;
@@ -242,8 +292,10 @@ __global__ __launch_bounds__(256) void k_hash_fill(TreeView tv, kLPM_stats *__re
 }
 
 // ------------------------------------------------------------------ tails
+// (verify: the matches were handed in by the caller; a prompt whose match does not stand up to the
+// local checks abandons the commit before anything is published)
 __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
-                                                    CommitWs ws) {
+                                                    CommitWs ws, int verify) {
     DevState *st = tv.st;
     if (st->skip) return;
     const int32_t j = blockIdx.x;
@@ -252,6 +304,10 @@ __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const 
     const int32_t m = ws.bm_len[j];
     const int32_t L = q.len[qi];
     const int32_t *__restrict__ src = q.tokens + q.off[qi] + m;
+    if (verify && threadIdx.x == 0 && !hinted_match_ok(tv, src - m, L, m, ws.bm_node[j])) {
+        st->skip = 1;
+        atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
+    }
     int32_t *__restrict__ dst = tv.pool + st->pool_top + ws.tail_off[j];
     const int32_t len = L - m;
     // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
@@ -871,7 +927,8 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
 }
 
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
-                    int32_t batch_cap, int64_t budget, int64_t protect, kLPM_stats *stats_out, hipStream_t stream) {
+                    int32_t batch_cap, int64_t budget, int64_t protect, kLPM_stats *stats_out, hipStream_t stream,
+                    const int32_t *hint_len, const int32_t *hint_node) {
     const TreeView &tv = t->tv;
     const CommitWs &ws = t->ws;
     if (batch_cap > t->cfg.max_batch) batch_cap = t->cfg.max_batch;
@@ -888,14 +945,14 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     const int n_pass = (hist_bits + kEvictDigitBits - 1) / kEvictDigitBits;  // <= 6: the arena holds six histograms
     const int final_shift = t->depth_bits + tail;  // key bits left to the sorting pass
     t->clock_ub = clock_ub;
-    if (batch_cap > 0) {
+    if (batch_cap > 0 && !hint_len) {
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
         if (rc) return rc;
     }
     hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
-                       ws);
+                       ws, hint_len, hint_node);
     if (batch_cap > 0) {
-        hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws);
+        hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws, hint_len ? 1 : 0);
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
     hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,

@@ -24,9 +24,11 @@ namespace klpm {
 int launch_match(const TreeView &tv, const QView &q, const int32_t *sel, const int32_t *n_dev, int32_t n_cap,
                  int honor_skip, int32_t *out_len, int32_t *out_node, hipStream_t stream);
 
-// Enqueue one whole commit (insert + evict) on the stream.
+// Enqueue one whole commit (insert + evict) on the stream.  hint_len/hint_node (both or neither):
+// queue-wide match results on the current tree, indexed like q, that replace the commit's own match.
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
-                    int32_t batch_cap, int64_t budget, int64_t protect, kLPM_stats *stats_out, hipStream_t stream);
+                    int32_t batch_cap, int64_t budget, int64_t protect, kLPM_stats *stats_out, hipStream_t stream,
+                    const int32_t *hint_len = nullptr, const int32_t *hint_node = nullptr);
 
 // The two total orders behind Algorithm 1's picks, as built by the sorting path of the selection:
 // queue indices in oldest-first order (arrival, index) and in longest-match order (-score, [tie key,]

@@ -361,6 +361,16 @@ extern "C" int kLPM_commit(kLPM_tree *tree, const kLPM_queries *q, const int32_t
                            (hipStream_t)stream_);
 }
 
+extern "C" int kLPM_commit_matched(kLPM_tree *tree, const kLPM_queries *q, const int32_t *match_len,
+                                   const int32_t *last_node, const int32_t *batch_idx, const int32_t *n_selected,
+                                   int32_t batch_cap, kLPM_stats *stats, kLPM_stream stream_) {
+    if (!tree || !queries_ok(q) || batch_cap < 0 || !match_len || !last_node) return KLPM_EINVAL;
+    if (batch_cap > 0 && (!batch_idx || !n_selected)) return KLPM_EINVAL;
+    if (batch_cap > tree->cfg.max_batch) return KLPM_EINVAL;
+    return commit_pipeline(tree, make_qview(q), batch_idx, n_selected, batch_cap, tree->budget, tree->protect, stats,
+                           (hipStream_t)stream_, match_len, last_node);
+}
+
 extern "C" int kLPM_reserve_clock(kLPM_tree *tree, uint64_t extra_prompts) {
     if (!tree) return KLPM_EINVAL;
     tree->clock_reserve = extra_prompts;

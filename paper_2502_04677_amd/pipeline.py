@@ -42,10 +42,13 @@ class Scheduler:
         self.stats = torch.zeros(B.STATS_BYTES, dtype=torch.uint8, device=device)
         self.ws_bytes = B.kLPM_select_workspace_bytes(self.n_max)
         self.ws = B.alloc_aligned(self.ws_bytes, device)
+        self._matched_q = None  # the query set whose match (lengths and nodes) is still valid for the tree
 
-    def match(self, q: B.DeviceQueries, want_nodes: bool = False) -> torch.Tensor:
+    def match(self, q: B.DeviceQueries, want_nodes: bool = True) -> torch.Tensor:
         assert q.n <= self.n_max
-        return B.kLPM_match(self.tree, q, self.match_len, self.last_node if want_nodes else None)
+        out = B.kLPM_match(self.tree, q, self.match_len, self.last_node if want_nodes else None)
+        self._matched_q = q if want_nodes else None
+        return out
 
     def select(self, q: B.DeviceQueries, k: int, batch: int, n: Optional[int] = None, fifo: bool = False,
                score: Optional[torch.Tensor] = None, score_max: int = 0, tie_key: Optional[torch.Tensor] = None) -> None:
@@ -59,9 +62,16 @@ class Scheduler:
                       max_match=self.cfg.max_prompt_len if score is None else score_max, n_live=q.n_live,
                       tie_key=tie_key)
 
-    def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None) -> None:
-        B.kLPM_commit(self.tree, q, self.batch_idx, self.n_selected,
-                      self.cfg.max_batch if batch_cap is None else batch_cap, self.stats)
+    def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None, reuse_match: bool = True) -> None:
+        """Commits the selected batch.  When ``q`` is the very object last passed to ``match`` and no
+        commit has happened since, the admitted prompts' matches are taken from that call."""
+        cap = self.cfg.max_batch if batch_cap is None else batch_cap
+        if reuse_match and self._matched_q is q:
+            B.kLPM_commit_matched(self.tree, q, self.match_len, self.last_node, self.batch_idx, self.n_selected, cap,
+                                  self.stats)
+        else:
+            B.kLPM_commit(self.tree, q, self.batch_idx, self.n_selected, cap, self.stats)
+        self._matched_q = None
 
     def step(self, q: B.DeviceQueries, k: int, batch: int) -> None:
         self.match(q)

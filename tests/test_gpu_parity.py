@@ -48,8 +48,14 @@ def _same_tree(s, ref, big=False):
         assert a == b
 
 
+_step_no = [0]
+
+
 def _check_step(s, ref, q, hq, k, batch, phase, budget, big=False, fifo=False):
-    """One match -> select -> commit step on both sides, compared at every stage."""
+    """One match -> select -> commit step on both sides, compared at every stage.  Calls alternate
+    between the commit that takes the step's match results and the one that matches again."""
+    _step_no[0] += 1
+    reuse = bool(_step_no[0] & 1)
     s.set_phase(phase)
     m = s.match(q).cpu().numpy()
     m_ref = ref.match(hq.tokens, hq.off, hq.len)
@@ -59,7 +65,7 @@ def _check_step(s, ref, q, hq, k, batch, phase, budget, big=False, fifo=False):
     assert s.batch().tolist() == idx_ref.tolist()
     assert s.phase_value() == ph_ref
     K.kLPM_set_budget(s.tree, budget)
-    s.commit(q, batch)
+    s.commit(q, batch, reuse_match=reuse)
     st_ref = ref.commit(hq.tokens, hq.off, hq.len, idx_ref, budget)
     st = s.read_stats()
     assert st.device_error == 0
@@ -287,9 +293,29 @@ def test_commit_refusals_leave_the_tree_as_it_was():
     st = s.read_stats()
     assert st.device_error & 4 and st.inserted_tokens == 0
     _same_tree(s, ref)
+    # match results handed to the commit that are not this tree's: every entry one off, or naming a
+    # node that cannot hold it, is refused
+    idx_ref, _ = oracle.select(hq.arrival, m_ref, 2, 32, 0)
+    inner = [int(i) for i in idx_ref if 2 <= m_ref[i] < hq.len[i]]
+    zero = [int(i) for i in idx_ref if m_ref[i] == 0]
+    assert inner and zero
+    tampers = [("len+1", inner[0], +1, None), ("len-1", inner[0], -1, None), ("past the end", inner[0], 1 << 20, None),
+               ("negative", inner[0], -(1 << 20), None), ("node out of range", inner[0], 0, 4096),
+               ("node negative", inner[0], 0, -1), ("root with a match", inner[0], 0, 0),
+               ("dead node", inner[0], 0, 4000), ("no match below the root", zero[0], 0, 1)]
+    for name, qi, dlen, node in tampers:
+        _say(f"  tampered match result: {name}")
+        s = fresh(K.make_config(1 << 40, big_pool, 4096, 32, max_len))
+        ml, ln = s.match_len.clone(), s.last_node.clone()
+        ml[qi] += dlen
+        if node is not None:
+            ln[qi] = node
+        K.kLPM_commit_matched(s.tree, q, ml, ln, s.batch_idx, s.n_selected, 32, s.stats)
+        st = s.read_stats()
+        assert st.device_error == 4 and st.inserted_tokens == 0 and st.clock == w.cache.n, name
+        _same_tree(s, ref)
     # after a refusal the same tree still commits normally
     s.commit(q, 32)
-    idx_ref, _ = oracle.select(hq.arrival, m_ref, 2, 32, 0)
     ref2 = oracle.OracleTree()
     ref2.build(w.cache)
     ref2.commit(hq.tokens, hq.off, hq.len, idx_ref, 1 << 60)
