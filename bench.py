@@ -266,7 +266,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
-    ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps timed for the CPU baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=32, help="oracle steps timed for the CPU baseline, at most all the steps run on the GPU (0 = skip)")
     ap.add_argument("--deep", action="store_true",
                     help="deep-tree variant of the workload (about 50-90 tokens per tree node)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
