@@ -128,6 +128,8 @@ def bench_def3(args) -> int:
     dev = torch.device("cuda:0")
     n, rep, c_num, c_den = 2000, 4, 1, 1 << 16
     u, d = args.def3_u, 6000 - args.def3_u
+    if args.sweep:
+        return bench_def3_sweep(args, n, rep, u, d, c_num, c_den)
     gap = ((u // rep + d) + (u + d)) // 2
     p, _ = W.shuffled_queue(n, u, rep, d, gap, seed=W.generators.SEED_BASE + 100)
     p.arrival[:] = p.arrival * np.uint64(c_den)
@@ -191,6 +193,64 @@ def bench_def3(args) -> int:
         assert r.ttft.tolist() == ttft.tolist(), "GPU and oracle disagree on the TTFT of the timed run"
         out["cpu_baseline"] = {"value": r.steps / cdt, "unit": "steps/s", "cores": 1, "kind": "oracle",
                                "sample": f"the whole run ({r.steps} steps), {cdt:.2f}s"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_def3_sweep(args, n, rep, u, d, c_num, c_den) -> int:
+    """Thm. 2's setting over a sweep of the arrival gap s and of k: processing starts when everything
+    has arrived (T = s n), equal match lengths are ordered by random keys, one query per step, one
+    prompt of cache.  Every run's TTFTs are checked against the oracle's; the table lists TTFT
+    percentiles in token times per (s, k)."""
+    import torch
+
+    import oracle
+    import paper_2502_04677_amd as K
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    cap, budget, seed = 2048, u + d, 99
+    cfg = K.size_config(0, 0, budget, 1, u + d, extra_prompts=2)
+    rows, gpu_s, cpu_s, steps = [], 0.0, 0.0, 0
+    for s_gap in (u // 6, u // 2, 5 * u // 6, 7 * u // 6, 5 * u // 3):
+        p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=W.generators.SEED_BASE + 100)
+        p.arrival[:] = p.arrival * np.uint64(c_den)
+        q = K.DeviceQueries.from_host(p, dev)
+        t_start = s_gap * n * c_den
+        for k in (1, 2, rep, 2 * rep, K.KLPM_K_INFINITY):
+            sched = K.Scheduler(cfg, None, cap, dev)
+            run = K.TimedRun(sched, q, cap, p.arrival, c_num=c_num, c_den=c_den, t_start=t_start, tie_seed=seed)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                run.step(k, 1)
+            torch.cuda.synchronize()
+            gpu_s += time.perf_counter() - t0
+            assert int(run.queue.n.item()) == 0 and int(run.dev_error.item()) == 0
+            ttft = run.ttft[:n].cpu().numpy()
+            t0 = time.perf_counter()
+            r = oracle.simulate_timed(p, k, 1, budget, c_num=c_num, c_den=c_den, queue_cap=cap, t_start=t_start,
+                                      tie_seed=seed)
+            cpu_s += time.perf_counter() - t0
+            assert r.ttft.tolist() == ttft.tolist(), f"GPU and oracle disagree at s={s_gap} k={k}"
+            steps += n
+            t = np.sort(ttft) / c_den
+            rows.append({"s": s_gap, "k": "inf" if k == K.KLPM_K_INFINITY else k,
+                         **{name: round(float(t[int(np.ceil(x * n)) - 1])) for name, x in
+                            (("p50", 0.5), ("p95", 0.95), ("p99", 0.99), ("max", 1.0))}})
+            log(f"s={s_gap} k={rows[-1]['k']}: {rows[-1]}")
+    out = {
+        "metric": "scheduling steps/sec (match + tie keys + select + commit + timed queue advance, one query per step)",
+        "value": steps / gpu_s, "unit": "steps/s", "n_gpus": 1, "steps": steps, "warmup": 0,
+        "ms_per_step": gpu_s / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"def3-n{n}-rep{rep}-u{u}-d{d}-gap-sweep", "batch": 1, "kv_budget_tokens": budget,
+                   "c_attn": c_num / c_den, "queue_cap": cap, "start": "after the last arrival", "ties": "random"},
+        "sweep_ttft_token_times": rows,
+        "roofline": None,  # launch-latency bound at this size; see the large configuration
+        "cpu_baseline": {"value": steps / cpu_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
+                         "sample": f"every run of the sweep ({steps} steps), {cpu_s:.1f}s"},
+    }
     print(json.dumps(out), flush=True)
     return 0
 
@@ -276,6 +336,8 @@ def main() -> int:
     ap.add_argument("--random-ties", action="store_true", help="break score ties uniformly at random (Philox keys)")
     ap.add_argument("--dynamic", action="store_true",
                     help="in-batch rescoring: scores follow the prompts picked earlier in the same batch")
+    ap.add_argument("--sweep", action="store_true",
+                    help="with --workload def3: sweep the arrival gap and k in the setting of Thm. 2 (late start, random ties)")
     ap.add_argument("--rematch", action="store_true",
                     help="let the commit match the admitted prompts again instead of taking the step's match results")
     ap.add_argument("--graph", action="store_true",

@@ -371,7 +371,8 @@ class TimedResult:
 
 
 def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_den: int = 1, t_start: int = 0,
-                   queue_cap: Optional[int] = None, tree: Optional[OracleTree] = None) -> TimedResult:
+                   queue_cap: Optional[int] = None, tree: Optional[OracleTree] = None,
+                   tie_seed: Optional[int] = None) -> TimedResult:
     """Def. 2's timeline driven through match -> select -> commit, with queries that become
     visible to the scheduler only once they have arrived (Def. 1: arrival time t_i).
 
@@ -382,7 +383,8 @@ def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_d
     before it has arrived: when nobody is waiting the clock jumps to the next arrival
     (the max(R, t) of Def. 2).  With batch = 1 and budget = one prompt this is Def. 2 itself.
     ``queue_cap`` bounds the waiting queue; arrivals that find it full stay outside, in arrival
-    order, keeping their arrival time.
+    order, keeping their arrival time.  With ``tie_seed`` equal match lengths are ordered by the
+    uniformly random keys of ``tie_keys`` (drawn per query id and step; footnote of Sec. 4.2).
     """
     n = prompts.n
     arr = np.asarray(prompts.arrival, dtype=np.uint64)
@@ -406,7 +408,8 @@ def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_d
         w = np.array(waiting, dtype=np.int64)
         off, ln = prompts.off[w], prompts.len[w]
         m = tree.match(prompts.tokens, off, ln)
-        idx, phase = select(arr[w], m, k, batch, phase)
+        tk = None if tie_seed is None else tie_keys(tie_seed, res.steps, w)
+        idx, phase = select(arr[w], m, k, batch, phase, tie_key=tk)
         tree.commit(prompts.tokens, off, ln, idx, budget)
         cost = 0
         for i in idx.tolist():

@@ -171,7 +171,9 @@ class TimedRun:
     """
 
     def __init__(self, sched: Scheduler, all_q: B.DeviceQueries, cap: int, arrival: np.ndarray, c_num: int = 0,
-                 c_den: int = 1, t_start: int = 0):
+                 c_den: int = 1, t_start: int = 0, tie_seed: Optional[int] = None):
+        """With ``tie_seed`` equal match lengths are ordered by uniformly random keys redrawn every
+        step (per query id and step number) instead of by arrival."""
         dev = sched.device
         self.s = sched
         self.all_q = all_q
@@ -182,6 +184,9 @@ class TimedRun:
         self.ttft = torch.full((max(all_q.n, 1),), -1, dtype=torch.int64, device=dev)
         self.matched = torch.zeros(1, dtype=torch.int64, device=dev)
         self.dev_error = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.tie_seed = tie_seed
+        self.tie = torch.zeros(max(self.cap, 1), dtype=torch.int32, device=dev) if tie_seed is not None else None
+        self.steps_done = 0
         sched.n_selected.zero_()
         self._advance(0)  # initial fill: everything that has arrived by t_start, or the first arrival
 
@@ -208,6 +213,11 @@ class TimedRun:
         s = self.s
         q = self.view()
         s.match(q)
-        s.select(q, k, batch, fifo=True)  # arrivals join in time order, removal is stable
+        if self.tie is None:
+            s.select(q, k, batch, fifo=True)  # arrivals join in time order, removal is stable
+        else:
+            B.kLPM_tie_keys(self.tie_seed, self.steps_done, self.queue.id, self.cap, self.tie, n_live=self.queue.n)
+            s.select(q, k, batch, tie_key=self.tie)
         s.commit(q, batch)
         self._advance(batch)
+        self.steps_done += 1

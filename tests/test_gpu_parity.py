@@ -515,15 +515,16 @@ def test_match_with_device_side_queue_length():
 
 
 # ----------------------------------------------------------------------------- Def. 2 timeline with timed arrivals
-def _run_timed(p, k, batch, budget, c_num=0, c_den=1, t_start=0, cap=None, check_every=1):
+def _run_timed(p, k, batch, budget, c_num=0, c_den=1, t_start=0, cap=None, check_every=1, tie_seed=None):
     """The device-resident timed run against the oracle's event loop: queue contents, match lengths
     and batch at the checked steps; TTFT of every query, final clock and step count at the end."""
     cap_o = p.n if cap is None else cap
-    r = oracle.simulate_timed(p, k, batch, budget, c_num=c_num, c_den=c_den, t_start=t_start, queue_cap=cap_o)
+    r = oracle.simulate_timed(p, k, batch, budget, c_num=c_num, c_den=c_den, t_start=t_start, queue_cap=cap_o,
+                              tie_seed=tie_seed)
     q = K.DeviceQueries.from_host(p)
     cfg = K.size_config(0, 0, budget, batch, int(p.len.max()), extra_prompts=2 * batch)
     s = K.Scheduler(cfg, None, cap_o)
-    run = K.TimedRun(s, q, cap_o, p.arrival, c_num=c_num, c_den=c_den, t_start=t_start)
+    run = K.TimedRun(s, q, cap_o, p.arrival, c_num=c_num, c_den=c_den, t_start=t_start, tie_seed=tie_seed)
     for step in range(r.steps):
         check = check_every and (step % check_every == 0 or step == r.steps - 1)
         if check:
@@ -584,6 +585,37 @@ def test_timed_shuffled_queue_paper_shape(u, d):
         # more reuse, lower median: LPM <= k-LPM <= FCFS at P50 (Sec. 4.2 and the discussion of the
         # table on varying the prefix-length ratio)
         assert res[K_INF][0] <= res[rep][0] <= res[1][0]
+
+
+def test_timed_runs_with_random_ties():
+    """The timed run with the uniformly random tie-break that the theory assumes for LPM (footnote of
+    Sec. 4.2): keys are redrawn per query id and step on both sides."""
+    for seed, (n, u, rep, d, s_gap) in enumerate([(24, 6, 3, 4, 0), (40, 9, 4, 3, 2), (64, 70, 2, 90, 40)]):
+        p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=seed + 20)
+        for k, batch, t_start in ((K_INF, 1, 0), (rep, 1, s_gap * n), (2, 3, 0), (1, 2, 5)):
+            _say(f"timed random ties: n={n} k={k} B={batch} T={t_start}")
+            _run_timed(p, k, batch, batch * (u + d), t_start=t_start, tie_seed=1000 + seed)
+    p, _ = W.shuffled_queue(96, 40, 4, 25, 30, seed=8)
+    _run_timed(p, K_INF, 4, 4 * 65, c_num=1, c_den=128, cap=16, tie_seed=5)
+
+
+def test_timed_gap_sweep_separates_the_policies_as_the_theory_says():
+    """Thm. 2's setting at the shape of the paper's table (n = 2000, 4 queries per shared prefix,
+    u = d = 3000): everything has arrived when processing starts, LPM breaks ties at random.  For an
+    arrival gap 0 < s < u, k-LPM with k = the replication has the lowest maximum TTFT of the three
+    policies (Corollary 1) while the median orders them by reuse."""
+    n, rep, u, d, c_num, c_den = 2000, 4, 3000, 3000, 1, 1 << 16
+    for s_gap in (500, 2500):
+        p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=12)
+        p.arrival[:] = p.arrival * np.uint64(c_den)
+        worst, median = {}, {}
+        for k in (1, rep, K_INF):
+            _say(f"timed gap sweep: s={s_gap} k={k}")
+            r = _run_timed(p, k, 1, u + d, c_num=c_num, c_den=c_den, t_start=s_gap * n * c_den, cap=2048,
+                           check_every=700, tie_seed=99)
+            worst[k], median[k] = int(r.ttft.max()), oracle.percentile_nearest_rank(r.ttft, 0.5)
+        assert worst[rep] < worst[K_INF] and worst[rep] < worst[1], (s_gap, worst)
+        assert median[K_INF] <= median[rep] <= median[1], (s_gap, median)
 
 
 # ----------------------------------------------------------------------------- score and tie variants of Algorithm 1

@@ -386,6 +386,43 @@ def test_timed_run_after_all_arrived_meets_closed_forms(seed, n, u, rep, d, s):
     assert r.ttft.max() <= T + n * (u / rep + d - s / rep) + 1e-9
 
 
+@pytest.mark.parametrize("s", [400, 1500, 2600])
+def test_timed_run_meets_the_separation_theorem_at_the_paper_shape(s):
+    """Thm. 2 with c_attn = 0 on a Def. 3 queue at the shape of the paper's table (n = 2000, k = 4,
+    u = d = 3000), processing from T = s n on, LPM with random ties: the k-LPM bound holds exactly,
+    the LPM and FCFS lower bounds hold up to their (1 - eps), and for 0 < s < u k-LPM has the lowest
+    maximum TTFT (Corollary 1)."""
+    n, rep, u, d = 2000, 4, 3000, 3000
+    p, _ = W.shuffled_queue(n, u, rep, d, s, seed=21)
+    T = s * n
+    worst = {}
+    for k in (1, rep, K_INF):
+        r = oracle.simulate_timed(p, k, batch=1, budget=u + d, t_start=T, tie_seed=4)
+        worst[k] = int(r.ttft.max())
+    assert worst[rep] <= T + n * (u // rep + d) - n * s // rep
+    assert worst[K_INF] >= 0.97 * (T + n * (u // rep + d))
+    assert worst[1] >= 0.97 * (T + n * (u + d - s))
+    assert worst[rep] < worst[K_INF] and worst[rep] < worst[1]
+
+
+def test_timed_random_ties_follow_the_keys():
+    """With a tie seed, a step's longest-match pick among equal match lengths is the query with the
+    smallest key of that step, whatever its arrival; without one it is the earliest arrival."""
+    n, u, rep, d = 12, 5, 3, 4
+    p, _ = W.shuffled_queue(n, u, rep, d, 1, seed=3)
+    r = oracle.simulate_timed(p, K_INF, batch=1, budget=u + d, t_start=n, tie_seed=9)  # everybody waits from the start
+    r0 = oracle.simulate_timed(p, K_INF, batch=1, budget=u + d, t_start=n)
+    assert sorted(r.order.tolist()) == list(range(n)) and r.clock == r0.clock  # same reuse, other order
+    for step in range(n):
+        w, m = r.waiting_ids[step], r.match_lens[step]
+        best = np.flatnonzero(m == m.max())
+        keys = oracle.tie_keys(9, step, w)[best]
+        assert int(r.batches[step][0]) == int(w[best[np.argmin(keys)]])
+        w0, m0 = r0.waiting_ids[step], r0.match_lens[step]
+        best0 = np.flatnonzero(m0 == m0.max())
+        assert int(r0.batches[step][0]) == int(w0[best0[np.argmin(p.arrival[w0[best0]])]])
+
+
 def test_timed_bounded_queue_keeps_everyone_and_fcfs_order():
     p, _ = W.shuffled_queue(24, 6, 3, 4, 1, seed=9)
     full = oracle.simulate_timed(p, 1, batch=2, budget=40)
