@@ -21,7 +21,7 @@ import ctypes as C
 import math
 import os
 import subprocess
-from dataclasses import dataclass
+from dataclasses import dataclass, field
 from typing import List, Optional, Tuple
 
 import numpy as np
@@ -260,6 +260,69 @@ def tie_keys(seed: int, step: int, ids) -> np.ndarray:
     return c0.astype(np.uint32)
 
 
+ADAPT_TAG = 0x6B4C504D  # third counter word of the draws below ("kLPM"), keeps them apart from the tie keys
+
+
+class AdaptiveK:
+    """k chosen per window of scheduling steps by an epsilon-greedy bandit over a list of k values.
+
+    Sec. 4.2 says that k can be set by back-testing or by an adaptive multi-armed bandit and leaves
+    the method open; this is the textbook epsilon-greedy rule with these choices: a pull lasts
+    ``window`` scheduling steps; its cost is the largest TTFT among the queries admitted during
+    those steps (the tail is what k-LPM is about, Thm. 2); a window that admitted nobody is not a
+    pull and leaves everything as it was.  After a pull: an arm never pulled yet goes next (lowest
+    index first); otherwise words (w0, w1, ., .) of Philox-4x32-10 at counter (pulls low, pulls high,
+    ADAPT_TAG, 0) under key (seed low, seed high) decide - explore arm w1 mod A if w0 < ``explore``
+    (probability explore / 2^32), else the arm with the smallest mean cost, compared as exact
+    fractions, the lower index on equality.
+    """
+
+    def __init__(self, arms, window: int, explore: int, seed: int):
+        assert len(arms) >= 1 and window >= 1 and 0 <= explore <= 1 << 32
+        self.arms = [int(a) for a in arms]
+        self.window, self.explore, self.seed = int(window), int(explore), int(seed)
+        self.count = [0] * len(self.arms)
+        self.cost = [0] * len(self.arms)
+        self.arm, self.steps, self.pulls = 0, 0, 0
+        self.cur_max, self.cur_n = 0, 0
+
+    def k(self) -> int:
+        return self.arms[self.arm]
+
+    def observe(self, ttfts) -> None:
+        """Called once per scheduling step with the TTFT of every query that step admitted."""
+        for t in ttfts:
+            self.cur_max = max(self.cur_max, int(t))
+            self.cur_n += 1
+        self.steps += 1
+        if self.steps < self.window:
+            return
+        self.steps = 0
+        if self.cur_n > 0:
+            self.count[self.arm] += 1
+            self.cost[self.arm] += self.cur_max
+            self.pulls += 1
+            self.arm = self._next_arm()
+        self.cur_max, self.cur_n = 0, 0
+
+    def _next_arm(self) -> int:
+        from fractions import Fraction
+
+        A = len(self.arms)
+        for a in range(A):
+            if self.count[a] == 0:
+                return a
+        w = philox4x32_10((self.pulls & 0xFFFFFFFF, (self.pulls >> 32) & 0xFFFFFFFF, ADAPT_TAG, 0),
+                          (self.seed & 0xFFFFFFFF, (self.seed >> 32) & 0xFFFFFFFF))
+        if w[0] < self.explore:
+            return w[1] % A
+        best = 0
+        for a in range(1, A):
+            if Fraction(self.cost[a], self.count[a]) < Fraction(self.cost[best], self.count[best]):
+                best = a
+        return best
+
+
 def def2_completion(prompts, order, c_attn: float = 0.0, t_start: float = 0.0) -> np.ndarray:
     """Completion time R(.) of every query (indexed by query, not by position) under Def. 2."""
     L = _load()
@@ -368,11 +431,12 @@ class TimedResult:
     waiting_ids: List[np.ndarray]  # query ids of the waiting queue, per step
     clock: int  # time at which the last batch finished
     steps: int
+    ks: List[int] = field(default_factory=list)  # the k each step ran with
 
 
 def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_den: int = 1, t_start: int = 0,
                    queue_cap: Optional[int] = None, tree: Optional[OracleTree] = None,
-                   tie_seed: Optional[int] = None) -> TimedResult:
+                   tie_seed: Optional[int] = None, adaptive: Optional[AdaptiveK] = None) -> TimedResult:
     """Def. 2's timeline driven through match -> select -> commit, with queries that become
     visible to the scheduler only once they have arrived (Def. 1: arrival time t_i).
 
@@ -385,6 +449,8 @@ def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_d
     ``queue_cap`` bounds the waiting queue; arrivals that find it full stay outside, in arrival
     order, keeping their arrival time.  With ``tie_seed`` equal match lengths are ordered by the
     uniformly random keys of ``tie_keys`` (drawn per query id and step; footnote of Sec. 4.2).
+    With ``adaptive`` each step runs with the k that object holds (``k`` is ignored) and reports the
+    TTFT of the queries it admitted to it.
     """
     n = prompts.n
     arr = np.asarray(prompts.arrival, dtype=np.uint64)
@@ -409,7 +475,8 @@ def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_d
         off, ln = prompts.off[w], prompts.len[w]
         m = tree.match(prompts.tokens, off, ln)
         tk = None if tie_seed is None else tie_keys(tie_seed, res.steps, w)
-        idx, phase = select(arr[w], m, k, batch, phase, tie_key=tk)
+        k_now = k if adaptive is None else adaptive.k()
+        idx, phase = select(arr[w], m, k_now, batch, phase, tie_key=tk)
         tree.commit(prompts.tokens, off, ln, idx, budget)
         cost = 0
         for i in idx.tolist():
@@ -418,6 +485,9 @@ def simulate_timed(prompts, k: int, batch: int, budget: int, c_num: int = 0, c_d
         clock += cost
         gids = w[idx]
         ttft[gids] = clock - arr[gids].astype(np.int64)
+        res.ks.append(k_now)
+        if adaptive is not None:
+            adaptive.observe(ttft[gids].tolist())
         order.extend(int(g) for g in gids)
         res.batches.append(gids.astype(np.int32))
         res.match_lens.append(m)

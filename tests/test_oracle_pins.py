@@ -1,6 +1,7 @@
 """CPU-only pins for the oracle: each test checks it against something other than itself
 (the paper's printed example, closed forms from the proof of Thm. 2, brute-force models in
 plain Python, textbook special cases)."""
+import math
 import os
 
 import numpy as np
@@ -664,3 +665,128 @@ def test_token_budget_cut_and_phase():
                 part, ph_part = oracle.select(arrival, mm, k, kept, phase)
                 assert part.tolist() == full[:kept].tolist()
                 assert oracle.phase_after_cut(ph_full, 12, kept, k) == ph_part
+
+
+# ----------------------------------------------------------------------------- adaptive k (epsilon-greedy over a list of k values)
+def _feed(ad, costs, window=None):
+    """One pull per entry of `costs`: `window` steps, the cost carried by one admitted query."""
+    arms = []
+    for c in costs:
+        arms.append(ad.arm)
+        for i in range(ad.window):
+            ad.observe([c] if i == ad.window // 2 else [])
+    return arms
+
+
+def test_adaptive_k_starts_round_robin_and_holds_an_arm_for_a_window():
+    ad = oracle.AdaptiveK([1, 4, K_INF], window=5, explore=0, seed=1)
+    ks = []
+    for step in range(15):
+        ks.append(ad.k())
+        ad.observe([100 + step])
+    assert ks == [1] * 5 + [4] * 5 + [K_INF] * 5
+    assert ad.count == [1, 1, 1] and ad.cost == [104, 109, 114]  # the largest TTFT of each window
+
+
+def test_adaptive_k_greedy_is_the_exact_argmin_of_the_mean_cost():
+    from fractions import Fraction
+
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        A = int(rng.integers(2, 7))
+        ad = oracle.AdaptiveK(list(range(1, A + 1)), window=int(rng.integers(1, 4)), explore=0, seed=trial)
+        hist = [[] for _ in range(A)]
+        for pull in range(60):
+            arm = ad.arm
+            if pull >= A:  # after the first round: what a table of per-arm cost lists says
+                means = [Fraction(sum(h), len(h)) for h in hist]
+                assert arm == min(range(A), key=lambda a: (means[a], a))
+            c = int(rng.integers(0, 6)) * (1 << int(rng.integers(0, 45)))
+            _feed(ad, [c])
+            hist[arm].append(c)
+    # equal means with different counts: 6/2 against 3/1 -> the lower index
+    ad = oracle.AdaptiveK([7, 9], window=1, explore=0, seed=0)
+    for c in (2, 3):  # arm 0: 2, arm 1: 3
+        ad.observe([c])
+    assert ad.arm == 0
+    ad.observe([4])  # arm 0: (2 + 4) / 2 = 3 = arm 1
+    assert ad.count == [2, 1] and ad.arm == 0
+    ad.observe([10**15])  # arm 0 now far worse
+    assert ad.arm == 1
+    # means that differ by less than one part in 2^64: exact fractions still tell them apart
+    ad = oracle.AdaptiveK([1, 2], window=1, explore=0, seed=0)
+    big = (1 << 62) + 1
+    ad.observe([big]); ad.observe([big - 1])
+    assert ad.arm == 1
+    ad.observe([big - 1]); assert ad.arm == 1
+    ad.observe([big + 2]); assert ad.arm == 0  # arm 1: (3 big) / 3 = big, arm 0: big
+
+
+def test_adaptive_k_windows_without_admissions_are_not_pulls():
+    ad = oracle.AdaptiveK([1, 2, 3], window=2, explore=0, seed=3)
+    for _ in range(6):
+        ad.observe([])
+    assert ad.arm == 0 and ad.pulls == 0 and ad.count == [0, 0, 0]
+    ad.observe([]); ad.observe([8])
+    assert ad.arm == 1 and ad.pulls == 1 and ad.count == [1, 0, 0] and ad.cost == [8, 0, 0]
+
+
+def test_adaptive_k_exploration_rate_and_uniformity():
+    A, n = 5, 20000
+    # always explore: every arm equally often (chi-square, 4 degrees of freedom, 0.999 quantile 18.5)
+    ad = oracle.AdaptiveK(list(range(1, A + 1)), window=1, explore=1 << 32, seed=11)
+    arms = np.array(_feed(ad, [1] * n))[A:]
+    cnt = np.bincount(arms, minlength=A)
+    assert ((cnt - arms.size / A) ** 2 / (arms.size / A)).sum() < 18.5
+    # pairs of consecutive draws are uniform too (no arm follows itself more than another)
+    pair = np.bincount(arms[:-1] * A + arms[1:], minlength=A * A)
+    assert ((pair - (arms.size - 1) / A**2) ** 2 / ((arms.size - 1) / A**2)).sum() < 52.6  # 24 dof, 0.999
+    # arm 0 is the cheapest by far, so any other arm is an exploration: rate eps (A-1)/A within 4 sigma
+    for eps_bits in (2, 4):
+        ad = oracle.AdaptiveK(list(range(1, A + 1)), window=1, explore=(1 << 32) >> eps_bits, seed=12 + eps_bits)
+        got = []
+        for pull in range(n):
+            got.append(ad.arm)
+            ad.observe([1 if ad.arm == 0 else 1000])
+        other = sum(1 for a in got[A:] if a != 0)
+        pr = (A - 1) / A / (1 << eps_bits)
+        m = n - A
+        assert abs(other - m * pr) < 4 * math.sqrt(m * pr * (1 - pr))
+    # never explore: after the first round only the cheapest arm
+    ad = oracle.AdaptiveK(list(range(1, A + 1)), window=1, explore=0, seed=13)
+    got = []
+    for pull in range(200):
+        got.append(ad.arm)
+        ad.observe([1 if ad.arm == 2 else 50])
+    assert got[:A] == list(range(A)) and set(got[A:]) == {2}
+
+
+def test_timed_run_with_adaptive_k_uses_the_arm_of_each_window():
+    n, u, rep, d = 48, 9, 4, 5
+    p, _ = W.shuffled_queue(n, u, rep, d, 3, seed=6)
+    # one arm is the fixed-k run; a window longer than the run never leaves the first arm
+    for k in (1, rep, K_INF):
+        fixed = oracle.simulate_timed(p, k, batch=2, budget=3 * (u + d))
+        one = oracle.simulate_timed(p, 0, batch=2, budget=3 * (u + d), adaptive=oracle.AdaptiveK([k], 3, 1 << 31, 1))
+        long_w = oracle.simulate_timed(p, 0, batch=2, budget=3 * (u + d),
+                                       adaptive=oracle.AdaptiveK([k, 2, 7], 10**6, 1 << 31, 1))
+        assert fixed.ttft.tolist() == one.ttft.tolist() == long_w.ttft.tolist()
+        assert set(one.ks) == {k} and set(long_w.ks) == {k}
+    # several arms: each step's batch is Algorithm 1 under that step's k (checked with the literal
+    # loop on the step's own queue), k changes only at window boundaries, and the counters hold
+    # the largest TTFT of every window
+    ad = oracle.AdaptiveK([1, rep, K_INF, 2], window=3, explore=1 << 30, seed=2)
+    r = oracle.simulate_timed(p, 0, batch=2, budget=3 * (u + d), t_start=40, adaptive=ad)
+    phase = 0
+    for step in range(r.steps):
+        w, m = r.waiting_ids[step], r.match_lens[step]
+        idx, phase = select_literal(p.arrival[w], m, r.ks[step], 2, phase)
+        assert w[idx].tolist() == r.batches[step].tolist()
+        if step % 3:
+            assert r.ks[step] == r.ks[step - 1]
+    assert len(set(r.ks)) > 1 and sum(ad.count) == r.steps // 3
+    by_arm = {}
+    for wdw in range(r.steps // 3):
+        worst = max(int(r.ttft[g]) for s3 in range(3 * wdw, 3 * wdw + 3) for g in r.batches[s3])
+        by_arm[r.ks[3 * wdw]] = by_arm.get(r.ks[3 * wdw], 0) + worst
+    assert [by_arm.get(a, 0) for a in ad.arms] == ad.cost
