@@ -217,20 +217,26 @@ def bench_def3_sweep(args, n, rep, u, d, c_num, c_den) -> int:
         p.arrival[:] = p.arrival * np.uint64(c_den)
         q = K.DeviceQueries.from_host(p, dev)
         t_start = s_gap * n * c_den
-        for k in (1, 2, rep, 2 * rep, K.KLPM_K_INFINITY):
+        arms = [1, 2, rep, 2 * rep, K.KLPM_K_INFINITY]
+        # the fixed values of k, then k chosen per window of 20 steps by the device-side epsilon-greedy
+        # rule over the same values (a quarter of the pulls exploring)
+        for k in arms + ["adaptive"]:
             sched = K.Scheduler(cfg, None, cap, dev)
             run = K.TimedRun(sched, q, cap, p.arrival, c_num=c_num, c_den=c_den, t_start=t_start, tie_seed=seed)
+            ad = K.AdaptiveK(arms, 20, 1 << 30, seed) if k == "adaptive" else None
+            k_host = 0 if ad is not None else k
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(n):
-                run.step(k, 1)
+                run.step(k_host, 1, adaptive=ad)
             torch.cuda.synchronize()
             gpu_s += time.perf_counter() - t0
             assert int(run.queue.n.item()) == 0 and int(run.dev_error.item()) == 0
             ttft = run.ttft[:n].cpu().numpy()
+            ad_ref = oracle.AdaptiveK(arms, 20, 1 << 30, seed) if ad is not None else None
             t0 = time.perf_counter()
-            r = oracle.simulate_timed(p, k, 1, budget, c_num=c_num, c_den=c_den, queue_cap=cap, t_start=t_start,
-                                      tie_seed=seed)
+            r = oracle.simulate_timed(p, k_host, 1, budget, c_num=c_num, c_den=c_den, queue_cap=cap, t_start=t_start,
+                                      tie_seed=seed, adaptive=ad_ref)
             cpu_s += time.perf_counter() - t0
             assert r.ttft.tolist() == ttft.tolist(), f"GPU and oracle disagree at s={s_gap} k={k}"
             steps += n
@@ -238,6 +244,10 @@ def bench_def3_sweep(args, n, rep, u, d, c_num, c_den) -> int:
             rows.append({"s": s_gap, "k": "inf" if k == K.KLPM_K_INFINITY else k,
                          **{name: round(float(t[int(np.ceil(x * n)) - 1])) for name, x in
                             (("p50", 0.5), ("p95", 0.95), ("p99", 0.99), ("max", 1.0))}})
+            if ad is not None:
+                st = ad.read()
+                assert list(st.count)[:len(arms)] == ad_ref.count and list(st.cost)[:len(arms)] == ad_ref.cost
+                rows[-1]["pulls_per_arm"] = ad_ref.count
             log(f"s={s_gap} k={rows[-1]['k']}: {rows[-1]}")
     out = {
         "metric": "scheduling steps/sec (match + tie keys + select + commit + timed queue advance, one query per step)",

@@ -134,6 +134,9 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  *                       the sorting path, whatever `flags` says
  *   n_live              DEVICE [1] or NULL: as in kLPM_queries, the queue holds min(n, max(0, *n_live))
  *                       entries; n then only sizes the launches and the workspace
+ *   k, k_dev            k_dev NULL: k is used.  Otherwise DEVICE [1]: the k that memory holds when
+ *                       the selection runs (for a k chosen on the device, see kLPM_adapt_*), and the
+ *                       argument k is ignored
  *   flags               0 or KLPM_SELECT_FIFO
  *   max_match           with KLPM_SELECT_FIFO: an upper bound of the match_len values (the longest
  *                       prompt accepted will do); 0 = unknown.  A smaller bound means fewer passes; a
@@ -146,7 +149,7 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
  */
 int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
-                const int32_t *n_live, uint32_t k,
+                const int32_t *n_live, uint32_t k, const uint32_t *k_dev,
                 int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                 void *workspace, size_t workspace_bytes, kLPM_stream stream);
 
@@ -163,12 +166,12 @@ int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_
  *   last_node   DEVICE [q->n] in: the last_node output of the same kLPM_match call
  *   dyn_match   DEVICE [q->n] out: for a picked query its score when it was picked (its overlap
  *               credit: it costs len - dyn_match), for the others their final score
- *   phase_inout, batch_idx, n_selected   as in kLPM_select
+ *   k, k_dev, phase_inout, batch_idx, n_selected   as in kLPM_select
  *   workspace   DEVICE, 256-byte aligned, >= kLPM_select_dynamic_workspace_bytes(q->n)
  */
 int kLPM_select_dynamic_workspace_bytes(int32_t n, size_t *out_bytes);
 int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node, uint32_t k,
-                        int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
+                        const uint32_t *k_dev, int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
                         int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream);
 
 /*
@@ -233,11 +236,11 @@ int kLPM_set_protect(kLPM_tree *tree, int64_t recent_prompts);
  * tokens, sum of len - match_len, fit `token_budget`; the first pick always stays.  *n_selected is
  * lowered accordingly and *phase_inout is rewound by the picks handed back, so that the k-cycle
  * continues as if only the kept picks had been made.  Call between kLPM_select and kLPM_commit with
- * the k that the selection used.  All pointers DEVICE.
+ * the k (and k_dev) that the selection used.  All pointers DEVICE.
  */
 int kLPM_batch_token_budget(const kLPM_queries *q, const int32_t *match_len, const int32_t *batch_idx,
                             int32_t *n_selected, int32_t batch_cap, int64_t token_budget, uint32_t k,
-                            uint32_t *phase_inout, kLPM_stream stream);
+                            const uint32_t *k_dev, uint32_t *phase_inout, kLPM_stream stream);
 
 /*
  * Cache slots of a batch's matched prefixes (what the prefix cache returns for attention to read:
@@ -338,6 +341,52 @@ int kLPM_queue_advance_timed(const kLPM_queue *cur, const kLPM_queue *next, cons
                              const int32_t *match_len, const int32_t *batch_idx, const int32_t *n_selected,
                              int32_t batch_cap, const kLPM_arrivals *pending, int64_t *ttft, int64_t *matched_accum,
                              uint32_t *dev_error, kLPM_stream stream);
+
+/*
+ * Adaptive k.  Sec. 4.2 says that k can be set by back-testing or by an adaptive multi-armed bandit
+ * and gives no method; this is the textbook epsilon-greedy rule over a caller's list of k values,
+ * with its state in device memory so that a scheduling loop never reads anything back:
+ *   - a pull lasts `window` scheduling steps (calls of kLPM_adapt_observe);
+ *   - its cost is the largest TTFT among the queries admitted during those steps; a window that
+ *     admitted nobody is not a pull and changes nothing;
+ *   - after a pull, an arm never pulled goes next (lowest index first); otherwise words w0, w1 of
+ *     Philox-4x32-10 at counter (pulls low, pulls high, 0x6B4C504D, 0) under key (seed low, seed high)
+ *     decide: arm w1 mod n_arms if w0 < explore (probability explore / 2^32), else the arm with the
+ *     smallest mean cost (compared exactly; the lower index on equality).
+ *   state    DEVICE, 8-byte aligned, >= kLPM_adapt_state_bytes; owned by the caller, initialised
+ *            by kLPM_adapt_init (enqueued on the stream)
+ *   k_dev    (kLPM_adapt_k) DEVICE pointer into the state: the current k, to be passed as the
+ *            k_dev argument of kLPM_select / kLPM_select_dynamic / kLPM_batch_token_budget
+ * kLPM_adapt_observe is called once per scheduling step, after the queue advance that wrote the
+ * TTFTs: `served` is the queue the batch was selected from (still intact: the advance writes the
+ * other buffer set), batch_idx / n_selected the selection, ttft DEVICE [n_ttft] indexed by query id.
+ * An entry that cannot be read (index or id out of range, TTFT < 0) is left out and sets
+ * KLPM_DEV_BAD_INPUT in the state.  The sum of an arm's costs must fit 64 bits.
+ * kLPM_adapt_read synchronises the stream and copies the counters to HOST memory.
+ */
+#define KLPM_ADAPT_MAX_ARMS 16
+typedef struct kLPM_adapt_config {
+    uint32_t arms[KLPM_ADAPT_MAX_ARMS]; /* the k values to choose among (0 or KLPM_K_INFINITY = LPM) */
+    int32_t n_arms;                     /* 1 .. KLPM_ADAPT_MAX_ARMS */
+    int32_t window;                     /* scheduling steps per pull, >= 1 */
+    uint64_t explore;                   /* exploration probability times 2^32, 0 .. 2^32 */
+    uint64_t seed;
+} kLPM_adapt_config;
+typedef struct kLPM_adapt_stats {
+    uint64_t count[KLPM_ADAPT_MAX_ARMS]; /* pulls per arm */
+    uint64_t cost[KLPM_ADAPT_MAX_ARMS];  /* summed cost per arm */
+    uint64_t pulls;
+    int32_t arm;                         /* current arm */
+    uint32_t k;                          /* its k */
+    int32_t steps_in_window;
+    uint32_t device_error;
+} kLPM_adapt_stats;
+int kLPM_adapt_state_bytes(size_t *out_bytes);
+int kLPM_adapt_init(void *state, size_t state_bytes, const kLPM_adapt_config *cfg, kLPM_stream stream);
+int kLPM_adapt_k(void *state, const uint32_t **k_dev);
+int kLPM_adapt_observe(void *state, const kLPM_queue *served, const int32_t *batch_idx, const int32_t *n_selected,
+                       int32_t batch_cap, const int64_t *ttft, int32_t n_ttft, kLPM_stream stream);
+int kLPM_adapt_read(void *state, kLPM_adapt_stats *host_out, kLPM_stream stream);
 
 /*
  * Measurement helper: one plain streaming read over `bytes` of DEVICE memory at `src` (16-byte

@@ -378,14 +378,16 @@ class StreamResult:
     snapshots: List[Optional[bytes]]
 
 
-def simulate_stream(stream, snapshot_every: int = 0, tree: Optional[OracleTree] = None) -> StreamResult:
+def simulate_stream(stream, snapshot_every: int = 0, tree: Optional[OracleTree] = None,
+                    adaptive: Optional[AdaptiveK] = None) -> StreamResult:
     """Online simulation: each step, enqueue that step's arrivals at the current simulated
     time, score the whole waiting queue, pick a k-LPM batch (phase persists across steps),
     commit it under the KV budget, then advance time by the batch's prefill cost.
 
     Prefill cost of a query is its uncached token count |x| - m (Def. 2 with c_attn = 0,
     m measured at step start); a batch finishes together (Sec. 2.1); time advances by
-    max(1, total cost); TTFT = finish time - enqueue time.
+    max(1, total cost); TTFT = finish time - enqueue time.  With ``adaptive`` each step runs with
+    the k that object holds and reports the TTFT of the queries it admitted to it.
     """
     q = stream.queries
     tree = tree or OracleTree()
@@ -403,13 +405,16 @@ def simulate_stream(stream, snapshot_every: int = 0, tree: Optional[OracleTree] 
         waiting = np.concatenate([waiting, new])
         off, ln, arr = q.off[waiting], q.len[waiting], enq[waiting]
         m = tree.match(q.tokens, off, ln)
-        idx, phase = select(arr, m, stream.k, stream.batch, phase)
+        k_now = stream.k if adaptive is None else adaptive.k()
+        idx, phase = select(arr, m, k_now, stream.batch, phase)
         st = tree.commit(q.tokens, off, ln, idx, stream.budget)
         cost = int((ln[idx].astype(np.int64) - m[idx].astype(np.int64)).sum())
         clock += max(1, cost)
         gids = waiting[idx]
         ttft[gids] = clock - enq[gids].astype(np.int64)
         adm[gids] = s
+        if adaptive is not None:
+            adaptive.observe(ttft[gids].tolist())
         res.batches.append(gids.copy())
         res.match_lens.append(m)
         res.waiting_ids.append(waiting.copy())

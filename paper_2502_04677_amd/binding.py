@@ -27,6 +27,7 @@ EXPORTS = (
     "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
     "kLPM_commit", "kLPM_commit_matched", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather",
     "kLPM_read_stats", "kLPM_probe_read",
+    "kLPM_adapt_state_bytes", "kLPM_adapt_init", "kLPM_adapt_k", "kLPM_adapt_observe", "kLPM_adapt_read",
     "kLPM_snapshot_bytes", "kLPM_snapshot", "kLPM_destroy", "kLPM_strerror",
 )
 
@@ -57,6 +58,17 @@ class Stats(C.Structure):
 
 
 STATS_BYTES = C.sizeof(Stats)
+ADAPT_MAX_ARMS = 16
+
+
+class AdaptConfig(C.Structure):
+    _fields_ = [("arms", C.c_uint32 * ADAPT_MAX_ARMS), ("n_arms", C.c_int32), ("window", C.c_int32),
+                ("explore", C.c_uint64), ("seed", C.c_uint64)]
+
+
+class AdaptStats(C.Structure):
+    _fields_ = [("count", C.c_uint64 * ADAPT_MAX_ARMS), ("cost", C.c_uint64 * ADAPT_MAX_ARMS), ("pulls", C.c_uint64),
+                ("arm", C.c_int32), ("k", C.c_uint32), ("steps_in_window", C.c_int32), ("device_error", C.c_uint32)]
 
 
 def load_library() -> C.CDLL:
@@ -73,9 +85,14 @@ def load_library() -> C.CDLL:
     lib.kLPM_build_tree.argtypes = [C.POINTER(vp), C.POINTER(Config), vp, sz, C.POINTER(Queries), vp]
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select.argtypes = [vp, vp, vp, i32, vp, u32, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select.argtypes = [vp, vp, vp, i32, vp, u32, vp, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_adapt_state_bytes.argtypes = [C.POINTER(sz)]
+    lib.kLPM_adapt_init.argtypes = [vp, sz, C.POINTER(AdaptConfig), vp]
+    lib.kLPM_adapt_k.argtypes = [vp, C.POINTER(vp)]
+    lib.kLPM_adapt_observe.argtypes = [vp, C.POINTER(Queue), vp, vp, i32, vp, i32, vp]
+    lib.kLPM_adapt_read.argtypes = [vp, C.POINTER(AdaptStats), vp]
     lib.kLPM_select_dynamic_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select_dynamic.argtypes = [C.POINTER(Queries), vp, vp, u32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select_dynamic.argtypes = [C.POINTER(Queries), vp, vp, u32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.kLPM_score_hit_rate.argtypes = [vp, vp, i32, vp, i32, vp, vp]
     lib.kLPM_tie_keys.argtypes = [C.c_uint64, C.c_uint64, vp, i32, vp, vp, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
@@ -83,7 +100,7 @@ def load_library() -> C.CDLL:
     lib.kLPM_set_budget.argtypes = [vp, i64]
     lib.kLPM_set_protect.argtypes = [vp, i64]
     lib.kLPM_reserve_clock.argtypes = [vp, C.c_uint64]
-    lib.kLPM_batch_token_budget.argtypes = [C.POINTER(Queries), vp, vp, vp, i32, i64, u32, vp, vp]
+    lib.kLPM_batch_token_budget.argtypes = [C.POINTER(Queries), vp, vp, vp, i32, i64, u32, vp, vp, vp]
     lib.kLPM_kv_slots.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, i32, vp, vp, vp]
     lib.kLPM_gather_slots.argtypes = [vp, vp, i64, vp, vp]
     lib.kLPM_queue_advance.argtypes = [C.POINTER(Queue), C.POINTER(Queue), C.POINTER(Queries), vp, vp, vp, i32, vp, i32,
@@ -226,8 +243,10 @@ def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, 
                 phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
                 workspace: Tuple[torch.Tensor, int], workspace_bytes: int, stream=None, flags: int = 0,
                 max_match: int = 0, n_live: Optional[torch.Tensor] = None,
-                tie_key: Optional[torch.Tensor] = None) -> None:
-    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), _ptr(tie_key), int(n), _ptr(n_live), C.c_uint32(k & 0xFFFFFFFF), int(batch),
+                tie_key: Optional[torch.Tensor] = None, k_dev: Optional[int] = None) -> None:
+    """``k_dev``: device address of a uint32 holding k (``AdaptiveK.k_dev``); ``k`` is then ignored."""
+    _check(_lib.kLPM_select(_ptr(arrival), _ptr(match_len), _ptr(tie_key), int(n), _ptr(n_live), C.c_uint32(k & 0xFFFFFFFF),
+                            C.c_void_p(k_dev), int(batch),
                             C.c_uint32(flags), int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
 
@@ -241,9 +260,10 @@ def kLPM_select_dynamic_workspace_bytes(n: int) -> int:
 def kLPM_select_dynamic(q: DeviceQueries, match_len: torch.Tensor, last_node: torch.Tensor, k: int, batch: int,
                         phase_inout: torch.Tensor, dyn_match: torch.Tensor, batch_idx: torch.Tensor,
                         n_selected: torch.Tensor, workspace: Tuple[torch.Tensor, int], workspace_bytes: int,
-                        stream=None) -> None:
+                        stream=None, k_dev: Optional[int] = None) -> None:
     qs = q.c_struct()
-    _check(_lib.kLPM_select_dynamic(C.byref(qs), _ptr(match_len), _ptr(last_node), C.c_uint32(k & 0xFFFFFFFF), int(batch),
+    _check(_lib.kLPM_select_dynamic(C.byref(qs), _ptr(match_len), _ptr(last_node), C.c_uint32(k & 0xFFFFFFFF),
+                                    C.c_void_p(k_dev), int(batch),
                                     _ptr(phase_inout), _ptr(dyn_match), _ptr(batch_idx), _ptr(n_selected),
                                     C.c_void_p(workspace[1]), int(workspace_bytes), _stream(stream)),
            "kLPM_select_dynamic")
@@ -278,6 +298,43 @@ def kLPM_commit_matched(tree: Tree, q: DeviceQueries, match_len: torch.Tensor, l
            "kLPM_commit_matched")
 
 
+def kLPM_adapt_state_bytes() -> int:
+    need = C.c_size_t(0)
+    _check(_lib.kLPM_adapt_state_bytes(C.byref(need)), "kLPM_adapt_state_bytes")
+    return int(need.value)
+
+
+def kLPM_adapt_init(state: int, state_bytes: int, arms, window: int, explore: int, seed: int, stream=None) -> None:
+    """``state``: device address (8-byte aligned) of at least ``kLPM_adapt_state_bytes()`` bytes."""
+    cfg = AdaptConfig()
+    if not 1 <= len(arms) <= ADAPT_MAX_ARMS:
+        raise KlpmError("kLPM_adapt_init: between 1 and 16 arms")
+    for i, a in enumerate(arms):
+        cfg.arms[i] = int(a) & 0xFFFFFFFF
+    cfg.n_arms, cfg.window, cfg.explore, cfg.seed = len(arms), int(window), int(explore), int(seed) & (2**64 - 1)
+    _check(_lib.kLPM_adapt_init(C.c_void_p(state), int(state_bytes), C.byref(cfg), _stream(stream)), "kLPM_adapt_init")
+
+
+def kLPM_adapt_k(state: int) -> int:
+    """Device address of the current k (the ``k_dev`` argument of the selection calls)."""
+    kp = C.c_void_p(0)
+    _check(_lib.kLPM_adapt_k(C.c_void_p(state), C.byref(kp)), "kLPM_adapt_k")
+    return int(kp.value)
+
+
+def kLPM_adapt_observe(state: int, served: "DeviceQueue", batch_idx: torch.Tensor, n_selected: torch.Tensor,
+                       batch_cap: int, ttft: torch.Tensor, stream=None) -> None:
+    qs = served.c_struct()
+    _check(_lib.kLPM_adapt_observe(C.c_void_p(state), C.byref(qs), _ptr(batch_idx), _ptr(n_selected), int(batch_cap),
+                                   _ptr(ttft), int(ttft.shape[0]), _stream(stream)), "kLPM_adapt_observe")
+
+
+def kLPM_adapt_read(state: int, stream=None) -> AdaptStats:
+    out = AdaptStats()
+    _check(_lib.kLPM_adapt_read(C.c_void_p(state), C.byref(out), _stream(stream)), "kLPM_adapt_read")
+    return out
+
+
 def kLPM_reserve_clock(tree: Tree, extra_prompts: int) -> None:
     _check(_lib.kLPM_reserve_clock(tree.handle, C.c_uint64(int(extra_prompts))), "kLPM_reserve_clock")
 
@@ -287,10 +344,12 @@ def kLPM_set_protect(tree: Tree, recent_prompts: int) -> None:
 
 
 def kLPM_batch_token_budget(q: DeviceQueries, match_len: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor,
-                            batch_cap: int, token_budget: int, k: int, phase_inout: torch.Tensor, stream=None) -> None:
+                            batch_cap: int, token_budget: int, k: int, phase_inout: torch.Tensor, stream=None,
+                            k_dev: Optional[int] = None) -> None:
     qs = q.c_struct()
     _check(_lib.kLPM_batch_token_budget(C.byref(qs), _ptr(match_len), _ptr(batch_idx), _ptr(n_selected), int(batch_cap),
-                                        int(token_budget), C.c_uint32(k & 0xFFFFFFFF), _ptr(phase_inout), _stream(stream)),
+                                        int(token_budget), C.c_uint32(k & 0xFFFFFFFF), C.c_void_p(k_dev),
+                                        _ptr(phase_inout), _stream(stream)),
            "kLPM_batch_token_budget")
 
 

@@ -144,6 +144,14 @@ __device__ __forceinline__ int32_t live_count(int32_t n, const int32_t *__restri
     return v < n ? v : n;
 }
 
+// k of Algorithm 1: the host's value, or the one that device memory holds when the launch runs
+// (a k that an earlier kernel of the stream chose).
+struct KArg {
+    uint32_t k;
+    const uint32_t *dev;
+    __device__ __forceinline__ uint32_t get() const { return dev ? *dev : k; }
+};
+
 // Read-only probe (tree not being modified by this kernel). Returns the slot index or -1 and, when
 // found, the child's id and edge span. All arguments are wave-uniform; so are the results.
 __device__ __forceinline__ int32_t slot_find(const Slot *__restrict__ slots, uint32_t mask, uint64_t key,

@@ -324,11 +324,12 @@ struct StagedAcc {
 __global__ __launch_bounds__(256) void k_sel_walk(const uint32_t *__restrict__ order_a,
                                                   const uint32_t *__restrict__ order_l,
                                                   const uint32_t *__restrict__ rank_a,
-                                                  const uint32_t *__restrict__ rank_l, LiveN nn, uint32_t k,
+                                                  const uint32_t *__restrict__ rank_l, LiveN nn, KArg ka,
                                                   int32_t batch, uint32_t *__restrict__ phase_inout,
                                                   int32_t *__restrict__ batch_idx,
                                                   int32_t *__restrict__ n_selected) {
     const int32_t n = nn.get();
+    const uint32_t k = ka.get();
     __shared__ uint32_t s_a_elem[kStage], s_l_elem[kStage], s_a_in_l[kStage], s_l_in_a[kStage];
     const int tid = threadIdx.x;
     const int32_t nb = batch < n ? batch : n;
@@ -379,11 +380,12 @@ struct FifoAcc {
 
 __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__restrict__ arrival,
                                                                const int32_t *__restrict__ match_len, LiveN nn,
-                                                               uint32_t k, int32_t batch,
+                                                               KArg ka, int32_t batch,
                                                                uint32_t *__restrict__ phase_inout,
                                                                int32_t *__restrict__ batch_idx,
                                                                int32_t *__restrict__ n_selected) {
     const int32_t n = nn.get();
+    const uint32_t k = ka.get();
     __shared__ uint32_t hist[kFifoBins];
     __shared__ uint64_t cand[kFifoMaxBatch];
     __shared__ uint32_t l_elem[kFifoMaxBatch];
@@ -797,11 +799,12 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restr
 }
 
 // Sort the nb winners by (-match_len, index) in LDS and run the two-cursor walk.
-__global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, uint32_t k, int32_t batch, FqWs ws,
+__global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, int32_t batch, FqWs ws,
                                                             uint32_t *__restrict__ phase_inout,
                                                             int32_t *__restrict__ batch_idx,
                                                             int32_t *__restrict__ n_selected) {
     const int32_t n = nn.get();
+    const uint32_t k = ka.get();
     __shared__ uint64_t cand[kFifoMaxBatch];
     __shared__ uint32_t l_elem[kFifoMaxBatch];
     __shared__ uint32_t a_in_l[kFifoMaxBatch];
@@ -888,7 +891,7 @@ static void carve_fq(FqWs &f, char *base, int32_t n, size_t *used) {
     *used = o;
 }
 
-static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, LiveN nn, uint32_t k, int32_t batch,
+static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, LiveN nn, KArg k, int32_t batch,
                             int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                             char *workspace, hipStream_t stream) {
     FqWs f;
@@ -903,7 +906,7 @@ static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, L
     int mbits = 0;
     while (mbits < 31 && (max_match >> mbits) != 0) ++mbits;
     if (mbits == 0) mbits = 1;
-    const bool fcfs = (k == 1u);
+    const bool fcfs = (!k.dev && k.k == 1u);  // (a k read on the device takes the general kernels)
     int shift = mbits, level = 0;
     while (shift > 0 && level < kFqMaxLevels) {
         int width = shift < kFqLevelBits ? shift : kFqLevelBits;
@@ -1065,13 +1068,15 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
 }
 
 extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
-                           const int32_t *n_live, uint32_t k, int32_t batch, uint32_t flags, int32_t max_match,
+                           const int32_t *n_live, uint32_t k_host, const uint32_t *k_dev, int32_t batch, uint32_t flags,
+                           int32_t max_match,
                            uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (n < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
     const LiveN nn{n, n_live};
+    const KArg k{k_host, k_dev};
     // (tie keys reorder the longest-match order within equal scores: that needs the full sort)
     if ((flags & KLPM_SELECT_FIFO) && !tie_key && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0) {
         if (n <= kFqSingleBlockN) {
@@ -1087,7 +1092,7 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, co
                                 batch_idx, n_selected, (char *)workspace, stream);
     }
     SelectOrders ord;
-    int rc = build_select_orders(arrival, match_len, tie_key, n, n_live, k != 1u && batch > 0, workspace, workspace_bytes,
+    int rc = build_select_orders(arrival, match_len, tie_key, n, n_live, (k_dev || k_host != 1u) && batch > 0, workspace, workspace_bytes,
                                  stream, &ord);
     if (rc) return rc;
     hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, ord.order_a, ord.order_l, ord.rank_a, ord.rank_l, nn, k,

@@ -104,10 +104,11 @@ __device__ __forceinline__ uint64_t pack_key(int32_t score, uint32_t rank_a) {
 }
 
 __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__restrict__ match_len, SelectOrders ord,
-                                                    DynWs ws, int32_t *__restrict__ dyn, uint32_t k, int32_t batch,
+                                                    DynWs ws, int32_t *__restrict__ dyn, KArg ka, int32_t batch,
                                                     uint32_t *__restrict__ phase_inout,
                                                     int32_t *__restrict__ batch_idx,
                                                     int32_t *__restrict__ n_selected) {
+    const uint32_t k = ka.get();
     __shared__ uint32_t st[kDynMaxN / 16];  // per query: bit 0 = picked, bit 1 = in the boosted set
     const int lane = threadIdx.x;
     const int32_t n = live_count(q.n, q.n_live);
@@ -384,7 +385,7 @@ extern "C" int kLPM_select_dynamic_workspace_bytes(int32_t n, size_t *out_bytes)
 }
 
 extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node, uint32_t k,
-                                   int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
+                                   const uint32_t *k_dev, int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
                                    int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (!q || q->n < 0 || q->n > kDynMaxN || q->n_tokens < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
@@ -412,7 +413,7 @@ extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_l
         hipLaunchKernelGGL(k_dyn_insert, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, match_len, d);
         hipLaunchKernelGGL(k_dyn_multi, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, d);
     }
-    hipLaunchKernelGGL(k_dyn_walk, dim3(1), dim3(kWave), 0, stream, qv, match_len, ord, d, dyn_match, k, batch, phase_inout,
+    hipLaunchKernelGGL(k_dyn_walk, dim3(1), dim3(kWave), 0, stream, qv, match_len, ord, d, dyn_match, KArg{k, k_dev}, batch, phase_inout,
                        batch_idx, n_selected);
     return check_launch();
 }

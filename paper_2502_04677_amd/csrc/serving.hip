@@ -12,8 +12,9 @@ constexpr int kCutThreads = 1024;
 __global__ __launch_bounds__(kCutThreads) void k_batch_token_budget(QView q, const int32_t *__restrict__ match_len,
                                                                     const int32_t *__restrict__ batch_idx,
                                                                     int32_t *__restrict__ n_selected, int32_t batch_cap,
-                                                                    int64_t token_budget, uint32_t k,
+                                                                    int64_t token_budget, KArg ka,
                                                                     uint32_t *__restrict__ phase_inout) {
+    const uint32_t k = ka.get();
     __shared__ int64_t part[kCutThreads / kWave];
     __shared__ int32_t s_keep;
     const int tid = threadIdx.x;
@@ -125,13 +126,13 @@ using namespace klpm;
 
 extern "C" int kLPM_batch_token_budget(const kLPM_queries *q, const int32_t *match_len, const int32_t *batch_idx,
                                        int32_t *n_selected, int32_t batch_cap, int64_t token_budget, uint32_t k,
-                                       uint32_t *phase_inout, kLPM_stream stream) {
+                                       const uint32_t *k_dev, uint32_t *phase_inout, kLPM_stream stream) {
     if (!q || q->n < 0 || batch_cap < 0 || token_budget < 0 || !n_selected || !phase_inout) return KLPM_EINVAL;
     if (batch_cap > 0 && (!batch_idx || !match_len || !q->len)) return KLPM_EINVAL;
     QView qv;
     qv.tokens = q->tokens; qv.off = q->off; qv.len = q->len; qv.n_tokens = q->n_tokens; qv.n = q->n; qv.n_live = q->n_live;
     hipLaunchKernelGGL(k_batch_token_budget, dim3(1), dim3(kCutThreads), 0, (hipStream_t)stream, qv, match_len, batch_idx,
-                       n_selected, batch_cap, token_budget, k, phase_inout);
+                       n_selected, batch_cap, token_budget, KArg{k, k_dev}, phase_inout);
     return check_launch();
 }
 

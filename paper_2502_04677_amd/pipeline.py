@@ -51,16 +51,18 @@ class Scheduler:
         return out
 
     def select(self, q: B.DeviceQueries, k: int, batch: int, n: Optional[int] = None, fifo: bool = False,
-               score: Optional[torch.Tensor] = None, score_max: int = 0, tie_key: Optional[torch.Tensor] = None) -> None:
+               score: Optional[torch.Tensor] = None, score_max: int = 0, tie_key: Optional[torch.Tensor] = None,
+               k_dev: Optional[int] = None) -> None:
         """``fifo`` promises that the queue is in arrival order (checked on the device).  ``score``
         (default: the match lengths of the last ``match``) is what longest-match picks maximise,
-        ``score_max`` its upper bound; ``tie_key`` decides between equal scores."""
+        ``score_max`` its upper bound; ``tie_key`` decides between equal scores; ``k_dev`` is the device
+        address of a k that replaces ``k`` (``AdaptiveK.k_dev``)."""
         assert batch <= self.cfg.max_batch
         B.kLPM_select(q.arrival, self.match_len if score is None else score, q.n if n is None else n, k, batch,
                       self.phase, self.batch_idx, self.n_selected, self.ws, self.ws_bytes,
                       flags=B.KLPM_SELECT_FIFO if fifo else 0,
                       max_match=self.cfg.max_prompt_len if score is None else score_max, n_live=q.n_live,
-                      tie_key=tie_key)
+                      tie_key=tie_key, k_dev=k_dev)
 
     def commit(self, q: B.DeviceQueries, batch_cap: Optional[int] = None, reuse_match: bool = True) -> None:
         """Commits the selected batch.  When ``q`` is the very object last passed to ``match`` and no
@@ -95,6 +97,24 @@ class Scheduler:
 
     def snapshot(self) -> bytes:
         return B.kLPM_snapshot(self.tree)
+
+
+class AdaptiveK:
+    """Device-resident epsilon-greedy choice of k: the state buffer and the address of its current k."""
+
+    def __init__(self, arms, window: int, explore: int, seed: int, device="cuda:0"):
+        nbytes = B.kLPM_adapt_state_bytes()
+        self.buf, self.state = B.alloc_aligned(nbytes, device)
+        B.kLPM_adapt_init(self.state, nbytes, arms, window, explore, seed)
+        self.k_dev = B.kLPM_adapt_k(self.state)
+        self.n_arms = len(arms)
+
+    def observe(self, served: B.DeviceQueue, batch_idx: torch.Tensor, n_selected: torch.Tensor, batch_cap: int,
+                ttft: torch.Tensor) -> None:
+        B.kLPM_adapt_observe(self.state, served, batch_idx, n_selected, batch_cap, ttft)
+
+    def read(self) -> B.AdaptStats:
+        return B.kLPM_adapt_read(self.state)
 
 
 class OnlineRun:
@@ -151,14 +171,20 @@ class OnlineRun:
         self.cur = 1 - self.cur
         self.n_host = min(self.cap, self.n_host - min(batch, self.n_host) + n_new)
 
-    def step(self, k: int, batch: int, new_ids: Optional[torch.Tensor]) -> None:
-        """One scheduling step: match, select, commit, then retire the batch and enqueue ``new_ids``."""
+    def step(self, k: int, batch: int, new_ids: Optional[torch.Tensor], adaptive: Optional[AdaptiveK] = None) -> None:
+        """One scheduling step: match, select, commit, then retire the batch and enqueue ``new_ids``.
+        With ``adaptive`` the step runs with the k that object holds on the device and reports the
+        TTFT of the queries it admitted to it."""
         s = self.s
         q = self.view()
+        served = self.queue
         s.match(q)
-        s.select(q, k, batch, fifo=True)  # this queue is append-only with stable removal
+        # this queue is append-only with stable removal
+        s.select(q, k, batch, fifo=True, k_dev=None if adaptive is None else adaptive.k_dev)
         s.commit(q, batch)
         self.advance(batch, new_ids)
+        if adaptive is not None:
+            adaptive.observe(served, s.batch_idx, s.n_selected, batch, self.ttft)
 
 
 class TimedRun:
@@ -209,15 +235,21 @@ class TimedRun:
                                    self.dev_error)
         self.cur = 1 - self.cur
 
-    def step(self, k: int, batch: int) -> None:
+    def step(self, k: int, batch: int, adaptive: Optional[AdaptiveK] = None) -> None:
+        """With ``adaptive`` the step runs with the k that object holds on the device (``k`` is ignored)
+        and reports the TTFT of the queries it admitted to it."""
         s = self.s
         q = self.view()
+        served = self.queue
+        k_dev = None if adaptive is None else adaptive.k_dev
         s.match(q)
         if self.tie is None:
-            s.select(q, k, batch, fifo=True)  # arrivals join in time order, removal is stable
+            s.select(q, k, batch, fifo=True, k_dev=k_dev)  # arrivals join in time order, removal is stable
         else:
             B.kLPM_tie_keys(self.tie_seed, self.steps_done, self.queue.id, self.cap, self.tie, n_live=self.queue.n)
-            s.select(q, k, batch, tie_key=self.tie)
+            s.select(q, k, batch, tie_key=self.tie, k_dev=k_dev)
         s.commit(q, batch)
         self._advance(batch)
+        if adaptive is not None:
+            adaptive.observe(served, s.batch_idx, s.n_selected, batch, self.ttft)
         self.steps_done += 1

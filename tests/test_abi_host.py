@@ -44,6 +44,7 @@ def test_struct_layouts_match_header(K):
     assert C.sizeof(binding.Arrivals) == 32 and C.sizeof(binding.Queue) == 64
     assert C.sizeof(binding.Config) == 32
     assert C.sizeof(binding.Stats) == 48 and binding.STATS_BYTES == 48
+    assert C.sizeof(binding.AdaptConfig) == 88 and C.sizeof(binding.AdaptStats) == 280
 
 
 def test_arena_sizing_and_config_validation(K):
@@ -107,3 +108,24 @@ def test_size_config_leaves_room_for_a_batch(K):
     cfg = K.size_config(cache_tokens=1_000_000, cache_prompts=500, budget=600_000, max_batch=64, max_prompt_len=4096)
     assert cfg.pool_tokens >= 600_000 + 64 * 4096 and cfg.max_nodes >= 2 * 500 + 2 * 64
     assert cfg.budget_tokens == 600_000
+
+
+def test_adaptive_k_arguments_are_validated_on_the_host(K):
+    from paper_2502_04677_amd import binding
+
+    lib = binding._lib
+    assert K.kLPM_adapt_state_bytes() % 256 == 0 and K.kLPM_adapt_state_bytes() >= 384
+    fake = 0x1000  # never dereferenced: every call below is refused before anything is enqueued
+
+    def init(n_arms, window, explore, nbytes=4096, addr=fake):
+        cfg = binding.AdaptConfig()
+        cfg.n_arms, cfg.window, cfg.explore, cfg.seed = n_arms, window, explore, 0
+        return lib.kLPM_adapt_init(C.c_void_p(addr), nbytes, C.byref(cfg), None)
+
+    assert init(0, 1, 0) != 0 and init(17, 1, 0) != 0 and init(-1, 1, 0) != 0
+    assert init(2, 0, 0) != 0 and init(2, 1, (1 << 32) + 1) != 0
+    assert init(2, 1, 0, nbytes=64) != 0 and init(2, 1, 0, addr=fake + 4) != 0 and init(2, 1, 0, addr=0) != 0
+    assert lib.kLPM_adapt_init(C.c_void_p(fake), 4096, None, None) != 0
+    assert K.kLPM_adapt_k(fake) == fake  # the current k is the first word of the state
+    assert lib.kLPM_adapt_k(None, None) != 0 and lib.kLPM_adapt_read(None, None, None) != 0
+    assert lib.kLPM_adapt_observe(None, None, None, None, 0, None, 0, None) != 0

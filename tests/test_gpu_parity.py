@@ -515,28 +515,38 @@ def test_match_with_device_side_queue_length():
 
 
 # ----------------------------------------------------------------------------- Def. 2 timeline with timed arrivals
-def _run_timed(p, k, batch, budget, c_num=0, c_den=1, t_start=0, cap=None, check_every=1, tie_seed=None):
+def _run_timed(p, k, batch, budget, c_num=0, c_den=1, t_start=0, cap=None, check_every=1, tie_seed=None,
+               adaptive=None):
     """The device-resident timed run against the oracle's event loop: queue contents, match lengths
     and batch at the checked steps; TTFT of every query, final clock and step count at the end."""
     cap_o = p.n if cap is None else cap
+    ad_ref = None if adaptive is None else oracle.AdaptiveK(*adaptive)
     r = oracle.simulate_timed(p, k, batch, budget, c_num=c_num, c_den=c_den, t_start=t_start, queue_cap=cap_o,
-                              tie_seed=tie_seed)
+                              tie_seed=tie_seed, adaptive=ad_ref)
     q = K.DeviceQueries.from_host(p)
     cfg = K.size_config(0, 0, budget, batch, int(p.len.max()), extra_prompts=2 * batch)
     s = K.Scheduler(cfg, None, cap_o)
     run = K.TimedRun(s, q, cap_o, p.arrival, c_num=c_num, c_den=c_den, t_start=t_start, tie_seed=tie_seed)
+    ad = None if adaptive is None else K.AdaptiveK(*adaptive)
+    k_host = k if adaptive is None else 0x5EED  # with a device-side k the host's value must not matter
     for step in range(r.steps):
         check = check_every and (step % check_every == 0 or step == r.steps - 1)
         if check:
             n_live = int(run.queue.n.item())
             ids = run.queue.id[:n_live].cpu().numpy()
             assert ids.tolist() == r.waiting_ids[step].tolist(), step
-        run.step(k, batch)
+        run.step(k_host, batch, adaptive=ad)
         if check:
             assert s.match_len[:n_live].cpu().numpy().tolist() == r.match_lens[step].tolist(), step
             assert ids[s.batch()].tolist() == r.batches[step].tolist(), step
-    run.step(k, batch)  # one step past the end: nobody is waiting, nothing is pending, nothing changes
+    run.step(k_host, batch)  # one step past the end: nobody is waiting, nothing is pending, nothing changes
     torch.cuda.synchronize()
+    if ad is not None:
+        st = ad.read()
+        A = len(ad_ref.arms)
+        assert st.device_error == 0
+        assert (list(st.count)[:A], list(st.cost)[:A], st.pulls, st.arm, st.k, st.steps_in_window) == (
+            ad_ref.count, ad_ref.cost, ad_ref.pulls, ad_ref.arm, ad_ref.k(), ad_ref.steps)
     assert int(run.queue.n.item()) == 0 and int(run.queue.n_joined.item()) == p.n
     assert int(run.sim_clock.item()) == r.clock
     assert run.ttft[:p.n].cpu().numpy().tolist() == r.ttft.tolist()
@@ -616,6 +626,114 @@ def test_timed_gap_sweep_separates_the_policies_as_the_theory_says():
             worst[k], median[k] = int(r.ttft.max()), oracle.percentile_nearest_rank(r.ttft, 0.5)
         assert worst[rep] < worst[K_INF] and worst[rep] < worst[1], (s_gap, worst)
         assert median[K_INF] <= median[rep] <= median[1], (s_gap, median)
+
+
+# ----------------------------------------------------------------------------- k read from device memory, adaptive k
+def test_select_reads_k_from_device_memory():
+    """Every selection path with k taken from device memory (the host's k is then ignored): the short
+    and the long arrival-ordered paths, the sorting path, in-batch rescoring and the token-budget cut."""
+    dev = "cuda:0"
+    w = W.config1(scale=0.125)
+    s, ref, q = _setup(w, max_batch=256)
+    hq = w.queries
+    m_ref = ref.match(hq.tokens, hq.off, hq.len)
+    s.match(q)
+    order = np.argsort(hq.arrival, kind="stable")
+    assert (order == np.arange(hq.n)).all()  # this queue is in arrival order
+    k_d = torch.zeros(1, dtype=torch.int32, device=dev)
+    dyn_bytes = K.kLPM_select_dynamic_workspace_bytes(q.n)
+    dyn_ws = K.alloc_aligned(dyn_bytes, dev)
+    dyn = torch.zeros(q.n, dtype=torch.int32, device=dev)
+    for k in (1, 2, 3, 7, 300, 0, K_INF):
+        k_d.copy_(torch.from_numpy(np.array([k], dtype=np.uint32).view(np.int32)))
+        for n, fifo in ((300, True), (hq.n, True), (hq.n, False), (300, False)):
+            for batch in (1, 64, 256):
+                _say(f"device-side k={k} n={n} fifo={fifo} B={batch}")
+                s.set_phase(5)
+                s.select(q, 0x5EED, batch, n=n, fifo=fifo, k_dev=k_d.data_ptr())
+                idx_ref, ph_ref = oracle.select(hq.arrival[:n], m_ref[:n], k, batch, 5)
+                assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref
+        # the token-budget cut rewinds the phase by the same k
+        s.set_phase(5)
+        s.select(q, 0x5EED, 64, fifo=True, k_dev=k_d.data_ptr())
+        full_ref, ph_full = oracle.select(hq.arrival, m_ref, k, 64, 5)
+        cost = (hq.len[full_ref] - m_ref[full_ref]).astype(np.int64)
+        K.kLPM_batch_token_budget(q, s.match_len, s.batch_idx, s.n_selected, 64, int(cost.sum() // 2), 0x5EED, s.phase,
+                                  k_dev=k_d.data_ptr())
+        keep = oracle.token_budget_cut(full_ref, hq.len, m_ref, int(cost.sum() // 2))
+        assert s.batch().tolist() == full_ref[:keep].tolist()
+        assert s.phase_value() == oracle.phase_after_cut(ph_full, 64, keep, k)
+        # in-batch rescoring
+        sub = 1500
+        qs = K.DeviceQueries(q.tokens, q.off, q.len, q.arrival, sub)
+        s.set_phase(1)
+        K.kLPM_select_dynamic(qs, s.match_len, s.last_node, 0x5EED, 48, s.phase, dyn, s.batch_idx, s.n_selected, dyn_ws,
+                              dyn_bytes, k_dev=k_d.data_ptr())
+        idx_ref, ph_ref, _ = oracle.select_dynamic(hq.tokens, hq.off[:sub], hq.len[:sub], hq.arrival[:sub], m_ref[:sub], k, 48, 1)
+        assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref
+
+
+def test_timed_runs_with_adaptive_k():
+    """k chosen per window by the device-resident epsilon-greedy rule: the run (every TTFT, hence every
+    batch and every k) and the bandit's counters equal the oracle's."""
+    for seed, (n, u, rep, d, s_gap) in enumerate([(48, 9, 4, 5, 3), (64, 70, 2, 90, 40), (96, 40, 4, 25, 30)]):
+        p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=seed + 30)
+        for arms, window, explore, batch, t_start in (((1, rep, K_INF), 3, 1 << 30, 1, 0),
+                                                      ((2, 1), 1, 0, 2, s_gap * n),
+                                                      ((K_INF, 3, 1, 8, 2), 2, 1 << 32, 3, 0),
+                                                      ((rep,), 4, 1 << 31, 1, 0),
+                                                      ((1, 0), 5, 1 << 29, 4, 7)):
+            _say(f"timed adaptive: n={n} arms={arms} window={window} explore={explore} B={batch}")
+            _run_timed(p, 0, batch, batch * (u + d), c_num=1, c_den=32, t_start=t_start,
+                       adaptive=(list(arms), window, explore, 100 + seed))
+    # with random ties as well (the sorting path of the selection reads the same device-side k)
+    p, _ = W.shuffled_queue(80, 30, 4, 20, 15, seed=40)
+    _run_timed(p, 0, 2, 2 * 50, tie_seed=3, adaptive=([1, 4, K_INF], 2, 1 << 30, 9))
+
+
+def test_adaptive_k_at_the_paper_shape():
+    """n = 2000, 4 queries per shared prefix, u = d = 3000, served after everything has arrived with
+    random ties; five arms, windows of 20 steps, a quarter of the pulls exploring."""
+    n, rep, u, d, c_num, c_den, s_gap = 2000, 4, 3000, 3000, 1, 1 << 16, 1500
+    p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=13)
+    p.arrival[:] = p.arrival * np.uint64(c_den)
+    r = _run_timed(p, 0, 1, u + d, c_num=c_num, c_den=c_den, t_start=s_gap * n * c_den, cap=2048, check_every=500,
+                   tie_seed=99, adaptive=([1, 2, rep, 2 * rep, K_INF], 20, 1 << 30, 77))
+    assert len(set(r.ks)) == 5
+
+
+def test_online_stream_with_adaptive_k():
+    """The online stream (arrivals per step, LRU eviction under a budget, batches of many queries)
+    with k chosen on the device."""
+    stream = W.config4_stream(steps=120, rate=40, groups=2000, budget=150_000, batch=32)  # more arrivals than a batch admits
+    ad_ref = oracle.AdaptiveK([1, 4, K_INF, 2], 4, 1 << 30, 21)
+    r = oracle.simulate_stream(stream, adaptive=ad_ref)
+    hq = stream.queries
+    q = K.DeviceQueries.from_host(hq)
+    cap = 4096
+    cfg = K.size_config(0, 0, stream.budget, stream.batch, int(hq.len.max()), extra_prompts=hq.n)
+    s = K.Scheduler(cfg, None, cap)
+    run = K.OnlineRun(s, q, cap, np.arange(int(stream.step_start[0]), int(stream.step_start[1])))
+    ad = K.AdaptiveK([1, 4, K_INF, 2], 4, 1 << 30, 21)
+    for step in range(stream.steps):
+        nxt = None
+        if step + 1 < stream.steps:
+            nxt = torch.arange(int(stream.step_start[step + 1]), int(stream.step_start[step + 2]), dtype=torch.int32,
+                               device="cuda:0")
+        run.step(0x5EED, stream.batch, nxt, adaptive=ad)
+    torch.cuda.synchronize()
+    assert run.ttft.cpu().numpy().tolist() == r.ttft.tolist()
+    assert int(run.sim_clock.item()) == r.clock and int(run.dev_error.item()) == 0
+    st = ad.read()
+    assert st.device_error == 0 and st.pulls == ad_ref.pulls > 8
+    assert (list(st.count)[:4], list(st.cost)[:4], st.arm, st.k) == (ad_ref.count, ad_ref.cost, ad_ref.arm, ad_ref.k())
+    assert s.snapshot() == oracle_tree_after(stream, ad=[1, 4, K_INF, 2])
+
+
+def oracle_tree_after(stream, ad):
+    tree = oracle.OracleTree()
+    oracle.simulate_stream(stream, tree=tree, adaptive=oracle.AdaptiveK(ad, 4, 1 << 30, 21))
+    return tree.snapshot()
 
 
 # ----------------------------------------------------------------------------- score and tie variants of Algorithm 1
