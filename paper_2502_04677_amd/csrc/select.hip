@@ -214,98 +214,161 @@ static int radix_sort(uint64_t *k0, uint32_t *v0, uint64_t *k1, uint32_t *v1, Li
 // (a_elem / l_elem) and the position of that same query in the other order (a_in_l / l_in_a; any
 // value >= nb stands for "not among the first nb of the other order").  One wavefront runs it.
 template <class Acc>
+struct TwoCursorWalk {
+    // Each order is looked at through a window of 64 consecutive entries held in registers (lane =
+    // entry); a window is read again once the cursor has moved kReload entries into it, so a pick
+    // costs ballots and scalar arithmetic, not a round trip to LDS or memory.
+    static constexpr int32_t kReload = 16;
+    const Acc &acc;
+    const int32_t n_valid, nb;
+    const uint32_t k, km1;
+    int32_t *__restrict__ const batch_idx;
+    const int lane;
+    const uint64_t below;
+    int32_t ia = 0, il = 0, j = 0;
+    int32_t wa = -kWave, wl = -kWave;  // first entry of each window (a load is due at the start)
+    uint32_t a_oth = 0, a_elv = 0, l_oth = 0, l_elv = 0;
+    bool a_ok = false, l_ok = false;
+
+    __device__ __forceinline__ TwoCursorWalk(const Acc &acc_, int32_t n_valid_, int32_t nb_, uint32_t k_,
+                                             int32_t *__restrict__ batch_idx_, int lane_)
+        : acc(acc_), n_valid(n_valid_), nb(nb_), k(k_), km1(k_ - 1u), batch_idx(batch_idx_), lane(lane_),
+          below((1ull << lane_) - 1ull) {}
+
+    __device__ __forceinline__ void reload() {
+        if (ia - wa >= kReload) {
+            wa = ia;
+            a_ok = wa + lane < n_valid;
+            a_oth = a_ok ? acc.a_in_l(wa + lane) : 0u;
+            a_elv = a_ok ? acc.a_elem(wa + lane) : 0u;
+        }
+        if (il - wl >= kReload) {
+            wl = il;
+            l_ok = wl + lane < n_valid;
+            l_oth = l_ok ? acc.l_in_a(wl + lane) : 0u;
+            l_elv = l_ok ? acc.l_elem(wl + lane) : 0u;
+        }
+    }
+    // after consuming A[0,ia) and L[0,il) the picked set is {pos_A < ia} U {pos_L < il}
+    __device__ __forceinline__ bool cand_a() const { return a_ok && wa + lane >= ia && a_oth >= (uint32_t)il; }
+    __device__ __forceinline__ bool cand_l(int32_t ia_now) const {
+        return l_ok && wl + lane >= il && l_oth >= (uint32_t)ia_now;
+    }
+
+    // Several whole cycles at once (at the start of a cycle, nb - j >= k, k - 1 <= 64), as many as
+    // the two orders do not interfere inside the windows.  Returns the number of cycles taken.
+    __device__ __forceinline__ int32_t bulk() {
+        const bool ca = cand_a(), cl = cand_l(ia);
+        const uint64_t mask_a = __ballot(ca), mask_l = __ballot(cl);
+        const int32_t my_a = (int32_t)__popcll(mask_a & below), my_l = (int32_t)__popcll(mask_l & below);
+        const int32_t n_a = (int32_t)__popcll(mask_a), n_l = (int32_t)__popcll(mask_l);
+        int32_t c = n_a;
+        if ((int32_t)((uint32_t)n_l / km1) < c) c = (int32_t)((uint32_t)n_l / km1);
+        if ((int32_t)((uint32_t)(nb - j) / k) < c) c = (int32_t)((uint32_t)(nb - j) / k);
+        if (c <= 0) return 0;
+        {
+            // an oldest pick that also lies in the consumed stretch of the longest-match order (or the
+            // other way round) makes the two streams interact: only the cycles before the first such
+            // pick are taken at once (a shorter stretch cannot create new clashes)
+            const int32_t take_l = c * (int32_t)km1;
+            const int32_t ia_end = wa + (int32_t)__builtin_ctzll(__ballot(ca && my_a == c - 1)) + 1;
+            const int32_t il_end = wl + (int32_t)__builtin_ctzll(__ballot(cl && my_l == take_l - 1)) + 1;
+            const uint64_t clash_a = __ballot(ca && my_a < c && a_oth < (uint32_t)il_end);
+            const uint64_t clash_l = __ballot(cl && my_l < take_l && l_oth < (uint32_t)ia_end);
+            if (clash_a) {
+                const int32_t before = (int32_t)__popcll(mask_a & ((1ull << __builtin_ctzll(clash_a)) - 1ull));
+                c = before < c ? before : c;
+            }
+            if (clash_l) {
+                const int32_t before = (int32_t)((uint32_t)__popcll(mask_l & ((1ull << __builtin_ctzll(clash_l)) - 1ull)) / km1);
+                c = before < c ? before : c;
+            }
+        }
+        if (c <= 0) return 0;
+        const int32_t take_l = c * (int32_t)km1;
+        if (ca && my_a < c) batch_idx[j + my_a * (int32_t)k] = (int32_t)a_elv;
+        if (cl && my_l < take_l) {
+            const uint32_t cyc = (uint32_t)my_l / km1;
+            const uint32_t within = (uint32_t)my_l - cyc * km1;
+            batch_idx[j + (int32_t)(cyc * k + 1u + within)] = (int32_t)l_elv;
+        }
+        ia = wa + (int32_t)__builtin_ctzll(__ballot(ca && my_a == c - 1)) + 1;
+        il = wl + (int32_t)__builtin_ctzll(__ballot(cl && my_l == take_l - 1)) + 1;
+        j += c * (int32_t)k;
+        return c;
+    }
+
+    // One whole cycle in straight-line code (same preconditions): the oldest pick, then the k-1
+    // longest-match picks among what is left.  False when a window does not hold all of it.
+    __device__ __forceinline__ bool cycle() {
+        const uint64_t mask_a = __ballot(cand_a());
+        if (!mask_a) return false;
+        const int fa = (int)__builtin_ctzll(mask_a);
+        const int32_t ia_next = wa + fa + 1;
+        const bool cl = cand_l(ia_next);
+        const uint64_t mask_l = __ballot(cl);
+        if ((uint32_t)__popcll(mask_l) < km1) return false;
+        const int32_t my_l = (int32_t)__popcll(mask_l & below);
+        if (lane == fa) batch_idx[j] = (int32_t)a_elv;
+        if (cl && my_l < (int32_t)km1) batch_idx[j + 1 + my_l] = (int32_t)l_elv;
+        il = wl + (int32_t)__builtin_ctzll(__ballot(cl && my_l == (int32_t)km1 - 1)) + 1;
+        ia = ia_next;
+        j += (int32_t)k;
+        return true;
+    }
+
+    // One run at cycle position pos: a single oldest pick, or the longest-match picks up to the next
+    // oldest pick, as far as the window reaches.  Returns the picks made.
+    __device__ __forceinline__ int32_t run(uint32_t pos) {
+        const bool oldest = (pos == 0u);
+        const uint32_t len = oldest ? 1u : (k - pos);
+        const int32_t want = (int32_t)(len < (uint32_t)(nb - j) ? len : (uint32_t)(nb - j));
+        const bool cand = oldest ? cand_a() : cand_l(ia);
+        const uint64_t mask = __ballot(cand);
+        const int32_t my = (int32_t)__popcll(mask & below);
+        const int32_t avail = (int32_t)__popcll(mask);
+        const int32_t take = avail < want ? avail : want;
+        if (cand && my < take) batch_idx[j + my] = (int32_t)(oldest ? a_elv : l_elv);
+        int32_t next = (oldest ? wa : wl) + kWave;  // window exhausted: go on behind it
+        if (take == want) next = (oldest ? wa : wl) + (int32_t)__builtin_ctzll(__ballot(cand && my == take - 1)) + 1;
+        if (oldest) ia = next; else il = next;
+        j += take;
+        if (take < want && next >= n_valid) j = nb;  // unreachable while nb <= n_valid
+        return take;
+    }
+};
+
+template <class Acc>
 __device__ __forceinline__ void two_cursor_walk(const Acc &acc, int32_t n_valid, int32_t nb, uint32_t k, uint32_t phase,
                                                 int32_t *__restrict__ batch_idx, int lane) {
-    int32_t ia = 0, il = 0, j = 0;
+    if (k == 1u) {  // oldest picks only: the first nb entries of that order
+        for (int32_t t = lane; t < nb; t += kWave) batch_idx[t] = (int32_t)acc.a_elem(t);
+        return;
+    }
+    TwoCursorWalk<Acc> w(acc, n_valid, nb, k, batch_idx, lane);
     uint32_t pos = phase;  // (phase + j) mod k, kept incrementally; phase < k on entry
-    const uint32_t km1 = k - 1u;
-    while (j < nb) {
-        // ---- several whole cycles at once, when the two orders do not interfere inside the window
-        if (pos == 0u && (uint32_t)(nb - j) >= k && km1 <= (uint32_t)kWave) {
-            const int32_t ra = ia + lane, rl = il + lane;
-            uint32_t a_other = 0, l_other = 0, a_el = 0, l_el = 0;
-            bool cand_a = false, cand_l = false;
-            if (ra < n_valid) { a_other = acc.a_in_l(ra); a_el = acc.a_elem(ra); cand_a = a_other >= (uint32_t)il; }
-            if (rl < n_valid) { l_other = acc.l_in_a(rl); l_el = acc.l_elem(rl); cand_l = l_other >= (uint32_t)ia; }
-            const uint64_t mask_a = __ballot(cand_a), mask_l = __ballot(cand_l);
-            const int32_t n_a = (int32_t)__popcll(mask_a), n_l = (int32_t)__popcll(mask_l);
-            int32_t c = n_a;
-            if ((int32_t)((uint32_t)n_l / km1) < c) c = (int32_t)((uint32_t)n_l / km1);
-            if ((int32_t)((uint32_t)(nb - j) / k) < c) c = (int32_t)((uint32_t)(nb - j) / k);
-            if (c > 0) {
-                const int32_t my_a = (int32_t)__popcll(mask_a & ((1ull << lane) - 1ull));
-                const int32_t my_l = (int32_t)__popcll(mask_l & ((1ull << lane) - 1ull));
-                {
-                    // an oldest pick that also lies in the consumed stretch of the longest-match order (or
-                    // the other way round) makes the two streams interact: only the cycles before the
-                    // first such pick are taken at once (a shorter stretch cannot create new clashes)
-                    const int32_t take_l = c * (int32_t)km1;
-                    const bool ch_a = cand_a && my_a < c;
-                    const bool ch_l = cand_l && my_l < take_l;
-                    const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
-                    const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
-                    const uint64_t clash_a = __ballot(ch_a && a_other < (uint32_t)il_end);
-                    const uint64_t clash_l = __ballot(ch_l && l_other < (uint32_t)ia_end);
-                    if (clash_a) {
-                        const int32_t before = (int32_t)__popcll(mask_a & ((1ull << __builtin_ctzll(clash_a)) - 1ull));
-                        c = before < c ? before : c;
-                    }
-                    if (clash_l) {
-                        const int32_t before = (int32_t)((uint32_t)__popcll(mask_l & ((1ull << __builtin_ctzll(clash_l)) - 1ull)) / km1);
-                        c = before < c ? before : c;
-                    }
-                }
-                if (c > 0) {
-                    const int32_t take_l = c * (int32_t)km1;
-                    const bool ch_a = cand_a && my_a < c;
-                    const bool ch_l = cand_l && my_l < take_l;
-                    const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
-                    const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
-                    if (ch_a) batch_idx[j + my_a * (int32_t)k] = (int32_t)a_el;
-                    if (ch_l) {
-                        uint32_t cyc = (uint32_t)my_l / km1;
-                        uint32_t within = (uint32_t)my_l - cyc * km1;
-                        batch_idx[j + (int32_t)(cyc * k + 1u + within)] = (int32_t)l_el;
-                    }
-                    ia = ia_end;
-                    il = il_end;
-                    j += c * (int32_t)k;
-                    continue;
-                }
+    int burst = 1;
+    while (w.j < nb) {
+        if (pos == 0u && w.km1 <= (uint32_t)kWave) {
+            // whole cycles: in bulk while that works; after an attempt that found a clash at once, a
+            // few cycles one by one (clashes come in stretches, e.g. when most of the queue is
+            // admitted, and a failed attempt costs as much as a cycle), then in bulk again
+            const int32_t j0 = w.j;
+            while ((uint32_t)(nb - w.j) >= k) {
+                w.reload();
+                if (w.bulk() == 0) break;
+                burst = 1;
             }
+            for (int t = 0; t < burst && (uint32_t)(nb - w.j) >= k; ++t) {
+                w.reload();
+                if (!w.cycle()) break;
+            }
+            burst = burst < 16 ? 2 * burst : 16;  // an isolated clash costs one single cycle, a stretch 1, 2, 4, 8, 16, 16 ...
+            if (w.j != j0) continue;
         }
-        // ---- one run: a single oldest pick, or the longest-match picks up to the next oldest pick
-        const bool oldest = (pos == 0u);
-        const uint32_t run = oldest ? 1u : (k - pos);
-        int32_t want = (int32_t)(run < (uint32_t)(nb - j) ? run : (uint32_t)(nb - j));
-        pos = oldest ? (k > 1u ? 1u : 0u) : 0u;  // position in the cycle after this run
-        while (want > 0) {
-            const int32_t cur = oldest ? ia : il;
-            const int32_t r = cur + lane;
-            bool cand = false;
-            uint32_t elem = 0;
-            if (r < n_valid) {
-                // after consuming A[0,ia) and L[0,il) the picked set is {pos_A < ia} U {pos_L < il}
-                uint32_t other = oldest ? acc.a_in_l(r) : acc.l_in_a(r);
-                cand = oldest ? (other >= (uint32_t)il) : (other >= (uint32_t)ia);
-                elem = oldest ? acc.a_elem(r) : acc.l_elem(r);
-            }
-            const uint64_t mask = __ballot(cand);
-            const int32_t avail = (int32_t)__popcll(mask);
-            const int32_t take = avail < want ? avail : want;
-            const int32_t my = (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (cand && my < take) batch_idx[j + my] = (int32_t)elem;
-            int32_t adv = kWave;  // window exhausted: keep looking further along the order
-            if (take == want) {
-                // advance just past the last candidate taken
-                const uint64_t lastm = __ballot(cand && my == take - 1);
-                adv = (int32_t)__builtin_ctzll(lastm) + 1;
-            }
-            if (oldest) ia += adv; else il += adv;
-            j += take;
-            want -= take;
-            if ((oldest ? ia : il) >= n_valid && want > 0) { want = 0; j = nb; }  // unreachable while nb <= n
-        }
+        w.reload();
+        pos += (uint32_t)w.run(pos);
+        if (pos >= k) pos -= k;
     }
 }
 
