@@ -75,6 +75,82 @@ __global__ __launch_bounds__(256) void k_sel_ranks(const uint32_t *__restrict__ 
     }
 }
 
+// ---- both orders of a short queue in one workgroup ----
+// Up to kSmallOrdersN entries: two bitonic sorts in LDS on two-word keys, (arrival, index) for the
+// oldest-first order and (inverted score | tie key, oldest-first rank) for the longest-match order,
+// instead of the ~40 launches of the radix sorts below.
+constexpr int kSmallOrdersN = 4096;
+constexpr int kSmallOrdersThreads = 1024;
+
+__device__ __forceinline__ void bitonic_sort_pairs(uint64_t *hi, uint32_t *lo, int32_t np2, int tid) {
+    for (int32_t size = 2; size <= np2; size <<= 1) {
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int32_t t = tid; t < (np2 >> 1); t += kSmallOrdersThreads) {
+                const int32_t a = 2 * t - (t & (stride - 1));
+                const int32_t b = a + stride;
+                const bool up = ((a & size) == 0);
+                const uint64_t ha = hi[a], hb = hi[b];
+                const uint32_t la = lo[a], lb = lo[b];
+                const bool gt = ha > hb || (ha == hb && la > lb);
+                if (gt == up) { hi[a] = hb; hi[b] = ha; lo[a] = lb; lo[b] = la; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(kSmallOrdersThreads) void k_orders_small(const uint64_t *__restrict__ arrival,
+                                                                      const int32_t *__restrict__ score,
+                                                                      const uint32_t *__restrict__ tie_key, LiveN nn,
+                                                                      int want_l, uint32_t *__restrict__ order_a,
+                                                                      uint32_t *__restrict__ order_l,
+                                                                      uint32_t *__restrict__ rank_a,
+                                                                      uint32_t *__restrict__ rank_l) {
+    __shared__ uint64_t hi[kSmallOrdersN];
+    __shared__ uint32_t lo[kSmallOrdersN];
+    __shared__ uint32_t oa[kSmallOrdersN];
+    int32_t n = nn.get();
+    n = n < kSmallOrdersN ? n : kSmallOrdersN;
+    const int tid = threadIdx.x;
+    int32_t np2 = 1;
+    while (np2 < n) np2 <<= 1;
+    for (int32_t i = tid; i < np2; i += kSmallOrdersThreads) {
+        hi[i] = i < n ? arrival[i] : ~0ull;
+        lo[i] = i < n ? (uint32_t)i : 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    bitonic_sort_pairs(hi, lo, np2, tid);
+    for (int32_t r = tid; r < n; r += kSmallOrdersThreads) {
+        const uint32_t i = lo[r];
+        oa[r] = i;
+        order_a[r] = i;
+        rank_a[i] = (uint32_t)r;
+    }
+    if (!want_l) return;
+    __syncthreads();
+    // longest-match keys in oldest-first order; the second word (that rank) settles equal keys by
+    // arrival, then index
+    for (int32_t r = tid; r < np2; r += kSmallOrdersThreads) {
+        uint64_t key = ~0ull;
+        if (r < n) {
+            const uint32_t i = oa[r];
+            int32_t m = score[i];
+            if (m < 0) m = 0;
+            const uint64_t inv = (uint64_t)(0x7FFFFFFFu - (uint32_t)m);
+            key = tie_key ? ((inv << 32) | (uint64_t)tie_key[i]) : inv;
+        }
+        hi[r] = key;
+        lo[r] = r < n ? (uint32_t)r : 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    bitonic_sort_pairs(hi, lo, np2, tid);
+    for (int32_t p = tid; p < n; p += kSmallOrdersThreads) {
+        const uint32_t i = oa[lo[p]];
+        order_l[p] = i;
+        rank_l[i] = (uint32_t)p;
+    }
+}
+
 // ---- stable LSD radix sort, 8-bit digits: histogram / scan / scatter per pass ----
 __global__ __launch_bounds__(kSortThreads) void k_rs_hist(const uint64_t *__restrict__ key, LiveN nn, int shift,
                                                           uint32_t *__restrict__ hist, int32_t nblk) {
@@ -1027,6 +1103,15 @@ int build_select_orders(const uint64_t *arrival, const int32_t *score, const uin
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
     const LiveN nn{n, n_live};
     const uint32_t *order_a = ws.val_a, *order_l = ws.val_a;
+    if (n > 0 && n <= kSmallOrdersN) {
+        hipLaunchKernelGGL(k_orders_small, dim3(1), dim3(kSmallOrdersThreads), 0, stream, arrival, score, tie_key, nn,
+                           want_l ? 1 : 0, ws.val_a, ws.val_c, ws.rank_a, ws.rank_l);
+        out->order_a = ws.val_a;
+        out->order_l = want_l ? ws.val_c : ws.val_a;
+        out->rank_a = ws.rank_a;
+        out->rank_l = ws.rank_l;
+        return check_launch();
+    }
     if (n > 0) {
         unsigned g = (unsigned)((n + 255) / 256);
         hipLaunchKernelGGL(k_sel_init, dim3(g), dim3(256), 0, stream, arrival, nn, ws.key_a, ws.val_a);
