@@ -212,11 +212,16 @@ def bench_def3_sweep(args, n, rep, u, d, c_num, c_den) -> int:
     cap, budget, seed = 2048, u + d, 99
     cfg = K.size_config(0, 0, budget, 1, u + d, extra_prompts=2)
     rows, gpu_s, cpu_s, steps = [], 0.0, 0.0, 0
-    for s_gap in (u // 6, u // 2, 5 * u // 6, 7 * u // 6, 5 * u // 3):
+    # late start (everything has arrived: Thm. 2), then service from time 0 at gaps between the cost of
+    # a query with full reuse and with none (the request-rate axis of the paper's TTFT plots)
+    full, none = u // rep + d, u + d
+    cases = [(g, True) for g in (u // 6, u // 2, 5 * u // 6, 7 * u // 6, 5 * u // 3)]
+    cases += [(g, False) for g in (full + (none - full) // 8, (full + none) // 2, none - (none - full) // 8, none + none // 8)]
+    for s_gap, late in cases:
         p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=W.generators.SEED_BASE + 100)
         p.arrival[:] = p.arrival * np.uint64(c_den)
         q = K.DeviceQueries.from_host(p, dev)
-        t_start = s_gap * n * c_den
+        t_start = s_gap * n * c_den if late else 0
         arms = [1, 2, rep, 2 * rep, K.KLPM_K_INFINITY]
         # the fixed values of k, then k chosen per window of 20 steps by the device-side epsilon-greedy
         # rule over the same values (a quarter of the pulls exploring)
@@ -241,7 +246,8 @@ def bench_def3_sweep(args, n, rep, u, d, c_num, c_den) -> int:
             assert r.ttft.tolist() == ttft.tolist(), f"GPU and oracle disagree at s={s_gap} k={k}"
             steps += n
             t = np.sort(ttft) / c_den
-            rows.append({"s": s_gap, "k": "inf" if k == K.KLPM_K_INFINITY else k,
+            rows.append({"s": s_gap, "start": "after the last arrival" if late else "0",
+                         "k": "inf" if k == K.KLPM_K_INFINITY else k,
                          **{name: round(float(t[int(np.ceil(x * n)) - 1])) for name, x in
                             (("p50", 0.5), ("p95", 0.95), ("p99", 0.99), ("max", 1.0))}})
             if ad is not None:
@@ -255,7 +261,7 @@ def bench_def3_sweep(args, n, rep, u, d, c_num, c_den) -> int:
         "ms_per_step": gpu_s / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"def3-n{n}-rep{rep}-u{u}-d{d}-gap-sweep", "batch": 1, "kv_budget_tokens": budget,
-                   "c_attn": c_num / c_den, "queue_cap": cap, "start": "after the last arrival", "ties": "random"},
+                   "c_attn": c_num / c_den, "queue_cap": cap, "ties": "random"},
         "sweep_ttft_token_times": rows,
         "roofline": None,  # launch-latency bound at this size; see the large configuration
         "cpu_baseline": {"value": steps / cpu_s, "unit": "steps/s", "cores": 1, "kind": "oracle",
