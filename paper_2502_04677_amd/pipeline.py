@@ -181,7 +181,10 @@ class OnlineRun:
         s.match(q)
         # this queue is append-only with stable removal
         s.select(q, k, batch, fifo=True, k_dev=None if adaptive is None else adaptive.k_dev)
-        s.commit(q, batch)
+        # (the host knows the queue length here, so the commit is sized for what can be admitted: its
+        # bound on the LRU clock, which sets the number of eviction passes, then grows no faster than
+        # the clock itself)
+        s.commit(q, min(batch, self.n_host))
         self.advance(batch, new_ids)
         if adaptive is not None:
             adaptive.observe(served, s.batch_idx, s.n_selected, batch, self.ttft)

@@ -626,6 +626,18 @@ def test_timed_gap_sweep_separates_the_policies_as_the_theory_says():
             worst[k], median[k] = int(r.ttft.max()), oracle.percentile_nearest_rank(r.ttft, 0.5)
         assert worst[rep] < worst[K_INF] and worst[rep] < worst[1], (s_gap, worst)
         assert median[K_INF] <= median[rep] <= median[1], (s_gap, median)
+    # served while arriving, at a gap between the cost of a query with full reuse and with none (an
+    # overloaded request rate): k = 2 has the lowest P99, as in the paper's serving experiments (Sec. 5.1)
+    s_gap = (u // rep + d + u + d) // 2
+    p, _ = W.shuffled_queue(n, u, rep, d, s_gap, seed=12)
+    p.arrival[:] = p.arrival * np.uint64(c_den)
+    p99, median = {}, {}
+    for k in (1, 2, K_INF):
+        _say(f"timed gap sweep while arriving: s={s_gap} k={k}")
+        r = _run_timed(p, k, 1, u + d, c_num=c_num, c_den=c_den, cap=2048, check_every=700, tie_seed=99)
+        p99[k], median[k] = (oracle.percentile_nearest_rank(r.ttft, x) for x in (0.99, 0.5))
+    assert p99[2] < p99[1] and p99[2] < p99[K_INF], p99
+    assert median[K_INF] < median[2] < median[1], median
 
 
 # ----------------------------------------------------------------------------- k read from device memory, adaptive k
