@@ -130,8 +130,7 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  *   tie_key             DEVICE [n] or NULL: decides between equal scores before the arrival time
  *                       does (smaller key first); kLPM_tie_keys fills it with uniform random numbers
  *                       for the random tie-break that the theory assumes (footnote of Sec. 4.2).
- *                       Oldest picks never look at it.  With tie keys the selection always takes
- *                       the sorting path, whatever `flags` says
+ *                       Oldest picks never look at it
  *   n_live              DEVICE [1] or NULL: as in kLPM_queries, the queue holds min(n, max(0, *n_live))
  *                       entries; n then only sizes the launches and the workspace
  *   k, k_dev            k_dev NULL: k is used.  Otherwise DEVICE [1]: the k that memory holds when

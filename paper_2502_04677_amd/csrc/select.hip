@@ -734,22 +734,48 @@ constexpr int kFqThreads = 256;
 constexpr int kFqTile = 1024;       // queue entries per workgroup
 constexpr int kFqLevelBits = 13;    // bits of match length resolved per histogram kernel
 constexpr int kFqBins = 1 << kFqLevelBits;
-constexpr int kFqMaxLevels = 3;     // 31 bits at most
+constexpr int kFqMaxLevels = 5;     // 31 bits of score (+ 32 bits of tie key) at most
 constexpr int kFqSingleBlockN = 8192;  // shorter queues are cheaper in the single-workgroup kernel
 
+// What the longest-match picks maximise, as one unsigned number ("goodness"): the score, or with
+// tie keys (score, inverted tie key) - a smaller tie key wins among equal scores.
+template <bool TIE>
+struct FqKey;
+template <>
+struct FqKey<false> {
+    using G = uint32_t;
+    const int32_t *__restrict__ score;
+    __device__ __forceinline__ G at(int32_t i, int32_t &m) const {
+        m = score[i];
+        m = m < 0 ? 0 : m;
+        return (uint32_t)m;
+    }
+};
+template <>
+struct FqKey<true> {
+    using G = uint64_t;
+    const int32_t *__restrict__ score;
+    const uint32_t *__restrict__ tie;
+    __device__ __forceinline__ G at(int32_t i, int32_t &m) const {
+        m = score[i];
+        m = m < 0 ? 0 : m;
+        return ((uint64_t)(uint32_t)m << 32) | (uint64_t)(0xFFFFFFFFu - tie[i]);
+    }
+};
+
 struct FqMeta {        // zeroed before every call
-    int32_t violated;  // arrival order broken, or a match length above the caller's bound
-    int32_t fixed_hi;  // decided high bits of the nb-th largest match length
+    uint64_t fixed_hi; // decided high bits of the nb-th largest goodness
+    int32_t violated;  // arrival order broken, or a score above the caller's bound
     int32_t need;      // winners still to be found among the entries that share fixed_hi
     int32_t done[kFqMaxLevels + 1];  // finished workgroups per kernel
-    int32_t pad;
 };
 
 struct FqWs {
     FqMeta *meta;
     uint32_t *hist;      // [kFqMaxLevels][kFqBins]
-    int32_t *blockcnt;   // [n_blocks][2]: entries above m*, entries equal to m*
-    uint64_t *cand;      // [kFifoMaxBatch] winners as (inverted match length, index)
+    int32_t *blockcnt;   // [n_blocks][2]: entries above g*, entries equal to g*
+    uint64_t *cand;      // [kFifoMaxBatch] winners as inverted goodness (no tie keys: with the index below it)
+    uint32_t *cand_idx;  // [kFifoMaxBatch] with tie keys: the winners' indices
 };
 
 __device__ __forceinline__ bool fq_last_block(int32_t *counter) {
@@ -764,12 +790,13 @@ __device__ __forceinline__ bool fq_last_block(int32_t *counter) {
     return s_last != 0;
 }
 
-// Histogram of one 13-bit digit of the match lengths that share the digits fixed so far; level 0 also
-// checks the arrival order.  The last workgroup to finish fixes the digit of the nb-th largest length.
-__global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restrict__ arrival,
-                                                       const int32_t *__restrict__ match_len, LiveN nn, int32_t batch,
-                                                       int32_t max_match, int level, int shift, int width,
+// Histogram of one 13-bit digit of the goodness values that share the digits fixed so far; level 0
+// also checks the arrival order.  The last workgroup to finish fixes the digit of the nb-th largest.
+template <bool TIE>
+__global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restrict__ arrival, FqKey<TIE> key, LiveN nn,
+                                                       int32_t batch, int32_t max_match, int level, int shift, int width,
                                                        FqWs ws) {
+    using G = typename FqKey<TIE>::G;
     const int32_t n = nn.get();
     __shared__ uint32_t h[kFqBins];
     __shared__ int32_t part[kFqThreads / kWave];
@@ -779,23 +806,23 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
     for (int i = tid; i < (1 << width); i += kFqThreads) h[i] = 0;
     if (tid == 0) { s_viol = 0; s_pick = 0; s_above = 0; }
     __syncthreads();
-    const int32_t fixed_hi = (level == 0) ? 0 : ws.meta->fixed_hi;
+    const G fixed_hi = (level == 0) ? (G)0 : (G)ws.meta->fixed_hi;
     const int32_t base = blockIdx.x * kFqTile;
     bool viol = false;
 #pragma unroll
     for (int r = 0; r < kFqTile / kFqThreads; ++r) {
         int32_t i = base + r * kFqThreads + tid;
         bool in = i < n;
-        int32_t m = in ? match_len[i] : 0;
-        m = m < 0 ? 0 : m;
+        int32_t m = 0;
+        const G g = in ? key.at(i, m) : (G)0;
         if (level == 0 && in) {
             viol |= m > max_match;
             viol |= (i + 1 < n) && (arrival[i] > arrival[i + 1]);
         }
-        in = in && ((m >> (shift + width)) == fixed_hi || level == 0);
-        int32_t bin = (m >> shift) & ((1 << width) - 1);
-        // lanes that share the first active lane's bin are added once (match lengths cluster and
-        // same-address LDS atomics serialise)
+        in = in && (level == 0 || (g >> (shift + width)) == fixed_hi);  // (level > 0: shift + width < bits of G)
+        int32_t bin = (int32_t)((g >> shift) & (G)((1 << width) - 1));
+        // lanes that share the first active lane's bin are added once (scores cluster and same-address
+        // LDS atomics serialise)
         uint64_t act = __ballot(in);
         if (act) {
             int32_t lead = __shfl(bin, (int)__builtin_ctzll(act));
@@ -843,46 +870,51 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
     }
     __syncthreads();
     if (tid == 0) {
-        ws.meta->fixed_hi = (fixed_hi << width) | s_pick;
+        ws.meta->fixed_hi = ((uint64_t)fixed_hi << width) | (uint64_t)(uint32_t)s_pick;
         ws.meta->need = need - s_above;
     }
 }
 
-// Per workgroup: how many of its entries lie above m* and how many equal it.
-__global__ __launch_bounds__(kFqThreads) void k_fq_count(const int32_t *__restrict__ match_len, LiveN nn, FqWs ws) {
+// Per workgroup: how many of its entries lie above g* and how many equal it.
+template <bool TIE>
+__global__ __launch_bounds__(kFqThreads) void k_fq_count(FqKey<TIE> key, LiveN nn, FqWs ws) {
+    using G = typename FqKey<TIE>::G;
     const int32_t n = nn.get();
     __shared__ int32_t s_gt, s_eq;
     const int tid = threadIdx.x;
     if (tid == 0) { s_gt = 0; s_eq = 0; }
     __syncthreads();
-    const int32_t m_star = ws.meta->fixed_hi;
+    const G g_star = (G)ws.meta->fixed_hi;
     const int32_t base = blockIdx.x * kFqTile;
     int32_t gt = 0, eq = 0;
 #pragma unroll
     for (int r = 0; r < kFqTile / kFqThreads; ++r) {
         int32_t i = base + r * kFqThreads + tid;
-        int32_t m = (i < n) ? match_len[i] : -1;
-        m = (m < 0 && i < n) ? 0 : m;
-        gt += (int32_t)__popcll(__ballot(m > m_star));
-        eq += (int32_t)__popcll(__ballot(i < n && m == m_star));
+        int32_t m;
+        const bool in = i < n;
+        const G g = in ? key.at(i, m) : (G)0;
+        gt += (int32_t)__popcll(__ballot(in && g > g_star));
+        eq += (int32_t)__popcll(__ballot(in && g == g_star));
     }
     if ((tid & (kWave - 1)) == 0) { atomicAdd(&s_gt, gt); atomicAdd(&s_eq, eq); }
     __syncthreads();
     if (tid == 0) { ws.blockcnt[2 * blockIdx.x] = s_gt; ws.blockcnt[2 * blockIdx.x + 1] = s_eq; }
 }
 
-// Winners = every entry above m* and the first `need` entries (by index) equal to m*; written in
+// Winners = every entry above g* and the first `need` entries (by index) equal to g*; written in
 // index order at positions given by prefix counts (no atomics).
-__global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restrict__ match_len, LiveN nn, FqWs ws) {
+template <bool TIE>
+__global__ __launch_bounds__(kFqThreads) void k_fq_gather(FqKey<TIE> key, LiveN nn, FqWs ws) {
+    using G = typename FqKey<TIE>::G;
     const int32_t n = nn.get();
     __shared__ int32_t part[kFqThreads / kWave];
     __shared__ int32_t s_rank, s_out;
     __shared__ int32_t w_eq[kFqThreads / kWave], w_win[kFqThreads / kWave];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wv = tid / kWave;
-    const int32_t m_star = ws.meta->fixed_hi;
+    const G g_star = (G)ws.meta->fixed_hi;
     const int32_t need = ws.meta->need;
-    // entries equal to m* and winners in the workgroups before this one
+    // entries equal to g* and winners in the workgroups before this one
     {
         int32_t eq_b = 0, gt_b = 0;
         for (int32_t b = tid; b < (int32_t)blockIdx.x; b += kFqThreads) {
@@ -903,9 +935,9 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restr
     for (int r = 0; r < kFqTile / kFqThreads; ++r) {
         int32_t i = base + r * kFqThreads + tid;
         bool in = i < n;
-        int32_t m = in ? match_len[i] : 0;
-        m = m < 0 ? 0 : m;
-        bool is_eq = in && m == m_star;
+        int32_t m = 0;
+        const G g = in ? key.at(i, m) : (G)0;
+        bool is_eq = in && g == g_star;
         uint64_t eqmask = __ballot(is_eq);
         // this row: counts of the wavefronts before mine
         __syncthreads();
@@ -917,7 +949,7 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restr
             eq_row += w_eq[w];
         }
         int32_t my_rank = rank + eq_before + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
-        bool win = in && (m > m_star || (is_eq && my_rank < need));
+        bool win = in && (g > g_star || (is_eq && my_rank < need));
         uint64_t wmask = __ballot(win);
         __syncthreads();
         if (lane == 0) w_win[wv] = (int32_t)__popcll(wmask);
@@ -929,15 +961,22 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_gather(const int32_t *__restr
         }
         if (win) {
             int32_t at = out + win_before + (int32_t)__popcll(wmask & ((1ull << lane) - 1ull));
-            if (at >= 0 && at < kFifoMaxBatch)
-                ws.cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+            if (at >= 0 && at < kFifoMaxBatch) {
+                if (TIE) {
+                    ws.cand[at] = ~(uint64_t)g;
+                    ws.cand_idx[at] = (uint32_t)i;
+                } else {
+                    ws.cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+                }
+            }
         }
         rank += eq_row;
         out += win_row;
     }
 }
 
-// Sort the nb winners by (-match_len, index) in LDS and run the two-cursor walk.
+// Sort the nb winners by (-score, [tie key,] index) in LDS and run the two-cursor walk.
+template <bool TIE>
 __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, int32_t batch, FqWs ws,
                                                             uint32_t *__restrict__ phase_inout,
                                                             int32_t *__restrict__ batch_idx,
@@ -962,7 +1001,10 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
     }
     int32_t np2 = 1;
     while (np2 < nb) np2 <<= 1;
-    for (int32_t i = tid; i < np2; i += kFifoThreads) cand[i] = (i < nb) ? ws.cand[i] : ~0ull;
+    for (int32_t i = tid; i < np2; i += kFifoThreads) {
+        cand[i] = (i < nb) ? ws.cand[i] : ~0ull;
+        if (TIE) l_elem[i] = (i < nb) ? ws.cand_idx[i] : 0xFFFFFFFFu;  // second key word: the index
+    }
     __syncthreads();
     for (int32_t size = 2; size <= np2; size <<= 1) {
         for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
@@ -970,14 +1012,20 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
                 int32_t a = 2 * t - (t & (stride - 1));
                 int32_t b = a + stride;
                 bool up = ((a & size) == 0);
-                uint64_t ka = cand[a], kb = cand[b];
-                if ((ka > kb) == up) { cand[a] = kb; cand[b] = ka; }
+                uint64_t key_a = cand[a], key_b = cand[b];
+                if (TIE) {
+                    const uint32_t ia = l_elem[a], ib = l_elem[b];
+                    const bool gt = key_a > key_b || (key_a == key_b && ia > ib);
+                    if (gt == up) { cand[a] = key_b; cand[b] = key_a; l_elem[a] = ib; l_elem[b] = ia; }
+                } else {
+                    if ((key_a > key_b) == up) { cand[a] = key_b; cand[b] = key_a; }
+                }
             }
             __syncthreads();
         }
     }
     for (int32_t p = tid; p < nb; p += kFifoThreads) {
-        l_elem[p] = (uint32_t)cand[p];
+        if (!TIE) l_elem[p] = (uint32_t)cand[p];
         a_in_l[p] = 0xFFFFFFFFu;
     }
     __syncthreads();
@@ -1027,10 +1075,12 @@ static void carve_fq(FqWs &f, char *base, int32_t n, size_t *used) {
     f.hist = (uint32_t *)take((size_t)kFqMaxLevels * kFqBins * 4);
     f.blockcnt = (int32_t *)take((size_t)nblk * 8);
     f.cand = (uint64_t *)take((size_t)kFifoMaxBatch * 8);
+    f.cand_idx = (uint32_t *)take((size_t)kFifoMaxBatch * 4);
     *used = o;
 }
 
-static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, LiveN nn, KArg k, int32_t batch,
+template <bool TIE>
+static int select_fifo_long(const uint64_t *arrival, FqKey<TIE> key, LiveN nn, KArg k, int32_t batch,
                             int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                             char *workspace, hipStream_t stream) {
     FqWs f;
@@ -1046,11 +1096,11 @@ static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, L
     while (mbits < 31 && (max_match >> mbits) != 0) ++mbits;
     if (mbits == 0) mbits = 1;
     const bool fcfs = (!k.dev && k.k == 1u);  // (a k read on the device takes the general kernels)
-    int shift = mbits, level = 0;
+    int shift = mbits + (TIE ? 32 : 0), level = 0;
     while (shift > 0 && level < kFqMaxLevels) {
         int width = shift < kFqLevelBits ? shift : kFqLevelBits;
         shift -= width;
-        hipLaunchKernelGGL(k_fq_hist, dim3(nblk), dim3(kFqThreads), 0, stream, arrival, match_len, n, batch, max_match,
+        hipLaunchKernelGGL(k_fq_hist<TIE>, dim3(nblk), dim3(kFqThreads), 0, stream, arrival, key, n, batch, max_match,
                            level, shift, width, f);
         ++level;
         if (fcfs) break;  // only the order check of level 0 is needed
@@ -1060,9 +1110,9 @@ static int select_fifo_long(const uint64_t *arrival, const int32_t *match_len, L
                            n_selected);
         return check_launch();
     }
-    hipLaunchKernelGGL(k_fq_count, dim3(nblk), dim3(kFqThreads), 0, stream, match_len, n, f);
-    hipLaunchKernelGGL(k_fq_gather, dim3(nblk), dim3(kFqThreads), 0, stream, match_len, n, f);
-    hipLaunchKernelGGL(k_fq_finish, dim3(1), dim3(kFifoThreads), 0, stream, n, k, batch, f, phase_inout, batch_idx,
+    hipLaunchKernelGGL(k_fq_count<TIE>, dim3(nblk), dim3(kFqThreads), 0, stream, key, n, f);
+    hipLaunchKernelGGL(k_fq_gather<TIE>, dim3(nblk), dim3(kFqThreads), 0, stream, key, n, f);
+    hipLaunchKernelGGL(k_fq_finish<TIE>, dim3(1), dim3(kFifoThreads), 0, stream, n, k, batch, f, phase_inout, batch_idx,
                        n_selected);
     return check_launch();
 }
@@ -1225,8 +1275,18 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, co
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
     const LiveN nn{n, n_live};
     const KArg k{k_host, k_dev};
-    // (tie keys reorder the longest-match order within equal scores: that needs the full sort)
-    if ((flags & KLPM_SELECT_FIFO) && !tie_key && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0) {
+    // (with tie keys a short queue goes to the one-workgroup sort of both orders further down)
+    const bool fifo = (flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0;
+    if (fifo && tie_key && n > kSmallOrdersN) {
+        size_t fq_need = 0;
+        FqWs probe;
+        carve_fq(probe, nullptr, n, &fq_need);
+        if (!workspace || workspace_bytes < fq_need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
+        return select_fifo_long<true>(arrival, FqKey<true>{match_len, tie_key}, nn, k, batch,
+                                      max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout, batch_idx, n_selected,
+                                      (char *)workspace, stream);
+    }
+    if (fifo && !tie_key) {
         if (n <= kFqSingleBlockN) {
             hipLaunchKernelGGL(k_select_fifo, dim3(1), dim3(kFifoThreads), 0, stream, arrival, match_len, nn, k, batch,
                                phase_inout, batch_idx, n_selected);
@@ -1236,8 +1296,9 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, co
         FqWs probe;
         carve_fq(probe, nullptr, n, &fq_need);
         if (!workspace || workspace_bytes < fq_need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
-        return select_fifo_long(arrival, match_len, nn, k, batch, max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout,
-                                batch_idx, n_selected, (char *)workspace, stream);
+        return select_fifo_long<false>(arrival, FqKey<false>{match_len}, nn, k, batch,
+                                       max_match > 0 ? max_match : 0x7FFFFFFF, phase_inout, batch_idx, n_selected,
+                                       (char *)workspace, stream);
     }
     SelectOrders ord;
     int rc = build_select_orders(arrival, match_len, tie_key, n, n_live, (k_dev || k_host != 1u) && batch > 0, workspace, workspace_bytes,

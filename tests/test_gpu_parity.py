@@ -703,6 +703,50 @@ def test_timed_runs_with_adaptive_k():
     _run_timed(p, 0, 2, 2 * 50, tie_seed=3, adaptive=([1, 4, K_INF], 2, 1 << 30, 9))
 
 
+def test_adaptive_k_observe_flags_what_it_cannot_read():
+    """Entries of a batch that cannot be read (queue index or query id out of range, a TTFT that was
+    never written) are left out of the window and flagged; an over-long batch is cut to the capacity
+    given.  The rest of the batch still counts."""
+    dev = "cuda:0"
+    cap = 16
+    qd = K.DeviceQueue.empty(cap, dev)
+    qd.id[:6] = torch.tensor([5, 2, 9, 40, -3, 1], dtype=torch.int32, device=dev)
+    qd.n.fill_(6)
+    ttft = torch.full((12,), -1, dtype=torch.int64, device=dev)
+    ttft[5], ttft[2], ttft[9], ttft[1] = 700, 300, 1 << 40, 50
+    n_sel = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def pull(idx, n, batch_cap):
+        ad = K.AdaptiveK([3, 7], 1, 0, 0)
+        bi = torch.tensor(idx + [0] * (8 - len(idx)), dtype=torch.int32, device=dev)
+        n_sel.fill_(n)
+        ad.observe(qd, bi, n_sel, batch_cap, ttft)
+        return ad.read()
+
+    st = pull([0, 1], 2, 8)
+    assert (st.device_error, st.pulls, st.count[0], st.cost[0], st.arm, st.k) == (0, 1, 1, 700, 1, 7)
+    st = pull([1, 2, 0], 3, 8)
+    assert (st.device_error, st.cost[0]) == (0, 1 << 40)
+    st = pull([1, 3], 2, 8)  # id 40 has no TTFT slot
+    assert (st.device_error, st.pulls, st.cost[0]) == (4, 1, 300)
+    st = pull([4, 5], 2, 8)  # negative id
+    assert (st.device_error, st.cost[0]) == (4, 50)
+    st = pull([7, 1], 2, 8)  # queue index beyond the queue's length
+    assert (st.device_error, st.cost[0]) == (4, 300)
+    st = pull([-1, 0], 2, 8)
+    assert (st.device_error, st.cost[0]) == (4, 700)
+    qd.id[6] = 3  # a query that was never admitted: its TTFT is still -1
+    qd.n.fill_(7)
+    st = pull([6, 0], 2, 8)
+    assert (st.device_error, st.cost[0]) == (4, 700)
+    st = pull([0, 1, 5], 3, 2)  # more selected than the capacity given: the first two count
+    assert (st.device_error, st.pulls, st.cost[0]) == (8, 1, 700)
+    st = pull([0], 0, 8)  # nobody admitted: not a pull
+    assert (st.device_error, st.pulls, st.arm, st.k, st.steps_in_window) == (0, 0, 0, 3, 0)
+    st = pull([0], -5, 8)
+    assert (st.device_error, st.pulls) == (0, 0)
+
+
 def test_adaptive_k_at_the_paper_shape():
     """n = 2000, 4 queries per shared prefix, u = d = 3000, served after everything has arrived with
     random ties; five arms, windows of 20 steps, a quarter of the pulls exploring."""
@@ -806,6 +850,19 @@ def test_select_with_random_ties_and_hit_rate_score():
                             assert got_n == idx_ref.shape[0]
                             assert out[:got_n].cpu().numpy().tolist() == idx_ref.tolist(), (n, which, k, batch, flags)
                             assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
+        # tie keys from a tiny range: most ties between equal scores fall through to arrival and index
+        K.kLPM_tie_keys(99, 5, None, n, tie)
+        tie.bitwise_and_(3)
+        tie_ref = oracle.tie_keys(99, 5, np.arange(n)) & np.uint32(3)
+        for k in (2, 0):
+            for flags in (0, K.KLPM_SELECT_FIFO):
+                out = torch.full((512,), -3, dtype=torch.int32, device=dev)
+                phase.fill_(1)
+                live_d.fill_(n)
+                K.kLPM_select(d_arr, d_m, n, k, 512, phase, out, nsel, ws, ws_bytes, flags=flags, max_match=4096,
+                              n_live=live_d, tie_key=tie)
+                idx_ref, ph_ref = oracle.select(arrival, m, k, 512, 1, tie_key=tie_ref)
+                assert out[: int(nsel.item())].cpu().numpy().tolist() == idx_ref.tolist(), (n, k, flags)
         # the hit-rate score without tie keys also runs on the arrival-ordered paths
         for k in (3, 0):
             out = torch.full((64,), -3, dtype=torch.int32, device=dev)
