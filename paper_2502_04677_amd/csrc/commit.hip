@@ -413,10 +413,11 @@ __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key,
 // Returns the new upper node (wave-uniform) or -1.
 __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs &ws, int32_t j, int32_t c,
                                               const NodeRec &rec, int32_t s, int32_t at, uint64_t tick, int32_t new_id,
-                                              int lane) {
+                                              int lane, bool have_low = false, int32_t low_known = 0) {
     int32_t up = -1;
     if (lane == 0) {
-        int32_t low_first = tv.pool[rec.edge_off + at];  // first token of the lower part (tokens never move)
+        // first token of the lower part (tokens never move)
+        int32_t low_first = have_low ? low_known : tv.pool[rec.edge_off + at];
         up = new_id;
         if (up < 0) flag_error(tv.st, 1u);
         if (up > 0) {
@@ -440,6 +441,27 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs
     up = uni(__shfl(up, 0));
     __syncthreads();
     return up;
+}
+
+// wave_common_prefix(a, b, lim) that also hands back, from the same round trip, the tokens the
+// insertion needs next: at a mismatch j < lim the two differing tokens a[j], b[j]; when all lim
+// positions agree, a[lim] (if a has a_len > lim tokens) and b[lim] (if b has b_len > lim).
+// Values that do not exist come back as -1.
+__device__ __forceinline__ int32_t common_prefix_and_next(const int32_t *__restrict__ a, int32_t a_len,
+                                                          const int32_t *__restrict__ b, int32_t b_len, int32_t lim,
+                                                          int lane, int32_t &a_tok, int32_t &b_tok) {
+    // the two tokens behind the compared span, requested together with the first window
+    const int32_t a_after = a[lim < a_len ? lim : a_len - 1];
+    const int32_t b_after = b[lim < b_len ? lim : b_len - 1];
+    const int32_t jj = wave_common_prefix(a, b, lim, lane);
+    if (jj < lim) {  // (re-reads two tokens of a window that has just been fetched: served by the cache)
+        a_tok = uni(a[jj]);
+        b_tok = uni(b[jj]);
+    } else {
+        a_tok = lim < a_len ? uni(a_after) : -1;
+        b_tok = lim < b_len ? uni(b_after) : -1;
+    }
+    return jj;
 }
 
 __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t *__restrict__ batch_idx,
@@ -469,6 +491,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
 
     int32_t cur = e;
     int32_t d = m;
+    bool fresh = false;  // cur has just been created by this wavefront: nothing hangs below it yet
     if (e != kRoot && m < de_e) {
         // The match stopped inside the edge that node e had before this commit. Earlier prompts of
         // this group may have cut that edge into a chain of pieces ending in e; find the piece
@@ -492,14 +515,18 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
             int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane);
             if (up < 0) return;
             cur = up;
+            fresh = true;
         }
     }
-    // From here on every child met is a node created by this commit; compare for real.
+    // From here on every child met is a node created by this commit; compare for real.  Each
+    // compare brings along the token that decides the next step, a node that this wavefront has
+    // just made has no children to look up, and a node reached through its table slot is described
+    // by that slot: a member of a large group costs a lookup, a compare and its stores.
+    int32_t tok = tok_m;  // x[d] (the first unmatched token came with the plan)
     while (d < L) {
-        int32_t tok = (d == m) ? tok_m : uni(x[d]);  // (the first unmatched token came with the plan)
-        int32_t c, el;
-        int64_t eo;
-        int32_t s = slot_find_live(tv, make_key(cur, tok), c, el, eo);
+        int32_t c = -1, el = 0;
+        int64_t eo = 0;
+        const int32_t s = fresh ? -1 : slot_find_live(tv, make_key(cur, tok), c, el, eo);
         if (s < 0) {
             int32_t leaf = -1;
             if (lane == 0) {
@@ -524,22 +551,30 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
             d = L;
             break;
         }
-        int32_t lim = el < L - d ? el : L - d;
-        int32_t jj = wave_common_prefix(x + d, tv.pool + eo, lim, lane);
+        const int32_t lim = el < L - d ? el : L - d;
+        int32_t a_tok, b_tok;
+        const int32_t jj = common_prefix_and_next(x + d, L - d, tv.pool + eo, el, lim, lane, a_tok, b_tok);
         if (jj <= 0) {  // the first token matched by construction; anything else is corruption
             if (lane == 0) flag_error(st, kDevInternal);
             return;
         }
+        tok = a_tok;  // x[d + jj], if the prompt goes on
         if (jj == el) {
             cur = c;
             d += el;
             continue;
         }
-        NodeRec rec = load_node(tv, c);
-        int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane);
+        // split c after jj tokens; it hangs below cur, which ends at depth d, and the slot mirrors its edge
+        NodeRec rec;
+        rec.parent = cur;
+        rec.edge_len = el;
+        rec.depth_end = d + el;
+        rec.edge_off = eo;
+        const int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane, true, b_tok);
         if (up < 0) return;
         cur = up;
         d += jj;
+        fresh = true;
     }
     if (lane == 0) ws.end_node[j] = cur;
 }
