@@ -1278,18 +1278,19 @@ def test_eviction_cut_inside_a_tick_with_thousands_of_nodes():
 
 # ----------------------------------------------------------------------------- everything mixed
 @pytest.mark.parametrize("seed", range(6))
-def test_mixed_operations_against_the_oracle(seed):
+def test_mixed_operations_against_the_oracle(seed, n_query=120, max_batch=32, steps=25, max_len=10):
     """Random sequences of scheduling steps over small, densely sharing workloads, each step drawing
     its own variant: score (length / hit rate), ties (arrival / random keys), rescoring (per step /
     in batch), queue promise (arrival-ordered or not), prefill token budget, KV budget, protection
-    window and a device-side queue length.  Batch, phase and tree are compared after every step."""
+    window, a device-side queue length, k from the host or from device memory, and a commit that
+    matches again or takes the step's match.  Batch, phase and tree are compared after every step."""
     rng = np.random.default_rng(8800 + seed)
-    w = W.random_small(seed + 900, n_cache=12, n_query=120, vocab=3, max_len=10, arrival_hi=1000)
+    w = W.random_small(seed + 900, n_cache=12, n_query=n_query, vocab=3, max_len=max_len, arrival_hi=1000)
     hq = w.queries
     order = np.argsort(hq.arrival, kind="stable")
     hq = W.take_prompts(hq, order)  # a queue in arrival order, so that either selection path applies
     w = W.Workload("mixed", w.cache, hq, 2, 16, 1 << 40)
-    s, ref, q = _setup(w, max_batch=32)
+    s, ref, q = _setup(w, max_batch=max_batch, extra_prompts=steps * max_batch)
     dev = "cuda:0"
     score = torch.zeros(q.n, dtype=torch.int32, device=dev)
     tie = torch.zeros(q.n, dtype=torch.int32, device=dev)
@@ -1297,11 +1298,15 @@ def test_mixed_operations_against_the_oracle(seed):
     dws_bytes = K.kLPM_select_dynamic_workspace_bytes(q.n)
     dws = K.alloc_aligned(dws_bytes, dev)
     live_d = torch.zeros(1, dtype=torch.int32, device=dev)
+    k_d = torch.zeros(1, dtype=torch.int32, device=dev)
     phase = 0
-    for step in range(25):
+    for step in range(steps):
         live = int(rng.integers(1, q.n + 1))
         k = int(rng.choice([1, 2, 3, 5, K_INF]))
-        batch = int(rng.integers(1, 33))
+        k_d.copy_(torch.from_numpy(np.array([k], dtype=np.uint32).view(np.int32)))
+        k_dev = k_d.data_ptr() if rng.integers(0, 3) == 0 else None
+        k_arg = 0x5EED if k_dev is not None else k  # with a device-side k the host's value must not matter
+        batch = int(rng.integers(1, max_batch + 1))
         budget = int(rng.choice([1 << 40, 400, 150, 60]))
         protect = int(rng.choice([0, 0, 5, 40]))
         variant = rng.choice(["plain", "fifo", "rate", "ties", "dynamic", "token_budget"])
@@ -1313,23 +1318,24 @@ def test_mixed_operations_against_the_oracle(seed):
         s.set_phase(phase)
         arr = hq.arrival[:live]
         if variant == "dynamic":
-            K.kLPM_select_dynamic(ql, s.match_len, s.last_node, k, batch, s.phase, dyn, s.batch_idx, s.n_selected, dws, dws_bytes)
+            K.kLPM_select_dynamic(ql, s.match_len, s.last_node, k_arg, batch, s.phase, dyn, s.batch_idx, s.n_selected, dws,
+                                  dws_bytes, k_dev=k_dev)
             idx_ref, phase, sc_ref = oracle.select_dynamic(hq.tokens, hq.off[:live], hq.len[:live], arr, m_ref, k, batch, phase)
             assert dyn[:live].cpu().numpy().tolist() == sc_ref.tolist(), (step, variant)
         elif variant == "rate":
             K.kLPM_score_hit_rate(s.match_len, q.len, q.n, 20, score, n_live=live_d)
-            s.select(ql, k, batch, fifo=bool(rng.integers(0, 2)), score=score, score_max=1 << 20)
+            s.select(ql, k_arg, batch, fifo=bool(rng.integers(0, 2)), score=score, score_max=1 << 20, k_dev=k_dev)
             idx_ref, phase = oracle.select(arr, oracle.score_hit_rate(m_ref, hq.len[:live], 20), k, batch, phase)
         elif variant == "ties":
             K.kLPM_tie_keys(seed, step, None, q.n, tie, n_live=live_d)
-            s.select(ql, k, batch, tie_key=tie)
+            s.select(ql, k_arg, batch, tie_key=tie, fifo=bool(rng.integers(0, 2)), k_dev=k_dev)
             idx_ref, phase = oracle.select(arr, m_ref, k, batch, phase, tie_key=oracle.tie_keys(seed, step, np.arange(live)))
         else:
-            s.select(ql, k, batch, fifo=(variant != "plain"))
+            s.select(ql, k_arg, batch, fifo=(variant != "plain"), k_dev=k_dev)
             idx_ref, ph = oracle.select(arr, m_ref, k, batch, phase)
             if variant == "token_budget":
                 tb = int(rng.integers(0, 60))
-                K.kLPM_batch_token_budget(ql, s.match_len, s.batch_idx, s.n_selected, batch, tb, k, s.phase)
+                K.kLPM_batch_token_budget(ql, s.match_len, s.batch_idx, s.n_selected, batch, tb, k_arg, s.phase, k_dev=k_dev)
                 keep = oracle.token_budget_cut(idx_ref, hq.len, m_ref, tb)
                 ph = oracle.phase_after_cut(ph, idx_ref.shape[0], keep, k)
                 idx_ref = idx_ref[:keep]
@@ -1338,7 +1344,7 @@ def test_mixed_operations_against_the_oracle(seed):
         assert s.phase_value() == phase, (step, variant)
         K.kLPM_set_budget(s.tree, budget)
         K.kLPM_set_protect(s.tree, protect)
-        s.commit(ql, 32)
+        s.commit(ql, max_batch, reuse_match=bool(rng.integers(0, 2)))
         st_ref = ref.commit(hq.tokens, hq.off, hq.len, idx_ref, budget, protect=protect)
         st = s.read_stats()
         assert st.device_error == 0
