@@ -59,18 +59,47 @@ __device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
 // A commit may take the admitted prompts' matches from queue-wide match results the caller vouches
 // for.  The plan kernel checks the ranges that later addressing depends on (index, the prompt's span,
 // 0 <= m <= |x|, node id); -1 = refused.
-__device__ __forceinline__ int32_t hinted_match(const TreeView &tv, const QView &q, int32_t qi,
-                                                const int32_t *__restrict__ hint_len,
-                                                const int32_t *__restrict__ hint_node, int32_t &node) {
-    node = kRoot;
-    if (qi < 0 || qi >= live_count(q.n, q.n_live)) return -1;
-    const int64_t off = q.off[qi];
-    const int32_t L = q.len[qi];
-    const int32_t m = hint_len[qi], e = hint_node[qi];
-    if (off < 0 || L < 1 || L > tv.max_prompt_len || off + (int64_t)L > q.n_tokens) return -1;
-    if (m < 0 || m > L || e < 0 || e >= tv.max_nodes) return -1;
-    node = e;
-    return m;
+struct PlanIn {  // what the plan reads about one admitted prompt (off, L valid when m >= 0)
+    int64_t off;
+    int32_t qi, L, m, e;
+};
+
+// Reads that need nothing but the batch index, so that the first 1,024 prompts' can be in flight
+// while thread 0 is still deciding whether the commit goes ahead.  n_host bounds the index for the
+// loads; the device-side queue length is checked in plan_check.
+__device__ __forceinline__ PlanIn plan_load(const QView &q, const CommitWs &ws, const int32_t *__restrict__ batch_idx,
+                                            const int32_t *__restrict__ hint_len,
+                                            const int32_t *__restrict__ hint_node, int32_t j) {
+    PlanIn r;
+    r.qi = batch_idx[j];
+    r.off = 0; r.L = 0; r.m = -1; r.e = kRoot;
+    if (hint_len) {
+        if (r.qi >= 0 && r.qi < q.n) {
+            r.off = q.off[r.qi];
+            r.L = q.len[r.qi];
+            r.m = hint_len[r.qi];
+            r.e = hint_node[r.qi];
+        }
+    } else {
+        r.m = ws.bm_len[j];
+        r.e = ws.bm_node[j];
+        // (the match inside the commit has checked index and span of every admitted prompt; entries
+        // behind them are leftovers and only must not be followed out of bounds)
+        if (r.m >= 0 && r.qi >= 0 && r.qi < q.n) {
+            r.off = q.off[r.qi];
+            r.L = q.len[r.qi];
+        } else {
+            r.m = -1;
+        }
+    }
+    return r;
+}
+
+// Range checks of a match taken from the caller's results; false = refused.
+__device__ __forceinline__ bool plan_check(const TreeView &tv, const QView &q, const PlanIn &r) {
+    if (r.qi < 0 || r.qi >= live_count(q.n, q.n_live)) return false;
+    if (r.off < 0 || r.L < 1 || r.L > tv.max_prompt_len || r.off + (int64_t)r.L > q.n_tokens) return false;
+    return r.m >= 0 && r.m <= r.L && r.e >= 0 && r.e < tv.max_nodes;
 }
 
 // What else can be checked locally about such a match, done by one lane per admitted prompt beside
@@ -109,6 +138,8 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
     __shared__ int32_t s_nb;
     DevState *st = tv.st;
     const int tid = threadIdx.x;
+    PlanIn first;  // of prompt tid, requested before the admission is known (batch_idx holds batch_cap entries)
+    if (tid < batch_cap) first = plan_load(q, ws, batch_idx, hint_len, hint_node, tid);
     if (tid == 0) {
         uint32_t err = 0;
         int32_t nb = commit_gate(tv, n_selected, batch_cap, &err);
@@ -142,28 +173,28 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
             // the two node ids this prompt may use (at most one split and one leaf)
             ws.resv_id[2 * j] = reserved_id(tv, 2 * j);
             ws.resv_id[2 * j + 1] = reserved_id(tv, 2 * j + 1);
-            int32_t m;
+            PlanIn in = first;
+            if (base > 0) in = plan_load(q, ws, batch_idx, hint_len, hint_node, j);
             if (hint_len) {
-                int32_t e_h;
-                m = hinted_match(tv, q, batch_idx[j], hint_len, hint_node, e_h);
-                if (m < 0) atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
-                ws.bm_len[j] = m;
-                ws.bm_node[j] = e_h;
-            } else {
-                m = ws.bm_len[j];
+                if (!plan_check(tv, q, in)) {
+                    in.m = -1;
+                    in.e = kRoot;
+                    atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
+                }
+                ws.bm_len[j] = in.m;
+                ws.bm_node[j] = in.e;
             }
+            const int32_t m = in.m;
             if (m < 0) {
                 atomicOr(&bad, 1);
                 ws.gkey[j] = kNoGroup;
                 ws.end_node[j] = kRoot;
                 ws.next_tok[j] = -1;
             } else {
-                int32_t qi = batch_idx[j];
-                int32_t L = q.len[qi];
-                int32_t e = ws.bm_node[j];
+                const int32_t L = in.L, e = in.e;
                 tl = (int64_t)(L - m);
                 bool inside = m < tv.depth_end[e];
-                const int32_t nxt = (m < L) ? q.tokens[q.off[qi] + m] : -1;
+                const int32_t nxt = (m < L) ? q.tokens[in.off + m] : -1;
                 uint64_t g;
                 if (!inside && m == L) {
                     g = kNoGroup;  // already present and ending on a node boundary: ticks only
