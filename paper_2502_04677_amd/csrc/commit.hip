@@ -661,9 +661,10 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass) {
     DevState *st = tv.st;
     const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int32_t v0 = j < tv.max_batch ? ws.end_node[j] : kRoot;  // requested together with the state words
     if (!st->skip && j < st->nb) {
         const uint64_t t = st->clock0 + (uint64_t)j;
-        int32_t v = ws.end_node[j];
+        int32_t v = v0;
         for (int32_t guard = 0; guard <= tv.max_prompt_len && v > kRoot && v < tv.max_nodes; ++guard) {
             const int32_t up = tv.parent[v];  // requested together with the atomic: one round trip per level
             unsigned long long old = atomicMax((unsigned long long *)&tv.tick[v], (unsigned long long)t);
@@ -692,23 +693,51 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
         const int32_t base = f0 - from_free;
         unsigned long long my_tok = 0;
         int32_t my_new = 0;
-        for (int32_t j2 = tid; j2 < nb; j2 += 256) {
-            int32_t u = ws.used[j2];
-            my_new += (u & 1) + ((u >> 1) & 1);
-            my_tok += (unsigned long long)ws.leaf_tok[j2];
+        // (loads in groups of eight, all requested before any is used: a loop that uses each value
+        // at once pays a round trip per iteration)
+        for (int32_t j0 = tid; j0 < nb; j0 += 8 * 256) {
+            int32_t u[8], lt[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int32_t j2 = j0 + t * 256;
+                u[t] = j2 < nb ? ws.used[j2] : 0;
+                lt[t] = j2 < nb ? ws.leaf_tok[j2] : 0;
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                my_new += (u[t] & 1) + ((u[t] >> 1) & 1);
+                my_tok += (unsigned long long)lt[t];
+            }
         }
         if (my_tok) atomicAdd(&s_tok, my_tok);
         if (my_new) atomicAdd(&s_new, my_new);
-        // each thread owns a contiguous run of reservations; one scan places the unused ones
+        // each thread owns a contiguous run of reservations; one scan places the unused ones.  The
+        // first eight of the run (all of it for batches up to 1,024) are read once and kept.
         const int32_t per = (A + 255) / 256;
         const int32_t lo = tid * per < A ? tid * per : A;
         const int32_t hi = lo + per < A ? lo + per : A;
+        int32_t head_u[8], head_id[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int32_t a = lo + t;
+            head_u[t] = a < hi ? ((ws.used[a >> 1] >> (a & 1)) & 1) : 1;
+            head_id[t] = a < hi ? ws.resv_id[a] : 0;
+        }
         int32_t cnt = 0;
-        for (int32_t a = lo; a < hi; ++a) cnt += ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) cnt += head_u[t] ? 0 : 1;
+        for (int32_t a = lo + 8; a < hi; ++a) cnt += ((ws.used[a >> 1] >> (a & 1)) & 1) ? 0 : 1;
         int32_t unused_total;
         int32_t incl = block_inclusive_scan<int32_t, 256>(cnt, sbuf, tid, unused_total);
         int32_t dst = base + incl - cnt;
-        for (int32_t a = lo; a < hi; ++a) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            if (!head_u[t]) {
+                if (dst >= 0 && dst < tv.max_nodes) tv.free_stack[dst] = head_id[t];
+                ++dst;
+            }
+        }
+        for (int32_t a = lo + 8; a < hi; ++a) {
             if (((ws.used[a >> 1] >> (a & 1)) & 1) == 0) {
                 if (dst >= 0 && dst < tv.max_nodes) tv.free_stack[dst] = ws.resv_id[a];
                 ++dst;
