@@ -807,6 +807,34 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
     return (tv.tick[id] << depth_bits) | (dm - (uint64_t)(uint32_t)tv.depth_end[id]);
 }
 
+// The sweeps over all nodes visit four nodes per thread and trip, every field requested before any
+// is looked at (one round trip per trip; a loop that tests edge_len, then tick, then builds the key
+// pays three per node).  f(id, edge_len, key) is called for every live node that may be evicted.
+template <class F>
+__device__ __forceinline__ void for_each_evictable(const TreeView &tv, int32_t n_slots, uint64_t keep_from, int depth_bits,
+                                                   int64_t first, int64_t stride, F f) {
+    constexpr int kUnroll = 4;
+    const uint64_t dm = (1ull << depth_bits) - 1ull;
+    for (int64_t id0 = first; id0 < n_slots; id0 += kUnroll * stride) {
+        int32_t len[kUnroll], de[kUnroll];
+        uint64_t tk[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t id = id0 + u * stride;
+            const int64_t idc = id < n_slots ? id : 0;  // (the root has no edge: skipped below)
+            len[u] = tv.edge_len[idc];
+            tk[u] = tv.tick[idc];
+            de[u] = tv.depth_end[idc];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t id = id0 + u * stride;
+            if (id >= n_slots || len[u] <= 0 || tk[u] >= keep_from) continue;
+            f(id, len[u], (tk[u] << depth_bits) | (dm - (uint64_t)(uint32_t)de[u]));
+        }
+    }
+}
+
 // One step of the search for the cut key, run by one workgroup of 256 threads once the weighted
 // histogram of the current digit (`width` bits) is complete: pick the smallest digit whose inclusive
 // weight reaches what is still to be freed, append it to the prefix and reduce the remainder.  When
@@ -849,22 +877,21 @@ __device__ void evict_descend_step(DevState *st, const int64_t *hist, int width,
 __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, int pass, int shift, int width,
                                                     int depth_bits) {
     DevState *st = tv.st;
-    if (!st->do_evict) return;
-    __shared__ unsigned long long h[kEvictBins];
-    const int tid = threadIdx.x;
+    const int do_evict = st->do_evict;  // (the state words are requested together)
     const uint64_t prefix = st->evict_prefix;  // digits fixed by the earlier passes
-    for (int i = tid; i < kEvictBins; i += 256) h[i] = 0;
-    __syncthreads();
     const int32_t n_slots = st->n_slots;
     const uint64_t keep_from = st->keep_from;
+    if (!do_evict) return;
+    __shared__ unsigned long long h[kEvictBins];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kEvictBins; i += 256) h[i] = 0;
+    __syncthreads();
     const int upper = shift + width;
-    for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
-        int32_t len = tv.edge_len[id];
-        if (len <= 0 || tv.tick[id] >= keep_from) continue;
-        uint64_t key = evict_key(tv, id, depth_bits);
+    for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                       (int64_t)gridDim.x * blockDim.x, [&](int64_t, int32_t len, uint64_t key) {
         bool in_prefix = (pass == 0) || (upper >= 64 ? prefix == 0 : (key >> upper) == prefix);
         if (in_prefix) atomicAdd(&h[(key >> shift) & (uint64_t)((1 << width) - 1)], (unsigned long long)len);
-    }
+    });
     __syncthreads();
     for (int i = tid; i < (1 << width); i += 256)
         if (h[i]) atomicAdd((unsigned long long *)&ws.evict_hist[pass * kEvictBins + i], h[i]);
@@ -877,21 +904,20 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
 // with digit passes of its own over all nodes.
 __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
     DevState *st = tv.st;
-    if (!st->do_evict) return;
+    const int do_evict = st->do_evict;
+    const uint64_t prefix = st->evict_prefix;
+    const int32_t n_slots = st->n_slots;
+    const uint64_t keep_from = st->keep_from;
+    const bool evict_all = st->evict_all != 0;
+    if (!do_evict) return;
     __shared__ uint64_t s_key[kEvictCand];
     __shared__ int32_t s_len[kEvictCand];
     __shared__ int64_t part[256 / kWave];
     __shared__ unsigned long long s_cut;
     const int tid = threadIdx.x;
-    const uint64_t prefix = st->evict_prefix;
-    const int32_t n_slots = st->n_slots;
-    const uint64_t keep_from = st->keep_from;
-    const bool evict_all = st->evict_all != 0;
     if (!evict_all) {
-        for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
-            int32_t len = tv.edge_len[id];
-            if (len <= 0 || tv.tick[id] >= keep_from) continue;
-            uint64_t key = evict_key(tv, id, depth_bits);
+        for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                           (int64_t)gridDim.x * blockDim.x, [&](int64_t, int32_t len, uint64_t key) {
             if (n_hist_pass == 0 || shift >= 64 || (key >> shift) == prefix) {
                 int32_t at = atomicAdd(&st->cand_cnt, 1);
                 if (at < kEvictCand) {
@@ -899,7 +925,7 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
                     ws.cand_len[at] = len;
                 }
             }
-        }
+        });
     }
     if (!last_block_done(st, 10)) return;
     if (evict_all) {
@@ -972,19 +998,19 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
 
 __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int depth_bits) {
     DevState *st = tv.st;
-    if (!st->do_evict) return;
+    const int do_evict = st->do_evict;
+    const uint64_t cut = st->evict_prefix;  // every live, unprotected node with key <= cut goes
+    const uint64_t keep_from = st->keep_from;
+    const int32_t n_slots = st->n_slots;
+    if (!do_evict) return;
     __shared__ unsigned long long s_tok;
     __shared__ int s_cnt;
     const int tid = threadIdx.x;
-    const uint64_t cut = st->evict_prefix;  // every live, unprotected node with key <= cut goes
-    const uint64_t keep_from = st->keep_from;
     if (tid == 0) { s_tok = 0; s_cnt = 0; }
     __syncthreads();
-    const int32_t n_slots = st->n_slots;
-    for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + tid; id < n_slots; id += (int64_t)gridDim.x * blockDim.x) {
-        int32_t len = tv.edge_len[id];
-        if (len <= 0 || tv.tick[id] >= keep_from) continue;
-        if (evict_key(tv, id, depth_bits) <= cut) {
+    for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                       (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t node_key) {
+        if (node_key <= cut) {
             tv.edge_len[id] = 0;
             // leave a tombstone where the parent pointed at this node
             const uint64_t key = make_key(tv.parent[id], tv.pool[tv.edge_off[id]]);
@@ -1003,7 +1029,7 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
             atomicAdd(&s_tok, (unsigned long long)len);
             atomicAdd(&s_cnt, 1);
         }
-    }
+    });
     __syncthreads();
     if (tid == 0 && s_cnt) {
         atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
