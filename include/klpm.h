@@ -300,7 +300,9 @@ int kLPM_queue_gather(const kLPM_queue *q, const kLPM_queries *all, kLPM_stream 
  * nothing of `cur` is written, so the two buffer sets are used in turn.
  *   all         the whole stream's prompts (tokens unused; off/len indexed by global id)
  *   match_len   DEVICE [*cur->n] match lengths of the queue as scored this step
- *   batch_idx / n_selected  as written by kLPM_select (distinct positions in `cur`)
+ *   batch_idx   DEVICE [batch_cap]: the first *n_selected entries as written by kLPM_select
+ *               (distinct positions in `cur`); the rest is read but ignored
+ *   n_selected  DEVICE [1], <= batch_cap
  *   new_id      DEVICE [n_new] global ids of the arrivals joining after this step
  *   ttft        DEVICE [all->n] out (written for admitted ids only)
  *   matched_accum DEVICE [1] or NULL: += sum of match_len over the queue (throughput accounting)

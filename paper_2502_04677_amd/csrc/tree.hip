@@ -135,6 +135,21 @@ __global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, Que
     __shared__ int32_t s_below, s_valid;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)blockIdx.x * kQaThreads;
+    // What can be requested without knowing the counts goes out with them: this thread's queue entry
+    // (the buffers hold cap entries) and its first two batch entries (batch_cap of them exist).
+    constexpr int kAhead = 2;
+    const int64_t i = base + tid;
+    const bool i_in = i < cur.cap;
+    const int32_t my_id = i_in ? cur.id[i] : -1;
+    const uint64_t my_arr = i_in ? cur.arrival[i] : 0;
+    const int64_t my_off = i_in ? cur.off[i] : 0;
+    const int32_t my_len = i_in ? cur.len[i] : 0;
+    int32_t w_ahead[kAhead];
+#pragma unroll
+    for (int t = 0; t < kAhead; ++t) {
+        const int32_t j = tid + t * kQaThreads;
+        w_ahead[t] = j < batch_cap ? batch_idx[j] : -1;
+    }
     int32_t nw = *cur.n;
     nw = nw < 0 ? 0 : (nw > cur.cap ? cur.cap : nw);
     int32_t nb = *n_selected;
@@ -146,20 +161,34 @@ __global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, Que
     {
         unsigned long long my_cost = 0;
         int32_t below = 0, valid = 0;
-        for (int32_t j = tid; j < nb; j += kQaThreads) {
-            const int32_t w = batch_idx[j];
-            if (w < 0 || w >= nw) continue;
+        auto retire = [&](int32_t w, int32_t len, int32_t m) {
             ++valid;
             if (w < base) ++below;
             else if (w < base + kQaThreads) atomicOr(&bm[(w - base) >> 5], 1u << ((w - base) & 31));
-            const int32_t len = cur.len[w];  // (the queue carries the CSR view of its prompts)
-            int32_t m = match_len[w];
             m = m < 0 ? 0 : m;
             // (1 + c_attn |x|)(|x| - overlap) token times, in units of 1/c_den (Def. 2); c_attn = 0 otherwise
             if (len > m)
                 my_cost += (unsigned long long)(len - m) *
                            (TIMED ? (unsigned long long)pend.c_den + (unsigned long long)pend.c_num * (unsigned long long)len
                                   : 1ull);
+        };
+        // the entries read ahead: their lengths and matches in one round trip
+        int32_t len_a[kAhead], m_a[kAhead];
+        bool ok_a[kAhead];
+#pragma unroll
+        for (int t = 0; t < kAhead; ++t) {
+            const int32_t w = w_ahead[t];
+            ok_a[t] = tid + t * kQaThreads < nb && w >= 0 && w < nw;
+            len_a[t] = ok_a[t] ? cur.len[w] : 0;  // (the queue carries the CSR view of its prompts)
+            m_a[t] = ok_a[t] ? match_len[w] : 0;
+        }
+#pragma unroll
+        for (int t = 0; t < kAhead; ++t)
+            if (ok_a[t]) retire(w_ahead[t], len_a[t], m_a[t]);
+        for (int32_t j = tid + kAhead * kQaThreads; j < nb; j += kQaThreads) {
+            const int32_t w = batch_idx[j];
+            if (w < 0 || w >= nw) continue;
+            retire(w, cur.len[w], match_len[w]);
         }
         if (my_cost) atomicAdd(&s_cost, my_cost);
         if (below) atomicAdd(&s_below, below);
@@ -192,7 +221,6 @@ __global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, Que
     }
     const bool overflow = !TIMED && (add > room || kept_all > next.cap);
     add = add < room ? add : room;  // (timed: the rest stay pending, in order)
-    const int64_t i = base + tid;
     unsigned long long my = 0;
     if (i < nw) {
         const int32_t m = match_len[i];
@@ -200,16 +228,16 @@ __global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, Que
         const uint32_t word = bm[tid >> 5], bit = 1u << (tid & 31);
         int32_t before = s_below + (int32_t)__popc(word & (bit - 1u));
         for (int wd = 0; wd < (tid >> 5); ++wd) before += (int32_t)__popc(bm[wd]);
-        const int32_t id = cur.id[i];
+        const int32_t id = my_id;
         if (word & bit) {
-            if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - cur.arrival[i]);  // TTFT = finish time - arrival
+            if (id >= 0 && id < all.n) ttft[id] = (int64_t)(now - my_arr);  // TTFT = finish time - arrival
         } else {
             const int64_t dst = i - before;
             if (dst >= 0 && dst < kept) {
                 next.id[dst] = id;
-                next.arrival[dst] = cur.arrival[i];
-                next.off[dst] = cur.off[i];
-                next.len[dst] = cur.len[i];
+                next.arrival[dst] = my_arr;
+                next.off[dst] = my_off;
+                next.len[dst] = my_len;
             }
         }
     } else if (i < (int64_t)nw + add) {
