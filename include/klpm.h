@@ -112,7 +112,8 @@ int kLPM_match(kLPM_tree *tree, const kLPM_queries *q, int32_t *match_len, int32
                kLPM_stream stream);
 
 /* kLPM_select flag: the caller asserts that arrival[] is non-decreasing in the queue index (a queue
- * kept in arrival order).  Selection then runs as a single kernel.  The assertion is checked on the
+ * kept in arrival order).  Selection then needs no sort of the whole queue (one kernel for up to
+ * 8,192 entries, five short ones beyond).  The assertion is checked on the
  * device; if it does not hold, *n_selected is set to -1, nothing is selected and the phase is kept. */
 #define KLPM_SELECT_FIFO 1u
 
@@ -196,7 +197,8 @@ int kLPM_tie_keys(uint64_t seed, uint64_t step, const int32_t *id, int32_t n, co
  * clock, extend the tree to hold it (splitting an edge where the prompt diverges from it or ends
  * inside it) and stamp the tick on every node of its path; then, while the token total exceeds the
  * budget, remove the least-recently-used leaf (fixed-size cache with LRU eviction, Sec. 1, Sec. 2.1).
- *   batch_idx   DEVICE [batch_cap] indices into q (as written by kLPM_select)
+ *   batch_idx   DEVICE [batch_cap] indices into q (as written by kLPM_select); entries behind the
+ *               first *n_selected may be read but are ignored
  *   n_selected  DEVICE [1] number of valid entries, <= batch_cap <= cfg.max_batch
  *   stats       DEVICE [1] out, or NULL
  * Tokens are copied into the arena, so q's buffers may be recycled once the stream has passed.
