@@ -580,9 +580,10 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         for (int32_t j = tid; j < nb; j += kFifoThreads) batch_idx[j] = j;
         return;
     }
-    // the entries that can be picked: all of a short queue, else the nb best by match length
+    // the entries that can be picked: all of a short queue of which a good part is admitted (sorting
+    // them all is then cheaper than the threshold search), else the nb best by match length
     int32_t n_cand = nb;
-    if (n <= kFifoMaxBatch) {
+    if (n <= kFifoMaxBatch && ((int64_t)nb * 8 >= n || n <= 256)) {
         n_cand = n;
         for (int32_t i = tid; i < n; i += kFifoThreads) {
             int32_t m = match_len[i];
