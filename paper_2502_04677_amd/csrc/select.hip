@@ -580,6 +580,35 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         for (int32_t j = tid; j < nb; j += kFifoThreads) batch_idx[j] = j;
         return;
     }
+    if (nb == 1) {
+        // one query per step (Def. 2 as it stands): the head of the queue, or the first query that
+        // holds the largest match length found by the sweep above
+        if (!lpm_only && phase == 0u) {
+            if (tid == 0) batch_idx[0] = 0;
+            return;
+        }
+        if (tid == 0) s_bin = n;
+        __syncthreads();
+        const int32_t best = s_max;
+        int32_t first = n;
+        for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
+            int32_t mv[kSweepRows];
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kFifoThreads + tid;
+                mv[r] = match_len[i < n ? i : n - 1];
+            }
+#pragma unroll
+            for (int r = 0; r < kSweepRows; ++r) {
+                int32_t i = base + r * kFifoThreads + tid;
+                if (i < n && (mv[r] < 0 ? 0 : mv[r]) == best && i < first) first = i;
+            }
+        }
+        if (first < n) atomicMin(&s_bin, first);
+        __syncthreads();
+        if (tid == 0) batch_idx[0] = s_bin;
+        return;
+    }
     // the entries that can be picked: all of a short queue of which a good part is admitted (sorting
     // them all is then cheaper than the threshold search), else the nb best by match length
     int32_t n_cand = nb;
