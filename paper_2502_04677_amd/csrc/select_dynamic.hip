@@ -5,8 +5,9 @@
 // few queries can gain: overlap(x_i, x_p) exceeds i's match against the cache only if x_p leaves the
 // cached tree at the very place x_i does and goes on with the same token, i.e. if both have the same
 // (stop node, match length, next token).  Queries are grouped by that key up front (a hash table
-// with one chain per key); a pick then rescans its own group only, and a query whose group has no
-// other member can neither gain nor give.  The picks themselves are made by one wavefront walking
+// gives every key a slot, a scan and a scatter lay each group's members out next to each other); a
+// pick then rescans its own group only, one lane per member, and a query whose group has no other
+// member can neither gain nor give.  The picks themselves are made by one wavefront walking
 // the oldest-first and longest-match orders: whole k-cycles at a time while no picked query has a
 // group, one pick at a time (static head of the longest-match order against the best boosted
 // query) otherwise.
@@ -19,11 +20,13 @@ constexpr int32_t kDynMaxN = 262144;  // two state bits per query are kept in LD
 struct DynWs {
     uint64_t *gk;       // [n] (stop node << 32) | next token
     int32_t *slot_of;   // [n] table slot of the query's group, -1: no group (prompt cached in full, bad input)
-    int32_t *next;      // [n] next member of the same group
     uint8_t *multi;     // [n] 1: the group has at least two members
     int32_t *rep;       // [table] first query that claimed the slot, -1: free
-    int32_t *head;      // [table] chain head
     int32_t *cnt;       // [table] members
+    int32_t *start;     // [table] first entry of the group in `members`
+    int32_t *fill;      // [table] scratch of the scatter
+    int32_t *tile_sum;  // [table / 8192, at least 1] scratch of the scan
+    int32_t *members;   // [n] query indices, the members of a group next to each other
     uint64_t *bkey;     // [n] boosted set: (inverted score, position in the oldest-first order)
     int32_t *bidx;      // [n] boosted set: query index
     int32_t *bpos;      // [n] where a boosted query sits in the set
@@ -46,8 +49,8 @@ __global__ __launch_bounds__(256) void k_dyn_init(QView q, const int32_t *__rest
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i <= (int64_t)ws.table_mask) {
         ws.rep[i] = -1;
-        ws.head[i] = -1;
         ws.cnt[i] = 0;
+        ws.fill[i] = 0;
     }
     const int32_t n = live_count(q.n, q.n_live);
     if (i >= n) return;
@@ -56,7 +59,6 @@ __global__ __launch_bounds__(256) void k_dyn_init(QView q, const int32_t *__rest
     const int32_t len = q.len[i];
     const bool ok = m >= 0 && off >= 0 && len >= 1 && off + (int64_t)len <= q.n_tokens && m <= len;
     dyn[i] = ok ? m : 0;
-    ws.next[i] = -1;
     ws.multi[i] = 0;
     // a prompt that is cached in full adds nothing to the cache and cannot gain either
     const bool grouped = ok && m < len;
@@ -77,19 +79,72 @@ __global__ __launch_bounds__(256) void k_dyn_insert(LiveQ nn, const int32_t *__r
         h = (h + 1u) & ws.table_mask;
     }
     ws.slot_of[i] = (int32_t)h;
-    ws.next[i] = atomicExch(&ws.head[h], i);
     atomicAdd(&ws.cnt[h], 1);
 }
 
-__global__ __launch_bounds__(256) void k_dyn_multi(LiveQ nn, DynWs ws) {
+// Exclusive scan of the group sizes: where each group's members start in `members`.  Two launches:
+// every workgroup sums its stretch of the table (eight slots per thread), then adds up the stretches
+// before its own and scans inside it.
+constexpr int kDynScanThreads = 1024;
+constexpr int kDynScanPer = 8;
+constexpr int kDynScanTile = kDynScanThreads * kDynScanPer;
+
+__global__ __launch_bounds__(kDynScanThreads) void k_dyn_tile_sums(DynWs ws) {
+    __shared__ int32_t s_sum;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_sum = 0;
+    __syncthreads();
+    const int64_t table = (int64_t)ws.table_mask + 1;
+    const int64_t base = (int64_t)blockIdx.x * kDynScanTile + (int64_t)tid * kDynScanPer;
+    int32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < kDynScanPer; ++u) mine += base + u < table ? ws.cnt[base + u] : 0;
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) mine += __shfl_xor(mine, d);
+    if ((tid & (kWave - 1)) == 0 && mine) atomicAdd(&s_sum, mine);
+    __syncthreads();
+    if (tid == 0) ws.tile_sum[blockIdx.x] = s_sum;
+}
+
+__global__ __launch_bounds__(kDynScanThreads) void k_dyn_offsets(DynWs ws) {
+    __shared__ int32_t part[kDynScanThreads / kWave];
+    __shared__ int32_t s_before;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_before = 0;
+    __syncthreads();
+    int32_t before = 0;  // members in the tiles before this one (a table has at most 64 tiles)
+    for (int32_t b = tid; b < (int32_t)blockIdx.x; b += kDynScanThreads) before += ws.tile_sum[b];
+    if (before) atomicAdd(&s_before, before);
+    const int64_t table = (int64_t)ws.table_mask + 1;
+    const int64_t base = (int64_t)blockIdx.x * kDynScanTile + (int64_t)tid * kDynScanPer;
+    int32_t c[kDynScanPer];
+    int32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < kDynScanPer; ++u) {
+        c[u] = base + u < table ? ws.cnt[base + u] : 0;
+        mine += c[u];
+    }
+    int32_t all;
+    int32_t run = block_inclusive_scan<int32_t, kDynScanThreads>(mine, part, tid, all) - mine + s_before;
+#pragma unroll
+    for (int u = 0; u < kDynScanPer; ++u) {
+        if (base + u < table) ws.start[base + u] = run;
+        run += c[u];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_dyn_scatter(LiveQ nn, DynWs ws) {
     const int32_t n = nn.get();
     const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t s = ws.slot_of[i];
     ws.multi[i] = (s >= 0 && ws.cnt[s] > 1) ? 1 : 0;
+    if (s < 0) return;
+    const int32_t at = ws.start[s] + atomicAdd(&ws.fill[s], 1);
+    if (at >= 0 && at < n) ws.members[at] = i;
 }
 
-// loads and stores of the arrays the walking wavefront both writes (lane 0) and reads (any lane)
+// loads and stores of the arrays the walking wavefront both writes and reads
 template <typename T>
 __device__ __forceinline__ T coh_load(const T *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -314,41 +369,91 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         pos = lpm_only ? 0u : (pos + 1u == k ? 0u : pos + 1u);
         if (ws.multi[p]) {
             // everything processed stays cached for the rest of the bin: raise the scores of the
-            // pick's group to their common prefix with it
+            // pick's group to their common prefix with it.  One lane per member: its fields in one
+            // round trip, the first kProbe tokens behind the shared part in another; only members
+            // that agree with the pick beyond those are compared by the whole wavefront.
+            constexpr int kProbe = 8;
             const int64_t off_p = uni64(q.off[p]);
             const int32_t len_p = uni(q.len[p]);
             const int32_t s0 = uni(match_len[p]) + 1;  // the group shares the cached part and the next token
-            int32_t i = uni(ws.head[ws.slot_of[p]]);
-            while (i >= 0) {
-                const int32_t nxt = uni(ws.next[i]);
-                const uint32_t si = state((uint32_t)i);
-                if (i != p && (si & 1u) == 0u) {
-                    const int64_t off_i = uni64(q.off[i]);
-                    const int32_t len_i = uni(q.len[i]);
-                    const int32_t lim = len_i < len_p ? len_i : len_p;
-                    int32_t ov = s0;
-                    if (lim > s0) ov = s0 + wave_common_prefix(q.tokens + off_i + s0, q.tokens + off_p + s0, lim - s0, lane);
-                    if (ov > uni(coh_load(&dyn[i]))) {
-                        const uint64_t key = pack_key(ov, ord.rank_a[i]);
-                        const bool in_set = (si & 2u) != 0u;
-                        const int32_t at = in_set ? uni(coh_load(&ws.bpos[i])) : n_boost;
-                        if (lane == 0) {
-                            coh_store(&dyn[i], ov);
-                            coh_store(&ws.bkey[at], key);
-                            if (!in_set) {
-                                coh_store(&ws.bidx[at], i);
-                                coh_store(&ws.bpos[i], at);
-                                set_bits((uint32_t)i, 2u);
-                            }
-                        }
-                        if (!in_set) n_boost += 1;
-                        if (kb_valid && key < kb) { kb = key; pb = at; }  // keys only ever get smaller
+            const int32_t slot = uni(ws.slot_of[p]);
+            const int32_t g0 = uni(ws.start[slot]), gn = uni(ws.cnt[slot]);
+            const uint64_t below = (1ull << lane) - 1ull;
+            for (int32_t b = 0; b < gn; b += kWave) {
+                const int32_t t = b + lane;
+                const int32_t i = t < gn ? ws.members[g0 + t] : -1;
+                uint32_t si = 1u;
+                if (i >= 0) si = state((uint32_t)i);
+                const bool act = i >= 0 && i != p && (si & 1u) == 0u;
+                int64_t off_i = 0;
+                int32_t len_i = 0, cur = 0, at_old = -1;
+                uint32_t ra = 0;
+                if (act) {
+                    off_i = q.off[i];
+                    len_i = q.len[i];
+                    cur = coh_load(&dyn[i]);
+                    ra = ord.rank_a[i];
+                    if (si & 2u) at_old = coh_load(&ws.bpos[i]);
+                }
+                const int32_t lim = len_i < len_p ? len_i : len_p;
+                const int32_t rem = act ? lim - s0 : 0;  // tokens that may still agree
+                int32_t add = 0;
+                bool more = false;
+                if (rem > 0) {
+                    int32_t av[kProbe], bv[kProbe];
+#pragma unroll
+                    for (int u = 0; u < kProbe; ++u) {
+                        const int32_t c = u < rem ? u : rem - 1;
+                        av[u] = q.tokens[off_i + s0 + c];
+                        bv[u] = q.tokens[off_p + s0 + c];
+                    }
+                    add = rem < kProbe ? rem : kProbe;
+#pragma unroll
+                    for (int u = kProbe - 1; u >= 0; --u)
+                        if (u < rem && av[u] != bv[u]) add = u;
+                    more = add == kProbe && rem > kProbe;
+                }
+                uint64_t longm = __ballot(more);
+                while (longm) {
+                    const int src = (int)__builtin_ctzll(longm);
+                    longm &= longm - 1ull;
+                    const int64_t oi = (int64_t)(((uint64_t)(uint32_t)__shfl((int32_t)((uint64_t)off_i >> 32), src) << 32) |
+                                                 (uint64_t)(uint32_t)__shfl((int32_t)(uint32_t)off_i, src));
+                    const int32_t ri = __shfl(rem, src);
+                    const int32_t extra = wave_common_prefix(q.tokens + oi + s0 + kProbe, q.tokens + off_p + s0 + kProbe,
+                                                             ri - kProbe, lane);
+                    if (lane == src) add += extra;
+                }
+                const int32_t ov = s0 + add;
+                const bool upd = act && ov > cur;
+                const bool fresh = upd && (si & 2u) == 0u;
+                const uint64_t fm = __ballot(fresh);
+                const int32_t at = fresh ? n_boost + (int32_t)__popcll(fm & below) : at_old;
+                uint64_t key = ~0ull;
+                if (upd) {
+                    key = pack_key(ov, ra);
+                    coh_store(&dyn[i], ov);
+                    coh_store(&ws.bkey[at], key);
+                    if (fresh) {
+                        coh_store(&ws.bidx[at], i);
+                        coh_store(&ws.bpos[i], at);
+                        set_bits((uint32_t)i, 2u);
                     }
                 }
-                i = nxt;
+                n_boost += (int32_t)__popcll(fm);
+                // the best of the keys just written (keys only ever get smaller)
+                uint64_t bk = key;
+                int32_t bp = at;
+#pragma unroll
+                for (int d = kWave / 2; d > 0; d >>= 1) {
+                    const uint64_t ok = __shfl_xor(bk, d);
+                    const int32_t op = __shfl_xor(bp, d);
+                    if (ok < bk) { bk = ok; bp = op; }
+                }
+                if (kb_valid && bk < kb) { kb = bk; pb = bp; }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");  // lane 0's stores before the next reads of any lane
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");  // this pick's stores before the next reads of any lane
         __syncthreads();
     }
 }
@@ -362,11 +467,13 @@ static size_t carve_dyn(DynWs &d, char *base, int32_t n, size_t start) {
     d.table_mask = table - 1u;
     d.gk = (uint64_t *)take(nn * 8);
     d.slot_of = (int32_t *)take(nn * 4);
-    d.next = (int32_t *)take(nn * 4);
     d.multi = (uint8_t *)take(nn);
     d.rep = (int32_t *)take((size_t)table * 4);
-    d.head = (int32_t *)take((size_t)table * 4);
     d.cnt = (int32_t *)take((size_t)table * 4);
+    d.start = (int32_t *)take((size_t)table * 4);
+    d.fill = (int32_t *)take((size_t)table * 4);
+    d.tile_sum = (int32_t *)take((size_t)((table + 8191) / 8192) * 4);
+    d.members = (int32_t *)take(nn * 4);
     d.bkey = (uint64_t *)take(nn * 8);
     d.bidx = (int32_t *)take(nn * 4);
     d.bpos = (int32_t *)take(nn * 4);
@@ -411,7 +518,10 @@ extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_l
         hipLaunchKernelGGL(k_dyn_init, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, qv, match_len, last_node, d,
                            dyn_match);
         hipLaunchKernelGGL(k_dyn_insert, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, match_len, d);
-        hipLaunchKernelGGL(k_dyn_multi, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, d);
+        const unsigned tiles = (unsigned)(((int64_t)d.table_mask + kDynScanTile) / kDynScanTile);
+        hipLaunchKernelGGL(k_dyn_tile_sums, dim3(tiles), dim3(kDynScanThreads), 0, stream, d);
+        hipLaunchKernelGGL(k_dyn_offsets, dim3(tiles), dim3(kDynScanThreads), 0, stream, d);
+        hipLaunchKernelGGL(k_dyn_scatter, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, d);
     }
     hipLaunchKernelGGL(k_dyn_walk, dim3(1), dim3(kWave), 0, stream, qv, match_len, ord, d, dyn_match, KArg{k, k_dev}, batch, phase_inout,
                        batch_idx, n_selected);
