@@ -27,6 +27,8 @@ struct DynWs {
     int32_t *fill;      // [table] scratch of the scatter
     int32_t *tile_sum;  // [table / 8192, at least 1] scratch of the scan
     int32_t *members;   // [n] query indices, the members of a group next to each other
+    int32_t *gstart;    // [n] where the query's group starts in `members`
+    int32_t *gcnt;      // [n] members of the query's group
     uint64_t *bkey;     // [n] boosted set: (inverted score, position in the oldest-first order)
     int32_t *bidx;      // [n] boosted set: query index
     int32_t *bpos;      // [n] where a boosted query sits in the set
@@ -138,9 +140,12 @@ __global__ __launch_bounds__(256) void k_dyn_scatter(LiveQ nn, DynWs ws) {
     const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t s = ws.slot_of[i];
-    ws.multi[i] = (s >= 0 && ws.cnt[s] > 1) ? 1 : 0;
+    const int32_t gn = s >= 0 ? ws.cnt[s] : 0, g0 = s >= 0 ? ws.start[s] : 0;
+    ws.multi[i] = gn > 1 ? 1 : 0;
+    ws.gstart[i] = g0;
+    ws.gcnt[i] = gn;
     if (s < 0) return;
-    const int32_t at = ws.start[s] + atomicAdd(&ws.fill[s], 1);
+    const int32_t at = g0 + atomicAdd(&ws.fill[s], 1);
     if (at >= 0 && at < n) ws.members[at] = i;
 }
 
@@ -264,6 +269,10 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         }
         // ---- a run of picks of one kind, up to the first pick that needs bookkeeping
         bool single_from_set = false;
+        // (what this window's lanes have read is kept for the single pick further down)
+        uint32_t w_el = 0;
+        uint64_t w_key = ~0ull, w_mask = 0ull;
+        int32_t w_multi = 0;
         {
             const uint32_t run = oldest ? (k == 1u ? (uint32_t)(nb - j) : 1u) : (lpm_only ? (uint32_t)(nb - j) : k - pos);
             const int32_t want = (int32_t)(run < (uint32_t)(nb - j) ? run : (uint32_t)(nb - j));
@@ -274,15 +283,19 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                 el = oldest ? ord.order_a[r] : ord.order_l[r];
                 const uint32_t sv = state(el);
                 cand = oldest ? ((sv & 1u) == 0u) : (sv == 0u);
-                hard = ws.multi[el] != 0;
+                w_multi = ws.multi[el];
+                hard = w_multi != 0;
                 if (oldest) {
                     hard = hard || (sv & 2u) != 0u;
-                } else if (cand && n_boost > 0) {
+                } else if (cand) {
                     int32_t ml = match_len[el];
-                    hard = hard || pack_key(ml < 0 ? 0 : ml, ord.rank_a[el]) > kb;
+                    w_key = pack_key(ml < 0 ? 0 : ml, ord.rank_a[el]);
+                    hard = hard || (n_boost > 0 && w_key > kb);
                 }
             }
+            w_el = el;
             const uint64_t mask = __ballot(cand), hmask = __ballot(cand && hard);
+            w_mask = mask;
             const int32_t my = (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
             int32_t take = (int32_t)__popcll(mask);
             take = take < want ? take : want;
@@ -313,36 +326,31 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         }
         // ---- one pick; then the rescoring of the pick's group
         int32_t p = -1;
+        int32_t p_multi = -1;  // whether the pick has a group, if a lane already knows
         if (oldest) {
-            const int32_t r = ia + lane;
-            uint32_t el = 0;
-            bool cand = false;
-            if (r < n) { el = ord.order_a[r]; cand = (state(el) & 1u) == 0u; }
-            const uint64_t mask = __ballot(cand);  // not empty: see the run block above
-            const int f = (int)__builtin_ctzll(mask);
-            p = __shfl((int32_t)el, f);
+            const int f = (int)__builtin_ctzll(w_mask);  // not empty: see the run block above
+            p = __shfl((int32_t)w_el, f);
+            p_multi = __shfl(w_multi, f);
             ia += f + 1;
         } else {
             // head of the static longest-match order among the queries never boosted, against the
             // best boosted query
             int32_t c1 = -1;
             uint64_t key1 = ~0ull;
+            int32_t c1_multi = -1;
             if (!single_from_set) {
-                const int32_t r = il + lane;
-                uint32_t el = 0;
-                bool cand = false;
-                if (r < n) { el = ord.order_l[r]; cand = state(el) == 0u; }
-                const uint64_t mask = __ballot(cand);  // not empty: see the run block above
-                const int f = (int)__builtin_ctzll(mask);
-                c1 = __shfl((int32_t)el, f);
+                const int f = (int)__builtin_ctzll(w_mask);  // not empty: see the run block above
+                c1 = __shfl((int32_t)w_el, f);
+                c1_multi = __shfl(w_multi, f);
                 il += f;  // stays on it until it is picked
-                int32_t m1 = match_len[c1];
-                key1 = pack_key(m1 < 0 ? 0 : m1, ord.rank_a[c1]);
+                key1 = (uint64_t)(((uint64_t)(uint32_t)__shfl((int32_t)(w_key >> 32), f) << 32) |
+                                  (uint64_t)(uint32_t)__shfl((int32_t)(uint32_t)w_key, f));
             }
             if (kb < key1) {
                 p = coh_load(&ws.bidx[pb]);
             } else {
                 p = c1;
+                p_multi = c1_multi;
                 il += 1;
             }
         }
@@ -367,7 +375,8 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         }
         j += 1;
         pos = lpm_only ? 0u : (pos + 1u == k ? 0u : pos + 1u);
-        if (ws.multi[p]) {
+        if (p_multi < 0) p_multi = uni((int32_t)ws.multi[p]);
+        if (uni(p_multi)) {
             // everything processed stays cached for the rest of the bin: raise the scores of the
             // pick's group to their common prefix with it.  One lane per member: its fields in one
             // round trip, the first kProbe tokens behind the shared part in another; only members
@@ -376,8 +385,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
             const int64_t off_p = uni64(q.off[p]);
             const int32_t len_p = uni(q.len[p]);
             const int32_t s0 = uni(match_len[p]) + 1;  // the group shares the cached part and the next token
-            const int32_t slot = uni(ws.slot_of[p]);
-            const int32_t g0 = uni(ws.start[slot]), gn = uni(ws.cnt[slot]);
+            const int32_t g0 = uni(ws.gstart[p]), gn = uni(ws.gcnt[p]);  // (requested with the three reads above)
             const uint64_t below = (1ull << lane) - 1ull;
             for (int32_t b = 0; b < gn; b += kWave) {
                 const int32_t t = b + lane;
@@ -474,6 +482,8 @@ static size_t carve_dyn(DynWs &d, char *base, int32_t n, size_t start) {
     d.fill = (int32_t *)take((size_t)table * 4);
     d.tile_sum = (int32_t *)take((size_t)((table + 8191) / 8192) * 4);
     d.members = (int32_t *)take(nn * 4);
+    d.gstart = (int32_t *)take(nn * 4);
+    d.gcnt = (int32_t *)take(nn * 4);
     d.bkey = (uint64_t *)take(nn * 8);
     d.bidx = (int32_t *)take(nn * 4);
     d.bpos = (int32_t *)take(nn * 4);
