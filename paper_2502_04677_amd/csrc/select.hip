@@ -178,16 +178,40 @@ __global__ __launch_bounds__(kScanThreads) void k_rs_scan(uint32_t *__restrict__
     const int64_t chunk = (total + kScanThreads - 1) / kScanThreads;
     const int64_t lo = tid * chunk;
     const int64_t hi = (lo + chunk < total) ? lo + chunk : total;
+    // (counts are read eight at a time, all requested before any is added up: a loop that uses each
+    // value at once pays a memory round trip per entry; the first eight are kept for the second sweep)
+    constexpr int kU = 8;
+    uint32_t head[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) head[u] = lo + u < hi ? hist[lo + u] : 0u;
     uint32_t s = 0;
-    for (int64_t i = lo; i < hi; ++i) s += hist[i];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) s += head[u];
+    for (int64_t i0 = lo + kU; i0 < hi; i0 += kU) {
+        uint32_t v[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) v[u] = i0 + u < hi ? hist[i0 + u] : 0u;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) s += v[u];
+    }
     if (tid == 0) *skip = 0;
     uint32_t all;
     const uint32_t incl = block_inclusive_scan<uint32_t, kScanThreads>(s, part, tid, all);
     uint32_t run = incl - s;  // exclusive prefix of this thread's chunk
-    for (int64_t i = lo; i < hi; ++i) {
-        uint32_t c = hist[i];
-        hist[i] = run;
-        run += c;
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+        if (lo + u < hi) hist[lo + u] = run;
+        run += head[u];
+    }
+    for (int64_t i0 = lo + kU; i0 < hi; i0 += kU) {
+        uint32_t v[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) v[u] = i0 + u < hi ? hist[i0 + u] : 0u;
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            if (i0 + u < hi) hist[i0 + u] = run;
+            run += v[u];
+        }
     }
     __syncthreads();
     if (tid < 256) {
@@ -209,26 +233,36 @@ __global__ __launch_bounds__(kSortThreads) void k_rs_scatter(const uint64_t *__r
     const int lane = tid & (kWave - 1);
     const int wv = tid / kWave;
     const int64_t wave_base = (int64_t)blockIdx.x * kSortTile + (int64_t)wv * kSortWaveTile;
-    if (*skip) {
+    // everything this thread reads is requested up front, together with the skip flag
+    const int32_t skip_pass = *skip;
+    const uint32_t run0 = hist[(int64_t)tid * nblk + blockIdx.x];
+    uint64_t k[kSortItems];
+    uint32_t v[kSortItems];
+    uint32_t rank[kSortItems];
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        int64_t i = wave_base + r * kWave + lane;
+        bool valid = i < n;
+        k[r] = valid ? key_in[i] : ~0ull;
+        v[r] = valid ? val_in[i] : 0u;
+    }
+    if (skip_pass) {
+#pragma unroll
         for (int r = 0; r < kSortItems; ++r) {
             int64_t i = wave_base + r * kWave + lane;
             if (i < n) {
-                key_out[i] = key_in[i];
-                val_out[i] = val_in[i];
+                key_out[i] = k[r];
+                val_out[i] = v[r];
             }
         }
         return;
     }
     for (int w = 0; w < kSortThreads / kWave; ++w) wcount[w][tid] = 0;
     __syncthreads();
-    uint64_t k[kSortItems];
-    uint32_t v[kSortItems];
-    uint32_t rank[kSortItems];
+#pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
         int64_t i = wave_base + r * kWave + lane;
         bool valid = i < n;
-        k[r] = valid ? key_in[i] : ~0ull;
-        v[r] = valid ? val_in[i] : 0u;
         uint32_t dg = (uint32_t)(k[r] >> shift) & 255u;
         // lanes of this row holding the same digit
         uint64_t peers = __ballot(valid);
@@ -244,7 +278,7 @@ __global__ __launch_bounds__(kSortThreads) void k_rs_scatter(const uint64_t *__r
     }
     __syncthreads();
     {
-        uint32_t run = hist[(int64_t)tid * nblk + blockIdx.x];
+        uint32_t run = run0;
         for (int w = 0; w < kSortThreads / kWave; ++w) {
             uint32_t c = wcount[w][tid];
             wcount[w][tid] = run;
