@@ -794,7 +794,7 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
 // One compute unit sweeping a 65,536-entry queue is bound by its own LDS-atomic and load rates, so
 // long queues are histogrammed, counted and gathered by many workgroups (1,024 entries each) and only
 // the final sort + walk over the nb winners runs in one workgroup.
-constexpr int kFqThreads = 256;
+constexpr int kFqThreads = 1024;    // (one entry per thread: what a workgroup spends its time on is the 8,192 bins)
 constexpr int kFqTile = 1024;       // queue entries per workgroup
 constexpr int kFqLevelBits = 13;    // bits of match length resolved per histogram kernel
 constexpr int kFqBins = 1 << kFqLevelBits;
