@@ -105,6 +105,14 @@ def concat_prompts(a: Prompts, b: Prompts) -> Prompts:
     return Prompts(toks, off, np.concatenate([a.len, b.len]), np.concatenate([a.arrival, b.arrival]))
 
 
+def concat_all(parts: Sequence[Prompts]) -> Prompts:
+    """The prompt sets one after the other, sharing one token array."""
+    base = np.cumsum([0] + [p.tokens.shape[0] for p in parts[:-1]])
+    return Prompts(np.concatenate([p.tokens for p in parts]),
+                   np.concatenate([p.off + b for p, b in zip(parts, base)]),
+                   np.concatenate([p.len for p in parts]), np.concatenate([p.arrival for p in parts]))
+
+
 def take_prompts(p: Prompts, idx: np.ndarray) -> Prompts:
     """Sub-selection that keeps sharing the token array (offsets are re-used)."""
     idx = np.asarray(idx, dtype=np.int64)
@@ -320,14 +328,19 @@ def config2(seed: int = SEED_BASE + 2, scale: float = 1.0, extra_queries: int = 
     group_of = group_of[:n_cache]
     suffix = suffix[:n_cache]
     cache = _grouped_cache(rc, group_of, ptok, poff, plen, suffix)
-    rq = _rng(seed, 2)
-    nq = n + int(extra_queries)
-    derived = rq.random(nq) < 0.85
-    qgroup = _zipf_draw(rq, cdf, nq)
     donors = _donors_from_cache(cache, group_of, plen)
-    allq = _grouped_queries(rq, nq, derived, qgroup, ptok, poff, plen, donors, 128, 32, 3968, 64, 8192)
-    queries = take_prompts(allq, np.arange(n))
-    extra = take_prompts(allq, np.arange(n, nq)) if extra_queries else None
+
+    def draw(rq, nq):
+        derived = rq.random(nq) < 0.85
+        qgroup = _zipf_draw(rq, cdf, nq)
+        return _grouped_queries(rq, nq, derived, qgroup, ptok, poff, plen, donors, 128, 32, 3968, 64, 8192)
+
+    # (the later arrivals are drawn batch by batch from streams of their own, so the queue and the
+    # first arrivals are the same whatever the number asked for)
+    queries = draw(_rng(seed, 2), n)
+    parts = [draw(_rng(seed, 1000 + c), min(batch, int(extra_queries) - c * batch))
+             for c in range((int(extra_queries) + batch - 1) // batch)]
+    extra = concat_all(parts) if parts else None
     return Workload("cfg2-large", cache, queries, k=8, batch=batch, budget=target, extra=extra)
 
 
@@ -390,14 +403,18 @@ def config2_deep(seed: int = SEED_BASE + 12, scale: float = 1.0, extra_queries: 
         return Prompts(toks, off, lens, np.arange(len(items), dtype=np.uint64))
 
     cache = assemble(plist)
-    rq = _rng(seed, 2)
-    nq = n + int(extra_queries)
-    qg = _zipf_draw(rq, cdf, nq)
-    qdepth = rq.integers(1, 7, size=nq)
-    qpicks = rq.integers(0, pool_segments, size=(nq, 6))
-    allq = assemble([(int(qg[i]), tuple(int(v) for v in qpicks[i, : int(qdepth[i])])) for i in range(nq)])
-    queries = take_prompts(allq, np.arange(n))
-    extra = take_prompts(allq, np.arange(n, nq)) if extra_queries else None
+    def draw(rq, nq):
+        qg = _zipf_draw(rq, cdf, nq)
+        qdepth = rq.integers(1, 7, size=nq)
+        qpicks = rq.integers(0, pool_segments, size=(nq, 6))
+        return assemble([(int(qg[i]), tuple(int(v) for v in qpicks[i, : int(qdepth[i])])) for i in range(nq)])
+
+    # (the later arrivals are drawn batch by batch from streams of their own, so the queue and the
+    # first arrivals are the same whatever the number asked for)
+    queries = draw(_rng(seed, 2), n)
+    parts = [draw(_rng(seed, 1000 + c), min(batch, int(extra_queries) - c * batch))
+             for c in range((int(extra_queries) + batch - 1) // batch)]
+    extra = concat_all(parts) if parts else None
     return Workload("cfg2-deep", cache, queries, k=8, batch=batch, budget=target, extra=extra)
 
 
