@@ -399,7 +399,7 @@ def main() -> int:
     sums = torch.zeros(steps_total, dtype=torch.int64, device=dev)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps_total)]
 
-    rate_bits = 26  # two 13-bit histogram levels; exact as a ratio order for prompts up to 8,192 tokens
+    rate_bits = 26  # two histogram levels; exact as a ratio order for prompts up to 8,192 tokens
     score = torch.zeros(n0, dtype=torch.int32, device=dev) if args.score == "rate" else None
     tie = torch.zeros(n0, dtype=torch.int32, device=dev) if args.random_ties else None
 

@@ -794,9 +794,9 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
 // One compute unit sweeping a 65,536-entry queue is bound by its own LDS-atomic and load rates, so
 // long queues are histogrammed, counted and gathered by many workgroups (1,024 entries each) and only
 // the final sort + walk over the nb winners runs in one workgroup.
-constexpr int kFqThreads = 1024;    // (one entry per thread: what a workgroup spends its time on is the 8,192 bins)
+constexpr int kFqThreads = 1024;    // (one entry per thread: what a workgroup spends its time on is the bins)
 constexpr int kFqTile = 1024;       // queue entries per workgroup
-constexpr int kFqLevelBits = 13;    // bits of match length resolved per histogram kernel
+constexpr int kFqLevelBits = 14;    // bits of match length resolved per histogram kernel (prompts of up to 16,383 tokens: one level)
 constexpr int kFqBins = 1 << kFqLevelBits;
 constexpr int kFqMaxLevels = 5;     // 31 bits of score (+ 32 bits of tie key) at most
 constexpr int kFqSingleBlockN = 8192;  // shorter queues are cheaper in the single-workgroup kernel
@@ -854,7 +854,7 @@ __device__ __forceinline__ bool fq_last_block(int32_t *counter) {
     return s_last != 0;
 }
 
-// Histogram of one 13-bit digit of the goodness values that share the digits fixed so far; level 0
+// Histogram of one digit (up to 14 bits) of the goodness values that share the digits fixed so far; level 0
 // also checks the arrival order.  The last workgroup to finish fixes the digit of the nb-th largest.
 template <bool TIE>
 __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restrict__ arrival, FqKey<TIE> key, LiveN nn,
