@@ -867,7 +867,9 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
     __shared__ int32_t s_viol, s_pick, s_above;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    for (int i = tid; i < (1 << width); i += kFqThreads) h[i] = 0;
+    // (the top digit only reaches as far as the caller's bound on the scores does)
+    const int nbins = (level == 0 && !TIE && (max_match >> shift) + 1 < (1 << width)) ? (max_match >> shift) + 1 : (1 << width);
+    for (int i = tid; i < nbins; i += kFqThreads) h[i] = 0;
     if (tid == 0) { s_viol = 0; s_pick = 0; s_above = 0; }
     __syncthreads();
     const G fixed_hi = (level == 0) ? (G)0 : (G)ws.meta->fixed_hi;
@@ -902,13 +904,12 @@ __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restri
     __syncthreads();
     if (tid == 0 && s_viol) atomicOr(&ws.meta->violated, 1);
     uint32_t *gh = ws.hist + (size_t)level * kFqBins;
-    for (int i = tid; i < (1 << width); i += kFqThreads) {
+    for (int i = tid; i < nbins; i += kFqThreads) {
         uint32_t c = h[i];
         if (c) atomicAdd(&gh[i], c);
     }
     if (!fq_last_block(&ws.meta->done[level])) return;
     // suffix counts over the bins, top down: thread t owns a contiguous run of bins counted from the top
-    const int nbins = 1 << width;
     const int per = (nbins + kFqThreads - 1) / kFqThreads;
     const int32_t nb = batch < n ? batch : n;
     const int32_t need = (level == 0) ? nb : ws.meta->need;
