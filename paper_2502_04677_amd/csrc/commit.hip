@@ -495,30 +495,63 @@ __device__ __forceinline__ int32_t common_prefix_and_next(const int32_t *__restr
     return jj;
 }
 
-__device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t *__restrict__ batch_idx,
-                              const CommitWs &ws, int32_t j, int lane) {
+// What an insertion reads about its prompt before it touches the tree.  A lane loads these for a
+// prompt of its own (two round trips, whatever the number of lanes doing so); the wavefront then
+// takes one lane's values.
+struct MemberIn {
+    int32_t qi, m, e, split_id, leaf_id, tok_m, L, de_e;
+    int64_t to, qoff;
+};
+__device__ __forceinline__ MemberIn member_load(const TreeView &tv, const QView &q,
+                                                const int32_t *__restrict__ batch_idx, const CommitWs &ws, int32_t j) {
+    MemberIn v;
+    v.qi = batch_idx[j];
+    v.m = ws.bm_len[j];
+    v.e = ws.bm_node[j];
+    v.to = ws.tail_off[j];
+    v.split_id = ws.resv_id[2 * j];
+    v.leaf_id = ws.resv_id[2 * j + 1];
+    v.tok_m = ws.next_tok[j];
+    v.qoff = q.off[v.qi];
+    v.L = q.len[v.qi];
+    v.de_e = ld_i32(&tv.depth_end[v.e]);
+    return v;
+}
+__device__ __forceinline__ MemberIn member_from_lane(const MemberIn &v, int b) {
+    MemberIn r;
+    r.qi = uni(__shfl(v.qi, b));
+    r.m = uni(__shfl(v.m, b));
+    r.e = uni(__shfl(v.e, b));
+    r.split_id = uni(__shfl(v.split_id, b));
+    r.leaf_id = uni(__shfl(v.leaf_id, b));
+    r.tok_m = uni(__shfl(v.tok_m, b));
+    r.L = uni(__shfl(v.L, b));
+    r.de_e = uni(__shfl(v.de_e, b));
+    r.to = uni64(__shfl(v.to, b));
+    r.qoff = uni64(__shfl(v.qoff, b));
+    return r;
+}
+
+// State a wavefront keeps across the prompts of one group: the piece of the group's old edge that
+// the previous prompt ended its search in (the upper part it has just cut off, or the piece that
+// ends exactly at its match), with that piece's record and table slot.  Picks of one group come
+// mostly in falling match length, so the next prompt's piece is this one or the one above it.
+struct GroupCtx {
+    uint64_t clock0;
+    int64_t pool_top;
+    int32_t piece;  // -1: none yet
+    int32_t piece_slot;  // slot of `piece` in its parent's table, -1 if not known
+    NodeRec piece_rec;
+};
+
+__device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs &ws, int32_t j, const MemberIn &in,
+                              GroupCtx &g, int lane) {
     DevState *st = tv.st;
-    // independent reads first, then the ones that depend on them
-    const int32_t qi_v = batch_idx[j];
-    const int32_t m_v = ws.bm_len[j];
-    const int32_t e_v = ws.bm_node[j];
-    const int64_t to_v = ws.tail_off[j];
-    const int32_t split_id_v = ws.resv_id[2 * j], leaf_id_v = ws.resv_id[2 * j + 1], tok_m_v = ws.next_tok[j];
-    const uint64_t clock0 = st->clock0;
-    const int64_t pool_top = st->pool_top;
-    const int32_t qi = uni(qi_v);
-    const int32_t m = uni(m_v);
-    const int32_t e = uni(e_v);
-    const int32_t split_id = uni(split_id_v), leaf_id = uni(leaf_id_v), tok_m = uni(tok_m_v);
-    const int64_t qoff_v = q.off[qi];
-    const int32_t L_v = q.len[qi];
-    const int32_t de_e_v = ld_i32(&tv.depth_end[e]);
-    const int64_t qoff = uni64(qoff_v);
-    const int32_t L = uni(L_v);
-    const int32_t de_e = uni(de_e_v);
-    const uint64_t tick = clock0 + (uint64_t)j;
-    const int64_t tail_base = uni64(pool_top + to_v);  // pool index holding x[m]
-    const int32_t *__restrict__ x = q.tokens + qoff;
+    const int32_t m = in.m, e = in.e, split_id = in.split_id, leaf_id = in.leaf_id, tok_m = in.tok_m;
+    const int32_t L = in.L, de_e = in.de_e;
+    const uint64_t tick = g.clock0 + (uint64_t)j;
+    const int64_t tail_base = g.pool_top + in.to;  // pool index holding x[m]
+    const int32_t *__restrict__ x = q.tokens + in.qoff;
 
     int32_t cur = e;
     int32_t d = m;
@@ -527,24 +560,46 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const int32_t 
         // The match stopped inside the edge that node e had before this commit. Earlier prompts of
         // this group may have cut that edge into a chain of pieces ending in e; find the piece
         // whose span (start, end] contains depth m.
-        NodeRec rec = load_node(tv, cur);
+        NodeRec rec;
+        int32_t s = -1;
+        if (g.piece >= 0 && m <= g.piece_rec.depth_end) {
+            cur = g.piece;
+            rec = g.piece_rec;
+            s = g.piece_slot;
+        } else {
+            rec = load_node(tv, cur);
+        }
         for (int guard = 0; guard <= tv.max_batch + 1; ++guard) {
             if (rec.depth_end - rec.edge_len < m) break;
             cur = rec.parent;
             rec = load_node(tv, cur);
+            s = -1;
         }
+        g.piece = cur;
+        g.piece_rec = rec;
+        g.piece_slot = s;
         if (m < rec.depth_end) {
             int32_t ds = rec.depth_end - rec.edge_len;
-            int32_t c2, el2;
-            int64_t eo2;
-            int32_t first = uni(tv.pool[rec.edge_off]);
-            int32_t s = slot_find_live(tv, make_key(rec.parent, first), c2, el2, eo2);
-            if (s < 0 || c2 != cur || m - ds <= 0) {
+            if (s < 0) {
+                int32_t c2, el2;
+                int64_t eo2;
+                int32_t first = uni(tv.pool[rec.edge_off]);
+                s = slot_find_live(tv, make_key(rec.parent, first), c2, el2, eo2);
+                if (s >= 0 && c2 != cur) s = -1;
+            }
+            if (s < 0 || m - ds <= 0) {
                 if (lane == 0) flag_error(st, kDevInternal);
                 return;
             }
             int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane);
             if (up < 0) return;
+            // the upper part takes over the slot and the start of the edge
+            g.piece = up;
+            g.piece_slot = s;
+            g.piece_rec.parent = rec.parent;
+            g.piece_rec.edge_len = m - ds;
+            g.piece_rec.depth_end = m;
+            g.piece_rec.edge_off = rec.edge_off;
             cur = up;
             fresh = true;
         }
@@ -634,7 +689,13 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
         for (int t = 0; t < 16; ++t) dup |= (base + t * kWave + lane < g) && (kk[t] == key);
     }
     if (__ballot(dup)) return;
-    insert_prompt(tv, q, batch_idx, ws, g, lane);
+    GroupCtx ctx;
+    ctx.clock0 = st->clock0;
+    ctx.pool_top = st->pool_top;
+    ctx.piece = -1;
+    ctx.piece_slot = -1;
+    ctx.piece_rec = NodeRec{};
+    insert_prompt(tv, q, ws, g, member_from_lane(member_load(tv, q, batch_idx, ws, g), 0), ctx, lane);
     // later members of the group, 4096 candidates at a time: bit t of `mine` = candidate base+64t+lane
     for (int32_t base = g + 1; base < nb; base += 64 * kWave) {
         uint64_t mine = 0;
@@ -648,10 +709,14 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
         if (!__ballot(mine != 0)) continue;
         for (int32_t t = 0; t < 64 && base + t * kWave < nb; ++t) {
             uint64_t mask = __ballot((mine >> t) & 1ull);
+            if (!mask) continue;
+            // every lane that owns a member of this row fetches that member's inputs
+            const int32_t own = base + t * kWave + lane;
+            const MemberIn mv = member_load(tv, q, batch_idx, ws, ((mine >> t) & 1ull) ? own : g);
             while (mask) {
                 int32_t b = (int32_t)__builtin_ctzll(mask);
                 mask &= mask - 1ull;
-                insert_prompt(tv, q, batch_idx, ws, base + t * kWave + b, lane);
+                insert_prompt(tv, q, ws, base + t * kWave + b, member_from_lane(mv, b), ctx, lane);
             }
         }
     }
