@@ -502,9 +502,8 @@ struct MemberIn {
     int32_t qi, m, e, split_id, leaf_id, tok_m, L, de_e;
     int64_t to, qoff;
 };
-__device__ __forceinline__ MemberIn member_load(const TreeView &tv, const QView &q,
-                                                const int32_t *__restrict__ batch_idx, const CommitWs &ws, int32_t j) {
-    MemberIn v;
+__device__ __forceinline__ void member_load_own(MemberIn &v, const int32_t *__restrict__ batch_idx, const CommitWs &ws,
+                                                int32_t j) {  // indexed by the prompt's place in the batch
     v.qi = batch_idx[j];
     v.m = ws.bm_len[j];
     v.e = ws.bm_node[j];
@@ -512,9 +511,17 @@ __device__ __forceinline__ MemberIn member_load(const TreeView &tv, const QView 
     v.split_id = ws.resv_id[2 * j];
     v.leaf_id = ws.resv_id[2 * j + 1];
     v.tok_m = ws.next_tok[j];
+}
+__device__ __forceinline__ void member_load_refs(MemberIn &v, const TreeView &tv, const QView &q) {  // behind qi and e
     v.qoff = q.off[v.qi];
     v.L = q.len[v.qi];
     v.de_e = ld_i32(&tv.depth_end[v.e]);
+}
+__device__ __forceinline__ MemberIn member_load(const TreeView &tv, const QView &q,
+                                                const int32_t *__restrict__ batch_idx, const CommitWs &ws, int32_t j) {
+    MemberIn v;
+    member_load_own(v, batch_idx, ws, j);
+    member_load_refs(v, tv, q);
     return v;
 }
 __device__ __forceinline__ MemberIn member_from_lane(const MemberIn &v, int b) {
@@ -668,57 +675,84 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
 __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                      CommitWs ws) {
     DevState *st = tv.st;
-    if (st->skip) return;
     const int lane = threadIdx.x;
-    const int32_t g = blockIdx.x;
-    const int32_t nb = st->nb;
-    if (g >= nb) return;
-    const uint64_t key = ws.gkey[g];
-    if (key == kNoGroup) return;
-    // the first prompt of a group (in pick order) owns the group; the compares are independent
-    // loads, so no early exit inside the loop
-    bool dup = false;
-    for (int32_t base = 0; base < g; base += 16 * kWave) {
-        uint64_t kk[16];
+    const int32_t g = blockIdx.x;  // below the capacity of batch_idx and of the per-prompt arrays
+    constexpr int kRows = 16;      // group keys of the first 1,024 prompts: one request per lane and row
+    // One round trip for everything that does not depend on anything else: the commit's state, the
+    // keys, and this prompt's own inputs (read before it is known that g is an admitted prompt;
+    // nothing is followed from them until then).
+    const int32_t skip_v = st->skip;
+    const int32_t nb_v = st->nb;
+    const uint64_t key_v = ws.gkey[g];
+    uint64_t kk[kRows];
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {  // sixteen rows requested together
-            const int32_t i = base + t * kWave + lane;
-            kk[t] = ws.gkey[i < g ? i : g];
-        }
-#pragma unroll
-        for (int t = 0; t < 16; ++t) dup |= (base + t * kWave + lane < g) && (kk[t] == key);
+    for (int t = 0; t < kRows; ++t) {
+        const int32_t i = t * kWave + lane;
+        kk[t] = ws.gkey[i < tv.max_batch ? i : tv.max_batch - 1];
     }
-    if (__ballot(dup)) return;
     GroupCtx ctx;
     ctx.clock0 = st->clock0;
     ctx.pool_top = st->pool_top;
     ctx.piece = -1;
     ctx.piece_slot = -1;
     ctx.piece_rec = NodeRec{};
-    insert_prompt(tv, q, ws, g, member_from_lane(member_load(tv, q, batch_idx, ws, g), 0), ctx, lane);
-    // later members of the group, 4096 candidates at a time: bit t of `mine` = candidate base+64t+lane
-    for (int32_t base = g + 1; base < nb; base += 64 * kWave) {
+    MemberIn lead;
+    member_load_own(lead, batch_idx, ws, g);
+    if (uni(skip_v)) return;
+    const int32_t nb = uni(nb_v);
+    if (g >= nb) return;
+    const uint64_t key = uni64(key_v);
+    if (key == kNoGroup) return;
+    member_load_refs(lead, tv, q);
+    // the first prompt of a group (in pick order) owns the group; bit t of `mine` = prompt 64t+lane
+    // is a later member
+    bool dup = false;
+    uint32_t mine0 = 0;
+#pragma unroll
+    for (int t = 0; t < kRows; ++t) {
+        const int32_t i = t * kWave + lane;
+        const bool eq = i < nb && kk[t] == key;
+        dup |= eq && i < g;
+        if (eq && i > g) mine0 |= 1u << t;
+    }
+    for (int32_t base = kRows * kWave; base < g; base += 16 * kWave) {
+        uint64_t k2[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {  // sixteen rows requested together
+            const int32_t i = base + t * kWave + lane;
+            k2[t] = ws.gkey[i < g ? i : g];
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) dup |= (base + t * kWave + lane < g) && (k2[t] == key);
+    }
+    if (__ballot(dup)) return;
+    insert_prompt(tv, q, ws, g, member_from_lane(lead, 0), ctx, lane);
+    // later members of the group; every lane that owns a member of a row fetches that member's inputs
+    auto row = [&](int32_t row_base, bool is_mine) {
+        uint64_t mask = __ballot(is_mine);
+        if (!mask) return;
+        const MemberIn mv = member_load(tv, q, batch_idx, ws, is_mine ? row_base + lane : g);
+        while (mask) {
+            int32_t b = (int32_t)__builtin_ctzll(mask);
+            mask &= mask - 1ull;
+            insert_prompt(tv, q, ws, row_base + b, member_from_lane(mv, b), ctx, lane);
+        }
+    };
+    if (__ballot(mine0 != 0)) {
+        for (int t = g / kWave; t < kRows; ++t) row(t * kWave, (mine0 >> t) & 1u);
+    }
+    // beyond the first 1,024: 4096 candidates at a time, bit t of `mine` = candidate base+64t+lane
+    for (int32_t base = g + 1 > kRows * kWave ? g + 1 : kRows * kWave; base < nb; base += 64 * kWave) {
         uint64_t mine = 0;
         const int32_t rows = (nb - base + kWave - 1) / kWave < 64 ? (nb - base + kWave - 1) / kWave : 64;
 #pragma unroll 8
         for (int32_t t = 0; t < rows; ++t) {
             int32_t i = base + t * kWave + lane;
-            uint64_t kk = ws.gkey[i < nb ? i : nb - 1];
-            if (i < nb && kk == key) mine |= (1ull << t);
+            uint64_t k1 = ws.gkey[i < nb ? i : nb - 1];
+            if (i < nb && k1 == key) mine |= (1ull << t);
         }
         if (!__ballot(mine != 0)) continue;
-        for (int32_t t = 0; t < 64 && base + t * kWave < nb; ++t) {
-            uint64_t mask = __ballot((mine >> t) & 1ull);
-            if (!mask) continue;
-            // every lane that owns a member of this row fetches that member's inputs
-            const int32_t own = base + t * kWave + lane;
-            const MemberIn mv = member_load(tv, q, batch_idx, ws, ((mine >> t) & 1ull) ? own : g);
-            while (mask) {
-                int32_t b = (int32_t)__builtin_ctzll(mask);
-                mask &= mask - 1ull;
-                insert_prompt(tv, q, ws, base + t * kWave + b, member_from_lane(mv, b), ctx, lane);
-            }
-        }
+        for (int32_t t = 0; t < 64 && base + t * kWave < nb; ++t) row(base + t * kWave, (mine >> t) & 1ull);
     }
 }
 
