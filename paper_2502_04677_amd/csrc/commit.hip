@@ -444,11 +444,12 @@ __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key,
 // Returns the new upper node (wave-uniform) or -1.
 __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs &ws, int32_t j, int32_t c,
                                               const NodeRec &rec, int32_t s, int32_t at, uint64_t tick, int32_t new_id,
-                                              int lane, bool have_low = false, int32_t low_known = 0) {
-    int32_t up = -1;
+                                              int lane, int32_t &low_first_out, int32_t &low_slot_out,
+                                              bool have_low = false, int32_t low_known = 0) {
+    int32_t up = -1, low_first = 0, low_slot = -1;
     if (lane == 0) {
         // first token of the lower part (tokens never move)
-        int32_t low_first = have_low ? low_known : tv.pool[rec.edge_off + at];
+        low_first = have_low ? low_known : tv.pool[rec.edge_off + at];
         up = new_id;
         if (up < 0) flag_error(tv.st, 1u);
         if (up > 0) {
@@ -465,11 +466,13 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs
             tv.edge_off[c] = eo + at;
             tv.edge_len[c] = el - at;
             tv.parent[c] = up;
-            slot_insert(tv, make_key(up, low_first), c, el - at, eo + at);
-            ws.used[j] |= 1;
+            low_slot = slot_insert(tv, make_key(up, low_first), c, el - at, eo + at);
+            ws.used[j] = 1;  // (zero since the plan; a split comes before the prompt's leaf)
         }
     }
     up = uni(__shfl(up, 0));
+    low_first_out = uni(__shfl(low_first, 0));
+    low_slot_out = uni(__shfl(low_slot, 0));
     __syncthreads();
     return up;
 }
@@ -546,10 +549,42 @@ __device__ __forceinline__ MemberIn member_from_lane(const MemberIn &v, int b) {
 struct GroupCtx {
     uint64_t clock0;
     int64_t pool_top;
+    // The table entries this wavefront has made in this commit, one per lane.  Everything a member
+    // of the group can meet below its stop was made by this wavefront (nothing continued the
+    // prompt there before, and other groups stop elsewhere), so a lookup is a compare across the
+    // lanes; the table in memory is written all the same and takes over if 64 entries are not enough.
+    int32_t c_parent, c_tok, c_child, c_el, c_slot;
+    int64_t c_eo;
+    int32_t n_ent;
+    bool cache_ok;
     int32_t piece;  // -1: none yet
     int32_t piece_slot;  // slot of `piece` in its parent's table, -1 if not known
     NodeRec piece_rec;
 };
+
+__device__ __forceinline__ void made_add(GroupCtx &g, int lane, int32_t parent, int32_t tok, int32_t child, int32_t el,
+                                         int64_t eo, int32_t slot) {
+    if (g.n_ent >= kWave || slot < 0) {
+        g.cache_ok = false;
+        return;
+    }
+    if (lane == g.n_ent) {
+        g.c_parent = parent;
+        g.c_tok = tok;
+        g.c_child = child;
+        g.c_el = el;
+        g.c_eo = eo;
+        g.c_slot = slot;
+    }
+    ++g.n_ent;
+}
+// the entry in table slot `slot` now leads to `child` over `el` tokens (its edge was cut)
+__device__ __forceinline__ void made_cut(GroupCtx &g, int lane, int32_t slot, int32_t child, int32_t el) {
+    if (lane < g.n_ent && g.c_slot == slot) {
+        g.c_child = child;
+        g.c_el = el;
+    }
+}
 
 __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs &ws, int32_t j, const MemberIn &in,
                               GroupCtx &g, int lane) {
@@ -598,8 +633,11 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
                 if (lane == 0) flag_error(st, kDevInternal);
                 return;
             }
-            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane);
+            int32_t low_first, low_slot;
+            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane, low_first, low_slot);
             if (up < 0) return;
+            made_cut(g, lane, s, up, m - ds);
+            made_add(g, lane, up, low_first, cur, rec.edge_len - (m - ds), rec.edge_off + (int64_t)(m - ds), low_slot);
             // the upper part takes over the slot and the start of the edge
             g.piece = up;
             g.piece_slot = s;
@@ -616,12 +654,24 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
     // just made has no children to look up, and a node reached through its table slot is described
     // by that slot: a member of a large group costs a lookup, a compare and its stores.
     int32_t tok = tok_m;  // x[d] (the first unmatched token came with the plan)
+    bool did_split = fresh;  // fresh here: the stop lay inside an edge and this prompt cut it
     while (d < L) {
-        int32_t c = -1, el = 0;
+        int32_t c = -1, el = 0, s = -1;
         int64_t eo = 0;
-        const int32_t s = fresh ? -1 : slot_find_live(tv, make_key(cur, tok), c, el, eo);
+        if (g.cache_ok) {
+            const uint64_t hit = __ballot(lane < g.n_ent && g.c_parent == cur && g.c_tok == tok);
+            if (hit) {
+                const int b = (int)__builtin_ctzll(hit);
+                c = uni(__shfl(g.c_child, b));
+                el = uni(__shfl(g.c_el, b));
+                eo = uni64(__shfl(g.c_eo, b));
+                s = uni(__shfl(g.c_slot, b));
+            }
+        } else if (!fresh) {
+            s = slot_find_live(tv, make_key(cur, tok), c, el, eo);
+        }
         if (s < 0) {
-            int32_t leaf = -1;
+            int32_t leaf = -1, leaf_slot = -1;
             if (lane == 0) {
                 leaf = leaf_id;
                 if (leaf < 0) flag_error(st, 1u);
@@ -632,14 +682,16 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
                     tv.edge_len[leaf] = L - d;
                     tv.depth_end[leaf] = L;
                     tv.tick[leaf] = tick;
-                    slot_insert(tv, make_key(cur, tok), leaf, L - d, off);
-                    ws.used[j] |= 2;
+                    leaf_slot = slot_insert(tv, make_key(cur, tok), leaf, L - d, off);
+                    ws.used[j] = did_split ? 3 : 2;
                     ws.leaf_tok[j] = L - d;
                 }
             }
             leaf = uni(__shfl(leaf, 0));
+            leaf_slot = uni(__shfl(leaf_slot, 0));
             __syncthreads();
             if (leaf < 0) return;
+            made_add(g, lane, cur, tok, leaf, L - d, tail_base + (int64_t)(d - m), leaf_slot);
             cur = leaf;
             d = L;
             break;
@@ -663,8 +715,12 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
         rec.edge_len = el;
         rec.depth_end = d + el;
         rec.edge_off = eo;
-        const int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane, true, b_tok);
+        int32_t low_first, low_slot;
+        const int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane, low_first, low_slot, true, b_tok);
         if (up < 0) return;
+        made_cut(g, lane, s, up, jj);
+        made_add(g, lane, up, low_first, c, el - jj, eo + (int64_t)jj, low_slot);
+        did_split = true;
         cur = up;
         d += jj;
         fresh = true;
@@ -693,6 +749,10 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
     GroupCtx ctx;
     ctx.clock0 = st->clock0;
     ctx.pool_top = st->pool_top;
+    ctx.n_ent = 0;
+    ctx.cache_ok = true;
+    ctx.c_parent = ctx.c_tok = ctx.c_child = ctx.c_el = ctx.c_slot = -1;
+    ctx.c_eo = 0;
     ctx.piece = -1;
     ctx.piece_slot = -1;
     ctx.piece_rec = NodeRec{};

@@ -1195,6 +1195,42 @@ def test_million_query_queue():
     assert s.batch().tolist() == idx_ref.tolist() and s.phase_value() == ph_ref
 
 
+def test_groups_larger_than_a_wavefront():
+    """Hundreds of admitted prompts that stop at the same place of the tree, so that one wavefront
+    inserts them one after the other and makes more table entries than it keeps a record of: stops
+    inside one long edge at many depths (with and without an own tail), and a common new prefix
+    below the root.  Both kinds of commit, then a second batch on top of the first."""
+    rng = np.random.default_rng(83)
+    long = rng.integers(0, 1000, size=600).astype(np.int32)
+    cache = W.generators._from_lists([long.tolist()], [0])
+
+    def batch_of(n_each):
+        out = []
+        for _ in range(n_each):  # tokens >= 1000 never continue the cached edge
+            cut = int(rng.integers(1, 600))
+            out.append(long[:cut].tolist() + (1000 + rng.integers(0, 3, size=int(rng.integers(0, 6)))).tolist())
+        for _ in range(n_each):
+            out.append([2000, 2001] + rng.integers(0, 3, size=int(rng.integers(0, 9))).tolist())
+        order = rng.permutation(len(out))
+        return [out[i] for i in order]
+
+    for n_each in (40, 230):
+        lists = batch_of(n_each) + batch_of(n_each)
+        hq = W.generators._from_lists(lists, list(range(len(lists))))
+        n = len(lists)
+        w = W.Workload("one-group", cache, hq, 1, n // 2, 1 << 40)
+        s, ref, q = _setup(w, max_batch=n // 2, extra_prompts=n)
+        _say(f"large groups: {n_each} prompts inside one edge and {n_each} below a new prefix, twice")
+        # FCFS takes the first half, then (the picks are not removed from this queue) longest match
+        # takes those again or their equals: every prompt is present by then, ticks only
+        ph = _check_step(s, ref, q, hq, 1, n // 2, 0, 1 << 40, fifo=True)
+        _check_step(s, ref, q, hq, K_INF, n // 2, ph, 1 << 40, fifo=True)
+        # the second half on top of the first: pieces of the old edge are cut again
+        tail = W.take_prompts(hq, np.arange(n // 2, n))
+        q2 = K.DeviceQueries.from_host(tail, "cuda:0")
+        _check_step(s, ref, q2, tail, 1, n // 2, 0, 1 << 40, fifo=True)
+
+
 def test_largest_batch_and_very_long_prompts():
     """A commit of 65,536 prompts at once (the largest batch a configuration may name), and prompts
     of several hundred thousand tokens (edges far longer than any window of the match kernel)."""
