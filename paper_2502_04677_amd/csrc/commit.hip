@@ -328,18 +328,23 @@ __global__ __launch_bounds__(256) void k_hash_fill(TreeView tv, kLPM_stats *__re
 __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                     CommitWs ws, int verify) {
     DevState *st = tv.st;
-    if (st->skip) return;
-    const int32_t j = blockIdx.x;
-    if (j >= st->nb) return;
+    const int32_t j = blockIdx.x;  // below the capacity of batch_idx and of the per-prompt arrays
+    // the state words and this prompt's plan come in one round trip; nothing is followed from the
+    // plan before j is known to be an admitted prompt
+    const int32_t skip = st->skip, nb = st->nb;
+    const int64_t pool_top = st->pool_top;
     const int32_t qi = batch_idx[j];
     const int32_t m = ws.bm_len[j];
+    const int32_t e = ws.bm_node[j];
+    const int64_t to = ws.tail_off[j];
+    if (skip || j >= nb) return;
     const int32_t L = q.len[qi];
     const int32_t *__restrict__ src = q.tokens + q.off[qi] + m;
-    if (verify && threadIdx.x == 0 && !hinted_match_ok(tv, src - m, L, m, ws.bm_node[j])) {
+    if (verify && threadIdx.x == 0 && !hinted_match_ok(tv, src - m, L, m, e)) {
         st->skip = 1;
         atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
     }
-    int32_t *__restrict__ dst = tv.pool + st->pool_top + ws.tail_off[j];
+    int32_t *__restrict__ dst = tv.pool + pool_top + to;
     const int32_t len = L - m;
     // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
     for (int32_t base = 0; base < len; base += 8 * (int32_t)blockDim.x) {
@@ -1170,9 +1175,14 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
     for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
                        (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t node_key) {
         if (node_key <= cut) {
+            // (the place on the free stack is asked for together with the node's fields: it does
+            // not depend on them)
+            const int32_t pa = tv.parent[id];
+            const int64_t eo = tv.edge_off[id];
+            const int32_t pos = atomicAdd(&st->free_cnt, 1);
             tv.edge_len[id] = 0;
             // leave a tombstone where the parent pointed at this node
-            const uint64_t key = make_key(tv.parent[id], tv.pool[tv.edge_off[id]]);
+            const uint64_t key = make_key(pa, tv.pool[eo]);
             uint32_t h = hash_key(key) & tv.slot_mask;
             for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
                 uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1183,7 +1193,6 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
                 if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
                 h = (h + 1) & tv.slot_mask;
             }
-            int32_t pos = atomicAdd(&st->free_cnt, 1);
             if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
             atomicAdd(&s_tok, (unsigned long long)len);
             atomicAdd(&s_cnt, 1);
