@@ -19,6 +19,7 @@
 //      nodes ordered by (tick ascending, depth descending) that frees enough tokens; the cut is
 //      found by a most-significant-digit-first search over weighted digit histograms, no sort.
 #include "klpm_internal.hpp"
+#include "bitonic.hpp"
 
 namespace klpm {
 
@@ -1128,20 +1129,7 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
     }
     __syncthreads();
-    for (int32_t size = 2; size <= np2; size <<= 1) {
-        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int32_t t = tid; t < (np2 >> 1); t += 256) {
-                const int32_t a = 2 * t - (t & (stride - 1)), b = a + stride;
-                const bool up = (a & size) == 0;
-                const uint64_t ka = s_key[a], kb = s_key[b];
-                if ((ka > kb) == up) {
-                    s_key[a] = kb; s_key[b] = ka;
-                    const int32_t la = s_len[a]; s_len[a] = s_len[b]; s_len[b] = la;
-                }
-            }
-            __syncthreads();
-        }
-    }
+    bitonic_sort_lds<256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
     // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
     // reaches the remainder is the last one to go
     const int64_t rem = st->evict_rem;

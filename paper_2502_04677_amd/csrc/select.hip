@@ -10,6 +10,7 @@
 // the picked set is exactly {rank_A < ia} U {rank_L < il}, which gives an O(1) "already picked"
 // test and lets one wavefront resolve a whole k-cycle with two ballots.
 #include "klpm_internal.hpp"
+#include "bitonic.hpp"
 
 namespace klpm {
 
@@ -83,20 +84,7 @@ constexpr int kSmallOrdersN = 4096;
 constexpr int kSmallOrdersThreads = 1024;
 
 __device__ __forceinline__ void bitonic_sort_pairs(uint64_t *hi, uint32_t *lo, int32_t np2, int tid) {
-    for (int32_t size = 2; size <= np2; size <<= 1) {
-        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int32_t t = tid; t < (np2 >> 1); t += kSmallOrdersThreads) {
-                const int32_t a = 2 * t - (t & (stride - 1));
-                const int32_t b = a + stride;
-                const bool up = ((a & size) == 0);
-                const uint64_t ha = hi[a], hb = hi[b];
-                const uint32_t la = lo[a], lb = lo[b];
-                const bool gt = ha > hb || (ha == hb && la > lb);
-                if (gt == up) { hi[a] = hb; hi[b] = ha; lo[a] = lb; lo[b] = la; }
-            }
-            __syncthreads();
-        }
-    }
+    bitonic_sort_lds<kSmallOrdersThreads, true>(hi, lo, np2, tid);
 }
 
 __global__ __launch_bounds__(kSmallOrdersThreads) void k_orders_small(const uint64_t *__restrict__ arrival,
@@ -759,18 +747,7 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
     while (np2 < n_cand) np2 <<= 1;
     for (int32_t i = n_cand + tid; i < np2; i += kFifoThreads) cand[i] = ~0ull;
     __syncthreads();
-    for (int32_t size = 2; size <= np2; size <<= 1) {
-        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int32_t t = tid; t < (np2 >> 1); t += kFifoThreads) {
-                int32_t a = 2 * t - (t & (stride - 1));
-                int32_t b = a + stride;
-                bool up = ((a & size) == 0);
-                uint64_t ka = cand[a], kb = cand[b];
-                if ((ka > kb) == up) { cand[a] = kb; cand[b] = ka; }
-            }
-            __syncthreads();
-        }
-    }
+    bitonic_sort_lds<kFifoThreads, false>(cand, nullptr, np2, tid);
     for (int32_t p = tid; p < nb; p += kFifoThreads) {
         l_elem[p] = (uint32_t)cand[p];
         a_in_l[p] = 0xFFFFFFFFu;
@@ -1071,24 +1048,7 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
         if (TIE) l_elem[i] = (i < nb) ? ws.cand_idx[i] : 0xFFFFFFFFu;  // second key word: the index
     }
     __syncthreads();
-    for (int32_t size = 2; size <= np2; size <<= 1) {
-        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int32_t t = tid; t < (np2 >> 1); t += kFifoThreads) {
-                int32_t a = 2 * t - (t & (stride - 1));
-                int32_t b = a + stride;
-                bool up = ((a & size) == 0);
-                uint64_t key_a = cand[a], key_b = cand[b];
-                if (TIE) {
-                    const uint32_t ia = l_elem[a], ib = l_elem[b];
-                    const bool gt = key_a > key_b || (key_a == key_b && ia > ib);
-                    if (gt == up) { cand[a] = key_b; cand[b] = key_a; l_elem[a] = ib; l_elem[b] = ia; }
-                } else {
-                    if ((key_a > key_b) == up) { cand[a] = key_b; cand[b] = key_a; }
-                }
-            }
-            __syncthreads();
-        }
-    }
+    bitonic_sort_lds<kFifoThreads, TIE>(cand, l_elem, np2, tid);
     for (int32_t p = tid; p < nb; p += kFifoThreads) {
         if (!TIE) l_elem[p] = (uint32_t)cand[p];
         a_in_l[p] = 0xFFFFFFFFu;
