@@ -19,7 +19,7 @@
 //      nodes ordered by (tick ascending, depth descending) that frees enough tokens; the cut is
 //      found by a most-significant-digit-first search over weighted digit histograms, no sort.
 #include "klpm_internal.hpp"
-#include "bitonic.hpp"
+#include "lds_sort.hpp"
 
 namespace klpm {
 
@@ -1121,7 +1121,7 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         }
         return;
     }
-    // sort the collected nodes by key (bitonic network in LDS), then the cut
+    // sort the collected nodes by key in LDS, then the cut
     int32_t np2 = 1;
     while (np2 < n) np2 <<= 1;
     for (int32_t i = tid; i < np2; i += 256) {
@@ -1129,7 +1129,7 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
     }
     __syncthreads();
-    bitonic_sort_lds<256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
+    sort_lds<256, kEvictCand / 256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
     // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
     // reaches the remainder is the last one to go
     const int64_t rem = st->evict_rem;

@@ -10,7 +10,7 @@
 // the picked set is exactly {rank_A < ia} U {rank_L < il}, which gives an O(1) "already picked"
 // test and lets one wavefront resolve a whole k-cycle with two ballots.
 #include "klpm_internal.hpp"
-#include "bitonic.hpp"
+#include "lds_sort.hpp"
 
 namespace klpm {
 
@@ -77,14 +77,14 @@ __global__ __launch_bounds__(256) void k_sel_ranks(const uint32_t *__restrict__ 
 }
 
 // ---- both orders of a short queue in one workgroup ----
-// Up to kSmallOrdersN entries: two bitonic sorts in LDS on two-word keys, (arrival, index) for the
+// Up to kSmallOrdersN entries: two sorts in LDS on two-word keys, (arrival, index) for the
 // oldest-first order and (inverted score | tie key, oldest-first rank) for the longest-match order,
 // instead of the ~40 launches of the radix sorts below.
 constexpr int kSmallOrdersN = 4096;
 constexpr int kSmallOrdersThreads = 1024;
 
-__device__ __forceinline__ void bitonic_sort_pairs(uint64_t *hi, uint32_t *lo, int32_t np2, int tid) {
-    bitonic_sort_lds<kSmallOrdersThreads, true>(hi, lo, np2, tid);
+__device__ __forceinline__ void sort_pairs(uint64_t *hi, uint32_t *lo, int32_t np2, int tid) {
+    sort_lds<kSmallOrdersThreads, kSmallOrdersN / kSmallOrdersThreads, true>(hi, lo, np2, tid);
 }
 
 __global__ __launch_bounds__(kSmallOrdersThreads) void k_orders_small(const uint64_t *__restrict__ arrival,
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kSmallOrdersThreads) void k_orders_small(const uint
         lo[i] = i < n ? (uint32_t)i : 0xFFFFFFFFu;
     }
     __syncthreads();
-    bitonic_sort_pairs(hi, lo, np2, tid);
+    sort_pairs(hi, lo, np2, tid);
     for (int32_t r = tid; r < n; r += kSmallOrdersThreads) {
         const uint32_t i = lo[r];
         oa[r] = i;
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kSmallOrdersThreads) void k_orders_small(const uint
         lo[r] = r < n ? (uint32_t)r : 0xFFFFFFFFu;
     }
     __syncthreads();
-    bitonic_sort_pairs(hi, lo, np2, tid);
+    sort_pairs(hi, lo, np2, tid);
     for (int32_t p = tid; p < n; p += kSmallOrdersThreads) {
         const uint32_t i = oa[lo[p]];
         order_l[p] = i;
@@ -742,12 +742,12 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         __syncthreads();
     }
     __syncthreads();
-    // sort them by (-match_len, index): bitonic network over the next power of two
+    // sort them by (-match_len, index), padded to the next power of two
     int32_t np2 = 1;
     while (np2 < n_cand) np2 <<= 1;
     for (int32_t i = n_cand + tid; i < np2; i += kFifoThreads) cand[i] = ~0ull;
     __syncthreads();
-    bitonic_sort_lds<kFifoThreads, false>(cand, nullptr, np2, tid);
+    sort_lds<kFifoThreads, kFifoMaxBatch / kFifoThreads, false>(cand, nullptr, np2, tid);
     for (int32_t p = tid; p < nb; p += kFifoThreads) {
         l_elem[p] = (uint32_t)cand[p];
         a_in_l[p] = 0xFFFFFFFFu;
@@ -1048,7 +1048,7 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
         if (TIE) l_elem[i] = (i < nb) ? ws.cand_idx[i] : 0xFFFFFFFFu;  // second key word: the index
     }
     __syncthreads();
-    bitonic_sort_lds<kFifoThreads, TIE>(cand, l_elem, np2, tid);
+    sort_lds<kFifoThreads, kFifoMaxBatch / kFifoThreads, TIE>(cand, l_elem, np2, tid);
     for (int32_t p = tid; p < nb; p += kFifoThreads) {
         if (!TIE) l_elem[p] = (uint32_t)cand[p];
         a_in_l[p] = 0xFFFFFFFFu;
