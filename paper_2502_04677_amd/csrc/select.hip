@@ -1023,17 +1023,28 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
                                                             uint32_t *__restrict__ phase_inout,
                                                             int32_t *__restrict__ batch_idx,
                                                             int32_t *__restrict__ n_selected) {
-    const int32_t n = nn.get();
-    const uint32_t k = ka.get();
     __shared__ uint64_t cand[kFifoMaxBatch];
     __shared__ uint32_t l_elem[kFifoMaxBatch];
     __shared__ uint32_t a_in_l[kFifoMaxBatch];
     const int tid = threadIdx.x;
+    // one round trip: the scalars, the verdict of the order check and this thread's winners (the
+    // winner arrays hold kFifoMaxBatch entries whatever nb is; what lies past nb is not used)
+    constexpr int kPer = kFifoMaxBatch / kFifoThreads;
+    const int32_t n = nn.get();
+    const uint32_t k = ka.get();
+    const uint32_t phase_in = *phase_inout;
+    const int32_t violated = ws.meta->violated;
+    uint64_t own[kPer];
+    uint32_t own_idx[kPer];
+#pragma unroll
+    for (int c = 0; c < kPer; ++c) {
+        own[c] = ws.cand[tid + c * kFifoThreads];
+        own_idx[c] = TIE ? ws.cand_idx[tid + c * kFifoThreads] : 0u;
+    }
     const int32_t nb = batch < n ? batch : n;
     const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
-    const uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
-    __syncthreads();
-    if (ws.meta->violated) {  // the caller's promise does not hold: select nothing, say so
+    const uint32_t phase = lpm_only ? 0u : (phase_in % k);
+    if (violated) {  // the caller's promise does not hold: select nothing, say so
         if (tid == 0) *n_selected = -1;
         return;
     }
@@ -1043,9 +1054,13 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
     }
     int32_t np2 = 1;
     while (np2 < nb) np2 <<= 1;
-    for (int32_t i = tid; i < np2; i += kFifoThreads) {
-        cand[i] = (i < nb) ? ws.cand[i] : ~0ull;
-        if (TIE) l_elem[i] = (i < nb) ? ws.cand_idx[i] : 0xFFFFFFFFu;  // second key word: the index
+#pragma unroll
+    for (int c = 0; c < kPer; ++c) {
+        const int32_t i = tid + c * kFifoThreads;
+        if (i < np2) {
+            cand[i] = (i < nb) ? own[c] : ~0ull;
+            if (TIE) l_elem[i] = (i < nb) ? own_idx[c] : 0xFFFFFFFFu;  // second key word: the index
+        }
     }
     __syncthreads();
     sort_lds<kFifoThreads, kFifoMaxBatch / kFifoThreads, TIE>(cand, l_elem, np2, tid);
