@@ -823,7 +823,8 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 }
 
 // ------------------------------------------------------------------ ticks, then publish the inserts
-__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass) {
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass,
+                                               int evict_enqueued) {
     DevState *st = tv.st;
     const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
     const int32_t v0 = j < tv.max_batch ? ws.end_node[j] : kRoot;  // requested together with the state words
@@ -941,6 +942,12 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
             if (tick_bits < 64 && (st->clock >> tick_bits) != 0) {
                 // the eviction passes enqueued behind this kernel were sized for a smaller clock
                 flag_error(st, 16u /* KLPM_DEV_CLOCK_RANGE */);
+                need = 0;
+            }
+            if (need > 0 && !evict_enqueued) {
+                // the host left the eviction kernels out because the budget is at least what the
+                // pool can hold: being over it means the counters are wrong
+                flag_error(st, kDevInternal);
                 need = 0;
             }
             if (need > 0) {
@@ -1232,19 +1239,24 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws, hint_len ? 1 : 0);
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
+    // Every live edge sits in the active half of the token pool, so a budget of at least that half
+    // can never be exceeded: the eviction kernels (no-ops that still cost a launch each) are left out.
+    const bool may_evict = budget < tv.pool_half;
     hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,
-                       budget, protect, tick_bits, n_pass);
-    // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
-    unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
-    if (ge > 256u) ge = 256u;
-    for (int p = 0; p < n_pass; ++p) {
-        // the first digit takes what the others leave over, so that the last one ends at final_shift
-        const int shift = final_shift + kEvictDigitBits * (n_pass - 1 - p);
-        const int width = p == 0 ? hist_bits - kEvictDigitBits * (n_pass - 1) : kEvictDigitBits;
-        hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, shift, width, t->depth_bits);
+                       budget, protect, tick_bits, n_pass, may_evict ? 1 : 0);
+    if (may_evict) {
+        // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
+        unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
+        if (ge > 256u) ge = 256u;
+        for (int p = 0; p < n_pass; ++p) {
+            // the first digit takes what the others leave over, so that the last one ends at final_shift
+            const int shift = final_shift + kEvictDigitBits * (n_pass - 1 - p);
+            const int width = p == 0 ? hist_bits - kEvictDigitBits * (n_pass - 1) : kEvictDigitBits;
+            hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, shift, width, t->depth_bits);
+        }
+        hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits);
+        hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
     }
-    hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits);
-    hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
     // maintenance and table refill usually have nothing to do: few workgroups with grid-stride loops
     // (compaction works one wavefront per node)
     unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
