@@ -1226,8 +1226,10 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     // digit passes narrow the tick down to a window of 2^tail ticks, the sorting pass does the rest
     const int tail = tick_bits < kEvictTailTicks ? tick_bits : kEvictTailTicks;
     const int hist_bits = tick_bits - tail;
-    const int n_pass = (hist_bits + kEvictDigitBits - 1) / kEvictDigitBits;  // <= 6: the arena holds six histograms
-    const int final_shift = t->depth_bits + tail;  // key bits left to the sorting pass
+    // (a tree of no more nodes than the sorting pass takes needs no digit passes at all)
+    const bool tiny = tv.max_nodes <= kEvictCand;
+    const int n_pass = tiny ? 0 : (hist_bits + kEvictDigitBits - 1) / kEvictDigitBits;  // <= 6: the arena holds six histograms
+    const int final_shift = tiny ? key_bits : t->depth_bits + tail;  // key bits left to the sorting pass
     t->clock_ub = clock_ub;
     if (batch_cap > 0 && !hint_len) {
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
