@@ -1070,11 +1070,53 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * kEvictBins, width, pass == 0);
 }
 
+// Removes every live, unprotected node with key <= cut among the nodes first, first + stride, ..:
+// tombstone in the parent's table slot, id back on the free stack; tokens and nodes removed are
+// added to the two workgroup counters.
+__device__ __forceinline__ void evict_apply_sweep(const TreeView &tv, DevState *st, uint64_t cut, uint64_t keep_from,
+                                                  int32_t n_slots, int depth_bits, int64_t first, int64_t stride,
+                                                  unsigned long long *s_tok, int *s_cnt) {
+    for_each_evictable(tv, n_slots, keep_from, depth_bits, first, stride, [&](int64_t id, int32_t len, uint64_t node_key) {
+        if (node_key <= cut) {
+            // (the place on the free stack is asked for together with the node's fields: it does
+            // not depend on them)
+            const int32_t pa = tv.parent[id];
+            const int64_t eo = tv.edge_off[id];
+            const int32_t pos = atomicAdd(&st->free_cnt, 1);
+            tv.edge_len[id] = 0;
+            // leave a tombstone where the parent pointed at this node
+            const uint64_t key = make_key(pa, tv.pool[eo]);
+            uint32_t h = hash_key(key) & tv.slot_mask;
+            for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+                uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (kk == key) {
+                    __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
+                h = (h + 1) & tv.slot_mask;
+            }
+            if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
+            atomicAdd(s_tok, (unsigned long long)len);
+            atomicAdd(s_cnt, 1);
+        }
+    });
+}
+// Books the removal (one thread, after every sweep has added its counts).
+__device__ __forceinline__ void evict_apply_publish(const TreeView &tv, DevState *st, int64_t ev_tok, int32_t ev_cnt) {
+    st->total_tokens -= ev_tok;
+    st->n_nodes -= ev_cnt;
+    st->tombstones += ev_cnt;
+    // rebuild the child table only when tombstones start to lengthen the probe sequences
+    if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact) st->need_rebuild = 1;
+}
+
 // Last stretch of the search: collect the nodes whose key agrees with the prefix above bit `shift`;
 // the last workgroup sorts them by key and cuts where their lengths add up to what is left to free.
 // More nodes than fit (very deep paths stamped by few prompts) are handled by the same workgroup
 // with digit passes of its own over all nodes.
-__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
+__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits,
+                                                      int apply_here) {
     DevState *st = tv.st;
     const int do_evict = st->do_evict;
     const uint64_t prefix = st->evict_prefix;
@@ -1086,6 +1128,8 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
     __shared__ int32_t s_len[kEvictCand];
     __shared__ int64_t part[256 / kWave];
     __shared__ unsigned long long s_cut;
+    __shared__ unsigned long long s_tok;
+    __shared__ int s_cnt;
     const int tid = threadIdx.x;
     if (!evict_all) {
         for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
@@ -1100,8 +1144,22 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         });
     }
     if (!last_block_done(st, 10)) return;
+    // (apply_here: the tree is small enough for this workgroup to remove the nodes itself, which
+    // saves the launch of the removal kernel)
+    auto apply = [&](uint64_t cut) {
+        if (tid == 0) { s_tok = 0; s_cnt = 0; }
+        __syncthreads();
+        evict_apply_sweep(tv, st, cut, keep_from, n_slots, depth_bits, 1 + tid, 256, &s_tok, &s_cnt);
+        __syncthreads();
+        if (tid == 0) {
+            st->evicted_tokens = (int64_t)s_tok;
+            st->evicted_nodes = s_cnt;
+            evict_apply_publish(tv, st, (int64_t)s_tok, s_cnt);
+        }
+    };
     if (evict_all) {
         if (tid == 0) st->evict_prefix = ~0ull;
+        if (apply_here) apply(~0ull);
         return;
     }
     const int32_t n = __hip_atomic_load(&st->cand_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1153,6 +1211,7 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
     }
     __syncthreads();
     if (tid == 0) st->evict_prefix = s_cut;
+    if (apply_here) apply(s_cut);
 }
 
 __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int depth_bits) {
@@ -1167,32 +1226,8 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
     const int tid = threadIdx.x;
     if (tid == 0) { s_tok = 0; s_cnt = 0; }
     __syncthreads();
-    for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
-                       (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t node_key) {
-        if (node_key <= cut) {
-            // (the place on the free stack is asked for together with the node's fields: it does
-            // not depend on them)
-            const int32_t pa = tv.parent[id];
-            const int64_t eo = tv.edge_off[id];
-            const int32_t pos = atomicAdd(&st->free_cnt, 1);
-            tv.edge_len[id] = 0;
-            // leave a tombstone where the parent pointed at this node
-            const uint64_t key = make_key(pa, tv.pool[eo]);
-            uint32_t h = hash_key(key) & tv.slot_mask;
-            for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
-                uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (kk == key) {
-                    __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
-                h = (h + 1) & tv.slot_mask;
-            }
-            if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
-            atomicAdd(&s_tok, (unsigned long long)len);
-            atomicAdd(&s_cnt, 1);
-        }
-    });
+    evict_apply_sweep(tv, st, cut, keep_from, n_slots, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                      (int64_t)gridDim.x * blockDim.x, &s_tok, &s_cnt);
     __syncthreads();
     if (tid == 0 && s_cnt) {
         atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
@@ -1202,11 +1237,7 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
         int64_t ev_tok = (int64_t)__hip_atomic_load((unsigned long long *)&st->evicted_tokens, __ATOMIC_RELAXED,
                                                      __HIP_MEMORY_SCOPE_AGENT);
         int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        st->total_tokens -= ev_tok;
-        st->n_nodes -= ev_cnt;
-        st->tombstones += ev_cnt;
-        // rebuild the child table only when tombstones start to lengthen the probe sequences
-        if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact) st->need_rebuild = 1;
+        evict_apply_publish(tv, st, ev_tok, ev_cnt);
     }
 }
 
@@ -1256,8 +1287,9 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
             const int width = p == 0 ? hist_bits - kEvictDigitBits * (n_pass - 1) : kEvictDigitBits;
             hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, shift, width, t->depth_bits);
         }
-        hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits);
-        hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
+        hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits,
+                           tiny ? 1 : 0);
+        if (!tiny) hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
     }
     // maintenance and table refill usually have nothing to do: few workgroups with grid-stride loops
     // (compaction works one wavefront per node)
