@@ -233,6 +233,42 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
 }
 
 // ------------------------------------------------------------------ end-of-commit maintenance (rare work)
+// Pool compaction, one wavefront per node: every live edge span moves into the other half and the
+// span kept in the child table is patched.
+__device__ __forceinline__ void compact_nodes(const TreeView &tv, DevState *st, int64_t wave, int64_t n_waves, int lane) {
+    const int32_t n_slots = st->n_slots;
+    const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
+    for (int64_t id = 1 + wave; id < n_slots; id += n_waves) {
+        int32_t len = uni(tv.edge_len[id]);
+        if (len <= 0) continue;
+        int64_t src = uni64(tv.edge_off[id]);
+        int64_t dst = 0;
+        if (lane == 0) dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)len);
+        dst = uni64(dst);
+        if (dst + len > dst_end) {  // cannot happen while total_tokens <= pool_half
+            if (lane == 0) flag_error(st, 2u);
+            continue;
+        }
+        int32_t first = uni(tv.pool[src]);
+        for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
+        if (lane == 0) {
+            tv.edge_off[id] = dst;
+            int32_t c, el;
+            int64_t eo;
+            int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
+            if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, kDevInternal);
+        }
+    }
+}
+__device__ __forceinline__ void compact_switch(const TreeView &tv, DevState *st) {
+    st->active_half = 1 - st->active_half;
+    st->pool_top = st->compact_cursor;
+}
+__device__ __forceinline__ void clear_table(const TreeView &tv, int64_t first, int64_t stride) {
+    const int64_t n = (int64_t)tv.slot_mask + 1;
+    for (int64_t i = first; i < n; i += stride) tv.slots[i].key = kEmptyKey;
+}
+
 // One launch that usually finds nothing to do.  Either pool compaction - when the active half no
 // longer has room for a worst-case batch and holds garbage, every live edge span moves into the other
 // half, the span kept in the child table is patched, and the last workgroup to finish switches
@@ -241,43 +277,13 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
 __global__ __launch_bounds__(256) void k_maintain(TreeView tv) {
     DevState *st = tv.st;
     if (st->need_compact) {
-        const int lane = threadIdx.x & (kWave - 1);
-        const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-        const int64_t n_waves = (int64_t)gridDim.x * (blockDim.x / kWave);
-        const int32_t n_slots = st->n_slots;
-        const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
-        for (int64_t id = 1 + wave; id < n_slots; id += n_waves) {
-            int32_t len = uni(tv.edge_len[id]);
-            if (len <= 0) continue;
-            int64_t src = uni64(tv.edge_off[id]);
-            int64_t dst = 0;
-            if (lane == 0) dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)len);
-            dst = uni64(dst);
-            if (dst + len > dst_end) {  // cannot happen while total_tokens <= pool_half
-                if (lane == 0) flag_error(st, 2u);
-                continue;
-            }
-            int32_t first = uni(tv.pool[src]);
-            for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
-            if (lane == 0) {
-                tv.edge_off[id] = dst;
-                int32_t c, el;
-                int64_t eo;
-                int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
-                if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, kDevInternal);
-            }
-        }
-        if (last_block_done(st, 0) && threadIdx.x == 0) {
-            st->active_half = 1 - st->active_half;
-            st->pool_top = st->compact_cursor;
-        }
+        compact_nodes(tv, st, (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave,
+                      (int64_t)gridDim.x * (blockDim.x / kWave), threadIdx.x & (kWave - 1));
+        if (last_block_done(st, 0) && threadIdx.x == 0) compact_switch(tv, st);
         return;
     }
-    if (st->need_rebuild) {
-        const int64_t n = (int64_t)tv.slot_mask + 1;
-        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-            tv.slots[i].key = kEmptyKey;
-    }
+    if (st->need_rebuild)
+        clear_table(tv, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
 }
 
 __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict__ out) {
@@ -296,31 +302,55 @@ __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict
 
 // Re-inserts every live node into the (cleared) child table; the last workgroup to finish writes
 // the commit's counters for the caller.
-__global__ __launch_bounds__(256) void k_hash_fill(TreeView tv, kLPM_stats *__restrict__ stats_out) {
-    DevState *st = tv.st;
-    if (st->need_rebuild) {
-        const int32_t n_slots = st->n_slots;
-        for (int64_t id = 1 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < n_slots;
-             id += (int64_t)gridDim.x * blockDim.x) {
-            int32_t len = tv.edge_len[id];
-            if (len <= 0) continue;
-            int64_t off = tv.edge_off[id];
-            uint64_t key = make_key(tv.parent[id], tv.pool[off]);
-            uint32_t h = hash_key(key) & tv.slot_mask;
-            for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
-                unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key,
-                                                    (unsigned long long)kEmptyKey, (unsigned long long)key);
-                if (prev == (unsigned long long)kEmptyKey) {
-                    tv.slots[h].child = (int32_t)id;
-                    tv.slots[h].edge_len = len;
-                    tv.slots[h].edge_off = off;
-                    break;
-                }
-                h = (h + 1) & tv.slot_mask;
+__device__ __forceinline__ void fill_table(const TreeView &tv, DevState *st, int64_t first, int64_t stride) {
+    const int32_t n_slots = st->n_slots;
+    for (int64_t id = 1 + first; id < n_slots; id += stride) {
+        int32_t len = tv.edge_len[id];
+        if (len <= 0) continue;
+        int64_t off = tv.edge_off[id];
+        uint64_t key = make_key(tv.parent[id], tv.pool[off]);
+        uint32_t h = hash_key(key) & tv.slot_mask;
+        for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+            unsigned long long prev = atomicCAS((unsigned long long *)&tv.slots[h].key,
+                                                (unsigned long long)kEmptyKey, (unsigned long long)key);
+            if (prev == (unsigned long long)kEmptyKey) {
+                tv.slots[h].child = (int32_t)id;
+                tv.slots[h].edge_len = len;
+                tv.slots[h].edge_off = off;
+                break;
             }
+            h = (h + 1) & tv.slot_mask;
         }
     }
+}
+
+__global__ __launch_bounds__(256) void k_hash_fill(TreeView tv, kLPM_stats *__restrict__ stats_out) {
+    DevState *st = tv.st;
+    if (st->need_rebuild)
+        fill_table(tv, st, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
     if (last_block_done(st, 3) && threadIdx.x == 0) write_stats(st, stats_out);
+}
+
+// Both of the above by one workgroup, for trees small enough that one launch fewer matters more
+// than how fast the (rare) work itself goes.
+constexpr int kSmallMaintainThreads = 1024;
+__global__ __launch_bounds__(kSmallMaintainThreads) void k_maintain_fill_small(TreeView tv,
+                                                                                kLPM_stats *__restrict__ stats_out) {
+    DevState *st = tv.st;
+    const int tid = threadIdx.x;
+    const int need_compact = st->need_compact, need_rebuild = st->need_rebuild;
+    if (need_compact) {
+        compact_nodes(tv, st, tid / kWave, kSmallMaintainThreads / kWave, tid & (kWave - 1));
+        __syncthreads();
+        if (tid == 0) compact_switch(tv, st);
+    } else if (need_rebuild) {
+        clear_table(tv, tid, kSmallMaintainThreads);
+        __threadfence();
+        __syncthreads();
+        fill_table(tv, st, tid, kSmallMaintainThreads);
+    }
+    __syncthreads();
+    if (tid == 0) write_stats(st, stats_out);
 }
 
 // ------------------------------------------------------------------ tails
@@ -1297,8 +1327,12 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
     if (gn > 1024u) gn = 1024u;
     unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
     if (gf > 128u) gf = 128u;
-    hipLaunchKernelGGL(k_maintain, dim3(gn), dim3(256), 0, stream, tv);
-    hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv, stats_out);
+    if (tiny) {
+        hipLaunchKernelGGL(k_maintain_fill_small, dim3(1), dim3(kSmallMaintainThreads), 0, stream, tv, stats_out);
+    } else {
+        hipLaunchKernelGGL(k_maintain, dim3(gn), dim3(256), 0, stream, tv);
+        hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv, stats_out);
+    }
     return check_launch();
 }
 
