@@ -472,6 +472,7 @@ __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key,
         }
         h = (h + 1) & tv.slot_mask;
     }
+    flag_error(tv.st, kDevInternal);  // (the table has two slots per node: it cannot be full)
     return -1;
 }
 
