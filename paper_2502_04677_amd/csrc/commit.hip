@@ -269,23 +269,6 @@ __device__ __forceinline__ void clear_table(const TreeView &tv, int64_t first, i
     for (int64_t i = first; i < n; i += stride) tv.slots[i].key = kEmptyKey;
 }
 
-// One launch that usually finds nothing to do.  Either pool compaction - when the active half no
-// longer has room for a worst-case batch and holds garbage, every live edge span moves into the other
-// half, the span kept in the child table is patched, and the last workgroup to finish switches
-// halves - or, when evictions have left many tombstones, the child table is emptied for the rebuild
-// that the next kernel does.  (Both at once: compaction now, the rebuild at the next commit.)
-__global__ __launch_bounds__(256) void k_maintain(TreeView tv) {
-    DevState *st = tv.st;
-    if (st->need_compact) {
-        compact_nodes(tv, st, (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave,
-                      (int64_t)gridDim.x * (blockDim.x / kWave), threadIdx.x & (kWave - 1));
-        if (last_block_done(st, 0) && threadIdx.x == 0) compact_switch(tv, st);
-        return;
-    }
-    if (st->need_rebuild)
-        clear_table(tv, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
-}
-
 __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict__ out) {
     if (st->need_rebuild) st->tombstones = 0;  // the table has just been rebuilt
     st->need_rebuild = 0;
@@ -300,8 +283,7 @@ __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict
     out->clock = st->clock;
 }
 
-// Re-inserts every live node into the (cleared) child table; the last workgroup to finish writes
-// the commit's counters for the caller.
+// Re-inserts every live node into the emptied child table.
 __device__ __forceinline__ void fill_table(const TreeView &tv, DevState *st, int64_t first, int64_t stride) {
     const int32_t n_slots = st->n_slots;
     for (int64_t id = 1 + first; id < n_slots; id += stride) {
@@ -324,18 +306,47 @@ __device__ __forceinline__ void fill_table(const TreeView &tv, DevState *st, int
     }
 }
 
-__global__ __launch_bounds__(256) void k_hash_fill(TreeView tv, kLPM_stats *__restrict__ stats_out) {
-    DevState *st = tv.st;
-    if (st->need_rebuild)
-        fill_table(tv, st, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)gridDim.x * blockDim.x);
-    if (last_block_done(st, 3) && threadIdx.x == 0) write_stats(st, stats_out);
+// `count` workgroups call this; true in the last one to arrive.
+__device__ __forceinline__ bool last_of(DevState *st, int slot, int count) {
+    __shared__ int s_last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        s_last = (atomicAdd(&st->done[slot], 1) == count - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (s_last) __threadfence();
+    return s_last != 0;
 }
 
-// Both of the above by one workgroup, for trees small enough that one launch fewer matters more
-// than how fast the (rare) work itself goes.
+// The launch that ends a commit and usually finds nothing to do but hand the counters to the
+// caller.  Either pool compaction - when the active half no longer has room for a worst-case batch
+// and holds garbage, every live edge span moves into the other half, the span kept in the child
+// table is patched, and the last workgroup to finish switches halves - or, when evictions have
+// left many tombstones, the refill of the child table (emptied by the workgroup that decided so).
+// Never both: a commit that compacts leaves the rebuild to a later one.  The grid is sized for
+// the compaction (a wavefront per node); without one only the first kEndBlocks workgroups stay.
+constexpr int kEndBlocks = 128;
+__global__ __launch_bounds__(256) void k_end_commit(TreeView tv, kLPM_stats *__restrict__ stats_out) {
+    DevState *st = tv.st;
+    const int need_compact = st->need_compact, need_rebuild = st->need_rebuild;
+    const int n_blocks = need_compact ? (int)gridDim.x : ((int)gridDim.x < kEndBlocks ? (int)gridDim.x : kEndBlocks);
+    if ((int)blockIdx.x >= n_blocks) return;
+    if (need_compact) {
+        compact_nodes(tv, st, (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave,
+                      (int64_t)gridDim.x * (blockDim.x / kWave), threadIdx.x & (kWave - 1));
+        if (last_of(st, 0, n_blocks) && threadIdx.x == 0) compact_switch(tv, st);
+    } else if (need_rebuild) {
+        fill_table(tv, st, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)n_blocks * blockDim.x);
+    }
+    if (last_of(st, 3, n_blocks) && threadIdx.x == 0) write_stats(st, stats_out);
+}
+
+// The same by one workgroup, for trees small enough that its speed at the (rare) work does not
+// matter.
 constexpr int kSmallMaintainThreads = 1024;
-__global__ __launch_bounds__(kSmallMaintainThreads) void k_maintain_fill_small(TreeView tv,
-                                                                                kLPM_stats *__restrict__ stats_out) {
+__global__ __launch_bounds__(kSmallMaintainThreads) void k_end_commit_small(TreeView tv,
+                                                                             kLPM_stats *__restrict__ stats_out) {
     DevState *st = tv.st;
     const int tid = threadIdx.x;
     const int need_compact = st->need_compact, need_rebuild = st->need_rebuild;
@@ -344,9 +355,6 @@ __global__ __launch_bounds__(kSmallMaintainThreads) void k_maintain_fill_small(T
         __syncthreads();
         if (tid == 0) compact_switch(tv, st);
     } else if (need_rebuild) {
-        clear_table(tv, tid, kSmallMaintainThreads);
-        __threadfence();
-        __syncthreads();
         fill_table(tv, st, tid, kSmallMaintainThreads);
     }
     __syncthreads();
@@ -1134,12 +1142,17 @@ __device__ __forceinline__ void evict_apply_sweep(const TreeView &tv, DevState *
     });
 }
 // Books the removal (one thread, after every sweep has added its counts).
-__device__ __forceinline__ void evict_apply_publish(const TreeView &tv, DevState *st, int64_t ev_tok, int32_t ev_cnt) {
+// Returns whether the child table is to be rebuilt at the end of this commit (the caller's
+// workgroup then empties it: a rare sweep that one workgroup can afford, and the kernel that ends
+// the commit only has to refill).
+__device__ __forceinline__ bool evict_apply_publish(const TreeView &tv, DevState *st, int64_t ev_tok, int32_t ev_cnt) {
     st->total_tokens -= ev_tok;
     st->n_nodes -= ev_cnt;
     st->tombstones += ev_cnt;
     // rebuild the child table only when tombstones start to lengthen the probe sequences
-    if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact) st->need_rebuild = 1;
+    const bool rebuild = (int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact;
+    if (rebuild) st->need_rebuild = 1;
+    return rebuild;
 }
 
 // Last stretch of the search: collect the nodes whose key agrees with the prefix above bit `shift`;
@@ -1185,8 +1198,10 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         if (tid == 0) {
             st->evicted_tokens = (int64_t)s_tok;
             st->evicted_nodes = s_cnt;
-            evict_apply_publish(tv, st, (int64_t)s_tok, s_cnt);
+            s_cnt = evict_apply_publish(tv, st, (int64_t)s_tok, s_cnt) ? 1 : 0;  // (reused: rebuild?)
         }
+        __syncthreads();
+        if (s_cnt) clear_table(tv, tid, 256);
     };
     if (evict_all) {
         if (tid == 0) st->evict_prefix = ~0ull;
@@ -1264,11 +1279,16 @@ __global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, i
         atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
         atomicAdd(&st->evicted_nodes, s_cnt);
     }
-    if (last_block_done(st, 2) && tid == 0) {
-        int64_t ev_tok = (int64_t)__hip_atomic_load((unsigned long long *)&st->evicted_tokens, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-        int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        evict_apply_publish(tv, st, ev_tok, ev_cnt);
+    __shared__ int s_rebuild;
+    if (last_block_done(st, 2)) {
+        if (tid == 0) {
+            int64_t ev_tok = (int64_t)__hip_atomic_load((unsigned long long *)&st->evicted_tokens, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+            int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_rebuild = evict_apply_publish(tv, st, ev_tok, ev_cnt) ? 1 : 0;
+        }
+        __syncthreads();
+        if (s_rebuild) clear_table(tv, tid, blockDim.x);
     }
 }
 
@@ -1322,17 +1342,13 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
                            tiny ? 1 : 0);
         if (!tiny) hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
     }
-    // maintenance and table refill usually have nothing to do: few workgroups with grid-stride loops
-    // (compaction works one wavefront per node)
-    unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
-    if (gn > 1024u) gn = 1024u;
-    unsigned gf = (unsigned)(((int64_t)tv.max_nodes + 255) / 256);
-    if (gf > 128u) gf = 128u;
+    // the end of the commit: grid sized for pool compaction, one wavefront per node
     if (tiny) {
-        hipLaunchKernelGGL(k_maintain_fill_small, dim3(1), dim3(kSmallMaintainThreads), 0, stream, tv, stats_out);
+        hipLaunchKernelGGL(k_end_commit_small, dim3(1), dim3(kSmallMaintainThreads), 0, stream, tv, stats_out);
     } else {
-        hipLaunchKernelGGL(k_maintain, dim3(gn), dim3(256), 0, stream, tv);
-        hipLaunchKernelGGL(k_hash_fill, dim3(gf), dim3(256), 0, stream, tv, stats_out);
+        unsigned gn = (unsigned)(((int64_t)tv.max_nodes + 3) / 4);
+        if (gn > 1024u) gn = 1024u;
+        hipLaunchKernelGGL(k_end_commit, dim3(gn), dim3(256), 0, stream, tv, stats_out);
     }
     return check_launch();
 }

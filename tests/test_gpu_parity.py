@@ -233,6 +233,32 @@ def test_pool_compaction_keeps_the_tree_intact():
         phase = _check_step(s, ref, q, hq, k, batch, phase, budget)
 
 
+def test_compaction_and_table_rebuild_on_a_larger_tree():
+    """The same squeeze on a tree with room for more nodes than the small-tree path takes, and a
+    child table small enough that tombstones force rebuilds: the commit's closing kernel compacts
+    the pool on some steps and refills the table on others."""
+    w = W.config0()
+    hq = w.queries
+    budget = 9000
+    max_len = int(max(w.cache.len.max(), hq.len.max()))
+    batch = 16
+    cache_tokens = int(w.cache.tokens.shape[0])
+    cfg = K.make_config(budget, cache_tokens + batch * max_len + 64, 2100, batch, max_len)
+    s = K.Scheduler(cfg, K.DeviceQueries.from_host(w.cache), hq.n)
+    ref = oracle.OracleTree()
+    ref.build(w.cache)
+    q = K.DeviceQueries.from_host(hq)
+    _same_tree(s, ref)
+    rng = np.random.default_rng(4)
+    phase = 0
+    evicted = 0
+    for step in range(150):
+        k = int(rng.choice([1, 2, 4, K_INF]))
+        phase = _check_step(s, ref, q, hq, k, batch, phase, (0, 500, budget)[step % 3])  # churn: most of the tree goes every step
+        evicted += s.read_stats().evicted_nodes
+    assert evicted > 2100  # more evictions than a quarter of the table's slots: it has been rebuilt
+
+
 def test_commit_refusals_leave_the_tree_as_it_was():
     w = W.config0()
     hq = w.queries
