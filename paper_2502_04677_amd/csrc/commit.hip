@@ -865,10 +865,36 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass,
                                                int evict_enqueued) {
     DevState *st = tv.st;
-    const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-    const int32_t v0 = j < tv.max_batch ? ws.end_node[j] : kRoot;  // requested together with the state words
-    if (!st->skip && j < st->nb) {
-        const uint64_t t = st->clock0 + (uint64_t)j;
+    const int tid = threadIdx.x;
+    const int32_t j = blockIdx.x * blockDim.x + tid;
+    // Everything the publishing below reads was written by the kernels before this one, so every
+    // workgroup asks for it at once - the state words with the prompt's end node, then what hangs on
+    // the batch size - and whichever workgroup turns out to be the last has it in registers.
+    const int32_t v0 = j < tv.max_batch ? ws.end_node[j] : kRoot;
+    const int32_t skip = st->skip, nb = st->nb, f0 = st->free_cnt0, ns0 = st->n_slots0, nodes0 = st->n_nodes;
+    const int32_t active_half = st->active_half;
+    const uint64_t clock0 = st->clock0;
+    const int64_t tail_total = st->tail_total, pool_top0 = st->pool_top, total0 = st->total_tokens;
+    const int32_t A = 2 * nb;  // reservations: two per admitted prompt
+    // each thread owns a contiguous run of reservations; the first eight of the run (all of it for
+    // batches up to 1,024) and the first eight rows of the per-prompt counters are read here
+    const int32_t per = (A + 255) / 256;
+    const int32_t lo = tid * per < A ? tid * per : A;
+    const int32_t hi = lo + per < A ? lo + per : A;
+    int32_t u[8], lt[8], head_u[8], head_id[8];
+    if (!skip) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int32_t j2 = tid + t * 256;
+            u[t] = j2 < nb ? ws.used[j2] : 0;
+            lt[t] = j2 < nb ? ws.leaf_tok[j2] : 0;
+            const int32_t a = lo + t;
+            head_u[t] = a < hi ? ((ws.used[a >> 1] >> (a & 1)) & 1) : 1;
+            head_id[t] = a < hi ? ws.resv_id[a] : 0;
+        }
+    }
+    if (!skip && j < nb) {
+        const uint64_t t = clock0 + (uint64_t)j;
         int32_t v = v0;
         for (int32_t guard = 0; guard <= tv.max_prompt_len && v > kRoot && v < tv.max_nodes; ++guard) {
             const int32_t up = tv.parent[v];  // requested together with the atomic: one round trip per level
@@ -886,48 +912,38 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
     __shared__ unsigned long long s_tok;
     __shared__ int32_t s_new;
     if (!last_block_done(st, 1)) return;
-    const int tid = threadIdx.x;
     if (tid == 0) { s_carry = 0; s_tok = 0; s_new = 0; evict = 0; }
     __syncthreads();
-    if (!st->skip) {
+    if (!skip) {
         // give back the reserved node ids that were not used, count what was added
-        const int32_t nb = st->nb;
-        const int32_t A = 2 * nb;
-        const int32_t f0 = st->free_cnt0;
         const int32_t from_free = A < f0 ? A : f0;
         const int32_t base = f0 - from_free;
         unsigned long long my_tok = 0;
         int32_t my_new = 0;
-        // (loads in groups of eight, all requested before any is used: a loop that uses each value
-        // at once pays a round trip per iteration)
-        for (int32_t j0 = tid; j0 < nb; j0 += 8 * 256) {
-            int32_t u[8], lt[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            my_new += (u[t] & 1) + ((u[t] >> 1) & 1);
+            my_tok += (unsigned long long)lt[t];
+        }
+        // (further rows in groups of eight, all requested before any is used: a loop that uses each
+        // value at once pays a round trip per iteration)
+        for (int32_t j0 = tid + 8 * 256; j0 < nb; j0 += 8 * 256) {
+            int32_t u2[8], lt2[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const int32_t j2 = j0 + t * 256;
-                u[t] = j2 < nb ? ws.used[j2] : 0;
-                lt[t] = j2 < nb ? ws.leaf_tok[j2] : 0;
+                u2[t] = j2 < nb ? ws.used[j2] : 0;
+                lt2[t] = j2 < nb ? ws.leaf_tok[j2] : 0;
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                my_new += (u[t] & 1) + ((u[t] >> 1) & 1);
-                my_tok += (unsigned long long)lt[t];
+                my_new += (u2[t] & 1) + ((u2[t] >> 1) & 1);
+                my_tok += (unsigned long long)lt2[t];
             }
         }
         if (my_tok) atomicAdd(&s_tok, my_tok);
         if (my_new) atomicAdd(&s_new, my_new);
-        // each thread owns a contiguous run of reservations; one scan places the unused ones.  The
-        // first eight of the run (all of it for batches up to 1,024) are read once and kept.
-        const int32_t per = (A + 255) / 256;
-        const int32_t lo = tid * per < A ? tid * per : A;
-        const int32_t hi = lo + per < A ? lo + per : A;
-        int32_t head_u[8], head_id[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int32_t a = lo + t;
-            head_u[t] = a < hi ? ((ws.used[a >> 1] >> (a & 1)) & 1) : 1;
-            head_id[t] = a < hi ? ws.resv_id[a] : 0;
-        }
+        // one scan places the unused reservations
         int32_t cnt = 0;
 #pragma unroll
         for (int t = 0; t < 8; ++t) cnt += head_u[t] ? 0 : 1;
@@ -951,53 +967,55 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
         if (tid == 255) s_carry = unused_total;
         __syncthreads();
     }
-    if (tid == 0) {
-        if (!st->skip) {
-            const int32_t A = 2 * st->nb;
-            st->clock = st->clock0 + (uint64_t)st->nb;
-            st->free_cnt = st->free_cnt0 - (A < st->free_cnt0 ? A : st->free_cnt0) + s_carry;
-            if (A > st->free_cnt0) st->n_slots = st->n_slots0 + (A - st->free_cnt0);
-            st->inserted_tokens = (int64_t)s_tok;
-            st->new_nodes = s_new;
-            st->pool_top += st->tail_total;
-            st->total_tokens += st->inserted_tokens;
-            st->n_nodes += st->new_nodes;
-            // pool compaction at the end of this commit: wanted when the active half could not take a
-            // worst-case batch any more, useful when part of what it holds is garbage (spans of
-            // evicted nodes; an eviction further down only adds to it)
-            {
-                const int64_t half_base = (int64_t)st->active_half * tv.pool_half;
-                const int64_t room = half_base + tv.pool_half - st->pool_top;
-                const int64_t used = st->pool_top - half_base;
-                const int64_t worst = (int64_t)tv.max_batch * (int64_t)tv.max_prompt_len;
-                if (room < worst && (used > st->total_tokens || st->total_tokens > budget)) {
-                    st->need_compact = 1;
-                    st->compact_cursor = (int64_t)(1 - st->active_half) * tv.pool_half;
-                }
+    if (tid == 0 && !skip) {
+        // (stores only: what they are computed from came with the first round trip)
+        const uint64_t clock = clock0 + (uint64_t)nb;
+        const int64_t inserted = (int64_t)s_tok;
+        const int64_t pool_top = pool_top0 + tail_total;
+        const int64_t total = total0 + inserted;
+        st->clock = clock;
+        st->free_cnt = f0 - (A < f0 ? A : f0) + s_carry;
+        if (A > f0) st->n_slots = ns0 + (A - f0);
+        st->inserted_tokens = inserted;
+        st->new_nodes = s_new;
+        st->pool_top = pool_top;
+        st->total_tokens = total;
+        st->n_nodes = nodes0 + s_new;
+        // pool compaction at the end of this commit: wanted when the active half could not take a
+        // worst-case batch any more, useful when part of what it holds is garbage (spans of
+        // evicted nodes; an eviction further down only adds to it)
+        {
+            const int64_t half_base = (int64_t)active_half * tv.pool_half;
+            const int64_t room = half_base + tv.pool_half - pool_top;
+            const int64_t used = pool_top - half_base;
+            const int64_t worst = (int64_t)tv.max_batch * (int64_t)tv.max_prompt_len;
+            if (room < worst && (used > total || total > budget)) {
+                st->need_compact = 1;
+                st->compact_cursor = (int64_t)(1 - active_half) * tv.pool_half;
             }
-            // the paths of the `protect` most recently admitted prompts (this batch included) stay
-            st->keep_from = protect <= 0 ? ~0ull : ((uint64_t)protect >= st->clock ? 0ull : st->clock - (uint64_t)protect);
-            int64_t need = st->total_tokens - budget;
-            if (tick_bits < 64 && (st->clock >> tick_bits) != 0) {
-                // the eviction passes enqueued behind this kernel were sized for a smaller clock
-                flag_error(st, 16u /* KLPM_DEV_CLOCK_RANGE */);
-                need = 0;
-            }
-            if (need > 0 && !evict_enqueued) {
-                // the host left the eviction kernels out because the budget is at least what the
-                // pool can hold: being over it means the counters are wrong
-                flag_error(st, kDevInternal);
-                need = 0;
-            }
-            if (need > 0) {
-                st->do_evict = 1;
-                st->need_evict = need;
-                st->evict_rem = need;
-                st->evict_prefix = 0;
-                st->evict_all = 0;
-                st->cand_cnt = 0;
-                evict = 1;
-            }
+        }
+        // the paths of the `protect` most recently admitted prompts (this batch included) stay
+        st->keep_from = protect <= 0 ? ~0ull : ((uint64_t)protect >= clock ? 0ull : clock - (uint64_t)protect);
+        int64_t need = total - budget;
+        if (tick_bits < 64 && (clock >> tick_bits) != 0) {
+            // the eviction passes enqueued behind this kernel were sized for a smaller clock
+            flag_error(st, 16u /* KLPM_DEV_CLOCK_RANGE */);
+            need = 0;
+        }
+        if (need > 0 && !evict_enqueued) {
+            // the host left the eviction kernels out because the budget is at least what the
+            // pool can hold: being over it means the counters are wrong
+            flag_error(st, kDevInternal);
+            need = 0;
+        }
+        if (need > 0) {
+            st->do_evict = 1;
+            st->need_evict = need;
+            st->evict_rem = need;
+            st->evict_prefix = 0;
+            st->evict_all = 0;
+            st->cand_cnt = 0;
+            evict = 1;
         }
     }
     __syncthreads();
