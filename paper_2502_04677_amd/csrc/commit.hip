@@ -941,8 +941,16 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
                 my_tok += (unsigned long long)lt2[t];
             }
         }
-        if (my_tok) atomicAdd(&s_tok, my_tok);
-        if (my_new) atomicAdd(&s_new, my_new);
+        // (summed across the wavefront first: 256 atomics on one LDS word are served one by one)
+#pragma unroll
+        for (int d = kWave / 2; d > 0; d >>= 1) {
+            my_tok += __shfl_down(my_tok, d);
+            my_new += __shfl_down(my_new, d);
+        }
+        if ((tid & (kWave - 1)) == 0) {
+            atomicAdd(&s_tok, my_tok);
+            atomicAdd(&s_new, my_new);
+        }
         // one scan places the unused reservations
         int32_t cnt = 0;
 #pragma unroll
