@@ -20,6 +20,7 @@
 //      found by a most-significant-digit-first search over weighted digit histograms, no sort.
 #include "klpm_internal.hpp"
 #include "lds_sort.hpp"
+#include "wave_ops.hpp"
 
 namespace klpm {
 
@@ -942,11 +943,8 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
             }
         }
         // (summed across the wavefront first: 256 atomics on one LDS word are served one by one)
-#pragma unroll
-        for (int d = kWave / 2; d > 0; d >>= 1) {
-            my_tok += __shfl_down(my_tok, d);
-            my_new += __shfl_down(my_new, d);
-        }
+        my_tok = wave_sum(my_tok);
+        my_new = wave_sum(my_new);
         if ((tid & (kWave - 1)) == 0) {
             atomicAdd(&s_tok, my_tok);
             atomicAdd(&s_new, my_new);

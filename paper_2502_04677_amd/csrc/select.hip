@@ -11,6 +11,7 @@
 // test and lets one wavefront resolve a whole k-cycle with two ballots.
 #include "klpm_internal.hpp"
 #include "lds_sort.hpp"
+#include "wave_ops.hpp"
 
 namespace klpm {
 
@@ -587,7 +588,8 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
             }
         }
         if (viol) atomicOr(&s_flag, 1);
-        atomicMax(&s_max, mx);
+        mx = wave_max(mx);
+        if ((tid & (kWave - 1)) == 0) atomicMax(&s_max, mx);
     }
     __syncthreads();
     if (s_flag) {  // the caller's promise does not hold: select nothing, say so

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "klpm_internal.hpp"
+#include "wave_ops.hpp"
 
 namespace klpm {
 
@@ -190,9 +191,14 @@ __global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, Que
             if (w < 0 || w >= nw) continue;
             retire(w, cur.len[w], match_len[w]);
         }
-        if (my_cost) atomicAdd(&s_cost, my_cost);
-        if (below) atomicAdd(&s_below, below);
-        if (valid) atomicAdd(&s_valid, valid);
+        my_cost = wave_sum(my_cost);
+        below = wave_sum(below);
+        valid = wave_sum(valid);
+        if ((tid & (kWave - 1)) == 0) {
+            if (my_cost) atomicAdd(&s_cost, my_cost);
+            if (below) atomicAdd(&s_below, below);
+            if (valid) atomicAdd(&s_valid, valid);
+        }
     }
     __syncthreads();
     // the whole batch finishes together (Sec. 2.1)
@@ -258,7 +264,8 @@ __global__ __launch_bounds__(kQaThreads) void k_queue_advance(QueueView cur, Que
         if (next.n_joined) *next.n_joined = first + add;
     }
     if (matched_accum) {
-        if (my) atomicAdd(&s_sum, my);
+        my = wave_sum(my);
+        if ((tid & (kWave - 1)) == 0 && my) atomicAdd(&s_sum, my);
         __syncthreads();
         if (tid == 0 && s_sum) atomicAdd((unsigned long long *)matched_accum, s_sum);
     }
