@@ -461,9 +461,8 @@ __device__ __forceinline__ int32_t slot_find_live(const TreeView &tv, uint64_t k
 
 // lane 0 only. Takes the first free slot of the probe sequence, empty or left by an evicted node.
 // The caller has just looked the key up and not found it.
-__device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key, int32_t child, int32_t edge_len,
-                                               int64_t edge_off) {
-    uint32_t h = hash_key(key) & tv.slot_mask;
+__device__ __forceinline__ int32_t slot_insert_from(const TreeView &tv, uint32_t h, uint64_t key, int32_t child,
+                                                    int32_t edge_len, int64_t edge_off) {
     for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
         unsigned long long *kp = (unsigned long long *)&tv.slots[h].key;
         unsigned long long prev = atomicCAS(kp, (unsigned long long)kEmptyKey, (unsigned long long)key);
@@ -484,15 +483,60 @@ __device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key,
     flag_error(tv.st, kDevInternal);  // (the table has two slots per node: it cannot be full)
     return -1;
 }
+__device__ __forceinline__ int32_t slot_insert(const TreeView &tv, uint64_t key, int32_t child, int32_t edge_len,
+                                               int64_t edge_off) {
+    return slot_insert_from(tv, hash_key(key) & tv.slot_mask, key, child, edge_len, edge_off);
+}
+// Two inserts whose first attempts travel together (one round trip when both home slots are free,
+// which is the rule in a table with two slots per node).
+__device__ __forceinline__ void slot_insert_pair(const TreeView &tv, uint64_t key_a, int32_t child_a, int32_t len_a,
+                                                 int64_t off_a, uint64_t key_b, int32_t child_b, int32_t len_b,
+                                                 int64_t off_b, int32_t &slot_a, int32_t &slot_b) {
+    const uint32_t ha = hash_key(key_a) & tv.slot_mask, hb = hash_key(key_b) & tv.slot_mask;
+    if (ha == hb) {
+        slot_a = slot_insert_from(tv, ha, key_a, child_a, len_a, off_a);
+        slot_b = slot_insert_from(tv, hb, key_b, child_b, len_b, off_b);
+        return;
+    }
+    const unsigned long long pa = atomicCAS((unsigned long long *)&tv.slots[ha].key, (unsigned long long)kEmptyKey,
+                                            (unsigned long long)key_a);
+    const unsigned long long pb = atomicCAS((unsigned long long *)&tv.slots[hb].key, (unsigned long long)kEmptyKey,
+                                            (unsigned long long)key_b);
+    if (pa == (unsigned long long)kEmptyKey) {
+        tv.slots[ha].child = child_a;
+        tv.slots[ha].edge_len = len_a;
+        tv.slots[ha].edge_off = off_a;
+        slot_a = (int32_t)ha;
+    } else {  // (taken, or a tombstone: the ordinary probe sequence, from the home slot again)
+        slot_a = slot_insert_from(tv, ha, key_a, child_a, len_a, off_a);
+    }
+    if (pb == (unsigned long long)kEmptyKey) {
+        tv.slots[hb].child = child_b;
+        tv.slots[hb].edge_len = len_b;
+        tv.slots[hb].edge_off = off_b;
+        slot_b = (int32_t)hb;
+    } else {
+        slot_b = slot_insert_from(tv, hb, key_b, child_b, len_b, off_b);
+    }
+}
 
 // Split node c (reached through table slot s) after its first `at` edge tokens. The new node takes
 // the upper part; c keeps the lower part, its id, its end boundary, its children and its tick.
 // Returns the new upper node (wave-uniform) or -1.
+// (leaf: the prompt goes on below the cut with token `tok`; its leaf - id, len tokens at pool index
+// off, ending at depth `end` - is hung below the new node in the same go, both table inserts
+// travelling together)
+struct LeafBelow {
+    bool want;
+    int32_t id, tok, len, end;
+    int64_t off;
+};
 __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs &ws, int32_t j, int32_t c,
                                               const NodeRec &rec, int32_t s, int32_t at, uint64_t tick, int32_t new_id,
                                               int lane, int32_t &low_first_out, int32_t &low_slot_out,
+                                              const LeafBelow &leaf, int32_t &leaf_slot_out,
                                               bool have_low = false, int32_t low_known = 0) {
-    int32_t up = -1, low_first = 0, low_slot = -1;
+    int32_t up = -1, low_first = 0, low_slot = -1, leaf_slot = -1;
     if (lane == 0) {
         // first token of the lower part (tokens never move)
         low_first = have_low ? low_known : tv.pool[rec.edge_off + at];
@@ -512,13 +556,26 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs
             tv.edge_off[c] = eo + at;
             tv.edge_len[c] = el - at;
             tv.parent[c] = up;
-            low_slot = slot_insert(tv, make_key(up, low_first), c, el - at, eo + at);
-            ws.used[j] = 1;  // (zero since the plan; a split comes before the prompt's leaf)
+            if (leaf.want) {
+                tv.parent[leaf.id] = up;
+                tv.edge_off[leaf.id] = leaf.off;
+                tv.edge_len[leaf.id] = leaf.len;
+                tv.depth_end[leaf.id] = leaf.end;
+                tv.tick[leaf.id] = tick;
+                slot_insert_pair(tv, make_key(up, low_first), c, el - at, eo + at, make_key(up, leaf.tok), leaf.id,
+                                 leaf.len, leaf.off, low_slot, leaf_slot);
+                ws.used[j] = 3;
+                ws.leaf_tok[j] = leaf.len;
+            } else {
+                low_slot = slot_insert(tv, make_key(up, low_first), c, el - at, eo + at);
+                ws.used[j] = 1;  // (zero since the plan; a split comes before the prompt's leaf)
+            }
         }
     }
     up = uni(__shfl(up, 0));
     low_first_out = uni(__shfl(low_first, 0));
     low_slot_out = uni(__shfl(low_slot, 0));
+    leaf_slot_out = uni(__shfl(leaf_slot, 0));
     __syncthreads();
     return up;
 }
@@ -644,6 +701,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
     int32_t cur = e;
     int32_t d = m;
     bool fresh = false;  // cur has just been created by this wavefront: nothing hangs below it yet
+    bool leaf_done = false;  // the prompt's leaf went in together with a split
     if (e != kRoot && m < de_e) {
         // The match stopped inside the edge that node e had before this commit. Earlier prompts of
         // this group may have cut that edge into a chain of pieces ending in e; find the piece
@@ -679,11 +737,21 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
                 if (lane == 0) flag_error(st, kDevInternal);
                 return;
             }
-            int32_t low_first, low_slot;
-            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane, low_first, low_slot);
+            int32_t low_first, low_slot, leaf_slot;
+            LeafBelow lf;
+            lf.want = m < L && leaf_id > 0;
+            lf.id = leaf_id;
+            lf.tok = tok_m;
+            lf.len = L - m;
+            lf.end = L;
+            lf.off = tail_base;
+            int32_t up = split_node(tv, ws, j, cur, rec, s, m - ds, tick, split_id, lane, low_first, low_slot, lf,
+                                    leaf_slot);
             if (up < 0) return;
             made_cut(g, lane, s, up, m - ds);
             made_add(g, lane, up, low_first, cur, rec.edge_len - (m - ds), rec.edge_off + (int64_t)(m - ds), low_slot);
+            if (lf.want) made_add(g, lane, up, lf.tok, lf.id, lf.len, lf.off, leaf_slot);
+            leaf_done = lf.want;
             // the upper part takes over the slot and the start of the edge
             g.piece = up;
             g.piece_slot = s;
@@ -691,7 +759,8 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
             g.piece_rec.edge_len = m - ds;
             g.piece_rec.depth_end = m;
             g.piece_rec.edge_off = rec.edge_off;
-            cur = up;
+            cur = leaf_done ? lf.id : up;
+            if (leaf_done) d = L;
             fresh = true;
         }
     }
@@ -761,12 +830,26 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
         rec.edge_len = el;
         rec.depth_end = d + el;
         rec.edge_off = eo;
-        int32_t low_first, low_slot;
-        const int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane, low_first, low_slot, true, b_tok);
+        int32_t low_first, low_slot, leaf_slot;
+        LeafBelow lf;
+        lf.want = d + jj < L && leaf_id > 0;
+        lf.id = leaf_id;
+        lf.tok = a_tok;
+        lf.len = L - (d + jj);
+        lf.end = L;
+        lf.off = tail_base + (int64_t)(d + jj - m);
+        const int32_t up = split_node(tv, ws, j, c, rec, s, jj, tick, split_id, lane, low_first, low_slot, lf, leaf_slot,
+                                      true, b_tok);
         if (up < 0) return;
         made_cut(g, lane, s, up, jj);
         made_add(g, lane, up, low_first, c, el - jj, eo + (int64_t)jj, low_slot);
         did_split = true;
+        if (lf.want) {
+            made_add(g, lane, up, lf.tok, lf.id, lf.len, lf.off, leaf_slot);
+            cur = lf.id;
+            d = L;
+            break;
+        }
         cur = up;
         d += jj;
         fresh = true;
