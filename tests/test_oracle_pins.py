@@ -321,6 +321,73 @@ def test_stream_fcfs_admits_in_arrival_order():
     assert (np.diff(flat) > 0).all()  # global ids are in arrival order, FCFS must preserve it
 
 
+def _toy_stream(k):
+    """The four queries of the worked example of Sec. 4.2 as an online stream: all of them arrive in
+    step 0 (the s = 0 case), one query per bin, a cache of one prompt (Def. 2's last-prompt cache)."""
+    p = W.toy_example(0)
+    return W.generators.Stream("toy", p, np.array([0, 4, 4, 4, 4], dtype=np.int64), k, 1, 10)
+
+
+@pytest.mark.parametrize("k", (1, 2, K_INF))
+def test_stream_clock_and_ttft_on_the_worked_example(k):
+    """Sec. 4.2 prints the per-query TTFT of the burst case: FCFS 10, 20, 30, 40 in arrival order;
+    LPM processes x1, x3, x2, x4 and they finish after 10, 15, 25, 30 (k-LPM with k = 2 takes the
+    same order).  With every enqueue time 0 the TTFT is the clock at which the query's bin ends, so
+    these values pin cost = sum(|x| - m), the running clock and TTFT = finish - enqueue."""
+    g = _golden()
+    r = oracle.simulate_stream(_toy_stream(k))
+    order = [int(b[0]) + 1 for b in r.batches]
+    if k == 1:
+        assert order == g["s0_fcfs_order"]
+        assert r.ttft.tolist() == g["s0_fcfs_ttft"] and r.clock == g["s0_fcfs_max"][0]
+    else:
+        assert order == g["s0_lpm_order"]
+        assert [int(r.ttft[i - 1]) for i in order] == g["s0_lpm_ttft_in_processing_order"]
+        assert r.clock == g["s0_lpm_max"][0]
+    assert all(len(b) == 1 for b in r.batches)
+
+
+@pytest.mark.parametrize("k,batch", ((4, 16), (1, 8), (K_INF, 5)))
+def test_stream_clock_and_ttft_recomputed_step_by_step(k, batch):
+    """Def. 2 with c_attn = 0 charges a query its uncached tokens; the queries of a bin finish
+    together (Sec. 2.1); a bin that costs nothing still takes one unit of time.  Every step's cost,
+    the clock and every TTFT are recomputed here from the recorded batches and match lengths with
+    plain Python integers, and the enqueue times from the clock at the start of the arrival step."""
+    s = W.config4_stream(steps=30, rate=14, groups=40, budget=40_000, batch=batch)
+    s.k = k
+    r = oracle.simulate_stream(s)
+    lens = s.queries.len.tolist()
+    clock, want, enq = 0, {}, {}
+    zero_cost_steps = 0
+    for step in range(s.steps):
+        for gid in range(int(s.step_start[step]), int(s.step_start[step + 1])):
+            enq[gid] = clock
+        pos = {int(g): i for i, g in enumerate(r.waiting_ids[step].tolist())}
+        m = r.match_lens[step].tolist()
+        cost = 0
+        for gid in r.batches[step].tolist():
+            assert gid in enq and gid not in want  # waiting, not served before
+            cost += lens[gid] - m[pos[gid]]
+        zero_cost_steps += cost == 0
+        clock += cost if cost > 0 else 1
+        for gid in r.batches[step].tolist():
+            want[gid] = clock - enq[gid]
+    assert r.clock == clock
+    got = {i: int(t) for i, t in enumerate(r.ttft.tolist()) if t >= 0}
+    assert got == want
+    # the stream reuses prefixes (some cost is saved) and some prompts cost their full length
+    full = sum(lens[g] for b in r.batches for g in b.tolist())
+    assert 0 < clock - zero_cost_steps < full
+
+
+def test_stream_bin_that_costs_nothing_takes_one_time_unit():
+    """An identical prompt costs nothing (Sec. 3.1); the simulated clock still moves by one."""
+    p = W.generators._from_lists([[1, 2, 3], [1, 2, 3], [1, 2, 3, 4]], [0, 0, 0])
+    s = W.generators.Stream("dup", p, np.array([0, 3, 3, 3], dtype=np.int64), 1, 1, 100)
+    r = oracle.simulate_stream(s)
+    assert r.ttft.tolist() == [3, 4, 5] and r.clock == 5
+
+
 # ----------------------------------------------------------------------------- timed arrivals (Def. 2 timeline)
 def test_timed_toy_example_values():
     g = _golden()
