@@ -94,7 +94,7 @@ int kLPM_arena_bytes(const kLPM_config *cfg, size_t *out_bytes);
  * Build the prefix cache (RadixAttention radix tree, Sec. 1) inside `arena` (DEVICE, 256-byte
  * aligned, arena_bytes >= kLPM_arena_bytes) from the prompts already processed.  Equivalent to
  * committing initial[0..n) one by one with ticks 0..n-1 and no eviction; `initial` may be NULL or
- * have n = 0 (empty cache, Def. 2: "the cache is empty initially").  initial->arrival is ignored.
+ * have n = 0 (the empty cache that Def. 2 starts from).  initial->arrival is ignored.
  * The handle is host memory owned by the library until kLPM_destroy.
  */
 int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *arena, size_t arena_bytes,
@@ -114,7 +114,10 @@ int kLPM_match(kLPM_tree *tree, const kLPM_queries *q, int32_t *match_len, int32
 /* kLPM_select flag: the caller asserts that arrival[] is non-decreasing in the queue index (a queue
  * kept in arrival order).  Selection then needs no sort of the whole queue (one kernel for up to
  * 8,192 entries, five short ones beyond).  The assertion is checked on the
- * device; if it does not hold, *n_selected is set to -1, nothing is selected and the phase is kept. */
+ * device; if it does not hold, *n_selected is set to -1, nothing is selected and the phase is kept.
+ * Two cases sort the queue all the same, and there the flag is only a hint - the promise is neither
+ * needed nor checked and the result is the correct batch whatever the arrival order: a tie_key with
+ * n <= 4096, and min(batch, n) > 4096. */
 #define KLPM_SELECT_FIFO 1u
 
 /* Workspace size for kLPM_select over n waiting queries. */
@@ -146,7 +149,8 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  *   batch_idx           DEVICE [min(batch, n)] out: queue indices in pick order
  *   n_selected          DEVICE [1] out: min(batch, number of entries)
  *   workspace           DEVICE, >= kLPM_select_workspace_bytes(n), 256-byte aligned
- * n = 0 or batch = 0 selects nothing and leaves the phase unchanged.
+ * n = 0 or batch = 0 selects nothing (*n_selected = 0), leaves the phase unchanged and needs no
+ * workspace (NULL will do).
  */
 int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
                 const int32_t *n_live, uint32_t k, const uint32_t *k_dev,

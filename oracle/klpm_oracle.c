@@ -13,7 +13,7 @@
  *                 the query with the largest prefix-cache hit; the resulting
  *                 order is cut into bins of B (Sec. 2.1).  k = 1 is FCFS and
  *                 k = infinity is LPM (Sec. 4).
- *   orc_commit  - the cache "stores the KV cache of processed queries" in a
+ *   orc_commit  - the cache keeps what every processed query left behind in a
  *                 radix tree and evicts least-recently-used entries under a
  *                 fixed memory size (Sec. 1; fixed pool, Sec. 2.1).
  *   orc_def2    - completion times R(j_k) of the LLM-instance computation model

@@ -1,7 +1,7 @@
 // Commit: insert the admitted prompts into the flattened radix tree, then LRU-evict to the budget.
 //
-// The cache "stores the KV cache of processed queries" in a radix tree and evicts the least
-// recently used entries under a fixed memory size (Sec. 1; fixed pool, Sec. 2.1).  The serial
+// The prefix cache keeps what every processed query left behind in a radix tree and evicts the
+// least recently used entries under a fixed memory size (Sec. 1; fixed pool, Sec. 2.1).  The serial
 // definition is: for each admitted prompt in pick order take the next tick, walk the prompt down
 // the tree, split the edge where it diverges or ends, hang the unmatched tail as a new leaf, stamp
 // the tick on the path; then repeatedly remove the smallest-tick leaf while over budget.

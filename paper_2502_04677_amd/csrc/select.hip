@@ -1307,18 +1307,26 @@ extern "C" int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes) {
     return KLPM_OK;
 }
 
-extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
-                           const int32_t *n_live, uint32_t k_host, const uint32_t *k_dev, int32_t batch, uint32_t flags,
-                           int32_t max_match,
-                           uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
+// Selects nothing: the count goes to zero, the phase stays (n = 0 or batch = 0).
+__global__ void k_sel_none(int32_t *__restrict__ n_selected) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *n_selected = 0;
+}
+
+static int select_impl(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
+                       const int32_t *n_live, uint32_t k_host, const uint32_t *k_dev, int32_t batch, uint32_t flags,
+                       int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected, void *workspace,
+                       size_t workspace_bytes, hipStream_t stream) {
     if (n < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     if (n > 0 && (!arrival || !match_len)) return KLPM_EINVAL;
     if (n > 0 && batch > 0 && !batch_idx) return KLPM_EINVAL;
+    if (n == 0 || batch == 0) {  // nothing to select: no workspace is needed either
+        hipLaunchKernelGGL(k_sel_none, dim3(1), dim3(kWave), 0, stream, n_selected);
+        return check_launch();
+    }
     const LiveN nn{n, n_live};
     const KArg k{k_host, k_dev};
     // (with tie keys a short queue goes to the one-workgroup sort of both orders further down)
-    const bool fifo = (flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch && batch > 0 && n > 0;
+    const bool fifo = (flags & KLPM_SELECT_FIFO) && (batch < n ? batch : n) <= kFifoMaxBatch;
     if (fifo && tie_key && n > kSmallOrdersN) {
         size_t fq_need = 0;
         FqWs probe;
@@ -1343,10 +1351,18 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, co
                                        (char *)workspace, stream);
     }
     SelectOrders ord;
-    int rc = build_select_orders(arrival, match_len, tie_key, n, n_live, (k_dev || k_host != 1u) && batch > 0, workspace, workspace_bytes,
-                                 stream, &ord);
+    int rc = build_select_orders(arrival, match_len, tie_key, n, n_live, k_dev || k_host != 1u, workspace,
+                                 workspace_bytes, stream, &ord);
     if (rc) return rc;
     hipLaunchKernelGGL(k_sel_walk, dim3(1), dim3(256), 0, stream, ord.order_a, ord.order_l, ord.rank_a, ord.rank_l, nn, k,
                        batch, phase_inout, batch_idx, n_selected);
     return check_launch();
+}
+
+extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
+                           const int32_t *n_live, uint32_t k_host, const uint32_t *k_dev, int32_t batch, uint32_t flags,
+                           int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+                           void *workspace, size_t workspace_bytes, kLPM_stream stream) {
+    return select_impl(arrival, match_len, tie_key, n, n_live, k_host, k_dev, batch, flags, max_match, phase_inout,
+                       batch_idx, n_selected, workspace, workspace_bytes, (hipStream_t)stream);
 }

@@ -197,6 +197,12 @@ def test_degenerate_inputs():
     assert s.batch().tolist() == [] and s.phase_value() == 3
     s.select(q, 4, 8, n=0)
     assert s.batch().tolist() == [] and s.phase_value() == 3
+    # ... on every path, and without a workspace
+    for flags in (0, K.KLPM_SELECT_FIFO):
+        for n, batch in ((0, 8), (q.n, 0), (0, 0)):
+            s.n_selected.fill_(77)
+            K.kLPM_select(q.arrival, s.match_len, n, 4, batch, s.phase, s.batch_idx, s.n_selected, (None, 0), 0, flags=flags)
+            assert int(s.n_selected.item()) == 0 and s.phase_value() == 3
     # empty tree: every match is 0; committing into it equals the oracle
     cfg = K.size_config(0, 0, 1 << 50, 32, 1024, extra_prompts=64, extra_tokens=int(w.queries.tokens.shape[0]))
     s2 = K.Scheduler(cfg, None, q.n)
