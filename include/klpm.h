@@ -33,6 +33,7 @@ extern "C" {
 #define KLPM_EARENA (-2) /* arena or workspace too small / misaligned */
 #define KLPM_EHIP (-3)   /* a HIP runtime call or kernel launch failed */
 #define KLPM_ENOMEM (-4) /* host allocation failed */
+#define KLPM_ELIMIT (-5) /* input larger than the fixed maximum of an entry point that brings its own scratch memory */
 
 /* bits of kLPM_stats.device_error */
 #define KLPM_DEV_NODES_FULL 1u     /* not enough free node slots for the batch */
@@ -156,6 +157,26 @@ int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_
                 const int32_t *n_live, uint32_t k, const uint32_t *k_dev,
                 int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
                 void *workspace, size_t workspace_bytes, kLPM_stream stream);
+
+/*
+ * kLPM_select for callers that cannot allocate device memory or hand a workspace over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The arguments and the
+ * result are those of kLPM_select without workspace / workspace_bytes; the workspace is a fixed
+ * array in the library's own device image (KLPM_SELECT_STATIC_MAX_N * 36 bytes + 1 MiB, about
+ * 5.5 MiB, held by every GPU the library runs on until the process ends).  The call allocates
+ * nothing and frees nothing.
+ *   n > KLPM_SELECT_STATIC_MAX_N returns KLPM_ELIMIT and enqueues nothing.
+ *   The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ *   outside any stream capture.
+ *   All calls on one GPU share the one array, whatever their stream: calls that may overlap in time
+ *   on a GPU race with each other (keep them on one stream, or order them with events).  Each call
+ *   clears what it needs cleared; nothing is carried from call to call.
+ */
+#define KLPM_SELECT_STATIC_MAX_N 131072
+int kLPM_select_static(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
+                       const int32_t *n_live, uint32_t k, const uint32_t *k_dev, int32_t batch, uint32_t flags,
+                       int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx, int32_t *n_selected,
+                       kLPM_stream stream);
 
 /*
  * k-LPM selection with in-batch rescoring: Algorithm 1 applied to scores that follow the cache

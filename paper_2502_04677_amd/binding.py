@@ -23,7 +23,7 @@ KLPM_SELECT_FIFO = 1
 DEV_NODES_FULL, DEV_POOL_FULL, DEV_BAD_INPUT, DEV_BATCH_OVERFLOW = 1, 2, 4, 8
 
 EXPORTS = (
-    "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select",
+    "kLPM_arena_bytes", "kLPM_build_tree", "kLPM_match", "kLPM_select_workspace_bytes", "kLPM_select", "kLPM_select_static",
     "kLPM_score_hit_rate", "kLPM_tie_keys", "kLPM_select_dynamic_workspace_bytes", "kLPM_select_dynamic",
     "kLPM_commit", "kLPM_commit_matched", "kLPM_set_budget", "kLPM_set_protect", "kLPM_reserve_clock", "kLPM_batch_token_budget", "kLPM_kv_slots", "kLPM_gather_slots", "kLPM_queue_advance", "kLPM_queue_advance_timed", "kLPM_queue_gather",
     "kLPM_read_stats", "kLPM_probe_read",
@@ -86,6 +86,7 @@ def load_library() -> C.CDLL:
     lib.kLPM_match.argtypes = [vp, C.POINTER(Queries), vp, vp, vp]
     lib.kLPM_select_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
     lib.kLPM_select.argtypes = [vp, vp, vp, i32, vp, u32, vp, i32, u32, i32, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select_static.argtypes = [vp, vp, vp, i32, vp, u32, vp, i32, u32, i32, vp, vp, vp, vp]
     lib.kLPM_adapt_state_bytes.argtypes = [C.POINTER(sz)]
     lib.kLPM_adapt_init.argtypes = [vp, sz, C.POINTER(AdaptConfig), vp]
     lib.kLPM_adapt_k.argtypes = [vp, C.POINTER(vp)]
@@ -249,6 +250,21 @@ def kLPM_select(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, 
                             C.c_void_p(k_dev), int(batch),
                             C.c_uint32(flags), int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected), C.c_void_p(workspace[1]),
                             int(workspace_bytes), _stream(stream)), "kLPM_select")
+
+
+KLPM_SELECT_STATIC_MAX_N = 131072
+KLPM_ELIMIT = -5
+
+
+def kLPM_select_static(arrival: torch.Tensor, match_len: torch.Tensor, n: int, k: int, batch: int,
+                       phase_inout: torch.Tensor, batch_idx: torch.Tensor, n_selected: torch.Tensor, stream=None,
+                       flags: int = 0, max_match: int = 0, n_live: Optional[torch.Tensor] = None,
+                       tie_key: Optional[torch.Tensor] = None, k_dev: Optional[int] = None) -> None:
+    """``kLPM_select`` with the library's own fixed scratch array as workspace (allocates nothing)."""
+    _check(_lib.kLPM_select_static(_ptr(arrival), _ptr(match_len), _ptr(tie_key), int(n), _ptr(n_live),
+                                   C.c_uint32(k & 0xFFFFFFFF), C.c_void_p(k_dev), int(batch), C.c_uint32(flags),
+                                   int(max_match), _ptr(phase_inout), _ptr(batch_idx), _ptr(n_selected),
+                                   _stream(stream)), "kLPM_select_static")
 
 
 def kLPM_select_dynamic_workspace_bytes(n: int) -> int:

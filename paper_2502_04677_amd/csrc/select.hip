@@ -9,6 +9,8 @@
 // then walks the two orders with two cursors.  After the cursors have consumed A[0,ia) and L[0,il)
 // the picked set is exactly {rank_A < ia} U {rank_L < il}, which gives an O(1) "already picked"
 // test and lets one wavefront resolve a whole k-cycle with two ballots.
+#include <mutex>
+
 #include "klpm_internal.hpp"
 #include "lds_sort.hpp"
 #include "wave_ops.hpp"
@@ -1365,4 +1367,52 @@ extern "C" int kLPM_select(const uint64_t *arrival, const int32_t *match_len, co
                            void *workspace, size_t workspace_bytes, kLPM_stream stream) {
     return select_impl(arrival, match_len, tie_key, n, n_live, k_host, k_dev, batch, flags, max_match, phase_inout,
                        batch_idx, n_selected, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+// ---- selection for callers that cannot allocate ----
+// The same selection with its workspace in a file-scope device array instead of caller memory.
+// Every GPU holds its own copy of the array (at its own address) from the moment the library is
+// loaded there until the process ends; the host-side name of the array is only a handle for
+// hipGetSymbolAddress, the kernels get the address that call returns.
+namespace klpm {
+constexpr size_t kStaticScratchBytes = (size_t)KLPM_SELECT_STATIC_MAX_N * 36 + (1u << 20);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];  // per device, filled on the first call there
+
+// Device address of the current device's copy of `scratch` (NULL and *rc set on failure).
+static void *static_scratch(int *rc) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        *rc = KLPM_EHIP;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            *rc = KLPM_EHIP;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *rc = KLPM_OK;
+    return g_scratch_ptr[dev];
+}
+}  // namespace klpm
+
+extern "C" int kLPM_select_static(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
+                                  const int32_t *n_live, uint32_t k_host, const uint32_t *k_dev, int32_t batch,
+                                  uint32_t flags, int32_t max_match, uint32_t *phase_inout, int32_t *batch_idx,
+                                  int32_t *n_selected, kLPM_stream stream) {
+    if (n > KLPM_SELECT_STATIC_MAX_N) return KLPM_ELIMIT;
+    size_t need = 0;
+    if (n >= 0 && (kLPM_select_workspace_bytes(n, &need) != KLPM_OK || need > kStaticScratchBytes)) return KLPM_ELIMIT;
+    int rc = KLPM_OK;
+    void *ws = static_scratch(&rc);
+    if (!ws) return rc;
+    return select_impl(arrival, match_len, tie_key, n, n_live, k_host, k_dev, batch, flags, max_match, phase_inout,
+                       batch_idx, n_selected, ws, kStaticScratchBytes, (hipStream_t)stream);
 }

@@ -625,6 +625,7 @@ extern "C" const char *kLPM_strerror(int code) {
         case KLPM_EARENA: return "arena or workspace too small or misaligned";
         case KLPM_EHIP: return "HIP runtime error";
         case KLPM_ENOMEM: return "host allocation failed";
+        case KLPM_ELIMIT: return "input larger than the fixed maximum of this entry point";
         default: return "unknown error";
     }
 }

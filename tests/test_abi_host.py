@@ -129,3 +129,12 @@ def test_adaptive_k_arguments_are_validated_on_the_host(K):
     assert K.kLPM_adapt_k(fake) == fake  # the current k is the first word of the state
     assert lib.kLPM_adapt_k(None, None) != 0 and lib.kLPM_adapt_read(None, None, None) != 0
     assert lib.kLPM_adapt_observe(None, None, None, None, 0, None, 0, None) != 0
+
+
+def test_select_static_refuses_sizes_beyond_its_maximum_on_the_host(K):
+    """The limit check comes before anything touches a GPU, so it can be seen on a CPU-only host."""
+    from paper_2502_04677_amd import binding
+
+    rc = binding._lib.kLPM_select_static(None, None, None, K.KLPM_SELECT_STATIC_MAX_N + 1, None, 2, None, 8, 0, 0, None,
+                                         None, None, None)
+    assert rc == K.KLPM_ELIMIT and b"maximum" in binding._lib.kLPM_strerror(rc)
