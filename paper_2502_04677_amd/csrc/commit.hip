@@ -51,11 +51,12 @@ __device__ __forceinline__ bool last_block_done(DevState *st, int slot) {
 // and at most one leaf), so the structure pass needs no shared allocation counter: reservation a
 // comes off the top of the free-id stack while it lasts, then from never-used ids.  Reservations
 // that end up unused are pushed back when the inserts are published.
-__device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
-    const DevState *st = tv.st;
-    int32_t f0 = st->free_cnt0;
-    int32_t id = (a < f0) ? tv.free_stack[f0 - 1 - a] : st->n_slots0 + (a - f0);
+__device__ __forceinline__ int32_t reserved_id_at(const TreeView &tv, int32_t a, int32_t f0, int32_t ns0) {
+    int32_t id = (a < f0) ? tv.free_stack[f0 - 1 - a] : ns0 + (a - f0);
     return (id > 0 && id < tv.max_nodes) ? id : -1;
+}
+__device__ __forceinline__ int32_t reserved_id(const TreeView &tv, int32_t a) {
+    return reserved_id_at(tv, a, tv.st->free_cnt0, tv.st->n_slots0);
 }
 
 // A commit may take the admitted prompts' matches from queue-wide match results the caller vouches
@@ -251,7 +252,20 @@ __device__ __forceinline__ void compact_nodes(const TreeView &tv, DevState *st, 
             continue;
         }
         int32_t first = uni(tv.pool[src]);
-        for (int32_t i = lane; i < len; i += kWave) tv.pool[dst + i] = tv.pool[src + i];
+        // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
+        for (int32_t base = 0; base < len; base += 8 * kWave) {
+            int32_t v[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int32_t i = base + r * kWave + lane;
+                v[r] = tv.pool[src + (i < len ? i : len - 1)];
+            }
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int32_t i = base + r * kWave + lane;
+                if (i < len) tv.pool[dst + i] = v[r];
+            }
+        }
         if (lane == 0) {
             tv.edge_off[id] = dst;
             int32_t c, el;
@@ -273,15 +287,38 @@ __device__ __forceinline__ void clear_table(const TreeView &tv, int64_t first, i
 __device__ __forceinline__ void write_stats(DevState *st, kLPM_stats *__restrict__ out) {
     if (st->need_rebuild) st->tombstones = 0;  // the table has just been rebuilt
     st->need_rebuild = 0;
+    const int32_t skip = st->skip;
+    st->skip = 0;  // (the kernels of a commit only ever raise it, several workgroups at a time)
     if (!out) return;
     out->total_tokens = st->total_tokens;
-    out->inserted_tokens = st->skip ? 0 : st->inserted_tokens;
+    out->inserted_tokens = skip ? 0 : st->inserted_tokens;
     out->evicted_tokens = st->evicted_tokens;
     out->n_nodes = st->n_nodes;
-    out->new_nodes = st->skip ? 0 : st->new_nodes;
+    out->new_nodes = skip ? 0 : st->new_nodes;
     out->evicted_nodes = st->evicted_nodes;
     out->device_error = st->device_error;
     out->clock = st->clock;
+}
+
+// All `count` workgroups of the grid wait here for each other (used on the rare maintenance path
+// only).  The grid is small enough to be resident at once, so the wait ends; it is bounded all the
+// same: false = the others did not arrive in time, and the caller gives up.
+__device__ __forceinline__ bool maintenance_barrier(DevState *st, int slot, int count) {
+    __shared__ int s_ok;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        atomicAdd(&st->done[slot], 1);
+        int ok = 1;
+        for (int spins = 0; __hip_atomic_load(&st->done[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < count; ++spins) {
+            if (spins > (1 << 24)) { ok = 0; break; }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        __threadfence();
+        s_ok = ok;
+    }
+    __syncthreads();
+    return s_ok != 0;
 }
 
 // Re-inserts every live node into the emptied child table.
@@ -338,6 +375,12 @@ __global__ __launch_bounds__(256) void k_end_commit(TreeView tv, kLPM_stats *__r
                       (int64_t)gridDim.x * (blockDim.x / kWave), threadIdx.x & (kWave - 1));
         if (last_of(st, 0, n_blocks) && threadIdx.x == 0) compact_switch(tv, st);
     } else if (need_rebuild) {
+        // empty the table, wait for every workgroup to have done its share, re-insert the live nodes
+        clear_table(tv, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)n_blocks * blockDim.x);
+        if (!maintenance_barrier(st, 0, n_blocks)) {
+            if (threadIdx.x == 0) flag_error(st, kDevInternal);
+            return;
+        }
         fill_table(tv, st, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, (int64_t)n_blocks * blockDim.x);
     }
     if (last_of(st, 3, n_blocks) && threadIdx.x == 0) write_stats(st, stats_out);
@@ -356,6 +399,8 @@ __global__ __launch_bounds__(kSmallMaintainThreads) void k_end_commit_small(Tree
         __syncthreads();
         if (tid == 0) compact_switch(tv, st);
     } else if (need_rebuild) {
+        clear_table(tv, tid, kSmallMaintainThreads);
+        __syncthreads();
         fill_table(tv, st, tid, kSmallMaintainThreads);
     }
     __syncthreads();
@@ -397,6 +442,152 @@ __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const 
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             int32_t i = base + r * (int32_t)blockDim.x + (int32_t)threadIdx.x;
+            if (i < len) dst[i] = v[r];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ plan and tails in one launch
+// For batches of up to kFusedPlanMax prompts the plan is not a kernel of its own: workgroup j, which
+// copies prompt j's tail, reads the whole batch's match results itself (a few KB, two round trips)
+// and derives from them everything it needs - the admission, where its tail goes (the sum of the
+// tails before it), whether the commit goes ahead - exactly as every other workgroup does from the
+// same inputs; workgroup 0 also writes the commit's scalars.  Nothing here raises or lowers a flag
+// that another workgroup of the same launch reads: the skip flag is only ever raised, and the end
+// of the previous commit has lowered it.
+constexpr int kFusedPlanMax = 2048;
+constexpr int kFusedThreads = 256;
+__global__ __launch_bounds__(kFusedThreads) void k_plan_copy(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                             const int32_t *__restrict__ n_selected, int32_t batch_cap,
+                                                             CommitWs ws, const int32_t *__restrict__ hint_len,
+                                                             const int32_t *__restrict__ hint_node) {
+    constexpr int kPer = kFusedPlanMax / kFusedThreads;
+    __shared__ int64_t p_before[kFusedThreads / kWave], p_total[kFusedThreads / kWave];
+    __shared__ int32_t p_bad[kFusedThreads / kWave];
+    __shared__ int32_t s_nb;
+    __shared__ uint32_t s_err;
+    __shared__ int64_t s_off;
+    __shared__ int32_t s_L, s_m, s_e;
+    DevState *st = tv.st;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int32_t j = blockIdx.x;
+    // one round trip: the persistent counters and every prompt's batch index; a second one: what
+    // hangs on the indices
+    const int32_t f0 = st->free_cnt, ns0 = st->n_slots, active_half = st->active_half;
+    const int64_t pool_top = st->pool_top;
+    const uint64_t clock0 = st->clock;
+    PlanIn in[kPer];
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+        const int32_t i = t * kFusedThreads + tid;
+        in[t].m = -1;
+        if (i < batch_cap) in[t] = plan_load(q, ws, batch_idx, hint_len, hint_node, i);
+    }
+    if (tid == 0) {
+        uint32_t err = 0;
+        s_nb = commit_gate(tv, n_selected, batch_cap, &err);
+        s_err = err;
+    }
+    __syncthreads();
+    const int32_t nb = s_nb;
+    const uint32_t err = s_err;
+    int64_t before = 0, total = 0;
+    int32_t bad = 0;
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+        const int32_t i = t * kFusedThreads + tid;
+        if (i >= nb) continue;
+        if (hint_len ? !plan_check(tv, q, in[t]) : in[t].m < 0) {
+            in[t].m = -1;
+            in[t].e = kRoot;
+            bad = 1;
+            continue;
+        }
+        const int64_t tl = (int64_t)(in[t].L - in[t].m);
+        total += tl;
+        if (i < j) before += tl;
+        if (i == j) { s_off = in[t].off; s_L = in[t].L; s_m = in[t].m; s_e = in[t].e; }
+    }
+    before = wave_sum(before);
+    total = wave_sum(total);
+    bad = wave_sum(bad);
+    if (lane == 0) { p_before[wv] = before; p_total[wv] = total; p_bad[wv] = bad; }
+    __syncthreads();
+    before = 0; total = 0; bad = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < kFusedThreads / kWave; ++w2) { before += p_before[w2]; total += p_total[w2]; bad += p_bad[w2]; }
+    // (the end of every commit leaves room for a worst-case batch if compaction can make it; tails
+    // that still do not fit mean the pool is too small for what must stay cached)
+    const int64_t half_end = ((int64_t)active_half + 1) * tv.pool_half;
+    const bool pool_full = nb > 0 && !bad && pool_top + total > half_end;
+    const bool skip = err != 0 || bad != 0 || pool_full;
+    if (j == 0 && tid == 0) {
+        uint32_t e = err;
+        if (bad) e |= 4u;        // KLPM_DEV_BAD_INPUT
+        if (pool_full) e |= 2u;  // KLPM_DEV_POOL_FULL
+        if (e) atomicOr(&st->device_error, e);
+        if (skip) st->skip = 1;
+        st->nb = nb;
+        st->need_compact = 0;
+        st->need_rebuild = 0;
+        st->do_evict = 0;
+        st->tail_total = nb > 0 ? total : 0;
+        st->inserted_tokens = 0;
+        st->evicted_tokens = 0;
+        st->new_nodes = 0;
+        st->evicted_nodes = 0;
+        st->free_cnt0 = f0;
+        st->n_slots0 = ns0;
+        st->clock0 = clock0;
+        for (int i = 0; i < 12; ++i) st->done[i] = 0;
+    }
+    if (skip || j >= nb) return;
+    // (s_* were written before the barrier above by the thread that holds prompt j)
+    const int64_t off = s_off;
+    const int32_t L = s_L, m = s_m, e = s_e;
+    const int32_t *__restrict__ src = q.tokens + off + m;
+    if (tid == 0) {
+        // this prompt's share of the plan (the group key needs where node e ends and the prompt's next token)
+        const bool inside = m < tv.depth_end[e];
+        const int32_t nxt = (m < L) ? src[0] : -1;
+        uint64_t g;
+        if (!inside && m == L) {
+            g = kNoGroup;  // already present and ending on a node boundary: ticks only
+        } else if (inside) {
+            g = (uint64_t)(uint32_t)e << 33;
+        } else {
+            g = ((uint64_t)(uint32_t)e << 33) | (1ull << 32) | (uint64_t)(uint32_t)nxt;
+        }
+        ws.used[j] = 0;
+        ws.leaf_tok[j] = 0;
+        ws.resv_id[2 * j] = reserved_id_at(tv, 2 * j, f0, ns0);
+        ws.resv_id[2 * j + 1] = reserved_id_at(tv, 2 * j + 1, f0, ns0);
+        if (hint_len) {
+            ws.bm_len[j] = m;
+            ws.bm_node[j] = e;
+        }
+        ws.gkey[j] = g;
+        ws.end_node[j] = e;
+        ws.next_tok[j] = nxt;
+        ws.tail_off[j] = before;
+        if (hint_len && !hinted_match_ok(tv, src - m, L, m, e)) {
+            st->skip = 1;
+            atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
+        }
+    }
+    int32_t *__restrict__ dst = tv.pool + pool_top + before;
+    const int32_t len = L - m;
+    // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
+    for (int32_t base = 0; base < len; base += 8 * kFusedThreads) {
+        int32_t v[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            int32_t i = base + r * kFusedThreads + tid;
+            v[r] = src[i < len ? i : len - 1];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            int32_t i = base + r * kFusedThreads + tid;
             if (i < len) dst[i] = v[r];
         }
     }
@@ -1216,58 +1407,57 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * kEvictBins, width, pass == 0);
 }
 
-// Removes every live, unprotected node with key <= cut among the nodes first, first + stride, ..:
-// tombstone in the parent's table slot, id back on the free stack; tokens and nodes removed are
-// added to the two workgroup counters.
+// Removes one live node: tombstone in the parent's table slot, id back on the free stack; its tokens
+// and the node are added to the two workgroup counters.
+__device__ __forceinline__ void evict_remove_node(const TreeView &tv, DevState *st, int64_t id, int32_t len,
+                                                  unsigned long long *s_tok, int *s_cnt) {
+    // (the place on the free stack is asked for together with the node's fields: it does not depend
+    // on them)
+    const int32_t pa = tv.parent[id];
+    const int64_t eo = tv.edge_off[id];
+    const int32_t pos = atomicAdd(&st->free_cnt, 1);
+    tv.edge_len[id] = 0;
+    // leave a tombstone where the parent pointed at this node
+    const uint64_t key = make_key(pa, tv.pool[eo]);
+    uint32_t h = hash_key(key) & tv.slot_mask;
+    for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+        uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (kk == key) {
+            __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+        if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
+        h = (h + 1) & tv.slot_mask;
+    }
+    if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
+    atomicAdd(s_tok, (unsigned long long)len);
+    atomicAdd(s_cnt, 1);
+}
+// Removes every live, unprotected node with key <= cut among the nodes first, first + stride, ...
 __device__ __forceinline__ void evict_apply_sweep(const TreeView &tv, DevState *st, uint64_t cut, uint64_t keep_from,
                                                   int32_t n_slots, int depth_bits, int64_t first, int64_t stride,
                                                   unsigned long long *s_tok, int *s_cnt) {
     for_each_evictable(tv, n_slots, keep_from, depth_bits, first, stride, [&](int64_t id, int32_t len, uint64_t node_key) {
-        if (node_key <= cut) {
-            // (the place on the free stack is asked for together with the node's fields: it does
-            // not depend on them)
-            const int32_t pa = tv.parent[id];
-            const int64_t eo = tv.edge_off[id];
-            const int32_t pos = atomicAdd(&st->free_cnt, 1);
-            tv.edge_len[id] = 0;
-            // leave a tombstone where the parent pointed at this node
-            const uint64_t key = make_key(pa, tv.pool[eo]);
-            uint32_t h = hash_key(key) & tv.slot_mask;
-            for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
-                uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (kk == key) {
-                    __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
-                h = (h + 1) & tv.slot_mask;
-            }
-            if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
-            atomicAdd(s_tok, (unsigned long long)len);
-            atomicAdd(s_cnt, 1);
-        }
+        if (node_key <= cut) evict_remove_node(tv, st, id, len, s_tok, s_cnt);
     });
 }
-// Books the removal (one thread, after every sweep has added its counts).
-// Returns whether the child table is to be rebuilt at the end of this commit (the caller's
-// workgroup then empties it: a rare sweep that one workgroup can afford, and the kernel that ends
-// the commit only has to refill).
-__device__ __forceinline__ bool evict_apply_publish(const TreeView &tv, DevState *st, int64_t ev_tok, int32_t ev_cnt) {
+// Books the removal (one thread, after every workgroup has added its counts): the child table is
+// rebuilt at the end of this commit once tombstones start to lengthen the probe sequences.
+__device__ __forceinline__ void evict_apply_publish(const TreeView &tv, DevState *st, int64_t ev_tok, int32_t ev_cnt) {
     st->total_tokens -= ev_tok;
     st->n_nodes -= ev_cnt;
     st->tombstones += ev_cnt;
-    // rebuild the child table only when tombstones start to lengthen the probe sequences
-    const bool rebuild = (int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact;
-    if (rebuild) st->need_rebuild = 1;
-    return rebuild;
+    if ((int64_t)st->tombstones * 4 > (int64_t)tv.slot_mask + 1 && !st->need_compact) st->need_rebuild = 1;
 }
 
-// Last stretch of the search: collect the nodes whose key agrees with the prefix above bit `shift`;
-// the last workgroup sorts them by key and cuts where their lengths add up to what is left to free.
-// More nodes than fit (very deep paths stamped by few prompts) are handled by the same workgroup
-// with digit passes of its own over all nodes.
-__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits,
-                                                      int apply_here) {
+// Last stretch of the search and the removal itself, in one sweep over the nodes.  The digit passes
+// have narrowed the cut key down to the keys that agree with `prefix` above bit `shift`: a node
+// whose key lies below that window goes for certain and is removed on the spot; the nodes inside the
+// window (few: a window is 64 ticks wide) are collected, and the last workgroup to finish sorts them
+// by key, cuts where their lengths add up to what is left to free, and removes those up to the cut.
+// More nodes in the window than the sort holds (very deep paths stamped by few prompts) are handled
+// by that workgroup with digit passes of its own over all nodes.
+__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
     DevState *st = tv.st;
     const int do_evict = st->do_evict;
     const uint64_t prefix = st->evict_prefix;
@@ -1282,41 +1472,35 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
     __shared__ unsigned long long s_tok;
     __shared__ int s_cnt;
     const int tid = threadIdx.x;
-    if (!evict_all) {
-        for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
-                           (int64_t)gridDim.x * blockDim.x, [&](int64_t, int32_t len, uint64_t key) {
-            if (n_hist_pass == 0 || shift >= 64 || (key >> shift) == prefix) {
-                int32_t at = atomicAdd(&st->cand_cnt, 1);
-                if (at < kEvictCand) {
-                    ws.cand_key[at] = key;
-                    ws.cand_len[at] = len;
-                }
+    if (tid == 0) { s_tok = 0; s_cnt = 0; }
+    __syncthreads();
+    const bool windowed = n_hist_pass > 0 && shift < 64;  // (otherwise every node that may go is a candidate)
+    for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                       (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t key) {
+        const uint64_t top = windowed ? (key >> shift) : 0ull;
+        if (evict_all || (windowed && top < prefix)) {
+            evict_remove_node(tv, st, id, len, &s_tok, &s_cnt);
+        } else if (!windowed || top == prefix) {
+            int32_t at = atomicAdd(&st->cand_cnt, 1);
+            if (at < kEvictCand) {
+                ws.cand_key[at] = key;
+                ws.cand_len[at] = len;
+                ws.cand_id[at] = (int32_t)id;
             }
-        });
+        }
+    });
+    __syncthreads();
+    if (tid == 0 && s_cnt) {
+        atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
+        atomicAdd(&st->evicted_nodes, s_cnt);
     }
     if (!last_block_done(st, 10)) return;
-    // (apply_here: the tree is small enough for this workgroup to remove the nodes itself, which
-    // saves the launch of the removal kernel)
-    auto apply = [&](uint64_t cut) {
-        if (tid == 0) { s_tok = 0; s_cnt = 0; }
-        __syncthreads();
-        evict_apply_sweep(tv, st, cut, keep_from, n_slots, depth_bits, 1 + tid, 256, &s_tok, &s_cnt);
-        __syncthreads();
-        if (tid == 0) {
-            st->evicted_tokens = (int64_t)s_tok;
-            st->evicted_nodes = s_cnt;
-            s_cnt = evict_apply_publish(tv, st, (int64_t)s_tok, s_cnt) ? 1 : 0;  // (reused: rebuild?)
-        }
-        __syncthreads();
-        if (s_cnt) clear_table(tv, tid, 256);
-    };
-    if (evict_all) {
-        if (tid == 0) st->evict_prefix = ~0ull;
-        if (apply_here) apply(~0ull);
-        return;
-    }
+    if (tid == 0) { s_tok = 0; s_cnt = 0; s_cut = ~0ull; }
+    __syncthreads();
     const int32_t n = __hip_atomic_load(&st->cand_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (n > kEvictCand) {
+    if (evict_all) {
+        // (everything that may go has gone in the sweeps)
+    } else if (n > kEvictCand) {
         // digit passes over all nodes by this workgroup alone (rare): the remaining `shift` bits of the key
         unsigned long long *h = reinterpret_cast<unsigned long long *>(s_key);  // kEvictBins words fit
         int low = shift;
@@ -1337,65 +1521,51 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
             __syncthreads();
             evict_descend_step(st, reinterpret_cast<const int64_t *>(h), width, false);
         }
-        return;
-    }
-    // sort the collected nodes by key in LDS, then the cut
-    int32_t np2 = 1;
-    while (np2 < n) np2 <<= 1;
-    for (int32_t i = tid; i < np2; i += 256) {
-        s_key[i] = i < n ? __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
-        s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-    }
-    __syncthreads();
-    sort_lds<256, kEvictCand / 256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
-    // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
-    // reaches the remainder is the last one to go
-    const int64_t rem = st->evict_rem;
-    const int32_t per = (n + 255) / 256;
-    const int32_t lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
-    int64_t mine = 0;
-    for (int32_t i = lo; i < hi; ++i) mine += s_len[i];
-    if (tid == 0) s_cut = ~0ull;  // (all of them, should the weights fall short)
-    int64_t all;
-    int64_t run = block_inclusive_scan<int64_t, 256>(mine, part, tid, all) - mine;
-    for (int32_t i = lo; i < hi; ++i) {
-        if (run < rem && run + s_len[i] >= rem) s_cut = s_key[i];
-        run += s_len[i];
-    }
-    __syncthreads();
-    if (tid == 0) st->evict_prefix = s_cut;
-    if (apply_here) apply(s_cut);
-}
-
-__global__ __launch_bounds__(256) void k_evict_apply(TreeView tv, CommitWs ws, int depth_bits) {
-    DevState *st = tv.st;
-    const int do_evict = st->do_evict;
-    const uint64_t cut = st->evict_prefix;  // every live, unprotected node with key <= cut goes
-    const uint64_t keep_from = st->keep_from;
-    const int32_t n_slots = st->n_slots;
-    if (!do_evict) return;
-    __shared__ unsigned long long s_tok;
-    __shared__ int s_cnt;
-    const int tid = threadIdx.x;
-    if (tid == 0) { s_tok = 0; s_cnt = 0; }
-    __syncthreads();
-    evict_apply_sweep(tv, st, cut, keep_from, n_slots, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
-                      (int64_t)gridDim.x * blockDim.x, &s_tok, &s_cnt);
-    __syncthreads();
-    if (tid == 0 && s_cnt) {
-        atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
-        atomicAdd(&st->evicted_nodes, s_cnt);
-    }
-    __shared__ int s_rebuild;
-    if (last_block_done(st, 2)) {
-        if (tid == 0) {
-            int64_t ev_tok = (int64_t)__hip_atomic_load((unsigned long long *)&st->evicted_tokens, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-            int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_rebuild = evict_apply_publish(tv, st, ev_tok, ev_cnt) ? 1 : 0;
+        // the key is complete: what lies below the window is gone already, the rest up to the cut goes now
+        evict_apply_sweep(tv, st, st->evict_prefix, keep_from, n_slots, depth_bits, 1 + tid, 256, &s_tok, &s_cnt);
+    } else {
+        // sort the collected nodes by key in LDS, then the cut
+        int32_t np2 = 1;
+        while (np2 < n) np2 <<= 1;
+        for (int32_t i = tid; i < np2; i += 256) {
+            s_key[i] = i < n ? __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
+            s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
         }
         __syncthreads();
-        if (s_rebuild) clear_table(tv, tid, blockDim.x);
+        sort_lds<256, kEvictCand / 256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
+        // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
+        // reaches the remainder is the last one to go (all of them, should the weights fall short)
+        const int64_t rem = st->evict_rem;
+        const int32_t per = (n + 255) / 256;
+        const int32_t lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
+        int64_t mine = 0;
+        for (int32_t i = lo; i < hi; ++i) mine += s_len[i];
+        int64_t all;
+        int64_t run = block_inclusive_scan<int64_t, 256>(mine, part, tid, all) - mine;
+        for (int32_t i = lo; i < hi; ++i) {
+            if (run < rem && run + s_len[i] >= rem) s_cut = s_key[i];
+            run += s_len[i];
+        }
+        __syncthreads();
+        const uint64_t cut = s_cut;
+        if (tid == 0) st->evict_prefix = cut;
+        // keys are unique among live nodes (nodes that share a tick lie on one root path, at
+        // different depths), so the collected nodes up to the cut are removed as they were stored
+        for (int32_t i = tid; i < n; i += 256) {
+            const uint64_t key = __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (key <= cut)
+                evict_remove_node(tv, st, __hip_atomic_load(&ws.cand_id[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                                  __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), &s_tok, &s_cnt);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int64_t ev_tok = (int64_t)__hip_atomic_load((unsigned long long *)&st->evicted_tokens, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT) + (int64_t)s_tok;
+        const int32_t ev_cnt = __hip_atomic_load(&st->evicted_nodes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + s_cnt;
+        st->evicted_tokens = ev_tok;
+        st->evicted_nodes = ev_cnt;
+        evict_apply_publish(tv, st, ev_tok, ev_cnt);
     }
 }
 
@@ -1424,12 +1594,15 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
         if (rc) return rc;
     }
-    hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
-                       ws, hint_len, hint_node);
-    if (batch_cap > 0) {
+    if (batch_cap <= kFusedPlanMax) {
+        hipLaunchKernelGGL(k_plan_copy, dim3(batch_cap > 0 ? batch_cap : 1), dim3(kFusedThreads), 0, stream, tv, q,
+                           batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+    } else {
+        hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
+                           ws, hint_len, hint_node);
         hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws, hint_len ? 1 : 0);
-        hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     }
+    if (batch_cap > 0) hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     // Every live edge sits in the active half of the token pool, so a budget of at least that half
     // can never be exceeded: the eviction kernels (no-ops that still cost a launch each) are left out.
     const bool may_evict = budget < tv.pool_half;
@@ -1445,9 +1618,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
             const int width = p == 0 ? hist_bits - kEvictDigitBits * (n_pass - 1) : kEvictDigitBits;
             hipLaunchKernelGGL(k_evict_hist, dim3(ge), dim3(256), 0, stream, tv, ws, p, shift, width, t->depth_bits);
         }
-        hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits,
-                           tiny ? 1 : 0);
-        if (!tiny) hipLaunchKernelGGL(k_evict_apply, dim3(ge), dim3(256), 0, stream, tv, ws, t->depth_bits);
+        hipLaunchKernelGGL(k_evict_gather, dim3(ge), dim3(256), 0, stream, tv, ws, n_pass, final_shift, t->depth_bits);
     }
     // the end of the commit: grid sized for pool compaction, one wavefront per node
     if (tiny) {

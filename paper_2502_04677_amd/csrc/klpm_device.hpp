@@ -101,6 +101,7 @@ struct CommitWs {
     int64_t *evict_hist; // [6][2048] weighted digit histograms of the eviction cut search
     uint64_t *cand_key;  // [kEvictCand] eviction keys of the nodes collected for the last stretch of the search
     int32_t *cand_len;   // [kEvictCand] their edge lengths
+    int32_t *cand_id;    // [kEvictCand] their node ids
     int32_t *iota_idx;  // [max_batch] scratch batch indices for build_tree
     int32_t *iota_n;    // [1]
 };

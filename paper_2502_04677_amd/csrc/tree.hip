@@ -12,7 +12,7 @@ namespace klpm {
 
 struct Layout {
     size_t state, parent, edge_off, edge_len, depth_end, tick, free_stack, slots, pool;
-    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, resv_id, evict_hist, cand_key, cand_len, iota_idx, iota_n;
+    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, resv_id, evict_hist, cand_key, cand_len, cand_id, iota_idx, iota_n;
     size_t total;
     uint32_t n_slots_table;
 };
@@ -52,6 +52,7 @@ static Layout make_layout(const kLPM_config &c) {
     L.evict_hist = take(6 * 2048 * 8);  // eviction cut search: 6 passes of 2048 weighted bins
     L.cand_key = take((size_t)kEvictCand * 8);
     L.cand_len = take((size_t)kEvictCand * 4);
+    L.cand_id = take((size_t)kEvictCand * 4);
     L.iota_idx = take(mb * 4);
     L.iota_n = take(256);
     L.total = o;
@@ -356,6 +357,7 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     ws.evict_hist = (int64_t *)(base + L.evict_hist);
     ws.cand_key = (uint64_t *)(base + L.cand_key);
     ws.cand_len = (int32_t *)(base + L.cand_len);
+    ws.cand_id = (int32_t *)(base + L.cand_id);
     ws.iota_idx = (int32_t *)(base + L.iota_idx);
     ws.iota_n = (int32_t *)(base + L.iota_n);
 
