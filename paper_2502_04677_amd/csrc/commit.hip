@@ -25,6 +25,10 @@
 namespace klpm {
 
 constexpr uint64_t kNoGroup = ~0ull;
+// ws.lcp_lead[j]: how many tokens prompt j's unmatched tail shares with the tail of the first prompt
+// of its group; kLcpPending until the wavefront of prompt j has worked it out, kLcpNone if it does not apply.
+constexpr int32_t kLcpPending = -1;
+constexpr int32_t kLcpNone = -2;
 constexpr uint32_t kDevInternal = 32u;  // KLPM_DEV_INTERNAL: the tree and its child table disagree
 constexpr int kEvictDigitBits = 11;  // eviction cut search: bits of the key resolved per pass
 constexpr int kEvictBins = 1 << kEvictDigitBits;
@@ -173,6 +177,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
         if (j < nb) {
             ws.used[j] = 0;
             ws.leaf_tok[j] = 0;
+            ws.lcp_lead[j] = kLcpPending;
             // the two node ids this prompt may use (at most one split and one leaf)
             ws.resv_id[2 * j] = reserved_id(tv, 2 * j);
             ws.resv_id[2 * j + 1] = reserved_id(tv, 2 * j + 1);
@@ -240,38 +245,51 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
 __device__ __forceinline__ void compact_nodes(const TreeView &tv, DevState *st, int64_t wave, int64_t n_waves, int lane) {
     const int32_t n_slots = st->n_slots;
     const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
-    for (int64_t id = 1 + wave; id < n_slots; id += n_waves) {
-        int32_t len = uni(tv.edge_len[id]);
-        if (len <= 0) continue;
-        int64_t src = uni64(tv.edge_off[id]);
-        int64_t dst = 0;
-        if (lane == 0) dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)len);
-        dst = uni64(dst);
-        if (dst + len > dst_end) {  // cannot happen while total_tokens <= pool_half
+    // 64 nodes at a time, one per lane: their lengths are summed across the wavefront so that the
+    // block takes its room with a single atomic (one atomic per node on the one cursor would be
+    // served one by one, about 13 ns each: a millisecond for a tree of 80,000 nodes)
+    for (int64_t id0 = 1 + wave * kWave; id0 < n_slots; id0 += n_waves * kWave) {
+        const int64_t id = id0 + lane;
+        int32_t len = id < n_slots ? tv.edge_len[id] : 0;
+        len = len > 0 ? len : 0;
+        const int64_t src = id < n_slots ? tv.edge_off[id] : 0;
+        const int32_t slot = id < n_slots ? tv.slot_of[id] : -1;
+        const int64_t incl = wave_inclusive_scan<int64_t>((int64_t)len, lane);
+        const int64_t block_len = __shfl(incl, kWave - 1);
+        if (block_len == 0) continue;
+        int64_t base_dst = 0;
+        if (lane == 0) base_dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)block_len);
+        base_dst = uni64(__shfl(base_dst, 0));
+        if (base_dst + block_len > dst_end) {  // cannot happen while total_tokens <= pool_half
             if (lane == 0) flag_error(st, 2u);
             continue;
         }
-        int32_t first = uni(tv.pool[src]);
-        // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
-        for (int32_t base = 0; base < len; base += 8 * kWave) {
-            int32_t v[8];
+        const int64_t dst = base_dst + incl - len;
+        // every node's tokens by the whole wavefront, eight independent rows per trip
+        uint64_t live = __ballot(len > 0);
+        while (live) {
+            const int b = (int)__builtin_ctzll(live);
+            live &= live - 1ull;
+            const int32_t n = uni(__shfl(len, b));
+            const int64_t from = uni64(__shfl(src, b)), to = uni64(__shfl(dst, b));
+            for (int32_t base = 0; base < n; base += 8 * kWave) {
+                int32_t v[8];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const int32_t i = base + r * kWave + lane;
-                v[r] = tv.pool[src + (i < len ? i : len - 1)];
-            }
+                for (int r = 0; r < 8; ++r) {
+                    const int32_t i = base + r * kWave + lane;
+                    v[r] = tv.pool[from + (i < n ? i : n - 1)];
+                }
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const int32_t i = base + r * kWave + lane;
-                if (i < len) tv.pool[dst + i] = v[r];
+                for (int r = 0; r < 8; ++r) {
+                    const int32_t i = base + r * kWave + lane;
+                    if (i < n) tv.pool[to + i] = v[r];
+                }
             }
         }
-        if (lane == 0) {
+        if (len > 0) {
             tv.edge_off[id] = dst;
-            int32_t c, el;
-            int64_t eo;
-            int32_t h = slot_find(tv.slots, tv.slot_mask, make_key(tv.parent[id], first), c, el, eo);
-            if (h >= 0 && c == (int32_t)id) tv.slots[h].edge_off = dst; else flag_error(st, kDevInternal);
+            if (slot >= 0 && (uint32_t)slot <= tv.slot_mask && tv.slots[slot].child == (int32_t)id) tv.slots[slot].edge_off = dst;
+            else flag_error(st, kDevInternal);
         }
     }
 }
@@ -337,6 +355,7 @@ __device__ __forceinline__ void fill_table(const TreeView &tv, DevState *st, int
                 tv.slots[h].child = (int32_t)id;
                 tv.slots[h].edge_len = len;
                 tv.slots[h].edge_off = off;
+                tv.slot_of[id] = (int32_t)h;
                 break;
             }
             h = (h + 1) & tv.slot_mask;
@@ -560,6 +579,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_plan_copy(TreeView tv, QView 
         }
         ws.used[j] = 0;
         ws.leaf_tok[j] = 0;
+        ws.lcp_lead[j] = kLcpPending;
         ws.resv_id[2 * j] = reserved_id_at(tv, 2 * j, f0, ns0);
         ws.resv_id[2 * j + 1] = reserved_id_at(tv, 2 * j + 1, f0, ns0);
         if (hint_len) {
@@ -667,6 +687,7 @@ __device__ __forceinline__ int32_t slot_insert_from(const TreeView &tv, uint32_t
             tv.slots[h].child = child;
             tv.slots[h].edge_len = edge_len;
             tv.slots[h].edge_off = edge_off;
+            tv.slot_of[child] = (int32_t)h;
             return (int32_t)h;
         }
         h = (h + 1) & tv.slot_mask;
@@ -697,6 +718,7 @@ __device__ __forceinline__ void slot_insert_pair(const TreeView &tv, uint64_t ke
         tv.slots[ha].child = child_a;
         tv.slots[ha].edge_len = len_a;
         tv.slots[ha].edge_off = off_a;
+        tv.slot_of[child_a] = (int32_t)ha;
         slot_a = (int32_t)ha;
     } else {  // (taken, or a tombstone: the ordinary probe sequence, from the home slot again)
         slot_a = slot_insert_from(tv, ha, key_a, child_a, len_a, off_a);
@@ -705,6 +727,7 @@ __device__ __forceinline__ void slot_insert_pair(const TreeView &tv, uint64_t ke
         tv.slots[hb].child = child_b;
         tv.slots[hb].edge_len = len_b;
         tv.slots[hb].edge_off = off_b;
+        tv.slot_of[child_b] = (int32_t)hb;
         slot_b = (int32_t)hb;
     } else {
         slot_b = slot_insert_from(tv, hb, key_b, child_b, len_b, off_b);
@@ -744,6 +767,7 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs
             tv.tick[up] = tick;
             tv.slots[s].child = up;
             tv.slots[s].edge_len = at;
+            tv.slot_of[up] = s;
             tv.edge_off[c] = eo + at;
             tv.edge_len[c] = el - at;
             tv.parent[c] = up;
@@ -755,11 +779,11 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs
                 tv.tick[leaf.id] = tick;
                 slot_insert_pair(tv, make_key(up, low_first), c, el - at, eo + at, make_key(up, leaf.tok), leaf.id,
                                  leaf.len, leaf.off, low_slot, leaf_slot);
-                ws.used[j] = 3;
+                atomicOr(&ws.used[j], 3);
                 ws.leaf_tok[j] = leaf.len;
             } else {
                 low_slot = slot_insert(tv, make_key(up, low_first), c, el - at, eo + at);
-                ws.used[j] = 1;  // (zero since the plan; a split comes before the prompt's leaf)
+                atomicOr(&ws.used[j], 1);  // (zero since the plan)
             }
         }
     }
@@ -880,8 +904,15 @@ __device__ __forceinline__ void made_cut(GroupCtx &g, int lane, int32_t slot, in
     }
 }
 
+// lead_h >= 0: the prompt's tail agrees with the tail of the group's first prompt in exactly lead_h
+// tokens (both stopped at the same depth m), and that tail starts at pool index lead_base.  An edge
+// met at depth d whose span starts at lead_base + (d - m) is a stretch of that first prompt's tail,
+// so how far the prompt follows it is known without reading it.
+// below >= 0: the prompt's stop lay inside an old edge that another part of this launch cuts at depth
+// m; `below` is the node that ends at that cut, and the insertion starts there.
 __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs &ws, int32_t j, const MemberIn &in,
-                              GroupCtx &g, int lane) {
+                              GroupCtx &g, int lane, int32_t lead_h = kLcpNone, int64_t lead_base = 0, int32_t below = -1,
+                              int32_t below_depth = -1, int32_t below_tok = -1) {
     DevState *st = tv.st;
     const int32_t m = in.m, e = in.e, split_id = in.split_id, leaf_id = in.leaf_id, tok_m = in.tok_m;
     const int32_t L = in.L, de_e = in.de_e;
@@ -889,11 +920,11 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
     const int64_t tail_base = g.pool_top + in.to;  // pool index holding x[m]
     const int32_t *__restrict__ x = q.tokens + in.qoff;
 
-    int32_t cur = e;
-    int32_t d = m;
+    int32_t cur = below >= 0 ? below : e;
+    int32_t d = below >= 0 && below_depth >= 0 ? below_depth : m;  // (a start below a node may lie deeper than the match)
     bool fresh = false;  // cur has just been created by this wavefront: nothing hangs below it yet
     bool leaf_done = false;  // the prompt's leaf went in together with a split
-    if (e != kRoot && m < de_e) {
+    if (below < 0 && e != kRoot && m < de_e) {
         // The match stopped inside the edge that node e had before this commit. Earlier prompts of
         // this group may have cut that edge into a chain of pieces ending in e; find the piece
         // whose span (start, end] contains depth m.
@@ -959,8 +990,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
     // compare brings along the token that decides the next step, a node that this wavefront has
     // just made has no children to look up, and a node reached through its table slot is described
     // by that slot: a member of a large group costs a lookup, a compare and its stores.
-    int32_t tok = tok_m;  // x[d] (the first unmatched token came with the plan)
-    bool did_split = fresh;  // fresh here: the stop lay inside an edge and this prompt cut it
+    int32_t tok = below >= 0 && below_depth >= 0 ? below_tok : tok_m;  // x[d] (the first unmatched token came with the plan)
     while (d < L) {
         int32_t c = -1, el = 0, s = -1;
         int64_t eo = 0;
@@ -989,7 +1019,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
                     tv.depth_end[leaf] = L;
                     tv.tick[leaf] = tick;
                     leaf_slot = slot_insert(tv, make_key(cur, tok), leaf, L - d, off);
-                    ws.used[j] = did_split ? 3 : 2;
+                    atomicOr(&ws.used[j], 2);
                     ws.leaf_tok[j] = L - d;
                 }
             }
@@ -1003,8 +1033,18 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
             break;
         }
         const int32_t lim = el < L - d ? el : L - d;
-        int32_t a_tok, b_tok;
-        const int32_t jj = common_prefix_and_next(x + d, L - d, tv.pool + eo, el, lim, lane, a_tok, b_tok);
+        int32_t a_tok, b_tok, jj;
+        if (lead_h >= 0 && eo == lead_base + (int64_t)(d - m) && m + lead_h > d) {
+            const int32_t agree = m + lead_h - d;
+            jj = agree < lim ? agree : lim;
+            // the two tokens behind the agreed span, one round trip
+            const int32_t av = x[d + jj < L ? d + jj : L - 1];
+            const int32_t bv = tv.pool[eo + (jj < el ? jj : el - 1)];
+            a_tok = d + jj < L ? uni(av) : -1;
+            b_tok = jj < el ? uni(bv) : -1;
+        } else {
+            jj = common_prefix_and_next(x + d, L - d, tv.pool + eo, el, lim, lane, a_tok, b_tok);
+        }
         if (jj <= 0) {  // the first token matched by construction; anything else is corruption
             if (lane == 0) flag_error(st, kDevInternal);
             return;
@@ -1034,7 +1074,6 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
         if (up < 0) return;
         made_cut(g, lane, s, up, jj);
         made_add(g, lane, up, low_first, c, el - jj, eo + (int64_t)jj, low_slot);
-        did_split = true;
         if (lf.want) {
             made_add(g, lane, up, lf.tok, lf.id, lf.len, lf.off, leaf_slot);
             cur = lf.id;
@@ -1048,7 +1087,353 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
     if (lane == 0) ws.end_node[j] = cur;
 }
 
+// The core of cutting one node's edge at several depths at once, one cut request per lane (lanes
+// below `cnt`, those with `cuts` set; requests are in pick order, several may name the same depth).
+// Node `e` with record `rec` hangs in table slot `s`; every depth lies strictly inside its edge.  The
+// lowest lane of every distinct depth creates the piece that ends there with its split id; the
+// topmost piece takes over slot s, the node itself - keeping id, end and children - is re-hung below
+// the last piece.  Returns, per lane, the id of the piece that ends at the lane's depth.
+__device__ __forceinline__ int32_t cut_edge_lanes(const TreeView &tv, const CommitWs &ws, const GroupCtx &ctx, int32_t e,
+                                                  const NodeRec &rec, int32_t s, int32_t cnt, bool cuts, int32_t j,
+                                                  int32_t depth, int32_t split_id, int lane) {
+    const int32_t ds = rec.depth_end - rec.edge_len;
+    // where my depth stands among the requested depths
+    const int32_t m = cuts ? depth : 0x7FFFFFFF;
+    int32_t prev_m = ds, next_m = 0x7FFFFFFF, cutter = lane;
+    for (int k = 0; k < cnt; ++k) {
+        const int32_t mk = __shfl(m, k);
+        if (mk < m && mk > prev_m) prev_m = mk;
+        if (mk > m && mk < next_m) next_m = mk;
+        if (mk == m && k < cutter) cutter = k;
+    }
+    int32_t prev_cut = -1;
+    for (int k = cnt - 1; k >= 0; --k)
+        if (__shfl(m, k) == prev_m) prev_cut = k;
+    const bool is_cutter = cuts && cutter == lane;
+    const bool is_last = is_cutter && next_m == 0x7FFFFFFF;
+    const int32_t up_id = __shfl(split_id, cutter);
+    const int32_t prev_up = __shfl(split_id, prev_cut < 0 ? 0 : prev_cut);
+    // the first token of my piece and (largest depth) of what is left of the node, one round trip
+    int32_t ftok = 0, low_first = 0;
+    if (is_cutter && prev_cut >= 0) ftok = tv.pool[rec.edge_off + (int64_t)(prev_m - ds)];
+    if (is_last) low_first = tv.pool[rec.edge_off + (int64_t)(depth - ds)];
+    if (is_cutter) {
+        const int64_t off = rec.edge_off + (int64_t)(prev_m - ds);
+        tv.parent[up_id] = prev_cut < 0 ? rec.parent : prev_up;
+        tv.edge_off[up_id] = off;
+        tv.edge_len[up_id] = depth - prev_m;
+        tv.depth_end[up_id] = depth;
+        tv.tick[up_id] = ctx.clock0 + (uint64_t)j;
+        atomicOr(&ws.used[j], 1);
+        if (prev_cut < 0) {  // the topmost piece takes over the node's table slot and the start of the edge
+            tv.slots[s].child = up_id;
+            tv.slots[s].edge_len = depth - prev_m;
+            tv.slot_of[up_id] = s;
+        } else {
+            slot_insert(tv, make_key(prev_up, ftok), up_id, depth - prev_m, off);
+        }
+        if (is_last) {
+            const int64_t low_off = rec.edge_off + (int64_t)(depth - ds);
+            tv.edge_off[e] = low_off;
+            tv.edge_len[e] = rec.depth_end - depth;
+            tv.parent[e] = up_id;
+            slot_insert(tv, make_key(up_id, low_first), e, rec.depth_end - depth, low_off);
+        }
+    }
+    return up_id;
+}
+
+// The prompts of a batch whose matches stopped inside one old edge cut it at their stop depths.
+// Inserted one after the other every prompt costs a few dependent round trips, and a popular edge
+// collects dozens of them; but the pieces follow from the sorted stop depths alone.  So the wavefront
+// of the first such prompt takes one prompt per lane (at most 64, among the first 1,024 of the batch):
+// the lowest lane of every distinct depth m creates the piece that ends at m (with its reserved id),
+// hangs it below the piece of the next smaller depth - the topmost piece takes over the old table
+// slot - and the lane of the largest depth re-hangs the old node, which keeps its id, its end and
+// its children, below the last piece.  What the prompts add behind their cuts is inserted by other
+// wavefronts of the same launch (one per depth and next token), which only need the id of the piece
+// that ends at their depth: the split id reserved for the first prompt, in pick order, that stops
+// there.  Ticks are the cutting prompts' own; the tick pass raises them as for any insert.
+// Returns false with nothing touched if the tree and its table disagree.
+__device__ bool cut_old_edge(const TreeView &tv, const QView &q, const CommitWs &ws, const int32_t *__restrict__ batch_idx,
+                             const GroupCtx &ctx, int32_t g, int32_t e, uint32_t mine_e, int lane) {
+    __shared__ int32_t s_mem[kWave];
+    constexpr int kRows = 16;
+    const uint64_t below = (1ull << lane) - 1ull;
+    int32_t cnt = 1;
+    if (lane == 0) s_mem[0] = g;
+    for (int t = g / kWave; t < kRows; ++t) {
+        const bool bit = (mine_e >> t) & 1u;
+        const uint64_t mask = __ballot(bit);
+        if (!mask) continue;
+        const int32_t pos = cnt + (int32_t)__popcll(mask & below);
+        if (bit && pos < kWave) s_mem[pos] = t * kWave + lane;
+        cnt += (int32_t)__popcll(mask);
+    }
+    if (cnt > kWave) return false;  // (the caller has counted: cannot happen)
+    __syncthreads();
+    const bool active = lane < cnt;
+    const int32_t j = active ? s_mem[lane] : g;
+    // (the old node's record and slot travel with the members' inputs)
+    const int32_t pa_v = ld_i32(&tv.parent[e]), el_v = ld_i32(&tv.edge_len[e]), de_v = ld_i32(&tv.depth_end[e]);
+    const int64_t eo_v = ld_i64(&tv.edge_off[e]);
+    const int32_t s_v = ld_i32(&tv.slot_of[e]);
+    const int32_t m_v = ws.bm_len[j], split_v = ws.resv_id[2 * j];
+    NodeRec rec;
+    rec.parent = uni(pa_v);
+    rec.edge_len = uni(el_v);
+    rec.depth_end = uni(de_v);
+    rec.edge_off = uni64(eo_v);
+    const int32_t s = uni(s_v);
+    const int32_t ds = rec.depth_end - rec.edge_len;
+    bool bad = active && (m_v <= ds || m_v >= rec.depth_end || split_v <= 0);
+    if (s < 0 || (uint32_t)s > tv.slot_mask) bad = true;
+    if (__ballot(bad) || uni(ld_i32(&tv.slots[s < 0 ? 0 : s].child)) != e) {
+        if (lane == 0) flag_error(tv.st, kDevInternal);
+        return false;
+    }
+    cut_edge_lanes(tv, ws, ctx, e, rec, s, cnt, active, j, m_v, split_v, lane);
+    __syncthreads();
+    return true;
+}
+
+// Batches of up to 1,024 prompts (the group keys, match lengths and next tokens of all of them fit
+// the registers of a wavefront: one request per lane and row).  Wavefront g looks at prompt g:
+//   - prompts that stopped at the same node boundary with the same next token form a group; the
+//     first of them, in pick order, inserts the group one after the other below that node;
+//   - prompts that stopped inside the same old edge: the first of them cuts the edge for all (one
+//     prompt per lane, cut_old_edge); behind the cuts the prompts group by stop depth and next token,
+//     and the first prompt of every such group inserts it below the piece that ends at that depth;
+//   - a prompt that is not the first of its group measures how far its unmatched tail agrees with
+//     the tail of that first prompt, which the inserting wavefront picks up (bounded wait).
+// Groups touch disjoint structure, so they proceed concurrently (compare-and-swap table inserts).
 __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                     CommitWs ws) {
+    DevState *st = tv.st;
+    const int lane = threadIdx.x;
+    const int32_t g = blockIdx.x;  // below the capacity of batch_idx and of the per-prompt arrays
+    constexpr int kRows = 16;
+    // One round trip for everything that does not depend on anything else: the commit's state, every
+    // prompt's key, match length and next token, and this prompt's own inputs (read before it is
+    // known that g is an admitted prompt; nothing is followed from them until then).
+    const int32_t skip_v = st->skip;
+    const int32_t nb_v = st->nb;
+    const uint64_t key_v = ws.gkey[g];
+    uint64_t kk[kRows];
+    int32_t mm[kRows], tt[kRows];
+#pragma unroll
+    for (int t = 0; t < kRows; ++t) {
+        const int32_t i = t * kWave + lane;
+        const int32_t ic = i < tv.max_batch ? i : tv.max_batch - 1;
+        kk[t] = ws.gkey[ic];
+        mm[t] = ws.bm_len[ic];
+        tt[t] = ws.next_tok[ic];
+    }
+    GroupCtx ctx;
+    ctx.clock0 = st->clock0;
+    ctx.pool_top = st->pool_top;
+    ctx.n_ent = 0;
+    ctx.cache_ok = true;
+    ctx.c_parent = ctx.c_tok = ctx.c_child = ctx.c_el = ctx.c_slot = -1;
+    ctx.c_eo = 0;
+    ctx.piece = -1;
+    ctx.piece_slot = -1;
+    ctx.piece_rec = NodeRec{};
+    MemberIn own;
+    member_load_own(own, batch_idx, ws, g);
+    if (uni(skip_v)) return;
+    const int32_t nb = uni(nb_v);
+    if (g >= nb) return;
+    const uint64_t key = uni64(key_v);
+    if (key == kNoGroup) return;
+    const bool inside = ((key >> 32) & 1ull) == 0;
+    const int32_t m = uni(own.m), tok = uni(own.tok_m);
+    // who shares the old edge with me (stops inside it), and who also shares depth and next token
+    bool first_e = true, first_s = true;
+    uint32_t mine_e = 0, mine_s = 0;
+    int32_t count_e = 0, cutter = 0x7FFFFFFF, leader = 0x7FFFFFFF;
+#pragma unroll
+    for (int t = 0; t < kRows; ++t) {
+        const int32_t i = t * kWave + lane;
+        const bool eq_e = i < nb && kk[t] == key;
+        const bool eq_d = eq_e && (!inside || mm[t] == m);
+        const bool eq_s = eq_d && (!inside || tt[t] == tok);
+        if (eq_e && i < g) first_e = false;
+        if (eq_s && i < g) first_s = false;
+        if (eq_e && i > g) mine_e |= 1u << t;
+        if (eq_s && i > g) mine_s |= 1u << t;
+        count_e += (int32_t)__popcll(__ballot(eq_e));
+        const uint64_t md = __ballot(eq_d), ms = __ballot(eq_s);
+        if (md && cutter == 0x7FFFFFFF) cutter = t * kWave + (int32_t)__builtin_ctzll(md);  // first prompt that stops at my depth
+        if (ms && leader == 0x7FFFFFFF) leader = t * kWave + (int32_t)__builtin_ctzll(ms);  // first prompt of my group
+    }
+    first_e = !__ballot(!first_e);
+    first_s = !__ballot(!first_s);
+    // an edge that more prompts stop inside than a wavefront has lanes is handled the slow way: its
+    // prompts are one group, inserted one after the other by the first of them
+    const bool cut_scheme = inside && count_e <= kWave;
+    if (inside && !cut_scheme) {
+        first_s = first_e;
+        mine_s = mine_e;
+        leader = 0x7FFFFFFF;
+#pragma unroll
+        for (int t = 0; t < kRows; ++t) {
+            const uint64_t me = __ballot(t * kWave + lane < nb && kk[t] == key);
+            if (me && leader == 0x7FFFFFFF) leader = t * kWave + (int32_t)__builtin_ctzll(me);
+        }
+    }
+    // what hangs on indices: my prompt's span, and the piece my group hangs below (the split id
+    // reserved for the first prompt that stops at my depth)
+    int32_t below_v = -1;
+    if (cut_scheme) below_v = ws.resv_id[2 * cutter];
+    member_load_refs(own, tv, q);
+    const MemberIn me = member_from_lane(own, 0);
+    if (!first_s) {
+        // Not the first of its group: that prompt's wavefront inserts this one.  Meanwhile this
+        // wavefront measures how far the two unmatched tails agree, which lets the insertion walk
+        // down the first prompt's new nodes without comparing tokens again.
+        int32_t h = kLcpNone;
+        const int32_t qf = batch_idx[leader], mf = ws.bm_len[leader];
+        if (uni(mf) == me.m && me.m < me.L) {
+            const int64_t off_f = uni64(q.off[uni(qf)]);
+            const int32_t len_f = uni(q.len[uni(qf)]);
+            const int32_t lim = (len_f < me.L ? len_f : me.L) - me.m;
+            if (lim > 0) h = wave_common_prefix(q.tokens + me.qoff + me.m, q.tokens + off_f + me.m, lim, lane);
+        }
+        int32_t after = -1;  // my token behind the agreed span (what my own tail starts with below the cut)
+        if (h >= 0 && me.m + h < me.L) after = uni(q.tokens[me.qoff + me.m + h]);
+        if (lane == 0) {
+            ws.lcp_tok[g] = after;
+            __hip_atomic_store(&ws.lcp_lead[g], h, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+    }
+    int32_t below = -1;
+    if (cut_scheme) {
+        below = uni(below_v);
+        if (first_e && !cut_old_edge(tv, q, ws, batch_idx, ctx, g, me.e, mine_e, lane)) return;
+        if (below <= 0) {
+            if (lane == 0) flag_error(st, 1u);
+            return;
+        }
+    }
+    const int64_t lead_base = ctx.pool_top + me.to;
+    insert_prompt(tv, q, ws, g, me, ctx, lane, kLcpNone, 0, below);
+    if (!__ballot(mine_s != 0)) return;
+    // The later members of the group, one per lane.  Each has measured how far its tail agrees with
+    // mine (its own wavefront did, concurrently), so it leaves the leaf that I have just hung at a
+    // known depth: the members cut that leaf like an old edge (cut_edge_lanes) and hang what they
+    // have behind their cuts below the pieces, all at once.  Only members that leave at the same
+    // depth with the same token still meet each other; they are inserted one by one afterwards.
+    if (me.m < me.L && ctx.n_ent == 1 && (!inside || cut_scheme)) {
+        __shared__ int32_t s_mem[kWave];
+        const uint64_t lower = (1ull << lane) - 1ull;
+        int32_t cnt = 0;
+        for (int t = g / kWave; t < kRows; ++t) {
+            const bool bit = (mine_s >> t) & 1u;
+            const uint64_t mask = __ballot(bit);
+            if (!mask) continue;
+            const int32_t pos = cnt + (int32_t)__popcll(mask & lower);
+            if (bit && pos < kWave) s_mem[pos] = t * kWave + lane;
+            cnt += (int32_t)__popcll(mask);
+        }
+        if (cnt <= kWave) {
+            __syncthreads();
+            const bool active = lane < cnt;
+            const int32_t j = active ? s_mem[lane] : g;
+            const MemberIn mv = member_load(tv, q, batch_idx, ws, j);
+            int32_t h = active ? kLcpPending : kLcpNone;
+            for (int spin = 0; spin < 2048; ++spin) {
+                if (h == kLcpPending) h = __hip_atomic_load(&ws.lcp_lead[j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                if (!__ballot(h == kLcpPending)) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            const int32_t after = active ? ld_i32(&ws.lcp_tok[j]) : -1;
+            const int32_t span = (mv.L < me.L ? mv.L : me.L) - me.m;
+            const bool ok = !active || (mv.m == me.m && h >= 1 && h <= span && mv.split_id > 0 && mv.leaf_id > 0);
+            if (!__ballot(!ok)) {
+                const int32_t leaf_id = uni(__shfl(ctx.c_child, 0)), leaf_slot = uni(__shfl(ctx.c_slot, 0));
+                NodeRec lrec;
+                lrec.parent = below >= 0 ? below : me.e;
+                lrec.edge_len = me.L - me.m;
+                lrec.depth_end = me.L;
+                lrec.edge_off = lead_base;
+                const int32_t d = me.m + h;            // where this member leaves my string
+                const bool cuts = active && d < me.L;  // (d == my length: it goes on below the whole leaf)
+                int32_t piece = cut_edge_lanes(tv, ws, ctx, leaf_id, lrec, leaf_slot, cnt, cuts, j, d, mv.split_id, lane);
+                if (!cuts) piece = leaf_id;
+                const bool has_tail = active && mv.L > d;
+                bool conflict = false;
+                for (int k = 0; k < cnt; ++k) {
+                    const int32_t dk = __shfl(d, k), ak = __shfl(after, k);
+                    const bool tk = __shfl((int)has_tail, k) != 0;
+                    if (k < lane && has_tail && tk && dk == d && ak == after) conflict = true;
+                }
+                if (active && !conflict) {
+                    int32_t end = piece, leaf_tokens = 0;
+                    if (has_tail) {
+                        const int64_t off = ctx.pool_top + mv.to + (int64_t)h;
+                        tv.parent[mv.leaf_id] = piece;
+                        tv.edge_off[mv.leaf_id] = off;
+                        tv.edge_len[mv.leaf_id] = mv.L - d;
+                        tv.depth_end[mv.leaf_id] = mv.L;
+                        tv.tick[mv.leaf_id] = ctx.clock0 + (uint64_t)j;
+                        slot_insert(tv, make_key(piece, after), mv.leaf_id, mv.L - d, off);
+                        atomicOr(&ws.used[j], 2);
+                        end = mv.leaf_id;
+                        leaf_tokens = mv.L - d;
+                    }
+                    ws.leaf_tok[j] = leaf_tokens;
+                    ws.end_node[j] = end;
+                }
+                __threadfence();
+                __syncthreads();
+                // (what follows looks nodes up in the table: the record of what this wavefront made is not kept here)
+                ctx.cache_ok = false;
+                ctx.piece = -1;
+                uint64_t todo = __ballot(active && conflict);
+                while (todo) {
+                    const int b = (int)__builtin_ctzll(todo);
+                    todo &= todo - 1ull;
+                    insert_prompt(tv, q, ws, uni(__shfl(j, b)), member_from_lane(mv, b), ctx, lane, kLcpNone, 0,
+                                  uni(__shfl(piece, b)), uni(__shfl(d, b)), uni(__shfl(after, b)));
+                }
+                return;
+            }
+        }
+    }
+    // A later member's overlap with this prompt's tail: worked out by that member's own wavefront,
+    // which started together with this one.  The wait is bounded; without an answer the insertion
+    // compares tokens as it would have anyway.
+    auto overlap_of = [&](int32_t j2) -> int32_t {
+        int32_t h = kLcpPending;
+        for (int spin = 0; spin < 2048; ++spin) {
+            h = uni(__hip_atomic_load(&ws.lcp_lead[j2], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT));
+            if (h != kLcpPending) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        return h;
+    };
+    // later members of the group; every lane that owns a member of a row fetches that member's inputs
+    for (int t = g / kWave; t < kRows; ++t) {
+        const bool is_mine = (mine_s >> t) & 1u;
+        uint64_t mask = __ballot(is_mine);
+        if (!mask) continue;
+        const MemberIn mv = member_load(tv, q, batch_idx, ws, is_mine ? t * kWave + lane : g);
+        while (mask) {
+            const int32_t b = (int32_t)__builtin_ctzll(mask);
+            mask &= mask - 1ull;
+            const MemberIn mi = member_from_lane(mv, b);
+            const int32_t h = mi.m == me.m ? overlap_of(t * kWave + b) : kLcpNone;
+            insert_prompt(tv, q, ws, t * kWave + b, mi, ctx, lane, h, lead_base, mi.m == me.m ? below : -1);
+        }
+    }
+}
+
+// Batches of more than 1,024 prompts: one wavefront per group of prompts that stopped at the same
+// place of the old tree (inside the same edge, or at the same node with the same next token), the
+// group's prompts inserted one after the other.
+__global__ __launch_bounds__(kWave) void k_structure_wide(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                      CommitWs ws) {
     DevState *st = tv.st;
     const int lane = threadIdx.x;
@@ -1105,8 +1490,49 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
 #pragma unroll
         for (int t = 0; t < 16; ++t) dup |= (base + t * kWave + lane < g) && (k2[t] == key);
     }
-    if (__ballot(dup)) return;
-    insert_prompt(tv, q, ws, g, member_from_lane(lead, 0), ctx, lane);
+    if (__ballot(dup)) {
+        // Not the first of its group: that prompt's wavefront inserts this one.  Meanwhile this
+        // wavefront measures how far the two unmatched tails agree, which lets the insertion walk
+        // down the first prompt's new nodes without comparing tokens again (prompts of one group
+        // typically share a long new prefix, and each later one would compare it once more).
+        int32_t f = -1;
+#pragma unroll
+        for (int t = 0; t < kRows; ++t) {
+            const int32_t i = t * kWave + lane;
+            const uint64_t mk = __ballot(i < nb && i < g && kk[t] == key);
+            if (mk && f < 0) f = t * kWave + (int32_t)__builtin_ctzll(mk);
+        }
+        int32_t h = kLcpNone;
+        if (f >= 0) {
+            const int32_t qf = batch_idx[f], mf = ws.bm_len[f];
+            const MemberIn me = member_from_lane(lead, 0);
+            if (uni(mf) == me.m && me.m < me.L) {
+                const int64_t off_f = uni64(q.off[uni(qf)]);
+                const int32_t len_f = uni(q.len[uni(qf)]);
+                const int32_t lim = (len_f < me.L ? len_f : me.L) - me.m;
+                if (lim > 0) h = wave_common_prefix(q.tokens + me.qoff + me.m, q.tokens + off_f + me.m, lim, lane);
+            }
+        }
+        if (lane == 0) __hip_atomic_store(&ws.lcp_lead[g], h, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    const MemberIn first_in = member_from_lane(lead, 0);
+    const int64_t lead_base = ctx.pool_top + first_in.to;
+    const int32_t lead_m = first_in.m;
+    insert_prompt(tv, q, ws, g, first_in, ctx, lane);
+    // A later member's overlap with this prompt's tail: worked out by that member's own wavefront,
+    // which started together with this one.  The wait is bounded; without an answer the insertion
+    // compares tokens as it would have anyway.
+    auto overlap_of = [&](int32_t j2) -> int32_t {
+        if (j2 >= kRows * kWave) return kLcpNone;  // (members beyond the first rows do not look for their leader)
+        int32_t h = kLcpPending;
+        for (int spin = 0; spin < 2048; ++spin) {
+            h = uni(__hip_atomic_load(&ws.lcp_lead[j2], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT));
+            if (h != kLcpPending) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+        return h;
+    };
     // later members of the group; every lane that owns a member of a row fetches that member's inputs
     auto row = [&](int32_t row_base, bool is_mine) {
         uint64_t mask = __ballot(is_mine);
@@ -1115,7 +1541,9 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
         while (mask) {
             int32_t b = (int32_t)__builtin_ctzll(mask);
             mask &= mask - 1ull;
-            insert_prompt(tv, q, ws, row_base + b, member_from_lane(mv, b), ctx, lane);
+            const MemberIn mi = member_from_lane(mv, b);
+            const int32_t h = mi.m == lead_m ? overlap_of(row_base + b) : kLcpNone;
+            insert_prompt(tv, q, ws, row_base + b, mi, ctx, lane, h, lead_base);
         }
     };
     if (__ballot(mine0 != 0)) {
@@ -1319,13 +1747,13 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
 // The sweeps over all nodes visit four nodes per thread and trip, every field requested before any
 // is looked at (one round trip per trip; a loop that tests edge_len, then tick, then builds the key
 // pays three per node).  f(id, edge_len, key) is called for every live node that may be evicted.
-template <class F>
-__device__ __forceinline__ void for_each_evictable(const TreeView &tv, int32_t n_slots, uint64_t keep_from, int depth_bits,
-                                                   int64_t first, int64_t stride, F f) {
+template <bool WITH_SLOT, class F>
+__device__ __forceinline__ void for_each_evictable_impl(const TreeView &tv, int32_t n_slots, uint64_t keep_from, int depth_bits,
+                                                        int64_t first, int64_t stride, F f) {
     constexpr int kUnroll = 4;
     const uint64_t dm = (1ull << depth_bits) - 1ull;
     for (int64_t id0 = first; id0 < n_slots; id0 += kUnroll * stride) {
-        int32_t len[kUnroll], de[kUnroll];
+        int32_t len[kUnroll], de[kUnroll], sl[kUnroll];
         uint64_t tk[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -1334,14 +1762,28 @@ __device__ __forceinline__ void for_each_evictable(const TreeView &tv, int32_t n
             len[u] = tv.edge_len[idc];
             tk[u] = tv.tick[idc];
             de[u] = tv.depth_end[idc];
+            sl[u] = WITH_SLOT ? tv.slot_of[idc] : -1;
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int64_t id = id0 + u * stride;
             if (id >= n_slots || len[u] <= 0 || tk[u] >= keep_from) continue;
-            f(id, len[u], (tk[u] << depth_bits) | (dm - (uint64_t)(uint32_t)de[u]));
+            f(id, len[u], (tk[u] << depth_bits) | (dm - (uint64_t)(uint32_t)de[u]), sl[u]);
         }
     }
+}
+// f(id, edge_len, key)
+template <class F>
+__device__ __forceinline__ void for_each_evictable(const TreeView &tv, int32_t n_slots, uint64_t keep_from, int depth_bits,
+                                                   int64_t first, int64_t stride, F f) {
+    for_each_evictable_impl<false>(tv, n_slots, keep_from, depth_bits, first, stride,
+                                   [&](int64_t id, int32_t len, uint64_t key, int32_t) { f(id, len, key); });
+}
+// f(id, edge_len, key, slot): also brings the node's child-table slot along (for sweeps that remove nodes)
+template <class F>
+__device__ __forceinline__ void for_each_evictable_slot(const TreeView &tv, int32_t n_slots, uint64_t keep_from,
+                                                        int depth_bits, int64_t first, int64_t stride, F f) {
+    for_each_evictable_impl<true>(tv, n_slots, keep_from, depth_bits, first, stride, f);
 }
 
 // One step of the search for the cut key, run by one workgroup of 256 threads once the weighted
@@ -1407,28 +1849,16 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     if (last_block_done(st, 4 + pass)) evict_descend_step(st, ws.evict_hist + pass * kEvictBins, width, pass == 0);
 }
 
-// Removes one live node: tombstone in the parent's table slot, id back on the free stack; its tokens
-// and the node are added to the two workgroup counters.
-__device__ __forceinline__ void evict_remove_node(const TreeView &tv, DevState *st, int64_t id, int32_t len,
+// Removes one live node: a tombstone in the table slot that leads to it (probe chains stay intact),
+// its id back on the free stack; its tokens and the node are added to the two workgroup counters.
+__device__ __forceinline__ void evict_remove_node(const TreeView &tv, DevState *st, int64_t id, int32_t len, int32_t slot,
                                                   unsigned long long *s_tok, int *s_cnt) {
-    // (the place on the free stack is asked for together with the node's fields: it does not depend
-    // on them)
-    const int32_t pa = tv.parent[id];
-    const int64_t eo = tv.edge_off[id];
     const int32_t pos = atomicAdd(&st->free_cnt, 1);
     tv.edge_len[id] = 0;
-    // leave a tombstone where the parent pointed at this node
-    const uint64_t key = make_key(pa, tv.pool[eo]);
-    uint32_t h = hash_key(key) & tv.slot_mask;
-    for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
-        uint64_t kk = __hip_atomic_load(&tv.slots[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (kk == key) {
-            __hip_atomic_store(&tv.slots[h].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            break;
-        }
-        if (kk == kEmptyKey) { flag_error(st, kDevInternal); break; }
-        h = (h + 1) & tv.slot_mask;
-    }
+    if (slot >= 0 && (uint32_t)slot <= tv.slot_mask)
+        __hip_atomic_store(&tv.slots[slot].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+        flag_error(st, kDevInternal);
     if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = (int32_t)id;
     atomicAdd(s_tok, (unsigned long long)len);
     atomicAdd(s_cnt, 1);
@@ -1437,8 +1867,9 @@ __device__ __forceinline__ void evict_remove_node(const TreeView &tv, DevState *
 __device__ __forceinline__ void evict_apply_sweep(const TreeView &tv, DevState *st, uint64_t cut, uint64_t keep_from,
                                                   int32_t n_slots, int depth_bits, int64_t first, int64_t stride,
                                                   unsigned long long *s_tok, int *s_cnt) {
-    for_each_evictable(tv, n_slots, keep_from, depth_bits, first, stride, [&](int64_t id, int32_t len, uint64_t node_key) {
-        if (node_key <= cut) evict_remove_node(tv, st, id, len, s_tok, s_cnt);
+    for_each_evictable_slot(tv, n_slots, keep_from, depth_bits, first, stride,
+                            [&](int64_t id, int32_t len, uint64_t node_key, int32_t slot) {
+        if (node_key <= cut) evict_remove_node(tv, st, id, len, slot, s_tok, s_cnt);
     });
 }
 // Books the removal (one thread, after every workgroup has added its counts): the child table is
@@ -1475,17 +1906,18 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
     if (tid == 0) { s_tok = 0; s_cnt = 0; }
     __syncthreads();
     const bool windowed = n_hist_pass > 0 && shift < 64;  // (otherwise every node that may go is a candidate)
-    for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
-                       (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t key) {
+    for_each_evictable_slot(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                            (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t key, int32_t slot) {
         const uint64_t top = windowed ? (key >> shift) : 0ull;
         if (evict_all || (windowed && top < prefix)) {
-            evict_remove_node(tv, st, id, len, &s_tok, &s_cnt);
+            evict_remove_node(tv, st, id, len, slot, &s_tok, &s_cnt);
         } else if (!windowed || top == prefix) {
             int32_t at = atomicAdd(&st->cand_cnt, 1);
             if (at < kEvictCand) {
                 ws.cand_key[at] = key;
                 ws.cand_len[at] = len;
                 ws.cand_id[at] = (int32_t)id;
+                ws.cand_slot[at] = slot;
             }
         }
     });
@@ -1553,9 +1985,10 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         // different depths), so the collected nodes up to the cut are removed as they were stored
         for (int32_t i = tid; i < n; i += 256) {
             const uint64_t key = __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (key <= cut)
-                evict_remove_node(tv, st, __hip_atomic_load(&ws.cand_id[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
-                                  __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), &s_tok, &s_cnt);
+            const int32_t id = __hip_atomic_load(&ws.cand_id[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int32_t len = __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int32_t slot = __hip_atomic_load(&ws.cand_slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (key <= cut) evict_remove_node(tv, st, id, len, slot, &s_tok, &s_cnt);
         }
     }
     __syncthreads();
@@ -1602,7 +2035,10 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
                            ws, hint_len, hint_node);
         hipLaunchKernelGGL(k_copy_tails, dim3(batch_cap), dim3(256), 0, stream, tv, q, batch_idx, ws, hint_len ? 1 : 0);
     }
-    if (batch_cap > 0) hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
+    if (batch_cap > 16 * kWave)
+        hipLaunchKernelGGL(k_structure_wide, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
+    else if (batch_cap > 0)
+        hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     // Every live edge sits in the active half of the token pool, so a budget of at least that half
     // can never be exceeded: the eviction kernels (no-ops that still cost a launch each) are left out.
     const bool may_evict = budget < tv.pool_half;

@@ -77,6 +77,7 @@ struct TreeView {
     int32_t *edge_len;   // 0 = dead slot (root is id 0 with length 0)
     int32_t *depth_end;  // tokens from the root to the end of this node's edge
     uint64_t *tick;      // last-use tick
+    int32_t *slot_of;    // index of the child-table slot that leads to this node
     int32_t *free_stack;
     Slot *slots;
     uint32_t slot_mask;  // number of slots - 1 (power of two)
@@ -97,11 +98,14 @@ struct CommitWs {
     int32_t *used;      // [max_batch] bit 0: prompt j used its reserved split id, bit 1: its reserved leaf id
     int32_t *leaf_tok;  // [max_batch] tokens of the leaf prompt j added (0 if none)
     int32_t *next_tok;  // [max_batch] first unmatched token of prompt j (-1: matched in full)
+    int32_t *lcp_lead;  // [max_batch] tokens that prompt j's unmatched tail shares with the tail of its group's first prompt
+    int32_t *lcp_tok;   // [max_batch] prompt j's token behind that shared span (-1: the prompt ends there)
     int32_t *resv_id;   // [2*max_batch] scratch: the node ids reserved for this commit
     int64_t *evict_hist; // [6][2048] weighted digit histograms of the eviction cut search
     uint64_t *cand_key;  // [kEvictCand] eviction keys of the nodes collected for the last stretch of the search
     int32_t *cand_len;   // [kEvictCand] their edge lengths
     int32_t *cand_id;    // [kEvictCand] their node ids
+    int32_t *cand_slot;  // [kEvictCand] their child-table slots
     int32_t *iota_idx;  // [max_batch] scratch batch indices for build_tree
     int32_t *iota_n;    // [1]
 };

@@ -11,8 +11,8 @@
 namespace klpm {
 
 struct Layout {
-    size_t state, parent, edge_off, edge_len, depth_end, tick, free_stack, slots, pool;
-    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, resv_id, evict_hist, cand_key, cand_len, cand_id, iota_idx, iota_n;
+    size_t state, parent, edge_off, edge_len, depth_end, tick, slot_of, free_stack, slots, pool;
+    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, lcp_lead, lcp_tok, resv_id, evict_hist, cand_key, cand_len, cand_id, cand_slot, iota_idx, iota_n;
     size_t total;
     uint32_t n_slots_table;
 };
@@ -37,6 +37,7 @@ static Layout make_layout(const kLPM_config &c) {
     L.edge_len = take(mn * 4);
     L.depth_end = take(mn * 4);
     L.tick = take(mn * 8);
+    L.slot_of = take(mn * 4);
     L.free_stack = take(mn * 4);
     L.slots = take((size_t)ns * sizeof(Slot));
     L.pool = take((size_t)c.pool_tokens * 2 * 4);
@@ -48,11 +49,14 @@ static Layout make_layout(const kLPM_config &c) {
     L.used = take(mb * 4);
     L.leaf_tok = take(mb * 4);
     L.next_tok = take(mb * 4);
+    L.lcp_lead = take(mb * 4);
+    L.lcp_tok = take(mb * 4);
     L.resv_id = take(mb * 8);
     L.evict_hist = take(6 * 2048 * 8);  // eviction cut search: 6 passes of 2048 weighted bins
     L.cand_key = take((size_t)kEvictCand * 8);
     L.cand_len = take((size_t)kEvictCand * 4);
     L.cand_id = take((size_t)kEvictCand * 4);
+    L.cand_slot = take((size_t)kEvictCand * 4);
     L.iota_idx = take(mb * 4);
     L.iota_n = take(256);
     L.total = o;
@@ -76,6 +80,7 @@ __global__ __launch_bounds__(256) void k_tree_init(TreeView tv) {
         tv.edge_len[i] = 0;
         tv.depth_end[i] = 0;
         tv.tick[i] = 0;
+        tv.slot_of[i] = -1;
         tv.free_stack[i] = 0;
     }
     if (gid == 0) {
@@ -336,6 +341,7 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     tv.edge_len = (int32_t *)(base + L.edge_len);
     tv.depth_end = (int32_t *)(base + L.depth_end);
     tv.tick = (uint64_t *)(base + L.tick);
+    tv.slot_of = (int32_t *)(base + L.slot_of);
     tv.free_stack = (int32_t *)(base + L.free_stack);
     tv.slots = (Slot *)(base + L.slots);
     tv.slot_mask = L.n_slots_table - 1;
@@ -353,11 +359,14 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     ws.used = (int32_t *)(base + L.used);
     ws.leaf_tok = (int32_t *)(base + L.leaf_tok);
     ws.next_tok = (int32_t *)(base + L.next_tok);
+    ws.lcp_lead = (int32_t *)(base + L.lcp_lead);
+    ws.lcp_tok = (int32_t *)(base + L.lcp_tok);
     ws.resv_id = (int32_t *)(base + L.resv_id);
     ws.evict_hist = (int64_t *)(base + L.evict_hist);
     ws.cand_key = (uint64_t *)(base + L.cand_key);
     ws.cand_len = (int32_t *)(base + L.cand_len);
     ws.cand_id = (int32_t *)(base + L.cand_id);
+    ws.cand_slot = (int32_t *)(base + L.cand_slot);
     ws.iota_idx = (int32_t *)(base + L.iota_idx);
     ws.iota_n = (int32_t *)(base + L.iota_n);
 

@@ -13,7 +13,7 @@ from . import binding as B
 
 
 def size_config(cache_tokens: int, cache_prompts: int, budget: int, max_batch: int, max_prompt_len: int,
-                extra_prompts: int = 0, extra_tokens: int = 0) -> B.Config:
+                extra_prompts: int = 0, extra_tokens: int = 0, slack_batches: int = 32) -> B.Config:
     """A configuration with room for the initial cache plus commits of ``max_batch`` prompts.
 
     The tree is built without eviction, so one pool half must hold the whole initial cache; under a
@@ -22,8 +22,9 @@ def size_config(cache_tokens: int, cache_prompts: int, budget: int, max_batch: i
     """
     finite = budget < (1 << 36)  # anything larger cannot be reached and means "never evict"
     live = max(int(cache_tokens), int(budget)) if finite else int(cache_tokens) + int(extra_tokens)
-    # (room for several worst-case batches between two pool compactions: the pool is cheap next to the HBM size)
-    pool = int(live * 1.05) + 8 * max_batch * max_prompt_len + 4096
+    # (room for ``slack_batches`` worst-case batches between two pool compactions, which move every cached
+    # token once: the pool is cheap next to the HBM size, a compaction costs a step a few hundred microseconds)
+    pool = int(live * 1.05) + slack_batches * max_batch * max_prompt_len + 4096
     nodes = 2 * (cache_prompts + extra_prompts) + 4 * max_batch + 64
     return B.make_config(budget, pool, nodes, max_batch, max_prompt_len)
 
