@@ -418,6 +418,18 @@ def test_config2_full_size_steps():
         phase = _check_step(s, ref, q, w.queries, w.k, w.batch, phase, w.budget, big=True, fifo=(step == 0))
 
 
+def test_config2_deep_full_size_step():
+    """The deep-tree variant at full size (100M tokens in 1.2M nodes, 65,536 waiting): one whole step
+    with the canonical tree compared before and after (the oracle's eviction is a scan per evicted
+    leaf there, about ten seconds for the one step)."""
+    w = W.config2_deep()
+    _say(f"config2-deep full: cache {w.cache.n} prompts / {w.cache.tokens.shape[0]} tokens, {w.queries.n} queries")
+    s, ref, q = _setup(w, extra_prompts=2 * w.batch, max_len=8192)
+    _say(f"  built both trees: {ref.total_tokens} tokens, {ref.n_nodes} nodes")
+    _same_tree(s, ref, big=True)
+    _check_step(s, ref, q, w.queries, w.k, w.batch, 0, w.budget, big=True, fifo=True)
+
+
 def test_config3_full_size_k_sweep():
     """The hierarchical configuration at full size: match once, select for every k of the sweep."""
     w = W.config3()
@@ -1261,6 +1273,43 @@ def test_groups_larger_than_a_wavefront():
         tail = W.take_prompts(hq, np.arange(n // 2, n))
         q2 = K.DeviceQueries.from_host(tail, "cuda:0")
         _check_step(s, ref, q2, tail, 1, n // 2, 0, 1 << 40, fifo=True)
+
+
+def test_batches_that_share_new_prefixes_at_several_levels():
+    """Admitted prompts of the shape prefix + first c tokens of a donor string + own tail, several per
+    donor with different c, some equal, some a prefix of another: behind the place where they leave
+    the old tree they share new prefixes of different lengths, level below level.  The cached prompt
+    of a prefix either continues it (the batch stops inside that edge, at the prefix end and at
+    other depths) or ends with it (the batch stops at a node boundary)."""
+    rng = np.random.default_rng(97)
+    n_pref = 12
+    prefixes = [rng.integers(0, 50, size=int(rng.integers(40, 300))).tolist() for _ in range(n_pref)]
+    for p_i in range(n_pref):
+        prefixes[p_i][0] = 100 + p_i  # distinct first tokens
+    cached = [p + (rng.integers(50, 60, size=int(rng.integers(5, 400))).tolist() if i % 2 else []) for i, p in enumerate(prefixes)]
+    cache = W.generators._from_lists(cached, list(range(n_pref)))
+    donors = [[rng.integers(60, 64, size=200).tolist() for _ in range(3)] for _ in range(n_pref)]
+    lists = []
+    for _ in range(900):
+        g = int(rng.integers(0, n_pref))
+        kind = rng.random()
+        if kind < 0.15:   # stops somewhere inside the prefix (or the cached continuation)
+            base = cached[g][: int(rng.integers(1, len(cached[g]) + 1))]
+            lists.append(base + rng.integers(70, 73, size=int(rng.integers(0, 4))).tolist())
+            continue
+        d = donors[g][int(rng.integers(0, 3))]
+        c = int(rng.choice([0, 1, 2, 5, 5, 17, 64, 64, 130, 200]))
+        own = rng.integers(80, 83, size=int(rng.choice([0, 0, 1, 3, 40]))).tolist()
+        lists.append(prefixes[g] + d[:c] + own)
+    hq = W.generators._from_lists(lists, list(range(len(lists))))
+    w = W.Workload("levels", cache, hq, 3, 450, 1 << 40)
+    s, ref, q = _setup(w, max_batch=450, extra_prompts=len(lists))
+    ph = _check_step(s, ref, q, hq, 3, 450, 0, 1 << 40, fifo=True)
+    rest = W.take_prompts(hq, np.setdiff1d(np.arange(hq.n), s.batch()))
+    q2 = K.DeviceQueries.from_host(rest, "cuda:0")
+    ph = _check_step(s, ref, q2, rest, 3, 450, ph, 1 << 40, fifo=True)
+    # once more under a budget that evicts part of what the two batches built
+    _check_step(s, ref, q, hq, K_INF, 300, ph, ref.total_tokens // 2, fifo=True)
 
 
 def test_largest_batch_and_very_long_prompts():
