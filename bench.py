@@ -796,6 +796,15 @@ def bench_single_step(args) -> int:
     log(f"tree built on the GPU in {time.time() - t0:.1f}s: {st.total_tokens} tokens, {st.n_nodes} nodes")
     fifo = bool((np.diff(hq.arrival.astype(np.int64)) >= 0).all())  # all of these queues are in arrival order
     R = max(args.steps, 20)
+    if args.calib_copy_mib > 0:
+        # a plain elementwise copy of known size: reads and writes calib_copy_mib MiB each
+        n_el = args.calib_copy_mib * (1 << 20) // 4
+        src = torch.ones(n_el, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -865,6 +874,9 @@ def bench_single_step(args) -> int:
                               "traffic": traffic_cold,
                               "traffic_GBps": traffic_cold / (cold_ms * 1e-3) / 1e9 if traffic_cold else None,
                               "overread": (traffic_cold - compulsory) / compulsory if traffic_cold else None}},
+        # queue-wide match launches in dispatch order, for reading a profiler's per-dispatch records
+        "match_launches": [["warm-up", len(ks)], ["timed steps", R * len(ks)], ["cold: one untimed, then timed after a sweep", 1 + args.cold_reps],
+                           ["back to back: one untimed, then timed", 1 + args.cold_reps]],
     }
     if args.cpu_steps > 0:
         import oracle
