@@ -36,6 +36,15 @@ constexpr int kPlanThreads = 1024;
 
 __device__ __forceinline__ void flag_error(DevState *st, uint32_t bit) { atomicOr(&st->device_error, bit); }
 
+// What a workgroup barrier does for memory, for code that runs inside one wavefront (the structure
+// pass: one wavefront per group, also when it is one part of a larger workgroup): the wavefront's
+// earlier stores are complete before its later loads are issued.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // ------------------------------------------------------------------ plan
 // True for exactly one workgroup of the grid: the one that finishes last. `slot` picks one of the
 // per-commit counters (reset by the plan kernel). Every thread of every workgroup must call it.
@@ -408,22 +417,26 @@ __global__ __launch_bounds__(256) void k_end_commit(TreeView tv, kLPM_stats *__r
 // The same by one workgroup, for trees small enough that its speed at the (rare) work does not
 // matter.
 constexpr int kSmallMaintainThreads = 1024;
-__global__ __launch_bounds__(kSmallMaintainThreads) void k_end_commit_small(TreeView tv,
-                                                                             kLPM_stats *__restrict__ stats_out) {
+template <int THREADS>
+__device__ __forceinline__ void end_commit_small_body(const TreeView &tv, kLPM_stats *__restrict__ stats_out) {
     DevState *st = tv.st;
     const int tid = threadIdx.x;
     const int need_compact = st->need_compact, need_rebuild = st->need_rebuild;
     if (need_compact) {
-        compact_nodes(tv, st, tid / kWave, kSmallMaintainThreads / kWave, tid & (kWave - 1));
+        compact_nodes(tv, st, tid / kWave, THREADS / kWave, tid & (kWave - 1));
         __syncthreads();
         if (tid == 0) compact_switch(tv, st);
     } else if (need_rebuild) {
-        clear_table(tv, tid, kSmallMaintainThreads);
+        clear_table(tv, tid, THREADS);
         __syncthreads();
-        fill_table(tv, st, tid, kSmallMaintainThreads);
+        fill_table(tv, st, tid, THREADS);
     }
     __syncthreads();
     if (tid == 0) write_stats(st, stats_out);
+}
+__global__ __launch_bounds__(kSmallMaintainThreads) void k_end_commit_small(TreeView tv,
+                                                                             kLPM_stats *__restrict__ stats_out) {
+    end_commit_small_body<kSmallMaintainThreads>(tv, stats_out);
 }
 
 // ------------------------------------------------------------------ tails
@@ -476,7 +489,7 @@ __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const 
 // of the previous commit has lowered it.
 constexpr int kFusedPlanMax = 2048;
 constexpr int kFusedThreads = 256;
-__global__ __launch_bounds__(kFusedThreads) void k_plan_copy(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+__device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                              const int32_t *__restrict__ n_selected, int32_t batch_cap,
                                                              CommitWs ws, const int32_t *__restrict__ hint_len,
                                                              const int32_t *__restrict__ hint_node) {
@@ -611,6 +624,12 @@ __global__ __launch_bounds__(kFusedThreads) void k_plan_copy(TreeView tv, QView 
             if (i < len) dst[i] = v[r];
         }
     }
+}
+__global__ __launch_bounds__(kFusedThreads) void k_plan_copy(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                             const int32_t *__restrict__ n_selected, int32_t batch_cap,
+                                                             CommitWs ws, const int32_t *__restrict__ hint_len,
+                                                             const int32_t *__restrict__ hint_node) {
+    plan_copy_body(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
 }
 
 // ------------------------------------------------------------------ structure pass
@@ -791,7 +810,7 @@ __device__ __forceinline__ int32_t split_node(const TreeView &tv, const CommitWs
     low_first_out = uni(__shfl(low_first, 0));
     low_slot_out = uni(__shfl(low_slot, 0));
     leaf_slot_out = uni(__shfl(leaf_slot, 0));
-    __syncthreads();
+    wave_sync();
     return up;
 }
 
@@ -1025,7 +1044,7 @@ __device__ void insert_prompt(const TreeView &tv, const QView &q, const CommitWs
             }
             leaf = uni(__shfl(leaf, 0));
             leaf_slot = uni(__shfl(leaf_slot, 0));
-            __syncthreads();
+            wave_sync();
             if (leaf < 0) return;
             made_add(g, lane, cur, tok, leaf, L - d, tail_base + (int64_t)(d - m), leaf_slot);
             cur = leaf;
@@ -1171,7 +1190,7 @@ __device__ bool cut_old_edge(const TreeView &tv, const QView &q, const CommitWs 
         cnt += (int32_t)__popcll(mask);
     }
     if (cnt > kWave) return false;  // (the caller has counted: cannot happen)
-    __syncthreads();
+    wave_sync();
     const bool active = lane < cnt;
     const int32_t j = active ? s_mem[lane] : g;
     // (the old node's record and slot travel with the members' inputs)
@@ -1193,7 +1212,7 @@ __device__ bool cut_old_edge(const TreeView &tv, const QView &q, const CommitWs 
         return false;
     }
     cut_edge_lanes(tv, ws, ctx, e, rec, s, cnt, active, j, m_v, split_v, lane);
-    __syncthreads();
+    wave_sync();
     return true;
 }
 
@@ -1207,7 +1226,7 @@ __device__ bool cut_old_edge(const TreeView &tv, const QView &q, const CommitWs 
 //   - a prompt that is not the first of its group measures how far its unmatched tail agrees with
 //     the tail of that first prompt, which the inserting wavefront picks up (bounded wait).
 // Groups touch disjoint structure, so they proceed concurrently (compare-and-swap table inserts).
-__global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+__device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                      CommitWs ws) {
     DevState *st = tv.st;
     const int lane = threadIdx.x;
@@ -1338,7 +1357,7 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
             cnt += (int32_t)__popcll(mask);
         }
         if (cnt <= kWave) {
-            __syncthreads();
+            wave_sync();
             const bool active = lane < cnt;
             const int32_t j = active ? s_mem[lane] : g;
             const MemberIn mv = member_load(tv, q, batch_idx, ws, j);
@@ -1387,7 +1406,7 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
                     ws.end_node[j] = end;
                 }
                 __threadfence();
-                __syncthreads();
+                wave_sync();
                 // (what follows looks nodes up in the table: the record of what this wavefront made is not kept here)
                 ctx.cache_ok = false;
                 ctx.piece = -1;
@@ -1428,6 +1447,10 @@ __global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const
             insert_prompt(tv, q, ws, t * kWave + b, mi, ctx, lane, h, lead_base, mi.m == me.m ? below : -1);
         }
     }
+}
+__global__ __launch_bounds__(kWave) void k_structure(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                     CommitWs ws) {
+    structure_body(tv, q, batch_idx, ws);
 }
 
 // Batches of more than 1,024 prompts: one wavefront per group of prompts that stopped at the same
@@ -1565,7 +1588,7 @@ __global__ __launch_bounds__(kWave) void k_structure_wide(TreeView tv, QView q, 
 }
 
 // ------------------------------------------------------------------ ticks, then publish the inserts
-__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass,
+__device__ __forceinline__ void ticks_body(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass,
                                                int evict_enqueued) {
     DevState *st = tv.st;
     const int tid = threadIdx.x;
@@ -1730,6 +1753,10 @@ __global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t
     if (evict)
         for (int i = tid; i < n_pass * kEvictBins; i += blockDim.x) ws.evict_hist[i] = 0;
 }
+__global__ __launch_bounds__(256) void k_ticks(TreeView tv, CommitWs ws, int64_t budget, int64_t protect, int tick_bits, int n_pass,
+                                               int evict_enqueued) {
+    ticks_body(tv, ws, budget, protect, tick_bits, n_pass, evict_enqueued);
+}
 
 // ------------------------------------------------------------------ eviction
 // Order of removal: tick ascending, then depth descending (the deepest node of the oldest path is
@@ -1863,6 +1890,48 @@ __device__ __forceinline__ void evict_remove_node(const TreeView &tv, DevState *
     atomicAdd(s_tok, (unsigned long long)len);
     atomicAdd(s_cnt, 1);
 }
+// Removals of one workgroup, listed in LDS first: the workgroup then takes its places on the free
+// stack with one atomic for all of them (an atomic per node on the one counter is served one by one,
+// and a commit removes a thousand nodes and more).
+constexpr int kRemovalList = 1024;
+struct RemovalList {
+    int32_t *ids, *slots;  // [kRemovalList] in LDS
+    int32_t *n;            // LDS counter, zeroed by the caller
+};
+__device__ __forceinline__ void removal_push(const TreeView &tv, DevState *st, const RemovalList &rl, int64_t id, int32_t len,
+                                             int32_t slot, unsigned long long *s_tok, int *s_cnt) {
+    const int32_t at = atomicAdd(rl.n, 1);
+    if (at < kRemovalList) {
+        rl.ids[at] = (int32_t)id;
+        rl.slots[at] = slot;
+        atomicAdd(s_tok, (unsigned long long)len);
+        atomicAdd(s_cnt, 1);
+    } else {
+        evict_remove_node(tv, st, id, len, slot, s_tok, s_cnt);  // (the list is full: one by one)
+    }
+}
+// Every thread of the workgroup calls it (barriers inside); the list is empty afterwards.
+__device__ __forceinline__ void removal_flush(const TreeView &tv, DevState *st, const RemovalList &rl, int tid, int n_threads) {
+    __shared__ int32_t s_base;
+    __syncthreads();
+    const int32_t n = *rl.n < kRemovalList ? *rl.n : kRemovalList;
+    if (tid == 0) s_base = n > 0 ? atomicAdd(&st->free_cnt, n) : 0;
+    __syncthreads();
+    const int32_t base = s_base;
+    for (int32_t i = tid; i < n; i += n_threads) {
+        const int32_t id = rl.ids[i], slot = rl.slots[i];
+        tv.edge_len[id] = 0;
+        if (slot >= 0 && (uint32_t)slot <= tv.slot_mask)
+            __hip_atomic_store(&tv.slots[slot].key, kTombKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else
+            flag_error(st, kDevInternal);
+        const int32_t pos = base + i;
+        if (pos >= 0 && pos < tv.max_nodes) tv.free_stack[pos] = id;
+    }
+    __syncthreads();
+    if (tid == 0) *rl.n = 0;
+    __syncthreads();
+}
 // Removes every live, unprotected node with key <= cut among the nodes first, first + stride, ...
 __device__ __forceinline__ void evict_apply_sweep(const TreeView &tv, DevState *st, uint64_t cut, uint64_t keep_from,
                                                   int32_t n_slots, int depth_bits, int64_t first, int64_t stride,
@@ -1888,7 +1957,7 @@ __device__ __forceinline__ void evict_apply_publish(const TreeView &tv, DevState
 // by key, cuts where their lengths add up to what is left to free, and removes those up to the cut.
 // More nodes in the window than the sort holds (very deep paths stamped by few prompts) are handled
 // by that workgroup with digit passes of its own over all nodes.
-__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
+__device__ __forceinline__ void evict_gather_body(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
     DevState *st = tv.st;
     const int do_evict = st->do_evict;
     const uint64_t prefix = st->evict_prefix;
@@ -1902,25 +1971,45 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
     __shared__ unsigned long long s_cut;
     __shared__ unsigned long long s_tok;
     __shared__ int s_cnt;
+    __shared__ int32_t l_ids[kRemovalList], l_slots[kRemovalList];
+    __shared__ int32_t c_id[kEvictCand], c_slot[kEvictCand];
+    __shared__ int32_t s_nrem, s_ncand, s_cbase;
+    const RemovalList rl{l_ids, l_slots, &s_nrem};
     const int tid = threadIdx.x;
-    if (tid == 0) { s_tok = 0; s_cnt = 0; }
+    if (tid == 0) { s_tok = 0; s_cnt = 0; s_nrem = 0; s_ncand = 0; }
     __syncthreads();
     const bool windowed = n_hist_pass > 0 && shift < 64;  // (otherwise every node that may go is a candidate)
+    // (removals and candidates are listed in LDS: one atomic per workgroup on each of the shared counters)
     for_each_evictable_slot(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
                             (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t key, int32_t slot) {
         const uint64_t top = windowed ? (key >> shift) : 0ull;
         if (evict_all || (windowed && top < prefix)) {
-            evict_remove_node(tv, st, id, len, slot, &s_tok, &s_cnt);
+            removal_push(tv, st, rl, id, len, slot, &s_tok, &s_cnt);
         } else if (!windowed || top == prefix) {
-            int32_t at = atomicAdd(&st->cand_cnt, 1);
-            if (at < kEvictCand) {
-                ws.cand_key[at] = key;
-                ws.cand_len[at] = len;
-                ws.cand_id[at] = (int32_t)id;
-                ws.cand_slot[at] = slot;
+            const int32_t at = atomicAdd(&s_ncand, 1);
+            if (at < kEvictCand) {  // (more than that in one workgroup: the search takes its other road, which only needs the count)
+                s_key[at] = key;
+                s_len[at] = len;
+                c_id[at] = (int32_t)id;
+                c_slot[at] = slot;
             }
         }
     });
+    removal_flush(tv, st, rl, tid, 256);
+    if (tid == 0) s_cbase = s_ncand > 0 ? atomicAdd(&st->cand_cnt, s_ncand) : 0;
+    __syncthreads();
+    {
+        const int32_t nc = s_ncand < kEvictCand ? s_ncand : kEvictCand, cbase = s_cbase;
+        for (int32_t i = tid; i < nc; i += 256) {
+            const int32_t at = cbase + i;
+            if (at < kEvictCand) {
+                ws.cand_key[at] = s_key[i];
+                ws.cand_len[at] = s_len[i];
+                ws.cand_id[at] = c_id[i];
+                ws.cand_slot[at] = c_slot[i];
+            }
+        }
+    }
     __syncthreads();
     if (tid == 0 && s_cnt) {
         atomicAdd((unsigned long long *)&st->evicted_tokens, s_tok);
@@ -1988,8 +2077,9 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
             const int32_t id = __hip_atomic_load(&ws.cand_id[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int32_t len = __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const int32_t slot = __hip_atomic_load(&ws.cand_slot[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (key <= cut) evict_remove_node(tv, st, id, len, slot, &s_tok, &s_cnt);
+            if (key <= cut) removal_push(tv, st, rl, id, len, slot, &s_tok, &s_cnt);
         }
+        removal_flush(tv, st, rl, tid, 256);
     }
     __syncthreads();
     if (tid == 0) {
@@ -2000,6 +2090,37 @@ __global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, 
         st->evicted_nodes = ev_cnt;
         evict_apply_publish(tv, st, ev_tok, ev_cnt);
     }
+}
+__global__ __launch_bounds__(256) void k_evict_gather(TreeView tv, CommitWs ws, int n_hist_pass, int shift, int depth_bits) {
+    evict_gather_body(tv, ws, n_hist_pass, shift, depth_bits);
+}
+
+// The whole commit of at most one prompt into a small tree (no more nodes than the eviction's sorting
+// pass holds) in one launch of one workgroup: plan and tail copy, the insertion (first wavefront),
+// the tick walk and the publishing, the eviction, the end-of-commit maintenance and the counters, one
+// after the other with a workgroup barrier between them.  This is the shape of a scheduler that
+// serves one query per step (Def. 2 as it stands): five dependent launches of a few microseconds
+// each become one.
+__global__ __launch_bounds__(kFusedThreads) void k_commit_one(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+                                                              const int32_t *__restrict__ n_selected, int32_t batch_cap,
+                                                              CommitWs ws, const int32_t *__restrict__ hint_len,
+                                                              const int32_t *__restrict__ hint_node, int64_t budget,
+                                                              int64_t protect, int tick_bits, int final_shift,
+                                                              int depth_bits, int may_evict,
+                                                              kLPM_stats *__restrict__ stats_out) {
+    plan_copy_body(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+    __threadfence();
+    __syncthreads();
+    if (batch_cap > 0 && threadIdx.x < kWave) structure_body(tv, q, batch_idx, ws);
+    __threadfence();
+    __syncthreads();
+    ticks_body(tv, ws, budget, protect, tick_bits, 0, may_evict);
+    __threadfence();
+    __syncthreads();
+    if (may_evict) evict_gather_body(tv, ws, 0, final_shift, depth_bits);
+    __threadfence();
+    __syncthreads();
+    end_commit_small_body<kFusedThreads>(tv, stats_out);
 }
 
 int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, const int32_t *n_selected,
@@ -2027,6 +2148,15 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         int rc = launch_match(tv, q, batch_idx, n_selected, batch_cap, 1, ws.bm_len, ws.bm_node, stream);
         if (rc) return rc;
     }
+    // Every live edge sits in the active half of the token pool, so a budget of at least that half
+    // can never be exceeded: the eviction kernels (no-ops that still cost a launch each) are left out.
+    const bool may_evict = budget < tv.pool_half;
+    if (tiny && batch_cap <= 1) {
+        hipLaunchKernelGGL(k_commit_one, dim3(1), dim3(kFusedThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap, ws,
+                           hint_len, hint_node, budget, protect, tick_bits, final_shift, t->depth_bits, may_evict ? 1 : 0,
+                           stats_out);
+        return check_launch();
+    }
     if (batch_cap <= kFusedPlanMax) {
         hipLaunchKernelGGL(k_plan_copy, dim3(batch_cap > 0 ? batch_cap : 1), dim3(kFusedThreads), 0, stream, tv, q,
                            batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
@@ -2039,15 +2169,13 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         hipLaunchKernelGGL(k_structure_wide, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
     else if (batch_cap > 0)
         hipLaunchKernelGGL(k_structure, dim3(batch_cap), dim3(kWave), 0, stream, tv, q, batch_idx, ws);
-    // Every live edge sits in the active half of the token pool, so a budget of at least that half
-    // can never be exceeded: the eviction kernels (no-ops that still cost a launch each) are left out.
-    const bool may_evict = budget < tv.pool_half;
     hipLaunchKernelGGL(k_ticks, dim3(batch_cap > 0 ? (batch_cap + 255) / 256 : 1), dim3(256), 0, stream, tv, ws,
                        budget, protect, tick_bits, n_pass, may_evict ? 1 : 0);
     if (may_evict) {
-        // few, fat workgroups: every workgroup ends with 256 global atomics into the shared histogram
-        unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 1023) / 1024);
-        if (ge > 256u) ge = 256u;
+        // (few, fat workgroups: each ends with atomics on shared words - its histogram bins, the
+        // counter that tells the last workgroup - which are served one by one)
+        unsigned ge = (unsigned)(((int64_t)tv.max_nodes + 4095) / 4096);
+        if (ge > 128u) ge = 128u;
         for (int p = 0; p < n_pass; ++p) {
             // the first digit takes what the others leave over, so that the last one ends at final_shift
             const int shift = final_shift + kEvictDigitBits * (n_pass - 1 - p);
