@@ -1275,12 +1275,14 @@ def test_groups_larger_than_a_wavefront():
         _check_step(s, ref, q2, tail, 1, n // 2, 0, 1 << 40, fifo=True)
 
 
-def test_batches_that_share_new_prefixes_at_several_levels():
+@pytest.mark.parametrize("n_prompts,batch", [(900, 450), (3000, 1500)])
+def test_batches_that_share_new_prefixes_at_several_levels(n_prompts, batch):
     """Admitted prompts of the shape prefix + first c tokens of a donor string + own tail, several per
     donor with different c, some equal, some a prefix of another: behind the place where they leave
     the old tree they share new prefixes of different lengths, level below level.  The cached prompt
     of a prefix either continues it (the batch stops inside that edge, at the prefix end and at
-    other depths) or ends with it (the batch stops at a node boundary)."""
+    other depths) or ends with it (the batch stops at a node boundary).  Batches of up to 1,024
+    prompts and larger ones take different structure passes."""
     rng = np.random.default_rng(97)
     n_pref = 12
     prefixes = [rng.integers(0, 50, size=int(rng.integers(40, 300))).tolist() for _ in range(n_pref)]
@@ -1290,7 +1292,7 @@ def test_batches_that_share_new_prefixes_at_several_levels():
     cache = W.generators._from_lists(cached, list(range(n_pref)))
     donors = [[rng.integers(60, 64, size=200).tolist() for _ in range(3)] for _ in range(n_pref)]
     lists = []
-    for _ in range(900):
+    for _ in range(n_prompts):
         g = int(rng.integers(0, n_pref))
         kind = rng.random()
         if kind < 0.15:   # stops somewhere inside the prefix (or the cached continuation)
@@ -1302,14 +1304,14 @@ def test_batches_that_share_new_prefixes_at_several_levels():
         own = rng.integers(80, 83, size=int(rng.choice([0, 0, 1, 3, 40]))).tolist()
         lists.append(prefixes[g] + d[:c] + own)
     hq = W.generators._from_lists(lists, list(range(len(lists))))
-    w = W.Workload("levels", cache, hq, 3, 450, 1 << 40)
-    s, ref, q = _setup(w, max_batch=450, extra_prompts=len(lists))
-    ph = _check_step(s, ref, q, hq, 3, 450, 0, 1 << 40, fifo=True)
+    w = W.Workload("levels", cache, hq, 3, batch, 1 << 40)
+    s, ref, q = _setup(w, max_batch=batch, extra_prompts=len(lists))
+    ph = _check_step(s, ref, q, hq, 3, batch, 0, 1 << 40, fifo=True)
     rest = W.take_prompts(hq, np.setdiff1d(np.arange(hq.n), s.batch()))
     q2 = K.DeviceQueries.from_host(rest, "cuda:0")
-    ph = _check_step(s, ref, q2, rest, 3, 450, ph, 1 << 40, fifo=True)
+    ph = _check_step(s, ref, q2, rest, 3, batch, ph, 1 << 40, fifo=True)
     # once more under a budget that evicts part of what the two batches built
-    _check_step(s, ref, q, hq, K_INF, 300, ph, ref.total_tokens // 2, fifo=True)
+    _check_step(s, ref, q, hq, K_INF, batch * 2 // 3, ph, ref.total_tokens // 2, fifo=True)
 
 
 def test_largest_batch_and_very_long_prompts():
