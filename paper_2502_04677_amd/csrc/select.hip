@@ -473,6 +473,131 @@ __device__ __forceinline__ void two_cursor_walk(const Acc &acc, int32_t n_valid,
     }
 }
 
+// ---- the same walk by a whole workgroup ----
+// Slot j of the batch is an oldest-first slot iff (phase + j) mod k = 0.  Were no query within reach of
+// both cursors, the t-th oldest-first slot would take A[t] and the u-th longest-match slot L[u], all
+// at once.  A query that both cursors can reach (a "dual": position i in A and p in L, both inside the
+// stretches the cursors can cover) goes to whichever cursor arrives first and is stepped over by the
+// other; every position behind a stepped-over one moves one slot forward.  Duals are few when the queue
+// is much longer than the batch, and their fates are settled one by one in order of time: with the fates
+// settled so far, a dual's arrival times are upper bounds (more may still be stepped over before it),
+// and the earliest of all those bounds is exact - everything stepped over before that moment is already
+// settled.  More than 64 duals: the one-wavefront walk does the batch instead.
+struct WalkSlots {
+    uint32_t k, km1, r0;  // r0: the first oldest-first slot
+    __device__ __forceinline__ uint64_t slot_a(uint32_t t) const { return (uint64_t)r0 + (uint64_t)t * k; }
+    __device__ __forceinline__ uint64_t slot_l(uint32_t u) const {
+        if (u < r0) return u;
+        const uint32_t v = u - r0;
+        const uint32_t c = v / km1;
+        return (uint64_t)r0 + (uint64_t)c * k + 1u + (uint64_t)(v - c * km1);
+    }
+};
+
+constexpr int kWalkDuals = 64;
+constexpr int kWalkScratch = 8 + 4 * kWalkDuals;  // words of LDS the workgroup walk needs
+
+// Every thread of the workgroup calls it (behind a barrier after the writes acc reads); same arguments
+// and result as two_cursor_walk.
+template <class Acc, int THREADS>
+__device__ __forceinline__ void two_cursor_block(const Acc &acc, int32_t n_valid, int32_t nb, uint32_t k, uint32_t phase,
+                                                 int32_t *__restrict__ batch_idx, int tid, int32_t *s_w) {
+    if (k == 1u) {
+        for (int32_t t = tid; t < nb; t += THREADS) batch_idx[t] = (int32_t)acc.a_elem(t);
+        return;
+    }
+    const int lane = tid & (kWave - 1);
+    const WalkSlots ws{k, k - 1u, (k - phase) % k};
+    const int32_t cnt_a = (uint32_t)nb > ws.r0 ? (int32_t)(((uint64_t)((uint32_t)nb - ws.r0) + k - 1u) / k) : 0;
+    const int32_t cnt_l = nb - cnt_a;
+    int32_t *du_i = s_w + 8, *du_p = du_i + kWalkDuals, *skip_a = du_p + kWalkDuals, *skip_l = skip_a + kWalkDuals;
+    if (tid < 8) s_w[tid] = 0;
+    __syncthreads();
+    // queries among the first nb of both orders
+    int32_t mine = 0;
+    for (int32_t i = tid; i < nb; i += THREADS) mine += acc.a_in_l(i) < (uint32_t)nb ? 1 : 0;
+    mine = wave_sum(mine);
+    if (lane == 0 && mine) atomicAdd(&s_w[0], mine);
+    __syncthreads();
+    const int32_t n_dual = s_w[0];
+    // ... and inside the stretch either cursor can cover (its slots plus what it may step over)
+    for (int32_t i = tid; i < nb; i += THREADS) {
+        const uint32_t p = acc.a_in_l(i);
+        if (p < (uint32_t)nb && i < cnt_a + n_dual && (int32_t)p < cnt_l + n_dual) {
+            const int32_t at = atomicAdd(&s_w[1], 1);
+            if (at < kWalkDuals) {
+                du_i[at] = i;
+                du_p[at] = (int32_t)p;
+            }
+        }
+    }
+    __syncthreads();
+    const int32_t n_both = s_w[1];
+    if (n_both > kWalkDuals) {
+        if (tid < kWave) two_cursor_walk(acc, n_valid, nb, k, phase, batch_idx, tid);
+        return;
+    }
+    if (n_both > 0 && tid < kWave) {
+        const int32_t di = lane < n_both ? du_i[lane] : 0, dp = lane < n_both ? du_p[lane] : 0;
+        uint64_t i_less = 0, p_less = 0;
+        for (int r = 0; r < n_both; ++r) {
+            const int32_t oi = __shfl(di, r), op = __shfl(dp, r);
+            if (oi < di) i_less |= 1ull << r;
+            if (op < dp) p_less |= 1ull << r;
+        }
+        uint64_t und = n_both == 64 ? ~0ull : ((1ull << n_both) - 1ull), to_a = 0, to_l = 0;
+        while (und) {
+            const uint32_t st_a = (uint32_t)__popcll(to_l & i_less), st_l = (uint32_t)__popcll(to_a & p_less);
+            const uint64_t ta = ws.slot_a((uint32_t)di - st_a), tl = ws.slot_l((uint32_t)dp - st_l);
+            const uint64_t t64 = ta < tl ? ta : tl;
+            const uint32_t t = ((und >> lane) & 1ull) ? (t64 < 0xFFFFFFFFull ? (uint32_t)t64 : 0xFFFFFFFFu) : 0xFFFFFFFFu;
+            uint32_t tmin = t;
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)tmin, d);
+                tmin = o < tmin ? o : tmin;
+            }
+            if (tmin >= (uint32_t)nb) break;  // nobody else is reached inside the batch
+            const int who = (int)__builtin_ctzll(__ballot(t == tmin));
+            if (__shfl((int)(ta < tl), who)) to_a |= 1ull << who; else to_l |= 1ull << who;
+            und &= ~(1ull << who);
+        }
+        const uint64_t below = (1ull << lane) - 1ull;
+        if ((to_l >> lane) & 1ull) skip_a[__popcll(to_l & below)] = di;
+        if ((to_a >> lane) & 1ull) skip_l[__popcll(to_a & below)] = dp;
+        if (lane == 0) {
+            s_w[2] = (int32_t)__popcll(to_l);
+            s_w[3] = (int32_t)__popcll(to_a);
+        }
+    }
+    __syncthreads();
+    const int32_t n_sa = s_w[2], n_sl = s_w[3];
+    for (int32_t r = tid; r < nb; r += THREADS) {
+        if (r < cnt_a + n_sa) {
+            int32_t before = 0;
+            bool skipped = false;
+            for (int q = 0; q < n_sa; ++q) {
+                const int32_t v = skip_a[q];
+                before += v < r ? 1 : 0;
+                skipped |= v == r;
+            }
+            const uint64_t slot = ws.slot_a((uint32_t)(r - before));
+            if (!skipped && slot < (uint64_t)nb) batch_idx[slot] = (int32_t)acc.a_elem(r);
+        }
+        if (r < cnt_l + n_sl) {
+            int32_t before = 0;
+            bool skipped = false;
+            for (int q = 0; q < n_sl; ++q) {
+                const int32_t v = skip_l[q];
+                before += v < r ? 1 : 0;
+                skipped |= v == r;
+            }
+            const uint64_t slot = ws.slot_l((uint32_t)(r - before));
+            if (!skipped && slot < (uint64_t)nb) batch_idx[slot] = (int32_t)acc.l_elem(r);
+        }
+    }
+}
+
 constexpr int kStage = 4096;  // entries of each order staged in LDS
 
 struct StagedAcc {
@@ -554,6 +679,7 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
     __shared__ uint64_t cand[kFifoMaxBatch];
     __shared__ uint32_t l_elem[kFifoMaxBatch];
     __shared__ uint32_t a_in_l[kFifoMaxBatch];
+    __shared__ int32_t s_walk[kWalkScratch];
     __shared__ int32_t sbuf[kFifoThreads];
     __shared__ int32_t s_flag, s_max, s_bin, s_above, s_count;
     const int tid = threadIdx.x;
@@ -766,19 +892,20 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         if (e < (uint32_t)nb) a_in_l[e] = (uint32_t)p;  // the e-th oldest query sits at position p of L
     }
     __syncthreads();
-    if (tid >= kWave) return;
     FifoAcc acc{l_elem, a_in_l};
-    two_cursor_walk(acc, nb, nb, k, phase, batch_idx, tid);
+    two_cursor_block<FifoAcc, kFifoThreads>(acc, nb, nb, k, phase, batch_idx, tid, s_walk);
 }
 
 // ---- the same selection for long arrival-ordered queues: short multi-workgroup kernels ----
 // One compute unit sweeping a 65,536-entry queue is bound by its own LDS-atomic and load rates, so
 // long queues are histogrammed, counted and gathered by many workgroups (1,024 entries each) and only
 // the final sort + walk over the nb winners runs in one workgroup.
-constexpr int kFqThreads = 1024;    // (one entry per thread: what a workgroup spends its time on is the bins)
-constexpr int kFqTile = 1024;       // queue entries per workgroup
+constexpr int kFqThreads = 1024;
+constexpr int kFqMinTile = 4096;    // queue entries per workgroup, at least
+constexpr int kFqMaxWg = 32;        // workgroups of the sweeps, at most (each owns one row of suffix counts)
 constexpr int kFqLevelBits = 14;    // bits of match length resolved per histogram kernel (prompts of up to 16,383 tokens: one level)
 constexpr int kFqBins = 1 << kFqLevelBits;
+constexpr int kFqRow = kFqBins + 64;   // words per row of suffix counts (bins 0 .. nbins, the last one zero)
 constexpr int kFqMaxLevels = 5;     // 31 bits of score (+ 32 bits of tie key) at most
 constexpr int kFqSingleBlockN = 8192;  // shorter queues are cheaper in the single-workgroup kernel
 
@@ -808,243 +935,255 @@ struct FqKey<true> {
     }
 };
 
-struct FqMeta {        // zeroed before every call
-    uint64_t fixed_hi; // decided high bits of the nb-th largest goodness
-    int32_t violated;  // arrival order broken, or a score above the caller's bound
-    int32_t need;      // winners still to be found among the entries that share fixed_hi
-    int32_t done[kFqMaxLevels + 1];  // finished workgroups per kernel
+// Nothing in the workspace has to hold a particular value when a selection starts, and no two
+// workgroups ever add into the same word: every workgroup owns one row of suffix counts (entries of
+// its stretch of the queue whose digit is >= bin), one state record and one flag.  The digit of the
+// nb-th largest goodness at a level is the largest bin whose column sum over the rows reaches the
+// number still needed; every workgroup finds it for itself at the start of the next kernel (two
+// rounds of independent loads), so there is no shared histogram to clear, no atomic on a shared
+// bin and no "last workgroup" between the levels.
+struct FqWgState {
+    uint64_t fixed_hi;  // digits decided before the level whose rows are current (written from level 1 on)
+    int32_t need;       // winners still to be found among the entries that share fixed_hi
+    int32_t gt;         // this workgroup's entries above fixed_hi at the levels already closed
+    int32_t viol;       // level 0: arrival order broken in this stretch, or a score above the caller's bound
+    int32_t flag;       // gather kernel: this workgroup's winners are written (cleared by the histogram kernels)
+    int32_t pad[2];
 };
 
 struct FqWs {
-    FqMeta *meta;
-    uint32_t *hist;      // [kFqMaxLevels][kFqBins]
-    int32_t *blockcnt;   // [n_blocks][2]: entries above g*, entries equal to g*
+    FqWgState *wg;       // [kFqMaxWg]
+    uint32_t *rows[2];   // [n_wg][kFqRow] suffix counts, by parity of the level
+    uint32_t *coarse[2]; // [n_wg][kFqThreads] every per-th suffix count of a row (per = ceil(nbins / 1024)), side by side
     uint64_t *cand;      // [kFifoMaxBatch] winners as inverted goodness (no tie keys: with the index below it)
     uint32_t *cand_idx;  // [kFifoMaxBatch] with tie keys: the winners' indices
 };
 
-__device__ __forceinline__ bool fq_last_block(int32_t *counter) {
-    __shared__ int s_last;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __threadfence();
-        s_last = (atomicAdd(counter, 1) == (int)gridDim.x - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    if (s_last) __threadfence();
-    return s_last != 0;
+struct FqDigit {
+    int32_t digit;  // largest bin whose suffix count over all rows is >= need
+    int32_t above;  // entries in the bins above it
+    int32_t base;   // first bin of the second round
+};
+// After fq_search, row g's suffix counts at the bins base + q (q = 0 .. per) of the second round sit at
+// s_a[kFqFine + 32 q + g] (until s_a is written again): the counts at the digit and above it need no
+// further load.
+constexpr int kFqFine = 64;
+__device__ __forceinline__ int32_t fq_fine(const int32_t *s_a, const FqDigit &d, int off, int g) {
+    return s_a[kFqFine + 32 * (d.digit - d.base + off) + g];
 }
 
-// Histogram of one digit (up to 14 bits) of the goodness values that share the digits fixed so far; level 0
-// also checks the arrival order.  The last workgroup to finish fixes the digit of the nb-th largest.
+// Every thread of the workgroup calls it (THREADS = kFqThreads); s_a holds kFqThreads + 1 words, s_b 32.
+// Column sums of suffix counts fall from bin to bin, so the digit lies behind the last of 1,024
+// evenly spaced probes that still reaches `need`; a second round looks at the bins between that
+// probe and the next.
+__device__ __forceinline__ FqDigit fq_search(const uint32_t *__restrict__ rows, const uint32_t *__restrict__ coarse,
+                                            int n_wg, int nbins, int32_t need, int32_t *s_a, int32_t *s_b, int tid) {
+    const int per = (nbins + kFqThreads - 1) / kFqThreads;  // <= 16
+    const int p = tid * per;
+    int32_t s = -1;
+    if (p < nbins) {
+        // (all loads of a chunk are issued before the first is added)
+        s = 0;
+        for (int g0 = 0; g0 < n_wg; g0 += 16) {
+            uint32_t v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = (g0 + u < n_wg) ? coarse[(size_t)(g0 + u) * kFqThreads + tid] : 0u;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) s += (int32_t)v[u];
+        }
+    }
+    __syncthreads();  // (the arrays may still be read from an earlier call)
+    s_a[tid] = s;
+    if (tid == 0) {
+        s_a[kFqThreads] = -1;
+        s_b[0] = 0;
+        s_b[1] = 0;
+        s_b[2] = 0;
+    }
+    __syncthreads();
+    if (s >= need && s_a[tid + 1] < need) s_b[0] = p;  // one thread: the sums fall and the first reaches need
+    __syncthreads();
+    const int base = s_b[0];
+    __syncthreads();
+    // the bins base .. base + per: one load per thread (bin = tid / 32, row = tid mod 32), summed in LDS
+    if (tid <= per) s_a[tid] = 0;
+    __syncthreads();
+    {
+        const int q = tid >> 5, g = tid & 31;
+        static_assert(kFqMaxWg <= 32 && (kFqBins / kFqThreads + 1) * 32 <= kFqThreads, "one load per thread");
+        static_assert(kFqFine + 32 * (kFqBins / kFqThreads + 1) <= kFqThreads, "room for the second round's counts");
+        if (q <= per) {
+            uint32_t v = 0;
+            if (g < n_wg && base + q <= nbins) v = rows[(size_t)g * kFqRow + base + q];  // (bin nbins holds zeros)
+            if (v) atomicAdd(&s_a[q], (int32_t)v);
+            s_a[kFqFine + 32 * q + g] = (int32_t)v;
+        }
+    }
+    __syncthreads();
+    if (tid < per && base + tid < nbins && s_a[tid] >= need && s_a[tid + 1] < need) {
+        s_b[1] = base + tid;
+        s_b[2] = s_a[tid + 1];
+    }
+    __syncthreads();
+    FqDigit d{s_b[1], s_b[2], base};
+    if (d.digit < base) d.digit = base;  // (only when no bin qualified: rows of a refused call)
+    return d;
+}
+
+// The state a kernel starts from: after one level nothing has been decided yet.
+__device__ __forceinline__ void fq_prev_state(const FqWs &ws, int levels_done, int32_t nb, uint64_t &fixed_hi,
+                                              int32_t &need, int32_t &gt) {
+    fixed_hi = 0;
+    need = nb;
+    gt = 0;
+    if (levels_done >= 2) {
+        const FqWgState *st = &ws.wg[blockIdx.x];
+        fixed_hi = st->fixed_hi;
+        need = st->need;
+        gt = st->gt;
+    }
+}
+
+// Suffix counts of one digit (up to 14 bits) of the goodness values that share the digits fixed so far, one
+// row per workgroup; level 0 also checks the arrival order and the caller's bound on the scores.
+// `tile` = queue entries per workgroup (a multiple of the workgroup size), `nbins` = bins of this
+// level, `prev_nbins` / `prev_width` = those of the level before.
 template <bool TIE>
 __global__ __launch_bounds__(kFqThreads) void k_fq_hist(const uint64_t *__restrict__ arrival, FqKey<TIE> key, LiveN nn,
                                                        int32_t batch, int32_t max_match, int level, int shift, int width,
-                                                       FqWs ws) {
+                                                       int nbins, int prev_nbins, int prev_width, int32_t tile,
+                                                       int order_only, FqWs ws) {
     using G = typename FqKey<TIE>::G;
     const int32_t n = nn.get();
-    __shared__ uint32_t h[kFqBins];
+    __shared__ uint32_t h[kFqBins + 1];
+    __shared__ int32_t s_a[kFqThreads + 1];
+    __shared__ int32_t s_b[32];
     __shared__ int32_t part[kFqThreads / kWave];
-    __shared__ int32_t s_viol, s_pick, s_above;
+    __shared__ int32_t s_viol;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    // (the top digit only reaches as far as the caller's bound on the scores does)
-    const int nbins = (level == 0 && !TIE && (max_match >> shift) + 1 < (1 << width)) ? (max_match >> shift) + 1 : (1 << width);
-    for (int i = tid; i < nbins; i += kFqThreads) h[i] = 0;
-    if (tid == 0) { s_viol = 0; s_pick = 0; s_above = 0; }
-    __syncthreads();
-    const G fixed_hi = (level == 0) ? (G)0 : (G)ws.meta->fixed_hi;
-    const int32_t base = blockIdx.x * kFqTile;
-    bool viol = false;
-#pragma unroll
-    for (int r = 0; r < kFqTile / kFqThreads; ++r) {
-        int32_t i = base + r * kFqThreads + tid;
-        bool in = i < n;
-        int32_t m = 0;
-        const G g = in ? key.at(i, m) : (G)0;
-        if (level == 0 && in) {
-            viol |= m > max_match;
-            viol |= (i + 1 < n) && (arrival[i] > arrival[i + 1]);
+    const int n_wg = (int)gridDim.x, b = (int)blockIdx.x;
+    const int32_t nb = batch < n ? batch : n;
+    if (tid == 0) {
+        s_viol = 0;
+        ws.wg[b].flag = 0;
+    }
+    G fixed_hi = 0;
+    if (level > 0) {
+        if (nb <= 0) return;  // (an empty queue: nothing is looked at by the kernels behind this one)
+        uint64_t f;
+        int32_t need, gt;
+        fq_prev_state(ws, level, nb, f, need, gt);
+        const uint32_t *prev = ws.rows[(level - 1) & 1];
+        const FqDigit d = fq_search(prev, ws.coarse[(level - 1) & 1], n_wg, prev_nbins, need, s_a, s_b, tid);
+        f = (f << prev_width) | (uint64_t)(uint32_t)d.digit;
+        fixed_hi = (G)f;
+        if (tid == 0) {
+            FqWgState *st = &ws.wg[b];
+            st->fixed_hi = f;
+            st->need = need - d.above;
+            st->gt = gt + fq_fine(s_a, d, 1, b);
         }
-        in = in && (level == 0 || (g >> (shift + width)) == fixed_hi);  // (level > 0: shift + width < bits of G)
-        int32_t bin = (int32_t)((g >> shift) & (G)((1 << width) - 1));
-        // lanes that share the first active lane's bin are added once (scores cluster and same-address
-        // LDS atomics serialise)
-        uint64_t act = __ballot(in);
-        if (act) {
-            int32_t lead = __shfl(bin, (int)__builtin_ctzll(act));
-            uint64_t same = __ballot(in && bin == lead);
-            if (in && bin == lead) {
-                if (lane == (int)__builtin_ctzll(same)) atomicAdd(&h[bin], (uint32_t)__popcll(same));
-            } else if (in) {
-                atomicAdd(&h[bin], 1u);
+    }
+    for (int i = tid; i <= nbins; i += kFqThreads) h[i] = 0;
+    __syncthreads();
+    const int32_t base = b * tile;
+    bool viol = false;
+    constexpr int kRows = 4;  // rows of the stretch whose loads are issued together
+    for (int32_t r0 = 0; r0 < tile; r0 += kRows * kFqThreads) {
+        if (base + r0 >= n) break;  // (uniform)
+        G gv[kRows];
+        int32_t mv[kRows];
+        uint64_t a0[kRows], a1[kRows];
+#pragma unroll
+        for (int u = 0; u < kRows; ++u) {
+            const int32_t i = base + r0 + u * kFqThreads + tid;
+            const bool in = r0 + u * kFqThreads < tile && i < n;
+            mv[u] = 0;
+            gv[u] = in ? key.at(i, mv[u]) : (G)0;
+            a0[u] = (level == 0 && in) ? arrival[i] : 0ull;
+            a1[u] = (level == 0 && in && i + 1 < n) ? arrival[i + 1] : ~0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < kRows; ++u) {
+            const int32_t i = base + r0 + u * kFqThreads + tid;
+            bool in = r0 + u * kFqThreads < tile && i < n;
+            const G g = gv[u];
+            if (level == 0 && in) {
+                viol |= mv[u] > max_match;
+                viol |= a0[u] > a1[u];
+            }
+            if (order_only) continue;
+            in = in && (level == 0 || (g >> (shift + width)) == fixed_hi);  // (level > 0: shift + width < bits of G)
+            const int32_t bin = (int32_t)((g >> shift) & (G)((1 << width) - 1));
+            // lanes that share the first active lane's bin are added once (scores cluster and same-address
+            // LDS atomics serialise)
+            const uint64_t act = __ballot(in);
+            if (act) {
+                const int32_t lead = __shfl(bin, (int)__builtin_ctzll(act));
+                const uint64_t same = __ballot(in && bin == lead);
+                if (in && bin == lead) {
+                    if (lane == (int)__builtin_ctzll(same)) atomicAdd(&h[bin], (uint32_t)__popcll(same));
+                } else if (in) {
+                    atomicAdd(&h[bin], 1u);
+                }
             }
         }
     }
-    if (viol) atomicOr(&s_viol, 1);
-    __syncthreads();
-    if (tid == 0 && s_viol) atomicOr(&ws.meta->violated, 1);
-    uint32_t *gh = ws.hist + (size_t)level * kFqBins;
-    for (int i = tid; i < nbins; i += kFqThreads) {
-        uint32_t c = h[i];
-        if (c) atomicAdd(&gh[i], c);
+    if (level == 0) {
+        if (viol) atomicOr(&s_viol, 1);
+        __syncthreads();
+        if (tid == 0) ws.wg[b].viol = s_viol;
     }
-    if (!fq_last_block(&ws.meta->done[level])) return;
-    // suffix counts over the bins, top down: thread t owns a contiguous run of bins counted from the top
+    if (order_only) return;
+    __syncthreads();
+    // suffix counts in place: thread t owns a run of bins counted from the top
     const int per = (nbins + kFqThreads - 1) / kFqThreads;
-    const int32_t nb = batch < n ? batch : n;
-    const int32_t need = (level == 0) ? nb : ws.meta->need;
-    // (after the fence of fq_last_block plain loads see the other workgroups' atomics)
     constexpr int kMaxPer = kFqBins / kFqThreads;
     int32_t c[kMaxPer];
     int32_t mine = 0;
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) {
-        int b = nbins - 1 - (tid * per + q);
-        c[q] = (q < per && b >= 0) ? (int32_t)gh[b] : 0;
+        const int bin = nbins - 1 - (tid * per + q);
+        c[q] = (q < per && bin >= 0) ? (int32_t)h[bin] : 0;
         mine += c[q];
     }
     int32_t all;
     int32_t run = block_inclusive_scan<int32_t, kFqThreads>(mine, part, tid, all) - mine;  // entries in higher bins
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) {
-        int b = nbins - 1 - (tid * per + q);
-        if (q < per && b >= 0) {
-            if (run < need && run + c[q] >= need) { s_pick = b; s_above = run; }
+        const int bin = nbins - 1 - (tid * per + q);
+        if (q < per && bin >= 0) {
             run += c[q];
+            h[bin] = (uint32_t)run;
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        ws.meta->fixed_hi = ((uint64_t)fixed_hi << width) | (uint64_t)(uint32_t)s_pick;
-        ws.meta->need = need - s_above;
-    }
+    uint32_t *row = ws.rows[level & 1] + (size_t)b * kFqRow;
+    for (int i = tid; i <= nbins; i += kFqThreads) row[i] = h[i];
+    ws.coarse[level & 1][(size_t)b * kFqThreads + tid] = (tid * per < nbins) ? h[tid * per] : 0u;
 }
 
-// Per workgroup: how many of its entries lie above g* and how many equal it.
-template <bool TIE>
-__global__ __launch_bounds__(kFqThreads) void k_fq_count(FqKey<TIE> key, LiveN nn, FqWs ws) {
-    using G = typename FqKey<TIE>::G;
-    const int32_t n = nn.get();
-    __shared__ int32_t s_gt, s_eq;
-    const int tid = threadIdx.x;
-    if (tid == 0) { s_gt = 0; s_eq = 0; }
-    __syncthreads();
-    const G g_star = (G)ws.meta->fixed_hi;
-    const int32_t base = blockIdx.x * kFqTile;
-    int32_t gt = 0, eq = 0;
-#pragma unroll
-    for (int r = 0; r < kFqTile / kFqThreads; ++r) {
-        int32_t i = base + r * kFqThreads + tid;
-        int32_t m;
-        const bool in = i < n;
-        const G g = in ? key.at(i, m) : (G)0;
-        gt += (int32_t)__popcll(__ballot(in && g > g_star));
-        eq += (int32_t)__popcll(__ballot(in && g == g_star));
-    }
-    if ((tid & (kWave - 1)) == 0) { atomicAdd(&s_gt, gt); atomicAdd(&s_eq, eq); }
-    __syncthreads();
-    if (tid == 0) { ws.blockcnt[2 * blockIdx.x] = s_gt; ws.blockcnt[2 * blockIdx.x + 1] = s_eq; }
-}
+struct FqLds {
+    uint64_t *cand;    // [kFifoMaxBatch]
+    uint32_t *l_elem;  // [kFifoMaxBatch]
+    uint32_t *a_in_l;  // [kFifoMaxBatch]
+    int32_t *walk;     // [kWalkScratch]
+};
 
-// Winners = every entry above g* and the first `need` entries (by index) equal to g*; written in
-// index order at positions given by prefix counts (no atomics).
+// The longest-match order of the nb winners - sorted here by (-score, [tie key,] index) in LDS, or, with
+// `placed`, read as the gather kernel placed it - and the walk over both orders.  Run by one whole
+// workgroup once every winner is written.
 template <bool TIE>
-__global__ __launch_bounds__(kFqThreads) void k_fq_gather(FqKey<TIE> key, LiveN nn, FqWs ws) {
-    using G = typename FqKey<TIE>::G;
-    const int32_t n = nn.get();
-    __shared__ int32_t part[kFqThreads / kWave];
-    __shared__ int32_t s_rank, s_out;
-    __shared__ int32_t w_eq[kFqThreads / kWave], w_win[kFqThreads / kWave];
+__device__ __forceinline__ void fq_finish(int32_t n, uint32_t k, uint32_t phase_in, int32_t violated, int32_t batch,
+                                          bool placed, const FqWs &ws, const FqLds &lds,
+                                          uint32_t *__restrict__ phase_inout, int32_t *__restrict__ batch_idx,
+                                          int32_t *__restrict__ n_selected) {
+    uint64_t *cand = lds.cand;
+    uint32_t *l_elem = lds.l_elem, *a_in_l = lds.a_in_l;
+    int32_t *s_walk = lds.walk;
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wv = tid / kWave;
-    const G g_star = (G)ws.meta->fixed_hi;
-    const int32_t need = ws.meta->need;
-    // entries equal to g* and winners in the workgroups before this one
-    {
-        int32_t eq_b = 0, gt_b = 0;
-        for (int32_t b = tid; b < (int32_t)blockIdx.x; b += kFqThreads) {
-            gt_b += ws.blockcnt[2 * b];
-            eq_b += ws.blockcnt[2 * b + 1];
-        }
-        int32_t eq_all, gt_all;
-        block_inclusive_scan<int32_t, kFqThreads>(eq_b, part, tid, eq_all);
-        block_inclusive_scan<int32_t, kFqThreads>(gt_b, part, tid, gt_all);
-        if (tid == 0) {
-            s_rank = eq_all;
-            s_out = gt_all + (eq_all < need ? eq_all : need);
-        }
-        __syncthreads();
-    }
-    int32_t rank = s_rank, out = s_out;
-    const int32_t base = blockIdx.x * kFqTile;
-    for (int r = 0; r < kFqTile / kFqThreads; ++r) {
-        int32_t i = base + r * kFqThreads + tid;
-        bool in = i < n;
-        int32_t m = 0;
-        const G g = in ? key.at(i, m) : (G)0;
-        bool is_eq = in && g == g_star;
-        uint64_t eqmask = __ballot(is_eq);
-        // this row: counts of the wavefronts before mine
-        __syncthreads();
-        if (lane == 0) w_eq[wv] = (int32_t)__popcll(eqmask);
-        __syncthreads();
-        int32_t eq_before = 0, eq_row = 0;
-        for (int w = 0; w < kFqThreads / kWave; ++w) {
-            if (w < wv) eq_before += w_eq[w];
-            eq_row += w_eq[w];
-        }
-        int32_t my_rank = rank + eq_before + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
-        bool win = in && (g > g_star || (is_eq && my_rank < need));
-        uint64_t wmask = __ballot(win);
-        __syncthreads();
-        if (lane == 0) w_win[wv] = (int32_t)__popcll(wmask);
-        __syncthreads();
-        int32_t win_before = 0, win_row = 0;
-        for (int w = 0; w < kFqThreads / kWave; ++w) {
-            if (w < wv) win_before += w_win[w];
-            win_row += w_win[w];
-        }
-        if (win) {
-            int32_t at = out + win_before + (int32_t)__popcll(wmask & ((1ull << lane) - 1ull));
-            if (at >= 0 && at < kFifoMaxBatch) {
-                if (TIE) {
-                    ws.cand[at] = ~(uint64_t)g;
-                    ws.cand_idx[at] = (uint32_t)i;
-                } else {
-                    ws.cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
-                }
-            }
-        }
-        rank += eq_row;
-        out += win_row;
-    }
-}
-
-// Sort the nb winners by (-score, [tie key,] index) in LDS and run the two-cursor walk.
-template <bool TIE>
-__global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, int32_t batch, FqWs ws,
-                                                            uint32_t *__restrict__ phase_inout,
-                                                            int32_t *__restrict__ batch_idx,
-                                                            int32_t *__restrict__ n_selected) {
-    __shared__ uint64_t cand[kFifoMaxBatch];
-    __shared__ uint32_t l_elem[kFifoMaxBatch];
-    __shared__ uint32_t a_in_l[kFifoMaxBatch];
-    const int tid = threadIdx.x;
-    // one round trip: the scalars, the verdict of the order check and this thread's winners (the
-    // winner arrays hold kFifoMaxBatch entries whatever nb is; what lies past nb is not used)
     constexpr int kPer = kFifoMaxBatch / kFifoThreads;
-    const int32_t n = nn.get();
-    const uint32_t k = ka.get();
-    const uint32_t phase_in = *phase_inout;
-    const int32_t violated = ws.meta->violated;
-    uint64_t own[kPer];
-    uint32_t own_idx[kPer];
-#pragma unroll
-    for (int c = 0; c < kPer; ++c) {
-        own[c] = ws.cand[tid + c * kFifoThreads];
-        own_idx[c] = TIE ? ws.cand_idx[tid + c * kFifoThreads] : 0u;
-    }
     const int32_t nb = batch < n ? batch : n;
     const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
     const uint32_t phase = lpm_only ? 0u : (phase_in % k);
@@ -1056,21 +1195,32 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
         *n_selected = nb;
         *phase_inout = lpm_only ? 0u : (uint32_t)(((uint64_t)phase + (uint64_t)nb) % k);
     }
-    int32_t np2 = 1;
-    while (np2 < nb) np2 <<= 1;
+    if (placed) {
 #pragma unroll
-    for (int c = 0; c < kPer; ++c) {
-        const int32_t i = tid + c * kFifoThreads;
-        if (i < np2) {
-            cand[i] = (i < nb) ? own[c] : ~0ull;
-            if (TIE) l_elem[i] = (i < nb) ? own_idx[c] : 0xFFFFFFFFu;  // second key word: the index
+        for (int c = 0; c < kPer; ++c) {
+            const int32_t i = tid + c * kFifoThreads;
+            if (i < nb) {
+                l_elem[i] = ws.cand_idx[i];
+                a_in_l[i] = 0xFFFFFFFFu;
+            }
         }
-    }
-    __syncthreads();
-    sort_lds<kFifoThreads, kFifoMaxBatch / kFifoThreads, TIE>(cand, l_elem, np2, tid);
-    for (int32_t p = tid; p < nb; p += kFifoThreads) {
-        if (!TIE) l_elem[p] = (uint32_t)cand[p];
-        a_in_l[p] = 0xFFFFFFFFu;
+    } else {
+        int32_t np2 = 1;
+        while (np2 < nb) np2 <<= 1;
+#pragma unroll
+        for (int c = 0; c < kPer; ++c) {
+            const int32_t i = tid + c * kFifoThreads;
+            if (i < np2) {
+                cand[i] = (i < nb) ? ws.cand[i] : ~0ull;
+                if (TIE) l_elem[i] = (i < nb) ? ws.cand_idx[i] : 0xFFFFFFFFu;  // second key word: the index
+            }
+        }
+        __syncthreads();
+        sort_lds<kFifoThreads, kFifoMaxBatch / kFifoThreads, TIE>(cand, l_elem, np2, tid);
+        for (int32_t p = tid; p < nb; p += kFifoThreads) {
+            if (!TIE) l_elem[p] = (uint32_t)cand[p];
+            a_in_l[p] = 0xFFFFFFFFu;
+        }
     }
     __syncthreads();
     if (lpm_only) {
@@ -1082,17 +1232,215 @@ __global__ __launch_bounds__(kFifoThreads) void k_fq_finish(LiveN nn, KArg ka, i
         if (e < (uint32_t)nb) a_in_l[e] = (uint32_t)p;  // the e-th oldest query sits at position p of L
     }
     __syncthreads();
-    if (tid >= kWave) return;
     FifoAcc acc{l_elem, a_in_l};
-    two_cursor_walk(acc, nb, nb, k, phase, batch_idx, tid);
+    two_cursor_block<FifoAcc, kFifoThreads>(acc, nb, nb, k, phase, batch_idx, tid, s_walk);
+}
+
+// Winners = every entry above g* and the first `need` entries (by index) equal to g*; written in index
+// order at positions given by prefix counts over the rows (no atomics).  A workgroup that finds every
+// flag set after raising its own runs the final sort and walk: the one whose flag went up last does,
+// and if two see it at once both write the same batch.
+// When one level resolved the whole score (no tie keys), the rows of suffix counts also give every
+// winner its place in the longest-match order, and the final sort is not needed: a workgroup sorts its
+// own winners (a few dozen, on registers), and the winner at place q of that list, of score m, has in
+// front of it in the whole queue the entries of score >= m of the workgroups before (their rows at m:
+// equal scores go by index), its own q, and the entries of score > m of the workgroups behind (their
+// rows at m + 1).
+template <bool TIE>
+__global__ __launch_bounds__(kFqThreads) void k_fq_gather(FqKey<TIE> key, LiveN nn, KArg ka, int32_t batch, int levels,
+                                                         int width, int nbins, int32_t tile, FqWs ws,
+                                                         uint32_t *__restrict__ phase_inout,
+                                                         int32_t *__restrict__ batch_idx,
+                                                         int32_t *__restrict__ n_selected) {
+    using G = typename FqKey<TIE>::G;
+    const int32_t n = nn.get();
+    const uint32_t k = ka.get();
+    const uint32_t phase_in = *phase_inout;  // (read by every workgroup before any flag is up, written after all are)
+    __shared__ int32_t s_a[kFqThreads + 1];
+    __shared__ int32_t s_b[32];
+    __shared__ int32_t s_rank, s_out, s_last, s_viol;
+    constexpr int kRows = 4;  // rows of the stretch handled together
+    __shared__ int32_t w_eq[kRows][kFqThreads / kWave], w_win[kRows][kFqThreads / kWave];
+    __shared__ uint64_t l_cand[kFifoMaxBatch];
+    __shared__ uint32_t l_elem[kFifoMaxBatch];
+    __shared__ uint32_t l_a_in_l[kFifoMaxBatch];
+    __shared__ int32_t l_walk[kWalkScratch];
+    const FqLds lds{l_cand, l_elem, l_a_in_l, l_walk};
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+    const int n_wg = (int)gridDim.x, b = (int)blockIdx.x;
+    const int32_t nb = batch < n ? batch : n;
+    const bool placed = !TIE && levels == 1;
+    const int32_t base = b * tile;
+    // (the first rows of the stretch are requested before the search: they do not depend on it)
+    G gv[kRows];
+    int32_t mv[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const int32_t i = base + u * kFqThreads + tid;
+        mv[u] = 0;
+        gv[u] = (u * kFqThreads < tile && i < n) ? key.at(i, mv[u]) : (G)0;
+    }
+    if (nb > 0) {
+        uint64_t f;
+        int32_t need, gt_unused;
+        fq_prev_state(ws, levels, nb, f, need, gt_unused);
+        const uint32_t *rows = ws.rows[(levels - 1) & 1];
+        const FqDigit d = fq_search(rows, ws.coarse[(levels - 1) & 1], n_wg, nbins, need, s_a, s_b, tid);
+        const G g_star = (G)((f << width) | (uint64_t)(uint32_t)d.digit);
+        need -= d.above;
+        // entries equal to g* and winners in the workgroups before this one
+        if (wv == 0) {
+            int32_t gt = 0, eq = 0;
+            if (lane < n_wg) {
+                const int32_t hi = fq_fine(s_a, d, 1, lane);
+                gt = (levels >= 2 ? ws.wg[lane].gt : 0) + hi;
+                eq = fq_fine(s_a, d, 0, lane) - hi;
+            }
+            const int32_t gt_before = wave_inclusive_scan(gt, lane) - gt;
+            const int32_t eq_before = wave_inclusive_scan(eq, lane) - eq;
+            if (lane == b) {
+                s_rank = eq_before;
+                s_out = gt_before + (eq_before < need ? eq_before : need);
+            }
+        }
+        __syncthreads();
+        int32_t rank = s_rank, out = s_out;
+        const int32_t out0 = out;
+        const uint64_t below = (1ull << lane) - 1ull;
+        for (int32_t r0 = 0; r0 < tile; r0 += kRows * kFqThreads) {
+            if (base + r0 >= n) break;  // (uniform)
+            if (r0 > 0) {
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) {
+                    const int32_t i = base + r0 + u * kFqThreads + tid;
+                    mv[u] = 0;
+                    gv[u] = (r0 + u * kFqThreads < tile && i < n) ? key.at(i, mv[u]) : (G)0;
+                }
+            }
+            bool in[kRows], is_eq[kRows];
+            uint64_t eqmask[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                in[u] = r0 + u * kFqThreads < tile && base + r0 + u * kFqThreads + tid < n;
+                is_eq[u] = in[u] && gv[u] == g_star;
+                eqmask[u] = __ballot(is_eq[u]);
+            }
+            __syncthreads();  // (the counts of the rows before are read)
+            if (lane == 0) {
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) w_eq[u][wv] = (int32_t)__popcll(eqmask[u]);
+            }
+            __syncthreads();
+            bool win[kRows];
+            uint64_t wmask[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {  // rows in turn, inside a row the wavefronts before mine
+                int32_t eq_before = 0, eq_row = 0;
+                for (int w = 0; w < kFqThreads / kWave; ++w) {
+                    const int32_t v = w_eq[u][w];
+                    if (w < wv) eq_before += v;
+                    eq_row += v;
+                }
+                const int32_t my_rank = rank + eq_before + (int32_t)__popcll(eqmask[u] & below);
+                win[u] = in[u] && (gv[u] > g_star || (is_eq[u] && my_rank < need));
+                wmask[u] = __ballot(win[u]);
+                rank += eq_row;
+            }
+            if (lane == 0) {
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) w_win[u][wv] = (int32_t)__popcll(wmask[u]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                int32_t win_before = 0, win_row = 0;
+                for (int w = 0; w < kFqThreads / kWave; ++w) {
+                    const int32_t v = w_win[u][w];
+                    if (w < wv) win_before += v;
+                    win_row += v;
+                }
+                if (win[u]) {
+                    const int32_t i = base + r0 + u * kFqThreads + tid;
+                    const int32_t at = out + win_before + (int32_t)__popcll(wmask[u] & below);
+                    if (at >= 0 && at < kFifoMaxBatch) {
+                        if (TIE) {
+                            ws.cand[at] = ~(uint64_t)gv[u];
+                            ws.cand_idx[at] = (uint32_t)i;
+                        } else if (!placed) {
+                            ws.cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)mv[u]) << 32) | (uint64_t)(uint32_t)i;
+                        } else {  // (this workgroup's list, in index order; at - out0 < nb)
+                            l_cand[at - out0] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)mv[u]) << 32) | (uint64_t)(uint32_t)i;
+                        }
+                    }
+                }
+                out += win_row;
+            }
+        }
+        if (placed) {
+            int32_t mine = out - out0;  // this workgroup's winners
+            if (mine > kFifoMaxBatch) mine = kFifoMaxBatch;
+            if (mine < 0) mine = 0;
+            int32_t np2 = 1;
+            while (np2 < mine) np2 <<= 1;
+            __syncthreads();
+            for (int32_t i = mine + tid; i < np2; i += kFqThreads) l_cand[i] = ~0ull;
+            __syncthreads();
+            sort_lds<kFqThreads, kFifoMaxBatch / kFqThreads, false>(l_cand, l_elem, np2, tid);
+            int32_t *place = (int32_t *)l_a_in_l;
+            for (int32_t q = tid; q < mine; q += kFqThreads) place[q] = q;
+            __syncthreads();
+            const int32_t pairs = mine * n_wg;
+            for (int32_t idx = tid; idx < pairs; idx += kFqThreads) {
+                const int32_t q = idx / n_wg, g = idx - q * n_wg;
+                const int32_t mm = (int32_t)(0x7FFFFFFFu - (uint32_t)(l_cand[q] >> 32)) + (g < b ? 0 : 1);
+                if (g != b && mm <= nbins) {  // (a score beyond the caller's bound has no bin; the call is refused anyway)
+                    const uint32_t v = rows[(size_t)g * kFqRow + mm];
+                    if (v) atomicAdd(&place[q], (int32_t)v);
+                }
+            }
+            __syncthreads();
+            for (int32_t q = tid; q < mine; q += kFqThreads) {
+                const int32_t at = place[q];
+                if (at >= 0 && at < kFifoMaxBatch) ws.cand_idx[at] = (uint32_t)l_cand[q];
+            }
+        }
+    }
+    // raise this workgroup's flag behind its winners, then look at everybody's
+    __syncthreads();
+    if (wv == 0) {
+        if (lane == 0) {
+            __threadfence();  // (behind the barrier: covers the whole workgroup's stores)
+            __hip_atomic_exchange(&ws.wg[b].flag, 1, __ATOMIC_SEQ_CST, __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence();
+        }
+        int32_t up = 1, v = 0;
+        if (lane < n_wg) {
+            up = __hip_atomic_load(&ws.wg[lane].flag, __ATOMIC_SEQ_CST, __HIP_MEMORY_SCOPE_AGENT);
+            v = ws.wg[lane].viol;
+        }
+        const bool all_up = __ballot(up == 0) == 0ull;
+        const bool any_viol = __ballot(v != 0) != 0ull;
+        if (lane == 0) {
+            s_last = all_up ? 1 : 0;
+            s_viol = any_viol ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    fq_finish<TIE>(n, k, phase_in, s_viol, batch, placed, ws, lds, phase_inout, batch_idx, n_selected);
 }
 
 // FCFS on an arrival-ordered queue: its first nb entries (after the order check of the histogram kernel).
-__global__ __launch_bounds__(256) void k_fq_fcfs(LiveN nn, int32_t batch, FqWs ws, uint32_t *__restrict__ phase_inout,
-                                                 int32_t *__restrict__ batch_idx, int32_t *__restrict__ n_selected) {
+__global__ __launch_bounds__(256) void k_fq_fcfs(LiveN nn, int32_t batch, int n_wg, FqWs ws,
+                                                 uint32_t *__restrict__ phase_inout, int32_t *__restrict__ batch_idx,
+                                                 int32_t *__restrict__ n_selected) {
     const int32_t n = nn.get();
     const int32_t nb = batch < n ? batch : n;
-    if (ws.meta->violated) {
+    int32_t violated = 0;
+    for (int g = 0; g < n_wg; ++g) violated |= ws.wg[g].viol;
+    if (violated) {
         if (blockIdx.x == 0 && threadIdx.x == 0) *n_selected = -1;
         return;
     }
@@ -1104,20 +1452,28 @@ __global__ __launch_bounds__(256) void k_fq_fcfs(LiveN nn, int32_t batch, FqWs w
     if (j < nb) batch_idx[j] = j;
 }
 
-// Zeroes the meta block and the histograms (a kernel rather than a memset node, so that the whole
-// selection can be captured into a HIP graph and replayed).
-__global__ __launch_bounds__(256) void k_fq_zero(uint32_t *__restrict__ p, int32_t n_words) {
-    for (int32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) p[i] = 0u;
+// Workgroups of the sweeps over a queue of n entries and the entries each of them takes.
+static void fq_grid(int32_t n, int *n_wg, int32_t *tile) {
+    int64_t g = ((int64_t)n + kFqMinTile - 1) / kFqMinTile;
+    if (g < 1) g = 1;
+    if (g > kFqMaxWg) g = kFqMaxWg;
+    int64_t t = ((int64_t)(n > 0 ? n : 1) + g - 1) / g;
+    t = (t + kFqThreads - 1) / kFqThreads * kFqThreads;
+    *n_wg = (int)g;
+    *tile = (int32_t)t;
 }
 
 static void carve_fq(FqWs &f, char *base, int32_t n, size_t *used) {
     size_t o = 0;
     auto take = [&](size_t bytes) { void *p = base ? base + o : nullptr; o += align_up(bytes, 256); return p; };
-    int32_t nblk = (n + kFqTile - 1) / kFqTile;
-    if (nblk < 1) nblk = 1;
-    f.meta = (FqMeta *)take(sizeof(FqMeta));
-    f.hist = (uint32_t *)take((size_t)kFqMaxLevels * kFqBins * 4);
-    f.blockcnt = (int32_t *)take((size_t)nblk * 8);
+    int n_wg;
+    int32_t tile;
+    fq_grid(n, &n_wg, &tile);
+    f.wg = (FqWgState *)take(sizeof(FqWgState) * kFqMaxWg);
+    f.rows[0] = (uint32_t *)take((size_t)n_wg * kFqRow * 4);
+    f.rows[1] = (uint32_t *)take((size_t)n_wg * kFqRow * 4);
+    f.coarse[0] = (uint32_t *)take((size_t)n_wg * kFqThreads * 4);
+    f.coarse[1] = (uint32_t *)take((size_t)n_wg * kFqThreads * 4);
     f.cand = (uint64_t *)take((size_t)kFifoMaxBatch * 8);
     f.cand_idx = (uint32_t *)take((size_t)kFifoMaxBatch * 4);
     *used = o;
@@ -1132,32 +1488,34 @@ static int select_fifo_long(const uint64_t *arrival, FqKey<TIE> key, LiveN nn, K
     carve_fq(f, workspace, nn.n, &used);
     const LiveN n = nn;
     const int32_t nb = batch < nn.n ? batch : nn.n;  // upper bound of the picks, sizes the FCFS launch
-    const int32_t nblk = (nn.n + kFqTile - 1) / kFqTile;
-    // meta and histograms are contiguous at the start of the workspace
-    const int32_t zero_words = (int32_t)(((char *)f.blockcnt - (char *)f.meta) / 4);
-    hipLaunchKernelGGL(k_fq_zero, dim3(32), dim3(256), 0, stream, (uint32_t *)f.meta, zero_words);
+    int n_wg;
+    int32_t tile;
+    fq_grid(nn.n, &n_wg, &tile);
     int mbits = 0;
     while (mbits < 31 && (max_match >> mbits) != 0) ++mbits;
     if (mbits == 0) mbits = 1;
     const bool fcfs = (!k.dev && k.k == 1u);  // (a k read on the device takes the general kernels)
     int shift = mbits + (TIE ? 32 : 0), level = 0;
+    int width = 0, nbins = 0, prev_width = 0, prev_nbins = 0;
     while (shift > 0 && level < kFqMaxLevels) {
-        int width = shift < kFqLevelBits ? shift : kFqLevelBits;
+        prev_width = width;
+        prev_nbins = nbins;
+        width = shift < kFqLevelBits ? shift : kFqLevelBits;
         shift -= width;
-        hipLaunchKernelGGL(k_fq_hist<TIE>, dim3(nblk), dim3(kFqThreads), 0, stream, arrival, key, n, batch, max_match,
-                           level, shift, width, f);
+        // (the top digit only reaches as far as the caller's bound on the scores does)
+        nbins = (level == 0 && !TIE && (max_match >> shift) + 1 < (1 << width)) ? (max_match >> shift) + 1 : (1 << width);
+        hipLaunchKernelGGL(k_fq_hist<TIE>, dim3(n_wg), dim3(kFqThreads), 0, stream, arrival, key, n, batch, max_match,
+                           level, shift, width, nbins, prev_nbins, prev_width, tile, fcfs ? 1 : 0, f);
         ++level;
         if (fcfs) break;  // only the order check of level 0 is needed
     }
     if (fcfs) {
-        hipLaunchKernelGGL(k_fq_fcfs, dim3((nb + 255) / 256), dim3(256), 0, stream, n, batch, f, phase_inout, batch_idx,
-                           n_selected);
+        hipLaunchKernelGGL(k_fq_fcfs, dim3((nb + 255) / 256), dim3(256), 0, stream, n, batch, n_wg, f, phase_inout,
+                           batch_idx, n_selected);
         return check_launch();
     }
-    hipLaunchKernelGGL(k_fq_count<TIE>, dim3(nblk), dim3(kFqThreads), 0, stream, key, n, f);
-    hipLaunchKernelGGL(k_fq_gather<TIE>, dim3(nblk), dim3(kFqThreads), 0, stream, key, n, f);
-    hipLaunchKernelGGL(k_fq_finish<TIE>, dim3(1), dim3(kFifoThreads), 0, stream, n, k, batch, f, phase_inout, batch_idx,
-                       n_selected);
+    hipLaunchKernelGGL(k_fq_gather<TIE>, dim3(n_wg), dim3(kFqThreads), 0, stream, key, n, k, batch, level, width, nbins,
+                       tile, f, phase_inout, batch_idx, n_selected);
     return check_launch();
 }
 

@@ -166,6 +166,8 @@ def test_select_arrival_ordered_queue_single_kernel():
             for batch in (1, 5, min(n, 1024), min(n, 4096)):
                 out = torch.full((min(batch, n),), -1, dtype=torch.int32, device="cuda:0")
                 phase.fill_(2)
+                # (nothing in the workspace has to hold a particular value when a selection starts)
+                ws[0].fill_(0xA5 if k & 1 else 0xFF) if batch == 5 else None
                 K.kLPM_select(d_arr, d_m, n, k, batch, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO)
                 idx_ref, ph_ref = oracle.select(arrival, m, k, batch, 2)
                 assert int(nsel.item()) == idx_ref.shape[0], (n, k, batch)
@@ -505,6 +507,36 @@ def test_config4_full_size_online_stream():
     stream = W.config4_stream()
     _say(f"config4 full: {stream.queries.n} queries / {stream.queries.tokens.shape[0]} tokens over {stream.steps} steps")
     _run_stream(stream, 8192, snapshot_every=100)
+
+
+@pytest.mark.parametrize("n,boost", [(9000, 0), (9000, 40), (30000, 8), (30000, 300), (70000, 0), (70000, 60)])
+def test_select_when_both_orders_reach_the_same_queries(n, boost):
+    """Alg. 1 on arrival-ordered queues in which some of the oldest queries are also among the longest
+    matches (none, a handful, more than a wavefront's worth), so that either cursor steps over what the
+    other took; every k, phase and batch size against the oracle."""
+    rng = np.random.default_rng(1000 + n + boost)
+    arrival = np.sort(rng.integers(0, n, size=n)).astype(np.uint64)
+    m = rng.integers(0, 4000, size=n).astype(np.int32)
+    m[rng.integers(0, n, size=n // 3)] = 0
+    if boost:
+        old = rng.choice(600, size=boost, replace=False)
+        m[old] = rng.integers(3000, 4200, size=boost).astype(np.int32)  # old queries with long matches
+    d_arr = torch.from_numpy(arrival.view(np.int64)).cuda()
+    d_m = torch.from_numpy(m).cuda()
+    ws_bytes = K.kLPM_select_workspace_bytes(n)
+    ws = K.alloc_aligned(ws_bytes, "cuda:0")
+    phase = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    nsel = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for k in (2, 3, 5, 8, 64, 1000):
+        for batch in (7, 512, 1024, 4096):
+            ph = int(rng.integers(0, k))
+            out = torch.full((batch,), -1, dtype=torch.int32, device="cuda:0")
+            phase.fill_(ph)
+            K.kLPM_select(d_arr, d_m, n, k, batch, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO)
+            idx_ref, ph_ref = oracle.select(arrival, m, k, batch, ph)
+            assert int(nsel.item()) == idx_ref.shape[0], (n, k, batch)
+            assert out.cpu().numpy().tolist() == idx_ref.tolist(), (n, boost, k, batch, ph)
+            assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
 
 
 # ----------------------------------------------------------------------------- device-side queue length
