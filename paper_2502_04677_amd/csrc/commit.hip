@@ -480,46 +480,77 @@ __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const 
 }
 
 // ------------------------------------------------------------------ plan and tails in one launch
-// For batches of up to kFusedPlanMax prompts the plan is not a kernel of its own: workgroup j, which
-// copies prompt j's tail, reads the whole batch's match results itself (a few KB, two round trips)
-// and derives from them everything it needs - the admission, where its tail goes (the sum of the
-// tails before it), whether the commit goes ahead - exactly as every other workgroup does from the
-// same inputs; workgroup 0 also writes the commit's scalars.  Nothing here raises or lowers a flag
-// that another workgroup of the same launch reads: the skip flag is only ever raised, and the end
-// of the previous commit has lowered it.
+// For batches of up to kFusedPlanMax prompts the plan is not a kernel of its own: a workgroup takes
+// kPlanGroup consecutive prompts of the batch, reads the whole batch's match lengths itself (a few KB,
+// two round trips) and derives from them everything it needs - the admission, where its tails go (the
+// sum of the tails before them), whether the commit goes ahead - exactly as every other workgroup
+// does from the same inputs; workgroup 0 also writes the commit's scalars.  What only concerns one
+// prompt (its span in the token array, its node, the local checks of a match handed in by the caller,
+// its reserved ids and group key) is read and checked by one lane per prompt of the workgroup that
+// owns it, while the other wavefronts already copy: the tails of a group lie side by side in the pool,
+// so the copy runs over them as over one span.  Nothing here raises or lowers a flag that another
+// workgroup of the same launch reads: the skip flag is only ever raised, and the end of the previous
+// commit has lowered it.  (Measured on batches of 1,024 prompts with 1.7M tail tokens: one prompt per
+// 256-thread workgroup, each workgroup reading everything about every prompt, 20 us; groups of 8, 4
+// and 2 prompts per 1,024-thread workgroup 18, 14 and 19 us - fewer workgroups repeat less of the plan,
+// more of them copy faster.)
 constexpr int kFusedPlanMax = 2048;
 constexpr int kFusedThreads = 256;
+constexpr int kPlanGroup = 4;
+
+// The key is absent from the child table (any lane on its own; the tree is not being modified).
+__device__ __forceinline__ bool slot_absent_lane(const TreeView &tv, uint64_t key) {
+    uint32_t h = hash_key(key) & tv.slot_mask;
+    for (uint32_t probe = 0; probe <= tv.slot_mask; ++probe) {
+        const uint64_t k = tv.slots[h].key;
+        if (k == key) return false;
+        if (k == kEmptyKey) return true;
+        h = (h + 1) & tv.slot_mask;
+    }
+    return true;
+}
+
+template <int THREADS>
 __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
-                                                             const int32_t *__restrict__ n_selected, int32_t batch_cap,
-                                                             CommitWs ws, const int32_t *__restrict__ hint_len,
-                                                             const int32_t *__restrict__ hint_node) {
-    constexpr int kPer = kFusedPlanMax / kFusedThreads;
-    __shared__ int64_t p_before[kFusedThreads / kWave], p_total[kFusedThreads / kWave];
-    __shared__ int32_t p_bad[kFusedThreads / kWave];
+                                               const int32_t *__restrict__ n_selected, int32_t batch_cap, CommitWs ws,
+                                               const int32_t *__restrict__ hint_len,
+                                               const int32_t *__restrict__ hint_node) {
+    constexpr int kPer = kFusedPlanMax / THREADS;
+    __shared__ int64_t p_before[THREADS / kWave], p_total[THREADS / kWave];
+    __shared__ int32_t p_bad[THREADS / kWave];
     __shared__ int32_t s_nb;
     __shared__ uint32_t s_err;
-    __shared__ int64_t s_off;
-    __shared__ int32_t s_L, s_m, s_e;
+    __shared__ int32_t s_qi[kPlanGroup], s_L[kPlanGroup], s_m[kPlanGroup];
+    __shared__ int64_t s_src[kPlanGroup];     // first tail token of each own prompt in q.tokens
+    __shared__ int32_t s_start[kPlanGroup + 1];  // tails of the own prompts, running sum
     DevState *st = tv.st;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const int32_t j = blockIdx.x;
+    const int32_t j0 = (int32_t)blockIdx.x * kPlanGroup;
     // one round trip: the persistent counters and every prompt's batch index; a second one: what
-    // hangs on the indices
+    // hangs on the indices (length and match length of every prompt)
     const int32_t f0 = st->free_cnt, ns0 = st->n_slots, active_half = st->active_half;
     const int64_t pool_top = st->pool_top;
     const uint64_t clock0 = st->clock;
-    PlanIn in[kPer];
+    const int32_t n_live = live_count(q.n, q.n_live);
+    int32_t qi[kPer], L[kPer], m[kPer];
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-        const int32_t i = t * kFusedThreads + tid;
-        in[t].m = -1;
-        if (i < batch_cap) in[t] = plan_load(q, ws, batch_idx, hint_len, hint_node, i);
+        const int32_t i = t * THREADS + tid;
+        qi[t] = i < batch_cap ? batch_idx[i] : -1;
+    }
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+        const int32_t i = t * THREADS + tid;
+        const bool in = i < batch_cap && qi[t] >= 0 && qi[t] < q.n;  // (q.n bounds the loads, n_live the admission)
+        L[t] = in ? q.len[qi[t]] : 0;
+        m[t] = !in ? -1 : hint_len ? hint_len[qi[t]] : ws.bm_len[i];
     }
     if (tid == 0) {
         uint32_t err = 0;
         s_nb = commit_gate(tv, n_selected, batch_cap, &err);
         s_err = err;
     }
+    if (tid < kPlanGroup) s_m[tid] = -1;
     __syncthreads();
     const int32_t nb = s_nb;
     const uint32_t err = s_err;
@@ -527,18 +558,22 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
     int32_t bad = 0;
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-        const int32_t i = t * kFusedThreads + tid;
+        const int32_t i = t * THREADS + tid;
         if (i >= nb) continue;
-        if (hint_len ? !plan_check(tv, q, in[t]) : in[t].m < 0) {
-            in[t].m = -1;
-            in[t].e = kRoot;
+        // (without hints the match inside the commit has checked index and span of every admitted
+        // prompt and left -1 for what it refused)
+        if (qi[t] < 0 || qi[t] >= n_live || L[t] < 1 || L[t] > tv.max_prompt_len || m[t] < 0 || m[t] > L[t]) {
             bad = 1;
             continue;
         }
-        const int64_t tl = (int64_t)(in[t].L - in[t].m);
+        const int64_t tl = (int64_t)(L[t] - m[t]);
         total += tl;
-        if (i < j) before += tl;
-        if (i == j) { s_off = in[t].off; s_L = in[t].L; s_m = in[t].m; s_e = in[t].e; }
+        if (i < j0) before += tl;
+        if (i >= j0 && i < j0 + kPlanGroup) {
+            s_qi[i - j0] = qi[t];
+            s_L[i - j0] = L[t];
+            s_m[i - j0] = m[t];
+        }
     }
     before = wave_sum(before);
     total = wave_sum(total);
@@ -547,13 +582,13 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
     __syncthreads();
     before = 0; total = 0; bad = 0;
 #pragma unroll
-    for (int w2 = 0; w2 < kFusedThreads / kWave; ++w2) { before += p_before[w2]; total += p_total[w2]; bad += p_bad[w2]; }
+    for (int w2 = 0; w2 < THREADS / kWave; ++w2) { before += p_before[w2]; total += p_total[w2]; bad += p_bad[w2]; }
     // (the end of every commit leaves room for a worst-case batch if compaction can make it; tails
     // that still do not fit mean the pool is too small for what must stay cached)
     const int64_t half_end = ((int64_t)active_half + 1) * tv.pool_half;
     const bool pool_full = nb > 0 && !bad && pool_top + total > half_end;
     const bool skip = err != 0 || bad != 0 || pool_full;
-    if (j == 0 && tid == 0) {
+    if (blockIdx.x == 0 && tid == 0) {
         uint32_t e = err;
         if (bad) e |= 4u;        // KLPM_DEV_BAD_INPUT
         if (pool_full) e |= 2u;  // KLPM_DEV_POOL_FULL
@@ -573,63 +608,108 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         st->clock0 = clock0;
         for (int i = 0; i < 12; ++i) st->done[i] = 0;
     }
-    if (skip || j >= nb) return;
-    // (s_* were written before the barrier above by the thread that holds prompt j)
-    const int64_t off = s_off;
-    const int32_t L = s_L, m = s_m, e = s_e;
-    const int32_t *__restrict__ src = q.tokens + off + m;
-    if (tid == 0) {
-        // this prompt's share of the plan (the group key needs where node e ends and the prompt's next token)
-        const bool inside = m < tv.depth_end[e];
-        const int32_t nxt = (m < L) ? src[0] : -1;
+    if (skip || j0 >= nb) return;
+    const int32_t own = nb - j0 < kPlanGroup ? nb - j0 : kPlanGroup;
+    // the last wavefront: one lane per own prompt for what only concerns that prompt
+    if (wv == THREADS / kWave - 1 && lane < own) {
+        const int32_t j = j0 + lane, Lj = s_L[lane], mj = s_m[lane], qj = s_qi[lane];
+        int64_t mine = 0;  // tails of the own prompts before this one
+        for (int c = 0; c < lane; ++c) mine += (int64_t)(s_L[c] - s_m[c]);
+        // first round trip: the prompt's span and node, the reserved ids
+        const int64_t off = q.off[qj];
+        const int32_t e = hint_len ? hint_node[qj] : ws.bm_node[j];
+        const int32_t id0 = reserved_id_at(tv, 2 * j, f0, ns0), id1 = reserved_id_at(tv, 2 * j + 1, f0, ns0);
+        bool ok = off >= 0 && off + (int64_t)Lj <= q.n_tokens && e >= 0 && e < tv.max_nodes;
+        const int32_t es = ok ? e : kRoot;
+        const int64_t os = ok ? off : 0;
+        // second: the node's edge and the prompt's tokens around the end of the match
+        const int32_t el = tv.edge_len[es], de = tv.depth_end[es];
+        const int64_t eo = tv.edge_off[es];
+        const int32_t *__restrict__ x = q.tokens + os;
+        const int32_t nxt = (ok && mj < Lj) ? x[mj] : -1;
+        const int32_t last = (ok && mj > 0) ? x[mj - 1] : 0;
+        const bool inside = mj < de;
+        if (hint_len && ok) {
+            // what can be checked locally about a match handed in by the caller: the node is alive, the
+            // match ends inside that node's edge (or is empty at the root), the last matched token is
+            // the edge's token there, and neither the edge nor a child continues the prompt
+            if (mj == 0) {
+                ok = es == kRoot;
+            } else if (es == kRoot || el <= 0 || mj > de || mj <= de - el) {
+                ok = false;
+            } else {
+                const int64_t at = eo + (int64_t)(mj - 1 - (de - el));
+                const int32_t t0 = tv.pool[at];
+                const int32_t t1 = (mj < Lj && mj < de) ? tv.pool[at + 1] : 0;
+                ok = t0 == last;
+                if (ok && mj < Lj) ok = mj < de ? t1 != nxt : slot_absent_lane(tv, make_key(es, nxt));
+            }
+        }
+        if (!ok) {
+            st->skip = 1;
+            atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
+        }
         uint64_t g;
-        if (!inside && m == L) {
+        if (!inside && mj == Lj) {
             g = kNoGroup;  // already present and ending on a node boundary: ticks only
         } else if (inside) {
-            g = (uint64_t)(uint32_t)e << 33;
+            g = (uint64_t)(uint32_t)es << 33;
         } else {
-            g = ((uint64_t)(uint32_t)e << 33) | (1ull << 32) | (uint64_t)(uint32_t)nxt;
+            g = ((uint64_t)(uint32_t)es << 33) | (1ull << 32) | (uint64_t)(uint32_t)nxt;
         }
         ws.used[j] = 0;
         ws.leaf_tok[j] = 0;
         ws.lcp_lead[j] = kLcpPending;
-        ws.resv_id[2 * j] = reserved_id_at(tv, 2 * j, f0, ns0);
-        ws.resv_id[2 * j + 1] = reserved_id_at(tv, 2 * j + 1, f0, ns0);
+        ws.resv_id[2 * j] = id0;
+        ws.resv_id[2 * j + 1] = id1;
         if (hint_len) {
-            ws.bm_len[j] = m;
-            ws.bm_node[j] = e;
+            ws.bm_len[j] = mj;
+            ws.bm_node[j] = es;
         }
         ws.gkey[j] = g;
-        ws.end_node[j] = e;
+        ws.end_node[j] = es;
         ws.next_tok[j] = nxt;
-        ws.tail_off[j] = before;
-        if (hint_len && !hinted_match_ok(tv, src - m, L, m, e)) {
-            st->skip = 1;
-            atomicOr(&st->device_error, 4u /* KLPM_DEV_BAD_INPUT */);
-        }
+        ws.tail_off[j] = before + mine;
     }
+    // everybody: the own prompts' tails as one span of the pool (eight independent rows per trip)
+    if (tid < kPlanGroup) {
+        int32_t run = 0;
+        for (int c = 0; c < tid; ++c) run += c < own ? s_L[c] - s_m[c] : 0;
+        s_start[tid] = run;
+        const bool mine = tid < own;
+        int64_t off = mine ? q.off[s_qi[tid]] : 0;
+        if (off < 0 || off + (int64_t)(mine ? s_L[tid] : 0) > q.n_tokens) off = -1;  // (its owner lane refuses the commit)
+        s_src[tid] = off < 0 ? -1 : off + (int64_t)(mine ? s_m[tid] : 0);
+        if (tid == kPlanGroup - 1) s_start[kPlanGroup] = run + (mine ? s_L[tid] - s_m[tid] : 0);
+    }
+    __syncthreads();
+    const int32_t len = s_start[kPlanGroup];
     int32_t *__restrict__ dst = tv.pool + pool_top + before;
-    const int32_t len = L - m;
-    // eight independent rows per trip (lanes past the end re-read the last token, stores are masked)
-    for (int32_t base = 0; base < len; base += 8 * kFusedThreads) {
+    for (int32_t base = 0; base < len; base += 8 * THREADS) {
         int32_t v[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            int32_t i = base + r * kFusedThreads + tid;
-            v[r] = src[i < len ? i : len - 1];
+            int32_t i = base + r * THREADS + tid;
+            i = i < len ? i : len - 1;
+            int c = 0;
+#pragma unroll
+            for (int u = 1; u < kPlanGroup; ++u) c += (i >= s_start[u]) ? 1 : 0;  // (empty tails share their start with the next)
+            const int64_t sp = s_src[c];
+            v[r] = q.tokens[sp >= 0 ? sp + (int64_t)(i - s_start[c]) : 0];  // (no branch around the load)
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            int32_t i = base + r * kFusedThreads + tid;
+            const int32_t i = base + r * THREADS + tid;
             if (i < len) dst[i] = v[r];
         }
     }
 }
-__global__ __launch_bounds__(kFusedThreads) void k_plan_copy(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
+constexpr int kPlanCopyThreads = 1024;  // (what a workgroup spends its time on is the copy: rows in flight)
+__global__ __launch_bounds__(kPlanCopyThreads) void k_plan_copy(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                              const int32_t *__restrict__ n_selected, int32_t batch_cap,
                                                              CommitWs ws, const int32_t *__restrict__ hint_len,
                                                              const int32_t *__restrict__ hint_node) {
-    plan_copy_body(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+    plan_copy_body<kPlanCopyThreads>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
 }
 
 // ------------------------------------------------------------------ structure pass
@@ -2108,7 +2188,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_commit_one(TreeView tv, QView
                                                               int64_t protect, int tick_bits, int final_shift,
                                                               int depth_bits, int may_evict,
                                                               kLPM_stats *__restrict__ stats_out) {
-    plan_copy_body(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+    plan_copy_body<kFusedThreads>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
     __threadfence();
     __syncthreads();
     if (batch_cap > 0 && threadIdx.x < kWave) structure_body(tv, q, batch_idx, ws);
@@ -2158,7 +2238,7 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
         return check_launch();
     }
     if (batch_cap <= kFusedPlanMax) {
-        hipLaunchKernelGGL(k_plan_copy, dim3(batch_cap > 0 ? batch_cap : 1), dim3(kFusedThreads), 0, stream, tv, q,
+        hipLaunchKernelGGL(k_plan_copy, dim3(batch_cap > 0 ? (batch_cap + kPlanGroup - 1) / kPlanGroup : 1), dim3(kPlanCopyThreads), 0, stream, tv, q,
                            batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
     } else {
         hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
