@@ -496,7 +496,8 @@ __global__ __launch_bounds__(256) void k_copy_tails(TreeView tv, QView q, const 
 // more of them copy faster.)
 constexpr int kFusedPlanMax = 2048;
 constexpr int kFusedThreads = 256;
-constexpr int kPlanGroup = 4;
+constexpr int kPlanGroup = 4;        // prompts per workgroup of a large batch
+constexpr int kPlanSmallBatch = 512;  // batches up to this size: one prompt per 256-thread workgroup (fewer rounds in a row count for more than repeated reads)
 
 // The key is absent from the child table (any lane on its own; the tree is not being modified).
 __device__ __forceinline__ bool slot_absent_lane(const TreeView &tv, uint64_t key) {
@@ -510,7 +511,7 @@ __device__ __forceinline__ bool slot_absent_lane(const TreeView &tv, uint64_t ke
     return true;
 }
 
-template <int THREADS>
+template <int THREADS, int GROUP>
 __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
                                                const int32_t *__restrict__ n_selected, int32_t batch_cap, CommitWs ws,
                                                const int32_t *__restrict__ hint_len,
@@ -520,12 +521,12 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
     __shared__ int32_t p_bad[THREADS / kWave];
     __shared__ int32_t s_nb;
     __shared__ uint32_t s_err;
-    __shared__ int32_t s_qi[kPlanGroup], s_L[kPlanGroup], s_m[kPlanGroup];
-    __shared__ int64_t s_src[kPlanGroup];     // first tail token of each own prompt in q.tokens
-    __shared__ int32_t s_start[kPlanGroup + 1];  // tails of the own prompts, running sum
+    __shared__ int32_t s_qi[GROUP], s_L[GROUP], s_m[GROUP];
+    __shared__ int64_t s_src[GROUP];     // first tail token of each own prompt in q.tokens
+    __shared__ int32_t s_start[GROUP + 1];  // tails of the own prompts, running sum
     DevState *st = tv.st;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const int32_t j0 = (int32_t)blockIdx.x * kPlanGroup;
+    const int32_t j0 = (int32_t)blockIdx.x * GROUP;
     // one round trip: the persistent counters and every prompt's batch index; a second one: what
     // hangs on the indices (length and match length of every prompt)
     const int32_t f0 = st->free_cnt, ns0 = st->n_slots, active_half = st->active_half;
@@ -550,7 +551,7 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         s_nb = commit_gate(tv, n_selected, batch_cap, &err);
         s_err = err;
     }
-    if (tid < kPlanGroup) s_m[tid] = -1;
+    if (tid < GROUP) s_m[tid] = -1;
     __syncthreads();
     const int32_t nb = s_nb;
     const uint32_t err = s_err;
@@ -569,7 +570,7 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         const int64_t tl = (int64_t)(L[t] - m[t]);
         total += tl;
         if (i < j0) before += tl;
-        if (i >= j0 && i < j0 + kPlanGroup) {
+        if (i >= j0 && i < j0 + GROUP) {
             s_qi[i - j0] = qi[t];
             s_L[i - j0] = L[t];
             s_m[i - j0] = m[t];
@@ -609,8 +610,21 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         for (int i = 0; i < 12; ++i) st->done[i] = 0;
     }
     if (skip || j0 >= nb) return;
-    const int32_t own = nb - j0 < kPlanGroup ? nb - j0 : kPlanGroup;
-    // the last wavefront: one lane per own prompt for what only concerns that prompt
+    const int32_t own = nb - j0 < GROUP ? nb - j0 : GROUP;
+    // where the own prompts' tails start in the span they form in the pool
+    if (tid < GROUP) {
+        int32_t run = 0;
+        for (int c = 0; c < tid; ++c) run += c < own ? s_L[c] - s_m[c] : 0;
+        s_start[tid] = run;
+        const bool mine = tid < own;
+        int64_t off = mine ? q.off[s_qi[tid]] : 0;
+        if (off < 0 || off + (int64_t)(mine ? s_L[tid] : 0) > q.n_tokens) off = -1;  // (its owner lane refuses the commit)
+        s_src[tid] = off < 0 ? -1 : off + (int64_t)(mine ? s_m[tid] : 0);
+        if (tid == GROUP - 1) s_start[GROUP] = run + (mine ? s_L[tid] - s_m[tid] : 0);
+    }
+    __syncthreads();
+    // the last wavefront: one lane per own prompt for what only concerns that prompt (the others already
+    // copy meanwhile)
     if (wv == THREADS / kWave - 1 && lane < own) {
         const int32_t j = j0 + lane, Lj = s_L[lane], mj = s_m[lane], qj = s_qi[lane];
         int64_t mine = 0;  // tails of the own prompts before this one
@@ -672,18 +686,7 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         ws.tail_off[j] = before + mine;
     }
     // everybody: the own prompts' tails as one span of the pool (eight independent rows per trip)
-    if (tid < kPlanGroup) {
-        int32_t run = 0;
-        for (int c = 0; c < tid; ++c) run += c < own ? s_L[c] - s_m[c] : 0;
-        s_start[tid] = run;
-        const bool mine = tid < own;
-        int64_t off = mine ? q.off[s_qi[tid]] : 0;
-        if (off < 0 || off + (int64_t)(mine ? s_L[tid] : 0) > q.n_tokens) off = -1;  // (its owner lane refuses the commit)
-        s_src[tid] = off < 0 ? -1 : off + (int64_t)(mine ? s_m[tid] : 0);
-        if (tid == kPlanGroup - 1) s_start[kPlanGroup] = run + (mine ? s_L[tid] - s_m[tid] : 0);
-    }
-    __syncthreads();
-    const int32_t len = s_start[kPlanGroup];
+    const int32_t len = s_start[GROUP];
     int32_t *__restrict__ dst = tv.pool + pool_top + before;
     for (int32_t base = 0; base < len; base += 8 * THREADS) {
         int32_t v[8];
@@ -693,7 +696,7 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
             i = i < len ? i : len - 1;
             int c = 0;
 #pragma unroll
-            for (int u = 1; u < kPlanGroup; ++u) c += (i >= s_start[u]) ? 1 : 0;  // (empty tails share their start with the next)
+            for (int u = 1; u < GROUP; ++u) c += (i >= s_start[u]) ? 1 : 0;  // (empty tails share their start with the next)
             const int64_t sp = s_src[c];
             v[r] = q.tokens[sp >= 0 ? sp + (int64_t)(i - s_start[c]) : 0];  // (no branch around the load)
         }
@@ -704,12 +707,19 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         }
     }
 }
-constexpr int kPlanCopyThreads = 1024;  // (what a workgroup spends its time on is the copy: rows in flight)
+constexpr int kPlanCopyThreads = 1024;  // (what a workgroup of a large batch spends its time on is the copy: rows in flight)
 __global__ __launch_bounds__(kPlanCopyThreads) void k_plan_copy(TreeView tv, QView q, const int32_t *__restrict__ batch_idx,
-                                                             const int32_t *__restrict__ n_selected, int32_t batch_cap,
-                                                             CommitWs ws, const int32_t *__restrict__ hint_len,
-                                                             const int32_t *__restrict__ hint_node) {
-    plan_copy_body<kPlanCopyThreads>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+                                                                const int32_t *__restrict__ n_selected, int32_t batch_cap,
+                                                                CommitWs ws, const int32_t *__restrict__ hint_len,
+                                                                const int32_t *__restrict__ hint_node) {
+    plan_copy_body<kPlanCopyThreads, kPlanGroup>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+}
+__global__ __launch_bounds__(kFusedThreads) void k_plan_copy_small(TreeView tv, QView q,
+                                                                   const int32_t *__restrict__ batch_idx,
+                                                                   const int32_t *__restrict__ n_selected, int32_t batch_cap,
+                                                                   CommitWs ws, const int32_t *__restrict__ hint_len,
+                                                                   const int32_t *__restrict__ hint_node) {
+    plan_copy_body<kFusedThreads, 1>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
 }
 
 // ------------------------------------------------------------------ structure pass
@@ -2188,17 +2198,14 @@ __global__ __launch_bounds__(kFusedThreads) void k_commit_one(TreeView tv, QView
                                                               int64_t protect, int tick_bits, int final_shift,
                                                               int depth_bits, int may_evict,
                                                               kLPM_stats *__restrict__ stats_out) {
-    plan_copy_body<kFusedThreads>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
-    __threadfence();
+    // (one workgroup: the barrier between two steps orders what the first wrote before what the second reads)
+    plan_copy_body<kFusedThreads, 1>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
     __syncthreads();
     if (batch_cap > 0 && threadIdx.x < kWave) structure_body(tv, q, batch_idx, ws);
-    __threadfence();
     __syncthreads();
     ticks_body(tv, ws, budget, protect, tick_bits, 0, may_evict);
-    __threadfence();
     __syncthreads();
     if (may_evict) evict_gather_body(tv, ws, 0, final_shift, depth_bits);
-    __threadfence();
     __syncthreads();
     end_commit_small_body<kFusedThreads>(tv, stats_out);
 }
@@ -2237,9 +2244,12 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
                            stats_out);
         return check_launch();
     }
-    if (batch_cap <= kFusedPlanMax) {
-        hipLaunchKernelGGL(k_plan_copy, dim3(batch_cap > 0 ? (batch_cap + kPlanGroup - 1) / kPlanGroup : 1), dim3(kPlanCopyThreads), 0, stream, tv, q,
+    if (batch_cap <= kPlanSmallBatch) {
+        hipLaunchKernelGGL(k_plan_copy_small, dim3(batch_cap > 0 ? batch_cap : 1), dim3(kFusedThreads), 0, stream, tv, q,
                            batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
+    } else if (batch_cap <= kFusedPlanMax) {
+        hipLaunchKernelGGL(k_plan_copy, dim3((batch_cap + kPlanGroup - 1) / kPlanGroup), dim3(kPlanCopyThreads), 0, stream,
+                           tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
     } else {
         hipLaunchKernelGGL(k_commit_plan, dim3(1), dim3(kPlanThreads), 0, stream, tv, q, batch_idx, n_selected, batch_cap,
                            ws, hint_len, hint_node);

@@ -655,9 +655,9 @@ __global__ __launch_bounds__(256) void k_sel_walk(const uint32_t *__restrict__ o
 // match length by a few histogram sweeps over match_len, gathers the nb winners of the
 // longest-match order, sorts them in LDS and runs the two-cursor walk, all in one launch.
 constexpr int kFifoThreads = 1024;
+constexpr int kFqSingleBlockN = 8192;  // queues up to this length take the single-workgroup kernel (longer ones: the kernels further down)
 constexpr int kFifoMaxBatch = 4096;
 constexpr int kFifoBins = 2048;
-constexpr int kSweepRows = 16;  // independent loads per thread and trip in the queue sweeps
 
 struct FifoAcc {
     const uint32_t *l_elem_, *a_in_l_;
@@ -692,28 +692,30 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         if (tid == 0) { *n_selected = 0; *phase_inout = phase; }
         return;
     }
-    // sweep 0 (coalesced): arrival order check and the largest match length
+    // The queue (at most kFqSingleBlockN entries) is read once: every thread keeps kOwn consecutive
+    // entries' match lengths in registers for the whole kernel (index order = thread order), so that
+    // everything behind this round trip runs on registers and LDS.  Arrival order check and the
+    // largest match length come with it.
+    constexpr int kOwn = kFqSingleBlockN / kFifoThreads;
+    int32_t mv[kOwn];
     {
+        uint64_t t[kOwn + 1];
+        const int32_t first = tid * kOwn;
+#pragma unroll
+        for (int r = 0; r < kOwn; ++r) {
+            const int32_t i = first + r;
+            const int32_t ic = i < n ? i : n - 1;
+            mv[r] = match_len[ic];
+            t[r] = arrival[ic];
+        }
+        t[kOwn] = arrival[first + kOwn < n ? first + kOwn : n - 1];
         int32_t mx = 0;
         bool viol = false;
-        // eight independent rows per trip keep the single workgroup's loads in flight together
-        for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
-            int32_t mv[kSweepRows];
-            uint64_t t0[kSweepRows], t1[kSweepRows];
 #pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kFifoThreads + tid;
-                int32_t ic = i < n ? i : n - 1;
-                int32_t in = ic + 1 < n ? ic + 1 : n - 1;
-                mv[r] = match_len[ic];
-                t0[r] = arrival[ic];
-                t1[r] = arrival[in];
-            }
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                mx = mv[r] > mx ? mv[r] : mx;
-                viol |= t0[r] > t1[r];
-            }
+        for (int r = 0; r < kOwn; ++r) {
+            mv[r] = (first + r < n) ? (mv[r] < 0 ? 0 : mv[r]) : -1;  // (-1: no entry)
+            mx = mv[r] > mx ? mv[r] : mx;
+            viol |= first + r + 1 < n && t[r] > t[r + 1];
         }
         if (viol) atomicOr(&s_flag, 1);
         mx = wave_max(mx);
@@ -734,7 +736,7 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
     }
     if (nb == 1) {
         // one query per step (Def. 2 as it stands): the head of the queue, or the first query that
-        // holds the largest match length found by the sweep above
+        // holds the largest match length found above
         if (!lpm_only && phase == 0u) {
             if (tid == 0) batch_idx[0] = 0;
             return;
@@ -743,19 +745,9 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
         __syncthreads();
         const int32_t best = s_max;
         int32_t first = n;
-        for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
-            int32_t mv[kSweepRows];
 #pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kFifoThreads + tid;
-                mv[r] = match_len[i < n ? i : n - 1];
-            }
-#pragma unroll
-            for (int r = 0; r < kSweepRows; ++r) {
-                int32_t i = base + r * kFifoThreads + tid;
-                if (i < n && (mv[r] < 0 ? 0 : mv[r]) == best && i < first) first = i;
-            }
-        }
+        for (int r = kOwn - 1; r >= 0; --r)
+            if (mv[r] == best) first = tid * kOwn + r;
         if (first < n) atomicMin(&s_bin, first);
         __syncthreads();
         if (tid == 0) batch_idx[0] = s_bin;
@@ -766,13 +758,13 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
     int32_t n_cand = nb;
     if (n <= kFifoMaxBatch && ((int64_t)nb * 8 >= n || n <= 256)) {
         n_cand = n;
-        for (int32_t i = tid; i < n; i += kFifoThreads) {
-            int32_t m = match_len[i];
-            m = m < 0 ? 0 : m;
-            cand[i] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
+#pragma unroll
+        for (int r = 0; r < kOwn; ++r) {
+            const int32_t i = tid * kOwn + r;
+            if (mv[r] >= 0) cand[i] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)mv[r]) << 32) | (uint64_t)(uint32_t)i;
         }
     } else {
-        // the nb-th largest match length m*, found digit by digit (11 bits per sweep)
+        // the nb-th largest match length m*, found digit by digit (11 bits per pass over the registers)
         int mbits = 0;
         while (mbits < 31 && (s_max >> mbits) != 0) ++mbits;
         int32_t fixed_hi = 0;      // value of the bits above `shift` already decided
@@ -783,18 +775,22 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
             const int nshift = shift - width;
             for (int i = tid; i < kFifoBins; i += kFifoThreads) hist[i] = 0;
             __syncthreads();
-            for (int32_t base = 0; base < n; base += kSweepRows * kFifoThreads) {
-                int32_t mv[kSweepRows];
 #pragma unroll
-                for (int r = 0; r < kSweepRows; ++r) {
-                    int32_t i = base + r * kFifoThreads + tid;
-                    mv[r] = match_len[i < n ? i : n - 1];
-                }
-#pragma unroll
-                for (int r = 0; r < kSweepRows; ++r) {
-                    int32_t i = base + r * kFifoThreads + tid;
-                    int32_t m = mv[r] < 0 ? 0 : mv[r];
-                    if (i < n && (m >> shift) == fixed_hi) atomicAdd(&hist[(m >> nshift) & ((1 << width) - 1)], 1u);
+            for (int r = 0; r < kOwn; ++r) {
+                const int32_t m = mv[r];
+                const bool in = m >= 0 && (m >> shift) == fixed_hi;
+                const int32_t bin = (m >> nshift) & ((1 << width) - 1);
+                // lanes that share the first active lane's bin are added once (scores cluster and same-address
+                // LDS atomics serialise)
+                const uint64_t act = __ballot(in);
+                if (act) {
+                    const int32_t lead = __shfl(bin, (int)__builtin_ctzll(act));
+                    const uint64_t same = __ballot(in && bin == lead);
+                    if (in && bin == lead) {
+                        if ((tid & (kWave - 1)) == (int)__builtin_ctzll(same)) atomicAdd(&hist[bin], (uint32_t)__popcll(same));
+                    } else if (in) {
+                        atomicAdd(&hist[bin], 1u);
+                    }
                 }
             }
             __syncthreads();
@@ -815,59 +811,23 @@ __global__ __launch_bounds__(kFifoThreads) void k_select_fifo(const uint64_t *__
             __syncthreads();
         }
         const int32_t m_star = fixed_hi;  // count(m > m*) = nb - need < nb <= count(m >= m*)
-        // gather: every query above m*, and the first `need` queries (by index) equal to m*.  Each
-        // wavefront owns a contiguous segment of the queue and reads it 64 entries at a time, so the
-        // index order of the equal-to-m* queries is a ballot prefix plus the counts of earlier segments.
-        {
-            const int lane = tid & (kWave - 1);
-            const int wv = tid / kWave;
-            const int n_wv = kFifoThreads / kWave;
-            const int32_t seg = ((n + n_wv - 1) / n_wv + kWave - 1) / kWave * kWave;
-            const int32_t lo = (int64_t)wv * seg < n ? wv * seg : n;
-            const int32_t hi = lo + seg < n ? lo + seg : n;
-            int32_t eq = 0;
-            for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
-                int32_t mv[kSweepRows];
+        // gather: every query above m*, and the first `need` queries (by index) equal to m*: a scan
+        // over the threads' counts of equal entries gives their index order
+        int32_t eq = 0;
 #pragma unroll
-                for (int r = 0; r < kSweepRows; ++r) {
-                    int32_t i = base + r * kWave + lane;
-                    mv[r] = match_len[i < hi ? i : hi - 1];
-                }
+        for (int r = 0; r < kOwn; ++r) eq += mv[r] == m_star ? 1 : 0;
+        int32_t eq_all;
+        int32_t rank = block_inclusive_scan<int32_t, kFifoThreads>(eq, sbuf, tid, eq_all) - eq;
 #pragma unroll
-                for (int r = 0; r < kSweepRows; ++r) {
-                    int32_t i = base + r * kWave + lane;
-                    int32_t m = mv[r] < 0 ? 0 : mv[r];
-                    eq += (int32_t)__popcll(__ballot(i < hi && m == m_star));
-                }
+        for (int r = 0; r < kOwn; ++r) {
+            const int32_t m = mv[r];
+            const bool is_eq = m == m_star;
+            if (m > m_star || (is_eq && rank < need)) {
+                const int32_t at = atomicAdd(&s_count, 1);
+                if (at < kFifoMaxBatch)
+                    cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)(tid * kOwn + r);
             }
-            if (lane == 0) sbuf[wv] = eq;
-            __syncthreads();
-            int32_t rank = 0;  // equal-to-m* queries in earlier segments
-            for (int w2 = 0; w2 < wv; ++w2) rank += sbuf[w2];
-            for (int32_t base = lo; base < hi; base += kSweepRows * kWave) {
-                int32_t mv[kSweepRows];
-#pragma unroll
-                for (int r = 0; r < kSweepRows; ++r) {
-                    int32_t i = base + r * kWave + lane;
-                    mv[r] = match_len[i < hi ? i : hi - 1];
-                }
-#pragma unroll
-                for (int r = 0; r < kSweepRows; ++r) {
-                    int32_t i = base + r * kWave + lane;
-                    bool in = i < hi;
-                    int32_t m = mv[r] < 0 ? 0 : mv[r];
-                    bool is_eq = in && m == m_star;
-                    uint64_t eqmask = __ballot(is_eq);
-                    int32_t my_rank = rank + (int32_t)__popcll(eqmask & ((1ull << lane) - 1ull));
-                    bool win = in && (m > m_star || (is_eq && my_rank < need));
-                    if (win) {
-                        int32_t at = atomicAdd(&s_count, 1);
-                        if (at < kFifoMaxBatch)
-                            cand[at] = ((uint64_t)(0x7FFFFFFFu - (uint32_t)m) << 32) | (uint64_t)(uint32_t)i;
-                    }
-                    rank += (int32_t)__popcll(eqmask);
-                }
-            }
+            rank += is_eq ? 1 : 0;
         }
         __syncthreads();
     }
@@ -907,7 +867,6 @@ constexpr int kFqLevelBits = 14;    // bits of match length resolved per histogr
 constexpr int kFqBins = 1 << kFqLevelBits;
 constexpr int kFqRow = kFqBins + 64;   // words per row of suffix counts (bins 0 .. nbins, the last one zero)
 constexpr int kFqMaxLevels = 5;     // 31 bits of score (+ 32 bits of tie key) at most
-constexpr int kFqSingleBlockN = 8192;  // shorter queues are cheaper in the single-workgroup kernel
 
 // What the longest-match picks maximise, as one unsigned number ("goodness"): the score, or with
 // tie keys (score, inverted tie key) - a smaller tie key wins among equal scores.
