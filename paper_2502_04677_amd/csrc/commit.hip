@@ -51,6 +51,7 @@ __device__ __forceinline__ void wave_sync() {
 __device__ __forceinline__ bool last_block_done(DevState *st, int slot) {
     __shared__ int s_last;
     __syncthreads();
+    if (gridDim.x == 1) return true;  // (nobody to wait for, nothing to make visible beyond the workgroup)
     if (threadIdx.x == 0) {
         __threadfence();
         s_last = (atomicAdd(&st->done[slot], 1) == (int)gridDim.x - 1) ? 1 : 0;
@@ -524,6 +525,8 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
     __shared__ int32_t s_qi[GROUP], s_L[GROUP], s_m[GROUP];
     __shared__ int64_t s_src[GROUP];     // first tail token of each own prompt in q.tokens
     __shared__ int32_t s_start[GROUP + 1];  // tails of the own prompts, running sum
+    __shared__ int64_t s_off1;                 // GROUP == 1: the own prompt's span and node
+    __shared__ int32_t s_e1;
     DevState *st = tv.st;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int32_t j0 = (int32_t)blockIdx.x * GROUP;
@@ -545,6 +548,19 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         const bool in = i < batch_cap && qi[t] >= 0 && qi[t] < q.n;  // (q.n bounds the loads, n_live the admission)
         L[t] = in ? q.len[qi[t]] : 0;
         m[t] = !in ? -1 : hint_len ? hint_len[qi[t]] : ws.bm_len[i];
+    }
+    // (a workgroup with one prompt of its own asks for that prompt's span and node in the same round)
+    int64_t off1 = -1;
+    int32_t e1 = -1;
+    if (GROUP == 1 && j0 < batch_cap && tid == (j0 & (THREADS - 1))) {
+        const int t1 = j0 / THREADS;
+        int32_t q1 = -1;
+#pragma unroll
+        for (int t = 0; t < kPer; ++t) q1 = t == t1 ? qi[t] : q1;
+        if (q1 >= 0 && q1 < q.n) {
+            off1 = q.off[q1];
+            e1 = hint_len ? hint_node[q1] : ws.bm_node[j0];
+        }
     }
     if (tid == 0) {
         uint32_t err = 0;
@@ -574,6 +590,10 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
             s_qi[i - j0] = qi[t];
             s_L[i - j0] = L[t];
             s_m[i - j0] = m[t];
+            if (GROUP == 1) {
+                s_off1 = off1;
+                s_e1 = e1;
+            }
         }
     }
     before = wave_sum(before);
@@ -617,7 +637,7 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         for (int c = 0; c < tid; ++c) run += c < own ? s_L[c] - s_m[c] : 0;
         s_start[tid] = run;
         const bool mine = tid < own;
-        int64_t off = mine ? q.off[s_qi[tid]] : 0;
+        int64_t off = !mine ? 0 : GROUP == 1 ? s_off1 : q.off[s_qi[tid]];
         if (off < 0 || off + (int64_t)(mine ? s_L[tid] : 0) > q.n_tokens) off = -1;  // (its owner lane refuses the commit)
         s_src[tid] = off < 0 ? -1 : off + (int64_t)(mine ? s_m[tid] : 0);
         if (tid == GROUP - 1) s_start[GROUP] = run + (mine ? s_L[tid] - s_m[tid] : 0);
@@ -630,8 +650,8 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         int64_t mine = 0;  // tails of the own prompts before this one
         for (int c = 0; c < lane; ++c) mine += (int64_t)(s_L[c] - s_m[c]);
         // first round trip: the prompt's span and node, the reserved ids
-        const int64_t off = q.off[qj];
-        const int32_t e = hint_len ? hint_node[qj] : ws.bm_node[j];
+        const int64_t off = GROUP == 1 ? s_off1 : q.off[qj];
+        const int32_t e = GROUP == 1 ? s_e1 : hint_len ? hint_node[qj] : ws.bm_node[j];
         const int32_t id0 = reserved_id_at(tv, 2 * j, f0, ns0), id1 = reserved_id_at(tv, 2 * j + 1, f0, ns0);
         bool ok = off >= 0 && off + (int64_t)Lj <= q.n_tokens && e >= 0 && e < tv.max_nodes;
         const int32_t es = ok ? e : kRoot;
