@@ -1884,10 +1884,9 @@ __device__ __forceinline__ uint64_t evict_key(const TreeView &tv, int64_t id, in
 // The sweeps over all nodes visit four nodes per thread and trip, every field requested before any
 // is looked at (one round trip per trip; a loop that tests edge_len, then tick, then builds the key
 // pays three per node).  f(id, edge_len, key) is called for every live node that may be evicted.
-template <bool WITH_SLOT, class F>
+template <bool WITH_SLOT, bool WITH_DEPTH, int kUnroll, class F>
 __device__ __forceinline__ void for_each_evictable_impl(const TreeView &tv, int32_t n_slots, uint64_t keep_from, int depth_bits,
                                                         int64_t first, int64_t stride, F f) {
-    constexpr int kUnroll = 4;
     const uint64_t dm = (1ull << depth_bits) - 1ull;
     for (int64_t id0 = first; id0 < n_slots; id0 += kUnroll * stride) {
         int32_t len[kUnroll], de[kUnroll], sl[kUnroll];
@@ -1898,7 +1897,7 @@ __device__ __forceinline__ void for_each_evictable_impl(const TreeView &tv, int3
             const int64_t idc = id < n_slots ? id : 0;  // (the root has no edge: skipped below)
             len[u] = tv.edge_len[idc];
             tk[u] = tv.tick[idc];
-            de[u] = tv.depth_end[idc];
+            de[u] = WITH_DEPTH ? tv.depth_end[idc] : 0;
             sl[u] = WITH_SLOT ? tv.slot_of[idc] : -1;
         }
 #pragma unroll
@@ -1913,14 +1912,51 @@ __device__ __forceinline__ void for_each_evictable_impl(const TreeView &tv, int3
 template <class F>
 __device__ __forceinline__ void for_each_evictable(const TreeView &tv, int32_t n_slots, uint64_t keep_from, int depth_bits,
                                                    int64_t first, int64_t stride, F f) {
-    for_each_evictable_impl<false>(tv, n_slots, keep_from, depth_bits, first, stride,
-                                   [&](int64_t id, int32_t len, uint64_t key, int32_t) { f(id, len, key); });
+    for_each_evictable_impl<false, true, 4>(tv, n_slots, keep_from, depth_bits, first, stride,
+                                         [&](int64_t id, int32_t len, uint64_t key, int32_t) { f(id, len, key); });
 }
 // f(id, edge_len, key, slot): also brings the node's child-table slot along (for sweeps that remove nodes)
 template <class F>
 __device__ __forceinline__ void for_each_evictable_slot(const TreeView &tv, int32_t n_slots, uint64_t keep_from,
                                                         int depth_bits, int64_t first, int64_t stride, F f) {
-    for_each_evictable_impl<true>(tv, n_slots, keep_from, depth_bits, first, stride, f);
+    for_each_evictable_impl<true, true, 4>(tv, n_slots, keep_from, depth_bits, first, stride, f);
+}
+
+// f(id, edge_len, key, slot) for the nodes whose tick passes want(tick): only edge length and tick are read
+// for every node, depth and table slot for those few (the sweep of a windowed eviction, whose window is a
+// range of ticks)
+template <class W, class F>
+__device__ __forceinline__ void for_each_evictable_wanted(const TreeView &tv, int32_t n_slots, uint64_t keep_from,
+                                                          int depth_bits, int64_t first, int64_t stride, W want, F f) {
+    constexpr int kUnroll = 8;
+    const uint64_t dm = (1ull << depth_bits) - 1ull;
+    for (int64_t id0 = first; id0 < n_slots; id0 += kUnroll * stride) {
+        int32_t len[kUnroll];
+        uint64_t tk[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t id = id0 + u * stride;
+            const int64_t idc = id < n_slots ? id : 0;  // (the root has no edge: skipped below)
+            len[u] = tv.edge_len[idc];
+            tk[u] = tv.tick[idc];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t id = id0 + u * stride;
+            if (id >= n_slots || len[u] <= 0 || tk[u] >= keep_from || !want(tk[u])) continue;
+            const int32_t de = tv.depth_end[id], sl = tv.slot_of[id];
+            f(id, len[u], (tk[u] << depth_bits) | (dm - (uint64_t)(uint32_t)de), sl);
+        }
+    }
+}
+
+// f(id, edge_len, key) with the depth part of the key left at its largest value: for sweeps that only look at
+// key bits above the depth (the digit histograms), which then need not read the depths
+template <class F>
+__device__ __forceinline__ void for_each_evictable_tick(const TreeView &tv, int32_t n_slots, uint64_t keep_from,
+                                                        int depth_bits, int64_t first, int64_t stride, F f) {
+    for_each_evictable_impl<false, false, 8>(tv, n_slots, keep_from, depth_bits, first, stride,
+                                          [&](int64_t id, int32_t len, uint64_t key, int32_t) { f(id, len, key); });
 }
 
 // One step of the search for the cut key, run by one workgroup of 256 threads once the weighted
@@ -1975,8 +2011,9 @@ __global__ __launch_bounds__(256) void k_evict_hist(TreeView tv, CommitWs ws, in
     for (int i = tid; i < kEvictBins; i += 256) h[i] = 0;
     __syncthreads();
     const int upper = shift + width;
-    for_each_evictable(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
-                       (int64_t)gridDim.x * blockDim.x, [&](int64_t, int32_t len, uint64_t key) {
+    // (shift >= depth_bits: the digits of the histograms lie in the tick)
+    for_each_evictable_tick(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
+                            (int64_t)gridDim.x * blockDim.x, [&](int64_t, int32_t len, uint64_t key) {
         bool in_prefix = (pass == 0) || (upper >= 64 ? prefix == 0 : (key >> upper) == prefix);
         if (in_prefix) atomicAdd(&h[(key >> shift) & (uint64_t)((1 << width) - 1)], (unsigned long long)len);
     });
@@ -2090,8 +2127,7 @@ __device__ __forceinline__ void evict_gather_body(TreeView tv, CommitWs ws, int 
     __syncthreads();
     const bool windowed = n_hist_pass > 0 && shift < 64;  // (otherwise every node that may go is a candidate)
     // (removals and candidates are listed in LDS: one atomic per workgroup on each of the shared counters)
-    for_each_evictable_slot(tv, n_slots, keep_from, depth_bits, 1 + (int64_t)blockIdx.x * blockDim.x + tid,
-                            (int64_t)gridDim.x * blockDim.x, [&](int64_t id, int32_t len, uint64_t key, int32_t slot) {
+    auto take = [&](int64_t id, int32_t len, uint64_t key, int32_t slot) {
         const uint64_t top = windowed ? (key >> shift) : 0ull;
         if (evict_all || (windowed && top < prefix)) {
             removal_push(tv, st, rl, id, len, slot, &s_tok, &s_cnt);
@@ -2104,7 +2140,16 @@ __device__ __forceinline__ void evict_gather_body(TreeView tv, CommitWs ws, int 
                 c_slot[at] = slot;
             }
         }
-    });
+    };
+    const int64_t first = 1 + (int64_t)blockIdx.x * blockDim.x + tid, stride = (int64_t)gridDim.x * blockDim.x;
+    if (windowed && !evict_all && shift >= depth_bits) {
+        // the window is a range of ticks: nodes above it (nearly all) are passed over on their tick alone
+        const int tshift = shift - depth_bits;
+        for_each_evictable_wanted(tv, n_slots, keep_from, depth_bits, first, stride,
+                                  [&](uint64_t tick) { return (tick >> tshift) <= prefix; }, take);
+    } else {
+        for_each_evictable_slot(tv, n_slots, keep_from, depth_bits, first, stride, take);
+    }
     removal_flush(tv, st, rl, tid, 256);
     if (tid == 0) s_cbase = s_ncand > 0 ? atomicAdd(&st->cand_cnt, s_ncand) : 0;
     __syncthreads();
@@ -2155,29 +2200,58 @@ __device__ __forceinline__ void evict_gather_body(TreeView tv, CommitWs ws, int 
         // the key is complete: what lies below the window is gone already, the rest up to the cut goes now
         evict_apply_sweep(tv, st, st->evict_prefix, keep_from, n_slots, depth_bits, 1 + tid, 256, &s_tok, &s_cnt);
     } else {
-        // sort the collected nodes by key in LDS, then the cut
-        int32_t np2 = 1;
-        while (np2 < n) np2 <<= 1;
-        for (int32_t i = tid; i < np2; i += 256) {
-            s_key[i] = i < n ? __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
-            s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        }
-        __syncthreads();
-        sort_lds<256, kEvictCand / 256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
-        // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
-        // reaches the remainder is the last one to go (all of them, should the weights fall short)
         const int64_t rem = st->evict_rem;
-        const int32_t per = (n + 255) / 256;
-        const int32_t lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
-        int64_t mine = 0;
-        for (int32_t i = lo; i < hi; ++i) mine += s_len[i];
-        int64_t all;
-        int64_t run = block_inclusive_scan<int64_t, 256>(mine, part, tid, all) - mine;
-        for (int32_t i = lo; i < hi; ++i) {
-            if (run < rem && run + s_len[i] >= rem) s_cut = s_key[i];
-            run += s_len[i];
+        if (n <= 256) {
+            // few collected nodes (the rule): no sort - every thread adds up the weights of the nodes whose
+            // key is not above its own node's; the node at which that sum reaches the remainder is the last
+            // one to go (all of them, should the weights fall short)
+            if (tid < n) {
+                s_key[tid] = __hip_atomic_load(&ws.cand_key[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_len[tid] = __hip_atomic_load(&ws.cand_len[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+            if (tid < n) {
+                const uint64_t mine = s_key[tid];
+                int64_t upto = 0;
+                for (int32_t i0 = 0; i0 < n; i0 += 16) {  // (sixteen LDS reads in flight; entries past n hold what an earlier commit left: masked)
+                    uint64_t kk[16];
+                    int32_t ll[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const int32_t i = (i0 + u) & (kEvictCand - 1);
+                        kk[u] = s_key[i];
+                        ll[u] = s_len[i];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) upto += (i0 + u < n && kk[u] <= mine) ? (int64_t)ll[u] : 0;
+                }
+                if (upto - (int64_t)s_len[tid] < rem && upto >= rem) s_cut = mine;
+            }
+            __syncthreads();
+        } else {
+            // sort the collected nodes by key in LDS, then the cut
+            int32_t np2 = 1;
+            while (np2 < n) np2 <<= 1;
+            for (int32_t i = tid; i < np2; i += 256) {
+                s_key[i] = i < n ? __hip_atomic_load(&ws.cand_key[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
+                s_len[i] = i < n ? __hip_atomic_load(&ws.cand_len[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+            }
+            __syncthreads();
+            sort_lds<256, kEvictCand / 256, true>(s_key, reinterpret_cast<uint32_t *>(s_len), np2, tid);
+            // every thread owns a contiguous run of the sorted nodes; the node at which the running weight
+            // reaches the remainder is the last one to go (all of them, should the weights fall short)
+            const int32_t per = (n + 255) / 256;
+            const int32_t lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
+            int64_t mine = 0;
+            for (int32_t i = lo; i < hi; ++i) mine += s_len[i];
+            int64_t all;
+            int64_t run = block_inclusive_scan<int64_t, 256>(mine, part, tid, all) - mine;
+            for (int32_t i = lo; i < hi; ++i) {
+                if (run < rem && run + s_len[i] >= rem) s_cut = s_key[i];
+                run += s_len[i];
+            }
+            __syncthreads();
         }
-        __syncthreads();
         const uint64_t cut = s_cut;
         if (tid == 0) st->evict_prefix = cut;
         // keys are unique among live nodes (nodes that share a tick lie on one root path, at
