@@ -149,7 +149,8 @@ int kLPM_select_workspace_bytes(int32_t n, size_t *out_bytes);
  *                       (write 0 before the call to restart the cycle every step)
  *   batch_idx           DEVICE [min(batch, n)] out: queue indices in pick order
  *   n_selected          DEVICE [1] out: min(batch, number of entries)
- *   workspace           DEVICE, >= kLPM_select_workspace_bytes(n), 256-byte aligned
+ *   workspace           DEVICE, >= kLPM_select_workspace_bytes(n), 256-byte aligned; scratch only: its
+ *                       contents need not be set before a call and mean nothing after it
  * n = 0 or batch = 0 selects nothing (*n_selected = 0), leaves the phase unchanged and needs no
  * workspace (NULL will do).
  */
@@ -169,8 +170,8 @@ int kLPM_select(const uint64_t *arrival, const int32_t *match_len, const uint32_
  *   The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
  *   outside any stream capture.
  *   All calls on one GPU share the one array, whatever their stream: calls that may overlap in time
- *   on a GPU race with each other (keep them on one stream, or order them with events).  Each call
- *   clears what it needs cleared; nothing is carried from call to call.
+ *   on a GPU race with each other (keep them on one stream, or order them with events).  Nothing in
+ *   the array has to hold a particular value when a call starts; nothing is carried from call to call.
  */
 #define KLPM_SELECT_STATIC_MAX_N 131072
 int kLPM_select_static(const uint64_t *arrival, const int32_t *match_len, const uint32_t *tie_key, int32_t n,
