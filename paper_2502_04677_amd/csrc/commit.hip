@@ -704,6 +704,9 @@ __device__ __forceinline__ void plan_copy_body(TreeView tv, QView q, const int32
         ws.end_node[j] = es;
         ws.next_tok[j] = nxt;
         ws.tail_off[j] = before + mine;
+        ws.p_off[j] = os;
+        ws.p_len[j] = Lj;
+        ws.p_de[j] = de;
     }
     // everybody: the own prompts' tails as one span of the pool (eight independent rows per trip)
     const int32_t len = s_start[GROUP];
@@ -972,6 +975,17 @@ __device__ __forceinline__ MemberIn member_load(const TreeView &tv, const QView 
     MemberIn v;
     member_load_own(v, batch_idx, ws, j);
     member_load_refs(v, tv, q);
+    return v;
+}
+// Everything about prompt j in one round trip, for batches whose plan also left the prompt's span and the
+// end depth of its stop node (an old node: it keeps its end whatever is cut above it) beside the rest.
+__device__ __forceinline__ MemberIn member_load_planned(const int32_t *__restrict__ batch_idx, const CommitWs &ws,
+                                                        int32_t j) {
+    MemberIn v;
+    member_load_own(v, batch_idx, ws, j);
+    v.qoff = ws.p_off[j];
+    v.L = ws.p_len[j];
+    v.de_e = ws.p_de[j];
     return v;
 }
 __device__ __forceinline__ MemberIn member_from_lane(const MemberIn &v, int b) {
@@ -1368,8 +1382,7 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
     ctx.piece = -1;
     ctx.piece_slot = -1;
     ctx.piece_rec = NodeRec{};
-    MemberIn own;
-    member_load_own(own, batch_idx, ws, g);
+    const MemberIn own = member_load_planned(batch_idx, ws, g);
     if (uni(skip_v)) return;
     const int32_t nb = uni(nb_v);
     if (g >= nb) return;
@@ -1415,7 +1428,6 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
     // reserved for the first prompt that stops at my depth)
     int32_t below_v = -1;
     if (cut_scheme) below_v = ws.resv_id[2 * cutter];
-    member_load_refs(own, tv, q);
     const MemberIn me = member_from_lane(own, 0);
     if (!first_s) {
         // Not the first of its group: that prompt's wavefront inserts this one.  Meanwhile this
@@ -1470,7 +1482,7 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
             wave_sync();
             const bool active = lane < cnt;
             const int32_t j = active ? s_mem[lane] : g;
-            const MemberIn mv = member_load(tv, q, batch_idx, ws, j);
+            const MemberIn mv = member_load_planned(batch_idx, ws, j);
             int32_t h = active ? kLcpPending : kLcpNone;
             for (int spin = 0; spin < 2048; ++spin) {
                 if (h == kLcpPending) h = __hip_atomic_load(&ws.lcp_lead[j], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
@@ -1498,16 +1510,18 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
                     const bool tk = __shfl((int)has_tail, k) != 0;
                     if (k < lane && has_tail && tk && dk == d && ak == after) conflict = true;
                 }
+                const int64_t off = ctx.pool_top + mv.to + (int64_t)h;
+                int32_t made_slot = -1;
+                const bool hangs = active && !conflict && has_tail;
                 if (active && !conflict) {
                     int32_t end = piece, leaf_tokens = 0;
                     if (has_tail) {
-                        const int64_t off = ctx.pool_top + mv.to + (int64_t)h;
                         tv.parent[mv.leaf_id] = piece;
                         tv.edge_off[mv.leaf_id] = off;
                         tv.edge_len[mv.leaf_id] = mv.L - d;
                         tv.depth_end[mv.leaf_id] = mv.L;
                         tv.tick[mv.leaf_id] = ctx.clock0 + (uint64_t)j;
-                        slot_insert(tv, make_key(piece, after), mv.leaf_id, mv.L - d, off);
+                        made_slot = slot_insert(tv, make_key(piece, after), mv.leaf_id, mv.L - d, off);
                         atomicOr(&ws.used[j], 2);
                         end = mv.leaf_id;
                         leaf_tokens = mv.L - d;
@@ -1517,8 +1531,18 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
                 }
                 __threadfence();
                 wave_sync();
-                // (what follows looks nodes up in the table: the record of what this wavefront made is not kept here)
-                ctx.cache_ok = false;
+                // The members that met each other follow, one after the other.  Whatever they can find below
+                // their pieces is a leaf that a lane has just hung there (the rest of my own leaf goes on with
+                // my token, not theirs), so the record of this wavefront's table entries is set up from the
+                // lanes: lane k describes the leaf of member k, if it hung one.
+                ctx.c_parent = hangs ? piece : -2;  // (no node has this id)
+                ctx.c_tok = after;
+                ctx.c_child = mv.leaf_id;
+                ctx.c_el = mv.L - d;
+                ctx.c_eo = off;
+                ctx.c_slot = made_slot;
+                ctx.n_ent = cnt;
+                ctx.cache_ok = !__ballot(hangs && made_slot < 0);
                 ctx.piece = -1;
                 uint64_t todo = __ballot(active && conflict);
                 while (todo) {
@@ -1548,7 +1572,7 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
         const bool is_mine = (mine_s >> t) & 1u;
         uint64_t mask = __ballot(is_mine);
         if (!mask) continue;
-        const MemberIn mv = member_load(tv, q, batch_idx, ws, is_mine ? t * kWave + lane : g);
+        const MemberIn mv = member_load_planned(batch_idx, ws, is_mine ? t * kWave + lane : g);
         while (mask) {
             const int32_t b = (int32_t)__builtin_ctzll(mask);
             mask &= mask - 1ull;

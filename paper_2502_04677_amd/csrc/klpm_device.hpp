@@ -100,6 +100,9 @@ struct CommitWs {
     int32_t *next_tok;  // [max_batch] first unmatched token of prompt j (-1: matched in full)
     int32_t *lcp_lead;  // [max_batch] tokens that prompt j's unmatched tail shares with the tail of its group's first prompt
     int32_t *lcp_tok;   // [max_batch] prompt j's token behind that shared span (-1: the prompt ends there)
+    int64_t *p_off;     // [max_batch] plan: where prompt j starts in the queue's token array
+    int32_t *p_len;     // [max_batch] plan: prompt j's length
+    int32_t *p_de;      // [max_batch] plan: depth at which prompt j's stop node ends
     int32_t *resv_id;   // [2*max_batch] scratch: the node ids reserved for this commit
     int64_t *evict_hist; // [6][2048] weighted digit histograms of the eviction cut search
     uint64_t *cand_key;  // [kEvictCand] eviction keys of the nodes collected for the last stretch of the search

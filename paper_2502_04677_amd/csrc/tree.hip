@@ -12,7 +12,7 @@ namespace klpm {
 
 struct Layout {
     size_t state, parent, edge_off, edge_len, depth_end, tick, slot_of, free_stack, slots, pool;
-    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, lcp_lead, lcp_tok, resv_id, evict_hist, cand_key, cand_len, cand_id, cand_slot, iota_idx, iota_n;
+    size_t bm_len, bm_node, tail_off, gkey, end_node, used, leaf_tok, next_tok, lcp_lead, lcp_tok, p_off, p_len, p_de, resv_id, evict_hist, cand_key, cand_len, cand_id, cand_slot, iota_idx, iota_n;
     size_t total;
     uint32_t n_slots_table;
 };
@@ -51,6 +51,9 @@ static Layout make_layout(const kLPM_config &c) {
     L.next_tok = take(mb * 4);
     L.lcp_lead = take(mb * 4);
     L.lcp_tok = take(mb * 4);
+    L.p_off = take(mb * 8);
+    L.p_len = take(mb * 4);
+    L.p_de = take(mb * 4);
     L.resv_id = take(mb * 8);
     L.evict_hist = take(6 * 2048 * 8);  // eviction cut search: 6 passes of 2048 weighted bins
     L.cand_key = take((size_t)kEvictCand * 8);
@@ -361,6 +364,9 @@ extern "C" int kLPM_build_tree(kLPM_tree **out, const kLPM_config *cfg, void *ar
     ws.next_tok = (int32_t *)(base + L.next_tok);
     ws.lcp_lead = (int32_t *)(base + L.lcp_lead);
     ws.lcp_tok = (int32_t *)(base + L.lcp_tok);
+    ws.p_off = (int64_t *)(base + L.p_off);
+    ws.p_len = (int32_t *)(base + L.p_len);
+    ws.p_de = (int32_t *)(base + L.p_de);
     ws.resv_id = (int32_t *)(base + L.resv_id);
     ws.evict_hist = (int64_t *)(base + L.evict_hist);
     ws.cand_key = (uint64_t *)(base + L.cand_key);
