@@ -502,7 +502,7 @@ def bench_cfg2(args) -> int:
             self.mark(s, 1)
             if args.dynamic:  # Algorithm 1 on scores that follow the picks made so far in the bin
                 K.kLPM_select_dynamic(q, sched.match_len, sched.last_node, k, batch, sched.phase, dyn, sched.batch_idx,
-                                      sched.n_selected, dyn_ws, dyn_bytes)
+                                      sched.n_selected, dyn_ws, dyn_bytes, flags=K.KLPM_SELECT_FIFO, max_match=max_len)
             else:
                 if score is not None:  # hit rate instead of match length (the wording of Algorithm 1)
                     K.kLPM_score_hit_rate(sched.match_len, q.len, n0, rate_bits, score)

@@ -193,12 +193,18 @@ int kLPM_select_static(const uint64_t *arrival, const int32_t *match_len, const 
  *   dyn_match   DEVICE [q->n] out: for a picked query its score when it was picked (its overlap
  *               credit: it costs len - dyn_match), for the others their final score
  *   k, k_dev, phase_inout, batch_idx, n_selected   as in kLPM_select
+ *   flags, max_match   as in kLPM_select: with KLPM_SELECT_FIFO and a bound max_match > 0 on the match
+ *               lengths, a queue of more than 4096 entries is not sorted by arrival and its match
+ *               lengths only over the bits the bound needs; a queue that breaks the promise, or a
+ *               match length above the bound, gives *n_selected = -1 and leaves the phase alone.
+ *               Without them (0, 0) any queue order is accepted
  *   workspace   DEVICE, 256-byte aligned, >= kLPM_select_dynamic_workspace_bytes(q->n)
  */
 int kLPM_select_dynamic_workspace_bytes(int32_t n, size_t *out_bytes);
 int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node, uint32_t k,
-                        const uint32_t *k_dev, int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
-                        int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream);
+                        const uint32_t *k_dev, int32_t batch, uint32_t flags, int32_t max_match, uint32_t *phase_inout,
+                        int32_t *dyn_match, int32_t *batch_idx, int32_t *n_selected, void *workspace,
+                        size_t workspace_bytes, kLPM_stream stream);
 
 /*
  * Prefix-cache hit *rate* (the wording of Algorithm 1) as a score for kLPM_select:

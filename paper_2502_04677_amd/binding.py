@@ -93,7 +93,7 @@ def load_library() -> C.CDLL:
     lib.kLPM_adapt_observe.argtypes = [vp, C.POINTER(Queue), vp, vp, i32, vp, i32, vp]
     lib.kLPM_adapt_read.argtypes = [vp, C.POINTER(AdaptStats), vp]
     lib.kLPM_select_dynamic_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
-    lib.kLPM_select_dynamic.argtypes = [C.POINTER(Queries), vp, vp, u32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.kLPM_select_dynamic.argtypes = [C.POINTER(Queries), vp, vp, u32, vp, i32, u32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.kLPM_score_hit_rate.argtypes = [vp, vp, i32, vp, i32, vp, vp]
     lib.kLPM_tie_keys.argtypes = [C.c_uint64, C.c_uint64, vp, i32, vp, vp, vp]
     lib.kLPM_commit.argtypes = [vp, C.POINTER(Queries), vp, vp, i32, vp, vp]
@@ -276,10 +276,10 @@ def kLPM_select_dynamic_workspace_bytes(n: int) -> int:
 def kLPM_select_dynamic(q: DeviceQueries, match_len: torch.Tensor, last_node: torch.Tensor, k: int, batch: int,
                         phase_inout: torch.Tensor, dyn_match: torch.Tensor, batch_idx: torch.Tensor,
                         n_selected: torch.Tensor, workspace: Tuple[torch.Tensor, int], workspace_bytes: int,
-                        stream=None, k_dev: Optional[int] = None) -> None:
+                        stream=None, k_dev: Optional[int] = None, flags: int = 0, max_match: int = 0) -> None:
     qs = q.c_struct()
     _check(_lib.kLPM_select_dynamic(C.byref(qs), _ptr(match_len), _ptr(last_node), C.c_uint32(k & 0xFFFFFFFF),
-                                    C.c_void_p(k_dev), int(batch),
+                                    C.c_void_p(k_dev), int(batch), C.c_uint32(flags), int(max_match),
                                     _ptr(phase_inout), _ptr(dyn_match), _ptr(batch_idx), _ptr(n_selected),
                                     C.c_void_p(workspace[1]), int(workspace_bytes), _stream(stream)),
            "kLPM_select_dynamic")

@@ -35,11 +35,12 @@ int commit_pipeline(kLPM_tree *t, const QView &q, const int32_t *batch_idx, cons
 // arrival, index), and every query's position in each.  The arrays live in the caller's workspace.
 struct SelectOrders {
     const uint32_t *order_a, *order_l, *rank_a, *rank_l;
+    const int32_t *violated;  // NULL, or DEVICE [1]: non-zero when a promise about the queue did not hold
 };
 size_t select_sort_workspace_bytes(int32_t n);
 int build_select_orders(const uint64_t *arrival, const int32_t *score, const uint32_t *tie_key, int32_t n,
                         const int32_t *n_live, bool want_l, void *workspace, size_t workspace_bytes,
-                        hipStream_t stream, SelectOrders *out);
+                        hipStream_t stream, SelectOrders *out, bool arrival_ordered = false, int32_t max_score = 0);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? KLPM_OK : KLPM_EHIP; }
 

@@ -37,6 +37,7 @@ struct SelectWs {
     uint32_t *rank_a, *rank_l;
     uint32_t *hist;
     int32_t *skip;
+    int32_t *viol;
 };
 
 __global__ __launch_bounds__(256) void k_sel_init(const uint64_t *__restrict__ arrival, LiveN nn,
@@ -66,6 +67,35 @@ __global__ __launch_bounds__(256) void k_sel_lkeys(const uint32_t *__restrict__ 
         key[r] = tie_key ? ((inv << 32) | (uint64_t)tie_key[i]) : inv;
         val[r] = i;
     }
+}
+
+__global__ void k_sel_zero_flag(int32_t *__restrict__ viol) {
+    if (threadIdx.x < 2) viol[threadIdx.x] = 0;
+}
+__global__ __launch_bounds__(256) void k_sel_rank_l(const uint32_t *__restrict__ order_l, LiveN nn,
+                                                    uint32_t *__restrict__ rank_l) {
+    const int32_t n = nn.get();
+    const int32_t r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < n) rank_l[order_l[r]] = (uint32_t)r;
+}
+// A queue promised to be in arrival order: the oldest-first order is the index order, and the keys of
+// the longest-match order, max_score - score, are laid out in it.  The promise and the bound are checked.
+__global__ __launch_bounds__(256) void k_sel_fifo_keys(const uint64_t *__restrict__ arrival,
+                                                       const int32_t *__restrict__ score, LiveN nn, int32_t max_score,
+                                                       uint64_t *__restrict__ key, uint32_t *__restrict__ val,
+                                                       uint32_t *__restrict__ order_a, uint32_t *__restrict__ rank_a,
+                                                       int32_t *__restrict__ viol) {
+    const int32_t n = nn.get();
+    const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    int32_t m = score[i];
+    if (m < 0) m = 0;
+    const bool bad = m > max_score || (i + 1 < n && arrival[i] > arrival[i + 1]);
+    key[i] = (uint64_t)(uint32_t)(max_score - (bad ? max_score : m));
+    val[i] = (uint32_t)i;
+    order_a[i] = (uint32_t)i;
+    rank_a[i] = (uint32_t)i;
+    if (bad) viol[1] = 1;
 }
 
 __global__ __launch_bounds__(256) void k_sel_ranks(const uint32_t *__restrict__ order_a,
@@ -1493,6 +1523,7 @@ static void carve(SelectWs &ws, char *base, int32_t n, size_t *used) {
     ws.rank_l = (uint32_t *)take(nn * 4);
     ws.hist = (uint32_t *)take((size_t)256 * nblk * 4);
     ws.skip = (int32_t *)take(256);
+    ws.viol = (int32_t *)take(256);
     *used = o;
 }
 
@@ -1507,13 +1538,34 @@ size_t select_sort_workspace_bytes(int32_t n) {
 // Without `want_l` only the oldest-first order is built (the other pointers then alias it).
 int build_select_orders(const uint64_t *arrival, const int32_t *score, const uint32_t *tie_key, int32_t n,
                         const int32_t *n_live, bool want_l, void *workspace, size_t workspace_bytes,
-                        hipStream_t stream, SelectOrders *out) {
+                        hipStream_t stream, SelectOrders *out, bool arrival_ordered, int32_t max_score) {
     SelectWs ws;
     size_t need = 0;
     carve(ws, (char *)workspace, n, &need);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return KLPM_EARENA;
     const LiveN nn{n, n_live};
     const uint32_t *order_a = ws.val_a, *order_l = ws.val_a;
+    out->violated = nullptr;
+    if (arrival_ordered && want_l && !tie_key && max_score > 0 && n > kSmallOrdersN) {
+        // no sort by arrival, and only as many passes over the scores as the bound needs
+        int bits = 1;
+        while (bits < 31 && (max_score >> bits) != 0) ++bits;
+        const unsigned g = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(k_sel_zero_flag, dim3(1), dim3(kWave), 0, stream, ws.viol);
+        hipLaunchKernelGGL(k_sel_fifo_keys, dim3(g), dim3(256), 0, stream, arrival, score, nn, max_score, ws.key_a, ws.val_c,
+                           ws.val_a, ws.rank_a, ws.viol);
+        bool lfirst = true;
+        int rc = radix_sort(ws.key_a, ws.val_c, ws.key_b, ws.val_b, nn, (bits + 7) / 8, ws, stream, &lfirst);
+        if (rc) return rc;
+        order_l = lfirst ? ws.val_c : ws.val_b;
+        hipLaunchKernelGGL(k_sel_rank_l, dim3(g), dim3(256), 0, stream, order_l, nn, ws.rank_l);
+        out->order_a = ws.val_a;
+        out->order_l = order_l;
+        out->rank_a = ws.rank_a;
+        out->rank_l = ws.rank_l;
+        out->violated = ws.viol + 1;
+        return check_launch();
+    }
     if (n > 0 && n <= kSmallOrdersN) {
         hipLaunchKernelGGL(k_orders_small, dim3(1), dim3(kSmallOrdersThreads), 0, stream, arrival, score, tie_key, nn,
                            want_l ? 1 : 0, ws.val_a, ws.val_c, ws.rank_a, ws.rank_l);

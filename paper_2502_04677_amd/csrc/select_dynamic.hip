@@ -149,14 +149,15 @@ __global__ __launch_bounds__(256) void k_dyn_scatter(LiveQ nn, DynWs ws) {
     if (at >= 0 && at < n) ws.members[at] = i;
 }
 
-// loads and stores of the arrays the walking wavefront both writes and reads
+// loads and stores of the arrays the walking wavefront both writes and reads (one wavefront: nobody else
+// looks at them while the kernel runs, so workgroup scope orders all there is to order)
 template <typename T>
 __device__ __forceinline__ T coh_load(const T *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 template <typename T>
 __device__ __forceinline__ void coh_store(T *p, T v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 __device__ __forceinline__ uint64_t pack_key(int32_t score, uint32_t rank_a) {
@@ -175,6 +176,10 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
     const int32_t nb = batch < n ? batch : n;
     const bool lpm_only = (k == 0u || k == 0xFFFFFFFFu);
     const uint32_t phase = lpm_only ? 0u : (*phase_inout % k);
+    if (ord.violated && *ord.violated) {  // the caller's promise about the queue does not hold: select nothing, say so
+        if (lane == 0) *n_selected = -1;
+        return;
+    }
     for (int32_t w = lane; w < (n + 15) / 16; w += kWave) st[w] = 0u;
     __syncthreads();
     if (lane == 0) {
@@ -190,8 +195,42 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
     uint64_t kb = ~0ull;
     int32_t pb = -1;
     bool kb_valid = true;
+    // Each order is looked at through a window of 64 consecutive entries held in registers (lane = entry;
+    // what is read there never changes during the walk: the query, its place in the other order, whether it
+    // has a group, its match length); a window is read again once the cursor has moved kReload entries into
+    // it.  What does change - picked, boosted - is two bits per query in LDS.  Entries that a cursor has
+    // passed are picked (oldest-first order) or picked or boosted (longest-match order), so they drop out
+    // as candidates by their bits alone, wherever the window starts.
+    constexpr int32_t kReload = 16;
+    int32_t wa = -kWave, wl = -kWave;
+    bool a_in = false, l_in = false;
+    uint32_t a_el = 0, a_other = 0, l_el = 0, l_other = 0;
+    int32_t a_multi = 0, l_multi = 0;
+    uint64_t l_key = ~0ull;
     while (j < nb) {
         const bool oldest = !lpm_only && pos == 0u;
+        if (ia - wa >= kReload || ia < wa) {
+            wa = ia;
+            a_in = wa + lane < n;
+            a_el = 0; a_other = 0; a_multi = 0;
+            if (a_in) {
+                a_el = ord.order_a[wa + lane];
+                a_other = ord.rank_l[a_el];
+                a_multi = ws.multi[a_el];
+            }
+        }
+        if (il - wl >= kReload || il < wl) {
+            wl = il;
+            l_in = wl + lane < n;
+            l_el = 0; l_other = 0; l_multi = 0; l_key = ~0ull;
+            if (l_in) {
+                l_el = ord.order_l[wl + lane];
+                l_other = ord.rank_a[l_el];
+                l_multi = ws.multi[l_el];
+                const int32_t ml = match_len[l_el];
+                l_key = pack_key(ml < 0 ? 0 : ml, l_other);
+            }
+        }
         if (!kb_valid) {
             kb = ~0ull;
             pb = -1;
@@ -210,25 +249,12 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         // A pick made in bulk must be one that needs no bookkeeping: it has no group (nobody gains
         // from it), it is not in the boosted set, and for a longest-match pick no boosted query
         // ranks before it.
+        const uint32_t sa = a_in ? state(a_el) : 1u, sl = l_in ? state(l_el) : 1u;
         // ---- whole k-cycles at once
         if (oldest && k > 1u && (uint32_t)(nb - j) >= k && km1 <= (uint32_t)kWave) {
-            const int32_t ra = ia + lane, rl = il + lane;
-            uint32_t a_el = 0, l_el = 0, a_other = 0, l_other = 0;
-            bool cand_a = false, cand_l = false, hard_a = false, hard_l = false;
-            if (ra < n) {
-                a_el = ord.order_a[ra];
-                const uint32_t sa = state(a_el);
-                cand_a = (sa & 1u) == 0u;
-                a_other = ord.rank_l[a_el];
-                hard_a = ws.multi[a_el] != 0 || (sa & 2u) != 0u;
-            }
-            if (rl < n) {
-                l_el = ord.order_l[rl];
-                cand_l = state(l_el) == 0u;
-                l_other = ord.rank_a[l_el];
-                int32_t ml = match_len[l_el];
-                hard_l = ws.multi[l_el] != 0 || pack_key(ml < 0 ? 0 : ml, l_other) > kb;
-            }
+            const bool cand_a = a_in && (sa & 1u) == 0u, cand_l = l_in && sl == 0u;
+            const bool hard_a = a_multi != 0 || (sa & 2u) != 0u;
+            const bool hard_l = l_multi != 0 || l_key > kb;
             const uint64_t mask_a = __ballot(cand_a), mask_l = __ballot(cand_l);
             int32_t c = (int32_t)__popcll(mask_a);
             const int32_t by_l = (int32_t)((uint32_t)__popcll(mask_l) / km1), by_b = (int32_t)((uint32_t)(nb - j) / k);
@@ -247,8 +273,8 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                 if (c > 0) {
                     const int32_t take_l = c * (int32_t)km1;
                     const bool ch_a = cand_a && my_a < c, ch_l = cand_l && my_l < take_l;
-                    const int32_t ia_end = ia + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
-                    const int32_t il_end = il + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
+                    const int32_t ia_end = wa + (int32_t)__builtin_ctzll(__ballot(cand_a && my_a == c - 1)) + 1;
+                    const int32_t il_end = wl + (int32_t)__builtin_ctzll(__ballot(cand_l && my_l == take_l - 1)) + 1;
                     // the two streams must not meet inside the consumed stretches
                     const uint64_t clash = __ballot((ch_a && a_other < (uint32_t)il_end) || (ch_l && l_other < (uint32_t)ia_end));
                     if (clash == 0ull) {
@@ -269,31 +295,22 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         }
         // ---- a run of picks of one kind, up to the first pick that needs bookkeeping
         bool single_from_set = false;
-        // (what this window's lanes have read is kept for the single pick further down)
-        uint32_t w_el = 0;
+        // (what this window's lanes hold is kept for the single pick further down)
+        const uint32_t w_el = oldest ? a_el : l_el;
+        const int32_t w_multi = oldest ? a_multi : l_multi;
+        const int32_t w_base = oldest ? wa : wl;
         uint64_t w_key = ~0ull, w_mask = 0ull;
-        int32_t w_multi = 0;
         {
             const uint32_t run = oldest ? (k == 1u ? (uint32_t)(nb - j) : 1u) : (lpm_only ? (uint32_t)(nb - j) : k - pos);
             const int32_t want = (int32_t)(run < (uint32_t)(nb - j) ? run : (uint32_t)(nb - j));
-            const int32_t r = (oldest ? ia : il) + lane;
-            uint32_t el = 0;
-            bool cand = false, hard = false;
-            if (r < n) {
-                el = oldest ? ord.order_a[r] : ord.order_l[r];
-                const uint32_t sv = state(el);
-                cand = oldest ? ((sv & 1u) == 0u) : (sv == 0u);
-                w_multi = ws.multi[el];
-                hard = w_multi != 0;
-                if (oldest) {
-                    hard = hard || (sv & 2u) != 0u;
-                } else if (cand) {
-                    int32_t ml = match_len[el];
-                    w_key = pack_key(ml < 0 ? 0 : ml, ord.rank_a[el]);
-                    hard = hard || (n_boost > 0 && w_key > kb);
-                }
+            const bool cand = oldest ? (a_in && (sa & 1u) == 0u) : (l_in && sl == 0u);
+            bool hard = w_multi != 0;
+            if (oldest) {
+                hard = hard || (sa & 2u) != 0u;
+            } else if (cand) {
+                w_key = l_key;
+                hard = hard || (n_boost > 0 && w_key > kb);
             }
-            w_el = el;
             const uint64_t mask = __ballot(cand), hmask = __ballot(cand && hard);
             w_mask = mask;
             const int32_t my = (int32_t)__popcll(mask & ((1ull << lane) - 1ull));
@@ -304,17 +321,17 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                 take = clean < take ? clean : take;
             }
             if (take > 0) {
-                if (cand && my < take) { batch_idx[j + my] = (int32_t)el; set_bits(el, 1u); }
+                if (cand && my < take) { batch_idx[j + my] = (int32_t)w_el; set_bits(w_el, 1u); }
                 __syncthreads();
-                const int32_t adv = (int32_t)__builtin_ctzll(__ballot(cand && my == take - 1)) + 1;
-                if (oldest) ia += adv; else il += adv;
+                const int32_t next = w_base + (int32_t)__builtin_ctzll(__ballot(cand && my == take - 1)) + 1;
+                if (oldest) ia = next; else il = next;
                 j += take;
                 pos = lpm_only ? 0u : (uint32_t)(((uint64_t)pos + (uint64_t)take) % k);
                 continue;
             }
             if (mask == 0ull) {  // nothing pickable in this window
-                if ((oldest ? ia : il) + kWave < n) {  // look further along the order
-                    if (oldest) ia += kWave; else il += kWave;
+                if (w_base + kWave < n) {  // look further along the order
+                    if (oldest) ia = w_base + kWave; else il = w_base + kWave;
                     continue;
                 }
                 if (oldest) break;          // unreachable while nb <= n
@@ -331,7 +348,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
             const int f = (int)__builtin_ctzll(w_mask);  // not empty: see the run block above
             p = __shfl((int32_t)w_el, f);
             p_multi = __shfl(w_multi, f);
-            ia += f + 1;
+            ia = w_base + f + 1;
         } else {
             // head of the static longest-match order among the queries never boosted, against the
             // best boosted query
@@ -342,7 +359,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                 const int f = (int)__builtin_ctzll(w_mask);  // not empty: see the run block above
                 c1 = __shfl((int32_t)w_el, f);
                 c1_multi = __shfl(w_multi, f);
-                il += f;  // stays on it until it is picked
+                il = w_base + f;  // stays on it until it is picked
                 key1 = (uint64_t)(((uint64_t)(uint32_t)__shfl((int32_t)(w_key >> 32), f) << 32) |
                                   (uint64_t)(uint32_t)__shfl((int32_t)(uint32_t)w_key, f));
             }
@@ -461,7 +478,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                 if (kb_valid && bk < kb) { kb = bk; pb = bp; }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");  // this pick's stores before the next reads of any lane
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");  // this pick's stores before the next reads of any lane
         __syncthreads();
     }
 }
@@ -502,8 +519,9 @@ extern "C" int kLPM_select_dynamic_workspace_bytes(int32_t n, size_t *out_bytes)
 }
 
 extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_len, const int32_t *last_node, uint32_t k,
-                                   const uint32_t *k_dev, int32_t batch, uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx,
-                                   int32_t *n_selected, void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
+                                   const uint32_t *k_dev, int32_t batch, uint32_t flags, int32_t max_match,
+                                   uint32_t *phase_inout, int32_t *dyn_match, int32_t *batch_idx, int32_t *n_selected,
+                                   void *workspace, size_t workspace_bytes, kLPM_stream stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     if (!q || q->n < 0 || q->n > kDynMaxN || q->n_tokens < 0 || batch < 0 || !phase_inout || !n_selected) return KLPM_EINVAL;
     const int32_t n = q->n;
@@ -520,7 +538,8 @@ extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_l
     qv.tokens = q->tokens; qv.off = q->off; qv.len = q->len; qv.n_tokens = q->n_tokens; qv.n = n; qv.n_live = q->n_live;
     SelectOrders ord;
     // the static orders are taken over the match lengths against the cache
-    int rc = build_select_orders(q->arrival, match_len, nullptr, n, q->n_live, true, workspace, sort_bytes, stream, &ord);
+    int rc = build_select_orders(q->arrival, match_len, nullptr, n, q->n_live, true, workspace, sort_bytes, stream, &ord,
+                                 (flags & KLPM_SELECT_FIFO) != 0, max_match);
     if (rc) return rc;
     if (n > 0) {
         const int64_t work = (int64_t)d.table_mask + 1 > n ? (int64_t)d.table_mask + 1 : n;

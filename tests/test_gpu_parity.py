@@ -975,7 +975,8 @@ def test_steps_with_hit_rate_score_and_random_ties_keep_the_tree_in_step():
 
 
 # ----------------------------------------------------------------------------- in-batch rescoring
-def _check_dynamic(s, ref, q, hq, ks, batches, live=None):
+def _check_dynamic(s, ref, q, hq, ks, batches, live=None, fifo_bound=0):
+    """``fifo_bound`` > 0: the queue is promised to be in arrival order with match lengths up to that bound."""
     dev = "cuda:0"
     n = q.n if live is None else min(live, q.n)
     live_d = None if live is None else torch.full((1,), live, dtype=torch.int32, device=dev)
@@ -991,7 +992,8 @@ def _check_dynamic(s, ref, q, hq, ks, batches, live=None):
             out = torch.full((max(batch, 1),), -9, dtype=torch.int32, device=dev)
             s.set_phase(1)
             dyn.fill_(-1)
-            K.kLPM_select_dynamic(ql, s.match_len, s.last_node, k, batch, s.phase, dyn, out, s.n_selected, ws, ws_bytes)
+            K.kLPM_select_dynamic(ql, s.match_len, s.last_node, k, batch, s.phase, dyn, out, s.n_selected, ws, ws_bytes,
+                                  flags=K.KLPM_SELECT_FIFO if fifo_bound else 0, max_match=fifo_bound)
             idx_ref, ph_ref, sc_ref = oracle.select_dynamic(hq.tokens, hq.off[:n], hq.len[:n], hq.arrival[:n], m_ref, k,
                                                             batch, 1)
             got_n = int(s.n_selected.item())
@@ -1060,6 +1062,38 @@ def test_dynamic_select_medium_queue_then_commit():
     ref.commit(hq2.tokens, hq2.off, hq2.len, idx_ref, w.budget)
     assert s.read_stats().device_error == 0
     _same_tree(s, ref, big=True)
+
+
+def test_dynamic_select_on_an_arrival_ordered_queue():
+    """The same selection told that the queue is in arrival order and how long a match can be (no sort by
+    arrival, fewer passes over the match lengths); a queue that breaks either promise is refused."""
+    w = W.config1(scale=0.5)
+    hq = w.queries
+    order = np.argsort(hq.arrival, kind="stable")
+    hq = W.take_prompts(hq, order)
+    w2 = W.Workload("cfg1-sorted", w.cache, hq, w.k, 256, w.budget)
+    s, ref, q = _setup(w2, max_batch=256)
+    assert hq.n > 4096
+    bound = int(hq.len.max())
+    _say(f"dynamic, arrival-ordered: {hq.n} waiting, bound {bound}")
+    _check_dynamic(s, ref, q, hq, (1, 4, K_INF), (256,), fifo_bound=bound)
+    _check_dynamic(s, ref, q, hq, (3,), (100,), live=hq.n - 1000, fifo_bound=bound)
+    ws_bytes = K.kLPM_select_dynamic_workspace_bytes(q.n)
+    ws = K.alloc_aligned(ws_bytes, "cuda:0")
+    dyn = torch.zeros(q.n, dtype=torch.int32, device="cuda:0")
+    m = s.match(q, want_nodes=True).cpu().numpy()
+    s.set_phase(2)
+    K.kLPM_select_dynamic(q, s.match_len, s.last_node, 4, 64, s.phase, dyn, s.batch_idx, s.n_selected, ws, ws_bytes,
+                          flags=K.KLPM_SELECT_FIFO, max_match=max(1, int(m.max()) - 1))
+    assert int(s.n_selected.item()) == -1 and s.phase_value() == 2  # a match length above the bound
+    arr = hq.arrival.copy()
+    arr[hq.n // 2] = arr[hq.n // 2 + 1] + 7
+    qbad = K.DeviceQueries(q.tokens, q.off, q.len, torch.from_numpy(arr.view(np.int64)).cuda(), q.n)
+    K.kLPM_select_dynamic(qbad, s.match_len, s.last_node, 4, 64, s.phase, dyn, s.batch_idx, s.n_selected, ws, ws_bytes,
+                          flags=K.KLPM_SELECT_FIFO, max_match=bound)
+    assert int(s.n_selected.item()) == -1 and s.phase_value() == 2  # arrival order broken
+    K.kLPM_select_dynamic(qbad, s.match_len, s.last_node, 4, 64, s.phase, dyn, s.batch_idx, s.n_selected, ws, ws_bytes)
+    assert int(s.n_selected.item()) == 64  # (no promise made: any order is accepted)
 
 
 # ----------------------------------------------------------------------------- serving-side variants
