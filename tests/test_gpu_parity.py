@@ -509,6 +509,39 @@ def test_config4_full_size_online_stream():
     _run_stream(stream, 8192, snapshot_every=100)
 
 
+@pytest.mark.parametrize("n", [150_000, 1_000_000])
+def test_select_long_arrival_ordered_queues(n):
+    """Queues long enough that every workgroup of the sweeps takes several rounds over its stretch; plain
+    scores (one level), scores beyond one level's range (two levels) and tie keys (five levels)."""
+    rng = np.random.default_rng(77 + n)
+    arrival = np.sort(rng.integers(0, n // 3, size=n)).astype(np.uint64)
+    d_arr = torch.from_numpy(arrival.view(np.int64)).cuda()
+    ws_bytes = K.kLPM_select_workspace_bytes(n)
+    ws = K.alloc_aligned(ws_bytes, "cuda:0")
+    phase = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    nsel = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for mmax, ties in ((6000, False), (300_000, False), (50, True)):
+        m = rng.integers(0, mmax + 1, size=n).astype(np.int32)
+        m[rng.integers(0, n, size=n // 2)] = 0
+        m[rng.integers(0, n, size=n // 50)] = mmax  # a tie class at the top, larger than some batches
+        tie = rng.integers(0, 2**32, size=n, dtype=np.uint64).astype(np.uint32) if ties else None
+        d_m = torch.from_numpy(m).cuda()
+        d_tie = None if tie is None else torch.from_numpy(tie.view(np.int32)).cuda()
+        for k, batch in ((4, 300), (8, 4096), (0, 1000)):
+            if n > 500_000 and batch > 1000:
+                continue  # (the oracle's literal loop is O(batch x n))
+            ph = int(rng.integers(0, max(k, 1)))
+            out = torch.full((batch,), -1, dtype=torch.int32, device="cuda:0")
+            phase.fill_(ph)
+            ws[0].fill_(0x5A)
+            K.kLPM_select(d_arr, d_m, n, k, batch, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO,
+                          max_match=mmax, tie_key=d_tie)
+            idx_ref, ph_ref = oracle.select(arrival, m, k, batch, ph, tie_key=tie)
+            assert int(nsel.item()) == idx_ref.shape[0], (n, mmax, k, batch)
+            assert out.cpu().numpy().tolist() == idx_ref.tolist(), (n, mmax, ties, k, batch, ph)
+            assert int(phase.cpu().numpy().view(np.uint32)[0]) == ph_ref
+
+
 @pytest.mark.parametrize("n,boost", [(9000, 0), (9000, 40), (30000, 8), (30000, 300), (70000, 0), (70000, 60)])
 def test_select_when_both_orders_reach_the_same_queries(n, boost):
     """Alg. 1 on arrival-ordered queues in which some of the oldest queries are also among the longest
