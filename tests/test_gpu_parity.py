@@ -1374,14 +1374,15 @@ def test_groups_larger_than_a_wavefront():
         _check_step(s, ref, q2, tail, 1, n // 2, 0, 1 << 40, fifo=True)
 
 
-@pytest.mark.parametrize("n_prompts,batch", [(900, 450), (3000, 1500)])
+@pytest.mark.parametrize("n_prompts,batch", [(900, 450), (3000, 1500), (1100, 513), (2100, 1023), (4200, 2047), (4200, 2049)])
 def test_batches_that_share_new_prefixes_at_several_levels(n_prompts, batch):
     """Admitted prompts of the shape prefix + first c tokens of a donor string + own tail, several per
     donor with different c, some equal, some a prefix of another: behind the place where they leave
     the old tree they share new prefixes of different lengths, level below level.  The cached prompt
     of a prefix either continues it (the batch stops inside that edge, at the prefix end and at
-    other depths) or ends with it (the batch stops at a node boundary).  Batches of up to 1,024
-    prompts and larger ones take different structure passes."""
+    other depths) or ends with it (the batch stops at a node boundary).  Batches of up to 512, 1,024
+    and 2,048 prompts and larger ones take different plan kernels and structure passes; sizes that are
+    no multiple of the plan's group of four leave its last workgroup a partial group."""
     rng = np.random.default_rng(97)
     n_pref = 12
     prefixes = [rng.integers(0, 50, size=int(rng.integers(40, 300))).tolist() for _ in range(n_pref)]
