@@ -2316,6 +2316,27 @@ __global__ __launch_bounds__(kFusedThreads) void k_commit_one(TreeView tv, QView
                                                               int64_t protect, int tick_bits, int final_shift,
                                                               int depth_bits, int may_evict,
                                                               kLPM_stats *__restrict__ stats_out) {
+    // The steps below are chains of dependent reads of a few words each, and what they read was last
+    // written by other kernels, possibly through another XCD's L2: every read would come from memory.  One
+    // read per 64-byte line of everything they may touch (the node arrays and the child table of a small
+    // tree, the commit's state and per-prompt records: some tens of KB), asked for at once up front, brings
+    // it close before it is needed (measured on a Def. 3 queue: 27.4 -> 22.5 us for the whole kernel).
+    {
+        int32_t acc = 0;
+        const int t = threadIdx.x;
+        const int32_t mn = tv.max_nodes;
+        for (int32_t i = t * 16; i < mn; i += kFusedThreads * 16)
+            acc += tv.parent[i] + tv.edge_len[i] + tv.depth_end[i] + tv.slot_of[i] + tv.free_stack[i];
+        for (int32_t i = t * 8; i < mn; i += kFusedThreads * 8) acc += (int32_t)tv.tick[i] + (int32_t)tv.edge_off[i];
+        for (uint32_t i = t * 2u; i <= tv.slot_mask; i += kFusedThreads * 2u) acc += (int32_t)tv.slots[i].key;
+        if (t * 16 < (int)(sizeof(DevState) / 4)) acc += reinterpret_cast<const int32_t *>(tv.st)[t * 16];
+        if (t == 0) {
+            acc += ws.bm_len[0] + ws.bm_node[0] + (int32_t)ws.tail_off[0] + (int32_t)ws.gkey[0] + ws.end_node[0] + ws.used[0] +
+                   ws.leaf_tok[0] + ws.next_tok[0] + ws.lcp_lead[0] + ws.resv_id[0] + (int32_t)ws.p_off[0] + ws.p_len[0] +
+                   ws.p_de[0] + ws.cand_id[0] + (int32_t)ws.cand_key[0] + ws.cand_len[0] + ws.cand_slot[0];
+        }
+        asm volatile("" ::"v"(acc));  // (the values are not used; the reads are)
+    }
     // (one workgroup: the barrier between two steps orders what the first wrote before what the second reads)
     plan_copy_body<kFusedThreads, 1>(tv, q, batch_idx, n_selected, batch_cap, ws, hint_len, hint_node);
     __syncthreads();
