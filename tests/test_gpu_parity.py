@@ -509,6 +509,39 @@ def test_config4_full_size_online_stream():
     _run_stream(stream, 8192, snapshot_every=100)
 
 
+def test_select_repeated_on_a_dirty_workspace():
+    """The long-queue selection hands its winners from workgroup to workgroup through flags in the
+    workspace; many calls in a row on the same input, the workspace overwritten with random bytes in
+    between, must all give the oracle's batch."""
+    rng = np.random.default_rng(5)
+    dev = "cuda:0"
+    for n, mmax, ties in ((65536, 8192, False), (40000, 100000, False), (30000, 6000, True)):
+        arrival = np.sort(rng.integers(0, n, size=n)).astype(np.uint64)
+        m = rng.integers(0, mmax + 1, size=n).astype(np.int32)
+        m[rng.integers(0, n, size=n // 3)] = 0
+        m[rng.choice(600, size=40, replace=False)] = mmax - 1  # old queries among the best matches
+        tie = rng.integers(0, 2**32, size=n, dtype=np.uint64).astype(np.uint32) if ties else None
+        d_arr = torch.from_numpy(arrival.view(np.int64)).to(dev)
+        d_m = torch.from_numpy(m).to(dev)
+        d_tie = None if tie is None else torch.from_numpy(tie.view(np.int32)).to(dev)
+        ws_bytes = K.kLPM_select_workspace_bytes(n)
+        ws = K.alloc_aligned(ws_bytes, dev)
+        phase = torch.zeros(1, dtype=torch.int32, device=dev)
+        nsel = torch.zeros(1, dtype=torch.int32, device=dev)
+        ref, ph_ref = oracle.select(arrival, m, 8, 1024, 3, tie_key=tie)
+        ref_t = torch.from_numpy(ref).to(dev)
+        out = torch.empty(1024, dtype=torch.int32, device=dev)
+        wrong = torch.zeros(1, dtype=torch.int64, device=dev)
+        for it in range(400):
+            phase.fill_(3)
+            if it % 5 == 0:
+                ws[0].random_(0, 255)
+            K.kLPM_select(d_arr, d_m, n, 8, 1024, phase, out, nsel, ws, ws_bytes, flags=K.KLPM_SELECT_FIFO, max_match=mmax,
+                          tie_key=d_tie)
+            wrong += (out != ref_t).sum() + (nsel[0] != 1024).long() + (phase[0] != ph_ref).long()
+        assert int(wrong.item()) == 0, (n, mmax, ties)
+
+
 @pytest.mark.parametrize("n", [150_000, 1_000_000])
 def test_select_long_arrival_ordered_queues(n):
     """Queues long enough that every workgroup of the sweeps takes several rounds over its stretch; plain
