@@ -16,6 +16,7 @@
 namespace klpm {
 
 constexpr int32_t kDynMaxN = 262144;  // two state bits per query are kept in LDS (64 KB)
+constexpr int kPairGroup = 8;         // groups of up to this many queries get their pairwise common prefixes before the walk
 
 struct DynWs {
     uint64_t *gk;       // [n] (stop node << 32) | next token
@@ -32,6 +33,10 @@ struct DynWs {
     uint64_t *bkey;     // [n] boosted set: (inverted score, position in the oldest-first order)
     int32_t *bidx;      // [n] boosted set: query index
     int32_t *bpos;      // [n] where a boosted query sits in the set
+    int32_t *bslot;     // [n] boosted set: the query's member record (-1: its group has none)
+    int32_t *gslot;     // [n] where the query sits in `members` (-1: no group)
+    int4 *mrec;         // [n] member records of the small groups, in `members` order: query, oldest-first rank, current score, place in the boosted set
+    int32_t *pair;      // [n][kPairGroup] small groups: common prefix of the member in this place with every member of its group
     uint32_t table_mask;
 };
 
@@ -144,9 +149,46 @@ __global__ __launch_bounds__(256) void k_dyn_scatter(LiveQ nn, DynWs ws) {
     ws.multi[i] = gn > 1 ? 1 : 0;
     ws.gstart[i] = g0;
     ws.gcnt[i] = gn;
+    ws.gslot[i] = -1;
     if (s < 0) return;
     const int32_t at = g0 + atomicAdd(&ws.fill[s], 1);
-    if (at >= 0 && at < n) ws.members[at] = i;
+    if (at >= 0 && at < n) {
+        ws.members[at] = i;
+        ws.gslot[i] = at;
+    }
+}
+
+// Small groups (2 .. kPairGroup queries): every pair's common prefix, found by the whole GPU before the
+// walk (one wavefront per query compares it with the members behind it in its group), and one record per
+// member, so that the walk's rescoring of such a group is one read of records and one row of prefixes
+// instead of a chain of reads and token compares per pick.
+__global__ __launch_bounds__(256) void k_dyn_pairs(QView q, const int32_t *__restrict__ match_len,
+                                                   const uint32_t *__restrict__ rank_a, DynWs ws) {
+    const int32_t n = live_count(q.n, q.n_live);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int32_t i = (int32_t)((blockIdx.x * blockDim.x + threadIdx.x) / kWave);
+    if (i >= n) return;
+    const int32_t s = uni(ws.gslot[i]), g0 = uni(ws.gstart[i]), gn = uni(ws.gcnt[i]);
+    if (s < 0 || gn < 2 || gn > kPairGroup) return;
+    const int32_t a = s - g0;
+    int32_t m = uni(match_len[i]);
+    m = m < 0 ? 0 : m;
+    const int64_t off_i = uni64(q.off[i]);
+    const int32_t len_i = uni(q.len[i]);
+    if (lane == 0) ws.mrec[s] = make_int4(i, (int32_t)rank_a[i], m, -1);
+    const int32_t s0 = m + 1;  // the group shares the cached part and the next token
+    for (int32_t b = a + 1; b < gn; ++b) {
+        const int32_t jq = uni(ws.members[g0 + b]);
+        const int64_t off_j = uni64(q.off[jq]);
+        const int32_t len_j = uni(q.len[jq]);
+        const int32_t lim = (len_i < len_j ? len_i : len_j) - s0;
+        int32_t lcp = s0;
+        if (lim > 0) lcp += wave_common_prefix(q.tokens + off_i + s0, q.tokens + off_j + s0, lim, lane);
+        if (lane == 0) {
+            ws.pair[(size_t)(g0 + a) * kPairGroup + b] = lcp;
+            ws.pair[(size_t)(g0 + b) * kPairGroup + a] = lcp;
+        }
+    }
 }
 
 // loads and stores of the arrays the walking wavefront both writes and reads (one wavefront: nobody else
@@ -207,6 +249,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
     uint32_t a_el = 0, a_other = 0, l_el = 0, l_other = 0;
     int32_t a_multi = 0, l_multi = 0;
     uint64_t l_key = ~0ull;
+    bool after_single = false;  // the pick before was made alone: such picks come in runs, and an attempt at whole cycles costs as much as a pick
     while (j < nb) {
         const bool oldest = !lpm_only && pos == 0u;
         if (ia - wa >= kReload || ia < wa) {
@@ -251,7 +294,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         // ranks before it.
         const uint32_t sa = a_in ? state(a_el) : 1u, sl = l_in ? state(l_el) : 1u;
         // ---- whole k-cycles at once
-        if (oldest && k > 1u && (uint32_t)(nb - j) >= k && km1 <= (uint32_t)kWave) {
+        if (oldest && k > 1u && (uint32_t)(nb - j) >= k && km1 <= (uint32_t)kWave && !after_single) {
             const bool cand_a = a_in && (sa & 1u) == 0u, cand_l = l_in && sl == 0u;
             const bool hard_a = a_multi != 0 || (sa & 2u) != 0u;
             const bool hard_l = l_multi != 0 || l_key > kb;
@@ -327,6 +370,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                 if (oldest) ia = next; else il = next;
                 j += take;
                 pos = lpm_only ? 0u : (uint32_t)(((uint64_t)pos + (uint64_t)take) % k);
+                after_single = false;
                 continue;
             }
             if (mask == 0ull) {  // nothing pickable in this window
@@ -344,6 +388,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
         // ---- one pick; then the rescoring of the pick's group
         int32_t p = -1;
         int32_t p_multi = -1;  // whether the pick has a group, if a lane already knows
+        int32_t p_at = -1;     // its place in the boosted set, if it was taken from there
         if (oldest) {
             const int f = (int)__builtin_ctzll(w_mask);  // not empty: see the run block above
             p = __shfl((int32_t)w_el, f);
@@ -365,6 +410,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
             }
             if (kb < key1) {
                 p = coh_load(&ws.bidx[pb]);
+                p_at = pb;
             } else {
                 p = c1;
                 p_multi = c1_multi;
@@ -372,6 +418,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
             }
         }
         if (p < 0) break;  // unreachable while nb <= n
+        after_single = true;
         p = uni(p);
         const uint32_t sp = state((uint32_t)p);
         if (lane == 0) {
@@ -379,13 +426,16 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
             set_bits((uint32_t)p, 1u);
         }
         if (sp & 2u) {  // leaves the boosted set: the last entry takes its place
-            const int32_t at = uni(coh_load(&ws.bpos[p]));
+            const int32_t at = p_at >= 0 ? p_at : uni(coh_load(&ws.bpos[p]));
             const int32_t last = n_boost - 1;
             if (lane == 0 && at != last) {
                 const int32_t moved = coh_load(&ws.bidx[last]);
+                const int32_t mslot = coh_load(&ws.bslot[last]);
                 coh_store(&ws.bkey[at], coh_load(&ws.bkey[last]));
                 coh_store(&ws.bidx[at], moved);
+                coh_store(&ws.bslot[at], mslot);
                 coh_store(&ws.bpos[moved], at);
+                if (mslot >= 0) coh_store(&ws.mrec[mslot].w, at);
             }
             n_boost = last;
             kb_valid = false;
@@ -403,7 +453,53 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
             const int32_t len_p = uni(q.len[p]);
             const int32_t s0 = uni(match_len[p]) + 1;  // the group shares the cached part and the next token
             const int32_t g0 = uni(ws.gstart[p]), gn = uni(ws.gcnt[p]);  // (requested with the three reads above)
+            const int32_t gs = uni(ws.gslot[p]);
             const uint64_t below = (1ull << lane) - 1ull;
+            if (gn <= kPairGroup && gs >= g0 && gs < g0 + gn) {
+                // a small group: the members' records and the pick's row of common prefixes, one round trip
+                const bool mine = lane < gn;
+                int4 rec = make_int4(-1, 0, 0, -1);
+                int32_t ov = 0;
+                if (mine) {
+                    rec.x = coh_load(&ws.mrec[g0 + lane].x);
+                    rec.y = coh_load(&ws.mrec[g0 + lane].y);
+                    rec.z = coh_load(&ws.mrec[g0 + lane].z);
+                    rec.w = coh_load(&ws.mrec[g0 + lane].w);
+                    ov = ws.pair[(size_t)gs * kPairGroup + lane];
+                }
+                const int32_t i = rec.x;
+                uint32_t si = 1u;
+                if (mine && i >= 0) si = state((uint32_t)i);
+                const bool act = mine && i >= 0 && i != p && (si & 1u) == 0u;
+                const bool upd = act && ov > rec.z;
+                const bool fresh = upd && (si & 2u) == 0u;
+                const uint64_t fm = __ballot(fresh);
+                const int32_t at = fresh ? n_boost + (int32_t)__popcll(fm & below) : rec.w;
+                uint64_t key = ~0ull;
+                if (upd) {
+                    key = pack_key(ov, (uint32_t)rec.y);
+                    coh_store(&dyn[i], ov);
+                    coh_store(&ws.mrec[g0 + lane].z, ov);
+                    coh_store(&ws.bkey[at], key);
+                    if (fresh) {
+                        coh_store(&ws.bidx[at], i);
+                        coh_store(&ws.bslot[at], g0 + lane);
+                        coh_store(&ws.bpos[i], at);
+                        coh_store(&ws.mrec[g0 + lane].w, at);
+                        set_bits((uint32_t)i, 2u);
+                    }
+                }
+                n_boost += (int32_t)__popcll(fm);
+                uint64_t bk = key;
+                int32_t bp = at;
+#pragma unroll
+                for (int d = kWave / 2; d > 0; d >>= 1) {
+                    const uint64_t ok = __shfl_xor(bk, d);
+                    const int32_t op = __shfl_xor(bp, d);
+                    if (ok < bk) { bk = ok; bp = op; }
+                }
+                if (kb_valid && bk < kb) { kb = bk; pb = bp; }
+            } else
             for (int32_t b = 0; b < gn; b += kWave) {
                 const int32_t t = b + lane;
                 const int32_t i = t < gn ? ws.members[g0 + t] : -1;
@@ -461,6 +557,7 @@ __global__ __launch_bounds__(kWave) void k_dyn_walk(QView q, const int32_t *__re
                     coh_store(&ws.bkey[at], key);
                     if (fresh) {
                         coh_store(&ws.bidx[at], i);
+                        coh_store(&ws.bslot[at], -1);
                         coh_store(&ws.bpos[i], at);
                         set_bits((uint32_t)i, 2u);
                     }
@@ -504,6 +601,10 @@ static size_t carve_dyn(DynWs &d, char *base, int32_t n, size_t start) {
     d.bkey = (uint64_t *)take(nn * 8);
     d.bidx = (int32_t *)take(nn * 4);
     d.bpos = (int32_t *)take(nn * 4);
+    d.bslot = (int32_t *)take(nn * 4);
+    d.gslot = (int32_t *)take(nn * 4);
+    d.mrec = (int4 *)take(nn * 16);
+    d.pair = (int32_t *)take(nn * 4 * kPairGroup);
     return o;
 }
 
@@ -551,6 +652,7 @@ extern "C" int kLPM_select_dynamic(const kLPM_queries *q, const int32_t *match_l
         hipLaunchKernelGGL(k_dyn_tile_sums, dim3(tiles), dim3(kDynScanThreads), 0, stream, d);
         hipLaunchKernelGGL(k_dyn_offsets, dim3(tiles), dim3(kDynScanThreads), 0, stream, d);
         hipLaunchKernelGGL(k_dyn_scatter, dim3(g), dim3(256), 0, stream, LiveQ{n, q->n_live}, d);
+        hipLaunchKernelGGL(k_dyn_pairs, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, qv, match_len, ord.rank_a, d);
     }
     hipLaunchKernelGGL(k_dyn_walk, dim3(1), dim3(kWave), 0, stream, qv, match_len, ord, d, dyn_match, KArg{k, k_dev}, batch, phase_inout,
                        batch_idx, n_selected);
