@@ -252,55 +252,70 @@ __global__ __launch_bounds__(kPlanThreads) void k_commit_plan(TreeView tv, QView
 // ------------------------------------------------------------------ end-of-commit maintenance (rare work)
 // Pool compaction, one wavefront per node: every live edge span moves into the other half and the
 // span kept in the child table is patched.
-__device__ __forceinline__ void compact_nodes(const TreeView &tv, DevState *st, int64_t wave, int64_t n_waves, int lane) {
+// Every thread of every workgroup of the launch calls it (blocks of 64 nodes go round the workgroups).
+constexpr int kCompactBlock = 64;  // nodes a workgroup takes room for at once
+__device__ __forceinline__ void compact_nodes(const TreeView &tv, DevState *st) {
+    __shared__ int64_t s_from[kWave], s_to[kWave];
+    __shared__ int32_t s_len[kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave, n_wv = (int)blockDim.x / kWave;
     const int32_t n_slots = st->n_slots;
     const int64_t dst_end = (int64_t)(2 - st->active_half) * tv.pool_half;
-    // 64 nodes at a time, one per lane: their lengths are summed across the wavefront so that the
-    // block takes its room with a single atomic (one atomic per node on the one cursor would be
-    // served one by one, about 13 ns each: a millisecond for a tree of 80,000 nodes)
-    for (int64_t id0 = 1 + wave * kWave; id0 < n_slots; id0 += n_waves * kWave) {
-        const int64_t id = id0 + lane;
-        int32_t len = id < n_slots ? tv.edge_len[id] : 0;
-        len = len > 0 ? len : 0;
-        const int64_t src = id < n_slots ? tv.edge_off[id] : 0;
-        const int32_t slot = id < n_slots ? tv.slot_of[id] : -1;
-        const int64_t incl = wave_inclusive_scan<int64_t>((int64_t)len, lane);
-        const int64_t block_len = __shfl(incl, kWave - 1);
-        if (block_len == 0) continue;
-        int64_t base_dst = 0;
-        if (lane == 0) base_dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)block_len);
-        base_dst = uni64(__shfl(base_dst, 0));
-        if (base_dst + block_len > dst_end) {  // cannot happen while total_tokens <= pool_half
-            if (lane == 0) flag_error(st, 2u);
-            continue;
+    // kCompactBlock nodes at a time, one per lane of the workgroup's first wavefront: their lengths are summed across
+    // the wavefront so that the block takes its room with a single atomic (one atomic per node on the one
+    // cursor would be served one by one, 13 ns each and more under load: a millisecond for a tree of 80,000
+    // nodes; blocks of 16 nodes, tried for the sake of more wavefronts at work, lost to their 4,900 atomics).
+    // The copy of a block is shared out among all wavefronts of the workgroup, a node each in turn: a tree of
+    // 80,000 nodes of 1,300 tokens is only 1,220 blocks, and one wavefront copies two KB at a time.
+    for (int64_t id0 = 1 + (int64_t)blockIdx.x * kCompactBlock; id0 < n_slots; id0 += (int64_t)gridDim.x * kCompactBlock) {
+        if (wv == 0) {
+            const int64_t id = id0 + lane;
+            const bool in = lane < kCompactBlock && id < n_slots;
+            int32_t len = in ? tv.edge_len[id] : 0;
+            len = len > 0 ? len : 0;
+            const int64_t src = in ? tv.edge_off[id] : 0;
+            const int32_t slot = in ? tv.slot_of[id] : -1;
+            const int64_t incl = wave_inclusive_scan<int64_t>((int64_t)len, lane);
+            const int64_t block_len = __shfl(incl, kWave - 1);
+            int64_t base_dst = 0;
+            if (lane == 0 && block_len > 0)
+                base_dst = (int64_t)atomicAdd((unsigned long long *)&st->compact_cursor, (unsigned long long)block_len);
+            base_dst = uni64(__shfl(base_dst, 0));
+            bool ok = true;
+            if (base_dst + block_len > dst_end) {  // cannot happen while total_tokens <= pool_half
+                if (lane == 0) flag_error(st, 2u);
+                ok = false;
+            }
+            const int64_t dst = base_dst + incl - len;
+            s_from[lane] = src;
+            s_to[lane] = dst;
+            s_len[lane] = ok ? len : 0;
+            if (ok && len > 0) {
+                tv.edge_off[id] = dst;
+                if (slot >= 0 && (uint32_t)slot <= tv.slot_mask && tv.slots[slot].child == (int32_t)id) tv.slots[slot].edge_off = dst;
+                else flag_error(st, kDevInternal);
+            }
         }
-        const int64_t dst = base_dst + incl - len;
-        // every node's tokens by the whole wavefront, eight independent rows per trip
-        uint64_t live = __ballot(len > 0);
-        while (live) {
-            const int b = (int)__builtin_ctzll(live);
-            live &= live - 1ull;
-            const int32_t n = uni(__shfl(len, b));
-            const int64_t from = uni64(__shfl(src, b)), to = uni64(__shfl(dst, b));
-            for (int32_t base = 0; base < n; base += 8 * kWave) {
-                int32_t v[8];
+        __syncthreads();
+        // every node's tokens by a whole wavefront, sixteen independent rows per trip
+        for (int b = wv; b < kCompactBlock; b += n_wv) {
+            const int32_t n = s_len[b];
+            if (n <= 0) continue;
+            const int64_t from = s_from[b], to = s_to[b];
+            for (int32_t base = 0; base < n; base += 16 * kWave) {
+                int32_t v[16];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
+                for (int r = 0; r < 16; ++r) {
                     const int32_t i = base + r * kWave + lane;
                     v[r] = tv.pool[from + (i < n ? i : n - 1)];
                 }
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
+                for (int r = 0; r < 16; ++r) {
                     const int32_t i = base + r * kWave + lane;
                     if (i < n) tv.pool[to + i] = v[r];
                 }
             }
         }
-        if (len > 0) {
-            tv.edge_off[id] = dst;
-            if (slot >= 0 && (uint32_t)slot <= tv.slot_mask && tv.slots[slot].child == (int32_t)id) tv.slots[slot].edge_off = dst;
-            else flag_error(st, kDevInternal);
-        }
+        __syncthreads();
     }
 }
 __device__ __forceinline__ void compact_switch(const TreeView &tv, DevState *st) {
@@ -400,8 +415,7 @@ __global__ __launch_bounds__(256) void k_end_commit(TreeView tv, kLPM_stats *__r
     const int n_blocks = need_compact ? (int)gridDim.x : ((int)gridDim.x < kEndBlocks ? (int)gridDim.x : kEndBlocks);
     if ((int)blockIdx.x >= n_blocks) return;
     if (need_compact) {
-        compact_nodes(tv, st, (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave,
-                      (int64_t)gridDim.x * (blockDim.x / kWave), threadIdx.x & (kWave - 1));
+        compact_nodes(tv, st);
         if (last_of(st, 0, n_blocks) && threadIdx.x == 0) compact_switch(tv, st);
     } else if (need_rebuild) {
         // empty the table, wait for every workgroup to have done its share, re-insert the live nodes
@@ -424,7 +438,7 @@ __device__ __forceinline__ void end_commit_small_body(const TreeView &tv, kLPM_s
     const int tid = threadIdx.x;
     const int need_compact = st->need_compact, need_rebuild = st->need_rebuild;
     if (need_compact) {
-        compact_nodes(tv, st, tid / kWave, THREADS / kWave, tid & (kWave - 1));
+        compact_nodes(tv, st);
         __syncthreads();
         if (tid == 0) compact_switch(tv, st);
     } else if (need_rebuild) {
