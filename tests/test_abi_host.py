@@ -101,6 +101,14 @@ def test_null_and_negative_arguments_are_rejected_before_any_launch(K):
     assert lib.kLPM_queue_advance_timed(C.byref(qa), C.byref(no_join), C.byref(q0), None, None, C.c_void_p(8), 0, C.byref(ok), *tail) == -1
     assert lib.kLPM_read_stats(None, None, None) == -1
     assert lib.kLPM_snapshot(None, None, 0, None, None) == -1
+    # in-batch rescoring: no queue, a queue beyond the limit of the state bits, no workspace
+    dyn_tail = (2, None, 8, K.KLPM_SELECT_FIFO, 100, C.c_void_p(8), C.c_void_p(8), C.c_void_p(8), C.c_void_p(8))
+    assert lib.kLPM_select_dynamic(None, None, None, *dyn_tail, None, 0, None) == -1
+    big = binding.Queries(8, 8, 8, 8, 1 << 20, 300_000)
+    assert lib.kLPM_select_dynamic(C.byref(big), C.c_void_p(8), C.c_void_p(8), *dyn_tail, C.c_void_p(256), 1 << 40, None) == -1
+    some = binding.Queries(8, 8, 8, 8, 1 << 20, 5000)
+    assert lib.kLPM_select_dynamic(C.byref(some), C.c_void_p(8), C.c_void_p(8), *dyn_tail, None, 0, None) == -2
+    assert lib.kLPM_select_dynamic(C.byref(some), C.c_void_p(8), C.c_void_p(8), *dyn_tail, C.c_void_p(256), 64, None) == -2
     assert lib.kLPM_destroy(None) == 0
 
 
