@@ -216,6 +216,36 @@ def test_commit_and_evict_equal_path_model(seed):
         assert st.total_tokens <= budget
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_commit_statistics_equal_path_model(seed):
+    """Every counter a commit reports (inserted / evicted tokens, new / evicted nodes, nodes, total, clock)
+    recomputed from the dictionary-of-paths model: insertion and eviction (Sec. 1) applied one after the other
+    there, node and token counts taken before, between and after."""
+    rng = np.random.default_rng(300 + seed)
+    w = W.random_small(seed + 500, n_cache=8, n_query=30, vocab=3, max_len=9)
+    tree, model = oracle.OracleTree(), PathModel()
+    st = tree.build(w.cache)
+    for x in w.cache.as_lists():
+        model.insert(x)
+    assert (st.n_nodes, st.total_tokens, st.clock) == (len(model.nodes), model.total(), w.cache.n)
+    assert (st.inserted_tokens, st.new_nodes, st.evicted_tokens, st.evicted_nodes) == (model.total(), len(model.nodes), 0, 0)
+    q = w.queries
+    qs = q.as_lists()
+    for step in range(5):
+        batch = rng.choice(q.n, size=int(rng.integers(1, 8)), replace=False).astype(np.int32)
+        budget = int(rng.integers(0, model.total() + 10))
+        nodes0, total0, clock0 = len(model.nodes), model.total(), model.clock
+        for i in batch:
+            model.insert(qs[i])
+        nodes1, total1 = len(model.nodes), model.total()
+        gone = model.evict(budget)
+        st = tree.commit(q.tokens, q.off, q.len, batch, budget)
+        assert st.inserted_tokens == total1 - total0 and st.new_nodes == nodes1 - nodes0, step
+        assert st.evicted_tokens == total1 - model.total() and st.evicted_nodes == gone, step
+        assert (st.n_nodes, st.total_tokens, st.clock) == (len(model.nodes), model.total(), clock0 + len(batch)), step
+        assert tree.snapshot() == model.snapshot()
+
+
 def test_commit_invariants_on_config0():
     w = W.config0()
     tree = oracle.OracleTree()
@@ -386,6 +416,35 @@ def test_stream_bin_that_costs_nothing_takes_one_time_unit():
     s = W.generators.Stream("dup", p, np.array([0, 3, 3, 3], dtype=np.int64), 1, 1, 100)
     r = oracle.simulate_stream(s)
     assert r.ttft.tolist() == [3, 4, 5] and r.clock == 5
+
+
+def test_stream_backlog_and_an_empty_stream():
+    """Queries still waiting when the stream ends keep TTFT -1 and admission step -1; a stream that never
+    steps ends at time 0."""
+    p = W.generators._from_lists([[1, 2], [3, 4, 5], [6], [7, 8, 9, 10]], [0, 0, 0, 0])
+    s = W.generators.Stream("backlog", p, np.array([0, 4, 4], dtype=np.int64), 1, 1, 100)  # two steps, one pick each
+    r = oracle.simulate_stream(s)
+    assert r.ttft.tolist() == [2, 5, -1, -1] and r.admitted_step.tolist() == [0, 1, -1, -1] and r.clock == 5
+    empty = W.generators.Stream("none", p, np.array([0], dtype=np.int64), 1, 1, 100)
+    r = oracle.simulate_stream(empty)
+    assert r.clock == 0 and r.ttft.tolist() == [-1] * 4 and r.batches == []
+
+
+def test_percentile_is_nearest_rank():
+    """sorted[ceil(p n) - 1], ranks counted from one; the smallest element for every p <= 1/n."""
+    v = [40, 10, 30, 20]
+    assert [oracle.percentile_nearest_rank(v, p) for p in (0.0, 0.01, 0.25, 0.26, 0.5, 0.51, 0.75, 0.76, 0.99, 1.0)] == [
+        10, 10, 10, 20, 20, 30, 30, 40, 40, 40]
+    assert oracle.percentile_nearest_rank([7, 5], 0.5) == 5 and oracle.percentile_nearest_rank([7], 0.99) == 7
+    assert oracle.percentile_nearest_rank([], 0.5) == 0
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        n = int(rng.integers(1, 40))
+        x = rng.integers(0, 100, size=n)
+        p_ = float(rng.random())
+        # definition: the smallest value with at least a fraction p of the sample at or below it
+        want = min(int(t) for t in x if (x <= t).sum() >= p_ * n)
+        assert oracle.percentile_nearest_rank(x, p_) == want
 
 
 # ----------------------------------------------------------------------------- timed arrivals (Def. 2 timeline)
@@ -703,6 +762,28 @@ def test_eviction_protects_prompts_in_flight(seed):
     assert a.snapshot() == b.snapshot()
 
 
+def test_eviction_protection_edge_windows():
+    """Protection windows of one prompt, of exactly and of more than all admitted prompts, under a budget of
+    zero: the window is the last `protect` ticks (ticks >= clock - protect), tick 0 included when the
+    window reaches back that far."""
+    # three prompts that share nothing: each is one leaf stamped with its own tick 0, 1, 2
+    toks = np.array([1, 1, 1, 2, 2, 3, 3, 3, 3], np.int32)
+    off, ln = np.array([0, 3, 5], np.int64), np.array([3, 2, 4], np.int32)
+    def after(protect):
+        t = oracle.OracleTree()
+        st = t.commit(toks, off, ln, np.arange(3, dtype=np.int32), 0, protect=protect)
+        return sorted(snapshot_paths(t.snapshot()).items()), st
+    paths, st = after(1)
+    assert paths == [((3, 3, 3, 3), 2)] and (st.evicted_nodes, st.evicted_tokens, st.total_tokens) == (2, 5, 4)
+    paths, st = after(2)
+    assert paths == [((2, 2), 1), ((3, 3, 3, 3), 2)] and st.evicted_nodes == 1
+    for protect in (3, 4, 1000):  # the window covers every admitted prompt, the one with tick 0 too
+        paths, st = after(protect)
+        assert paths == [((1, 1, 1), 0), ((2, 2), 1), ((3, 3, 3, 3), 2)] and st.evicted_nodes == 0 and st.total_tokens == 9
+    paths, st = after(0)
+    assert paths == [] and (st.evicted_nodes, st.evicted_tokens, st.total_tokens, st.n_nodes) == (3, 9, 0, 0)
+
+
 def test_token_budget_cut_and_phase():
     ln = np.array([10, 4, 7, 3, 9], np.int32)
     m = np.array([2, 4, 0, 1, 9], np.int32)   # costs 8, 0, 7, 2, 0
@@ -725,7 +806,7 @@ def test_token_budget_cut_and_phase():
     # handing picks back rewinds the k-cycle: selecting n_kept in the first place gives the same phase
     arrival = np.arange(20, dtype=np.uint64)
     mm = rng.integers(0, 9, size=20).astype(np.int32)
-    for k in (1, 2, 3, 7, K_INF):
+    for k in (1, 2, 3, 7, 0, K_INF):
         for phase in (0, 1, 5):
             full, ph_full = oracle.select(arrival, mm, k, 12, phase)
             for kept in (1, 5, 12):
@@ -753,6 +834,29 @@ def test_adaptive_k_starts_round_robin_and_holds_an_arm_for_a_window():
         ad.observe([100 + step])
     assert ks == [1] * 5 + [4] * 5 + [K_INF] * 5
     assert ad.count == [1, 1, 1] and ad.cost == [104, 109, 114]  # the largest TTFT of each window
+
+
+def test_adaptive_k_window_maximum_starts_from_zero_and_draws_follow_the_stated_words():
+    # a window whose admitted queries all had TTFT 0 is a pull of cost 0 (the maximum starts from zero in
+    # every window, it is not carried over and has no floor)
+    ad = oracle.AdaptiveK([2, 8], window=2, explore=0, seed=3)
+    ad.observe([7]); ad.observe([])          # arm 0: cost 7
+    ad.observe([0, 0]); ad.observe([0])      # arm 1: cost 0
+    assert ad.count == [1, 1] and ad.cost == [7, 0] and ad.arm == 1
+    # the exploring draw: word 0 of Philox-4x32-10 at counter (pulls, 0, tag, 0) against `explore`, word 1
+    # picks the arm - recomputed here from the known-answer-pinned generator for a run that always explores
+    # and one that explores about half the time
+    for explore in (1 << 32, 1 << 31):
+        ad = oracle.AdaptiveK([1, 2, 4, 8, 16], window=1, explore=explore, seed=0x1234_5678_9ABC)
+        costs = [50, 10, 40, 30, 20]
+        for c in costs:
+            ad.observe([c])                  # round robin first
+        for pull in range(5, 60):
+            w = oracle.philox4x32_10((pull, 0, oracle.ADAPT_TAG, 0), (0x5678_9ABC, 0x1234))
+            mean = [ad.cost[a] / ad.count[a] for a in range(5)]
+            want = w[1] % 5 if w[0] < explore else mean.index(min(mean))
+            assert ad.arm == want, (explore, pull)
+            ad.observe([costs[ad.arm]])      # every arm keeps its mean
 
 
 def test_adaptive_k_greedy_is_the_exact_argmin_of_the_mean_cost():
