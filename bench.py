@@ -385,6 +385,78 @@ def bench_cfg4(args) -> int:
     return 0
 
 
+def bench_cfg4_overload(args) -> int:
+    """The online stream served with a batch smaller than the arrival rate (Poisson(128) arrivals against a
+    batch of `--overload-batch`, default 96), so that the queue backs up and k decides who waits: the same
+    1,000 steps of arrivals, then steps without arrivals until the queue has drained, once per k of
+    {1, 2, 4, 8, infinity}.  Reports steps/s and the simulated TTFT distribution (uncached-token times) per k;
+    with --cpu-steps > 0 the oracle runs every stream too and every TTFT must agree."""
+    import torch
+
+    import paper_2502_04677_amd as K
+    import workloads as W
+
+    dev = torch.device("cuda:0")
+    base = W.config4_stream()
+    hq = base.queries
+    batch = int(args.overload_batch)
+    drain = (hq.n + batch - 1) // batch - base.steps
+    step_start = np.concatenate([base.step_start, np.full(max(drain, 0), base.step_start[-1], dtype=np.int64)])
+    steps = int(step_start.shape[0] - 1)
+    cap = 1 << 16
+    q = K.DeviceQueries.from_host(hq, dev)
+    cfg = K.size_config(0, 0, base.budget, batch, int(hq.len.max()), extra_prompts=hq.n)
+    ids = [torch.arange(int(step_start[s]), int(step_start[s + 1]), dtype=torch.int32, device=dev) if step_start[s + 1] > step_start[s]
+           else None for s in range(steps)]
+    rows = []
+    total_dt = 0.0
+    for k in (1, 2, 4, 8, 0xFFFFFFFF):
+        def one_run():
+            sched = K.Scheduler(cfg, None, cap, dev)
+            run = K.OnlineRun(sched, q, cap, np.arange(int(step_start[0]), int(step_start[1])))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s in range(steps):
+                run.step(k, batch, ids[s + 1] if s + 1 < steps else None)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            assert int(run.dev_error.item()) == 0 and K.kLPM_read_stats(sched.tree).device_error == 0
+            return dt, run
+        one_run()
+        dt, run = one_run()
+        total_dt += dt
+        ttft = run.ttft[:hq.n].cpu().numpy()
+        assert (ttft >= 0).all(), "the drain steps must admit every query"
+        done = np.sort(ttft)
+        pct = lambda p: int(done[int(np.ceil(p * done.shape[0])) - 1])
+        row = {"k": "inf" if k == 0xFFFFFFFF else k, "steps": steps, "steps_per_s": steps / dt, "ms_per_step": dt / steps * 1e3,
+               "matched_tokens": int(run.matched.item()), "makespan": int(run.sim_clock.item()),
+               "ttft_p50": pct(0.5), "ttft_p90": pct(0.9), "ttft_p99": pct(0.99), "ttft_max": int(done[-1])}
+        if args.cpu_steps > 0:
+            import oracle
+
+            t0 = time.perf_counter()
+            r = oracle.simulate_stream(W.generators.Stream(base.name + "-overload", hq, step_start, k, batch, base.budget))
+            row["oracle_steps_per_s"] = steps / (time.perf_counter() - t0)
+            assert r.ttft.tolist() == ttft.tolist() and r.clock == row["makespan"], f"GPU and oracle disagree on the stream (k = {k})"
+        log(f"overloaded stream k={row['k']}: {row['steps_per_s']:.0f} steps/s, TTFT p50 {row['ttft_p50']} p99 {row['ttft_p99']} max {row['ttft_max']}")
+        rows.append(row)
+    out = {
+        "metric": "scheduling steps/sec (overloaded online stream: match + select + commit + queue update per step)",
+        "value": 5 * steps / total_dt, "unit": "steps/s", "n_gpus": 1, "steps": 5 * steps, "warmup": 5 * steps,
+        "ms_per_step": total_dt / (5 * steps) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": base.name + "-overload", "arrival_steps": base.steps, "drain_steps": steps - base.steps,
+                   "queries": hq.n, "batch": batch, "kv_budget_tokens": base.budget, "k": [r["k"] for r in rows]},
+        "per_k": rows, "roofline": None,
+    }
+    if args.cpu_steps > 0:
+        out["cpu_baseline"] = {"value": float(np.mean([r["oracle_steps_per_s"] for r in rows])), "unit": "steps/s", "cores": 1,
+                               "kind": "oracle", "sample": "every stream of the sweep; every TTFT equal to the GPU's"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def build_workload(scale: float, steps_total: int, deep: bool = False):
     import workloads as W
 
@@ -935,6 +1007,9 @@ def main() -> int:
     ap.add_argument("--workload", choices=("cfg2-large", "cfg0", "cfg1", "cfg3", "def3", "cfg4"), default="cfg2-large",
                     help="cfg0/cfg1/cfg3: the single-step configurations; def3: the timed Regular Arrival Shuffled "
                          "Queue run; cfg4: the 1,000-step online stream")
+    ap.add_argument("--overload", action="store_true",
+                    help="with --workload cfg4: a batch below the arrival rate (the queue backs up), k swept over {1,2,4,8,inf}, drained at the end")
+    ap.add_argument("--overload-batch", type=int, default=96, help="batch size of --overload (arrivals are Poisson(128) per step)")
     ap.add_argument("--def3-u", type=int, default=3000, help="shared-prefix length of the def3 workload (prompt = 6000)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -948,7 +1023,7 @@ def main() -> int:
     if args.workload == "def3":
         return bench_def3(args)
     if args.workload == "cfg4":
-        return bench_cfg4(args)
+        return bench_cfg4_overload(args) if args.overload else bench_cfg4(args)
     if args.workload in ("cfg0", "cfg1", "cfg3"):
         return bench_single_step(args)
     return bench_cfg2(args)
