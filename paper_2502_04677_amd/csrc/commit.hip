@@ -30,6 +30,7 @@ constexpr uint64_t kNoGroup = ~0ull;
 constexpr int32_t kLcpPending = -1;
 constexpr int32_t kLcpNone = -2;
 constexpr uint32_t kDevInternal = 32u;  // KLPM_DEV_INTERNAL: the tree and its child table disagree
+constexpr int kCutRows = 4;  // an old edge is cut for up to 64 * kCutRows prompts of a batch at once (several per lane beyond 64)
 constexpr int kEvictDigitBits = 11;  // eviction cut search: bits of the key resolved per pass
 constexpr int kEvictBins = 1 << kEvictDigitBits;
 constexpr int kPlanThreads = 1024;
@@ -1300,6 +1301,101 @@ __device__ __forceinline__ int32_t cut_edge_lanes(const TreeView &tv, const Comm
     return up_id;
 }
 
+// The same for more cut requests than lanes: request i sits in lane i % 64, row i / 64 (R rows, so up to
+// 64 R requests; lanes hold the rows' values side by side).  Used for an old edge that more than 64 prompts
+// of a batch stop inside.
+template <int R>
+__device__ __forceinline__ void cut_edge_rows(const TreeView &tv, const CommitWs &ws, const GroupCtx &ctx, int32_t e,
+                                              const NodeRec &rec, int32_t s, int32_t cnt, const bool (&cuts)[R],
+                                              const int32_t (&j)[R], const int32_t (&depth)[R],
+                                              const int32_t (&split_id)[R], int lane) {
+    const int32_t ds = rec.depth_end - rec.edge_len;
+    int32_t m[R], prev_m[R], next_m[R], cutter[R], prev_cut[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        m[r] = cuts[r] ? depth[r] : 0x7FFFFFFF;
+        prev_m[r] = ds;
+        next_m[r] = 0x7FFFFFFF;
+        cutter[r] = r * kWave + lane;
+        prev_cut[r] = -1;
+    }
+    // where every request's depth stands among all requested depths
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        const int32_t row_n = cnt - rr * kWave < kWave ? cnt - rr * kWave : kWave;
+        for (int k = 0; k < row_n; ++k) {
+            const int32_t mk = __shfl(m[rr], k);
+            const int32_t idx = rr * kWave + k;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (mk < m[r] && mk > prev_m[r]) prev_m[r] = mk;
+                if (mk > m[r] && mk < next_m[r]) next_m[r] = mk;
+                if (mk == m[r] && idx < cutter[r]) cutter[r] = idx;
+            }
+        }
+    }
+    // the first request, in pick order, that cuts at the next smaller depth
+#pragma unroll
+    for (int rr = R - 1; rr >= 0; --rr) {
+        const int32_t row_n = cnt - rr * kWave < kWave ? cnt - rr * kWave : kWave;
+        for (int k = row_n - 1; k >= 0; --k) {
+            const int32_t mk = __shfl(m[rr], k);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (mk == prev_m[r]) prev_cut[r] = rr * kWave + k;
+        }
+    }
+    // split id of a request by its index (its row differs from lane to lane)
+    auto id_of = [&](int32_t idx) -> int32_t {
+        int32_t v = 0;
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            const int32_t t = __shfl(split_id[rr], idx & (kWave - 1));
+            if ((idx >> 6) == rr) v = t;
+        }
+        return v;
+    };
+    int32_t up_id[R], prev_up[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        up_id[r] = id_of(cutter[r]);
+        prev_up[r] = id_of(prev_cut[r] < 0 ? 0 : prev_cut[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool is_cutter = cuts[r] && cutter[r] == r * kWave + lane;
+        const bool is_last = is_cutter && next_m[r] == 0x7FFFFFFF;
+        // the first token of this piece and (largest depth) of what is left of the node, one round trip
+        int32_t ftok = 0, low_first = 0;
+        if (is_cutter && prev_cut[r] >= 0) ftok = tv.pool[rec.edge_off + (int64_t)(prev_m[r] - ds)];
+        if (is_last) low_first = tv.pool[rec.edge_off + (int64_t)(depth[r] - ds)];
+        if (is_cutter) {
+            const int32_t up = up_id[r];
+            const int64_t off = rec.edge_off + (int64_t)(prev_m[r] - ds);
+            tv.parent[up] = prev_cut[r] < 0 ? rec.parent : prev_up[r];
+            tv.edge_off[up] = off;
+            tv.edge_len[up] = depth[r] - prev_m[r];
+            tv.depth_end[up] = depth[r];
+            tv.tick[up] = ctx.clock0 + (uint64_t)j[r];
+            atomicOr(&ws.used[j[r]], 1);
+            if (prev_cut[r] < 0) {  // the topmost piece takes over the node's table slot and the start of the edge
+                tv.slots[s].child = up;
+                tv.slots[s].edge_len = depth[r] - prev_m[r];
+                tv.slot_of[up] = s;
+            } else {
+                slot_insert(tv, make_key(prev_up[r], ftok), up, depth[r] - prev_m[r], off);
+            }
+            if (is_last) {
+                const int64_t low_off = rec.edge_off + (int64_t)(depth[r] - ds);
+                tv.edge_off[e] = low_off;
+                tv.edge_len[e] = rec.depth_end - depth[r];
+                tv.parent[e] = up;
+                slot_insert(tv, make_key(up, low_first), e, rec.depth_end - depth[r], low_off);
+            }
+        }
+    }
+}
+
 // The prompts of a batch whose matches stopped inside one old edge cut it at their stop depths.
 // Inserted one after the other every prompt costs a few dependent round trips, and a popular edge
 // collects dozens of them; but the pieces follow from the sorted stop depths alone.  So the wavefront
@@ -1314,7 +1410,7 @@ __device__ __forceinline__ int32_t cut_edge_lanes(const TreeView &tv, const Comm
 // Returns false with nothing touched if the tree and its table disagree.
 __device__ bool cut_old_edge(const TreeView &tv, const QView &q, const CommitWs &ws, const int32_t *__restrict__ batch_idx,
                              const GroupCtx &ctx, int32_t g, int32_t e, uint32_t mine_e, int lane) {
-    __shared__ int32_t s_mem[kWave];
+    __shared__ int32_t s_mem[kCutRows * kWave];
     constexpr int kRows = 16;
     const uint64_t below = (1ull << lane) - 1ull;
     int32_t cnt = 1;
@@ -1324,11 +1420,44 @@ __device__ bool cut_old_edge(const TreeView &tv, const QView &q, const CommitWs 
         const uint64_t mask = __ballot(bit);
         if (!mask) continue;
         const int32_t pos = cnt + (int32_t)__popcll(mask & below);
-        if (bit && pos < kWave) s_mem[pos] = t * kWave + lane;
+        if (bit && pos < kCutRows * kWave) s_mem[pos] = t * kWave + lane;
         cnt += (int32_t)__popcll(mask);
     }
-    if (cnt > kWave) return false;  // (the caller has counted: cannot happen)
+    if (cnt > kCutRows * kWave) return false;  // (the caller has counted: cannot happen)
     wave_sync();
+    if (cnt > kWave) {
+        // more prompts than lanes: kCutRows requests per lane
+        const int32_t pa_w = ld_i32(&tv.parent[e]), el_w = ld_i32(&tv.edge_len[e]), de_w = ld_i32(&tv.depth_end[e]);
+        const int64_t eo_w = ld_i64(&tv.edge_off[e]);
+        const int32_t s_w = ld_i32(&tv.slot_of[e]);
+        bool act[kCutRows];
+        int32_t jj[kCutRows], mv[kCutRows], sp[kCutRows];
+#pragma unroll
+        for (int r = 0; r < kCutRows; ++r) {
+            act[r] = r * kWave + lane < cnt;
+            jj[r] = act[r] ? s_mem[r * kWave + lane] : g;
+            mv[r] = ws.bm_len[jj[r]];
+            sp[r] = ws.resv_id[2 * jj[r]];
+        }
+        NodeRec wrec;
+        wrec.parent = uni(pa_w);
+        wrec.edge_len = uni(el_w);
+        wrec.depth_end = uni(de_w);
+        wrec.edge_off = uni64(eo_w);
+        const int32_t sw = uni(s_w);
+        const int32_t dsw = wrec.depth_end - wrec.edge_len;
+        bool badw = sw < 0 || (uint32_t)sw > tv.slot_mask;
+#pragma unroll
+        for (int r = 0; r < kCutRows; ++r)
+            if (act[r] && (mv[r] <= dsw || mv[r] >= wrec.depth_end || sp[r] <= 0)) badw = true;
+        if (__ballot(badw) || uni(ld_i32(&tv.slots[sw < 0 ? 0 : sw].child)) != e) {
+            if (lane == 0) flag_error(tv.st, kDevInternal);
+            return false;
+        }
+        cut_edge_rows<kCutRows>(tv, ws, ctx, e, wrec, sw, cnt, act, jj, mv, sp, lane);
+        wave_sync();
+        return true;
+    }
     const bool active = lane < cnt;
     const int32_t j = active ? s_mem[lane] : g;
     // (the old node's record and slot travel with the members' inputs)
@@ -1425,9 +1554,9 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
     }
     first_e = !__ballot(!first_e);
     first_s = !__ballot(!first_s);
-    // an edge that more prompts stop inside than a wavefront has lanes is handled the slow way: its
-    // prompts are one group, inserted one after the other by the first of them
-    const bool cut_scheme = inside && count_e <= kWave;
+    // an edge that more prompts stop inside than the cutting wavefront takes (kCutRows per lane) is handled
+    // the slow way: its prompts are one group, inserted one after the other by the first of them
+    const bool cut_scheme = inside && count_e <= kCutRows * kWave;
     if (inside && !cut_scheme) {
         first_s = first_e;
         mine_s = mine_e;

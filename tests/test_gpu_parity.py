@@ -1372,10 +1372,11 @@ def test_million_query_queue():
 
 
 def test_groups_larger_than_a_wavefront():
-    """Hundreds of admitted prompts that stop at the same place of the tree, so that one wavefront
-    inserts them one after the other and makes more table entries than it keeps a record of: stops
-    inside one long edge at many depths (with and without an own tail), and a common new prefix
-    below the root.  Both kinds of commit, then a second batch on top of the first."""
+    """Dozens to hundreds of admitted prompts that stop at the same place of the tree: stops inside one long
+    edge at many depths (with and without an own tail; cut for all of them at once by one wavefront, one to
+    four prompts per lane, or - beyond 256 - inserted one after the other, which makes more table entries
+    than the wavefront keeps a record of), and a common new prefix below the root.  Both kinds of commit,
+    then a second batch on top of the first."""
     rng = np.random.default_rng(83)
     long = rng.integers(0, 1000, size=600).astype(np.int32)
     cache = W.generators._from_lists([long.tolist()], [0])
@@ -1390,7 +1391,7 @@ def test_groups_larger_than_a_wavefront():
         order = rng.permutation(len(out))
         return [out[i] for i in order]
 
-    for n_each in (40, 230):
+    for n_each in (40, 70, 130, 230, 300):  # one prompt per lane; two, three, four per lane; the serial road
         lists = batch_of(n_each) + batch_of(n_each)
         hq = W.generators._from_lists(lists, list(range(len(lists))))
         n = len(lists)
