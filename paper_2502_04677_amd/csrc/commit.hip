@@ -1612,16 +1612,21 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
     if (me.m < me.L && ctx.n_ent == 1 && (!inside || cut_scheme)) {
         __shared__ int32_t s_mem[kWave];
         const uint64_t lower = (1ull << lane) - 1ull;
-        int32_t cnt = 0;
+        int32_t cnt_all = 0;
+        uint32_t by_lanes = 0;  // my members among the first 64 of the group: those go in all at once
         for (int t = g / kWave; t < kRows; ++t) {
             const bool bit = (mine_s >> t) & 1u;
             const uint64_t mask = __ballot(bit);
             if (!mask) continue;
-            const int32_t pos = cnt + (int32_t)__popcll(mask & lower);
-            if (bit && pos < kWave) s_mem[pos] = t * kWave + lane;
-            cnt += (int32_t)__popcll(mask);
+            const int32_t pos = cnt_all + (int32_t)__popcll(mask & lower);
+            if (bit && pos < kWave) {
+                s_mem[pos] = t * kWave + lane;
+                by_lanes |= 1u << t;
+            }
+            cnt_all += (int32_t)__popcll(mask);
         }
-        if (cnt <= kWave) {
+        const int32_t cnt = cnt_all < kWave ? cnt_all : kWave;
+        {
             wave_sync();
             const bool active = lane < cnt;
             const int32_t j = active ? s_mem[lane] : g;
@@ -1694,7 +1699,13 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
                     insert_prompt(tv, q, ws, uni(__shfl(j, b)), member_from_lane(mv, b), ctx, lane, kLcpNone, 0,
                                   uni(__shfl(piece, b)), uni(__shfl(d, b)), uni(__shfl(after, b)));
                 }
-                return;
+                if (cnt_all <= kWave) return;
+                // a group of more than 64 later members: the rest follow one after the other below, finding
+                // what the lanes have made through the table in memory (the record kept in the lanes describes
+                // the members' leaves only, not the pieces of my leaf)
+                mine_s &= ~by_lanes;
+                ctx.cache_ok = false;
+                ctx.n_ent = kWave;
             }
         }
     }
