@@ -30,6 +30,9 @@ constexpr uint64_t kNoGroup = ~0ull;
 constexpr int32_t kLcpPending = -1;
 constexpr int32_t kLcpNone = -2;
 constexpr uint32_t kDevInternal = 32u;  // KLPM_DEV_INTERNAL: the tree and its child table disagree
+constexpr int kDeepRounds = 6;     // structure pass: rounds in which classes of members that met each other settle among themselves
+constexpr int kDeepMinClass = 3;   // ... classes of at least this many members (smaller ones are inserted one after the other)
+constexpr int kDeepCompare = 512;  // ... tokens a lane compares by itself before it leaves its member to the slow road
 constexpr int kCutRows = 4;  // an old edge is cut for up to 64 * kCutRows prompts of a batch at once (several per lane beyond 64)
 constexpr int kEvictDigitBits = 11;  // eviction cut search: bits of the key resolved per pass
 constexpr int kEvictBins = 1 << kEvictDigitBits;
@@ -1679,25 +1682,141 @@ __device__ __forceinline__ void structure_body(TreeView tv, QView q, const int32
                 }
                 __threadfence();
                 wave_sync();
-                // The members that met each other follow, one after the other.  Whatever they can find below
+                // Members that met each other (same depth, same token) agree with one another for longer than
+                // with me: near-duplicates whose common part is longer than mine.  The first of such a class
+                // has hung its leaf; the others now do with that leaf what everybody did with mine - every
+                // lane measures by itself how far its member follows the class's first member, the class cuts
+                // that leaf at those depths at once and hangs what is left - and so on while classes of
+                // several members remain.  Small classes and what is left after kDeepRounds rounds are
+                // inserted one after the other below.
+                int32_t d_c = d, after_c = after, piece_c = piece, slot_c = made_slot;
+                int64_t off_c = off;
+                bool hangs_c = hangs, conflict_c = active && conflict;
+                bool deeper = false;
+                for (int round = 0; round < kDeepRounds; ++round) {
+                    int32_t head = -1, csize = 0;
+                    for (int k = 0; k < cnt; ++k) {
+                        const int32_t pk = __shfl(piece_c, k), ak = __shfl(after_c, k);
+                        const bool hk = __shfl((int)hangs_c, k) != 0, ck = __shfl((int)conflict_c, k) != 0;
+                        if (conflict_c && pk == piece_c && ak == after_c) {
+                            if (hk && head < 0) head = k;
+                            if (ck) ++csize;
+                        }
+                    }
+                    const int32_t hl = head < 0 ? 0 : head;
+                    const int32_t slot_h = __shfl(slot_c, hl), L_h = __shfl(mv.L, hl);
+                    const int64_t qoff_h = (int64_t)(((uint64_t)(uint32_t)__shfl((int32_t)((uint64_t)mv.qoff >> 32), hl) << 32) |
+                                                     (uint64_t)(uint32_t)__shfl((int32_t)(uint32_t)mv.qoff, hl));
+                    bool go = conflict_c && head >= 0 && csize >= kDeepMinClass && slot_h >= 0;
+                    if (!__ballot(go)) break;
+                    // how far my member follows the first member of its class (both continue with the same token)
+                    int32_t h2 = 0;
+                    if (go) {
+                        const int32_t lim = (mv.L < L_h ? mv.L : L_h) - d_c;
+                        const int32_t cap = lim < kDeepCompare ? lim : kDeepCompare;
+                        const int32_t *__restrict__ xa = q.tokens + mv.qoff + d_c;
+                        const int32_t *__restrict__ xb = q.tokens + qoff_h + d_c;
+                        bool differ = false;
+                        constexpr int kChunk = 32;  // tokens of both prompts requested per round trip
+                        for (int32_t t = 0; t < cap && !differ; t += kChunk) {
+                            int32_t av[kChunk], bv[kChunk];
+#pragma unroll
+                            for (int u = 0; u < kChunk; ++u) {
+                                const int32_t i = t + u < cap ? t + u : cap - 1;
+                                av[u] = xa[i];
+                                bv[u] = xb[i];
+                            }
+#pragma unroll
+                            for (int u = 0; u < kChunk; ++u) {
+                                if (!differ && t + u < cap) {
+                                    if (av[u] != bv[u]) differ = true; else ++h2;
+                                }
+                            }
+                        }
+                        if ((!differ && cap < lim) || h2 < 1) go = false;  // longer than a lane compares by itself: left to the slow road
+                    }
+                    const int32_t d_n = d_c + h2;
+                    int32_t after_n = -1;
+                    if (go && d_n < mv.L) after_n = q.tokens[mv.qoff + d_n];
+                    const bool tail_n = go && mv.L > d_n;
+                    // every class cuts the leaf of its first member
+                    uint64_t heads = 0;
+                    for (int k = 0; k < cnt; ++k)
+                        if (__shfl((int)go, k)) heads |= 1ull << __shfl(hl, k);
+                    if (!heads) break;
+                    deeper = true;
+                    int32_t piece_n = -1;
+                    while (heads) {
+                        const int b = (int)__builtin_ctzll(heads);
+                        heads &= heads - 1ull;
+                        const int32_t leaf_b = uni(__shfl(mv.leaf_id, b)), slot_b = uni(__shfl(slot_c, b));
+                        const int32_t L_b = uni(__shfl(mv.L, b)), d_b = uni(__shfl(d_c, b));
+                        NodeRec hrec;
+                        hrec.parent = uni(__shfl(piece_c, b));
+                        hrec.edge_len = L_b - d_b;
+                        hrec.depth_end = L_b;
+                        hrec.edge_off = uni64(__shfl(off_c, b));
+                        const bool in_cls = go && head == b;
+                        const bool cuts_b = in_cls && d_n < L_b;
+                        const int32_t pc = cut_edge_lanes(tv, ws, ctx, leaf_b, hrec, slot_b, cnt, cuts_b, j, d_n, mv.split_id, lane);
+                        if (in_cls) piece_n = cuts_b ? pc : leaf_b;
+                    }
+                    // who still meets whom behind the new cuts
+                    bool conflict_n = false;
+                    for (int k = 0; k < cnt; ++k) {
+                        const int32_t pk = __shfl(piece_n, k), ak = __shfl(after_n, k);
+                        const bool gk = __shfl((int)go, k) != 0, tk = __shfl((int)tail_n, k) != 0;
+                        if (k < lane && go && tail_n && gk && tk && pk == piece_n && ak == after_n) conflict_n = true;
+                    }
+                    if (go) {
+                        d_c = d_n;
+                        after_c = after_n;
+                        piece_c = piece_n;
+                        off_c = ctx.pool_top + mv.to + (int64_t)(d_n - me.m);
+                        conflict_c = conflict_n;
+                        hangs_c = false;
+                        slot_c = -1;
+                        if (!conflict_n) {
+                            int32_t end = piece_n, leaf_tokens = 0;
+                            if (tail_n) {
+                                tv.parent[mv.leaf_id] = piece_n;
+                                tv.edge_off[mv.leaf_id] = off_c;
+                                tv.edge_len[mv.leaf_id] = mv.L - d_n;
+                                tv.depth_end[mv.leaf_id] = mv.L;
+                                tv.tick[mv.leaf_id] = ctx.clock0 + (uint64_t)j;
+                                slot_c = slot_insert(tv, make_key(piece_n, after_n), mv.leaf_id, mv.L - d_n, off_c);
+                                atomicOr(&ws.used[j], 2);
+                                end = mv.leaf_id;
+                                leaf_tokens = mv.L - d_n;
+                                hangs_c = true;
+                            }
+                            ws.leaf_tok[j] = leaf_tokens;
+                            ws.end_node[j] = end;
+                        }
+                    }
+                    __threadfence();
+                    wave_sync();
+                }
+                // The members that still meet each other follow, one after the other.  Whatever they can find below
                 // their pieces is a leaf that a lane has just hung there (the rest of my own leaf goes on with
                 // my token, not theirs), so the record of this wavefront's table entries is set up from the
-                // lanes: lane k describes the leaf of member k, if it hung one.
-                ctx.c_parent = hangs ? piece : -2;  // (no node has this id)
-                ctx.c_tok = after;
+                // lanes: lane k describes the leaf of member k, if it hung one.  (After further rounds leaves have
+                // been cut that the lanes do not describe any more: the table in memory answers then.)
+                ctx.c_parent = hangs_c ? piece_c : -2;  // (no node has this id)
+                ctx.c_tok = after_c;
                 ctx.c_child = mv.leaf_id;
-                ctx.c_el = mv.L - d;
-                ctx.c_eo = off;
-                ctx.c_slot = made_slot;
-                ctx.n_ent = cnt;
-                ctx.cache_ok = !__ballot(hangs && made_slot < 0);
+                ctx.c_el = mv.L - d_c;
+                ctx.c_eo = off_c;
+                ctx.c_slot = slot_c;
+                ctx.n_ent = deeper ? kWave : cnt;
+                ctx.cache_ok = !deeper && !__ballot(hangs_c && slot_c < 0);
                 ctx.piece = -1;
-                uint64_t todo = __ballot(active && conflict);
+                uint64_t todo = __ballot(conflict_c);
                 while (todo) {
                     const int b = (int)__builtin_ctzll(todo);
                     todo &= todo - 1ull;
                     insert_prompt(tv, q, ws, uni(__shfl(j, b)), member_from_lane(mv, b), ctx, lane, kLcpNone, 0,
-                                  uni(__shfl(piece, b)), uni(__shfl(d, b)), uni(__shfl(after, b)));
+                                  uni(__shfl(piece_c, b)), uni(__shfl(d_c, b)), uni(__shfl(after_c, b)));
                 }
                 if (cnt_all <= kWave) return;
                 // a group of more than 64 later members: the rest follow one after the other below, finding

@@ -1408,6 +1408,37 @@ def test_groups_larger_than_a_wavefront():
         _check_step(s, ref, q2, tail, 1, n // 2, 0, 1 << 40, fifo=True)
 
 
+@pytest.mark.parametrize("donor_len,n_members", [(160, 60), (160, 200), (1500, 40)])
+def test_near_duplicates_of_an_uncached_prompt(donor_len, n_members):
+    """One batch of prompts that all repeat the head of the same string, which the cache does not hold, each
+    for a length of its own, before a tail of their own: they stop at one node boundary with the same next
+    token and form one group whose members agree with each other for longer than with the group's first
+    prompt, level after level (the classes that settle among themselves in the structure pass; with the
+    long string the agreement exceeds what a lane compares by itself).  Exact duplicates, prompts that are
+    prefixes of others and prompts that end inside the common part are among them."""
+    rng = np.random.default_rng(1234 + donor_len + n_members)
+    prefix = rng.integers(0, 1000, size=40).astype(np.int32)
+    cache = W.generators._from_lists([prefix.tolist() + [5000, 5001]], [0])
+    donor = rng.integers(1000, 2000, size=donor_len).astype(np.int32)
+    lists = []
+    for i in range(n_members):
+        c = int(rng.integers(1, donor_len + 1))
+        kind = int(rng.integers(0, 6))
+        tail = [] if kind == 0 else (3000 + rng.integers(0, 3 if kind == 1 else 100000, size=int(rng.integers(1, 6)))).tolist()
+        lists.append(prefix.tolist() + donor[:c].tolist() + tail)
+    lists += [lists[3], lists[7], lists[3]]  # exact duplicates
+    order = rng.permutation(len(lists))
+    lists = [lists[i] for i in order]
+    n = len(lists)
+    hq = W.generators._from_lists(lists, list(range(n)))
+    w = W.Workload("near-duplicates", cache, hq, 1, n, 1 << 40)
+    s, ref, q = _setup(w, max_batch=n, extra_prompts=2 * n)
+    _say(f"near duplicates: {n} prompts repeating up to {donor_len} tokens of one uncached string")
+    ph = _check_step(s, ref, q, hq, 1, n, 0, 1 << 40, fifo=True)
+    _check_step(s, ref, q, hq, K_INF, n, ph, 1 << 40, fifo=True)  # everything is cached by now: ticks only
+    _check_step(s, ref, q, hq, 2, n // 2, 0, 300, fifo=True)      # and under eviction pressure
+
+
 @pytest.mark.parametrize("n_prompts,batch", [(900, 450), (3000, 1500), (1100, 513), (2100, 1023), (4200, 2047), (4200, 2049)])
 def test_batches_that_share_new_prefixes_at_several_levels(n_prompts, batch):
     """Admitted prompts of the shape prefix + first c tokens of a donor string + own tail, several per
